@@ -1,0 +1,186 @@
+/*
+ * libsocket -- the decode-time hot path of SOCKET (soft-collision LSH sparse
+ * attention) for AMD MI355X (gfx950).  C ABI; every kernel behind it is
+ * hand-written HIP.
+ *
+ * Call order for one attention layer (the paper's three stages):
+ *   prefill : socket_hash_keys over all cached keys            (Alg. 1)
+ *   decode  : socket_hash_keys over the one appended key       (Alg. 1)
+ *             socket_score        soft-hash q, score every key (Alg. 2 + Alg. 5 / Eq. 3)
+ *             socket_topk_select  keep the k best tokens       (Alg. 3, TopK step)
+ *             socket_sparse_decode  exact attention on them    (Eq. 2; Eq. 1 when all are kept)
+ *
+ * General rules
+ *   - Every tensor argument is a caller-owned DEVICE pointer.  The library never
+ *     allocates, frees or keeps one.  `socket_ctx` owns only its own scratch.
+ *   - Every call is asynchronous on `stream` (a hipStream_t passed as void*;
+ *     NULL = the default stream), does no host synchronisation and records no
+ *     memset node, so a sequence of calls may be captured into a HIP graph.
+ *   - One ctx serves one stream at a time: calls that share a ctx and overlap
+ *     in time race on its scratch.
+ *   - Every call returns 0 or a negative SOCKET_E* code; nothing throws.
+ *     Arguments are checked on the host before any launch.
+ *   - Per-sequence integers (lengths, k, row ranges) live in device memory, so a
+ *     captured graph can be replayed with new values.
+ *
+ * Shapes: B sequences, Hq query heads, Hkv key/value heads (Hq = G * Hkv),
+ * head dimension d, L hash tables of P hyperplanes (R = 2^P buckets per table).
+ *
+ * Layouts
+ *   q        [B, Hq, d]                              element type = kv_dtype
+ *   K, V     contiguous: [B, Hkv, max_n, d]          element type = kv_dtype
+ *            paged:      [num_blocks, Hkv, page_size, d], with
+ *            block_table [B, max_blocks_per_seq] int32; token t of sequence b is
+ *            row t % page_size of block block_table[b][t / page_size]
+ *   proj     [Hkv, d, L*P]  element type = kv_dtype; column l*P+i is hyperplane i
+ *            of table l (the paper's W^(l), row i)
+ *   codes    same token layout as K with d replaced by Lpad:
+ *            [B, Hkv, max_n, Lpad] or [num_blocks, Hkv, page_size, Lpad];
+ *            element uint8 when P <= 8, uint16 otherwise.
+ *            Lpad = 16, 32 or 64 (the smallest that holds L) when L <= 64, else L
+ *            rounded up to a multiple of 64.  The L bucket ids of token t are
+ *            stored in a rotated order chosen so that the scoring kernel's table
+ *            look-ups are free of LDS bank conflicts: with S = min(Lpad,64)/16 and
+ *            l = 64*c + l' (l' < 64), the id of table l sits at position
+ *                64*c + (l' % S)*16 + ((l' / S - t) mod 16).
+ *            socket_code_position() returns that position.  Positions that map to
+ *            tables >= L hold 0.
+ *   bucket id: bit i is 1 when hyperplane i gives a projection >= 0.
+ *   scores   [B, Hkv, max_n] float32, logical token order; -inf for t >= seq_len
+ *   idx      [B, Hkv, max_k] int32 logical token positions in ascending order,
+ *            unused tail = -1;  n_selected [B, Hkv] int32
+ *   out      [B, Hq, d] float32 or bf16
+ */
+#ifndef SOCKET_H
+#define SOCKET_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* element types */
+#define SOCKET_BF16 0
+#define SOCKET_F32 1
+
+/* error codes */
+#define SOCKET_OK 0
+#define SOCKET_EINVAL (-1)       /* null pointer, size out of range, inconsistent sizes */
+#define SOCKET_EUNSUPPORTED (-2) /* a valid request this build has no kernel for */
+#define SOCKET_ENOMEM (-3)       /* scratch allocation failed */
+#define SOCKET_EHIP (-4)         /* a HIP call failed; see socket_last_hip_error */
+
+typedef struct socket_ctx socket_ctx;
+
+typedef struct socket_params {
+    int32_t d;         /* head dimension: 64, 128 or 256 */
+    int32_t Hq;        /* query heads; Hq/Hkv must be 1, 2, 4 or 8 */
+    int32_t Hkv;       /* key/value heads */
+    int32_t L;         /* hash tables, 1..1024 */
+    int32_t P;         /* hyperplanes per table, 1..16 */
+    int32_t kv_dtype;  /* SOCKET_BF16 or SOCKET_F32: type of q, K, V and proj */
+    int32_t max_batch; /* largest B any call will pass */
+    int32_t max_n;     /* token capacity per sequence, a multiple of 16 */
+    int32_t max_k;     /* largest k any call will select, <= max_n */
+    int32_t page_size; /* 0 = contiguous K/V/codes; else tokens per block, a multiple of 16 */
+    int32_t max_blocks_per_seq; /* paged only: columns of block_table */
+    int32_t num_blocks;         /* paged only: blocks in the K/V/codes pools; a block_table
+                                   entry outside [0, num_blocks) marks its tokens as absent */
+} socket_params;
+
+/* Host-only check of a parameter block; no GPU needed.  0 or SOCKET_EINVAL /
+ * SOCKET_EUNSUPPORTED (for example a bucket-probability table that cannot fit in
+ * the 160 KB of LDS). */
+int socket_validate_params(const socket_params *p);
+
+/* Padded codes-per-token (Lpad above) for L tables; -1 when L is out of range. */
+int32_t socket_codes_per_token(int32_t L);
+
+/* Position of table l's bucket id inside token t's Lpad-long code row. */
+int32_t socket_code_position(int32_t L, int32_t l, int32_t t);
+
+/* Create / destroy a context on the current HIP device.  Creation allocates the
+ * scratch (bucket-probability tables, radix histograms, candidate lists,
+ * split-K partial results), sized from max_batch, max_n and max_k. */
+int socket_create(socket_ctx **out, const socket_params *p);
+int socket_destroy(socket_ctx *ctx);
+
+/* Bytes of device scratch the context holds. */
+int64_t socket_scratch_bytes(const socket_ctx *ctx);
+
+/*
+ * Alg. 1 (PrecomputeKeyHashes): bucket ids of cached keys.
+ * For each sequence b < batch, tokens row_begin[b] .. row_begin[b]+row_count[b]-1
+ * are hashed: h = sign(W^(l) k) per table, encoded as a bucket id, and written
+ * into `codes`.  Prefill passes (0, n); a decode step passes (n, 1) for the
+ * appended key.  `max_rows` (host) bounds every row_count[b] and sizes the
+ * launch; rows beyond row_count[b] are not touched.
+ * bf16 keys use bf16 MFMA with fp32 accumulation; fp32 keys use fp32 FMA.
+ * row_begin, row_count: device int32 [batch].  block_table: device, paged only
+ * (NULL otherwise).
+ */
+int socket_hash_keys(socket_ctx *ctx, const void *K, const void *proj,
+                     const int32_t *block_table, const int32_t *row_begin,
+                     const int32_t *row_count, int32_t batch, int32_t max_rows,
+                     void *codes, void *stream);
+
+/*
+ * Alg. 2 + Alg. 5 (SoftBucketProbs, SoftHashCollisionScores; Eq. 3, soft score).
+ * Soft-hashes each query into its L x R bucket probabilities
+ * (u = tanh(W q)/sqrt(d), softmax of u.c_r/tau over the R corners; evaluated in
+ * fp64, stored as fp32), then gives every cached key j < seq_len[b] the score
+ *     scores[b,h,j] = vnorm[b,h,j] * (1/G) * sum_{g in group(h)} sum_l p_g^(l)(codes[j,l])
+ * and -inf to j >= seq_len[b].  G = 1 is the paper's single-query form; for
+ * grouped-query attention the G queries sharing KV head h are averaged.
+ * vnorm: device float32 [B, Hkv, max_n] (the paper's value-norm weights) or NULL
+ * for 1.  seq_len: device int32 [batch].  tau > 0.
+ */
+int socket_score(socket_ctx *ctx, const void *q, const void *codes, const void *proj,
+                 float tau, const float *vnorm, const int32_t *block_table,
+                 const int32_t *seq_len, int32_t batch, float *scores, void *stream);
+
+/*
+ * Alg. 3, TopK step: for each (b, h) the min(k[b], #valid) tokens with the
+ * largest scores, ties broken towards the smaller token position; -inf and NaN
+ * scores are never selected.  The chosen positions are written in ascending
+ * order, the rest of the max_k-long row is -1, and n_selected[b,h] is the count.
+ * Exact (radix select on the fp32 bit patterns).
+ * seq_len, k: device int32 [batch]; k[b] is clamped to max_k.
+ */
+int socket_topk_select(socket_ctx *ctx, const float *scores, const int32_t *seq_len,
+                       const int32_t *k, int32_t batch, int32_t *idx,
+                       int32_t *n_selected, void *stream);
+
+/*
+ * Eq. 2 (sparse attention over the selected set; Eq. 1 when the set is all
+ * tokens): for each query head, alpha_i = softmax_{i in S}(scale * k_i.q) and
+ * out = sum alpha_i v_i, with S = idx[b, h(kv head of that query head), :n_selected].
+ * scale = 1 is the paper's definition (no 1/sqrt(d)).  Entries < 0 are skipped;
+ * an empty set gives zeros; duplicate indices are a caller error.
+ * out_dtype: SOCKET_F32 or SOCKET_BF16.
+ */
+int socket_sparse_decode(socket_ctx *ctx, const void *q, const void *K, const void *V,
+                         const int32_t *idx, const int32_t *n_selected,
+                         const int32_t *block_table, int32_t batch, float scale,
+                         int32_t out_dtype, void *out, void *stream);
+
+/* Text for an error code; last HIP error code seen by this context (0 if none). */
+const char *socket_strerror(int code);
+int socket_last_hip_error(const socket_ctx *ctx);
+
+/*
+ * HIP-graph helpers, so that a caller without HIP headers can record a chain of
+ * the calls above once and replay it: begin capture on `stream`, issue calls on
+ * that stream, end capture (instantiates), launch any number of times, destroy.
+ */
+typedef struct socket_graph socket_graph;
+int socket_graph_begin(void *stream);
+int socket_graph_end(void *stream, socket_graph **out);
+int socket_graph_launch(socket_graph *g, void *stream);
+int socket_graph_destroy(socket_graph *g);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SOCKET_H */

@@ -1,0 +1,194 @@
+"""ctypes binding of libsocket.so: the same calls as include/socket.h, taking torch tensors.
+
+Argument marshalling only -- every step of the path runs in the library's HIP kernels.
+PyTorch supplies device memory and the current stream.  If the shared library is missing
+this module raises; there is no fallback implementation.
+"""
+import ctypes
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libsocket.so")
+
+BF16, F32 = 0, 1
+OK, EINVAL, EUNSUPPORTED, ENOMEM, EHIP = 0, -1, -2, -3, -4
+
+
+class Params(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "d", "Hq", "Hkv", "L", "P", "kv_dtype", "max_batch", "max_n", "max_k", "page_size",
+        "max_blocks_per_seq", "num_blocks")]
+
+
+class SocketError(RuntimeError):
+    def __init__(self, code, what):
+        self.code = code
+        super().__init__(f"{what}: {strerror(code)} ({code})")
+
+
+_lib = None
+
+
+def lib():
+    """Load libsocket.so (built by `python -m paper_2602_06283_amd.build`)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2602_06283_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float
+        L.socket_validate_params.argtypes = [ctypes.POINTER(Params)]
+        L.socket_codes_per_token.argtypes = [i32]
+        L.socket_code_position.argtypes = [i32, i32, i32]
+        L.socket_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(Params)]
+        L.socket_destroy.argtypes = [vp]
+        L.socket_scratch_bytes.argtypes = [vp]
+        L.socket_scratch_bytes.restype = ctypes.c_int64
+        L.socket_hash_keys.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, vp, vp]
+        L.socket_score.argtypes = [vp, vp, vp, vp, f32, vp, vp, vp, i32, vp, vp]
+        L.socket_topk_select.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp]
+        L.socket_sparse_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, f32, i32, vp, vp]
+        L.socket_strerror.argtypes = [ctypes.c_int]
+        L.socket_strerror.restype = ctypes.c_char_p
+        L.socket_last_hip_error.argtypes = [vp]
+        L.socket_graph_begin.argtypes = [vp]
+        L.socket_graph_end.argtypes = [vp, ctypes.POINTER(vp)]
+        L.socket_graph_launch.argtypes = [vp, vp]
+        L.socket_graph_destroy.argtypes = [vp]
+        _lib = L
+    return _lib
+
+
+EXPORTS = ("socket_validate_params", "socket_codes_per_token", "socket_code_position",
+           "socket_create", "socket_destroy", "socket_scratch_bytes", "socket_hash_keys",
+           "socket_score", "socket_topk_select", "socket_sparse_decode", "socket_strerror",
+           "socket_last_hip_error", "socket_graph_begin", "socket_graph_end",
+           "socket_graph_launch", "socket_graph_destroy")
+
+
+def strerror(code: int) -> str:
+    return lib().socket_strerror(int(code)).decode()
+
+
+def make_params(d, Hq, Hkv, L, P, kv_dtype, max_batch, max_n, max_k, page_size=0,
+                max_blocks_per_seq=0, num_blocks=0) -> Params:
+    return Params(d, Hq, Hkv, L, P, kv_dtype, max_batch, max_n, max_k, page_size,
+                  max_blocks_per_seq, num_blocks)
+
+
+def validate_params(p: Params) -> int:
+    return lib().socket_validate_params(ctypes.byref(p))
+
+
+def codes_per_token(L: int) -> int:
+    return lib().socket_codes_per_token(L)
+
+
+def code_position(L: int, l: int, t: int) -> int:
+    return lib().socket_code_position(L, l, t)
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensors only"
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+class Context:
+    """socket_ctx with the four calls of the decode path as methods."""
+
+    def __init__(self, params: Params):
+        self.params = params
+        self._h = ctypes.c_void_p()
+        rc = lib().socket_create(ctypes.byref(self._h), ctypes.byref(params))
+        if rc != OK:
+            self._h = None
+            raise SocketError(rc, "socket_create")
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().socket_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def scratch_bytes(self) -> int:
+        return lib().socket_scratch_bytes(self._h)
+
+    def _check(self, rc, what):
+        if rc != OK:
+            hip = lib().socket_last_hip_error(self._h)
+            raise SocketError(rc, f"{what} (hip error {hip})")
+
+    def hash_keys(self, K, proj, row_begin, row_count, batch, max_rows, codes, block_table=None,
+                  stream=None):
+        self._check(lib().socket_hash_keys(self._h, _ptr(K), _ptr(proj), _ptr(block_table),
+                                           _ptr(row_begin), _ptr(row_count), batch, max_rows,
+                                           _ptr(codes), _stream(stream)), "socket_hash_keys")
+
+    def score(self, q, codes, proj, tau, seq_len, batch, scores, vnorm=None, block_table=None,
+              stream=None):
+        self._check(lib().socket_score(self._h, _ptr(q), _ptr(codes), _ptr(proj), float(tau),
+                                       _ptr(vnorm), _ptr(block_table), _ptr(seq_len), batch,
+                                       _ptr(scores), _stream(stream)), "socket_score")
+
+    def topk_select(self, scores, seq_len, k, batch, idx, n_selected, stream=None):
+        self._check(lib().socket_topk_select(self._h, _ptr(scores), _ptr(seq_len), _ptr(k), batch,
+                                             _ptr(idx), _ptr(n_selected), _stream(stream)),
+                    "socket_topk_select")
+
+    def sparse_decode(self, q, K, V, idx, n_selected, batch, scale, out, block_table=None,
+                      stream=None):
+        out_dtype = F32 if out.dtype == torch.float32 else BF16
+        self._check(lib().socket_sparse_decode(self._h, _ptr(q), _ptr(K), _ptr(V), _ptr(idx),
+                                               _ptr(n_selected), _ptr(block_table), batch,
+                                               float(scale), out_dtype, _ptr(out), _stream(stream)),
+                    "socket_sparse_decode")
+
+
+class Graph:
+    """A captured chain of library calls: `with Graph.capture(stream) as g: ...; g.launch()`."""
+
+    def __init__(self, stream):
+        self.stream = stream
+        self._h = ctypes.c_void_p()
+
+    @classmethod
+    def capture(cls, stream):
+        return cls(stream)
+
+    def __enter__(self):
+        rc = lib().socket_graph_begin(ctypes.c_void_p(self.stream.cuda_stream))
+        if rc != OK:
+            raise SocketError(rc, "socket_graph_begin")
+        return self
+
+    def __exit__(self, et, ev, tb):
+        rc = lib().socket_graph_end(ctypes.c_void_p(self.stream.cuda_stream), ctypes.byref(self._h))
+        if rc != OK and et is None:
+            raise SocketError(rc, "socket_graph_end")
+        return False
+
+    def launch(self, stream=None):
+        s = stream if stream is not None else self.stream
+        rc = lib().socket_graph_launch(self._h, ctypes.c_void_p(s.cuda_stream))
+        if rc != OK:
+            raise SocketError(rc, "socket_graph_launch")
+
+    def close(self):
+        if self._h:
+            lib().socket_graph_destroy(self._h)
+            self._h = ctypes.c_void_p()

@@ -1,0 +1,256 @@
+// C-ABI entry points of libsocket: parameter checks, scratch ownership, dispatch.
+#include <new>
+
+#include "socket_internal.h"
+
+namespace sk {
+
+static int pad_codes(int L) {
+    if (L < 1 || L > 1024) return -1;
+    if (L <= 16) return 16;
+    if (L <= 32) return 32;
+    if (L <= 64) return 64;
+    return (L + 63) / 64 * 64;
+}
+
+int fill_geometry(const socket_params *p, Geometry *g) {
+    if (!p || !g) return SOCKET_EINVAL;
+    if (p->d != 64 && p->d != 128 && p->d != 256) return SOCKET_EINVAL;
+    if (p->Hkv < 1 || p->Hq < 1 || p->Hq % p->Hkv) return SOCKET_EINVAL;
+    int G = p->Hq / p->Hkv;
+    if (G != 1 && G != 2 && G != 4 && G != 8) return SOCKET_EUNSUPPORTED;
+    if (p->L < 1 || p->L > 1024 || p->P < 1 || p->P > 16) return SOCKET_EINVAL;
+    if (p->kv_dtype != SOCKET_BF16 && p->kv_dtype != SOCKET_F32) return SOCKET_EINVAL;
+    if (p->max_batch < 1 || p->max_n < 16 || p->max_n % 16) return SOCKET_EINVAL;
+    if (p->max_k < 1 || p->max_k > p->max_n) return SOCKET_EINVAL;
+    if (p->page_size < 0 || p->page_size % 16) return SOCKET_EINVAL;
+    if (p->page_size > 0) {
+        if (p->max_blocks_per_seq < 1 || p->num_blocks < 1) return SOCKET_EINVAL;
+        if ((int64_t)p->max_blocks_per_seq * p->page_size < p->max_n) return SOCKET_EINVAL;
+    }
+    if ((int64_t)p->max_batch * p->Hkv * (int64_t)p->max_n > (int64_t)1 << 40) return SOCKET_EINVAL;
+
+    g->d = p->d; g->Hq = p->Hq; g->Hkv = p->Hkv; g->G = G; g->L = p->L; g->P = p->P;
+    g->R = 1 << p->P;
+    g->Lpad = pad_codes(p->L);
+    g->S = g->Lpad >= 64 ? 4 : g->Lpad / 16;
+    g->rounds = g->Lpad >= 64 ? g->Lpad / 64 : 1;
+    g->cb = p->P <= 8 ? 1 : 2;
+    g->page = p->page_size; g->max_blocks = p->max_blocks_per_seq; g->num_blocks = p->num_blocks;
+    g->max_n = p->max_n; g->max_k = p->max_k; g->max_batch = p->max_batch;
+    g->kv_dtype = p->kv_dtype;
+
+    // Pick the bucket-probability layout that fits in LDS (a row is 64 floats = 256 B).
+    const int64_t budget = 144 * 1024;
+    int64_t direct = (int64_t)g->rounds * g->R * 256;
+    g->Plo = (p->P + 1) / 2; g->Phi = p->P - g->Plo;
+    g->Rlo = 1 << g->Plo; g->Rhi = 1 << g->Phi;
+    int64_t factor = (int64_t)G * g->rounds * (g->Rlo + g->Rhi) * 256;
+    if (p->P <= 8 && direct <= 128 * 1024) {
+        g->mode = kDirect;
+        g->table_rows = g->R;
+        g->table_words = (int64_t)g->rounds * g->R * 64;
+    } else if (p->P >= 2 && factor <= budget) {
+        g->mode = kFactor;
+        g->table_rows = g->Rlo + g->Rhi;
+        g->table_words = (int64_t)G * g->rounds * g->table_rows * 64;
+    } else {
+        return SOCKET_EUNSUPPORTED;
+    }
+    // split-K of the sparse decode: about 64 selected rows per workgroup, at most 64 splits
+    int ns = (p->max_k + kDecodeChunk - 1) / kDecodeChunk;
+    g->n_split = ns < 1 ? 1 : (ns > 64 ? 64 : ns);
+    return SOCKET_OK;
+}
+
+int record_hip(socket_ctx *ctx, hipError_t e) {
+    if (e == hipSuccess) return SOCKET_OK;
+    if (ctx) ctx->last_hip_error = (int)e;
+    return SOCKET_EHIP;
+}
+
+}  // namespace sk
+
+using namespace sk;
+
+extern "C" {
+
+int socket_validate_params(const socket_params *p) {
+    Geometry g;
+    return fill_geometry(p, &g);
+}
+
+int32_t socket_codes_per_token(int32_t L) { return pad_codes(L); }
+
+int32_t socket_code_position(int32_t L, int32_t l, int32_t t) {
+    int Lpad = pad_codes(L);
+    if (Lpad < 0 || l < 0 || l >= Lpad || t < 0) return -1;
+    int S = Lpad >= 64 ? 4 : Lpad / 16;
+    int c = Lpad >= 64 ? l / 64 : 0;
+    int lp = l - 64 * c;
+    int sub = lp % S, m = lp / S;
+    int s = ((m - t) % 16 + 16) % 16;
+    return 64 * c + sub * 16 + s;
+}
+
+int socket_create(socket_ctx **out, const socket_params *p) {
+    if (!out || !p) return SOCKET_EINVAL;
+    *out = nullptr;
+    Geometry g;
+    int rc = fill_geometry(p, &g);
+    if (rc != SOCKET_OK) return rc;
+    socket_ctx *ctx = new (std::nothrow) socket_ctx();
+    if (!ctx) return SOCKET_ENOMEM;
+    ctx->p = *p;
+    ctx->g = g;
+    ctx->last_hip_error = 0;
+    hipError_t e = hipGetDevice(&ctx->device);
+    if (e != hipSuccess) {
+        delete ctx;
+        return SOCKET_EHIP;
+    }
+    const int64_t BH = (int64_t)g.max_batch * g.Hkv;
+    const int64_t sz_tables = BH * g.table_words * 4;
+    const int64_t sz_hist = BH * kHistBins * 4;
+    const int64_t sz_cnt = BH * kCounterStride * 4;
+    const int64_t sz_cand = BH * g.max_n * 4;
+    const int64_t sz_part = (int64_t)g.max_batch * g.Hq * g.n_split * (g.d + 2) * 4;
+    ctx->scratch_bytes = sz_tables + sz_hist + sz_cnt + 2 * sz_cand + sz_part;
+    bool ok = hipMalloc((void **)&ctx->tables, sz_tables) == hipSuccess &&
+              hipMalloc((void **)&ctx->hist, sz_hist) == hipSuccess &&
+              hipMalloc((void **)&ctx->counters, sz_cnt) == hipSuccess &&
+              hipMalloc((void **)&ctx->cand_key, sz_cand) == hipSuccess &&
+              hipMalloc((void **)&ctx->cand_idx, sz_cand) == hipSuccess &&
+              hipMalloc((void **)&ctx->partials, sz_part) == hipSuccess;
+    // Histograms and counters must start at zero; the kernels that use them leave them
+    // at zero again, so this is the only clear (and it is outside any graph capture).
+    ok = ok && hipMemset(ctx->hist, 0, sz_hist) == hipSuccess &&
+         hipMemset(ctx->counters, 0, sz_cnt) == hipSuccess &&
+         hipDeviceSynchronize() == hipSuccess;
+    if (!ok) {
+        (void)hipGetLastError();
+        socket_destroy(ctx);
+        return SOCKET_ENOMEM;
+    }
+    *out = ctx;
+    return SOCKET_OK;
+}
+
+int socket_destroy(socket_ctx *ctx) {
+    if (!ctx) return SOCKET_EINVAL;
+    void *bufs[] = {ctx->tables, ctx->hist, ctx->counters, ctx->cand_key, ctx->cand_idx, ctx->partials};
+    for (void *b : bufs)
+        if (b) (void)hipFree(b);
+    delete ctx;
+    return SOCKET_OK;
+}
+
+int64_t socket_scratch_bytes(const socket_ctx *ctx) { return ctx ? ctx->scratch_bytes : 0; }
+
+static bool batch_ok(const socket_ctx *ctx, int batch) {
+    return batch >= 1 && batch <= ctx->g.max_batch;
+}
+
+static bool paging_ok(const socket_ctx *ctx, const int32_t *block_table) {
+    return (ctx->g.page > 0) == (block_table != nullptr);
+}
+
+int socket_hash_keys(socket_ctx *ctx, const void *K, const void *proj, const int32_t *block_table,
+                     const int32_t *row_begin, const int32_t *row_count, int32_t batch,
+                     int32_t max_rows, void *codes, void *stream) {
+    if (!ctx || !K || !proj || !row_begin || !row_count || !codes) return SOCKET_EINVAL;
+    if (!batch_ok(ctx, batch) || !paging_ok(ctx, block_table)) return SOCKET_EINVAL;
+    if (max_rows < 0 || max_rows > ctx->g.max_n) return SOCKET_EINVAL;
+    if (max_rows == 0) return SOCKET_OK;
+    return launch_hash_keys(ctx, K, proj, block_table, row_begin, row_count, batch, max_rows, codes,
+                            (hipStream_t)stream);
+}
+
+int socket_score(socket_ctx *ctx, const void *q, const void *codes, const void *proj, float tau,
+                 const float *vnorm, const int32_t *block_table, const int32_t *seq_len,
+                 int32_t batch, float *scores, void *stream) {
+    if (!ctx || !q || !codes || !proj || !seq_len || !scores) return SOCKET_EINVAL;
+    if (!batch_ok(ctx, batch) || !paging_ok(ctx, block_table)) return SOCKET_EINVAL;
+    if (!(tau > 0.0f) || !(tau < 3.0e38f)) return SOCKET_EINVAL;
+    return launch_score(ctx, q, codes, proj, tau, vnorm, block_table, seq_len, batch, scores,
+                        (hipStream_t)stream);
+}
+
+int socket_topk_select(socket_ctx *ctx, const float *scores, const int32_t *seq_len,
+                       const int32_t *k, int32_t batch, int32_t *idx, int32_t *n_selected,
+                       void *stream) {
+    if (!ctx || !scores || !seq_len || !k || !idx || !n_selected) return SOCKET_EINVAL;
+    if (!batch_ok(ctx, batch)) return SOCKET_EINVAL;
+    return launch_topk(ctx, scores, seq_len, k, batch, idx, n_selected, (hipStream_t)stream);
+}
+
+int socket_sparse_decode(socket_ctx *ctx, const void *q, const void *K, const void *V,
+                         const int32_t *idx, const int32_t *n_selected,
+                         const int32_t *block_table, int32_t batch, float scale, int32_t out_dtype,
+                         void *out, void *stream) {
+    if (!ctx || !q || !K || !V || !idx || !n_selected || !out) return SOCKET_EINVAL;
+    if (!batch_ok(ctx, batch) || !paging_ok(ctx, block_table)) return SOCKET_EINVAL;
+    if (out_dtype != SOCKET_BF16 && out_dtype != SOCKET_F32) return SOCKET_EINVAL;
+    if (!(scale == scale) || scale > 3.0e38f || scale < -3.0e38f) return SOCKET_EINVAL;
+    return launch_sparse_decode(ctx, q, K, V, idx, n_selected, block_table, batch, scale, out_dtype,
+                                out, (hipStream_t)stream);
+}
+
+const char *socket_strerror(int code) {
+    switch (code) {
+        case SOCKET_OK: return "ok";
+        case SOCKET_EINVAL: return "invalid argument";
+        case SOCKET_EUNSUPPORTED: return "unsupported configuration";
+        case SOCKET_ENOMEM: return "scratch allocation failed";
+        case SOCKET_EHIP: return "HIP runtime error";
+        default: return "unknown error";
+    }
+}
+
+int socket_last_hip_error(const socket_ctx *ctx) { return ctx ? ctx->last_hip_error : 0; }
+
+struct socket_graph {
+    hipGraph_t graph;
+    hipGraphExec_t exec;
+};
+
+int socket_graph_begin(void *stream) {
+    if (!stream) return SOCKET_EINVAL;  // the default stream cannot be captured
+    hipError_t e = hipStreamBeginCapture((hipStream_t)stream, hipStreamCaptureModeThreadLocal);
+    return e == hipSuccess ? SOCKET_OK : SOCKET_EHIP;
+}
+
+int socket_graph_end(void *stream, socket_graph **out) {
+    if (!stream || !out) return SOCKET_EINVAL;
+    *out = nullptr;
+    hipGraph_t graph = nullptr;
+    if (hipStreamEndCapture((hipStream_t)stream, &graph) != hipSuccess || !graph) return SOCKET_EHIP;
+    hipGraphExec_t exec = nullptr;
+    if (hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0) != hipSuccess) {
+        (void)hipGraphDestroy(graph);
+        return SOCKET_EHIP;
+    }
+    socket_graph *g = new (std::nothrow) socket_graph{graph, exec};
+    if (!g) {
+        (void)hipGraphExecDestroy(exec);
+        (void)hipGraphDestroy(graph);
+        return SOCKET_ENOMEM;
+    }
+    *out = g;
+    return SOCKET_OK;
+}
+
+int socket_graph_launch(socket_graph *g, void *stream) {
+    if (!g) return SOCKET_EINVAL;
+    return hipGraphLaunch(g->exec, (hipStream_t)stream) == hipSuccess ? SOCKET_OK : SOCKET_EHIP;
+}
+
+int socket_graph_destroy(socket_graph *g) {
+    if (!g) return SOCKET_EINVAL;
+    (void)hipGraphExecDestroy(g->exec);
+    (void)hipGraphDestroy(g->graph);
+    delete g;
+    return SOCKET_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,103 @@
+// Internal declarations shared by the libsocket translation units (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/socket.h"
+
+namespace sk {
+
+constexpr int kTile = 16;            // tokens per rotation period of the code layout
+constexpr int kHistBits = 12;        // first radix digit of the top-k select
+constexpr int kHistBins = 1 << kHistBits;
+constexpr int kMaxLdsBytes = 160 * 1024;
+constexpr int kScoreThreads = 512;
+constexpr int kDecodeThreads = 256;
+constexpr int kDecodeChunk = 64;     // selected rows a decode workgroup handles per pass
+constexpr int kCounterStride = 16;   // uint32 counters per (sequence, KV head)
+
+// How the L x R bucket probabilities of one KV head are laid out for the scoring kernel.
+//   direct : one entry per (table, bucket), already averaged over the G query heads:
+//            T[c][r][64] floats, c = table / 64.
+//   factor : bucket id split into low/high bit fields, p(r) = A[r_lo] * B[r_hi], kept per
+//            query head: F[g][c][Rlo + Rhi][64] floats (rows < Rlo are A, the rest B).
+// In both, word w of the 64 holds table l' = w % min(Lpad, 64); tables >= L hold 0.
+enum TableMode { kDirect = 0, kFactor = 1 };
+
+struct Geometry {
+    int d, Hq, Hkv, G, L, P, R;
+    int Lpad;        // codes per token
+    int S;           // lanes that share one token's 64 codes of a chunk (Lpad<64: Lpad/16, else 4)
+    int rounds;      // 64-table chunks per token
+    int cb;          // bytes per code
+    int mode;        // TableMode
+    int Plo, Phi, Rlo, Rhi;
+    int table_rows;  // rows of 64 floats per chunk (direct: R, factor: Rlo+Rhi)
+    int64_t table_words;  // floats per (sequence, KV head)
+    int page, max_blocks, num_blocks, max_n, max_k, max_batch, kv_dtype;
+    int n_split;     // split-K factor of sparse_decode
+};
+
+}  // namespace sk
+
+struct socket_ctx {
+    socket_params p;
+    sk::Geometry g;
+    int device;
+    int last_hip_error;
+    int64_t scratch_bytes;
+    float *tables;        // [max_batch*Hkv][table_words]
+    uint32_t *hist;       // [max_batch*Hkv][kHistBins]
+    uint32_t *counters;   // [max_batch*Hkv][kCounterStride]
+    uint32_t *cand_key;   // [max_batch*Hkv][max_n]
+    int32_t *cand_idx;    // [max_batch*Hkv][max_n]
+    float *partials;      // [max_batch*Hq][n_split][d+2]
+};
+
+namespace sk {
+
+int fill_geometry(const socket_params *p, Geometry *g);  // host-only validation
+int record_hip(socket_ctx *ctx, hipError_t e);
+
+// launchers (each returns a SOCKET_* code)
+int launch_hash_keys(socket_ctx *ctx, const void *K, const void *proj, const int32_t *block_table,
+                     const int32_t *row_begin, const int32_t *row_count, int batch, int max_rows,
+                     void *codes, hipStream_t st);
+int launch_score(socket_ctx *ctx, const void *q, const void *codes, const void *proj, float tau,
+                 const float *vnorm, const int32_t *block_table, const int32_t *seq_len, int batch,
+                 float *scores, hipStream_t st);
+int launch_topk(socket_ctx *ctx, const float *scores, const int32_t *seq_len, const int32_t *k,
+                int batch, int32_t *idx, int32_t *n_selected, hipStream_t st);
+int launch_sparse_decode(socket_ctx *ctx, const void *q, const void *K, const void *V,
+                         const int32_t *idx, const int32_t *n_selected, const int32_t *block_table,
+                         int batch, float scale, int out_dtype, void *out, hipStream_t st);
+
+// ---- device helpers -------------------------------------------------------------------
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) {
+    return __uint_as_float(((uint32_t)h) << 16);
+}
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);  // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// Row index (in units of rows of the [.., Hkv, tokens, width] tensor) of token t of
+// sequence b, KV head h; handles contiguous and paged storage.
+struct RowMap {
+    const int32_t *block_table;  // null = contiguous
+    int Hkv, max_n, page, max_blocks, num_blocks;
+    // -1 when the token's block is absent (paged storage with an out-of-range table entry)
+    __device__ __forceinline__ int64_t row(int b, int h, int t) const {
+        if (block_table == nullptr) return ((int64_t)b * Hkv + h) * max_n + t;
+        int blk = block_table[(int64_t)b * max_blocks + t / page];
+        if ((unsigned)blk >= (unsigned)num_blocks) return -1;
+        return ((int64_t)blk * Hkv + h) * page + (t % page);
+    }
+};
+
+}  // namespace sk

@@ -1,0 +1,281 @@
+// Eq. 2: exact softmax attention restricted to the selected tokens (Eq. 1 when every token is
+// selected).  Split-K flash-decode: the selected rows of one (sequence, KV head) are divided
+// among n_split workgroups; each gathers its K rows once for all G query heads of the group,
+// keeps a running (max, sum, weighted value sum) per query head in fp32, then gathers the V
+// rows.  The workgroup that finishes last (atomic ticket) merges the partial results in LDS.
+// Logits use no 1/sqrt(d) unless the caller passes one as `scale`; with unit-variance data
+// they reach +-100, so everything is max-subtracted.
+#include "socket_internal.h"
+
+namespace sk {
+
+struct DecodeArgs {
+    const void *q;
+    const void *K;
+    const void *V;
+    const int32_t *idx;
+    const int32_t *n_selected;
+    float *partials;
+    uint32_t *counters;
+    void *out;
+    RowMap map;
+    float scale;
+    int Hq, max_k, n_split, out_dtype;
+};
+
+template <typename T> struct Row8;     // 8 consecutive elements of a K/V row as floats
+template <> struct Row8<uint16_t> {
+    uint4 raw;
+    __device__ __forceinline__ void load(const void *p) { raw = *(const uint4 *)p; }
+    __device__ __forceinline__ void zero() { raw = make_uint4(0, 0, 0, 0); }
+    __device__ __forceinline__ void get(float *f) const {
+        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            f[2 * i] = __uint_as_float(w[i] << 16);
+            f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+};
+template <> struct Row8<float> {
+    float4 a, b;
+    __device__ __forceinline__ void load(const void *p) { a = ((const float4 *)p)[0]; b = ((const float4 *)p)[1]; }
+    __device__ __forceinline__ void zero() { a = make_float4(0, 0, 0, 0); b = a; }
+    __device__ __forceinline__ void get(float *f) const {
+        f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+    }
+};
+
+template <typename T, int D, int G>
+__global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(DecodeArgs a) {
+    constexpr int LPR = D / 8;                       // lanes per row
+    constexpr int RPW = 64 / LPR;                    // rows per wavefront pass
+    constexpr int NWAVE = kDecodeThreads / 64;
+    constexpr int RPP = NWAVE * RPW;                 // rows per workgroup pass
+    constexpr int CH = kDecodeChunk;
+    constexpr int NPASS = CH / RPP;
+    static_assert(CH % RPP == 0, "chunk must be whole passes");
+
+    __shared__ float s_p[G][CH];                     // logits, then softmax numerators
+    __shared__ int64_t s_row[CH];                    // K/V row of each chunk entry (-1 = none)
+    __shared__ float s_m[G], s_l[G], s_corr[G];
+    __shared__ float s_red[NWAVE][G][D];
+    __shared__ uint32_t s_last;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int bh = b * a.map.Hkv + h;
+    const int sub = lane % LPR, rl = lane / LPR;     // this lane's 8-element slice and row slot
+    const float ninf = -__builtin_inff();
+
+    int nsel = a.n_selected[bh];
+    nsel = nsel < 0 ? 0 : (nsel > a.max_k ? a.max_k : nsel);
+    const int per = (nsel + a.n_split - 1) / a.n_split;
+    const int r_begin = split * per;
+    const int r_end = min(nsel, r_begin + per);
+    const int32_t *idx = a.idx + (int64_t)bh * a.max_k;
+
+    float qf[G][8];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        Row8<T> r;
+        r.load((const T *)a.q + ((int64_t)b * a.Hq + h * G + g) * D + sub * 8);
+        r.get(qf[g]);
+    }
+    float acc[G][8];
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[g][e] = 0.0f;
+    if (tid < G) {
+        s_m[tid] = ninf;
+        s_l[tid] = 0.0f;
+    }
+    __syncthreads();
+
+    for (int c0 = r_begin; c0 < r_end; c0 += CH) {
+        // ---- rows of this chunk
+        if (tid < CH) {
+            int r = c0 + tid;
+            int64_t row = -1;
+            if (r < r_end) {
+                int t = idx[r];
+                if (t >= 0 && t < a.map.max_n) row = a.map.row(b, h, t);
+            }
+            s_row[tid] = row;
+        }
+        __syncthreads();
+
+        // ---- logits: scale * k.q for every query head of the group
+        {
+            Row8<T> kr[NPASS];
+            int64_t rows[NPASS];
+#pragma unroll
+            for (int p = 0; p < NPASS; ++p) {
+                rows[p] = s_row[p * RPP + wave * RPW + rl];
+                if (rows[p] >= 0) kr[p].load((const T *)a.K + rows[p] * D + sub * 8);
+                else kr[p].zero();
+            }
+#pragma unroll
+            for (int p = 0; p < NPASS; ++p) {
+                float kf[8];
+                kr[p].get(kf);
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    float dot = 0.0f;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) dot = fmaf(kf[e], qf[g][e], dot);
+#pragma unroll
+                    for (int off = 1; off < LPR; off <<= 1) dot += __shfl_xor(dot, off);
+                    if (sub == 0) s_p[g][p * RPP + wave * RPW + rl] = rows[p] >= 0 ? dot * a.scale : ninf;
+                }
+            }
+        }
+        __syncthreads();
+
+        // ---- running softmax statistics, one wavefront per query head at a time
+        for (int g = wave; g < G; g += NWAVE) {
+            float v = s_p[g][lane];                  // CH == 64 == wavefront size
+            float cmax = v;
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) cmax = fmaxf(cmax, __shfl_xor(cmax, off));
+            const float m_old = s_m[g];
+            const float m_new = fmaxf(m_old, cmax);
+            const float p = (v == ninf) ? 0.0f : expf(v - m_new);
+            float sum = p;
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+            const float corr = (m_old == ninf) ? 0.0f : expf(m_old - m_new);
+            s_p[g][lane] = p;
+            if (lane == 0) {
+                s_m[g] = m_new;
+                s_l[g] = s_l[g] * corr + sum;
+                s_corr[g] = corr;
+            }
+        }
+        __syncthreads();
+
+        // ---- weighted value rows
+        {
+            Row8<T> vr[NPASS];
+            int64_t rows[NPASS];
+#pragma unroll
+            for (int p = 0; p < NPASS; ++p) {
+                rows[p] = s_row[p * RPP + wave * RPW + rl];
+                if (rows[p] >= 0) vr[p].load((const T *)a.V + rows[p] * D + sub * 8);
+                else vr[p].zero();
+            }
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const float corr = s_corr[g];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[g][e] *= corr;
+            }
+#pragma unroll
+            for (int p = 0; p < NPASS; ++p) {
+                float vf[8];
+                vr[p].get(vf);
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    const float w = s_p[g][p * RPP + wave * RPW + rl];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc[g][e] = fmaf(w, vf[e], acc[g][e]);
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- combine the row slots of a wavefront, then the wavefronts
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float v = acc[g][e];
+#pragma unroll
+            for (int off = LPR; off < 64; off <<= 1) v += __shfl_xor(v, off);
+            if (rl == 0) s_red[wave][g][sub * 8 + e] = v;
+        }
+    __syncthreads();
+    float *part = a.partials + ((int64_t)(b * a.Hq + h * G) * a.n_split) * (D + 2);
+    for (int i = tid; i < G * D; i += kDecodeThreads) {
+        int g = i / D, c = i - g * D;
+        float v = 0.0f;
+#pragma unroll
+        for (int w = 0; w < NWAVE; ++w) v += s_red[w][g][c];
+        part[((int64_t)g * a.n_split + split) * (D + 2) + 2 + c] = v;
+    }
+    if (tid < G) {
+        part[((int64_t)tid * a.n_split + split) * (D + 2) + 0] = s_m[tid];
+        part[((int64_t)tid * a.n_split + split) * (D + 2) + 1] = s_l[tid];
+    }
+
+    // ---- last workgroup of this (sequence, KV head) merges the splits
+    __threadfence();
+    __syncthreads();
+    uint32_t *ticket = a.counters + (int64_t)bh * kCounterStride + 8;
+    if (tid == 0) s_last = atomicAdd(ticket, 1u) == gridDim.x - 1 ? 1u : 0u;
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+    for (int i = tid; i < G * D; i += kDecodeThreads) {
+        int g = i / D, c = i - g * D;
+        const float *pg = part + (int64_t)g * a.n_split * (D + 2);
+        float top = ninf;
+        for (int s = 0; s < a.n_split; ++s) top = fmaxf(top, pg[s * (D + 2)]);
+        float num = 0.0f, den = 0.0f;
+        if (top != ninf) {
+            for (int s = 0; s < a.n_split; ++s) {
+                float m = pg[s * (D + 2)];
+                float w = (m == ninf) ? 0.0f : expf(m - top);
+                den = fmaf(w, pg[s * (D + 2) + 1], den);
+                num = fmaf(w, pg[s * (D + 2) + 2 + c], num);
+            }
+        }
+        float y = den > 0.0f ? num / den : 0.0f;
+        int64_t at = ((int64_t)b * a.Hq + h * G + g) * D + c;
+        if (a.out_dtype == SOCKET_F32) ((float *)a.out)[at] = y;
+        else ((uint16_t *)a.out)[at] = f32_to_bf16_rne(y);
+    }
+    if (tid == 0) *ticket = 0;
+}
+
+template <typename T, int D>
+static int launch_decode_g(const DecodeArgs &a, int G, dim3 grid, hipStream_t st) {
+    switch (G) {
+        case 1: hipLaunchKernelGGL((sparse_decode_kernel<T, D, 1>), grid, dim3(kDecodeThreads), 0, st, a); break;
+        case 2: hipLaunchKernelGGL((sparse_decode_kernel<T, D, 2>), grid, dim3(kDecodeThreads), 0, st, a); break;
+        case 4: hipLaunchKernelGGL((sparse_decode_kernel<T, D, 4>), grid, dim3(kDecodeThreads), 0, st, a); break;
+        case 8: hipLaunchKernelGGL((sparse_decode_kernel<T, D, 8>), grid, dim3(kDecodeThreads), 0, st, a); break;
+        default: return SOCKET_EUNSUPPORTED;
+    }
+    return SOCKET_OK;
+}
+
+template <typename T>
+static int launch_decode_d(const DecodeArgs &a, int D, int G, dim3 grid, hipStream_t st) {
+    switch (D) {
+        case 64: return launch_decode_g<T, 64>(a, G, grid, st);
+        case 128: return launch_decode_g<T, 128>(a, G, grid, st);
+        case 256: return launch_decode_g<T, 256>(a, G, grid, st);
+        default: return SOCKET_EUNSUPPORTED;
+    }
+}
+
+int launch_sparse_decode(socket_ctx *ctx, const void *q, const void *K, const void *V,
+                         const int32_t *idx, const int32_t *n_selected, const int32_t *block_table,
+                         int batch, float scale, int out_dtype, void *out, hipStream_t st) {
+    const Geometry &g = ctx->g;
+    DecodeArgs a;
+    a.q = q; a.K = K; a.V = V; a.idx = idx; a.n_selected = n_selected;
+    a.partials = ctx->partials; a.counters = ctx->counters; a.out = out;
+    a.map = RowMap{block_table, g.Hkv, g.max_n, g.page, g.max_blocks, g.num_blocks};
+    a.scale = scale; a.Hq = g.Hq; a.max_k = g.max_k; a.n_split = g.n_split; a.out_dtype = out_dtype;
+    dim3 grid(g.n_split, g.Hkv, batch);
+    int rc = g.kv_dtype == SOCKET_F32 ? launch_decode_d<float>(a, g.d, g.G, grid, st)
+                                      : launch_decode_d<uint16_t>(a, g.d, g.G, grid, st);
+    if (rc != SOCKET_OK) return rc;
+    return record_hip(ctx, hipGetLastError());
+}
+
+}  // namespace sk

@@ -1,0 +1,313 @@
+// Alg. 3, TopK step: exact selection of the k largest scores per (sequence, KV head) by a
+// most-significant-digit radix select on the fp32 bit patterns, spread over many workgroups.
+//
+//   topk_hist_kernel    12-bit histogram of the leading digit of every valid score.
+//   topk_filter_kernel  every workgroup finds the threshold digit from the histogram, then
+//                       sweeps its slice: scores above the threshold digit are selected,
+//                       scores in it become candidates.  The workgroup that finishes last
+//                       (atomic ticket) resolves the candidates on the remaining score bits
+//                       and then on the token position (smaller position wins a tie), writes
+//                       the selection in ascending position order through an LDS bitmap, and
+//                       leaves histogram and counters at zero for the next call.
+// No kernel waits on another workgroup, so every launch drains.
+#include "socket_internal.h"
+
+namespace sk {
+
+constexpr int kTopkThreads = 512;
+constexpr int kBitmapTokens = kHistBins * 32;   // tokens one LDS bitmap pass covers
+
+struct TopkArgs {
+    const float *scores;
+    const int32_t *seq_len;
+    const int32_t *k;
+    int32_t *idx;
+    int32_t *n_selected;
+    uint32_t *hist;
+    uint32_t *counters;
+    uint32_t *cand_key;
+    int32_t *cand_idx;
+    int Hkv, max_n, max_k, slice;
+};
+
+// Order-preserving map from fp32 to uint32 (larger float -> larger key).
+__device__ __forceinline__ uint32_t order_key(float f) {
+    uint32_t u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ bool selectable(float f) { return f > -__builtin_inff(); }  // false for NaN
+
+// Exclusive prefix sum over the 512 threads of a block; *total gets the block sum.
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *total, uint32_t *tmp) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t x = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        uint32_t y = __shfl_up(x, off);
+        if (lane >= off) x += y;
+    }
+    if (lane == 63) tmp[wave] = x;
+    __syncthreads();
+    uint32_t base = 0, sum = 0;
+#pragma unroll
+    for (int w = 0; w < kTopkThreads / 64; ++w) {
+        uint32_t t = tmp[w];
+        if (w < wave) base += t;
+        sum += t;
+    }
+    __syncthreads();
+    *total = sum;
+    return base + x - v;
+}
+
+// Largest bin tb of the 4096-bin LDS histogram h with count(bins >= tb) >= target.
+// res[0] = tb, res[1] = count(bins > tb), res[2] = h[tb].  Requires 1 <= target <= sum(h).
+__device__ __forceinline__ void find_threshold(const uint32_t *h, uint32_t target, uint32_t *res,
+                                               uint32_t *tmp) {
+    const int t = threadIdx.x;
+    constexpr int PER = kHistBins / kTopkThreads;   // 8 bins per thread, highest bins first
+    const int top = kHistBins - 1 - t * PER;
+    uint32_t part = 0;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) part += h[top - i];
+    uint32_t total;
+    uint32_t above = block_excl_scan(part, &total, tmp);
+    if (above < target && target <= above + part) {
+        uint32_t cum = above;
+        for (int i = 0; i < PER; ++i) {
+            uint32_t c = h[top - i];
+            if (cum + c >= target) {
+                res[0] = (uint32_t)(top - i);
+                res[1] = cum;
+                res[2] = c;
+                break;
+            }
+            cum += c;
+        }
+    }
+    __syncthreads();
+}
+
+__global__ __launch_bounds__(kTopkThreads) void topk_hist_kernel(TopkArgs a) {
+    __shared__ uint32_t h[kHistBins];
+    const int tid = threadIdx.x;
+    const int bh = blockIdx.y, b = bh / a.Hkv;
+    int seq = a.seq_len[b];
+    seq = seq < 0 ? 0 : (seq > a.max_n ? a.max_n : seq);
+    const int key0 = blockIdx.x * a.slice;
+    const int key1 = min(key0 + a.slice, seq);
+    if (key0 >= key1) return;
+    for (int i = tid; i < kHistBins; i += kTopkThreads) h[i] = 0;
+    __syncthreads();
+    const float *s = a.scores + (int64_t)bh * a.max_n;
+    for (int i = key0 + tid * 4; i < key1; i += kTopkThreads * 4) {
+        float4 v = *(const float4 *)(s + i);      // max_n and slice are multiples of 4
+        float e[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (i + j < key1 && selectable(e[j])) atomicAdd(&h[order_key(e[j]) >> 20], 1u);
+    }
+    __syncthreads();
+    uint32_t *gh = a.hist + (int64_t)bh * kHistBins;
+    for (int i = tid; i < kHistBins; i += kTopkThreads)
+        if (h[i]) atomicAdd(&gh[i], h[i]);
+}
+
+// Refinement digits of a candidate after the leading 12 score bits:
+//   level 0: score bits 19..8   level 1: score bits 7..0
+//   level 2..4: bits 30..19, 18..7, 6..0 of (2^31-1 - position), so a smaller position ranks higher
+__device__ __forceinline__ uint32_t refine_digit(int level, uint32_t key, int32_t pos) {
+    uint32_t inv = 0x7fffffffu - (uint32_t)pos;
+    switch (level) {
+        case 0: return (key >> 8) & 0xfffu;
+        case 1: return key & 0xffu;
+        case 2: return (inv >> 19) & 0xfffu;
+        case 3: return (inv >> 7) & 0xfffu;
+        default: return inv & 0x7fu;
+    }
+}
+
+__global__ __launch_bounds__(kTopkThreads) void topk_filter_kernel(TopkArgs a) {
+    __shared__ uint32_t h[kHistBins];
+    __shared__ uint32_t tmp[16];
+    __shared__ uint32_t res[4];
+    __shared__ uint32_t chosen[5];
+    __shared__ uint32_t s_flag, s_count;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int bh = blockIdx.y, b = bh / a.Hkv;
+    int seq = a.seq_len[b];
+    seq = seq < 0 ? 0 : (seq > a.max_n ? a.max_n : seq);
+    uint32_t *gh = a.hist + (int64_t)bh * kHistBins;
+    uint32_t *cnt = a.counters + (int64_t)bh * kCounterStride;
+    uint32_t *ckey = a.cand_key + (int64_t)bh * a.max_n;
+    int32_t *cidx = a.cand_idx + (int64_t)bh * a.max_n;
+    int32_t *staged = cidx + a.max_n - 1;          // selected positions grow downwards from here
+    const float *s = a.scores + (int64_t)bh * a.max_n;
+
+    // ---- threshold digit from the global histogram (same result in every workgroup)
+    uint32_t part = 0;
+    for (int i = tid; i < kHistBins; i += kTopkThreads) {
+        uint32_t c = gh[i];
+        h[i] = c;
+        part += c;
+    }
+    if (tid < 4) res[tid] = 0;
+    __syncthreads();
+    uint32_t valid;
+    (void)block_excl_scan(part, &valid, tmp);
+    int kreq = a.k[b];
+    kreq = kreq < 0 ? 0 : (kreq > a.max_k ? a.max_k : kreq);
+    const uint32_t k_eff = min((uint32_t)kreq, valid);
+    if (k_eff > 0) find_threshold(h, k_eff, res, tmp);
+    const uint32_t tb = res[0], above = res[1], n_cand = res[2];
+
+    // ---- sweep this workgroup's slice
+    const int key0 = blockIdx.x * a.slice;
+    const int key1 = min(key0 + a.slice, seq);
+    if (k_eff > 0) {
+        for (int i0 = key0; i0 < key1; i0 += kTopkThreads * 4) {
+            const int i = i0 + tid * 4;
+            float e[4] = {0, 0, 0, 0};
+            if (i < key1) {
+                float4 v = *(const float4 *)(s + i);
+                e[0] = v.x; e[1] = v.y; e[2] = v.z; e[3] = v.w;
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const bool ok = i + j < key1 && selectable(e[j]);
+                const uint32_t key = order_key(e[j]);
+                const uint32_t dig = key >> 20;
+                const bool sel = ok && dig > tb, cand = ok && dig == tb;
+                unsigned long long ms = __ballot(sel), mc = __ballot(cand);
+                if (ms) {
+                    uint32_t base = 0;
+                    if (lane == 0) base = atomicAdd(&cnt[0], (uint32_t)__popcll(ms));
+                    base = __shfl(base, 0);
+                    if (sel) *(staged - (base + __popcll(ms & ((1ull << lane) - 1)))) = i + j;
+                }
+                if (mc) {
+                    uint32_t base = 0;
+                    if (lane == 0) base = atomicAdd(&cnt[1], (uint32_t)__popcll(mc));
+                    base = __shfl(base, 0);
+                    if (cand) {
+                        uint32_t at = base + __popcll(mc & ((1ull << lane) - 1));
+                        ckey[at] = key;
+                        cidx[at] = i + j;
+                    }
+                }
+            }
+        }
+    }
+
+    // ---- last workgroup of this (sequence, head) finishes the job
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) s_flag = atomicAdd(&cnt[2], 1u) == gridDim.x - 1 ? 1u : 0u;
+    __syncthreads();
+    if (!s_flag) return;
+    __threadfence();   // acquire: other workgroups' staged positions and candidates
+
+    int32_t *out = a.idx + (int64_t)bh * a.max_k;
+    if (k_eff > 0) {
+        // resolve the candidates: keep the `need` best of the n_cand in the threshold digit
+        uint32_t need = k_eff - above, remaining = n_cand;
+        if (tid == 0) s_count = above;            // next free staging slot
+        __syncthreads();
+        int level = 0;
+        while (need > 0 && need < remaining && level < 5) {
+            for (int i = tid; i < kHistBins; i += kTopkThreads) h[i] = 0;
+            __syncthreads();
+            for (uint32_t i = tid; i < n_cand; i += kTopkThreads) {
+                uint32_t key = ckey[i];
+                int32_t pos = cidx[i];
+                bool match = true;
+                for (int l = 0; l < level; ++l) match = match && refine_digit(l, key, pos) == chosen[l];
+                if (match) atomicAdd(&h[refine_digit(level, key, pos)], 1u);
+            }
+            __syncthreads();
+            find_threshold(h, need, res, tmp);
+            const uint32_t td = res[0];
+            // candidates on the current prefix with a larger digit are selected
+            for (uint32_t i = tid; i < n_cand; i += kTopkThreads) {
+                uint32_t key = ckey[i];
+                int32_t pos = cidx[i];
+                bool match = true;
+                for (int l = 0; l < level; ++l) match = match && refine_digit(l, key, pos) == chosen[l];
+                if (match && refine_digit(level, key, pos) > td) *(staged - atomicAdd(&s_count, 1u)) = pos;
+            }
+            need -= res[1];
+            remaining = res[2];
+            __syncthreads();
+            if (tid == 0) chosen[level] = td;
+            ++level;
+            __syncthreads();
+        }
+        if (need > 0) {   // need == remaining: everything left on the prefix is selected
+            for (uint32_t i = tid; i < n_cand; i += kTopkThreads) {
+                uint32_t key = ckey[i];
+                int32_t pos = cidx[i];
+                bool match = true;
+                for (int l = 0; l < level; ++l) match = match && refine_digit(l, key, pos) == chosen[l];
+                if (match) *(staged - atomicAdd(&s_count, 1u)) = pos;
+            }
+        }
+        __syncthreads();
+
+        // ---- ascending emit through an LDS bitmap, kBitmapTokens tokens per pass
+        uint32_t written = 0;
+        for (int base = 0; base < seq; base += kBitmapTokens) {
+            for (int i = tid; i < kHistBins; i += kTopkThreads) h[i] = 0;
+            __syncthreads();
+            for (uint32_t i = tid; i < k_eff; i += kTopkThreads) {
+                int32_t pos = *(staged - i) - base;
+                if (pos >= 0 && pos < kBitmapTokens) atomicOr(&h[pos >> 5], 1u << (pos & 31));
+            }
+            __syncthreads();
+            constexpr int PER = kHistBins / kTopkThreads;
+            uint32_t c = 0;
+#pragma unroll
+            for (int i = 0; i < PER; ++i) c += __popc(h[tid * PER + i]);
+            uint32_t total;
+            uint32_t at = written + block_excl_scan(c, &total, tmp);
+            for (int i = 0; i < PER; ++i) {
+                uint32_t w = h[tid * PER + i];
+                while (w) {
+                    int bit = __ffs(w) - 1;
+                    w &= w - 1;
+                    if (at < (uint32_t)a.max_k) out[at] = base + (tid * PER + i) * 32 + bit;
+                    ++at;
+                }
+            }
+            written += total;
+            __syncthreads();
+        }
+    }
+    for (int i = (int)k_eff + tid; i < a.max_k; i += kTopkThreads) out[i] = -1;
+    if (tid == 0) a.n_selected[bh] = (int32_t)k_eff;
+    // leave the shared scratch clean for the next call
+    for (int i = tid; i < kHistBins; i += kTopkThreads) gh[i] = 0;
+    if (tid < 3) cnt[tid] = 0;
+}
+
+int launch_topk(socket_ctx *ctx, const float *scores, const int32_t *seq_len, const int32_t *k,
+                int batch, int32_t *idx, int32_t *n_selected, hipStream_t st) {
+    const Geometry &g = ctx->g;
+    TopkArgs a;
+    a.scores = scores; a.seq_len = seq_len; a.k = k; a.idx = idx; a.n_selected = n_selected;
+    a.hist = ctx->hist; a.counters = ctx->counters; a.cand_key = ctx->cand_key; a.cand_idx = ctx->cand_idx;
+    a.Hkv = g.Hkv; a.max_n = g.max_n; a.max_k = g.max_k;
+    // slices of at least one block sweep (2048 scores), about 512 workgroups in flight
+    const int BH = batch * g.Hkv;
+    int per = 512 / BH;
+    if (per < 1) per = 1;
+    int slice = (g.max_n + per - 1) / per;
+    const int quantum = kTopkThreads * 4;
+    slice = (slice + quantum - 1) / quantum * quantum;
+    a.slice = slice;
+    dim3 grid((g.max_n + slice - 1) / slice, BH);
+    hipLaunchKernelGGL(topk_hist_kernel, grid, dim3(kTopkThreads), 0, st, a);
+    hipLaunchKernelGGL(topk_filter_kernel, grid, dim3(kTopkThreads), 0, st, a);
+    return record_hip(ctx, hipGetLastError());
+}
+
+}  // namespace sk

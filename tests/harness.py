@@ -1,0 +1,116 @@
+"""Glue shared by the GPU parity tests, the smoke check and the benchmark: moves the seeded
+inputs to the device, re-indexes bucket-id rows between the library's rotated layout and
+plain [token, table] order, and runs the CPU oracle per (sequence, KV head).
+
+Nothing here computes any part of the method; it only reshapes, copies and calls.
+"""
+import numpy as np
+import torch
+
+import oracle
+from paper_2602_06283_amd import binding as sk
+from paper_2602_06283_amd import workloads as wl
+
+
+def dev(x: np.ndarray, kv_dtype: str) -> torch.Tensor:
+    t = torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    return t.to(torch.bfloat16) if kv_dtype == wl.BF16 else t.float()
+
+
+def i32(x) -> torch.Tensor:
+    return torch.tensor(np.asarray(x, dtype=np.int32), dtype=torch.int32, device="cuda")
+
+
+def lpad_of(L: int) -> int:
+    if L <= 16:
+        return 16
+    if L <= 32:
+        return 32
+    if L <= 64:
+        return 64
+    return (L + 63) // 64 * 64
+
+
+def positions(L: int, n: int) -> np.ndarray:
+    """pos[t, l] = where table l's id sits in token t's Lpad-long code row (see socket.h)."""
+    Lpad = lpad_of(L)
+    S = 4 if Lpad >= 64 else Lpad // 16
+    l = np.arange(L)[None, :]
+    t = np.arange(n)[:, None]
+    c = l // 64 if Lpad >= 64 else np.zeros_like(l)
+    lp = l - 64 * c
+    return 64 * c + (lp % S) * 16 + ((lp // S - t) % 16)
+
+
+def codes_to_natural(codes: np.ndarray, L: int, t0: int = 0) -> np.ndarray:
+    """[..., n, Lpad] in the library's order -> [..., n, L]; row i is token t0 + i."""
+    n = codes.shape[-2]
+    pos = positions(L, t0 + n)[t0:]
+    return np.take_along_axis(codes, np.broadcast_to(pos, codes.shape[:-1] + (L,)), axis=-1)
+
+
+def codes_from_natural(nat: np.ndarray, L: int, dtype) -> np.ndarray:
+    """[..., n, L] -> [..., n, Lpad] in the library's order (padding positions 0)."""
+    n = nat.shape[-2]
+    out = np.zeros(nat.shape[:-1] + (lpad_of(L),), dtype=dtype)
+    pos = positions(L, n)
+    np.put_along_axis(out, np.broadcast_to(pos, nat.shape), nat.astype(dtype), axis=-1)
+    return out
+
+
+def code_dtype(P: int):
+    return np.uint8 if P <= 8 else np.uint16
+
+
+def torch_code_dtype(P: int):
+    return torch.uint8 if P <= 8 else torch.int16
+
+
+def make_ctx(layer: wl.Layer, max_k=None, page=0, max_blocks=0, num_blocks=0, max_n=None):
+    p = sk.make_params(layer.d, layer.Hq, layer.Hkv, layer.L, layer.P,
+                       sk.BF16 if layer.kv_dtype == wl.BF16 else sk.F32, layer.B,
+                       max_n if max_n is not None else layer.n,
+                       int(max_k if max_k is not None else layer.k.max()), page, max_blocks, num_blocks)
+    return sk.Context(p)
+
+
+# ---- oracle per (sequence, KV head) --------------------------------------------------
+
+def oracle_codes(layer: wl.Layer, b: int, h: int, rows=None):
+    K = layer.K[b, h] if rows is None else layer.K[b, h][rows]
+    return oracle.hash_keys(K, layer.W[h], layer.L, layer.P)
+
+
+def oracle_probs(layer: wl.Layer, b: int, h: int, tau=None, q=None):
+    tau = layer.tau if tau is None else tau
+    q = layer.q if q is None else q
+    G = layer.G
+    return np.stack([oracle.soft_probs(q[b, h * G + g], layer.W[h], layer.L, layer.P, tau)
+                     for g in range(G)])
+
+
+def oracle_scores(layer: wl.Layer, b: int, h: int, codes_nat, tau=None, vnorm=None, seq_len=None, q=None):
+    p = oracle_probs(layer, b, h, tau, q)
+    return oracle.score(codes_nat, p, layer.P, vnorm=vnorm,
+                        seq_len=int(layer.seq_len[b]) if seq_len is None else seq_len)
+
+
+def oracle_attention(layer: wl.Layer, b: int, h: int, idx, q=None):
+    q = layer.q if q is None else q
+    G = layer.G
+    return np.stack([oracle.sparse_decode(q[b, h * G + g], layer.K[b, h], layer.V[b, h], idx, layer.scale)
+                     for g in range(G)])
+
+
+def topk_sets_agree(got_idx, want_idx, scores32, margin=1e-6):
+    """Index sets must agree except for members whose score is within `margin` of the
+    k-th largest score (ties and near-ties).  Returns (ok, n_in_margin_swaps)."""
+    got, want = set(int(i) for i in got_idx if i >= 0), set(int(i) for i in want_idx if i >= 0)
+    if len(got) != len(want):
+        return False, 0
+    if got == want:
+        return True, 0
+    kth = min(float(scores32[i]) for i in want)
+    diff = got ^ want
+    ok = all(abs(float(scores32[i]) - kth) <= margin for i in diff)
+    return ok, len(diff) // 2
