@@ -114,13 +114,15 @@ int socket_create(socket_ctx **out, const socket_params *p) {
     const int64_t sz_hist = BH * kHistBins * 4;
     const int64_t sz_cnt = BH * kCounterStride * 4;
     const int64_t sz_cand = BH * g.max_n * 4;
+    const int64_t sz_staged = BH * g.max_k * 4;
     const int64_t sz_part = (int64_t)g.max_batch * g.Hq * g.n_split * (g.d + 2) * 4;
-    ctx->scratch_bytes = sz_tables + sz_hist + sz_cnt + 2 * sz_cand + sz_part;
+    ctx->scratch_bytes = sz_tables + sz_hist + sz_cnt + 2 * sz_cand + sz_staged + sz_part;
     bool ok = hipMalloc((void **)&ctx->tables, sz_tables) == hipSuccess &&
               hipMalloc((void **)&ctx->hist, sz_hist) == hipSuccess &&
               hipMalloc((void **)&ctx->counters, sz_cnt) == hipSuccess &&
               hipMalloc((void **)&ctx->cand_key, sz_cand) == hipSuccess &&
               hipMalloc((void **)&ctx->cand_idx, sz_cand) == hipSuccess &&
+              hipMalloc((void **)&ctx->staged, sz_staged) == hipSuccess &&
               hipMalloc((void **)&ctx->partials, sz_part) == hipSuccess;
     // Histograms and counters must start at zero; the kernels that use them leave them
     // at zero again, so this is the only clear (and it is outside any graph capture).
@@ -138,7 +140,7 @@ int socket_create(socket_ctx **out, const socket_params *p) {
 
 int socket_destroy(socket_ctx *ctx) {
     if (!ctx) return SOCKET_EINVAL;
-    void *bufs[] = {ctx->tables, ctx->hist, ctx->counters, ctx->cand_key, ctx->cand_idx, ctx->partials};
+    void *bufs[] = {ctx->tables, ctx->hist, ctx->counters, ctx->cand_key, ctx->cand_idx, ctx->staged, ctx->partials};
     for (void *b : bufs)
         if (b) (void)hipFree(b);
     delete ctx;

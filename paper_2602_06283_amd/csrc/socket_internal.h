@@ -52,6 +52,7 @@ struct socket_ctx {
     uint32_t *counters;   // [max_batch*Hkv][kCounterStride]
     uint32_t *cand_key;   // [max_batch*Hkv][max_n]
     int32_t *cand_idx;    // [max_batch*Hkv][max_n]
+    int32_t *staged;      // [max_batch*Hkv][max_k] selected positions before ordering
     float *partials;      // [max_batch*Hq][n_split][d+2]
 };
 

@@ -27,6 +27,7 @@ struct TopkArgs {
     uint32_t *counters;
     uint32_t *cand_key;
     int32_t *cand_idx;
+    int32_t *staged;
     int Hkv, max_n, max_k, slice;
 };
 
@@ -141,7 +142,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_filter_kernel(TopkArgs a) {
     uint32_t *cnt = a.counters + (int64_t)bh * kCounterStride;
     uint32_t *ckey = a.cand_key + (int64_t)bh * a.max_n;
     int32_t *cidx = a.cand_idx + (int64_t)bh * a.max_n;
-    int32_t *staged = cidx + a.max_n - 1;          // selected positions grow downwards from here
+    int32_t *staged = a.staged + (int64_t)bh * a.max_k;   // selected positions, unordered
     const float *s = a.scores + (int64_t)bh * a.max_n;
 
     // ---- threshold digit from the global histogram (same result in every workgroup)
@@ -183,7 +184,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_filter_kernel(TopkArgs a) {
                     uint32_t base = 0;
                     if (lane == 0) base = atomicAdd(&cnt[0], (uint32_t)__popcll(ms));
                     base = __shfl(base, 0);
-                    if (sel) *(staged - (base + __popcll(ms & ((1ull << lane) - 1)))) = i + j;
+                    if (sel) staged[base + __popcll(ms & ((1ull << lane) - 1))] = i + j;
                 }
                 if (mc) {
                     uint32_t base = 0;
@@ -233,7 +234,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_filter_kernel(TopkArgs a) {
                 int32_t pos = cidx[i];
                 bool match = true;
                 for (int l = 0; l < level; ++l) match = match && refine_digit(l, key, pos) == chosen[l];
-                if (match && refine_digit(level, key, pos) > td) *(staged - atomicAdd(&s_count, 1u)) = pos;
+                if (match && refine_digit(level, key, pos) > td) staged[atomicAdd(&s_count, 1u)] = pos;
             }
             need -= res[1];
             remaining = res[2];
@@ -248,7 +249,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_filter_kernel(TopkArgs a) {
                 int32_t pos = cidx[i];
                 bool match = true;
                 for (int l = 0; l < level; ++l) match = match && refine_digit(l, key, pos) == chosen[l];
-                if (match) *(staged - atomicAdd(&s_count, 1u)) = pos;
+                if (match) staged[atomicAdd(&s_count, 1u)] = pos;
             }
         }
         __syncthreads();
@@ -259,7 +260,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_filter_kernel(TopkArgs a) {
             for (int i = tid; i < kHistBins; i += kTopkThreads) h[i] = 0;
             __syncthreads();
             for (uint32_t i = tid; i < k_eff; i += kTopkThreads) {
-                int32_t pos = *(staged - i) - base;
+                int32_t pos = staged[i] - base;
                 if (pos >= 0 && pos < kBitmapTokens) atomicOr(&h[pos >> 5], 1u << (pos & 31));
             }
             __syncthreads();
@@ -294,7 +295,7 @@ int launch_topk(socket_ctx *ctx, const float *scores, const int32_t *seq_len, co
     const Geometry &g = ctx->g;
     TopkArgs a;
     a.scores = scores; a.seq_len = seq_len; a.k = k; a.idx = idx; a.n_selected = n_selected;
-    a.hist = ctx->hist; a.counters = ctx->counters; a.cand_key = ctx->cand_key; a.cand_idx = ctx->cand_idx;
+    a.hist = ctx->hist; a.counters = ctx->counters; a.cand_key = ctx->cand_key; a.cand_idx = ctx->cand_idx; a.staged = ctx->staged;
     a.Hkv = g.Hkv; a.max_n = g.max_n; a.max_k = g.max_k;
     // slices of at least one block sweep (2048 scores), about 512 workgroups in flight
     const int BH = batch * g.Hkv;
