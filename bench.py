@@ -1,0 +1,258 @@
+"""Benchmark of the SOCKET decode hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 128k|32k] [--layers 32]
+
+One "step" is one decode step of a Llama-3-8B-shaped attention stack: for each of `layers`
+layers (distinct K/V/bucket-id buffers, so the 256 MB Infinity Cache cannot stand in for
+HBM) append-hash the new key, soft-hash the query, score every cached key, select the
+top-k and run sparse attention over them.  All inputs are synthetic, seeded, and resident
+in HBM before the timed region.  The whole step is replayed as one HIP graph.
+
+Prints one JSON line (see the keys at the bottom).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+
+WORKLOADS = {
+    # name: (n, k, seed)   -- BASELINE configs[2] and configs[1]
+    "128k": (131072, 2048, 1002),
+    "32k": (32768, 1024, 1001),
+}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="128k", choices=sorted(WORKLOADS))
+    ap.add_argument("--layers", type=int, default=32)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2602_06283_amd import binding as sk
+    from paper_2602_06283_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    n, k, seed = WORKLOADS[args.workload]
+    Hq, Hkv, d, L, P, tau = 32, 8, 128, 64, 8, 0.5
+    NL = args.layers
+    extra = args.steps + args.warmup + 64
+    n_alloc = (n + extra + 15) // 16 * 16
+    Lpad = sk.codes_per_token(L)
+
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        ctx = sk.Context(sk.make_params(d, Hq, Hkv, L, P, sk.BF16, 1, n_alloc, k))
+        layers = []
+        for li in range(NL):
+            K, V, q, W = wl.device_layer(seed + 100 * li, Hq, Hkv, d, n, n_alloc, L, P)
+            codes = torch.zeros((1, Hkv, n_alloc, Lpad), dtype=torch.uint8, device="cuda")
+            layers.append((K, V, q, W, codes))
+        scores = torch.zeros((1, Hkv, n_alloc), dtype=torch.float32, device="cuda")
+        idx = torch.zeros((1, Hkv, k), dtype=torch.int32, device="cuda")
+        nsel = torch.zeros((1, Hkv), dtype=torch.int32, device="cuda")
+        out = torch.zeros((NL, 1, Hq, d), dtype=torch.bfloat16, device="cuda")
+        zero = torch.zeros(1, dtype=torch.int32, device="cuda")
+        one = torch.ones(1, dtype=torch.int32, device="cuda")
+        n_t = torch.full((1,), n, dtype=torch.int32, device="cuda")
+        pos = torch.full((1,), n, dtype=torch.int32, device="cuda")       # tokens before the append
+        length = torch.full((1,), n + 1, dtype=torch.int32, device="cuda")  # tokens after it
+        k_t = torch.full((1,), k, dtype=torch.int32, device="cuda")
+        stream.synchronize()
+
+        def ev():
+            return torch.cuda.Event(enable_timing=True)
+
+        def timed(fn, reps):
+            """Mean milliseconds of fn() over reps runs, HIP events on the launch stream."""
+            a, b = ev(), ev()
+            fn()
+            stream.synchronize()
+            a.record(stream)
+            for _ in range(reps):
+                fn()
+            b.record(stream)
+            stream.synchronize()
+            return a.elapsed_time(b) / reps
+
+        def capture(fn):
+            fn()                      # warm-up outside capture (first-launch work)
+            stream.synchronize()
+            with sk.Graph.capture(stream) as g:
+                fn()
+            return g
+
+        # ---------------- prefill: hash every cached key of every layer (Alg. 1) ----------
+        def prefill():
+            for (K, V, q, W, codes) in layers:
+                ctx.hash_keys(K, W, zero, n_t, 1, n, codes)
+        t_prefill_ms = timed(prefill, 2)
+        hash_flops = 2.0 * NL * Hkv * n * d * L * P
+        hash_bytes = NL * Hkv * n * (d * 2 + Lpad)
+        # the rows that decode steps will append get hashed inside the step
+
+        # ---------------- one decode step over all layers --------------------------------
+        def step():
+            for li, (K, V, q, W, codes) in enumerate(layers):
+                ctx.hash_keys(K, W, pos, one, 1, 1, codes)
+                ctx.soft_hash(q, W, tau, 1)
+                ctx.score_keys(codes, length, 1, scores)
+                ctx.topk_select(scores, length, k_t, 1, idx, nsel)
+                ctx.sparse_decode(q, K, V, idx, nsel, 1, 1.0, out[li])
+            pos.add_(1)
+            length.add_(1)
+
+        g_step = capture(step)
+        for _ in range(args.warmup):
+            g_step.launch()
+        stream.synchronize()
+        t0 = time.perf_counter()
+        a, b = ev(), ev()
+        a.record(stream)
+        for _ in range(args.steps):
+            g_step.launch()
+        b.record(stream)
+        stream.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3
+        ms_per_step = wall_ms / args.steps
+        ev_ms_per_step = a.elapsed_time(b) / args.steps
+        assert int(nsel.min()) == k and int(length[0]) <= n_alloc
+
+        # ---------------- per-stage times: each stage alone, all layers back to back ------
+        def stage_graph(body):
+            def fn():
+                for li, lay in enumerate(layers):
+                    body(li, *lay)
+            return capture(fn)
+
+        stages = {
+            "append_hash": lambda li, K, V, q, W, codes: ctx.hash_keys(K, W, pos, one, 1, 1, codes),
+            "soft_hash": lambda li, K, V, q, W, codes: ctx.soft_hash(q, W, tau, 1),
+            "score": lambda li, K, V, q, W, codes: ctx.score_keys(codes, length, 1, scores),
+            "topk": lambda li, K, V, q, W, codes: ctx.topk_select(scores, length, k_t, 1, idx, nsel),
+            "sparse_decode": lambda li, K, V, q, W, codes: ctx.sparse_decode(q, K, V, idx, nsel, 1, 1.0, out[li]),
+        }
+        stage_us = {}
+        for name, body in stages.items():
+            g = stage_graph(body)
+            stage_us[name] = timed(g.launch, 10) * 1e3 / NL     # microseconds per launch
+            g.close()
+        cur_len = int(length[0])
+
+    # ---------------- roofline of the dominant kernel (scoring) -------------------------
+    # algorithmic bytes per launch: every bucket id read once + one fp32 score written per key
+    score_bytes = Hkv * cur_len * (Lpad * 1 + 4)
+    score_gbs = score_bytes / (stage_us["score"] * 1e-6) / 1e9
+    chain_bytes = Hkv * (cur_len * (Lpad + 8) + k * (4 * d + 8))
+    chain_us = stage_us["score"] + stage_us["topk"] + stage_us["sparse_decode"]
+    traffic = None
+    prof = os.path.join(ROOT, "profiles", f"score_kernel_{args.workload}_traffic.json")
+    if os.path.exists(prof):
+        try:
+            traffic = json.load(open(prof)).get("hbm_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    result = {
+        "metric": "decode_steps_per_s",
+        "value": 1000.0 / ms_per_step,
+        "unit": "steps/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": f"llama3-8b-shaped decode attention, batch 1, ctx {n}, {NL} layers per step "
+                        f"(Hq=32, Hkv=8, d=128, bf16 KV, L=64, P=8, tau=0.5, top-k={k})",
+            "ctx": n, "layers": NL, "L": L, "P": P, "k": k, "graph": "one HIP graph per step",
+        },
+        "ms_per_step_events": ev_ms_per_step,
+        "keys_scored_per_s": Hkv * cur_len / (stage_us["score"] * 1e-6),
+        "layer_step_us": ms_per_step * 1e3 / NL,
+        "stage_us_per_layer": stage_us,
+        "chain": {"score_topk_decode_us": chain_us, "algorithmic_bytes": chain_bytes,
+                  "gbs": chain_bytes / (chain_us * 1e-6) / 1e9,
+                  "frac_of_hbm_peak": chain_bytes / (chain_us * 1e-6) / 1e9 / HBM_PEAK_GBS},
+        "roofline": {"kernel": "score_kernel", "bound": "hbm", "achieved": score_gbs,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": score_gbs / HBM_PEAK_GBS,
+                     "traffic": traffic, "algorithmic_bytes": score_bytes,
+                     "avg_launch_us": stage_us["score"]},
+        "hash_prefill": {"ms_per_layer": t_prefill_ms / NL,
+                         "tflops": hash_flops / (t_prefill_ms * 1e-3) / 1e12,
+                         "mfma_util": hash_flops / (t_prefill_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                         "gbs": hash_bytes / (t_prefill_ms * 1e-3) / 1e9},
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(layers[0], idx.shape[-1], n, Hq, Hkv, d, L, P, tau, NL,
+                                              args.cpu_seconds)
+    print(json.dumps(result))
+
+
+def cpu_baseline(layer0, k, n, Hq, Hkv, d, L, P, tau, NL, budget_s):
+    """The CPU oracle, as it stands, on one layer's share of a decode step (all 8 KV heads of
+    layer 0: hash the appended key, soft-hash 4 queries per head, score n keys, full-sort
+    top-k, attention over the k rows), repeated for about `budget_s` seconds."""
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    import numpy as np
+    import harness as hz
+    import oracle
+
+    K, V, q, W, codes = layer0
+    Kh = K[0, :, :n + 1].float().cpu().numpy()
+    Vh = V[0, :, :n + 1].float().cpu().numpy()
+    qh = q[0].float().cpu().numpy()
+    Wh = W.float().cpu().numpy()
+    nat = hz.codes_to_natural(codes[0, :, :n + 1].cpu().numpy(), L).astype(np.uint16)
+    G = Hq // Hkv
+
+    def layer_step():
+        for h in range(Hkv):
+            new_code, _ = oracle.hash_keys(Kh[h, n:n + 1], Wh[h], L, P)
+            c = nat[h].copy()
+            c[n] = new_code[0]
+            p = np.stack([oracle.soft_probs(qh[h * G + g], Wh[h], L, P, tau) for g in range(G)])
+            s = oracle.score(c, p, P)
+            sel, cnt = oracle.topk(s, k)
+            for g in range(G):
+                oracle.sparse_decode(qh[h * G + g], Kh[h], Vh[h], sel[:cnt], 1.0)
+
+    layer_step()
+    reps, t0 = 0, time.perf_counter()
+    while True:
+        layer_step()
+        reps += 1
+        el = time.perf_counter() - t0
+        if el >= budget_s or reps >= 50:
+            break
+    per_layer = el / reps
+    return {"value": 1.0 / (per_layer * NL), "unit": "steps/s", "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": f"{reps} layer-steps of layer 0 (8 KV heads, ctx {n}) in {el:.1f} s; "
+                      f"a decode step is {NL} layer-steps, so value = 1/({NL} x {per_layer:.3f} s)"}
+
+
+if __name__ == "__main__":
+    main()

@@ -141,6 +141,19 @@ int socket_score(socket_ctx *ctx, const void *q, const void *codes, const void *
                  const int32_t *seq_len, int32_t batch, float *scores, void *stream);
 
 /*
+ * The two halves of socket_score as separate calls, for callers that want to overlap or
+ * time them: socket_soft_hash is Alg. 2 (SoftBucketProbs) and leaves the bucket
+ * probabilities of every (sequence, KV head) in the context; socket_score_keys is Alg. 5
+ * (SoftHashCollisionScores) and scores the keys against the probabilities the context
+ * holds.  socket_score(...) == socket_soft_hash(...) followed by socket_score_keys(...).
+ */
+int socket_soft_hash(socket_ctx *ctx, const void *q, const void *proj, float tau, int32_t batch,
+                     void *stream);
+int socket_score_keys(socket_ctx *ctx, const void *codes, const float *vnorm,
+                      const int32_t *block_table, const int32_t *seq_len, int32_t batch,
+                      float *scores, void *stream);
+
+/*
  * Alg. 3, TopK step: for each (b, h) the min(k[b], #valid) tokens with the
  * largest scores, ties broken towards the smaller token position; -inf and NaN
  * scores are never selected.  The chosen positions are written in ascending

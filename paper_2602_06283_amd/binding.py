@@ -48,6 +48,8 @@ def lib():
         L.socket_scratch_bytes.restype = ctypes.c_int64
         L.socket_hash_keys.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, vp, vp]
         L.socket_score.argtypes = [vp, vp, vp, vp, f32, vp, vp, vp, i32, vp, vp]
+        L.socket_soft_hash.argtypes = [vp, vp, vp, f32, i32, vp]
+        L.socket_score_keys.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp]
         L.socket_topk_select.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp]
         L.socket_sparse_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, f32, i32, vp, vp]
         L.socket_strerror.argtypes = [ctypes.c_int]
@@ -63,7 +65,7 @@ def lib():
 
 EXPORTS = ("socket_validate_params", "socket_codes_per_token", "socket_code_position",
            "socket_create", "socket_destroy", "socket_scratch_bytes", "socket_hash_keys",
-           "socket_score", "socket_topk_select", "socket_sparse_decode", "socket_strerror",
+           "socket_score", "socket_soft_hash", "socket_score_keys", "socket_topk_select", "socket_sparse_decode", "socket_strerror",
            "socket_last_hip_error", "socket_graph_begin", "socket_graph_end",
            "socket_graph_launch", "socket_graph_destroy")
 
@@ -144,6 +146,15 @@ class Context:
         self._check(lib().socket_score(self._h, _ptr(q), _ptr(codes), _ptr(proj), float(tau),
                                        _ptr(vnorm), _ptr(block_table), _ptr(seq_len), batch,
                                        _ptr(scores), _stream(stream)), "socket_score")
+
+    def soft_hash(self, q, proj, tau, batch, stream=None):
+        self._check(lib().socket_soft_hash(self._h, _ptr(q), _ptr(proj), float(tau), batch,
+                                           _stream(stream)), "socket_soft_hash")
+
+    def score_keys(self, codes, seq_len, batch, scores, vnorm=None, block_table=None, stream=None):
+        self._check(lib().socket_score_keys(self._h, _ptr(codes), _ptr(vnorm), _ptr(block_table),
+                                            _ptr(seq_len), batch, _ptr(scores), _stream(stream)),
+                    "socket_score_keys")
 
     def topk_select(self, scores, seq_len, k, batch, idx, n_selected, stream=None):
         self._check(lib().socket_topk_select(self._h, _ptr(scores), _ptr(seq_len), _ptr(k), batch,

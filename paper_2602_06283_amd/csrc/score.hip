@@ -134,10 +134,10 @@ struct ScoreArgs {
     const float *vnorm;
     const int32_t *seq_len;
     float *scores;
+    uint32_t *hist;          // optional [B*Hkv][kHistBins]: leading-digit histogram of the scores
     RowMap map;
     int Lpad, rounds, R, G, Plo, Rlo, table_rows;
     int64_t table_words;
-    int keys_per_wg;
 };
 
 // 16 bucket ids of one lane: CB = 1 -> 16 bytes, CB = 2 -> 32 bytes.
@@ -159,124 +159,273 @@ template <> struct CodeVec<2> {
     __device__ __forceinline__ uint32_t code(int s) const { return (word(s >> 1) >> (16 * (s & 1))) & 0xffffu; }
 };
 
-template <int S, int CB, int MODE, bool ONE_ROUND>
+typedef __attribute__((address_space(3))) const float lds_cfloat_t;
+typedef __attribute__((address_space(3))) float lds_float_t;
+
+// LDS read at a raw byte address (the table look-ups compute their addresses as integers).
+__device__ __forceinline__ float lds_read(uint32_t addr) { return *(lds_cfloat_t *)(size_t)addr; }
+
+// Sum over this lane's 16 tables of 64-table chunk c of the bucket probabilities of one key.
+// tbase = LDS byte address of the table; BASE0 says it is known to be 0, which lets the
+// direct one-byte-id path form each address with a single v_perm_b32 when, in addition, the
+// table has a single 64-table chunk (NOOFF: nothing to add at all).
+template <int CB, int MODE, bool BASE0, bool NOOFF>
+__device__ __forceinline__ float gather16(const CodeVec<CB> &cv, uint32_t tbase, const uint32_t *woff,
+                                          int c, const ScoreArgs &a) {
+    float acc0 = 0.0f, acc1 = 0.0f;
+    if (MODE == kDirect) {
+        const uint32_t toff = (BASE0 ? 0u : tbase) + (uint32_t)c * (uint32_t)a.R * 256u;
+#pragma unroll
+        for (int s = 0; s < 16; ++s) {
+            uint32_t addr;
+            if (CB == 1)   // byte 0 <- table offset, byte 1 <- bucket id: address = id*256 + offset
+                addr = __builtin_amdgcn_perm(cv.word(s >> 2), woff[s], 0x0c0c0400u + ((uint32_t)(s & 3) << 8));
+            else
+                addr = (cv.code(s) << 8) | woff[s];
+            if (!NOOFF) addr += toff;
+            const float p = lds_read(addr);
+            if (s == 0) acc0 = p;
+            else if (s == 1) acc1 = p;
+            else if (s & 1) acc1 += p;
+            else acc0 += p;
+        }
+    } else {
+        for (int g = 0; g < a.G; ++g) {
+            const uint32_t toff = tbase + (uint32_t)((g * a.rounds + c) * a.table_rows) * 256u;
+#pragma unroll
+            for (int s = 0; s < 16; ++s) {
+                uint32_t code = cv.code(s);
+                uint32_t lo = code & (uint32_t)(a.Rlo - 1), hi = code >> a.Plo;
+                float pa = lds_read(toff + ((lo << 8) | woff[s]));
+                float pb = lds_read(toff + ((((uint32_t)a.Rlo + hi) << 8) | woff[s]));
+                if (s & 1) acc1 = fmaf(pa, pb, acc1); else acc0 = fmaf(pa, pb, acc0);
+            }
+        }
+    }
+    return acc0 + acc1;
+}
+
+// Sum over the S adjacent lanes that share a key (DPP quad permutes, no LDS traffic).
+template <int S>
+__device__ __forceinline__ float group_sum(float v) {
+    if (S >= 2) v += __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), 0xB1, 0xF, 0xF, true));  // lane ^ 1
+    if (S >= 4) v += __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), 0x4E, 0xF, 0xF, true));  // lane ^ 2
+    return v;
+}
+
+__device__ __forceinline__ uint32_t score_order_key(float f) {
+    uint32_t u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+template <bool V> struct BoolTag { static constexpr bool value = V; };
+
+// A workgroup owns chunks of CKEYS consecutive keys, taken round-robin; inside a chunk each
+// wavefront owns U*KPW consecutive keys and keeps U 16-byte loads per lane in flight.  Chunks
+// that lie wholly inside the sequence take a branch-free path in which the loads of the next
+// chunk are issued before the current one is processed (two register sets, ping-pong).
+template <int S, int CB, int MODE, bool ONE_ROUND, bool PAGED>
 __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
     extern __shared__ float tbl[];
     constexpr int KPW = 64 / S;                      // keys per wavefront pass
     constexpr int NW = kScoreThreads / 64;
-    constexpr int U = 4;                             // passes in flight per wavefront
+    constexpr int U = kScoreU;                       // passes per wavefront per chunk
+    constexpr int WKEYS = U * KPW;                   // consecutive keys a wavefront owns in a chunk
+    constexpr int CKEYS = NW * WKEYS;                // keys per chunk
+    static_assert(U % S == 0, "each lane of a key's group emits U/S results");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int h = blockIdx.y, b = blockIdx.z;
     const int64_t bh = (int64_t)b * a.map.Hkv + h;
-    const int key0 = blockIdx.x * a.keys_per_wg;
-    const int key1 = min(key0 + a.keys_per_wg, a.map.max_n);
+    const int max_n = a.map.max_n;
     int seq = a.seq_len[b];
-    seq = seq < 0 ? 0 : (seq > a.map.max_n ? a.map.max_n : seq);
-    float *out = a.scores + bh * a.map.max_n;
+    seq = seq < 0 ? 0 : (seq > max_n ? max_n : seq);
+    float *out = a.scores + bh * max_n;
+    const float *vn = a.vnorm ? a.vnorm + bh * max_n : nullptr;
     const float ninf = -__builtin_inff();
-
-    if (key0 >= seq) {                               // nothing valid here: only the -inf fill
-        for (int k = key0 + tid; k < key1; k += kScoreThreads) out[k] = ninf;
-        return;
-    }
-
-    {   // bucket-probability table -> LDS
-        const float4 *src = (const float4 *)(a.tables + bh * a.table_words);
-        float4 *dst = (float4 *)tbl;
-        for (int i = tid; i < (int)(a.table_words >> 2); i += kScoreThreads) dst[i] = src[i];
-    }
+    const int nchunks = (max_n + CKEYS - 1) / CKEYS;
+    const int nfull = seq / CKEYS;                   // chunks with every key valid
+    const int nlive = (seq + CKEYS - 1) / CKEYS;     // chunks with at least one valid key
+    const int stride = gridDim.x;
 
     const int sub = lane % S, kk = lane / S;
     const int lw = a.Lpad < 64 ? a.Lpad : 64;
-    uint32_t woff[16];                               // byte offset of this lane's table within a 64-float row
+    uint32_t woff[16];                               // byte offset of this lane's table in a 64-float row
 #pragma unroll
     for (int s = 0; s < 16; ++s) woff[s] = 4u * (uint32_t)(sub + S * ((kk + s) & 15) + lw * (kk >> 4));
-    const float *vn = a.vnorm ? a.vnorm + bh * a.map.max_n : nullptr;
+    const uint32_t tbase = (uint32_t)(size_t)(lds_float_t *)tbl;
+    uint32_t *lhist = (uint32_t *)(tbl + a.table_words);
+    const int row_bytes = a.Lpad * CB;
+    // contiguous storage: this lane's ids of chunk 0, pass 0, round 0
+    const char *lane0 = (const char *)a.codes + ((bh * max_n + wave * WKEYS + kk) * (int64_t)a.Lpad + sub * 16) * CB;
+
+    // address of this lane's 16 ids of (chunk, pass u, round c); dead = token's block is absent
+    auto code_ptr = [&](int chunk, int u, int c, bool &dead) -> const char * {
+        if (PAGED) {
+            const int key = chunk * CKEYS + wave * WKEYS + u * KPW + kk;
+            int64_t row = a.map.row(b, h, key);
+            dead = row < 0;
+            if (dead) row = 0;
+            return (const char *)a.codes + (row * a.Lpad + c * 64 + sub * 16) * CB;
+        }
+        dead = false;
+        return lane0 + (int64_t)chunk * (CKEYS * row_bytes) + u * (KPW * row_bytes) + c * (64 * CB);
+    };
+    // lane `sub` of a key's group writes the results of passes sub, sub+S, ...
+    auto emit = [&](int chunk, const float *sum, const bool *dead, int limit) {
+#pragma unroll
+        for (int j = 0; j < U / S; ++j) {
+            float v = sum[j * S];
+            bool dd = dead[j * S];
+#pragma unroll
+            for (int t = 1; t < S; ++t) {
+                v = sub == t ? sum[j * S + t] : v;
+                dd = sub == t ? dead[j * S + t] : dd;
+            }
+            const int key = chunk * CKEYS + wave * WKEYS + (j * S + sub) * KPW + kk;
+            if (key < limit) {
+                if (dd) v = ninf;
+                else if (vn) v *= vn[key];
+                out[key] = v;
+                if (a.hist && v > ninf) atomicAdd(&lhist[score_order_key(v) >> (32 - kHistBits)], 1u);
+            }
+        }
+    };
+    auto load_set = [&](CodeVec<CB> *cv, bool *dead, int chunk) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) cv[u].load(code_ptr(chunk, u, 0, dead[u]));
+    };
+
+    constexpr bool PREFETCH = ONE_ROUND;
+    CodeVec<CB> setA[U], setB[U];
+    bool deadA[U], deadB[U];
+    int chunk = blockIdx.x;
+    if (PREFETCH && chunk < nfull) load_set(setA, deadA, chunk);
+    if (blockIdx.x < nlive) {   // bucket-probability table -> LDS (skipped when only -inf fill is left)
+        const float4 *src = (const float4 *)(a.tables + bh * a.table_words);
+        float4 *dst = (float4 *)tbl;
+        const int n4 = (int)(a.table_words >> 2);
+        constexpr int B8 = 8;                        // independent loads in flight per thread
+        for (int i0 = tid; i0 < n4; i0 += B8 * kScoreThreads) {
+            float4 t[B8];
+#pragma unroll
+            for (int j = 0; j < B8; ++j) {
+                const int i = i0 + j * kScoreThreads;
+                t[j] = i < n4 ? src[i] : make_float4(0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int j = 0; j < B8; ++j) {
+                const int i = i0 + j * kScoreThreads;
+                if (i < n4) dst[i] = t[j];
+            }
+        }
+        if (a.hist)
+            for (int i = tid; i < kHistBins; i += kScoreThreads) lhist[i] = 0;
+    }
     __syncthreads();
 
-    const int span = NW * KPW;                       // keys per workgroup pass
-    for (int base0 = key0 + wave * KPW; base0 < key1; base0 += U * span) {
-        CodeVec<CB> cv[U];
-        bool live[U];
-        float sum[U];
+    // ---- chunks wholly inside the sequence
+    auto full_chunks = [&](auto base0) {
+        constexpr bool BASE0 = decltype(base0)::value;
+        auto process = [&](const CodeVec<CB> *cv, const bool *dead, int ch) {
+            float sum[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int key = base0 + u * span + kk;
-            live[u] = key < seq;
-            sum[u] = 0.0f;
-        }
-        for (int c = 0; c < (ONE_ROUND ? 1 : a.rounds); ++c) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int key = base0 + u * span + kk;
-                int64_t row = live[u] ? a.map.row(b, h, key) : -1;
-                if (row < 0) live[u] = false;
-                if (live[u])
-                    cv[u].load((const char *)a.codes + (row * a.Lpad + c * 64 + sub * 16) * CB);
+            for (int u = 0; u < U; ++u) sum[u] = group_sum<S>(gather16<CB, MODE, BASE0, BASE0 && ONE_ROUND>(cv[u], tbase, woff, 0, a));
+            emit(ch, sum, dead, max_n);
+        };
+        if (PREFETCH) {
+            while (chunk < nfull) {
+                const int c1 = chunk + stride;
+                if (c1 < nfull) load_set(setB, deadB, c1);
+                process(setA, deadA, chunk);
+                chunk = c1;
+                if (c1 >= nfull) break;
+                const int c2 = c1 + stride;
+                if (c2 < nfull) load_set(setA, deadA, c2);
+                process(setB, deadB, c1);
+                chunk = c2;
             }
+        } else {
+            for (; chunk < nfull; chunk += stride) {
+                float sum[U];
+                bool dead[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (!live[u]) continue;
-                float acc = 0.0f;
-                if (MODE == kDirect) {
-                    const char *T = (const char *)tbl + (size_t)c * a.R * 256;
+                for (int u = 0; u < U; ++u) sum[u] = 0.0f;
+                for (int c = 0; c < a.rounds; ++c) {
+                    CodeVec<CB> cur[U];
 #pragma unroll
-                    for (int s = 0; s < 16; ++s) {
-                        uint32_t addr;
-                        if (CB == 1) {
-                            // byte 0 <- woff, byte 1 <- id: address = id*256 + woff
-                            addr = __builtin_amdgcn_perm(cv[u].word(s >> 2), woff[s], 0x0c0c0400u + ((uint32_t)(s & 3) << 8));
-                        } else {
-                            addr = (cv[u].code(s) << 8) | woff[s];
-                        }
-                        acc += *(const float *)(T + addr);
-                    }
-                } else {
-                    for (int g = 0; g < a.G; ++g) {
-                        const char *T = (const char *)tbl + ((size_t)(g * a.rounds + c) * a.table_rows) * 256;
-                        float part = 0.0f;
+                    for (int u = 0; u < U; ++u) cur[u].load(code_ptr(chunk, u, c, dead[u]));
 #pragma unroll
-                        for (int s = 0; s < 16; ++s) {
-                            uint32_t code = cv[u].code(s);
-                            uint32_t lo = code & (uint32_t)(a.Rlo - 1), hi = code >> a.Plo;
-                            float pa = *(const float *)(T + ((lo << 8) | woff[s]));
-                            float pb = *(const float *)(T + (((uint32_t)a.Rlo + hi) << 8 | woff[s]));
-                            part = fmaf(pa, pb, part);
-                        }
-                        acc += part;
-                    }
+                    for (int u = 0; u < U; ++u) sum[u] += gather16<CB, MODE, BASE0, false>(cur[u], tbase, woff, c, a);
                 }
-                sum[u] += acc;
+#pragma unroll
+                for (int u = 0; u < U; ++u) sum[u] = group_sum<S>(sum[u]);
+                emit(chunk, sum, dead, max_n);
+            }
+        }
+    };
+    if (tbase == 0) full_chunks(BoolTag<true>());
+    else full_chunks(BoolTag<false>());
+
+    // ---- the chunk that straddles the end of the sequence, and the -inf fill beyond it
+    for (; chunk < nchunks; chunk += stride) {
+        float sum[U];
+        bool dead[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int key = chunk * CKEYS + wave * WKEYS + u * KPW + kk;
+            sum[u] = 0.0f;
+            dead[u] = key >= seq;
+        }
+        if (chunk < nlive) {
+            for (int c = 0; c < a.rounds; ++c) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    if (dead[u]) continue;
+                    bool absent;
+                    CodeVec<CB> cv;
+                    cv.load(code_ptr(chunk, u, c, absent));
+                    if (absent) dead[u] = true;
+                    else sum[u] += gather16<CB, MODE, false, false>(cv, tbase, woff, c, a);
+                }
             }
         }
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            float v = sum[u];
-            if (S >= 2) v += __shfl_xor(v, 1);
-            if (S >= 4) v += __shfl_xor(v, 2);
-            const int key = base0 + u * span + kk;
-            if (sub == 0 && key < key1) {
-                if (live[u]) out[key] = vn ? v * vn[key] : v;
-                else out[key] = ninf;
-            }
-        }
+        for (int u = 0; u < U; ++u) sum[u] = group_sum<S>(sum[u]);   // every lane of a key's group takes part
+        emit(chunk, sum, dead, max_n);
+    }
+
+    if (a.hist && blockIdx.x < nlive) {
+        __syncthreads();
+        uint32_t *gh = a.hist + bh * kHistBins;
+        for (int i = tid; i < kHistBins; i += kScoreThreads)
+            if (lhist[i]) atomicAdd(&gh[i], lhist[i]);
     }
 }
 
+typedef void (*score_fn_t)(ScoreArgs);
+
 template <int S, int CB, int MODE>
-static void launch_score_kernel(const ScoreArgs &a, bool one_round, dim3 grid, size_t lds, hipStream_t st) {
-    if (one_round) hipLaunchKernelGGL((score_kernel<S, CB, MODE, true>), grid, dim3(kScoreThreads), lds, st, a);
-    else hipLaunchKernelGGL((score_kernel<S, CB, MODE, false>), grid, dim3(kScoreThreads), lds, st, a);
+static score_fn_t pick_score_variant(bool one_round, bool paged) {
+    if (one_round) return paged ? score_kernel<S, CB, MODE, true, true> : score_kernel<S, CB, MODE, true, false>;
+    return paged ? score_kernel<S, CB, MODE, false, true> : score_kernel<S, CB, MODE, false, false>;
 }
 
 template <int CB, int MODE>
-static int dispatch_score_s(const ScoreArgs &a, int S, bool one_round, dim3 grid, size_t lds, hipStream_t st) {
+static score_fn_t pick_score_s(int S, bool one_round, bool paged) {
     switch (S) {
-        case 1: launch_score_kernel<1, CB, MODE>(a, one_round, grid, lds, st); return SOCKET_OK;
-        case 2: launch_score_kernel<2, CB, MODE>(a, one_round, grid, lds, st); return SOCKET_OK;
-        case 4: launch_score_kernel<4, CB, MODE>(a, one_round, grid, lds, st); return SOCKET_OK;
-        default: return SOCKET_EUNSUPPORTED;
+        case 1: return pick_score_variant<1, CB, MODE>(one_round, paged);
+        case 2: return pick_score_variant<2, CB, MODE>(one_round, paged);
+        case 4: return pick_score_variant<4, CB, MODE>(one_round, paged);
+        default: return nullptr;
     }
+}
+
+static score_fn_t pick_score(const Geometry &g) {
+    const bool one_round = g.rounds == 1, paged = g.page > 0;
+    if (g.mode == kDirect && g.cb == 1) return pick_score_s<1, kDirect>(g.S, one_round, paged);
+    if (g.mode == kFactor && g.cb == 1) return pick_score_s<1, kFactor>(g.S, one_round, paged);
+    if (g.mode == kFactor && g.cb == 2) return pick_score_s<2, kFactor>(g.S, one_round, paged);
+    return nullptr;
 }
 
 static int set_lds_limit(const void *fn, size_t lds) {
@@ -285,9 +434,8 @@ static int set_lds_limit(const void *fn, size_t lds) {
                ? SOCKET_OK : SOCKET_EHIP;
 }
 
-int launch_score(socket_ctx *ctx, const void *q, const void *codes, const void *proj, float tau,
-                 const float *vnorm, const int32_t *block_table, const int32_t *seq_len, int batch,
-                 float *scores, hipStream_t st) {
+int launch_soft_hash(socket_ctx *ctx, const void *q, const void *proj, float tau, int batch,
+                     hipStream_t st) {
     const Geometry &g = ctx->g;
     SoftHashArgs sa;
     sa.q = q; sa.W = proj; sa.tables = ctx->tables; sa.tau = (double)tau;
@@ -295,52 +443,38 @@ int launch_score(socket_ctx *ctx, const void *q, const void *codes, const void *
     sa.Lpad = g.Lpad; sa.rounds = g.rounds; sa.R = g.R; sa.mode = g.mode;
     sa.Plo = g.Plo; sa.Phi = g.Phi; sa.Rlo = g.Rlo; sa.Rhi = g.Rhi; sa.table_rows = g.table_rows;
     sa.table_words = g.table_words; sa.kv_dtype = g.kv_dtype;
-    {
-        dim3 grid((g.Lpad + kTablesPerWg - 1) / kTablesPerWg, g.Hkv, batch);
-        size_t lds = (size_t)(g.G * g.d + 2 * g.G * kTablesPerWg * g.P) * sizeof(double);
-        hipLaunchKernelGGL(soft_hash_kernel, grid, dim3(256), lds, st, sa);
-        int rc = record_hip(ctx, hipGetLastError());
-        if (rc != SOCKET_OK) return rc;
-    }
+    dim3 grid((g.Lpad + kTablesPerWg - 1) / kTablesPerWg, g.Hkv, batch);
+    size_t lds = (size_t)(g.G * g.d + 2 * g.G * kTablesPerWg * g.P) * sizeof(double);
+    hipLaunchKernelGGL(soft_hash_kernel, grid, dim3(256), lds, st, sa);
+    return record_hip(ctx, hipGetLastError());
+}
 
+int launch_score_keys(socket_ctx *ctx, const void *codes, const float *vnorm,
+                      const int32_t *block_table, const int32_t *seq_len, int batch, float *scores,
+                      hipStream_t st) {
+    const Geometry &g = ctx->g;
     ScoreArgs a;
     a.codes = codes; a.tables = ctx->tables; a.vnorm = vnorm; a.seq_len = seq_len; a.scores = scores;
     a.map = RowMap{block_table, g.Hkv, g.max_n, g.page, g.max_blocks, g.num_blocks};
     a.Lpad = g.Lpad; a.rounds = g.rounds; a.R = g.R; a.G = g.G; a.Plo = g.Plo; a.Rlo = g.Rlo;
     a.table_rows = g.table_rows; a.table_words = g.table_words;
-    // About two workgroups per CU over the whole launch; a workgroup pass covers
-    // 8 waves * 4 passes * (64/S) keys, and each workgroup pays one table load.
-    const int quantum = (kScoreThreads / 64) * 4 * (64 / g.S);
-    int64_t per_bh_wgs = 512 / ((int64_t)batch * g.Hkv);
-    if (per_bh_wgs < 1) per_bh_wgs = 1;
-    int64_t kpw = (g.max_n + per_bh_wgs - 1) / per_bh_wgs;
-    kpw = (kpw + quantum - 1) / quantum * quantum;
-    a.keys_per_wg = (int)kpw;
-    dim3 grid((g.max_n + a.keys_per_wg - 1) / a.keys_per_wg, g.Hkv, batch);
-    size_t lds = (size_t)g.table_words * 4;
-    const bool one_round = g.rounds == 1;
-    int rc;
-    // the attribute must be raised before a launch that needs more than 64 KB of LDS
-#define SK_PREP(S_, CB_, MODE_)                                                                   \
-    do {                                                                                          \
-        int r1 = set_lds_limit((const void *)score_kernel<S_, CB_, MODE_, true>, lds);            \
-        int r2 = set_lds_limit((const void *)score_kernel<S_, CB_, MODE_, false>, lds);           \
-        if (r1 != SOCKET_OK || r2 != SOCKET_OK) return SOCKET_EHIP;                               \
-    } while (0)
-    if (g.mode == kDirect && g.cb == 1) {
-        if (g.S == 1) SK_PREP(1, 1, kDirect); else if (g.S == 2) SK_PREP(2, 1, kDirect); else SK_PREP(4, 1, kDirect);
-        rc = dispatch_score_s<1, kDirect>(a, g.S, one_round, grid, lds, st);
-    } else if (g.mode == kFactor && g.cb == 1) {
-        if (g.S == 1) SK_PREP(1, 1, kFactor); else if (g.S == 2) SK_PREP(2, 1, kFactor); else SK_PREP(4, 1, kFactor);
-        rc = dispatch_score_s<1, kFactor>(a, g.S, one_round, grid, lds, st);
-    } else if (g.mode == kFactor && g.cb == 2) {
-        if (g.S == 1) SK_PREP(1, 2, kFactor); else if (g.S == 2) SK_PREP(2, 2, kFactor); else SK_PREP(4, 2, kFactor);
-        rc = dispatch_score_s<2, kFactor>(a, g.S, one_round, grid, lds, st);
-    } else {
-        return SOCKET_EUNSUPPORTED;
-    }
-#undef SK_PREP
-    if (rc != SOCKET_OK) return rc;
+    // Two resident workgroups per CU over the whole launch, chunks dealt round-robin.
+    const int ckeys = (kScoreThreads / 64) * kScoreU * (64 / g.S);
+    const int nchunks = (g.max_n + ckeys - 1) / ckeys;
+#ifndef SK_SCORE_WGS
+#define SK_SCORE_WGS (256 * 1024 / SK_SCORE_THREADS)
+#endif
+    int per_bh = SK_SCORE_WGS / (batch * g.Hkv);
+    if (per_bh < 1) per_bh = 1;
+    if (per_bh > nchunks) per_bh = nchunks;
+    dim3 grid(per_bh, g.Hkv, batch);
+    a.hist = nullptr;
+    size_t lds = (size_t)g.table_words * 4 + (a.hist ? kHistBins * 4 : 0);
+    score_fn_t fn = pick_score(g);
+    if (!fn) return SOCKET_EUNSUPPORTED;
+    // more than 64 KB of dynamic LDS has to be allowed per kernel before the launch
+    if (set_lds_limit((const void *)fn, lds) != SOCKET_OK) return SOCKET_EHIP;
+    hipLaunchKernelGGL(fn, grid, dim3(kScoreThreads), lds, st, a);
     return record_hip(ctx, hipGetLastError());
 }
 

@@ -174,8 +174,25 @@ int socket_score(socket_ctx *ctx, const void *q, const void *codes, const void *
     if (!ctx || !q || !codes || !proj || !seq_len || !scores) return SOCKET_EINVAL;
     if (!batch_ok(ctx, batch) || !paging_ok(ctx, block_table)) return SOCKET_EINVAL;
     if (!(tau > 0.0f) || !(tau < 3.0e38f)) return SOCKET_EINVAL;
-    return launch_score(ctx, q, codes, proj, tau, vnorm, block_table, seq_len, batch, scores,
-                        (hipStream_t)stream);
+    int rc = launch_soft_hash(ctx, q, proj, tau, batch, (hipStream_t)stream);
+    if (rc != SOCKET_OK) return rc;
+    return launch_score_keys(ctx, codes, vnorm, block_table, seq_len, batch, scores, (hipStream_t)stream);
+}
+
+int socket_soft_hash(socket_ctx *ctx, const void *q, const void *proj, float tau, int32_t batch,
+                     void *stream) {
+    if (!ctx || !q || !proj) return SOCKET_EINVAL;
+    if (!batch_ok(ctx, batch)) return SOCKET_EINVAL;
+    if (!(tau > 0.0f) || !(tau < 3.0e38f)) return SOCKET_EINVAL;
+    return launch_soft_hash(ctx, q, proj, tau, batch, (hipStream_t)stream);
+}
+
+int socket_score_keys(socket_ctx *ctx, const void *codes, const float *vnorm,
+                      const int32_t *block_table, const int32_t *seq_len, int32_t batch,
+                      float *scores, void *stream) {
+    if (!ctx || !codes || !seq_len || !scores) return SOCKET_EINVAL;
+    if (!batch_ok(ctx, batch) || !paging_ok(ctx, block_table)) return SOCKET_EINVAL;
+    return launch_score_keys(ctx, codes, vnorm, block_table, seq_len, batch, scores, (hipStream_t)stream);
 }
 
 int socket_topk_select(socket_ctx *ctx, const float *scores, const int32_t *seq_len,

@@ -12,7 +12,14 @@ constexpr int kTile = 16;            // tokens per rotation period of the code l
 constexpr int kHistBits = 12;        // first radix digit of the top-k select
 constexpr int kHistBins = 1 << kHistBits;
 constexpr int kMaxLdsBytes = 160 * 1024;
-constexpr int kScoreThreads = 512;
+#ifndef SK_SCORE_THREADS
+#define SK_SCORE_THREADS 512
+#endif
+#ifndef SK_SCORE_U
+#define SK_SCORE_U 4
+#endif
+constexpr int kScoreThreads = SK_SCORE_THREADS;
+constexpr int kScoreU = SK_SCORE_U;          // 16-byte loads a lane keeps in flight
 constexpr int kDecodeThreads = 256;
 constexpr int kDecodeChunk = 64;     // selected rows a decode workgroup handles per pass
 constexpr int kCounterStride = 16;   // uint32 counters per (sequence, KV head)
@@ -65,9 +72,11 @@ int record_hip(socket_ctx *ctx, hipError_t e);
 int launch_hash_keys(socket_ctx *ctx, const void *K, const void *proj, const int32_t *block_table,
                      const int32_t *row_begin, const int32_t *row_count, int batch, int max_rows,
                      void *codes, hipStream_t st);
-int launch_score(socket_ctx *ctx, const void *q, const void *codes, const void *proj, float tau,
-                 const float *vnorm, const int32_t *block_table, const int32_t *seq_len, int batch,
-                 float *scores, hipStream_t st);
+int launch_soft_hash(socket_ctx *ctx, const void *q, const void *proj, float tau, int batch,
+                     hipStream_t st);
+int launch_score_keys(socket_ctx *ctx, const void *codes, const float *vnorm,
+                      const int32_t *block_table, const int32_t *seq_len, int batch, float *scores,
+                      hipStream_t st);
 int launch_topk(socket_ctx *ctx, const float *scores, const int32_t *seq_len, const int32_t *k,
                 int batch, int32_t *idx, int32_t *n_selected, hipStream_t st);
 int launch_sparse_decode(socket_ctx *ctx, const void *q, const void *K, const void *V,

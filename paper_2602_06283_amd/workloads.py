@@ -201,3 +201,34 @@ def to_paged(X: np.ndarray, seq_len: np.ndarray, block_table: np.ndarray, num_bl
             hi = min(ln, lo + page)
             pool[block_table[b, i], :, : hi - lo, :] = X[b, :, lo:hi, :]
     return pool
+
+
+# ---- device-side generator for the benchmark's many layers ------------------------------
+
+def device_layer(seed: int, Hq: int, Hkv: int, d: int, n: int, n_alloc: int, L: int, P: int,
+                 channel_sigma: float = 0.5, planted_frac: float = 0.01, plant_coef: float = 0.7,
+                 device: str = "cuda"):
+    """Same recipe as make_layer (B = 1, bf16), drawn on the GPU with torch's generator so that
+    tens of layers of a 128K-token cache can be filled in seconds.  Rows [n, n_alloc) are
+    filled too: they are the keys/values that later decode steps "append".
+    Returns K, V [1, Hkv, n_alloc, d] bf16, q [1, Hq, d] bf16, W [Hkv, d, L*P] bf16."""
+    import torch
+    G = Hq // Hkv
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    q = torch.randn((1, Hq, d), generator=gen, device=device, dtype=torch.float32)
+    scale = torch.exp(channel_sigma * torch.randn((Hkv, 1, d), generator=gen, device=device))
+    K = torch.empty((1, Hkv, n_alloc, d), device=device, dtype=torch.bfloat16)
+    V = torch.empty((1, Hkv, n_alloc, d), device=device, dtype=torch.bfloat16)
+    cnt = int(round(planted_frac * n))
+    noise_w = float(np.sqrt(max(0.0, 1.0 - plant_coef * plant_coef)))
+    for h in range(Hkv):            # one head at a time keeps the fp32 temporaries small
+        k = torch.randn((n_alloc, d), generator=gen, device=device) * scale[h]
+        if cnt:
+            pos = torch.randperm(n, generator=gen, device=device)[:cnt]
+            g = torch.randint(0, G, (cnt,), generator=gen, device=device)
+            k[pos] = plant_coef * q[0, h * G + g] + noise_w * torch.randn((cnt, d), generator=gen, device=device)
+        K[0, h] = k.to(torch.bfloat16)
+        V[0, h] = torch.randn((n_alloc, d), generator=gen, device=device).to(torch.bfloat16)
+    W = torch.randn((Hkv, d, L * P), generator=gen, device=device).to(torch.bfloat16)
+    return K, V, q.to(torch.bfloat16), W
