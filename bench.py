@@ -111,11 +111,7 @@ def main():
         # ---------------- one decode step over all layers --------------------------------
         def step():
             for li, (K, V, q, W, codes) in enumerate(layers):
-                ctx.hash_keys(K, W, pos, one, 1, 1, codes)
-                ctx.soft_hash(q, W, tau, 1)
-                ctx.score_keys(codes, length, 1, scores)
-                ctx.topk_select(scores, length, k_t, 1, idx, nsel)
-                ctx.sparse_decode(q, K, V, idx, nsel, 1, 1.0, out[li])
+                ctx.decode_step(q, K, V, codes, W, tau, pos, k_t, 1, 1.0, scores, idx, nsel, out[li])
             pos.add_(1)
             length.add_(1)
 
@@ -143,6 +139,8 @@ def main():
             return capture(fn)
 
         stages = {
+            "fused_decode_step": lambda li, K, V, q, W, codes: ctx.decode_step(q, K, V, codes, W, tau, pos, k_t, 1, 1.0,
+                                                                          scores, idx, nsel, out[li]),
             "append_hash": lambda li, K, V, q, W, codes: ctx.hash_keys(K, W, pos, one, 1, 1, codes),
             "soft_hash": lambda li, K, V, q, W, codes: ctx.soft_hash(q, W, tau, 1),
             "score": lambda li, K, V, q, W, codes: ctx.score_keys(codes, length, 1, scores),

@@ -178,6 +178,24 @@ int socket_sparse_decode(socket_ctx *ctx, const void *q, const void *K, const vo
                          const int32_t *block_table, int32_t batch, float scale,
                          int32_t out_dtype, void *out, void *stream);
 
+/*
+ * One decode step for one attention layer, fused: the caller has already written the new
+ * key/value rows at position pos[b] of K and V.  Equivalent to
+ *     socket_hash_keys(rows pos[b] .. pos[b])            (Alg. 1 on the appended key)
+ *     socket_score with seq_len = pos + 1                (Alg. 2 + Alg. 5)
+ *     socket_topk_select with seq_len = pos + 1          (Alg. 3, TopK)
+ *     socket_sparse_decode                               (Eq. 2)
+ * in four launches instead of seven: the appended key's hash shares a launch with the
+ * queries' soft hash, and the scoring pass also produces the histogram that the selection
+ * starts from.  Results are bit-identical to the separate calls.
+ * pos, k: device int32 [batch].
+ */
+int socket_decode_step(socket_ctx *ctx, const void *q, const void *K, const void *V, void *codes,
+                       const void *proj, float tau, const float *vnorm, const int32_t *block_table,
+                       const int32_t *pos, const int32_t *k, int32_t batch, float scale,
+                       float *scores, int32_t *idx, int32_t *n_selected, int32_t out_dtype,
+                       void *out, void *stream);
+
 /* Text for an error code; last HIP error code seen by this context (0 if none). */
 const char *socket_strerror(int code);
 int socket_last_hip_error(const socket_ctx *ctx);

@@ -52,6 +52,8 @@ def lib():
         L.socket_score_keys.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp]
         L.socket_topk_select.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp]
         L.socket_sparse_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, f32, i32, vp, vp]
+        L.socket_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, i32, f32, vp, vp, vp,
+                                         i32, vp, vp]
         L.socket_strerror.argtypes = [ctypes.c_int]
         L.socket_strerror.restype = ctypes.c_char_p
         L.socket_last_hip_error.argtypes = [vp]
@@ -65,7 +67,7 @@ def lib():
 
 EXPORTS = ("socket_validate_params", "socket_codes_per_token", "socket_code_position",
            "socket_create", "socket_destroy", "socket_scratch_bytes", "socket_hash_keys",
-           "socket_score", "socket_soft_hash", "socket_score_keys", "socket_topk_select", "socket_sparse_decode", "socket_strerror",
+           "socket_score", "socket_soft_hash", "socket_score_keys", "socket_topk_select", "socket_sparse_decode", "socket_decode_step", "socket_strerror",
            "socket_last_hip_error", "socket_graph_begin", "socket_graph_end",
            "socket_graph_launch", "socket_graph_destroy")
 
@@ -168,6 +170,16 @@ class Context:
                                                _ptr(n_selected), _ptr(block_table), batch,
                                                float(scale), out_dtype, _ptr(out), _stream(stream)),
                     "socket_sparse_decode")
+
+
+    def decode_step(self, q, K, V, codes, proj, tau, pos, k, batch, scale, scores, idx, n_selected, out,
+                    vnorm=None, block_table=None, stream=None):
+        out_dtype = F32 if out.dtype == torch.float32 else BF16
+        self._check(lib().socket_decode_step(self._h, _ptr(q), _ptr(K), _ptr(V), _ptr(codes), _ptr(proj),
+                                             float(tau), _ptr(vnorm), _ptr(block_table), _ptr(pos),
+                                             _ptr(k), batch, float(scale), _ptr(scores), _ptr(idx),
+                                             _ptr(n_selected), out_dtype, _ptr(out), _stream(stream)),
+                    "socket_decode_step")
 
 
 class Graph:

@@ -29,21 +29,6 @@ struct HashArgs {
     int n_chunks;
 };
 
-// Table whose id is stored at position pos of token t's code row.
-__device__ __forceinline__ int table_at(int pos, int t, int S) {
-    int c = pos >> 6, p = pos & 63;
-    int sub = p >> 4, s = p & 15;
-    return (c << 6) + sub + S * ((t + s) & 15);
-}
-
-// P-bit field starting at bit `bitpos` of a little-endian bit row.
-__device__ __forceinline__ uint32_t bit_field(const uint32_t *row, int bitpos, int P) {
-    int w = bitpos >> 5, off = bitpos & 31;
-    uint32_t v = row[w] >> off;
-    if (off + P > 32) v |= row[w + 1] << (32 - off);
-    return v & ((1u << P) - 1u);
-}
-
 // Cut `nrows` bit rows (LDS, stride `stride` words, bit j of a row = sign bit of the
 // projection onto column first_table*P + j) into bucket ids and store them.
 // tok[r] = logical token of row r, grow[r] = its row in the codes tensor (-1 = skip).
@@ -348,7 +333,11 @@ int launch_hash_keys(socket_ctx *ctx, const void *K, const void *proj, const int
     a.d = g.d; a.L = g.L; a.P = g.P; a.LP = g.L * g.P; a.Lpad = g.Lpad; a.S = g.S; a.cb = g.cb;
     a.rows_per_wg = 0; a.tables_per_chunk = g.L; a.n_chunks = 1;
     int rc;
-    if (g.kv_dtype == SOCKET_F32) {
+    if (max_rows == 1) {
+        // one appended key per sequence: the projection kernel with its W slab staged in LDS
+        return launch_project(ctx, nullptr, proj, 1.0f, K, codes, block_table, row_begin, row_count,
+                              nullptr, batch, st);
+    } else if (g.kv_dtype == SOCKET_F32) {
         rc = launch_rows<float>(a, g.Hkv, batch, max_rows, st);
     } else if (max_rows < 64) {
         rc = launch_rows<uint16_t>(a, g.Hkv, batch, max_rows, st);

@@ -1,9 +1,11 @@
 // Alg. 2 (SoftBucketProbs) and Alg. 5 (SoftHashCollisionScores, the soft score of Eq. 3).
 //
-//   soft_hash_kernel  builds, per (sequence, KV head), the table of bucket probabilities of
+//   project_kernel    builds, per (sequence, KV head), the table of bucket probabilities of
 //                     the G queries that share the head.  Evaluated in fp64 and stored as
 //                     fp32.  A softmax over the corners of {+-1}^P factorises over the
 //                     planes, p(r) = prod_i sigmoid(+-2 u_i / tau), which is the form used.
+//                     The same launch can hash the one key a decode step appends (Alg. 1),
+//                     since both are projections onto the same hyperplanes.
 //   score_kernel      loads that table into LDS and streams the bucket ids of every key
 //                     once: 64/S keys per wavefront pass, S lanes per key, each lane reading
 //                     16 ids with one 16-byte load.  The rotated id order (see socket.h)
@@ -13,115 +15,220 @@
 
 namespace sk {
 
-struct SoftHashArgs {
-    const void *q;
-    const void *W;
+struct ProjectArgs {
+    const void *q;          // [B, Hq, d]; null = no soft hash
+    const void *W;          // [Hkv, d, L*P]
     float *tables;
     double tau;
-    int d, G, Hkv, Hq, L, P, LP, Lpad, rounds, R, mode, Plo, Phi, Rlo, Rhi, table_rows;
+    const void *K;          // key cache; null = no append hash
+    void *codes;
+    const int32_t *pos;     // [B] position of the appended key (append hash only)
+    const int32_t *count;   // optional [B]: append only where count[b] >= 1
+    int32_t *len_out;       // optional [B]: pos[b] + 1
+    RowMap map;
+    int d, G, Hkv, Hq, L, P, LP, Lpad, S, cb, rounds, R, mode, Plo, Phi, Rlo, Rhi, table_rows, tpw;
     int64_t table_words;
-    int kv_dtype;
 };
 
-constexpr int kTablesPerWg = 8;
+template <typename T> __device__ __forceinline__ float elem_to_f32(T v);
+template <> __device__ __forceinline__ float elem_to_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ float elem_to_f32<uint16_t>(uint16_t v) { return bf16_to_f32(v); }
 
-__device__ __forceinline__ double sigmoid64(double x) { return 1.0 / (1.0 + exp(-x)); }
-
-__global__ __launch_bounds__(256) void soft_hash_kernel(SoftHashArgs a) {
+// One workgroup projects onto the hyperplanes of `tpw` consecutive tables of one KV head:
+//   - the G queries of the head's group, in fp64, giving those tables' bucket probabilities
+//     (Alg. 2; the softmax over corners is evaluated as a product of per-plane sigmoids);
+//   - optionally the key appended at position pos[b], in fp32 FMA, giving its bucket ids for
+//     those tables (Alg. 1 on one row).
+// The slab of W it needs is staged in LDS with all loads of a thread in flight at once.
+template <typename T>
+__global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
     extern __shared__ double sm64[];
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int h = blockIdx.y, b = blockIdx.z;
-    const int t0 = blockIdx.x * kTablesPerWg;               // first table of this workgroup
+    const int t0 = blockIdx.x * a.tpw;                       // first table of this workgroup
+    const int cols = a.tpw * a.P;                            // <= 64
+    const int col0 = t0 * a.P;
+    const int ncols = max(0, min(cols, a.LP - col0));        // live columns
+    const bool soft = a.q != nullptr, app = a.K != nullptr;
+
     double *qd = sm64;                                       // [G][d]
-    double *sp = qd + a.G * a.d;                             // [G][8][P] sigmoid(+2u/tau)
-    double *sn = sp + a.G * kTablesPerWg * a.P;              // [G][8][P] sigmoid(-2u/tau)
+    double *sp = qd + a.G * a.d;                             // [G][tpw][P] sigmoid(+2u/tau)
+    double *sn = sp + a.G * a.tpw * a.P;                     // [G][tpw][P] sigmoid(-2u/tau)
+    double *half = sn + a.G * a.tpw * a.P;                   // [G][tpw][Rlo+Rhi] (direct mode)
+    const int nhalf = a.mode == kDirect ? a.G * a.tpw * (a.Rlo + a.Rhi) : 0;
+    float *kf = (float *)(half + nhalf);                     // [d]
+    uint32_t *bits = (uint32_t *)(kf + a.d);                 // [2]
+    T *w = (T *)(bits + 4);                                  // [d][cols], 16-byte aligned
 
-    for (int i = tid; i < a.G * a.d; i += 256) {
-        int g = i / a.d, c = i - g * a.d;
-        int64_t at = ((int64_t)b * a.Hq + h * a.G + g) * a.d + c;
-        qd[i] = a.kv_dtype == SOCKET_F32 ? (double)((const float *)a.q)[at]
-                                         : (double)bf16_to_f32(((const uint16_t *)a.q)[at]);
-    }
-    __syncthreads();
-
-    const int cols = kTablesPerWg * a.P;
-    const double inv_sqrt_d = 1.0 / sqrt((double)a.d);
-    for (int i = tid; i < a.G * cols; i += 256) {
-        int g = i / cols, j = i - g * cols;
-        int tl = j / a.P, pl = j - tl * a.P;
-        int l = t0 + tl;
-        double plus = 0.0, minus = 0.0;
-        if (l < a.L) {
-            int64_t col = (int64_t)l * a.P + pl;
-            double z = 0.0;
-            if (a.kv_dtype == SOCKET_F32) {
-                const float *W = (const float *)a.W + (int64_t)h * a.d * a.LP;
-                for (int c = 0; c < a.d; ++c) z += (double)W[(int64_t)c * a.LP + col] * qd[g * a.d + c];
-            } else {
-                const uint16_t *W = (const uint16_t *)a.W + (int64_t)h * a.d * a.LP;
-                for (int c = 0; c < a.d; ++c)
-                    z += (double)bf16_to_f32(W[(int64_t)c * a.LP + col]) * qd[g * a.d + c];
+    // ---- W slab -> LDS
+    const T *Wg = (const T *)a.W + (int64_t)h * a.d * a.LP + col0;
+    constexpr int ES = sizeof(T), EPD = 4 / ES;              // elements per dword
+    const bool wide = (col0 % EPD == 0) && (a.LP % EPD == 0) && (ncols % EPD == 0) && (cols % EPD == 0);
+    constexpr int NB = 16;                                   // loads in flight per thread
+    if (wide) {
+        const int dpr = ncols / EPD, total = a.d * dpr;
+        for (int i0 = tid; i0 < total; i0 += NB * 256) {
+            uint32_t v[NB];
+#pragma unroll
+            for (int j = 0; j < NB; ++j) {
+                const int i = i0 + j * 256;
+                if (i < total) {
+                    const int c = i / dpr, x = i - c * dpr;
+                    v[j] = *(const uint32_t *)(Wg + (int64_t)c * a.LP + x * EPD);
+                }
             }
-            double u = tanh(z) * inv_sqrt_d;
-            plus = sigmoid64(2.0 * u / a.tau);
-            minus = sigmoid64(-2.0 * u / a.tau);
+#pragma unroll
+            for (int j = 0; j < NB; ++j) {
+                const int i = i0 + j * 256;
+                if (i < total) {
+                    const int c = i / dpr, x = i - c * dpr;
+                    *(uint32_t *)(w + c * cols + x * EPD) = v[j];
+                }
+            }
         }
-        sp[(g * kTablesPerWg + tl) * a.P + pl] = plus;
-        sn[(g * kTablesPerWg + tl) * a.P + pl] = minus;
+    } else {
+        const int total = a.d * ncols;
+        for (int i0 = tid; i0 < total; i0 += NB * 256) {
+            T v[NB];
+#pragma unroll
+            for (int j = 0; j < NB; ++j) {
+                const int i = i0 + j * 256;
+                if (i < total) {
+                    const int c = i / ncols, x = i - c * ncols;
+                    v[j] = Wg[(int64_t)c * a.LP + x];
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < NB; ++j) {
+                const int i = i0 + j * 256;
+                if (i < total) {
+                    const int c = i / ncols, x = i - c * ncols;
+                    w[c * cols + x] = v[j];
+                }
+            }
+        }
+    }
+    if (soft) {
+        for (int i = tid; i < a.G * a.d; i += 256) {
+            int g = i / a.d, c = i - g * a.d;
+            qd[i] = (double)elem_to_f32<T>(((const T *)a.q)[((int64_t)b * a.Hq + h * a.G + g) * a.d + c]);
+        }
+    }
+    int tok = 0;
+    int64_t krow = -1;
+    if (app) {
+        tok = a.pos[b];
+        const bool wanted = a.count == nullptr || a.count[b] >= 1;
+        if (wanted && tok >= 0 && tok < a.map.max_n) krow = a.map.row(b, h, tok);
+        for (int c = tid; c < a.d; c += 256)
+            kf[c] = krow >= 0 ? elem_to_f32<T>(((const T *)a.K)[krow * a.d + c]) : 0.0f;
+        if (a.len_out && blockIdx.x == 0 && h == 0 && tid == 0) a.len_out[b] = tok + 1;
     }
     __syncthreads();
+
+    // ---- appended key: fp32 FMA over the channels in ascending order, sign bits by ballot
+    if (app && wave == 0) {
+        float acc = 0.0f;
+        if (lane < ncols)
+            for (int c = 0; c < a.d; ++c) acc = fmaf(kf[c], elem_to_f32<T>(w[c * cols + lane]), acc);
+        unsigned long long m = __ballot(lane < ncols && acc >= 0.0f);
+        if (lane == 0) {
+            bits[0] = (uint32_t)m;
+            bits[1] = (uint32_t)(m >> 32);
+            bits[2] = 0;
+        }
+    }
+    // ---- queries: fp64 projections, u = tanh(z)/sqrt(d), per-plane sigmoids of +-2u/tau
+    if (soft) {
+        const double inv_sqrt_d = 1.0 / sqrt((double)a.d);
+        for (int i = tid; i < a.G * cols; i += 256) {
+            int g = i / cols, j = i - g * cols;
+            double plus = 0.0, minus = 0.0;
+            if (j < ncols) {
+                double z = 0.0;
+                for (int c = 0; c < a.d; ++c) z += (double)elem_to_f32<T>(w[c * cols + j]) * qd[g * a.d + c];
+                const double x = 2.0 * tanh(z) * inv_sqrt_d / a.tau;
+                const double e = exp(-fabs(x));                 // in (0, 1]
+                const double big = 1.0 / (1.0 + e), small = e / (1.0 + e);
+                plus = x >= 0.0 ? big : small;
+                minus = x >= 0.0 ? small : big;
+            }
+            sp[g * cols + j] = plus;        // [g][tl][pl] with j = tl*P + pl
+            sn[g * cols + j] = minus;
+        }
+    }
+    __syncthreads();
+
+    if (app && krow >= 0 && tid < a.tpw) {
+        const int l = t0 + tid;
+        if (l < a.Lpad) {
+            const uint32_t code = l < a.L ? bit_field(bits, tid * a.P, a.P) : 0u;
+            const int64_t at = krow * a.Lpad + code_pos(l, tok, a.S);
+            if (a.cb == 1) ((uint8_t *)a.codes)[at] = (uint8_t)code;
+            else ((uint16_t *)a.codes)[at] = (uint16_t)code;
+        }
+    }
+    if (!soft) return;
 
     const int lw = a.Lpad < 64 ? a.Lpad : 64;        // distinct tables per 64-word row
     const int copies = 64 / lw;
-    float *T = a.tables + ((int64_t)b * a.Hkv + h) * a.table_words;
+    const int hrows = a.Rlo + a.Rhi;
+    float *Tg = a.tables + ((int64_t)b * a.Hkv + h) * a.table_words;
+    // products over the low and the high planes: p(r) = lo[r & (Rlo-1)] * hi[r >> Plo]
+    auto half_product = [&](int g, int tl, int row) -> double {
+        double p = 1.0;
+        if (row < a.Rlo) {
+            for (int pl = 0; pl < a.Plo; ++pl) {
+                int at = g * cols + tl * a.P + pl;
+                p *= ((row >> pl) & 1) ? sp[at] : sn[at];
+            }
+        } else {
+            const int rh = row - a.Rlo;
+            for (int pl = 0; pl < a.Phi; ++pl) {
+                int at = g * cols + tl * a.P + a.Plo + pl;
+                p *= ((rh >> pl) & 1) ? sp[at] : sn[at];
+            }
+        }
+        return p;
+    };
     if (a.mode == kDirect) {
-        for (int i = tid; i < kTablesPerWg * a.R; i += 256) {
-            int tl = i % kTablesPerWg, r = i / kTablesPerWg;
+        for (int i = tid; i < a.G * a.tpw * hrows; i += 256) {
+            int row = i % hrows, rest = i / hrows;
+            int tl = rest % a.tpw, g = rest / a.tpw;
+            half[i] = half_product(g, tl, row);               // [g][tl][row]
+        }
+        __syncthreads();
+        const double inv_g = 1.0 / (double)a.G;
+        for (int i = tid; i < a.tpw * a.R; i += 256) {
+            int tl = i % a.tpw, r = i / a.tpw;
             int l = t0 + tl;
             if (l >= a.Lpad) continue;
             double mean = 0.0;
             if (l < a.L) {
                 for (int g = 0; g < a.G; ++g) {
-                    double p = 1.0;
-                    for (int pl = 0; pl < a.P; ++pl) {
-                        int at = (g * kTablesPerWg + tl) * a.P + pl;
-                        p *= ((r >> pl) & 1) ? sp[at] : sn[at];
-                    }
-                    mean += p;
+                    const double *hp = half + (g * a.tpw + tl) * hrows;
+                    mean += hp[r & (a.Rlo - 1)] * hp[a.Rlo + (r >> a.Plo)];
                 }
-                mean /= (double)a.G;
+                mean *= inv_g;
             }
             int c = l >> 6, lp = l & 63;
             for (int cp = 0; cp < copies; ++cp)
-                T[((int64_t)c * a.R + r) * 64 + lp + cp * lw] = (float)mean;
+                Tg[((int64_t)c * a.R + r) * 64 + lp + cp * lw] = (float)mean;
         }
     } else {
-        const int rows = a.Rlo + a.Rhi;
-        for (int i = tid; i < kTablesPerWg * rows * a.G; i += 256) {
-            int tl = i % kTablesPerWg, rest = i / kTablesPerWg;
-            int row = rest % rows, g = rest / rows;
+        for (int i = tid; i < a.tpw * hrows * a.G; i += 256) {
+            int tl = i % a.tpw, rest = i / a.tpw;
+            int row = rest % hrows, g = rest / hrows;
             int l = t0 + tl;
             if (l >= a.Lpad) continue;
             double p = 0.0;
             if (l < a.L) {
-                if (row < a.Rlo) {
-                    p = 1.0 / (double)a.G;      // the 1/G of the group mean rides on the low factor
-                    for (int pl = 0; pl < a.Plo; ++pl) {
-                        int at = (g * kTablesPerWg + tl) * a.P + pl;
-                        p *= ((row >> pl) & 1) ? sp[at] : sn[at];
-                    }
-                } else {
-                    int rh = row - a.Rlo;
-                    p = 1.0;
-                    for (int pl = 0; pl < a.Phi; ++pl) {
-                        int at = (g * kTablesPerWg + tl) * a.P + a.Plo + pl;
-                        p *= ((rh >> pl) & 1) ? sp[at] : sn[at];
-                    }
-                }
+                p = half_product(g, tl, row);
+                if (row < a.Rlo) p /= (double)a.G;    // the 1/G of the group mean rides on the low factor
             }
             int c = l >> 6, lp = l & 63;
             for (int cp = 0; cp < copies; ++cp)
-                T[(((int64_t)g * a.rounds + c) * rows + row) * 64 + lp + cp * lw] = (float)p;
+                Tg[(((int64_t)g * a.rounds + c) * hrows + row) * 64 + lp + cp * lw] = (float)p;
         }
     }
 }
@@ -434,24 +541,45 @@ static int set_lds_limit(const void *fn, size_t lds) {
                ? SOCKET_OK : SOCKET_EHIP;
 }
 
+int launch_project(socket_ctx *ctx, const void *q, const void *proj, float tau, const void *K,
+                   void *codes, const int32_t *block_table, const int32_t *pos, const int32_t *count,
+                   int32_t *len_out, int batch, hipStream_t st) {
+    const Geometry &g = ctx->g;
+    ProjectArgs a;
+    a.q = q; a.W = proj; a.tables = ctx->tables; a.tau = (double)tau;
+    a.K = K; a.codes = codes; a.pos = pos; a.count = count; a.len_out = len_out;
+    a.map = RowMap{block_table, g.Hkv, g.max_n, g.page, g.max_blocks, g.num_blocks};
+    a.d = g.d; a.G = g.G; a.Hkv = g.Hkv; a.Hq = g.Hq; a.L = g.L; a.P = g.P; a.LP = g.L * g.P;
+    a.Lpad = g.Lpad; a.S = g.S; a.cb = g.cb; a.rounds = g.rounds; a.R = g.R; a.mode = g.mode;
+    a.Plo = g.Plo; a.Phi = g.Phi; a.Rlo = g.Rlo; a.Rhi = g.Rhi; a.table_rows = g.table_rows;
+    a.table_words = g.table_words;
+    a.tpw = g.P <= 8 ? 8 : 4;                                 // tpw * P <= 64 columns
+    const int cols = a.tpw * g.P;
+    const int nhalf = g.mode == kDirect ? g.G * a.tpw * (g.Rlo + g.Rhi) : 0;
+    const int esize = g.kv_dtype == SOCKET_F32 ? 4 : 2;
+    size_t lds = (size_t)(g.G * g.d + 2 * g.G * cols + nhalf) * sizeof(double) + (size_t)g.d * 4 + 16 +
+                 (size_t)g.d * cols * esize;
+    dim3 grid((g.Lpad + a.tpw - 1) / a.tpw, g.Hkv, batch);
+    if (g.kv_dtype == SOCKET_F32) {
+        if (lds > 64 * 1024 && hipFuncSetAttribute((const void *)project_kernel<float>,
+                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return SOCKET_EHIP;
+        hipLaunchKernelGGL(project_kernel<float>, grid, dim3(256), lds, st, a);
+    } else {
+        if (lds > 64 * 1024 && hipFuncSetAttribute((const void *)project_kernel<uint16_t>,
+                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return SOCKET_EHIP;
+        hipLaunchKernelGGL(project_kernel<uint16_t>, grid, dim3(256), lds, st, a);
+    }
+    return record_hip(ctx, hipGetLastError());
+}
+
 int launch_soft_hash(socket_ctx *ctx, const void *q, const void *proj, float tau, int batch,
                      hipStream_t st) {
-    const Geometry &g = ctx->g;
-    SoftHashArgs sa;
-    sa.q = q; sa.W = proj; sa.tables = ctx->tables; sa.tau = (double)tau;
-    sa.d = g.d; sa.G = g.G; sa.Hkv = g.Hkv; sa.Hq = g.Hq; sa.L = g.L; sa.P = g.P; sa.LP = g.L * g.P;
-    sa.Lpad = g.Lpad; sa.rounds = g.rounds; sa.R = g.R; sa.mode = g.mode;
-    sa.Plo = g.Plo; sa.Phi = g.Phi; sa.Rlo = g.Rlo; sa.Rhi = g.Rhi; sa.table_rows = g.table_rows;
-    sa.table_words = g.table_words; sa.kv_dtype = g.kv_dtype;
-    dim3 grid((g.Lpad + kTablesPerWg - 1) / kTablesPerWg, g.Hkv, batch);
-    size_t lds = (size_t)(g.G * g.d + 2 * g.G * kTablesPerWg * g.P) * sizeof(double);
-    hipLaunchKernelGGL(soft_hash_kernel, grid, dim3(256), lds, st, sa);
-    return record_hip(ctx, hipGetLastError());
+    return launch_project(ctx, q, proj, tau, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, batch, st);
 }
 
 int launch_score_keys(socket_ctx *ctx, const void *codes, const float *vnorm,
                       const int32_t *block_table, const int32_t *seq_len, int batch, float *scores,
-                      hipStream_t st) {
+                      bool with_hist, hipStream_t st) {
     const Geometry &g = ctx->g;
     ScoreArgs a;
     a.codes = codes; a.tables = ctx->tables; a.vnorm = vnorm; a.seq_len = seq_len; a.scores = scores;
@@ -468,7 +596,7 @@ int launch_score_keys(socket_ctx *ctx, const void *codes, const float *vnorm,
     if (per_bh < 1) per_bh = 1;
     if (per_bh > nchunks) per_bh = nchunks;
     dim3 grid(per_bh, g.Hkv, batch);
-    a.hist = nullptr;
+    a.hist = with_hist ? ctx->hist : nullptr;
     size_t lds = (size_t)g.table_words * 4 + (a.hist ? kHistBins * 4 : 0);
     score_fn_t fn = pick_score(g);
     if (!fn) return SOCKET_EUNSUPPORTED;

@@ -115,15 +115,17 @@ int socket_create(socket_ctx **out, const socket_params *p) {
     const int64_t sz_cnt = BH * kCounterStride * 4;
     const int64_t sz_cand = BH * g.max_n * 4;
     const int64_t sz_staged = BH * g.max_k * 4;
+    const int64_t sz_seq = (int64_t)g.max_batch * 4;
     const int64_t sz_part = (int64_t)g.max_batch * g.Hq * g.n_split * (g.d + 2) * 4;
-    ctx->scratch_bytes = sz_tables + sz_hist + sz_cnt + 2 * sz_cand + sz_staged + sz_part;
+    ctx->scratch_bytes = sz_tables + sz_hist + sz_cnt + 2 * sz_cand + sz_staged + sz_part + sz_seq;
     bool ok = hipMalloc((void **)&ctx->tables, sz_tables) == hipSuccess &&
               hipMalloc((void **)&ctx->hist, sz_hist) == hipSuccess &&
               hipMalloc((void **)&ctx->counters, sz_cnt) == hipSuccess &&
               hipMalloc((void **)&ctx->cand_key, sz_cand) == hipSuccess &&
               hipMalloc((void **)&ctx->cand_idx, sz_cand) == hipSuccess &&
               hipMalloc((void **)&ctx->staged, sz_staged) == hipSuccess &&
-              hipMalloc((void **)&ctx->partials, sz_part) == hipSuccess;
+              hipMalloc((void **)&ctx->partials, sz_part) == hipSuccess &&
+              hipMalloc((void **)&ctx->seq_scratch, sz_seq) == hipSuccess;
     // Histograms and counters must start at zero; the kernels that use them leave them
     // at zero again, so this is the only clear (and it is outside any graph capture).
     ok = ok && hipMemset(ctx->hist, 0, sz_hist) == hipSuccess &&
@@ -140,7 +142,7 @@ int socket_create(socket_ctx **out, const socket_params *p) {
 
 int socket_destroy(socket_ctx *ctx) {
     if (!ctx) return SOCKET_EINVAL;
-    void *bufs[] = {ctx->tables, ctx->hist, ctx->counters, ctx->cand_key, ctx->cand_idx, ctx->staged, ctx->partials};
+    void *bufs[] = {ctx->tables, ctx->hist, ctx->counters, ctx->cand_key, ctx->cand_idx, ctx->staged, ctx->partials, ctx->seq_scratch};
     for (void *b : bufs)
         if (b) (void)hipFree(b);
     delete ctx;
@@ -176,7 +178,7 @@ int socket_score(socket_ctx *ctx, const void *q, const void *codes, const void *
     if (!(tau > 0.0f) || !(tau < 3.0e38f)) return SOCKET_EINVAL;
     int rc = launch_soft_hash(ctx, q, proj, tau, batch, (hipStream_t)stream);
     if (rc != SOCKET_OK) return rc;
-    return launch_score_keys(ctx, codes, vnorm, block_table, seq_len, batch, scores, (hipStream_t)stream);
+    return launch_score_keys(ctx, codes, vnorm, block_table, seq_len, batch, scores, false, (hipStream_t)stream);
 }
 
 int socket_soft_hash(socket_ctx *ctx, const void *q, const void *proj, float tau, int32_t batch,
@@ -192,7 +194,7 @@ int socket_score_keys(socket_ctx *ctx, const void *codes, const float *vnorm,
                       float *scores, void *stream) {
     if (!ctx || !codes || !seq_len || !scores) return SOCKET_EINVAL;
     if (!batch_ok(ctx, batch) || !paging_ok(ctx, block_table)) return SOCKET_EINVAL;
-    return launch_score_keys(ctx, codes, vnorm, block_table, seq_len, batch, scores, (hipStream_t)stream);
+    return launch_score_keys(ctx, codes, vnorm, block_table, seq_len, batch, scores, false, (hipStream_t)stream);
 }
 
 int socket_topk_select(socket_ctx *ctx, const float *scores, const int32_t *seq_len,
@@ -200,7 +202,33 @@ int socket_topk_select(socket_ctx *ctx, const float *scores, const int32_t *seq_
                        void *stream) {
     if (!ctx || !scores || !seq_len || !k || !idx || !n_selected) return SOCKET_EINVAL;
     if (!batch_ok(ctx, batch)) return SOCKET_EINVAL;
-    return launch_topk(ctx, scores, seq_len, k, batch, idx, n_selected, (hipStream_t)stream);
+    return launch_topk(ctx, scores, seq_len, k, batch, idx, n_selected, false, (hipStream_t)stream);
+}
+
+int socket_decode_step(socket_ctx *ctx, const void *q, const void *K, const void *V, void *codes,
+                       const void *proj, float tau, const float *vnorm, const int32_t *block_table,
+                       const int32_t *pos, const int32_t *k, int32_t batch, float scale,
+                       float *scores, int32_t *idx, int32_t *n_selected, int32_t out_dtype,
+                       void *out, void *stream) {
+    if (!ctx || !q || !K || !V || !codes || !proj || !pos || !k || !scores || !idx || !n_selected || !out)
+        return SOCKET_EINVAL;
+    if (!batch_ok(ctx, batch) || !paging_ok(ctx, block_table)) return SOCKET_EINVAL;
+    if (!(tau > 0.0f) || !(tau < 3.0e38f)) return SOCKET_EINVAL;
+    if (out_dtype != SOCKET_BF16 && out_dtype != SOCKET_F32) return SOCKET_EINVAL;
+    if (!(scale == scale) || scale > 3.0e38f || scale < -3.0e38f) return SOCKET_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    int32_t *len = ctx->seq_scratch;
+    // 1. hash the appended key and soft-hash the queries (one launch); len = pos + 1
+    int rc = launch_project(ctx, q, proj, tau, K, codes, block_table, pos, nullptr, len, batch, st);
+    if (rc != SOCKET_OK) return rc;
+    // 2. score every key; the leading-digit histogram of the scores comes out of the same pass
+    rc = launch_score_keys(ctx, codes, vnorm, block_table, len, batch, scores, true, st);
+    if (rc != SOCKET_OK) return rc;
+    // 3. select, 4. attend
+    rc = launch_topk(ctx, scores, len, k, batch, idx, n_selected, true, st);
+    if (rc != SOCKET_OK) return rc;
+    return launch_sparse_decode(ctx, q, K, V, idx, n_selected, block_table, batch, scale, out_dtype,
+                                out, st);
 }
 
 int socket_sparse_decode(socket_ctx *ctx, const void *q, const void *K, const void *V,

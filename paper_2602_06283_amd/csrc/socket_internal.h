@@ -9,7 +9,7 @@
 namespace sk {
 
 constexpr int kTile = 16;            // tokens per rotation period of the code layout
-constexpr int kHistBits = 12;        // first radix digit of the top-k select
+constexpr int kHistBits = 11;        // first radix digit of the top-k select (sign, exponent, 2 mantissa bits)
 constexpr int kHistBins = 1 << kHistBits;
 constexpr int kMaxLdsBytes = 160 * 1024;
 #ifndef SK_SCORE_THREADS
@@ -61,6 +61,7 @@ struct socket_ctx {
     int32_t *cand_idx;    // [max_batch*Hkv][max_n]
     int32_t *staged;      // [max_batch*Hkv][max_k] selected positions before ordering
     float *partials;      // [max_batch*Hq][n_split][d+2]
+    int32_t *seq_scratch; // [max_batch] lengths after the append of a fused decode step
 };
 
 namespace sk {
@@ -72,13 +73,19 @@ int record_hip(socket_ctx *ctx, hipError_t e);
 int launch_hash_keys(socket_ctx *ctx, const void *K, const void *proj, const int32_t *block_table,
                      const int32_t *row_begin, const int32_t *row_count, int batch, int max_rows,
                      void *codes, hipStream_t st);
+// q null = append hash only; K null = soft hash only
+int launch_project(socket_ctx *ctx, const void *q, const void *proj, float tau, const void *K,
+                   void *codes, const int32_t *block_table, const int32_t *pos, const int32_t *count,
+                   int32_t *len_out, int batch, hipStream_t st);
 int launch_soft_hash(socket_ctx *ctx, const void *q, const void *proj, float tau, int batch,
                      hipStream_t st);
+// with_hist: also accumulate the leading-digit histogram of the scores into the context
 int launch_score_keys(socket_ctx *ctx, const void *codes, const float *vnorm,
                       const int32_t *block_table, const int32_t *seq_len, int batch, float *scores,
-                      hipStream_t st);
+                      bool with_hist, hipStream_t st);
+// have_hist: the context's histogram already holds the leading digits of `scores`
 int launch_topk(socket_ctx *ctx, const float *scores, const int32_t *seq_len, const int32_t *k,
-                int batch, int32_t *idx, int32_t *n_selected, hipStream_t st);
+                int batch, int32_t *idx, int32_t *n_selected, bool have_hist, hipStream_t st);
 int launch_sparse_decode(socket_ctx *ctx, const void *q, const void *K, const void *V,
                          const int32_t *idx, const int32_t *n_selected, const int32_t *block_table,
                          int batch, float scale, int out_dtype, void *out, hipStream_t st);
@@ -94,6 +101,27 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
     if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);  // NaN stays NaN
     u += 0x7fffu + ((u >> 16) & 1u);
     return (uint16_t)(u >> 16);
+}
+
+// Table whose id is stored at position pos of token t's code row.
+__device__ __forceinline__ int table_at(int pos, int t, int S) {
+    int c = pos >> 6, p = pos & 63;
+    int sub = p >> 4, s = p & 15;
+    return (c << 6) + sub + S * ((t + s) & 15);
+}
+
+// P-bit field starting at bit `bitpos` of a little-endian bit row.
+__device__ __forceinline__ uint32_t bit_field(const uint32_t *row, int bitpos, int P) {
+    int w = bitpos >> 5, off = bitpos & 31;
+    uint32_t v = row[w] >> off;
+    if (off + P > 32) v |= row[w + 1] << (32 - off);
+    return v & ((1u << P) - 1u);
+}
+
+// Position of table l's id inside token t's code row (inverse of table_at).
+__device__ __forceinline__ int code_pos(int l, int t, int S) {
+    int c = l >> 6, lp = l & 63;
+    return (c << 6) + (lp % S) * 16 + ((lp / S - t) & 15);
 }
 
 // Row index (in units of rows of the [.., Hkv, tokens, width] tensor) of token t of

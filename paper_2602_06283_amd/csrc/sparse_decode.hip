@@ -106,29 +106,33 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(DecodeArg
         }
         __syncthreads();
 
-        // ---- logits: scale * k.q for every query head of the group
-        {
-            Row8<T> kr[NPASS];
-            int64_t rows[NPASS];
+        // ---- gather this chunk's K and V rows together (one memory latency, not two)
+        Row8<T> kr[NPASS], vr[NPASS];
+        int64_t rows[NPASS];
 #pragma unroll
-            for (int p = 0; p < NPASS; ++p) {
-                rows[p] = s_row[p * RPP + wave * RPW + rl];
-                if (rows[p] >= 0) kr[p].load((const T *)a.K + rows[p] * D + sub * 8);
-                else kr[p].zero();
+        for (int p = 0; p < NPASS; ++p) {
+            rows[p] = s_row[p * RPP + wave * RPW + rl];
+            if (rows[p] >= 0) {
+                kr[p].load((const T *)a.K + rows[p] * D + sub * 8);
+                vr[p].load((const T *)a.V + rows[p] * D + sub * 8);
+            } else {
+                kr[p].zero();
+                vr[p].zero();
             }
+        }
+        // ---- logits: scale * k.q for every query head of the group
 #pragma unroll
-            for (int p = 0; p < NPASS; ++p) {
-                float kf[8];
-                kr[p].get(kf);
+        for (int p = 0; p < NPASS; ++p) {
+            float kf[8];
+            kr[p].get(kf);
 #pragma unroll
-                for (int g = 0; g < G; ++g) {
-                    float dot = 0.0f;
+            for (int g = 0; g < G; ++g) {
+                float dot = 0.0f;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) dot = fmaf(kf[e], qf[g][e], dot);
+                for (int e = 0; e < 8; ++e) dot = fmaf(kf[e], qf[g][e], dot);
 #pragma unroll
-                    for (int off = 1; off < LPR; off <<= 1) dot += __shfl_xor(dot, off);
-                    if (sub == 0) s_p[g][p * RPP + wave * RPW + rl] = rows[p] >= 0 ? dot * a.scale : ninf;
-                }
+                for (int off = 1; off < LPR; off <<= 1) dot += __shfl_xor(dot, off);
+                if (sub == 0) s_p[g][p * RPP + wave * RPW + rl] = rows[p] >= 0 ? dot * a.scale : ninf;
             }
         }
         __syncthreads();
@@ -156,31 +160,21 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(DecodeArg
         __syncthreads();
 
         // ---- weighted value rows
-        {
-            Row8<T> vr[NPASS];
-            int64_t rows[NPASS];
 #pragma unroll
-            for (int p = 0; p < NPASS; ++p) {
-                rows[p] = s_row[p * RPP + wave * RPW + rl];
-                if (rows[p] >= 0) vr[p].load((const T *)a.V + rows[p] * D + sub * 8);
-                else vr[p].zero();
-            }
+        for (int g = 0; g < G; ++g) {
+            const float corr = s_corr[g];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[g][e] *= corr;
+        }
+#pragma unroll
+        for (int p = 0; p < NPASS; ++p) {
+            float vf[8];
+            vr[p].get(vf);
 #pragma unroll
             for (int g = 0; g < G; ++g) {
-                const float corr = s_corr[g];
+                const float w = s_p[g][p * RPP + wave * RPW + rl];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) acc[g][e] *= corr;
-            }
-#pragma unroll
-            for (int p = 0; p < NPASS; ++p) {
-                float vf[8];
-                vr[p].get(vf);
-#pragma unroll
-                for (int g = 0; g < G; ++g) {
-                    const float w = s_p[g][p * RPP + wave * RPW + rl];
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) acc[g][e] = fmaf(w, vf[e], acc[g][e]);
-                }
+                for (int e = 0; e < 8; ++e) acc[g][e] = fmaf(w, vf[e], acc[g][e]);
             }
         }
         __syncthreads();
@@ -218,20 +212,43 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(DecodeArg
     __syncthreads();
     if (!s_last) return;
     __threadfence();
+    // weights of the splits: w[g][s] = exp(m_s - max_s m_s); reuse s_red as staging
+    float *s_w = &s_red[0][0][0];                    // [G][n_split], n_split <= 64
+    float *s_wl = s_w + G * 64;                      // [G][n_split] weight * sum
+    for (int i = tid; i < G * a.n_split; i += kDecodeThreads) {
+        int g = i / a.n_split, sp = i - g * a.n_split;
+        const float *ps = part + ((int64_t)g * a.n_split + sp) * (D + 2);
+        s_w[g * 64 + sp] = ps[0];
+        s_wl[g * 64 + sp] = ps[1];
+    }
+    __syncthreads();
+    if (tid < G) {
+        float top = ninf;
+        for (int sp = 0; sp < a.n_split; ++sp) top = fmaxf(top, s_w[tid * 64 + sp]);
+        float den = 0.0f;
+        for (int sp = 0; sp < a.n_split; ++sp) {
+            float m = s_w[tid * 64 + sp];
+            float w = (m == ninf) ? 0.0f : expf(m - top);
+            den = fmaf(w, s_wl[tid * 64 + sp], den);
+            s_w[tid * 64 + sp] = w;
+        }
+        s_l[tid] = den;
+    }
+    __syncthreads();
     for (int i = tid; i < G * D; i += kDecodeThreads) {
         int g = i / D, c = i - g * D;
-        const float *pg = part + (int64_t)g * a.n_split * (D + 2);
-        float top = ninf;
-        for (int s = 0; s < a.n_split; ++s) top = fmaxf(top, pg[s * (D + 2)]);
-        float num = 0.0f, den = 0.0f;
-        if (top != ninf) {
-            for (int s = 0; s < a.n_split; ++s) {
-                float m = pg[s * (D + 2)];
-                float w = (m == ninf) ? 0.0f : expf(m - top);
-                den = fmaf(w, pg[s * (D + 2) + 1], den);
-                num = fmaf(w, pg[s * (D + 2) + 2 + c], num);
-            }
+        const float *pg = part + (int64_t)g * a.n_split * (D + 2) + 2 + c;
+        float num = 0.0f;
+        constexpr int BATCH = 8;                     // independent loads in flight
+        for (int s0 = 0; s0 < a.n_split; s0 += BATCH) {
+            float v[BATCH];
+#pragma unroll
+            for (int j = 0; j < BATCH; ++j) v[j] = s0 + j < a.n_split ? pg[(int64_t)(s0 + j) * (D + 2)] : 0.0f;
+#pragma unroll
+            for (int j = 0; j < BATCH; ++j)
+                if (s0 + j < a.n_split) num = fmaf(s_w[g * 64 + s0 + j], v[j], num);
         }
+        const float den = s_l[g];
         float y = den > 0.0f ? num / den : 0.0f;
         int64_t at = ((int64_t)b * a.Hq + h * G + g) * D + c;
         if (a.out_dtype == SOCKET_F32) ((float *)a.out)[at] = y;

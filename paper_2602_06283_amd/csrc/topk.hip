@@ -15,7 +15,12 @@
 namespace sk {
 
 constexpr int kTopkThreads = 512;
-constexpr int kBitmapTokens = kHistBins * 32;   // tokens one LDS bitmap pass covers
+constexpr int kRefineBins = 4096;                // bins of the candidate-refinement digits and words of the bitmap
+constexpr int kBitmapTokens = kRefineBins * 32;  // tokens one LDS bitmap pass covers
+constexpr int kLowBits = 32 - kHistBits;         // score bits below the leading digit
+static_assert(kLowBits > 12 && kLowBits <= 24, "two refinement digits of at most 12 bits");
+constexpr int kPer = 8;                         // scores per thread in a sweep
+constexpr int kSlice = kTopkThreads * kPer;     // scores per workgroup
 
 struct TopkArgs {
     const float *scores;
@@ -28,7 +33,7 @@ struct TopkArgs {
     uint32_t *cand_key;
     int32_t *cand_idx;
     int32_t *staged;
-    int Hkv, max_n, max_k, slice;
+    int Hkv, max_n, max_k;
 };
 
 // Order-preserving map from fp32 to uint32 (larger float -> larger key).
@@ -61,13 +66,14 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *total,
     return base + x - v;
 }
 
-// Largest bin tb of the 4096-bin LDS histogram h with count(bins >= tb) >= target.
+// Largest bin tb of the NBINS-bin LDS histogram h with count(bins >= tb) >= target.
 // res[0] = tb, res[1] = count(bins > tb), res[2] = h[tb].  Requires 1 <= target <= sum(h).
+template <int NBINS>
 __device__ __forceinline__ void find_threshold(const uint32_t *h, uint32_t target, uint32_t *res,
                                                uint32_t *tmp) {
     const int t = threadIdx.x;
-    constexpr int PER = kHistBins / kTopkThreads;   // 8 bins per thread, highest bins first
-    const int top = kHistBins - 1 - t * PER;
+    constexpr int PER = NBINS / kTopkThreads;       // bins per thread, highest bins first
+    const int top = NBINS - 1 - t * PER;
     uint32_t part = 0;
 #pragma unroll
     for (int i = 0; i < PER; ++i) part += h[top - i];
@@ -95,8 +101,8 @@ __global__ __launch_bounds__(kTopkThreads) void topk_hist_kernel(TopkArgs a) {
     const int bh = blockIdx.y, b = bh / a.Hkv;
     int seq = a.seq_len[b];
     seq = seq < 0 ? 0 : (seq > a.max_n ? a.max_n : seq);
-    const int key0 = blockIdx.x * a.slice;
-    const int key1 = min(key0 + a.slice, seq);
+    const int key0 = blockIdx.x * kSlice;
+    const int key1 = min(key0 + kSlice, seq);
     if (key0 >= key1) return;
     for (int i = tid; i < kHistBins; i += kTopkThreads) h[i] = 0;
     __syncthreads();
@@ -106,7 +112,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_hist_kernel(TopkArgs a) {
         float e[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            if (i + j < key1 && selectable(e[j])) atomicAdd(&h[order_key(e[j]) >> 20], 1u);
+            if (i + j < key1 && selectable(e[j])) atomicAdd(&h[order_key(e[j]) >> kLowBits], 1u);
     }
     __syncthreads();
     uint32_t *gh = a.hist + (int64_t)bh * kHistBins;
@@ -115,13 +121,13 @@ __global__ __launch_bounds__(kTopkThreads) void topk_hist_kernel(TopkArgs a) {
 }
 
 // Refinement digits of a candidate after the leading 12 score bits:
-//   level 0: score bits 19..8   level 1: score bits 7..0
+//   level 0: the next 12 score bits   level 1: the remaining low score bits
 //   level 2..4: bits 30..19, 18..7, 6..0 of (2^31-1 - position), so a smaller position ranks higher
 __device__ __forceinline__ uint32_t refine_digit(int level, uint32_t key, int32_t pos) {
     uint32_t inv = 0x7fffffffu - (uint32_t)pos;
     switch (level) {
-        case 0: return (key >> 8) & 0xfffu;
-        case 1: return key & 0xffu;
+        case 0: return (key >> (kLowBits - 12)) & 0xfffu;
+        case 1: return key & ((1u << (kLowBits - 12)) - 1u);
         case 2: return (inv >> 19) & 0xfffu;
         case 3: return (inv >> 7) & 0xfffu;
         default: return inv & 0x7fu;
@@ -129,12 +135,12 @@ __device__ __forceinline__ uint32_t refine_digit(int level, uint32_t key, int32_
 }
 
 __global__ __launch_bounds__(kTopkThreads) void topk_filter_kernel(TopkArgs a) {
-    __shared__ uint32_t h[kHistBins];
+    __shared__ uint32_t h[kRefineBins];
     __shared__ uint32_t tmp[16];
     __shared__ uint32_t res[4];
     __shared__ uint32_t chosen[5];
     __shared__ uint32_t s_flag, s_count;
-    const int tid = threadIdx.x, lane = tid & 63;
+    const int tid = threadIdx.x;
     const int bh = blockIdx.y, b = bh / a.Hkv;
     int seq = a.seq_len[b];
     seq = seq < 0 ? 0 : (seq > a.max_n ? a.max_n : seq);
@@ -159,43 +165,52 @@ __global__ __launch_bounds__(kTopkThreads) void topk_filter_kernel(TopkArgs a) {
     int kreq = a.k[b];
     kreq = kreq < 0 ? 0 : (kreq > a.max_k ? a.max_k : kreq);
     const uint32_t k_eff = min((uint32_t)kreq, valid);
-    if (k_eff > 0) find_threshold(h, k_eff, res, tmp);
+    if (k_eff > 0) find_threshold<kHistBins>(h, k_eff, res, tmp);
     const uint32_t tb = res[0], above = res[1], n_cand = res[2];
 
-    // ---- sweep this workgroup's slice
-    const int key0 = blockIdx.x * a.slice;
-    const int key1 = min(key0 + a.slice, seq);
-    if (k_eff > 0) {
-        for (int i0 = key0; i0 < key1; i0 += kTopkThreads * 4) {
-            const int i = i0 + tid * 4;
+    // ---- sweep this workgroup's slice (kSlice scores, kPer per thread, held in registers).
+    //      Positions are handed out with one atomic per workgroup and list: every thread
+    //      counts its hits, a block scan turns the counts into offsets.
+    const int key0 = blockIdx.x * kSlice;
+    const int key1 = min(key0 + kSlice, seq);
+    if (k_eff > 0 && key0 < key1) {
+        uint32_t keys[kPer];
+        uint32_t flags = 0;                       // bit j: selected, bit 16+j: candidate
+        const int i = key0 + tid * kPer;
+#pragma unroll
+        for (int v = 0; v < kPer / 4; ++v) {
             float e[4] = {0, 0, 0, 0};
-            if (i < key1) {
-                float4 v = *(const float4 *)(s + i);
-                e[0] = v.x; e[1] = v.y; e[2] = v.z; e[3] = v.w;
+            if (i + 4 * v < key1) {
+                float4 q = *(const float4 *)(s + i + 4 * v);
+                e[0] = q.x; e[1] = q.y; e[2] = q.z; e[3] = q.w;
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const bool ok = i + j < key1 && selectable(e[j]);
-                const uint32_t key = order_key(e[j]);
-                const uint32_t dig = key >> 20;
-                const bool sel = ok && dig > tb, cand = ok && dig == tb;
-                unsigned long long ms = __ballot(sel), mc = __ballot(cand);
-                if (ms) {
-                    uint32_t base = 0;
-                    if (lane == 0) base = atomicAdd(&cnt[0], (uint32_t)__popcll(ms));
-                    base = __shfl(base, 0);
-                    if (sel) staged[base + __popcll(ms & ((1ull << lane) - 1))] = i + j;
-                }
-                if (mc) {
-                    uint32_t base = 0;
-                    if (lane == 0) base = atomicAdd(&cnt[1], (uint32_t)__popcll(mc));
-                    base = __shfl(base, 0);
-                    if (cand) {
-                        uint32_t at = base + __popcll(mc & ((1ull << lane) - 1));
-                        ckey[at] = key;
-                        cidx[at] = i + j;
-                    }
-                }
+                const int at = 4 * v + j;
+                const bool ok = i + at < key1 && selectable(e[j]);
+                keys[at] = order_key(e[j]);
+                const uint32_t dig = keys[at] >> kLowBits;
+                if (ok && dig > tb) flags |= 1u << at;
+                if (ok && dig == tb) flags |= 1u << (16 + at);
+            }
+        }
+        const uint32_t mine = (uint32_t)__popc(flags & 0xffffu) | ((uint32_t)__popc(flags >> 16) << 16);
+        uint32_t total;
+        const uint32_t before = block_excl_scan(mine, &total, tmp);   // both counts in one word
+        if (tid == 0) {
+            const uint32_t nsel = total & 0xffffu, ncand = total >> 16;
+            res[3] = nsel ? atomicAdd(&cnt[0], nsel) : 0u;
+            s_count = ncand ? atomicAdd(&cnt[1], ncand) : 0u;
+        }
+        __syncthreads();
+        uint32_t at_sel = res[3] + (before & 0xffffu), at_cand = s_count + (before >> 16);
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) {
+            if (flags & (1u << j)) staged[at_sel++] = i + j;
+            if (flags & (1u << (16 + j))) {
+                ckey[at_cand] = keys[j];
+                cidx[at_cand] = i + j;
+                ++at_cand;
             }
         }
     }
@@ -216,7 +231,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_filter_kernel(TopkArgs a) {
         __syncthreads();
         int level = 0;
         while (need > 0 && need < remaining && level < 5) {
-            for (int i = tid; i < kHistBins; i += kTopkThreads) h[i] = 0;
+            for (int i = tid; i < kRefineBins; i += kTopkThreads) h[i] = 0;
             __syncthreads();
             for (uint32_t i = tid; i < n_cand; i += kTopkThreads) {
                 uint32_t key = ckey[i];
@@ -226,7 +241,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_filter_kernel(TopkArgs a) {
                 if (match) atomicAdd(&h[refine_digit(level, key, pos)], 1u);
             }
             __syncthreads();
-            find_threshold(h, need, res, tmp);
+            find_threshold<kRefineBins>(h, need, res, tmp);
             const uint32_t td = res[0];
             // candidates on the current prefix with a larger digit are selected
             for (uint32_t i = tid; i < n_cand; i += kTopkThreads) {
@@ -257,14 +272,14 @@ __global__ __launch_bounds__(kTopkThreads) void topk_filter_kernel(TopkArgs a) {
         // ---- ascending emit through an LDS bitmap, kBitmapTokens tokens per pass
         uint32_t written = 0;
         for (int base = 0; base < seq; base += kBitmapTokens) {
-            for (int i = tid; i < kHistBins; i += kTopkThreads) h[i] = 0;
+            for (int i = tid; i < kRefineBins; i += kTopkThreads) h[i] = 0;
             __syncthreads();
             for (uint32_t i = tid; i < k_eff; i += kTopkThreads) {
                 int32_t pos = staged[i] - base;
                 if (pos >= 0 && pos < kBitmapTokens) atomicOr(&h[pos >> 5], 1u << (pos & 31));
             }
             __syncthreads();
-            constexpr int PER = kHistBins / kTopkThreads;
+            constexpr int PER = kRefineBins / kTopkThreads;
             uint32_t c = 0;
 #pragma unroll
             for (int i = 0; i < PER; ++i) c += __popc(h[tid * PER + i]);
@@ -291,22 +306,15 @@ __global__ __launch_bounds__(kTopkThreads) void topk_filter_kernel(TopkArgs a) {
 }
 
 int launch_topk(socket_ctx *ctx, const float *scores, const int32_t *seq_len, const int32_t *k,
-                int batch, int32_t *idx, int32_t *n_selected, hipStream_t st) {
+                int batch, int32_t *idx, int32_t *n_selected, bool have_hist, hipStream_t st) {
     const Geometry &g = ctx->g;
     TopkArgs a;
     a.scores = scores; a.seq_len = seq_len; a.k = k; a.idx = idx; a.n_selected = n_selected;
     a.hist = ctx->hist; a.counters = ctx->counters; a.cand_key = ctx->cand_key; a.cand_idx = ctx->cand_idx; a.staged = ctx->staged;
     a.Hkv = g.Hkv; a.max_n = g.max_n; a.max_k = g.max_k;
-    // slices of at least one block sweep (2048 scores), about 512 workgroups in flight
     const int BH = batch * g.Hkv;
-    int per = 512 / BH;
-    if (per < 1) per = 1;
-    int slice = (g.max_n + per - 1) / per;
-    const int quantum = kTopkThreads * 4;
-    slice = (slice + quantum - 1) / quantum * quantum;
-    a.slice = slice;
-    dim3 grid((g.max_n + slice - 1) / slice, BH);
-    hipLaunchKernelGGL(topk_hist_kernel, grid, dim3(kTopkThreads), 0, st, a);
+    dim3 grid((g.max_n + kSlice - 1) / kSlice, BH);
+    if (!have_hist) hipLaunchKernelGGL(topk_hist_kernel, grid, dim3(kTopkThreads), 0, st, a);
     hipLaunchKernelGGL(topk_filter_kernel, grid, dim3(kTopkThreads), 0, st, a);
     return record_hip(ctx, hipGetLastError());
 }

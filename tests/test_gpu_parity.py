@@ -492,3 +492,44 @@ def test_runs_are_bitwise_repeatable():
     for x, y in zip(a, b):
         assert (x == y).all()
     ctx.close()
+
+
+# ------------------------------------------------------------------ fused decode step
+
+@pytest.mark.parametrize("kv_dtype,L,P,G", [(wl.BF16, 64, 8, 4), (wl.F32, 32, 8, 1), (wl.BF16, 60, 10, 4)])
+def test_decode_step_equals_separate_calls_and_oracle(kv_dtype, L, P, G):
+    """socket_decode_step must give, bit for bit, what the four separate calls give, for a
+    few consecutive steps; the last step is also checked against the oracle."""
+    _need_gpu()
+    n0, steps, B, Hkv = 3000, 3, 2, 2
+    n = 3072
+    layer = small_layer(seed=61, B=B, Hq=Hkv * G, Hkv=Hkv, n=n, L=L, P=P, k=[100, 37], kv_dtype=kv_dtype,
+                        seq_len=[n0 + steps, n0 - 500 + steps])
+    start = np.array([n0, n0 - 500], dtype=np.int32)
+    ctx = hz.make_ctx(layer)
+    Kd, Vd, qd, Wd = (hz.dev(x, layer.kv_dtype) for x in (layer.K, layer.V, layer.q, layer.W))
+    max_k = int(layer.k.max())
+
+    def fresh():
+        return dict(codes=torch.zeros((B, Hkv, n, hz.lpad_of(L)), dtype=hz.torch_code_dtype(P), device="cuda"),
+                    scores=torch.zeros((B, Hkv, n), dtype=torch.float32, device="cuda"),
+                    idx=torch.zeros((B, Hkv, max_k), dtype=torch.int32, device="cuda"),
+                    nsel=torch.zeros((B, Hkv), dtype=torch.int32, device="cuda"),
+                    out=torch.zeros((B, layer.Hq, layer.d), dtype=torch.float32, device="cuda"))
+    a, f = fresh(), fresh()
+    kk, zero, one = hz.i32(layer.k), hz.i32(np.zeros(B)), hz.i32(np.ones(B))
+    for t in (a, f):
+        ctx.hash_keys(Kd, Wd, zero, hz.i32(start), B, n, t["codes"])
+    for s in range(steps):
+        pos, ln = hz.i32(start + s), hz.i32(start + s + 1)
+        ctx.hash_keys(Kd, Wd, pos, one, B, 1, a["codes"])
+        ctx.score(qd, a["codes"], Wd, 0.5, ln, B, a["scores"])
+        ctx.topk_select(a["scores"], ln, kk, B, a["idx"], a["nsel"])
+        ctx.sparse_decode(qd, Kd, Vd, a["idx"], a["nsel"], B, 1.0, a["out"])
+        ctx.decode_step(qd, Kd, Vd, f["codes"], Wd, 0.5, pos, kk, B, 1.0, f["scores"], f["idx"], f["nsel"], f["out"])
+        torch.cuda.synchronize()
+        for key in a:
+            assert torch.equal(a[key], f[key]), (s, key)
+    res = tuple(f[key].cpu().numpy() for key in ("codes", "scores", "idx", "nsel")) + (f["out"].cpu().numpy(),)
+    check_chain(layer, *res, atol=1e-4)
+    ctx.close()
