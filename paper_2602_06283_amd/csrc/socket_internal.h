@@ -55,7 +55,7 @@ struct socket_ctx {
     int last_hip_error;
     int64_t scratch_bytes;
     float *tables;        // [max_batch*Hkv][table_words]
-    uint32_t *hist;       // [max_batch*Hkv][kHistBins]
+    uint32_t *hist;       // [2][max_batch*Hkv][kHistBins]
     uint32_t *counters;   // [max_batch*Hkv][kCounterStride]
     uint32_t *cand_key;   // [max_batch*Hkv][max_n]
     int32_t *cand_idx;    // [max_batch*Hkv][max_n]

@@ -1,8 +1,8 @@
 // Eq. 2: exact softmax attention restricted to the selected tokens (Eq. 1 when every token is
 // selected).  Split-K flash-decode: the selected rows of one (sequence, KV head) are divided
 // among n_split workgroups; each gathers its K rows once for all G query heads of the group,
-// keeps a running (max, sum, weighted value sum) per query head in fp32, then gathers the V
-// rows.  The workgroup that finishes last (atomic ticket) merges the partial results in LDS.
+// keeps a running (max, sum, weighted value sum) per query head in fp32 over the gathered
+// K and V rows, and writes one partial result per split; a second small kernel merges them.
 // Logits use no 1/sqrt(d) unless the caller passes one as `scale`; with unit-variance data
 // they reach +-100, so everything is max-subtracted.
 #include "socket_internal.h"
@@ -60,7 +60,6 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(DecodeArg
     __shared__ int64_t s_row[CH];                    // K/V row of each chunk entry (-1 = none)
     __shared__ float s_m[G], s_l[G], s_corr[G];
     __shared__ float s_red[NWAVE][G][D];
-    __shared__ uint32_t s_last;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
@@ -203,58 +202,47 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(DecodeArg
         part[((int64_t)tid * a.n_split + split) * (D + 2) + 0] = s_m[tid];
         part[((int64_t)tid * a.n_split + split) * (D + 2) + 1] = s_l[tid];
     }
+}
 
-    // ---- last workgroup of this (sequence, KV head) merges the splits
-    __threadfence();
-    __syncthreads();
-    uint32_t *ticket = a.counters + (int64_t)bh * kCounterStride + 8;
-    if (tid == 0) s_last = atomicAdd(ticket, 1u) == gridDim.x - 1 ? 1u : 0u;
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
-    // weights of the splits: w[g][s] = exp(m_s - max_s m_s); reuse s_red as staging
-    float *s_w = &s_red[0][0][0];                    // [G][n_split], n_split <= 64
-    float *s_wl = s_w + G * 64;                      // [G][n_split] weight * sum
-    for (int i = tid; i < G * a.n_split; i += kDecodeThreads) {
-        int g = i / a.n_split, sp = i - g * a.n_split;
-        const float *ps = part + ((int64_t)g * a.n_split + sp) * (D + 2);
-        s_w[g * 64 + sp] = ps[0];
-        s_wl[g * 64 + sp] = ps[1];
-    }
-    __syncthreads();
-    if (tid < G) {
-        float top = ninf;
-        for (int sp = 0; sp < a.n_split; ++sp) top = fmaxf(top, s_w[tid * 64 + sp]);
-        float den = 0.0f;
-        for (int sp = 0; sp < a.n_split; ++sp) {
-            float m = s_w[tid * 64 + sp];
-            float w = (m == ninf) ? 0.0f : expf(m - top);
-            den = fmaf(w, s_wl[tid * 64 + sp], den);
-            s_w[tid * 64 + sp] = w;
-        }
-        s_l[tid] = den;
-    }
-    __syncthreads();
-    for (int i = tid; i < G * D; i += kDecodeThreads) {
-        int g = i / D, c = i - g * D;
-        const float *pg = part + (int64_t)g * a.n_split * (D + 2) + 2 + c;
-        float num = 0.0f;
-        constexpr int BATCH = 8;                     // independent loads in flight
-        for (int s0 = 0; s0 < a.n_split; s0 += BATCH) {
-            float v[BATCH];
+// Merge of the split-K partial results of one query head: out = sum_s w_s acc_s / sum_s w_s l_s
+// with w_s = exp(m_s - max m).  One workgroup per query head, one thread per output channel;
+// every load of a thread is issued before the first use, so the kernel costs one memory
+// latency.  Runs as a kernel of its own after the partial pass: no fence, no signalling.
+template <int D>
+__global__ __launch_bounds__(D) void decode_merge_kernel(DecodeArgs a) {
+    __shared__ float s_w[64];
+    __shared__ float s_den;
+    const int c = threadIdx.x, g = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int G = a.Hq / a.map.Hkv;
+    const int64_t head = (int64_t)b * a.Hq + h * G + g;
+    const float *part = a.partials + head * a.n_split * (D + 2);
+    const float ninf = -__builtin_inff();
+    float acc[64];
 #pragma unroll
-            for (int j = 0; j < BATCH; ++j) v[j] = s0 + j < a.n_split ? pg[(int64_t)(s0 + j) * (D + 2)] : 0.0f;
+    for (int s = 0; s < 64; ++s) acc[s] = s < a.n_split ? part[(int64_t)s * (D + 2) + 2 + c] : 0.0f;
+    if (c < 64) {                                    // the first wavefront weighs the splits
+        const bool live = c < a.n_split;
+        const float m = live ? part[(int64_t)c * (D + 2)] : ninf;
+        const float l = live ? part[(int64_t)c * (D + 2) + 1] : 0.0f;
+        float top = m;
 #pragma unroll
-            for (int j = 0; j < BATCH; ++j)
-                if (s0 + j < a.n_split) num = fmaf(s_w[g * 64 + s0 + j], v[j], num);
-        }
-        const float den = s_l[g];
-        float y = den > 0.0f ? num / den : 0.0f;
-        int64_t at = ((int64_t)b * a.Hq + h * G + g) * D + c;
-        if (a.out_dtype == SOCKET_F32) ((float *)a.out)[at] = y;
-        else ((uint16_t *)a.out)[at] = f32_to_bf16_rne(y);
+        for (int off = 32; off > 0; off >>= 1) top = fmaxf(top, __shfl_xor(top, off));
+        const float w = (m == ninf) ? 0.0f : expf(m - top);
+        float den = w * l;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) den += __shfl_xor(den, off);
+        s_w[c] = w;
+        if (c == 0) s_den = den;
     }
-    if (tid == 0) *ticket = 0;
+    __syncthreads();
+    float num = 0.0f;
+#pragma unroll
+    for (int s = 0; s < 64; ++s)
+        if (s < a.n_split) num = fmaf(s_w[s], acc[s], num);
+    const float den = s_den;
+    const float y = den > 0.0f ? num / den : 0.0f;
+    if (a.out_dtype == SOCKET_F32) ((float *)a.out)[head * D + c] = y;
+    else ((uint16_t *)a.out)[head * D + c] = f32_to_bf16_rne(y);
 }
 
 template <typename T, int D>
@@ -292,6 +280,13 @@ int launch_sparse_decode(socket_ctx *ctx, const void *q, const void *K, const vo
     int rc = g.kv_dtype == SOCKET_F32 ? launch_decode_d<float>(a, g.d, g.G, grid, st)
                                       : launch_decode_d<uint16_t>(a, g.d, g.G, grid, st);
     if (rc != SOCKET_OK) return rc;
+    dim3 mgrid(g.G, g.Hkv, batch);
+    switch (g.d) {
+        case 64: hipLaunchKernelGGL(decode_merge_kernel<64>, mgrid, dim3(64), 0, st, a); break;
+        case 128: hipLaunchKernelGGL(decode_merge_kernel<128>, mgrid, dim3(128), 0, st, a); break;
+        case 256: hipLaunchKernelGGL(decode_merge_kernel<256>, mgrid, dim3(256), 0, st, a); break;
+        default: return SOCKET_EUNSUPPORTED;
+    }
     return record_hip(ctx, hipGetLastError());
 }
 

@@ -1,15 +1,16 @@
 // Alg. 3, TopK step: exact selection of the k largest scores per (sequence, KV head) by a
 // most-significant-digit radix select on the fp32 bit patterns, spread over many workgroups.
 //
-//   topk_hist_kernel    12-bit histogram of the leading digit of every valid score.
-//   topk_filter_kernel  every workgroup finds the threshold digit from the histogram, then
-//                       sweeps its slice: scores above the threshold digit are selected,
-//                       scores in it become candidates.  The workgroup that finishes last
-//                       (atomic ticket) resolves the candidates on the remaining score bits
-//                       and then on the token position (smaller position wins a tie), writes
-//                       the selection in ascending position order through an LDS bitmap, and
-//                       leaves histogram and counters at zero for the next call.
-// No kernel waits on another workgroup, so every launch drains.
+//   topk_hist_kernel    histogram of the leading 11-bit digit of every valid score (the fused
+//                       decode step gets it from the scoring pass instead).
+//   topk_hist2_kernel   histogram of the next 11 bits over the scores in the threshold digit.
+//   topk_filter_kernel  sweep: scores above the two-digit threshold are selected, scores equal
+//                       to it become candidates.
+//   topk_resolve_kernel one workgroup per (sequence, head): resolves the candidates on the
+//                       remaining score bits and then on the token position, and writes the
+//                       selection in ascending position order.
+// Stages talk through global memory across kernel boundaries only: no workgroup waits on
+// another and no fence is needed.
 #include "socket_internal.h"
 
 namespace sk {
@@ -28,7 +29,8 @@ struct TopkArgs {
     const int32_t *k;
     int32_t *idx;
     int32_t *n_selected;
-    uint32_t *hist;
+    uint32_t *hist;       // first-digit histograms [B*Hkv][kHistBins]
+    uint32_t *hist2;      // second-digit histograms of the threshold bin
     uint32_t *counters;
     uint32_t *cand_key;
     int32_t *cand_idx;
@@ -120,41 +122,17 @@ __global__ __launch_bounds__(kTopkThreads) void topk_hist_kernel(TopkArgs a) {
         if (h[i]) atomicAdd(&gh[i], h[i]);
 }
 
-// Refinement digits of a candidate after the leading 12 score bits:
-//   level 0: the next 12 score bits   level 1: the remaining low score bits
-//   level 2..4: bits 30..19, 18..7, 6..0 of (2^31-1 - position), so a smaller position ranks higher
-__device__ __forceinline__ uint32_t refine_digit(int level, uint32_t key, int32_t pos) {
-    uint32_t inv = 0x7fffffffu - (uint32_t)pos;
-    switch (level) {
-        case 0: return (key >> (kLowBits - 12)) & 0xfffu;
-        case 1: return key & ((1u << (kLowBits - 12)) - 1u);
-        case 2: return (inv >> 19) & 0xfffu;
-        case 3: return (inv >> 7) & 0xfffu;
-        default: return inv & 0x7fu;
-    }
-}
-
-__global__ __launch_bounds__(kTopkThreads) void topk_filter_kernel(TopkArgs a) {
-    __shared__ uint32_t h[kRefineBins];
-    __shared__ uint32_t tmp[16];
-    __shared__ uint32_t res[4];
-    __shared__ uint32_t chosen[5];
-    __shared__ uint32_t s_flag, s_count;
+// Threshold of the two leading digits, recomputed identically by every workgroup that
+// needs it: tb1 from the first-digit histogram, then tb2 among the scores whose first digit
+// is tb1.  out: [0] k_eff, [1] tb1, [2] tb2, [3] scores selected outright (above the pair),
+// [4] scores equal to the pair (candidates).  h is LDS scratch of >= kHistBins words.
+__device__ __forceinline__ void two_digit_threshold(const uint32_t *gh1, const uint32_t *gh2, int kreq,
+                                                    bool want_second, uint32_t *h, uint32_t *res,
+                                                    uint32_t *tmp, uint32_t *out) {
     const int tid = threadIdx.x;
-    const int bh = blockIdx.y, b = bh / a.Hkv;
-    int seq = a.seq_len[b];
-    seq = seq < 0 ? 0 : (seq > a.max_n ? a.max_n : seq);
-    uint32_t *gh = a.hist + (int64_t)bh * kHistBins;
-    uint32_t *cnt = a.counters + (int64_t)bh * kCounterStride;
-    uint32_t *ckey = a.cand_key + (int64_t)bh * a.max_n;
-    int32_t *cidx = a.cand_idx + (int64_t)bh * a.max_n;
-    int32_t *staged = a.staged + (int64_t)bh * a.max_k;   // selected positions, unordered
-    const float *s = a.scores + (int64_t)bh * a.max_n;
-
-    // ---- threshold digit from the global histogram (same result in every workgroup)
     uint32_t part = 0;
     for (int i = tid; i < kHistBins; i += kTopkThreads) {
-        uint32_t c = gh[i];
+        uint32_t c = gh1[i];
         h[i] = c;
         part += c;
     }
@@ -162,75 +140,185 @@ __global__ __launch_bounds__(kTopkThreads) void topk_filter_kernel(TopkArgs a) {
     __syncthreads();
     uint32_t valid;
     (void)block_excl_scan(part, &valid, tmp);
-    int kreq = a.k[b];
-    kreq = kreq < 0 ? 0 : (kreq > a.max_k ? a.max_k : kreq);
     const uint32_t k_eff = min((uint32_t)kreq, valid);
-    if (k_eff > 0) find_threshold<kHistBins>(h, k_eff, res, tmp);
-    const uint32_t tb = res[0], above = res[1], n_cand = res[2];
+    out[0] = k_eff; out[1] = 0; out[2] = 0; out[3] = 0; out[4] = 0;
+    if (k_eff == 0) return;
+    find_threshold<kHistBins>(h, k_eff, res, tmp);
+    const uint32_t tb1 = res[0], above1 = res[1], cnt1 = res[2];
+    out[1] = tb1; out[3] = above1; out[4] = cnt1;
+    if (!want_second) return;
+    __syncthreads();
+    for (int i = tid; i < kHistBins; i += kTopkThreads) h[i] = gh2[i];
+    __syncthreads();
+    find_threshold<kHistBins>(h, k_eff - above1, res, tmp);   // 1 <= k_eff - above1 <= cnt1
+    out[2] = res[0]; out[3] = above1 + res[1]; out[4] = res[2];
+}
 
-    // ---- sweep this workgroup's slice (kSlice scores, kPer per thread, held in registers).
-    //      Positions are handed out with one atomic per workgroup and list: every thread
-    //      counts its hits, a block scan turns the counts into offsets.
+constexpr int kDigit2Shift = kLowBits - kHistBits;    // second digit: the next kHistBits score bits
+static_assert(kDigit2Shift >= 0 && kDigit2Shift <= 12, "the low score bits fit one refinement digit");
+__device__ __forceinline__ uint32_t digit2(uint32_t key) { return (key >> kDigit2Shift) & (kHistBins - 1); }
+
+// Histogram of the second digit over the scores whose first digit is the threshold digit.
+__global__ __launch_bounds__(kTopkThreads) void topk_hist2_kernel(TopkArgs a) {
+    __shared__ uint32_t h[kHistBins];
+    __shared__ uint32_t tmp[16];
+    __shared__ uint32_t res[4];
+    const int tid = threadIdx.x;
+    const int bh = blockIdx.y, b = bh / a.Hkv;
+    int seq = a.seq_len[b];
+    seq = seq < 0 ? 0 : (seq > a.max_n ? a.max_n : seq);
     const int key0 = blockIdx.x * kSlice;
     const int key1 = min(key0 + kSlice, seq);
-    if (k_eff > 0 && key0 < key1) {
-        uint32_t keys[kPer];
-        uint32_t flags = 0;                       // bit j: selected, bit 16+j: candidate
-        const int i = key0 + tid * kPer;
+    if (key0 >= key1) return;
+    int kreq = a.k[b];
+    kreq = kreq < 0 ? 0 : (kreq > a.max_k ? a.max_k : kreq);
+    uint32_t th[5];
+    two_digit_threshold(a.hist + (int64_t)bh * kHistBins, nullptr, kreq, false, h, res, tmp, th);
+    if (th[0] == 0) return;
+    const uint32_t tb1 = th[1];
+    __syncthreads();
+    for (int i = tid; i < kHistBins; i += kTopkThreads) h[i] = 0;
+    __syncthreads();
+    const float *s = a.scores + (int64_t)bh * a.max_n;
+    const int i = key0 + tid * kPer;
 #pragma unroll
-        for (int v = 0; v < kPer / 4; ++v) {
-            float e[4] = {0, 0, 0, 0};
-            if (i + 4 * v < key1) {
-                float4 q = *(const float4 *)(s + i + 4 * v);
-                e[0] = q.x; e[1] = q.y; e[2] = q.z; e[3] = q.w;
-            }
+    for (int v = 0; v < kPer / 4; ++v) {
+        if (i + 4 * v >= key1) continue;
+        float4 q = *(const float4 *)(s + i + 4 * v);
+        float e[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int at = 4 * v + j;
-                const bool ok = i + at < key1 && selectable(e[j]);
-                keys[at] = order_key(e[j]);
-                const uint32_t dig = keys[at] >> kLowBits;
-                if (ok && dig > tb) flags |= 1u << at;
-                if (ok && dig == tb) flags |= 1u << (16 + at);
-            }
-        }
-        const uint32_t mine = (uint32_t)__popc(flags & 0xffffu) | ((uint32_t)__popc(flags >> 16) << 16);
-        uint32_t total;
-        const uint32_t before = block_excl_scan(mine, &total, tmp);   // both counts in one word
-        if (tid == 0) {
-            const uint32_t nsel = total & 0xffffu, ncand = total >> 16;
-            res[3] = nsel ? atomicAdd(&cnt[0], nsel) : 0u;
-            s_count = ncand ? atomicAdd(&cnt[1], ncand) : 0u;
-        }
-        __syncthreads();
-        uint32_t at_sel = res[3] + (before & 0xffffu), at_cand = s_count + (before >> 16);
-#pragma unroll
-        for (int j = 0; j < kPer; ++j) {
-            if (flags & (1u << j)) staged[at_sel++] = i + j;
-            if (flags & (1u << (16 + j))) {
-                ckey[at_cand] = keys[j];
-                cidx[at_cand] = i + j;
-                ++at_cand;
-            }
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t key = order_key(e[j]);
+            if (i + 4 * v + j < key1 && selectable(e[j]) && (key >> kLowBits) == tb1) atomicAdd(&h[digit2(key)], 1u);
         }
     }
-
-    // ---- last workgroup of this (sequence, head) finishes the job
-    __threadfence();
     __syncthreads();
-    if (tid == 0) s_flag = atomicAdd(&cnt[2], 1u) == gridDim.x - 1 ? 1u : 0u;
-    __syncthreads();
-    if (!s_flag) return;
-    __threadfence();   // acquire: other workgroups' staged positions and candidates
+    uint32_t *gh2 = a.hist2 + (int64_t)bh * kHistBins;
+    for (int j = tid; j < kHistBins; j += kTopkThreads)
+        if (h[j]) atomicAdd(&gh2[j], h[j]);
+}
 
+// Sweep: scores above the two-digit threshold are selected, scores equal to it become
+// candidates (few: one bin of a 2^22-bin histogram unless many scores tie).
+__global__ __launch_bounds__(kTopkThreads) void topk_filter_kernel(TopkArgs a) {
+    __shared__ uint32_t h[kHistBins];
+    __shared__ uint32_t tmp[16];
+    __shared__ uint32_t res[4];
+    __shared__ uint32_t s_base[2];
+    const int tid = threadIdx.x;
+    const int bh = blockIdx.y, b = bh / a.Hkv;
+    int seq = a.seq_len[b];
+    seq = seq < 0 ? 0 : (seq > a.max_n ? a.max_n : seq);
+    const int key0 = blockIdx.x * kSlice;
+    const int key1 = min(key0 + kSlice, seq);
+    if (key0 >= key1) return;
+    int kreq = a.k[b];
+    kreq = kreq < 0 ? 0 : (kreq > a.max_k ? a.max_k : kreq);
+    uint32_t th[5];
+    two_digit_threshold(a.hist + (int64_t)bh * kHistBins, a.hist2 + (int64_t)bh * kHistBins, kreq, true, h,
+                        res, tmp, th);
+    if (th[0] == 0) return;
+    const uint32_t pair = (th[1] << kHistBits) | th[2];       // the 2*kHistBits leading bits
+    uint32_t *cnt = a.counters + (int64_t)bh * kCounterStride;
+    uint32_t *ckey = a.cand_key + (int64_t)bh * a.max_n;
+    int32_t *cidx = a.cand_idx + (int64_t)bh * a.max_n;
+    int32_t *staged = a.staged + (int64_t)bh * a.max_k;       // selected positions, unordered
+    const float *s = a.scores + (int64_t)bh * a.max_n;
+
+    // kSlice scores per workgroup, kPer per thread, held in registers.  Positions in the two
+    // lists are handed out with one atomic per workgroup and list: every thread counts its
+    // hits and a block scan turns the counts into offsets.
+    uint32_t keys[kPer];
+    uint32_t flags = 0;                           // bit j: selected, bit 16+j: candidate
+    const int i = key0 + tid * kPer;
+#pragma unroll
+    for (int v = 0; v < kPer / 4; ++v) {
+        float e[4] = {0, 0, 0, 0};
+        if (i + 4 * v < key1) {
+            float4 q = *(const float4 *)(s + i + 4 * v);
+            e[0] = q.x; e[1] = q.y; e[2] = q.z; e[3] = q.w;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int at = 4 * v + j;
+            const bool ok = i + at < key1 && selectable(e[j]);
+            keys[at] = order_key(e[j]);
+            const uint32_t lead = keys[at] >> kDigit2Shift;
+            if (ok && lead > pair) flags |= 1u << at;
+            if (ok && lead == pair) flags |= 1u << (16 + at);
+        }
+    }
+    const uint32_t mine = (uint32_t)__popc(flags & 0xffffu) | ((uint32_t)__popc(flags >> 16) << 16);
+    uint32_t total;
+    const uint32_t before = block_excl_scan(mine, &total, tmp);   // both counts in one word
+    if (tid == 0) {
+        const uint32_t nsel = total & 0xffffu, ncand = total >> 16;
+        s_base[0] = nsel ? atomicAdd(&cnt[0], nsel) : 0u;
+        s_base[1] = ncand ? atomicAdd(&cnt[1], ncand) : 0u;
+    }
+    __syncthreads();
+    uint32_t at_sel = s_base[0] + (before & 0xffffu), at_cand = s_base[1] + (before >> 16);
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+        if (flags & (1u << j)) staged[at_sel++] = i + j;
+        if (flags & (1u << (16 + j))) {
+            ckey[at_cand] = keys[j];
+            cidx[at_cand] = i + j;
+            ++at_cand;
+        }
+    }
+}
+
+// Refinement digits of a candidate below the two leading digits:
+//   level 0: the remaining low score bits
+//   level 1..3: bits 30..19, 18..7, 6..0 of (2^31-1 - position), so a smaller position ranks higher
+constexpr int kLevels = 4;
+__device__ __forceinline__ uint32_t refine_digit(int level, uint32_t key, int32_t pos) {
+    uint32_t inv = 0x7fffffffu - (uint32_t)pos;
+    switch (level) {
+        case 0: return key & ((1u << kDigit2Shift) - 1u);
+        case 1: return (inv >> 19) & 0xfffu;
+        case 2: return (inv >> 7) & 0xfffu;
+        default: return inv & 0x7fu;
+    }
+}
+
+// One workgroup per (sequence, KV head): resolves the candidates on the remaining score bits
+// and then on the token position (smaller position wins a tie), writes the selection in
+// ascending position order through an LDS bitmap, and leaves histograms and counters at
+// zero for the next call.  Runs after the sweep as a kernel of its own, so it needs no
+// fence or inter-workgroup signalling.
+__global__ __launch_bounds__(kTopkThreads) void topk_resolve_kernel(TopkArgs a) {
+    __shared__ uint32_t h[kRefineBins];
+    __shared__ uint32_t tmp[16];
+    __shared__ uint32_t res[4];
+    __shared__ uint32_t chosen[kLevels];
+    __shared__ uint32_t s_count;
+    const int tid = threadIdx.x;
+    const int bh = blockIdx.x, b = bh / a.Hkv;
+    int seq = a.seq_len[b];
+    seq = seq < 0 ? 0 : (seq > a.max_n ? a.max_n : seq);
+    uint32_t *gh1 = a.hist + (int64_t)bh * kHistBins;
+    uint32_t *gh2 = a.hist2 + (int64_t)bh * kHistBins;
+    uint32_t *cnt = a.counters + (int64_t)bh * kCounterStride;
+    const uint32_t *ckey = a.cand_key + (int64_t)bh * a.max_n;
+    const int32_t *cidx = a.cand_idx + (int64_t)bh * a.max_n;
+    int32_t *staged = a.staged + (int64_t)bh * a.max_k;
     int32_t *out = a.idx + (int64_t)bh * a.max_k;
+    int kreq = a.k[b];
+    kreq = kreq < 0 ? 0 : (kreq > a.max_k ? a.max_k : kreq);
+    uint32_t th[5];
+    two_digit_threshold(gh1, gh2, kreq, true, h, res, tmp, th);
+    const uint32_t k_eff = th[0], above = th[3], n_cand = th[4];
+    __syncthreads();
+
     if (k_eff > 0) {
-        // resolve the candidates: keep the `need` best of the n_cand in the threshold digit
+        // keep the `need` best of the n_cand candidates
         uint32_t need = k_eff - above, remaining = n_cand;
         if (tid == 0) s_count = above;            // next free staging slot
         __syncthreads();
         int level = 0;
-        while (need > 0 && need < remaining && level < 5) {
+        while (need > 0 && need < remaining && level < kLevels) {
             for (int i = tid; i < kRefineBins; i += kTopkThreads) h[i] = 0;
             __syncthreads();
             for (uint32_t i = tid; i < n_cand; i += kTopkThreads) {
@@ -274,9 +362,16 @@ __global__ __launch_bounds__(kTopkThreads) void topk_filter_kernel(TopkArgs a) {
         for (int base = 0; base < seq; base += kBitmapTokens) {
             for (int i = tid; i < kRefineBins; i += kTopkThreads) h[i] = 0;
             __syncthreads();
-            for (uint32_t i = tid; i < k_eff; i += kTopkThreads) {
-                int32_t pos = staged[i] - base;
-                if (pos >= 0 && pos < kBitmapTokens) atomicOr(&h[pos >> 5], 1u << (pos & 31));
+            for (uint32_t i0 = tid; i0 < k_eff; i0 += 8 * kTopkThreads) {
+                int32_t p8[8];                    // all of a thread's loads in flight together
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const uint32_t i = i0 + j * kTopkThreads;
+                    p8[j] = i < k_eff ? staged[i] - base : -1;
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (p8[j] >= 0 && p8[j] < kBitmapTokens) atomicOr(&h[p8[j] >> 5], 1u << (p8[j] & 31));
             }
             __syncthreads();
             constexpr int PER = kRefineBins / kTopkThreads;
@@ -301,8 +396,11 @@ __global__ __launch_bounds__(kTopkThreads) void topk_filter_kernel(TopkArgs a) {
     for (int i = (int)k_eff + tid; i < a.max_k; i += kTopkThreads) out[i] = -1;
     if (tid == 0) a.n_selected[bh] = (int32_t)k_eff;
     // leave the shared scratch clean for the next call
-    for (int i = tid; i < kHistBins; i += kTopkThreads) gh[i] = 0;
-    if (tid < 3) cnt[tid] = 0;
+    for (int i = tid; i < kHistBins; i += kTopkThreads) {
+        gh1[i] = 0;
+        gh2[i] = 0;
+    }
+    if (tid < 2) cnt[tid] = 0;
 }
 
 int launch_topk(socket_ctx *ctx, const float *scores, const int32_t *seq_len, const int32_t *k,
@@ -310,12 +408,14 @@ int launch_topk(socket_ctx *ctx, const float *scores, const int32_t *seq_len, co
     const Geometry &g = ctx->g;
     TopkArgs a;
     a.scores = scores; a.seq_len = seq_len; a.k = k; a.idx = idx; a.n_selected = n_selected;
-    a.hist = ctx->hist; a.counters = ctx->counters; a.cand_key = ctx->cand_key; a.cand_idx = ctx->cand_idx; a.staged = ctx->staged;
+    a.hist = ctx->hist; a.hist2 = ctx->hist + (int64_t)g.max_batch * g.Hkv * kHistBins; a.counters = ctx->counters; a.cand_key = ctx->cand_key; a.cand_idx = ctx->cand_idx; a.staged = ctx->staged;
     a.Hkv = g.Hkv; a.max_n = g.max_n; a.max_k = g.max_k;
     const int BH = batch * g.Hkv;
     dim3 grid((g.max_n + kSlice - 1) / kSlice, BH);
     if (!have_hist) hipLaunchKernelGGL(topk_hist_kernel, grid, dim3(kTopkThreads), 0, st, a);
+    hipLaunchKernelGGL(topk_hist2_kernel, grid, dim3(kTopkThreads), 0, st, a);
     hipLaunchKernelGGL(topk_filter_kernel, grid, dim3(kTopkThreads), 0, st, a);
+    hipLaunchKernelGGL(topk_resolve_kernel, dim3(BH), dim3(kTopkThreads), 0, st, a);
     return record_hip(ctx, hipGetLastError());
 }
 
