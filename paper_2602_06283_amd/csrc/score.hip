@@ -126,17 +126,21 @@ __global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
     }
     __syncthreads();
 
-    // ---- appended key: fp32 FMA over the channels in ascending order, sign bits by ballot
-    if (app && wave == 0) {
+    // ---- appended key: fp32 FMA; each of the 4 wavefronts sums a quarter of the channels,
+    //      wavefront 0 adds the four partial sums in order and takes the sign bits by ballot
+    float *kpart = (float *)(w + a.d * cols);                // [4][64]
+    if (app) {
         float acc = 0.0f;
-        if (lane < ncols)
-            for (int c = 0; c < a.d; ++c) acc = fmaf(kf[c], elem_to_f32<T>(w[c * cols + lane]), acc);
-        unsigned long long m = __ballot(lane < ncols && acc >= 0.0f);
-        if (lane == 0) {
-            bits[0] = (uint32_t)m;
-            bits[1] = (uint32_t)(m >> 32);
-            bits[2] = 0;
+        if (lane < ncols) {
+            const int q4 = a.d >> 2;
+            float a0 = 0.0f, a1 = 0.0f;
+            for (int c = wave * q4; c < (wave + 1) * q4; c += 2) {
+                a0 = fmaf(kf[c], elem_to_f32<T>(w[c * cols + lane]), a0);
+                a1 = fmaf(kf[c + 1], elem_to_f32<T>(w[(c + 1) * cols + lane]), a1);
+            }
+            acc = a0 + a1;
         }
+        kpart[wave * 64 + lane] = acc;
     }
     // ---- queries: fp64 projections, u = tanh(z)/sqrt(d), per-plane sigmoids of +-2u/tau
     if (soft) {
@@ -145,8 +149,16 @@ __global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
             int g = i / cols, j = i - g * cols;
             double plus = 0.0, minus = 0.0;
             if (j < ncols) {
-                double z = 0.0;
-                for (int c = 0; c < a.d; ++c) z += (double)elem_to_f32<T>(w[c * cols + j]) * qd[g * a.d + c];
+                double z0 = 0.0, z1 = 0.0, z2 = 0.0, z3 = 0.0;   // independent chains hide LDS latency
+                const double *qg = qd + g * a.d;
+#pragma unroll 4
+                for (int c = 0; c < a.d; c += 4) {
+                    z0 = fma((double)elem_to_f32<T>(w[c * cols + j]), qg[c], z0);
+                    z1 = fma((double)elem_to_f32<T>(w[(c + 1) * cols + j]), qg[c + 1], z1);
+                    z2 = fma((double)elem_to_f32<T>(w[(c + 2) * cols + j]), qg[c + 2], z2);
+                    z3 = fma((double)elem_to_f32<T>(w[(c + 3) * cols + j]), qg[c + 3], z3);
+                }
+                const double z = (z0 + z1) + (z2 + z3);
                 const double x = 2.0 * tanh(z) * inv_sqrt_d / a.tau;
                 const double e = exp(-fabs(x));                 // in (0, 1]
                 const double big = 1.0 / (1.0 + e), small = e / (1.0 + e);
@@ -158,6 +170,16 @@ __global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
         }
     }
     __syncthreads();
+    if (app && wave == 0) {
+        const float z = ((kpart[lane] + kpart[64 + lane]) + kpart[128 + lane]) + kpart[192 + lane];
+        unsigned long long m = __ballot(lane < ncols && z >= 0.0f);
+        if (lane == 0) {
+            bits[0] = (uint32_t)m;
+            bits[1] = (uint32_t)(m >> 32);
+            bits[2] = 0;
+        }
+    }
+    if (app) __syncthreads();
 
     if (app && krow >= 0 && tid < a.tpw) {
         const int l = t0 + tid;
@@ -558,7 +580,7 @@ int launch_project(socket_ctx *ctx, const void *q, const void *proj, float tau, 
     const int nhalf = g.mode == kDirect ? g.G * a.tpw * (g.Rlo + g.Rhi) : 0;
     const int esize = g.kv_dtype == SOCKET_F32 ? 4 : 2;
     size_t lds = (size_t)(g.G * g.d + 2 * g.G * cols + nhalf) * sizeof(double) + (size_t)g.d * 4 + 16 +
-                 (size_t)g.d * cols * esize;
+                 (size_t)g.d * cols * esize + 4 * 64 * 4 + 16;
     dim3 grid((g.Lpad + a.tpw - 1) / a.tpw, g.Hkv, batch);
     if (g.kv_dtype == SOCKET_F32) {
         if (lds > 64 * 1024 && hipFuncSetAttribute((const void *)project_kernel<float>,

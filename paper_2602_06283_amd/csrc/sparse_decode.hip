@@ -67,11 +67,11 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(DecodeArg
     const int sub = lane % LPR, rl = lane / LPR;     // this lane's 8-element slice and row slot
     const float ninf = -__builtin_inff();
 
-    int nsel = a.n_selected[bh];
-    nsel = nsel < 0 ? 0 : (nsel > a.max_k ? a.max_k : nsel);
-    const int per = (nsel + a.n_split - 1) / a.n_split;
+    // Splits own fixed slices of the max_k-long index row, so the index loads do not have to
+    // wait for the selected count; entries at or beyond the count are ignored.
+    const int per = (a.max_k + a.n_split - 1) / a.n_split;
     const int r_begin = split * per;
-    const int r_end = min(nsel, r_begin + per);
+    const int r_end = min(a.max_k, r_begin + per);
     const int32_t *idx = a.idx + (int64_t)bh * a.max_k;
 
     float qf[G][8];
@@ -99,7 +99,8 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(DecodeArg
             int64_t row = -1;
             if (r < r_end) {
                 int t = idx[r];
-                if (t >= 0 && t < a.map.max_n) row = a.map.row(b, h, t);
+                int nsel = a.n_selected[bh];
+                if (r < nsel && t >= 0 && t < a.map.max_n) row = a.map.row(b, h, t);
             }
             s_row[tid] = row;
         }

@@ -15,9 +15,17 @@
 
 namespace sk {
 
+#ifdef SK_DEBUG_CLOCKS
+__device__ long long sk_dbg[64];
+#define SK_STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x == 0) sk_dbg[i] = wall_clock64(); } while (0)
+#else
+#define SK_STAMP(i) ((void)0)
+#endif
+
 constexpr int kTopkThreads = 512;
-constexpr int kRefineBins = 4096;                // bins of the candidate-refinement digits and words of the bitmap
-constexpr int kBitmapTokens = kRefineBins * 32;  // tokens one LDS bitmap pass covers
+constexpr int kRefineBins = 4096;                // bins of the candidate-refinement digits
+constexpr int kBitmapWords = 8192;               // 32 KB of LDS
+constexpr int kBitmapTokens = kBitmapWords * 32; // tokens one LDS bitmap pass covers
 constexpr int kLowBits = 32 - kHistBits;         // score bits below the leading digit
 static_assert(kLowBits > 12 && kLowBits <= 24, "two refinement digits of at most 12 bits");
 constexpr int kPer = 8;                         // scores per thread in a sweep
@@ -130,11 +138,18 @@ __device__ __forceinline__ void two_digit_threshold(const uint32_t *gh1, const u
                                                     bool want_second, uint32_t *h, uint32_t *res,
                                                     uint32_t *tmp, uint32_t *out) {
     const int tid = threadIdx.x;
+    constexpr int PER = kHistBins / kTopkThreads;
+    uint32_t c1[PER], c2[PER];                    // both histograms' loads go out together
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+        c1[j] = gh1[tid + j * kTopkThreads];
+        c2[j] = want_second ? gh2[tid + j * kTopkThreads] : 0u;
+    }
     uint32_t part = 0;
-    for (int i = tid; i < kHistBins; i += kTopkThreads) {
-        uint32_t c = gh1[i];
-        h[i] = c;
-        part += c;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+        h[tid + j * kTopkThreads] = c1[j];
+        part += c1[j];
     }
     if (tid < 4) res[tid] = 0;
     __syncthreads();
@@ -148,7 +163,8 @@ __device__ __forceinline__ void two_digit_threshold(const uint32_t *gh1, const u
     out[1] = tb1; out[3] = above1; out[4] = cnt1;
     if (!want_second) return;
     __syncthreads();
-    for (int i = tid; i < kHistBins; i += kTopkThreads) h[i] = gh2[i];
+#pragma unroll
+    for (int j = 0; j < PER; ++j) h[tid + j * kTopkThreads] = c2[j];
     __syncthreads();
     find_threshold<kHistBins>(h, k_eff - above1, res, tmp);   // 1 <= k_eff - above1 <= cnt1
     out[2] = res[0]; out[3] = above1 + res[1]; out[4] = res[2];
@@ -165,9 +181,19 @@ __global__ __launch_bounds__(kTopkThreads) void topk_hist2_kernel(TopkArgs a) {
     __shared__ uint32_t res[4];
     const int tid = threadIdx.x;
     const int bh = blockIdx.y, b = bh / a.Hkv;
+    const int key0 = blockIdx.x * kSlice;
+    const int i = key0 + tid * kPer;
+    // this thread's scores first (in bounds for any length), so that their latency overlaps
+    // the histogram loads and the threshold search
+    const float *s = a.scores + (int64_t)bh * a.max_n;
+    float e[kPer];
+#pragma unroll
+    for (int v = 0; v < kPer / 4; ++v) {
+        float4 q = i + 4 * v < a.max_n ? *(const float4 *)(s + i + 4 * v) : make_float4(0, 0, 0, 0);
+        e[4 * v] = q.x; e[4 * v + 1] = q.y; e[4 * v + 2] = q.z; e[4 * v + 3] = q.w;
+    }
     int seq = a.seq_len[b];
     seq = seq < 0 ? 0 : (seq > a.max_n ? a.max_n : seq);
-    const int key0 = blockIdx.x * kSlice;
     const int key1 = min(key0 + kSlice, seq);
     if (key0 >= key1) return;
     int kreq = a.k[b];
@@ -177,20 +203,12 @@ __global__ __launch_bounds__(kTopkThreads) void topk_hist2_kernel(TopkArgs a) {
     if (th[0] == 0) return;
     const uint32_t tb1 = th[1];
     __syncthreads();
-    for (int i = tid; i < kHistBins; i += kTopkThreads) h[i] = 0;
+    for (int j = tid; j < kHistBins; j += kTopkThreads) h[j] = 0;
     __syncthreads();
-    const float *s = a.scores + (int64_t)bh * a.max_n;
-    const int i = key0 + tid * kPer;
 #pragma unroll
-    for (int v = 0; v < kPer / 4; ++v) {
-        if (i + 4 * v >= key1) continue;
-        float4 q = *(const float4 *)(s + i + 4 * v);
-        float e[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const uint32_t key = order_key(e[j]);
-            if (i + 4 * v + j < key1 && selectable(e[j]) && (key >> kLowBits) == tb1) atomicAdd(&h[digit2(key)], 1u);
-        }
+    for (int j = 0; j < kPer; ++j) {
+        const uint32_t key = order_key(e[j]);
+        if (i + j < key1 && selectable(e[j]) && (key >> kLowBits) == tb1) atomicAdd(&h[digit2(key)], 1u);
     }
     __syncthreads();
     uint32_t *gh2 = a.hist2 + (int64_t)bh * kHistBins;
@@ -207,9 +225,18 @@ __global__ __launch_bounds__(kTopkThreads) void topk_filter_kernel(TopkArgs a) {
     __shared__ uint32_t s_base[2];
     const int tid = threadIdx.x;
     const int bh = blockIdx.y, b = bh / a.Hkv;
+    const int key0 = blockIdx.x * kSlice;
+    const int i = key0 + tid * kPer;
+    // kSlice scores per workgroup, kPer per thread, loaded first and held in registers
+    const float *s = a.scores + (int64_t)bh * a.max_n;
+    float e[kPer];
+#pragma unroll
+    for (int v = 0; v < kPer / 4; ++v) {
+        float4 q = i + 4 * v < a.max_n ? *(const float4 *)(s + i + 4 * v) : make_float4(0, 0, 0, 0);
+        e[4 * v] = q.x; e[4 * v + 1] = q.y; e[4 * v + 2] = q.z; e[4 * v + 3] = q.w;
+    }
     int seq = a.seq_len[b];
     seq = seq < 0 ? 0 : (seq > a.max_n ? a.max_n : seq);
-    const int key0 = blockIdx.x * kSlice;
     const int key1 = min(key0 + kSlice, seq);
     if (key0 >= key1) return;
     int kreq = a.k[b];
@@ -223,30 +250,18 @@ __global__ __launch_bounds__(kTopkThreads) void topk_filter_kernel(TopkArgs a) {
     uint32_t *ckey = a.cand_key + (int64_t)bh * a.max_n;
     int32_t *cidx = a.cand_idx + (int64_t)bh * a.max_n;
     int32_t *staged = a.staged + (int64_t)bh * a.max_k;       // selected positions, unordered
-    const float *s = a.scores + (int64_t)bh * a.max_n;
 
-    // kSlice scores per workgroup, kPer per thread, held in registers.  Positions in the two
-    // lists are handed out with one atomic per workgroup and list: every thread counts its
-    // hits and a block scan turns the counts into offsets.
+    // Positions in the two lists are handed out with one atomic per workgroup and list:
+    // every thread counts its hits and a block scan turns the counts into offsets.
     uint32_t keys[kPer];
     uint32_t flags = 0;                           // bit j: selected, bit 16+j: candidate
-    const int i = key0 + tid * kPer;
 #pragma unroll
-    for (int v = 0; v < kPer / 4; ++v) {
-        float e[4] = {0, 0, 0, 0};
-        if (i + 4 * v < key1) {
-            float4 q = *(const float4 *)(s + i + 4 * v);
-            e[0] = q.x; e[1] = q.y; e[2] = q.z; e[3] = q.w;
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int at = 4 * v + j;
-            const bool ok = i + at < key1 && selectable(e[j]);
-            keys[at] = order_key(e[j]);
-            const uint32_t lead = keys[at] >> kDigit2Shift;
-            if (ok && lead > pair) flags |= 1u << at;
-            if (ok && lead == pair) flags |= 1u << (16 + at);
-        }
+    for (int j = 0; j < kPer; ++j) {
+        const bool ok = i + j < key1 && selectable(e[j]);
+        keys[j] = order_key(e[j]);
+        const uint32_t lead = keys[j] >> kDigit2Shift;
+        if (ok && lead > pair) flags |= 1u << j;
+        if (ok && lead == pair) flags |= 1u << (16 + j);
     }
     const uint32_t mine = (uint32_t)__popc(flags & 0xffffu) | ((uint32_t)__popc(flags >> 16) << 16);
     uint32_t total;
@@ -289,15 +304,14 @@ __device__ __forceinline__ uint32_t refine_digit(int level, uint32_t key, int32_
 // zero for the next call.  Runs after the sweep as a kernel of its own, so it needs no
 // fence or inter-workgroup signalling.
 __global__ __launch_bounds__(kTopkThreads) void topk_resolve_kernel(TopkArgs a) {
-    __shared__ uint32_t h[kRefineBins];
+    extern __shared__ uint32_t h[];               // kBitmapWords words: refinement histogram, then bitmap
     __shared__ uint32_t tmp[16];
     __shared__ uint32_t res[4];
     __shared__ uint32_t chosen[kLevels];
     __shared__ uint32_t s_count;
+    constexpr int PRE = 8;                        // list entries per thread fetched up front
     const int tid = threadIdx.x;
     const int bh = blockIdx.x, b = bh / a.Hkv;
-    int seq = a.seq_len[b];
-    seq = seq < 0 ? 0 : (seq > a.max_n ? a.max_n : seq);
     uint32_t *gh1 = a.hist + (int64_t)bh * kHistBins;
     uint32_t *gh2 = a.hist2 + (int64_t)bh * kHistBins;
     uint32_t *cnt = a.counters + (int64_t)bh * kCounterStride;
@@ -305,12 +319,46 @@ __global__ __launch_bounds__(kTopkThreads) void topk_resolve_kernel(TopkArgs a) 
     const int32_t *cidx = a.cand_idx + (int64_t)bh * a.max_n;
     int32_t *staged = a.staged + (int64_t)bh * a.max_k;
     int32_t *out = a.idx + (int64_t)bh * a.max_k;
+    // The heads of both lists are fetched before their lengths are known (the reads stay inside
+    // the buffers), so that their latency overlaps the histogram loads and threshold search.
+    SK_STAMP(0);
+    uint32_t pk[PRE];
+    int32_t pp[PRE], ps[PRE];
+#pragma unroll
+    for (int j = 0; j < PRE; ++j) {
+        const int i = tid + j * kTopkThreads;
+        pk[j] = i < a.max_n ? ckey[i] : 0u;
+        pp[j] = i < a.max_n ? cidx[i] : 0;
+        ps[j] = i < a.max_k ? staged[i] : 0;
+    }
+    int seq = a.seq_len[b];
+    seq = seq < 0 ? 0 : (seq > a.max_n ? a.max_n : seq);
     int kreq = a.k[b];
     kreq = kreq < 0 ? 0 : (kreq > a.max_k ? a.max_k : kreq);
     uint32_t th[5];
     two_digit_threshold(gh1, gh2, kreq, true, h, res, tmp, th);
     const uint32_t k_eff = th[0], above = th[3], n_cand = th[4];
     __syncthreads();
+    SK_STAMP(1);
+
+    // visit every candidate on the prefix chosen so far: f(key, position)
+    auto for_candidates = [&](int level, auto f) {
+#pragma unroll
+        for (int j = 0; j < PRE; ++j) {
+            const uint32_t i = tid + j * kTopkThreads;
+            if (i >= n_cand) continue;
+            bool match = true;
+            for (int l = 0; l < level; ++l) match = match && refine_digit(l, pk[j], pp[j]) == chosen[l];
+            if (match) f(pk[j], pp[j]);
+        }
+        for (uint32_t i = tid + PRE * kTopkThreads; i < n_cand; i += kTopkThreads) {
+            const uint32_t key = ckey[i];
+            const int32_t pos = cidx[i];
+            bool match = true;
+            for (int l = 0; l < level; ++l) match = match && refine_digit(l, key, pos) == chosen[l];
+            if (match) f(key, pos);
+        }
+    };
 
     if (k_eff > 0) {
         // keep the `need` best of the n_cand candidates
@@ -321,24 +369,14 @@ __global__ __launch_bounds__(kTopkThreads) void topk_resolve_kernel(TopkArgs a) 
         while (need > 0 && need < remaining && level < kLevels) {
             for (int i = tid; i < kRefineBins; i += kTopkThreads) h[i] = 0;
             __syncthreads();
-            for (uint32_t i = tid; i < n_cand; i += kTopkThreads) {
-                uint32_t key = ckey[i];
-                int32_t pos = cidx[i];
-                bool match = true;
-                for (int l = 0; l < level; ++l) match = match && refine_digit(l, key, pos) == chosen[l];
-                if (match) atomicAdd(&h[refine_digit(level, key, pos)], 1u);
-            }
+            for_candidates(level, [&](uint32_t key, int32_t pos) { atomicAdd(&h[refine_digit(level, key, pos)], 1u); });
             __syncthreads();
             find_threshold<kRefineBins>(h, need, res, tmp);
             const uint32_t td = res[0];
             // candidates on the current prefix with a larger digit are selected
-            for (uint32_t i = tid; i < n_cand; i += kTopkThreads) {
-                uint32_t key = ckey[i];
-                int32_t pos = cidx[i];
-                bool match = true;
-                for (int l = 0; l < level; ++l) match = match && refine_digit(l, key, pos) == chosen[l];
-                if (match && refine_digit(level, key, pos) > td) staged[atomicAdd(&s_count, 1u)] = pos;
-            }
+            for_candidates(level, [&](uint32_t key, int32_t pos) {
+                if (refine_digit(level, key, pos) > td) staged[atomicAdd(&s_count, 1u)] = pos;
+            });
             need -= res[1];
             remaining = res[2];
             __syncthreads();
@@ -346,40 +384,37 @@ __global__ __launch_bounds__(kTopkThreads) void topk_resolve_kernel(TopkArgs a) 
             ++level;
             __syncthreads();
         }
-        if (need > 0) {   // need == remaining: everything left on the prefix is selected
-            for (uint32_t i = tid; i < n_cand; i += kTopkThreads) {
-                uint32_t key = ckey[i];
-                int32_t pos = cidx[i];
-                bool match = true;
-                for (int l = 0; l < level; ++l) match = match && refine_digit(l, key, pos) == chosen[l];
-                if (match) staged[atomicAdd(&s_count, 1u)] = pos;
-            }
-        }
+        if (need > 0)     // need == remaining: everything left on the prefix is selected
+            for_candidates(level, [&](uint32_t, int32_t pos) { staged[atomicAdd(&s_count, 1u)] = pos; });
         __syncthreads();
+        SK_STAMP(2);
 
         // ---- ascending emit through an LDS bitmap, kBitmapTokens tokens per pass
         uint32_t written = 0;
         for (int base = 0; base < seq; base += kBitmapTokens) {
-            for (int i = tid; i < kRefineBins; i += kTopkThreads) h[i] = 0;
+            for (int i = tid; i < kBitmapWords; i += kTopkThreads) h[i] = 0;
             __syncthreads();
-            for (uint32_t i0 = tid; i0 < k_eff; i0 += 8 * kTopkThreads) {
-                int32_t p8[8];                    // all of a thread's loads in flight together
+            SK_STAMP(5);
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const uint32_t i = i0 + j * kTopkThreads;
-                    p8[j] = i < k_eff ? staged[i] - base : -1;
-                }
-#pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    if (p8[j] >= 0 && p8[j] < kBitmapTokens) atomicOr(&h[p8[j] >> 5], 1u << (p8[j] & 31));
+            for (int j = 0; j < PRE; ++j) {       // slots filled by the sweep: already in registers
+                const uint32_t i = tid + j * kTopkThreads;
+                const int32_t p = ps[j] - base;
+                if (i < above && p >= 0 && p < kBitmapTokens) atomicOr(&h[p >> 5], 1u << (p & 31));
+            }
+            for (uint32_t i = tid; i < k_eff; i += kTopkThreads) {
+                if (i < above && i < (uint32_t)(PRE * kTopkThreads)) continue;
+                const int32_t p = staged[i] - base;
+                if (p >= 0 && p < kBitmapTokens) atomicOr(&h[p >> 5], 1u << (p & 31));
             }
             __syncthreads();
-            constexpr int PER = kRefineBins / kTopkThreads;
+            SK_STAMP(6);
+            constexpr int PER = kBitmapWords / kTopkThreads;
             uint32_t c = 0;
 #pragma unroll
             for (int i = 0; i < PER; ++i) c += __popc(h[tid * PER + i]);
             uint32_t total;
             uint32_t at = written + block_excl_scan(c, &total, tmp);
+            SK_STAMP(7);
             for (int i = 0; i < PER; ++i) {
                 uint32_t w = h[tid * PER + i];
                 while (w) {
@@ -389,10 +424,12 @@ __global__ __launch_bounds__(kTopkThreads) void topk_resolve_kernel(TopkArgs a) 
                     ++at;
                 }
             }
+            SK_STAMP(8);
             written += total;
             __syncthreads();
         }
     }
+    SK_STAMP(3);
     for (int i = (int)k_eff + tid; i < a.max_k; i += kTopkThreads) out[i] = -1;
     if (tid == 0) a.n_selected[bh] = (int32_t)k_eff;
     // leave the shared scratch clean for the next call
@@ -401,7 +438,17 @@ __global__ __launch_bounds__(kTopkThreads) void topk_resolve_kernel(TopkArgs a) 
         gh2[i] = 0;
     }
     if (tid < 2) cnt[tid] = 0;
+    SK_STAMP(4);
+#ifdef SK_DEBUG_CLOCKS
+    if (threadIdx.x == 0 && blockIdx.x == 0) { sk_dbg[10] = n_cand; sk_dbg[11] = above; sk_dbg[12] = k_eff; }
+#endif
 }
+
+#ifdef SK_DEBUG_CLOCKS
+extern "C" int socket_debug_clocks(long long *out) {
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(sk_dbg), sizeof(long long) * 64);
+}
+#endif
 
 int launch_topk(socket_ctx *ctx, const float *scores, const int32_t *seq_len, const int32_t *k,
                 int batch, int32_t *idx, int32_t *n_selected, bool have_hist, hipStream_t st) {
@@ -415,7 +462,7 @@ int launch_topk(socket_ctx *ctx, const float *scores, const int32_t *seq_len, co
     if (!have_hist) hipLaunchKernelGGL(topk_hist_kernel, grid, dim3(kTopkThreads), 0, st, a);
     hipLaunchKernelGGL(topk_hist2_kernel, grid, dim3(kTopkThreads), 0, st, a);
     hipLaunchKernelGGL(topk_filter_kernel, grid, dim3(kTopkThreads), 0, st, a);
-    hipLaunchKernelGGL(topk_resolve_kernel, dim3(BH), dim3(kTopkThreads), 0, st, a);
+    hipLaunchKernelGGL(topk_resolve_kernel, dim3(BH), dim3(kTopkThreads), kBitmapWords * 4, st, a);
     return record_hip(ctx, hipGetLastError());
 }
 

@@ -289,10 +289,15 @@ def test_topk_long_row_uses_several_bitmap_passes():
     n = 131072 * 2 + 64
     rng = np.random.default_rng(4)
     s = (0.25 + 0.02 * rng.standard_normal((1, 1, n))).astype(np.float32)
-    p = sk.make_params(128, 1, 1, 64, 8, sk.BF16, 1, n, 4096)
+    p = sk.make_params(128, 1, 1, 64, 8, sk.BF16, 1, n, 5000)
     ctx = sk.Context(p)
-    idx, nsel = run_topk(ctx, s, [n - 5], [4096], 1, 1, 4096)
-    check_topk(idx, nsel, s, [n - 5], [4096])
+    for k in (4096, 5000):
+        idx, nsel = run_topk(ctx, s, [n - 5], [k], 1, 1, 5000)
+        check_topk(idx, nsel, s, [n - 5], [k])
+    # many exact ties at the cut with a long candidate list
+    s2 = np.round(s * 64) / 64
+    idx, nsel = run_topk(ctx, s2, [n - 5], [5000], 1, 1, 5000)
+    check_topk(idx, nsel, s2, [n - 5], [5000])
     ctx.close()
 
 
