@@ -112,7 +112,7 @@ int socket_create(socket_ctx **out, const socket_params *p) {
     const int64_t BH = (int64_t)g.max_batch * g.Hkv;
     const int64_t sz_tables = BH * g.table_words * 4;
     const int64_t sz_hist = 2 * BH * kHistBins * 4;   // first- and second-digit histograms
-    const int64_t sz_cnt = BH * kCounterStride * 4;
+    const int64_t sz_cnt = BH * (kCounterStride + kThrStride) * 4;
     const int64_t sz_cand = BH * g.max_n * 4;
     const int64_t sz_staged = BH * g.max_k * 4;
     const int64_t sz_seq = (int64_t)g.max_batch * 4;

@@ -23,6 +23,7 @@ constexpr int kScoreU = SK_SCORE_U;          // 16-byte loads a lane keeps in fl
 constexpr int kDecodeThreads = 256;
 constexpr int kDecodeChunk = 64;     // selected rows a decode workgroup handles per pass
 constexpr int kCounterStride = 16;   // uint32 counters per (sequence, KV head)
+constexpr int kThrStride = 8;        // uint32 words of the top-k threshold record per (sequence, KV head)
 
 // How the L x R bucket probabilities of one KV head are laid out for the scoring kernel.
 //   direct : one entry per (table, bucket), already averaged over the G query heads:
@@ -56,7 +57,7 @@ struct socket_ctx {
     int64_t scratch_bytes;
     float *tables;        // [max_batch*Hkv][table_words]
     uint32_t *hist;       // [2][max_batch*Hkv][kHistBins]
-    uint32_t *counters;   // [max_batch*Hkv][kCounterStride]
+    uint32_t *counters;   // [max_batch*Hkv][kCounterStride] counters, then [max_batch*Hkv][kThrStride] records
     uint32_t *cand_key;   // [max_batch*Hkv][max_n]
     int32_t *cand_idx;    // [max_batch*Hkv][max_n]
     int32_t *staged;      // [max_batch*Hkv][max_k] selected positions before ordering

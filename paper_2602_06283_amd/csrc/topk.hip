@@ -3,14 +3,18 @@
 //
 //   topk_hist_kernel    histogram of the leading 11-bit digit of every valid score (the fused
 //                       decode step gets it from the scoring pass instead).
-//   topk_hist2_kernel   histogram of the next 11 bits over the scores in the threshold digit.
-//   topk_filter_kernel  sweep: scores above the two-digit threshold are selected, scores equal
-//                       to it become candidates.
-//   topk_resolve_kernel one workgroup per (sequence, head): resolves the candidates on the
-//                       remaining score bits and then on the token position, and writes the
-//                       selection in ascending position order.
+//   topk_hist2_kernel   finds the threshold digit, then histograms the next 11 bits over the
+//                       scores in that digit.
+//   topk_filter_kernel  finds the second threshold digit, then sweeps: scores above the
+//                       two-digit threshold are selected, scores equal to it are candidates
+//                       (one bin of a 2^22-bin histogram: a handful unless many scores tie).
+//   topk_resolve_kernel one workgroup per (sequence, head): ranks the candidates on the
+//                       remaining score bits and then on the token position (smaller position
+//                       wins a tie), and writes the selection in ascending position order
+//                       through an LDS bitmap.  Leaves histograms and counters at zero.
 // Stages talk through global memory across kernel boundaries only: no workgroup waits on
-// another and no fence is needed.
+// another and no fence is needed.  LDS arrays that a thread walks in runs of PER consecutive
+// words carry one pad word per run, which makes those walks free of bank conflicts.
 #include "socket_internal.h"
 
 namespace sk {
@@ -23,13 +27,17 @@ __device__ long long sk_dbg[64];
 #endif
 
 constexpr int kTopkThreads = 512;
-constexpr int kRefineBins = 4096;                // bins of the candidate-refinement digits
+constexpr int kRefineBins = 4096;                // bins of a candidate-refinement digit
 constexpr int kBitmapWords = 8192;               // 32 KB of LDS
 constexpr int kBitmapTokens = kBitmapWords * 32; // tokens one LDS bitmap pass covers
 constexpr int kLowBits = 32 - kHistBits;         // score bits below the leading digit
-static_assert(kLowBits > 12 && kLowBits <= 24, "two refinement digits of at most 12 bits");
-constexpr int kPer = 8;                         // scores per thread in a sweep
-constexpr int kSlice = kTopkThreads * kPer;     // scores per workgroup
+constexpr int kDigit2Shift = kLowBits - kHistBits;   // second digit: the next kHistBits score bits
+static_assert(kDigit2Shift >= 0 && kDigit2Shift <= 12, "the low score bits fit one refinement digit");
+constexpr int kPer = 8;                          // scores per thread in a sweep
+constexpr int kSlice = kTopkThreads * kPer;      // scores per workgroup
+constexpr int kRankMax = 2 * kTopkThreads;       // candidates the all-pairs ranking handles
+// threshold record: [0] k_eff, [1] first digit, [2] scores above it, [3] scores in it,
+//                   [4] second digit, [5] scores selected outright, [6] candidates
 
 struct TopkArgs {
     const float *scores;
@@ -39,6 +47,7 @@ struct TopkArgs {
     int32_t *n_selected;
     uint32_t *hist;       // first-digit histograms [B*Hkv][kHistBins]
     uint32_t *hist2;      // second-digit histograms of the threshold bin
+    uint32_t *thr;        // threshold records [B*Hkv][kThrStride]
     uint32_t *counters;
     uint32_t *cand_key;
     int32_t *cand_idx;
@@ -52,6 +61,11 @@ __device__ __forceinline__ uint32_t order_key(float f) {
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 __device__ __forceinline__ bool selectable(float f) { return f > -__builtin_inff(); }  // false for NaN
+__device__ __forceinline__ uint32_t digit2(uint32_t key) { return (key >> kDigit2Shift) & (kHistBins - 1); }
+
+// word w of an array walked in runs of PER words, one pad word per run
+template <int PER> __device__ __forceinline__ int padded(int w) { return w + w / PER; }
+template <int N, int PER> constexpr int padded_size() { return N + N / PER; }
 
 // Exclusive prefix sum over the 512 threads of a block; *total gets the block sum.
 __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *total, uint32_t *tmp) {
@@ -76,150 +90,131 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *total,
     return base + x - v;
 }
 
-// Largest bin tb of the NBINS-bin LDS histogram h with count(bins >= tb) >= target.
-// res[0] = tb, res[1] = count(bins > tb), res[2] = h[tb].  Requires 1 <= target <= sum(h).
+// Largest bin tb of the NBINS-bin padded LDS histogram h with count(bins >= tb) >= target.
+// res[0] = tb, res[1] = count(bins > tb), res[2] = h[tb], res[3] = sum(h).
+// A target outside [1, sum(h)] leaves res[0..2] untouched.
 template <int NBINS>
 __device__ __forceinline__ void find_threshold(const uint32_t *h, uint32_t target, uint32_t *res,
                                                uint32_t *tmp) {
     const int t = threadIdx.x;
     constexpr int PER = NBINS / kTopkThreads;       // bins per thread, highest bins first
     const int top = NBINS - 1 - t * PER;
+    uint32_t c[PER];
     uint32_t part = 0;
 #pragma unroll
-    for (int i = 0; i < PER; ++i) part += h[top - i];
+    for (int i = 0; i < PER; ++i) {
+        c[i] = h[padded<PER>(top - i)];
+        part += c[i];
+    }
     uint32_t total;
     uint32_t above = block_excl_scan(part, &total, tmp);
+    if (t == 0) res[3] = total;
     if (above < target && target <= above + part) {
         uint32_t cum = above;
+#pragma unroll
         for (int i = 0; i < PER; ++i) {
-            uint32_t c = h[top - i];
-            if (cum + c >= target) {
+            if (cum < target && cum + c[i] >= target) {
                 res[0] = (uint32_t)(top - i);
                 res[1] = cum;
-                res[2] = c;
-                break;
+                res[2] = c[i];
             }
-            cum += c;
+            cum += c[i];
         }
     }
     __syncthreads();
 }
 
+// this thread's kPer scores of the slice starting at key0 (in bounds for any sequence length)
+__device__ __forceinline__ void load_scores(const float *s, int i, int max_n, float *e) {
+#pragma unroll
+    for (int v = 0; v < kPer / 4; ++v) {
+        float4 q = i + 4 * v < max_n ? *(const float4 *)(s + i + 4 * v) : make_float4(0, 0, 0, 0);
+        e[4 * v] = q.x; e[4 * v + 1] = q.y; e[4 * v + 2] = q.z; e[4 * v + 3] = q.w;
+    }
+}
+
+__device__ __forceinline__ int clamp_len(int v, int hi) { return v < 0 ? 0 : (v > hi ? hi : v); }
+
 __global__ __launch_bounds__(kTopkThreads) void topk_hist_kernel(TopkArgs a) {
     __shared__ uint32_t h[kHistBins];
     const int tid = threadIdx.x;
     const int bh = blockIdx.y, b = bh / a.Hkv;
-    int seq = a.seq_len[b];
-    seq = seq < 0 ? 0 : (seq > a.max_n ? a.max_n : seq);
     const int key0 = blockIdx.x * kSlice;
-    const int key1 = min(key0 + kSlice, seq);
+    const int i = key0 + tid * kPer;
+    float e[kPer];
+    load_scores(a.scores + (int64_t)bh * a.max_n, i, a.max_n, e);
+    const int key1 = min(key0 + kSlice, clamp_len(a.seq_len[b], a.max_n));
     if (key0 >= key1) return;
-    for (int i = tid; i < kHistBins; i += kTopkThreads) h[i] = 0;
+    for (int j = tid; j < kHistBins; j += kTopkThreads) h[j] = 0;
     __syncthreads();
-    const float *s = a.scores + (int64_t)bh * a.max_n;
-    for (int i = key0 + tid * 4; i < key1; i += kTopkThreads * 4) {
-        float4 v = *(const float4 *)(s + i);      // max_n and slice are multiples of 4
-        float e[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (i + j < key1 && selectable(e[j])) atomicAdd(&h[order_key(e[j]) >> kLowBits], 1u);
-    }
+    for (int j = 0; j < kPer; ++j)
+        if (i + j < key1 && selectable(e[j])) atomicAdd(&h[order_key(e[j]) >> kLowBits], 1u);
     __syncthreads();
     uint32_t *gh = a.hist + (int64_t)bh * kHistBins;
-    for (int i = tid; i < kHistBins; i += kTopkThreads)
-        if (h[i]) atomicAdd(&gh[i], h[i]);
+    for (int j = tid; j < kHistBins; j += kTopkThreads)
+        if (h[j]) atomicAdd(&gh[j], h[j]);
 }
 
-// Threshold of the two leading digits, recomputed identically by every workgroup that
-// needs it: tb1 from the first-digit histogram, then tb2 among the scores whose first digit
-// is tb1.  out: [0] k_eff, [1] tb1, [2] tb2, [3] scores selected outright (above the pair),
-// [4] scores equal to the pair (candidates).  h is LDS scratch of >= kHistBins words.
-__device__ __forceinline__ void two_digit_threshold(const uint32_t *gh1, const uint32_t *gh2, int kreq,
-                                                    bool want_second, uint32_t *h, uint32_t *res,
-                                                    uint32_t *tmp, uint32_t *out) {
-    const int tid = threadIdx.x;
-    constexpr int PER = kHistBins / kTopkThreads;
-    uint32_t c1[PER], c2[PER];                    // both histograms' loads go out together
-#pragma unroll
-    for (int j = 0; j < PER; ++j) {
-        c1[j] = gh1[tid + j * kTopkThreads];
-        c2[j] = want_second ? gh2[tid + j * kTopkThreads] : 0u;
-    }
-    uint32_t part = 0;
-#pragma unroll
-    for (int j = 0; j < PER; ++j) {
-        h[tid + j * kTopkThreads] = c1[j];
-        part += c1[j];
-    }
-    if (tid < 4) res[tid] = 0;
-    __syncthreads();
-    uint32_t valid;
-    (void)block_excl_scan(part, &valid, tmp);
-    const uint32_t k_eff = min((uint32_t)kreq, valid);
-    out[0] = k_eff; out[1] = 0; out[2] = 0; out[3] = 0; out[4] = 0;
-    if (k_eff == 0) return;
-    find_threshold<kHistBins>(h, k_eff, res, tmp);
-    const uint32_t tb1 = res[0], above1 = res[1], cnt1 = res[2];
-    out[1] = tb1; out[3] = above1; out[4] = cnt1;
-    if (!want_second) return;
-    __syncthreads();
-#pragma unroll
-    for (int j = 0; j < PER; ++j) h[tid + j * kTopkThreads] = c2[j];
-    __syncthreads();
-    find_threshold<kHistBins>(h, k_eff - above1, res, tmp);   // 1 <= k_eff - above1 <= cnt1
-    out[2] = res[0]; out[3] = above1 + res[1]; out[4] = res[2];
-}
-
-constexpr int kDigit2Shift = kLowBits - kHistBits;    // second digit: the next kHistBits score bits
-static_assert(kDigit2Shift >= 0 && kDigit2Shift <= 12, "the low score bits fit one refinement digit");
-__device__ __forceinline__ uint32_t digit2(uint32_t key) { return (key >> kDigit2Shift) & (kHistBins - 1); }
-
-// Histogram of the second digit over the scores whose first digit is the threshold digit.
+// First threshold digit, then the histogram of the second digit over the scores in it.
 __global__ __launch_bounds__(kTopkThreads) void topk_hist2_kernel(TopkArgs a) {
-    __shared__ uint32_t h[kHistBins];
+    constexpr int PER = kHistBins / kTopkThreads;
+    __shared__ uint32_t h[padded_size<kHistBins, PER>()];
     __shared__ uint32_t tmp[16];
     __shared__ uint32_t res[4];
     const int tid = threadIdx.x;
     const int bh = blockIdx.y, b = bh / a.Hkv;
     const int key0 = blockIdx.x * kSlice;
     const int i = key0 + tid * kPer;
-    // this thread's scores first (in bounds for any length), so that their latency overlaps
-    // the histogram loads and the threshold search
-    const float *s = a.scores + (int64_t)bh * a.max_n;
     float e[kPer];
+    load_scores(a.scores + (int64_t)bh * a.max_n, i, a.max_n, e);   // first: overlaps what follows
+    const uint32_t *gh1 = a.hist + (int64_t)bh * kHistBins;
+    uint32_t c1[PER];
 #pragma unroll
-    for (int v = 0; v < kPer / 4; ++v) {
-        float4 q = i + 4 * v < a.max_n ? *(const float4 *)(s + i + 4 * v) : make_float4(0, 0, 0, 0);
-        e[4 * v] = q.x; e[4 * v + 1] = q.y; e[4 * v + 2] = q.z; e[4 * v + 3] = q.w;
-    }
-    int seq = a.seq_len[b];
-    seq = seq < 0 ? 0 : (seq > a.max_n ? a.max_n : seq);
-    const int key1 = min(key0 + kSlice, seq);
-    if (key0 >= key1) return;
-    int kreq = a.k[b];
-    kreq = kreq < 0 ? 0 : (kreq > a.max_k ? a.max_k : kreq);
-    uint32_t th[5];
-    two_digit_threshold(a.hist + (int64_t)bh * kHistBins, nullptr, kreq, false, h, res, tmp, th);
-    if (th[0] == 0) return;
-    const uint32_t tb1 = th[1];
+    for (int j = 0; j < PER; ++j) c1[j] = gh1[tid + j * kTopkThreads];
+    const int key1 = min(key0 + kSlice, clamp_len(a.seq_len[b], a.max_n));
+    const uint32_t kreq = (uint32_t)clamp_len(a.k[b], a.max_k);
+    if (key0 >= key1 && blockIdx.x != 0) return;       // workgroup 0 always publishes the record
+#pragma unroll
+    for (int j = 0; j < PER; ++j) h[padded<PER>(tid + j * kTopkThreads)] = c1[j];
+    if (tid < 4) res[tid] = 0;
     __syncthreads();
-    for (int j = tid; j < kHistBins; j += kTopkThreads) h[j] = 0;
+    // a target beyond the number of valid scores finds nothing; res[3] then gives that number
+    find_threshold<kHistBins>(h, kreq, res, tmp);
+    uint32_t k_eff = kreq, tb1 = res[0], above1 = res[1], cnt1 = res[2];
+    const uint32_t valid = res[3];
+    if (valid < kreq) {                                 // fewer valid scores than asked for: take all
+        k_eff = valid;
+        if (valid > 0) {
+            __syncthreads();
+            find_threshold<kHistBins>(h, valid, res, tmp);
+            tb1 = res[0]; above1 = res[1]; cnt1 = res[2];
+        }
+    }
+    uint32_t *thr = a.thr + (int64_t)bh * kThrStride;
+    if (blockIdx.x == 0 && tid == 0) {
+        thr[0] = k_eff; thr[1] = tb1; thr[2] = above1; thr[3] = cnt1;
+    }
+    if (k_eff == 0 || key0 >= key1) return;
+    __syncthreads();
+    uint32_t *h2 = h;                                   // plain (unpadded) use from here on
+    for (int j = tid; j < kHistBins; j += kTopkThreads) h2[j] = 0;
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < kPer; ++j) {
         const uint32_t key = order_key(e[j]);
-        if (i + j < key1 && selectable(e[j]) && (key >> kLowBits) == tb1) atomicAdd(&h[digit2(key)], 1u);
+        if (i + j < key1 && selectable(e[j]) && (key >> kLowBits) == tb1) atomicAdd(&h2[digit2(key)], 1u);
     }
     __syncthreads();
     uint32_t *gh2 = a.hist2 + (int64_t)bh * kHistBins;
     for (int j = tid; j < kHistBins; j += kTopkThreads)
-        if (h[j]) atomicAdd(&gh2[j], h[j]);
+        if (h2[j]) atomicAdd(&gh2[j], h2[j]);
 }
 
-// Sweep: scores above the two-digit threshold are selected, scores equal to it become
-// candidates (few: one bin of a 2^22-bin histogram unless many scores tie).
+// Second threshold digit, then the sweep.
 __global__ __launch_bounds__(kTopkThreads) void topk_filter_kernel(TopkArgs a) {
-    __shared__ uint32_t h[kHistBins];
+    constexpr int PER = kHistBins / kTopkThreads;
+    __shared__ uint32_t h[padded_size<kHistBins, PER>()];
     __shared__ uint32_t tmp[16];
     __shared__ uint32_t res[4];
     __shared__ uint32_t s_base[2];
@@ -227,29 +222,32 @@ __global__ __launch_bounds__(kTopkThreads) void topk_filter_kernel(TopkArgs a) {
     const int bh = blockIdx.y, b = bh / a.Hkv;
     const int key0 = blockIdx.x * kSlice;
     const int i = key0 + tid * kPer;
-    // kSlice scores per workgroup, kPer per thread, loaded first and held in registers
-    const float *s = a.scores + (int64_t)bh * a.max_n;
     float e[kPer];
+    load_scores(a.scores + (int64_t)bh * a.max_n, i, a.max_n, e);
+    const uint32_t *gh2 = a.hist2 + (int64_t)bh * kHistBins;
+    uint32_t c2[PER];
 #pragma unroll
-    for (int v = 0; v < kPer / 4; ++v) {
-        float4 q = i + 4 * v < a.max_n ? *(const float4 *)(s + i + 4 * v) : make_float4(0, 0, 0, 0);
-        e[4 * v] = q.x; e[4 * v + 1] = q.y; e[4 * v + 2] = q.z; e[4 * v + 3] = q.w;
+    for (int j = 0; j < PER; ++j) c2[j] = gh2[tid + j * kTopkThreads];
+    uint32_t *thr = a.thr + (int64_t)bh * kThrStride;
+    const uint32_t k_eff = thr[0], tb1 = thr[1], above1 = thr[2];
+    const int key1 = min(key0 + kSlice, clamp_len(a.seq_len[b], a.max_n));
+    if (k_eff == 0) return;
+    if (key0 >= key1 && blockIdx.x != 0) return;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) h[padded<PER>(tid + j * kTopkThreads)] = c2[j];
+    if (tid < 4) res[tid] = 0;
+    __syncthreads();
+    find_threshold<kHistBins>(h, k_eff - above1, res, tmp);    // 1 <= k_eff - above1 <= scores in tb1
+    const uint32_t tb2 = res[0], above = above1 + res[1], n_cand = res[2];
+    if (blockIdx.x == 0 && tid == 0) {
+        thr[4] = tb2; thr[5] = above; thr[6] = n_cand;
     }
-    int seq = a.seq_len[b];
-    seq = seq < 0 ? 0 : (seq > a.max_n ? a.max_n : seq);
-    const int key1 = min(key0 + kSlice, seq);
     if (key0 >= key1) return;
-    int kreq = a.k[b];
-    kreq = kreq < 0 ? 0 : (kreq > a.max_k ? a.max_k : kreq);
-    uint32_t th[5];
-    two_digit_threshold(a.hist + (int64_t)bh * kHistBins, a.hist2 + (int64_t)bh * kHistBins, kreq, true, h,
-                        res, tmp, th);
-    if (th[0] == 0) return;
-    const uint32_t pair = (th[1] << kHistBits) | th[2];       // the 2*kHistBits leading bits
+    const uint32_t pair = (tb1 << kHistBits) | tb2;            // the 2*kHistBits leading bits
     uint32_t *cnt = a.counters + (int64_t)bh * kCounterStride;
     uint32_t *ckey = a.cand_key + (int64_t)bh * a.max_n;
     int32_t *cidx = a.cand_idx + (int64_t)bh * a.max_n;
-    int32_t *staged = a.staged + (int64_t)bh * a.max_k;       // selected positions, unordered
+    int32_t *staged = a.staged + (int64_t)bh * a.max_k;        // selected positions, unordered
 
     // Positions in the two lists are handed out with one atomic per workgroup and list:
     // every thread counts its hits and a block scan turns the counts into offsets.
@@ -284,7 +282,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_filter_kernel(TopkArgs a) {
     }
 }
 
-// Refinement digits of a candidate below the two leading digits:
+// Refinement digits of a candidate below the two leading digits (long candidate lists only):
 //   level 0: the remaining low score bits
 //   level 1..3: bits 30..19, 18..7, 6..0 of (2^31-1 - position), so a smaller position ranks higher
 constexpr int kLevels = 4;
@@ -298,13 +296,9 @@ __device__ __forceinline__ uint32_t refine_digit(int level, uint32_t key, int32_
     }
 }
 
-// One workgroup per (sequence, KV head): resolves the candidates on the remaining score bits
-// and then on the token position (smaller position wins a tie), writes the selection in
-// ascending position order through an LDS bitmap, and leaves histograms and counters at
-// zero for the next call.  Runs after the sweep as a kernel of its own, so it needs no
-// fence or inter-workgroup signalling.
 __global__ __launch_bounds__(kTopkThreads) void topk_resolve_kernel(TopkArgs a) {
-    extern __shared__ uint32_t h[];               // kBitmapWords words: refinement histogram, then bitmap
+    constexpr int RPER = kRefineBins / kTopkThreads, BPER = kBitmapWords / kTopkThreads;
+    extern __shared__ uint32_t h[];               // 2 * padded_size<kBitmapWords, BPER>() words
     __shared__ uint32_t tmp[16];
     __shared__ uint32_t res[4];
     __shared__ uint32_t chosen[kLevels];
@@ -315,61 +309,74 @@ __global__ __launch_bounds__(kTopkThreads) void topk_resolve_kernel(TopkArgs a) 
     uint32_t *gh1 = a.hist + (int64_t)bh * kHistBins;
     uint32_t *gh2 = a.hist2 + (int64_t)bh * kHistBins;
     uint32_t *cnt = a.counters + (int64_t)bh * kCounterStride;
+    const uint32_t *thr = a.thr + (int64_t)bh * kThrStride;
     const uint32_t *ckey = a.cand_key + (int64_t)bh * a.max_n;
     const int32_t *cidx = a.cand_idx + (int64_t)bh * a.max_n;
     int32_t *staged = a.staged + (int64_t)bh * a.max_k;
     int32_t *out = a.idx + (int64_t)bh * a.max_k;
-    // The heads of both lists are fetched before their lengths are known (the reads stay inside
-    // the buffers), so that their latency overlaps the histogram loads and threshold search.
     SK_STAMP(0);
-    uint32_t pk[PRE];
-    int32_t pp[PRE], ps[PRE];
+    // The heads of both lists are fetched before their lengths are known (the reads stay inside
+    // the buffers), so that their latency overlaps the load of the threshold record.
+    uint32_t pk[2];
+    int32_t pp[2], ps[PRE];
 #pragma unroll
     for (int j = 0; j < PRE; ++j) {
         const int i = tid + j * kTopkThreads;
-        pk[j] = i < a.max_n ? ckey[i] : 0u;
-        pp[j] = i < a.max_n ? cidx[i] : 0;
+        if (j < 2) {
+            pk[j] = i < a.max_n ? ckey[i] : 0u;
+            pp[j] = i < a.max_n ? cidx[i] : 0;
+        }
         ps[j] = i < a.max_k ? staged[i] : 0;
     }
-    int seq = a.seq_len[b];
-    seq = seq < 0 ? 0 : (seq > a.max_n ? a.max_n : seq);
-    int kreq = a.k[b];
-    kreq = kreq < 0 ? 0 : (kreq > a.max_k ? a.max_k : kreq);
-    uint32_t th[5];
-    two_digit_threshold(gh1, gh2, kreq, true, h, res, tmp, th);
-    const uint32_t k_eff = th[0], above = th[3], n_cand = th[4];
-    __syncthreads();
+    const uint32_t k_eff = thr[0], above = k_eff ? thr[5] : 0u, n_cand = k_eff ? thr[6] : 0u;
+    const int seq = clamp_len(a.seq_len[b], a.max_n);
+    const uint32_t need0 = k_eff - above;         // candidates to keep
     SK_STAMP(1);
 
-    // visit every candidate on the prefix chosen so far: f(key, position)
-    auto for_candidates = [&](int level, auto f) {
+    bool keep[2] = {false, false};                // short list: this thread's candidates that are kept
+    const bool short_list = n_cand <= (uint32_t)kRankMax;
+    if (k_eff > 0 && short_list) {
+        // ---- all-pairs ranking in LDS on (score bits, smaller position first)
+        unsigned long long *ck = (unsigned long long *)h;
 #pragma unroll
-        for (int j = 0; j < PRE; ++j) {
+        for (int j = 0; j < 2; ++j) {
             const uint32_t i = tid + j * kTopkThreads;
-            if (i >= n_cand) continue;
-            bool match = true;
-            for (int l = 0; l < level; ++l) match = match && refine_digit(l, pk[j], pp[j]) == chosen[l];
-            if (match) f(pk[j], pp[j]);
+            if (i < n_cand) ck[i] = ((unsigned long long)pk[j] << 32) | (0x7fffffffu - (uint32_t)pp[j]);
         }
-        for (uint32_t i = tid + PRE * kTopkThreads; i < n_cand; i += kTopkThreads) {
-            const uint32_t key = ckey[i];
-            const int32_t pos = cidx[i];
-            bool match = true;
-            for (int l = 0; l < level; ++l) match = match && refine_digit(l, key, pos) == chosen[l];
-            if (match) f(key, pos);
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const uint32_t i = tid + j * kTopkThreads;
+            if (i < n_cand) {
+                const unsigned long long me = ck[i];
+                uint32_t rank = 0;
+                for (uint32_t o = 0; o < n_cand; ++o) rank += ck[o] > me;
+                keep[j] = rank < need0;
+            }
         }
-    };
-
-    if (k_eff > 0) {
-        // keep the `need` best of the n_cand candidates
-        uint32_t need = k_eff - above, remaining = n_cand;
+        __syncthreads();
+    } else if (k_eff > 0) {
+        // ---- long list (many tied scores): digit-by-digit refinement over the list in memory
+        auto for_candidates = [&](int level, auto f) {
+            for (uint32_t i = tid; i < n_cand; i += kTopkThreads) {
+                const uint32_t key = ckey[i];
+                const int32_t pos = cidx[i];
+                bool match = true;
+                for (int l = 0; l < level; ++l) match = match && refine_digit(l, key, pos) == chosen[l];
+                if (match) f(key, pos);
+            }
+        };
+        uint32_t need = need0, remaining = n_cand;
         if (tid == 0) s_count = above;            // next free staging slot
         __syncthreads();
         int level = 0;
         while (need > 0 && need < remaining && level < kLevels) {
-            for (int i = tid; i < kRefineBins; i += kTopkThreads) h[i] = 0;
+            for (int i = tid; i < padded_size<kRefineBins, RPER>(); i += kTopkThreads) h[i] = 0;
+            if (tid < 4) res[tid] = 0;
             __syncthreads();
-            for_candidates(level, [&](uint32_t key, int32_t pos) { atomicAdd(&h[refine_digit(level, key, pos)], 1u); });
+            for_candidates(level, [&](uint32_t key, int32_t pos) {
+                atomicAdd(&h[padded<RPER>((int)refine_digit(level, key, pos))], 1u);
+            });
             __syncthreads();
             find_threshold<kRefineBins>(h, need, res, tmp);
             const uint32_t td = res[0];
@@ -387,44 +394,59 @@ __global__ __launch_bounds__(kTopkThreads) void topk_resolve_kernel(TopkArgs a) 
         if (need > 0)     // need == remaining: everything left on the prefix is selected
             for_candidates(level, [&](uint32_t, int32_t pos) { staged[atomicAdd(&s_count, 1u)] = pos; });
         __syncthreads();
-        SK_STAMP(2);
+    }
+    SK_STAMP(2);
 
-        // ---- ascending emit through an LDS bitmap, kBitmapTokens tokens per pass
+    if (k_eff > 0) {
+        // ---- ascending emit: a bitmap of the selected positions in LDS, the running count of
+        //      set bits before every bitmap word, then each selected position looks up its own
+        //      rank (count before its word + set bits below it inside the word).
+        uint32_t *before = h + padded_size<kBitmapWords, BPER>();       // [kBitmapWords], padded
+        auto mark = [&](int32_t p) {
+            if (p >= 0 && p < kBitmapTokens) atomicOr(&h[padded<BPER>(p >> 5)], 1u << (p & 31));
+        };
         uint32_t written = 0;
+        // every selected position, wherever it is kept, goes through f once
+        auto for_selected = [&](auto f) {
+#pragma unroll
+            for (int j = 0; j < PRE; ++j)         // slots filled by the sweep: already in registers
+                if (tid + j * kTopkThreads < above) f(ps[j]);
+            for (uint32_t i = tid + PRE * kTopkThreads; i < above; i += kTopkThreads) f(staged[i]);
+            if (short_list) {
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    if (keep[j]) f(pp[j]);
+            } else {
+                for (uint32_t i = above + tid; i < k_eff; i += kTopkThreads) f(staged[i]);
+            }
+        };
         for (int base = 0; base < seq; base += kBitmapTokens) {
-            for (int i = tid; i < kBitmapWords; i += kTopkThreads) h[i] = 0;
+            for (int i = tid; i < padded_size<kBitmapWords, BPER>(); i += kTopkThreads) h[i] = 0;
             __syncthreads();
-            SK_STAMP(5);
-#pragma unroll
-            for (int j = 0; j < PRE; ++j) {       // slots filled by the sweep: already in registers
-                const uint32_t i = tid + j * kTopkThreads;
-                const int32_t p = ps[j] - base;
-                if (i < above && p >= 0 && p < kBitmapTokens) atomicOr(&h[p >> 5], 1u << (p & 31));
-            }
-            for (uint32_t i = tid; i < k_eff; i += kTopkThreads) {
-                if (i < above && i < (uint32_t)(PRE * kTopkThreads)) continue;
-                const int32_t p = staged[i] - base;
-                if (p >= 0 && p < kBitmapTokens) atomicOr(&h[p >> 5], 1u << (p & 31));
-            }
+            for_selected([&](int32_t p) { mark(p - base); });
             __syncthreads();
-            SK_STAMP(6);
-            constexpr int PER = kBitmapWords / kTopkThreads;
-            uint32_t c = 0;
+            uint32_t c[BPER];
+            uint32_t mine = 0;
 #pragma unroll
-            for (int i = 0; i < PER; ++i) c += __popc(h[tid * PER + i]);
+            for (int i = 0; i < BPER; ++i) {
+                c[i] = __popc(h[padded<BPER>(tid * BPER + i)]);
+                mine += c[i];
+            }
             uint32_t total;
-            uint32_t at = written + block_excl_scan(c, &total, tmp);
-            SK_STAMP(7);
-            for (int i = 0; i < PER; ++i) {
-                uint32_t w = h[tid * PER + i];
-                while (w) {
-                    int bit = __ffs(w) - 1;
-                    w &= w - 1;
-                    if (at < (uint32_t)a.max_k) out[at] = base + (tid * PER + i) * 32 + bit;
-                    ++at;
-                }
+            uint32_t run = block_excl_scan(mine, &total, tmp);
+#pragma unroll
+            for (int i = 0; i < BPER; ++i) {
+                before[padded<BPER>(tid * BPER + i)] = run;
+                run += c[i];
             }
-            SK_STAMP(8);
+            __syncthreads();
+            for_selected([&](int32_t p) {
+                const int32_t q = p - base;
+                if (q < 0 || q >= kBitmapTokens) return;
+                const int wi = padded<BPER>(q >> 5);
+                const uint32_t rank = written + before[wi] + __popc(h[wi] & ((1u << (q & 31)) - 1u));
+                if (rank < (uint32_t)a.max_k) out[rank] = p;
+            });
             written += total;
             __syncthreads();
         }
@@ -455,14 +477,23 @@ int launch_topk(socket_ctx *ctx, const float *scores, const int32_t *seq_len, co
     const Geometry &g = ctx->g;
     TopkArgs a;
     a.scores = scores; a.seq_len = seq_len; a.k = k; a.idx = idx; a.n_selected = n_selected;
-    a.hist = ctx->hist; a.hist2 = ctx->hist + (int64_t)g.max_batch * g.Hkv * kHistBins; a.counters = ctx->counters; a.cand_key = ctx->cand_key; a.cand_idx = ctx->cand_idx; a.staged = ctx->staged;
+    const int64_t BHmax = (int64_t)g.max_batch * g.Hkv;
+    a.hist = ctx->hist; a.hist2 = ctx->hist + BHmax * kHistBins; a.thr = ctx->counters + BHmax * kCounterStride;
+    a.counters = ctx->counters; a.cand_key = ctx->cand_key; a.cand_idx = ctx->cand_idx; a.staged = ctx->staged;
     a.Hkv = g.Hkv; a.max_n = g.max_n; a.max_k = g.max_k;
     const int BH = batch * g.Hkv;
     dim3 grid((g.max_n + kSlice - 1) / kSlice, BH);
     if (!have_hist) hipLaunchKernelGGL(topk_hist_kernel, grid, dim3(kTopkThreads), 0, st, a);
     hipLaunchKernelGGL(topk_hist2_kernel, grid, dim3(kTopkThreads), 0, st, a);
     hipLaunchKernelGGL(topk_filter_kernel, grid, dim3(kTopkThreads), 0, st, a);
-    hipLaunchKernelGGL(topk_resolve_kernel, dim3(BH), dim3(kTopkThreads), kBitmapWords * 4, st, a);
+    constexpr size_t kResolveLds = 2 * (size_t)padded_size<kBitmapWords, kBitmapWords / kTopkThreads>() * 4;
+    static bool lds_raised = false;   // 68 KB of dynamic LDS has to be allowed once per process
+    if (!lds_raised) {
+        if (hipFuncSetAttribute((const void *)topk_resolve_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)kResolveLds) != hipSuccess) return SOCKET_EHIP;
+        lds_raised = true;
+    }
+    hipLaunchKernelGGL(topk_resolve_kernel, dim3(BH), dim3(kTopkThreads), kResolveLds, st, a);
     return record_hip(ctx, hipGetLastError());
 }
 
