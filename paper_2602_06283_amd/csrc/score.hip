@@ -11,15 +11,28 @@
 //                     16 ids with one 16-byte load.  The rotated id order (see socket.h)
 //                     makes the 64 lanes of a pass hit 64 different tables, and the table is
 //                     stored [bucket][table], so the LDS gathers are free of bank conflicts.
+#include <cmath>
+
 #include "socket_internal.h"
 
 namespace sk {
+
+#ifdef SK_DEBUG_CLOCKS
+__device__ long long sk_dbg2[64];
+#define SK_STAMP2(i) do { if (threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.y == 0) { sk_dbg2[i] = wall_clock64(); sk_dbg2[32 + i] = clock64(); } } while (0)
+extern "C" int socket_debug_clocks2(long long *out) {
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(sk_dbg2), sizeof(long long) * 64);
+}
+#else
+#define SK_STAMP2(i) ((void)0)
+#endif
 
 struct ProjectArgs {
     const void *q;          // [B, Hq, d]; null = no soft hash
     const void *W;          // [Hkv, d, L*P]
     float *tables;
     double tau;
+    double x_scale;         // 2 / (sqrt(d) * tau)
     const void *K;          // key cache; null = no append hash
     void *codes;
     const int32_t *pos;     // [B] position of the appended key (append hash only)
@@ -34,77 +47,66 @@ template <typename T> __device__ __forceinline__ float elem_to_f32(T v);
 template <> __device__ __forceinline__ float elem_to_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ float elem_to_f32<uint16_t>(uint16_t v) { return bf16_to_f32(v); }
 
-// One workgroup projects onto the hyperplanes of `tpw` consecutive tables of one KV head:
-//   - the G queries of the head's group, in fp64, giving those tables' bucket probabilities
+// 1/x for x in [1, 2]: hardware estimate plus two Newton steps (relative error < 1e-15)
+__device__ __forceinline__ double rcp64(double x) {
+    double r = __builtin_amdgcn_rcp(x);
+    r = fma(r, fma(-x, r, 1.0), r);
+    r = fma(r, fma(-x, r, 1.0), r);
+    return r;
+}
+
+__device__ __forceinline__ double shfl_xor_f64(double v, int mask) {
+    int lo = __double2loint(v), hi = __double2hiint(v);
+    lo = __shfl_xor(lo, mask);
+    hi = __shfl_xor(hi, mask);
+    return __hiloint2double(hi, lo);
+}
+
+// One workgroup projects onto the P hyperplanes of ONE table of one KV head:
+//   - the G queries of the head's group, in fp64, giving that table's bucket probabilities
 //     (Alg. 2; the softmax over corners is evaluated as a product of per-plane sigmoids);
-//   - optionally the key appended at position pos[b], in fp32 FMA, giving its bucket ids for
-//     those tables (Alg. 1 on one row).
-// The slab of W it needs is staged in LDS with all loads of a thread in flight at once.
+//   - optionally the key appended at position pos[b], in fp32 FMA, giving its bucket id for
+//     that table (Alg. 1 on one row).
+// The kernel is a chain of short dependent phases, so each phase is spread over as many
+// threads as it has independent work: every dot product is cut into TPP channel ranges that
+// adjacent lanes sum with shuffles.
 template <typename T>
 __global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
     extern __shared__ double sm64[];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int h = blockIdx.y, b = blockIdx.z;
-    const int t0 = blockIdx.x * a.tpw;                       // first table of this workgroup
-    const int cols = a.tpw * a.P;                            // <= 64
-    const int col0 = t0 * a.P;
-    const int ncols = max(0, min(cols, a.LP - col0));        // live columns
+    const int tid = threadIdx.x;
+    const int l = blockIdx.x, h = blockIdx.y, b = blockIdx.z;   // table, KV head, sequence
+    const int cols = a.P;
+    const int col0 = l * a.P;
+    const bool live = l < a.L;                               // tables >= L are padding: zero rows
     const bool soft = a.q != nullptr, app = a.K != nullptr;
 
     double *qd = sm64;                                       // [G][d]
-    double *sp = qd + a.G * a.d;                             // [G][tpw][P] sigmoid(+2u/tau)
-    double *sn = sp + a.G * a.tpw * a.P;                     // [G][tpw][P] sigmoid(-2u/tau)
-    double *half = sn + a.G * a.tpw * a.P;                   // [G][tpw][Rlo+Rhi] (direct mode)
-    const int nhalf = a.mode == kDirect ? a.G * a.tpw * (a.Rlo + a.Rhi) : 0;
+    double *sp = qd + a.G * a.d;                             // [G][P] sigmoid(+2u/tau)
+    double *sn = sp + a.G * a.P;                             // [G][P] sigmoid(-2u/tau)
+    double *half = sn + a.G * a.P;                           // [G][Rlo+Rhi] (direct mode)
+    const int hrows = a.Rlo + a.Rhi;
+    const int nhalf = a.mode == kDirect ? a.G * hrows : 0;
     float *kf = (float *)(half + nhalf);                     // [d]
-    uint32_t *bits = (uint32_t *)(kf + a.d);                 // [2]
-    T *w = (T *)(bits + 4);                                  // [d][cols], 16-byte aligned
+    uint32_t *sgn = (uint32_t *)(kf + a.d);                  // [16] sign bits of the key's projections
+    T *w = (T *)(sgn + 16);                                  // [d][P]
+    SK_STAMP2(0);
 
-    // ---- W slab -> LDS
-    const T *Wg = (const T *)a.W + (int64_t)h * a.d * a.LP + col0;
-    constexpr int ES = sizeof(T), EPD = 4 / ES;              // elements per dword
-    const bool wide = (col0 % EPD == 0) && (a.LP % EPD == 0) && (ncols % EPD == 0) && (cols % EPD == 0);
-    constexpr int NB = 16;                                   // loads in flight per thread
-    if (wide) {
-        const int dpr = ncols / EPD, total = a.d * dpr;
-        for (int i0 = tid; i0 < total; i0 += NB * 256) {
-            uint32_t v[NB];
-#pragma unroll
-            for (int j = 0; j < NB; ++j) {
-                const int i = i0 + j * 256;
-                if (i < total) {
-                    const int c = i / dpr, x = i - c * dpr;
-                    v[j] = *(const uint32_t *)(Wg + (int64_t)c * a.LP + x * EPD);
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < NB; ++j) {
-                const int i = i0 + j * 256;
-                if (i < total) {
-                    const int c = i / dpr, x = i - c * dpr;
-                    *(uint32_t *)(w + c * cols + x * EPD) = v[j];
-                }
-            }
-        }
-    } else {
-        const int total = a.d * ncols;
+    // ---- the table's slab of W, the queries and the key row -> LDS, all loads in flight at once
+    constexpr int NB = 8;
+    if (live) {
+        const T *Wg = (const T *)a.W + (int64_t)h * a.d * a.LP + col0;
+        const int total = a.d * cols;
         for (int i0 = tid; i0 < total; i0 += NB * 256) {
             T v[NB];
 #pragma unroll
             for (int j = 0; j < NB; ++j) {
                 const int i = i0 + j * 256;
-                if (i < total) {
-                    const int c = i / ncols, x = i - c * ncols;
-                    v[j] = Wg[(int64_t)c * a.LP + x];
-                }
+                if (i < total) v[j] = Wg[(int64_t)(i / cols) * a.LP + i % cols];
             }
 #pragma unroll
             for (int j = 0; j < NB; ++j) {
                 const int i = i0 + j * 256;
-                if (i < total) {
-                    const int c = i / ncols, x = i - c * ncols;
-                    w[c * cols + x] = v[j];
-                }
+                if (i < total) w[i] = v[j];
             }
         }
     }
@@ -122,135 +124,122 @@ __global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
         if (wanted && tok >= 0 && tok < a.map.max_n) krow = a.map.row(b, h, tok);
         for (int c = tid; c < a.d; c += 256)
             kf[c] = krow >= 0 ? elem_to_f32<T>(((const T *)a.K)[krow * a.d + c]) : 0.0f;
-        if (a.len_out && blockIdx.x == 0 && h == 0 && tid == 0) a.len_out[b] = tok + 1;
+        if (a.len_out && l == 0 && h == 0 && tid == 0) a.len_out[b] = tok + 1;
     }
+    if (tid < 16) sgn[tid] = 0;
     __syncthreads();
+    SK_STAMP2(1);
 
-    // ---- appended key: fp32 FMA; each of the 4 wavefronts sums a quarter of the channels,
-    //      wavefront 0 adds the four partial sums in order and takes the sign bits by ballot
-    float *kpart = (float *)(w + a.d * cols);                // [4][64]
-    if (app) {
+    // ---- appended key: 16 lanes per hyperplane, fp32 FMA over a 16th of the channels each
+    if (app && live) {
+        const int pl = tid >> 4, part = tid & 15;            // 16 planes x 16 parts = 256 threads
         float acc = 0.0f;
-        if (lane < ncols) {
-            const int q4 = a.d >> 2;
-            float a0 = 0.0f, a1 = 0.0f;
-            for (int c = wave * q4; c < (wave + 1) * q4; c += 2) {
-                a0 = fmaf(kf[c], elem_to_f32<T>(w[c * cols + lane]), a0);
-                a1 = fmaf(kf[c + 1], elem_to_f32<T>(w[(c + 1) * cols + lane]), a1);
-            }
-            acc = a0 + a1;
+        if (pl < cols) {
+            const int per = a.d >> 4;
+            for (int c = part * per; c < (part + 1) * per; ++c) acc = fmaf(kf[c], elem_to_f32<T>(w[c * cols + pl]), acc);
         }
-        kpart[wave * 64 + lane] = acc;
+#pragma unroll
+        for (int m = 8; m > 0; m >>= 1) acc += __shfl_xor(acc, m);
+        if (pl < cols && part == 0) sgn[pl] = acc >= 0.0f ? 1u : 0u;
     }
-    // ---- queries: fp64 projections, u = tanh(z)/sqrt(d), per-plane sigmoids of +-2u/tau
-    if (soft) {
-        const double inv_sqrt_d = 1.0 / sqrt((double)a.d);
-        for (int i = tid; i < a.G * cols; i += 256) {
-            int g = i / cols, j = i - g * cols;
-            double plus = 0.0, minus = 0.0;
-            if (j < ncols) {
-                double z0 = 0.0, z1 = 0.0, z2 = 0.0, z3 = 0.0;   // independent chains hide LDS latency
-                const double *qg = qd + g * a.d;
-#pragma unroll 4
-                for (int c = 0; c < a.d; c += 4) {
-                    z0 = fma((double)elem_to_f32<T>(w[c * cols + j]), qg[c], z0);
-                    z1 = fma((double)elem_to_f32<T>(w[(c + 1) * cols + j]), qg[c + 1], z1);
-                    z2 = fma((double)elem_to_f32<T>(w[(c + 2) * cols + j]), qg[c + 2], z2);
-                    z3 = fma((double)elem_to_f32<T>(w[(c + 3) * cols + j]), qg[c + 3], z3);
+    // ---- queries: fp64 dot products, TPP lanes each; then u = tanh(z)/sqrt(d) and the
+    //      per-plane sigmoids of +-2u/tau
+    if (soft && live) {
+        const int npairs = a.G * cols;                       // <= 128
+        int tpp = 1;
+        while (tpp * 2 * npairs <= 256 && tpp < 32 && (a.d / (tpp * 2)) >= 2) tpp *= 2;
+        const int pair = tid / tpp, part = tid % tpp;
+        double z = 0.0;
+        if (pair < npairs) {
+            const int g = pair / cols, j = pair - g * cols;
+            const int per = a.d / tpp;
+            const double *qg = qd + g * a.d + part * per;
+            const T *wj = w + (part * per) * cols + j;
+            double z0 = 0.0, z1 = 0.0;
+            for (int c0 = 0; c0 < per; c0 += 8) {            // 8 channels' LDS reads issued together
+                T wv[8];
+                double qv[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const bool in = c0 + e < per;
+                    wv[e] = in ? wj[(c0 + e) * cols] : (T)0;
+                    qv[e] = in ? qg[c0 + e] : 0.0;
                 }
-                const double z = (z0 + z1) + (z2 + z3);
-                const double x = 2.0 * tanh(z) * inv_sqrt_d / a.tau;
-                const double e = exp(-fabs(x));                 // in (0, 1]
-                const double big = 1.0 / (1.0 + e), small = e / (1.0 + e);
-                plus = x >= 0.0 ? big : small;
-                minus = x >= 0.0 ? small : big;
+#pragma unroll
+                for (int e = 0; e < 8; e += 2) {
+                    z0 = fma((double)elem_to_f32<T>(wv[e]), qv[e], z0);
+                    z1 = fma((double)elem_to_f32<T>(wv[e + 1]), qv[e + 1], z1);
+                }
             }
-            sp[g * cols + j] = plus;        // [g][tl][pl] with j = tl*P + pl
-            sn[g * cols + j] = minus;
+            z = z0 + z1;
+        }
+        for (int m = tpp >> 1; m > 0; m >>= 1) z += shfl_xor_f64(z, m);
+        if (pair < npairs && part == 0) {
+            // tanh|z| = (1 - t)/(1 + t) with t = exp(-2|z|); sigmoid(+-x) from e = exp(-|x|)
+            const double t = exp(-2.0 * fabs(z));
+            const double th = (1.0 - t) * rcp64(1.0 + t);
+            const double e = exp(-a.x_scale * th);           // x = 2 tanh|z| / (sqrt(d) tau) >= 0
+            const double big = rcp64(1.0 + e), small = e * big;
+            sp[pair] = z >= 0.0 ? big : small;                // [g][pl]
+            sn[pair] = z >= 0.0 ? small : big;
         }
     }
     __syncthreads();
-    if (app && wave == 0) {
-        const float z = ((kpart[lane] + kpart[64 + lane]) + kpart[128 + lane]) + kpart[192 + lane];
-        unsigned long long m = __ballot(lane < ncols && z >= 0.0f);
-        if (lane == 0) {
-            bits[0] = (uint32_t)m;
-            bits[1] = (uint32_t)(m >> 32);
-            bits[2] = 0;
-        }
-    }
-    if (app) __syncthreads();
+    SK_STAMP2(2);
 
-    if (app && krow >= 0 && tid < a.tpw) {
-        const int l = t0 + tid;
-        if (l < a.Lpad) {
-            const uint32_t code = l < a.L ? bit_field(bits, tid * a.P, a.P) : 0u;
-            const int64_t at = krow * a.Lpad + code_pos(l, tok, a.S);
-            if (a.cb == 1) ((uint8_t *)a.codes)[at] = (uint8_t)code;
-            else ((uint16_t *)a.codes)[at] = (uint16_t)code;
-        }
+    if (app && krow >= 0 && tid == 0 && l < a.Lpad) {
+        uint32_t code = 0;
+        if (live)
+            for (int pl = 0; pl < cols; ++pl) code |= sgn[pl] << pl;
+        const int64_t at = krow * a.Lpad + code_pos(l, tok, a.S);
+        if (a.cb == 1) ((uint8_t *)a.codes)[at] = (uint8_t)code;
+        else ((uint16_t *)a.codes)[at] = (uint16_t)code;
     }
     if (!soft) return;
+    SK_STAMP2(3);
 
     const int lw = a.Lpad < 64 ? a.Lpad : 64;        // distinct tables per 64-word row
     const int copies = 64 / lw;
-    const int hrows = a.Rlo + a.Rhi;
+    const int c64 = l >> 6, lp = l & 63;
     float *Tg = a.tables + ((int64_t)b * a.Hkv + h) * a.table_words;
     // products over the low and the high planes: p(r) = lo[r & (Rlo-1)] * hi[r >> Plo]
-    auto half_product = [&](int g, int tl, int row) -> double {
+    auto half_product = [&](int g, int row) -> double {
         double p = 1.0;
         if (row < a.Rlo) {
-            for (int pl = 0; pl < a.Plo; ++pl) {
-                int at = g * cols + tl * a.P + pl;
-                p *= ((row >> pl) & 1) ? sp[at] : sn[at];
-            }
+            for (int pl = 0; pl < a.Plo; ++pl) p *= ((row >> pl) & 1) ? sp[g * cols + pl] : sn[g * cols + pl];
         } else {
             const int rh = row - a.Rlo;
-            for (int pl = 0; pl < a.Phi; ++pl) {
-                int at = g * cols + tl * a.P + a.Plo + pl;
-                p *= ((rh >> pl) & 1) ? sp[at] : sn[at];
-            }
+            for (int pl = 0; pl < a.Phi; ++pl)
+                p *= ((rh >> pl) & 1) ? sp[g * cols + a.Plo + pl] : sn[g * cols + a.Plo + pl];
         }
         return p;
     };
     if (a.mode == kDirect) {
-        for (int i = tid; i < a.G * a.tpw * hrows; i += 256) {
-            int row = i % hrows, rest = i / hrows;
-            int tl = rest % a.tpw, g = rest / a.tpw;
-            half[i] = half_product(g, tl, row);               // [g][tl][row]
+        if (live) {
+            for (int i = tid; i < a.G * hrows; i += 256) half[i] = half_product(i / hrows, i % hrows);   // [g][row]
         }
         __syncthreads();
+        SK_STAMP2(4);
         const double inv_g = 1.0 / (double)a.G;
-        for (int i = tid; i < a.tpw * a.R; i += 256) {
-            int tl = i % a.tpw, r = i / a.tpw;
-            int l = t0 + tl;
-            if (l >= a.Lpad) continue;
+        for (int r = tid; r < a.R; r += 256) {
             double mean = 0.0;
-            if (l < a.L) {
-                for (int g = 0; g < a.G; ++g) {
-                    const double *hp = half + (g * a.tpw + tl) * hrows;
-                    mean += hp[r & (a.Rlo - 1)] * hp[a.Rlo + (r >> a.Plo)];
-                }
+            if (live) {
+                for (int g = 0; g < a.G; ++g) mean += half[g * hrows + (r & (a.Rlo - 1))] * half[g * hrows + a.Rlo + (r >> a.Plo)];
                 mean *= inv_g;
             }
-            int c = l >> 6, lp = l & 63;
-            for (int cp = 0; cp < copies; ++cp)
-                Tg[((int64_t)c * a.R + r) * 64 + lp + cp * lw] = (float)mean;
+            for (int cp = 0; cp < copies; ++cp) Tg[((int64_t)c64 * a.R + r) * 64 + lp + cp * lw] = (float)mean;
         }
+        SK_STAMP2(5);
     } else {
-        for (int i = tid; i < a.tpw * hrows * a.G; i += 256) {
-            int tl = i % a.tpw, rest = i / a.tpw;
-            int row = rest % hrows, g = rest / hrows;
-            int l = t0 + tl;
-            if (l >= a.Lpad) continue;
+        for (int i = tid; i < hrows * a.G; i += 256) {
+            int row = i % hrows, g = i / hrows;
             double p = 0.0;
-            if (l < a.L) {
-                p = half_product(g, tl, row);
+            if (live) {
+                p = half_product(g, row);
                 if (row < a.Rlo) p /= (double)a.G;    // the 1/G of the group mean rides on the low factor
             }
-            int c = l >> 6, lp = l & 63;
             for (int cp = 0; cp < copies; ++cp)
-                Tg[(((int64_t)g * a.rounds + c) * hrows + row) * 64 + lp + cp * lw] = (float)p;
+                Tg[(((int64_t)g * a.rounds + c64) * hrows + row) * 64 + lp + cp * lw] = (float)p;
         }
     }
 }
@@ -569,19 +558,19 @@ int launch_project(socket_ctx *ctx, const void *q, const void *proj, float tau, 
     const Geometry &g = ctx->g;
     ProjectArgs a;
     a.q = q; a.W = proj; a.tables = ctx->tables; a.tau = (double)tau;
+    a.x_scale = 2.0 / (sqrt((double)g.d) * (double)tau);
     a.K = K; a.codes = codes; a.pos = pos; a.count = count; a.len_out = len_out;
     a.map = RowMap{block_table, g.Hkv, g.max_n, g.page, g.max_blocks, g.num_blocks};
     a.d = g.d; a.G = g.G; a.Hkv = g.Hkv; a.Hq = g.Hq; a.L = g.L; a.P = g.P; a.LP = g.L * g.P;
     a.Lpad = g.Lpad; a.S = g.S; a.cb = g.cb; a.rounds = g.rounds; a.R = g.R; a.mode = g.mode;
     a.Plo = g.Plo; a.Phi = g.Phi; a.Rlo = g.Rlo; a.Rhi = g.Rhi; a.table_rows = g.table_rows;
     a.table_words = g.table_words;
-    a.tpw = g.P <= 8 ? 8 : 4;                                 // tpw * P <= 64 columns
-    const int cols = a.tpw * g.P;
-    const int nhalf = g.mode == kDirect ? g.G * a.tpw * (g.Rlo + g.Rhi) : 0;
+    a.tpw = 1;
+    const int nhalf = g.mode == kDirect ? g.G * (g.Rlo + g.Rhi) : 0;
     const int esize = g.kv_dtype == SOCKET_F32 ? 4 : 2;
-    size_t lds = (size_t)(g.G * g.d + 2 * g.G * cols + nhalf) * sizeof(double) + (size_t)g.d * 4 + 16 +
-                 (size_t)g.d * cols * esize + 4 * 64 * 4 + 16;
-    dim3 grid((g.Lpad + a.tpw - 1) / a.tpw, g.Hkv, batch);
+    size_t lds = (size_t)(g.G * g.d + 2 * g.G * g.P + nhalf) * sizeof(double) + (size_t)g.d * 4 + 64 +
+                 (size_t)g.d * g.P * esize;
+    dim3 grid(g.Lpad, g.Hkv, batch);
     if (g.kv_dtype == SOCKET_F32) {
         if (lds > 64 * 1024 && hipFuncSetAttribute((const void *)project_kernel<float>,
                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return SOCKET_EHIP;
