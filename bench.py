@@ -22,6 +22,8 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 
+MEASURED_SCORE_TRAFFIC = {("128k", 32): 73862 * 1024}   # bytes per score_kernel launch
+
 WORKLOADS = {
     # name: (n, k, seed)   -- BASELINE configs[2] and configs[1]
     "128k": (131072, 2048, 1002),
@@ -37,6 +39,9 @@ def main():
     ap.add_argument("--workload", default="128k", choices=sorted(WORKLOADS))
     ap.add_argument("--layers", type=int, default=32)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only", default="", choices=["", "score"],
+                    help="profiling aid: 'score' runs just the scoring kernel over all layers "
+                         "(plus a plain 256 MiB copy that calibrates rocprofv3's HBM byte counters)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -108,6 +113,25 @@ def main():
         hash_bytes = NL * Hkv * n * (d * 2 + Lpad)
         # the rows that decode steps will append get hashed inside the step
 
+        if args.only == "score":
+            ctx.soft_hash(layers[0][2], layers[0][3], tau, 1)
+
+            def score_all():
+                for (K, V, q, W, codes) in layers:
+                    ctx.score_keys(codes, n_t, 1, scores)
+            g = capture(score_all)
+            us = timed(g.launch, args.steps) * 1e3 / NL
+            src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device="cuda").normal_()
+            dst = torch.empty_like(src)
+            for _ in range(4):
+                dst.copy_(src)           # 256 MiB read + 256 MiB written: counter calibration
+            stream.synchronize()
+            print(json.dumps({"only": "score", "ctx": n, "layers": NL, "avg_launch_us": us,
+                              "algorithmic_bytes": Hkv * n * (Lpad + 4),
+                              "gbs": Hkv * n * (Lpad + 4) / (us * 1e-6) / 1e9,
+                              "calibration_copy_bytes_each_way": src.numel() * 4}))
+            return
+
         # ---------------- one decode step over all layers --------------------------------
         def step():
             for li, (K, V, q, W, codes) in enumerate(layers):
@@ -160,13 +184,9 @@ def main():
     score_gbs = score_bytes / (stage_us["score"] * 1e-6) / 1e9
     chain_bytes = Hkv * (cur_len * (Lpad + 8) + k * (4 * d + 8))
     chain_us = stage_us["score"] + stage_us["topk"] + stage_us["sparse_decode"]
-    traffic = None
-    prof = os.path.join(ROOT, "profiles", f"score_kernel_{args.workload}_traffic.json")
-    if os.path.exists(prof):
-        try:
-            traffic = json.load(open(prof)).get("hbm_bytes_per_launch")
-        except Exception:
-            traffic = None
+    # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by a plain copy of
+    # known size (profiles/score_kernel_128k.md); not measured for other workloads
+    traffic = MEASURED_SCORE_TRAFFIC.get((args.workload, NL))
 
     result = {
         "metric": "decode_steps_per_s",
