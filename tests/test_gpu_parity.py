@@ -538,3 +538,133 @@ def test_decode_step_equals_separate_calls_and_oracle(kv_dtype, L, P, G):
     res = tuple(f[key].cpu().numpy() for key in ("codes", "scores", "idx", "nsel")) + (f["out"].cpu().numpy(),)
     check_chain(layer, *res, atol=1e-4)
     ctx.close()
+
+
+# ------------------------------------------------------------------ paged K/V/ids (configs[3] layout)
+
+def paged_setup(seed, B, Hq, Hkv, n_cap, L, P, lens, k, page=16, kv_dtype=wl.BF16):
+    """Logical layer + its paged pools and a random block table with room for n_cap tokens."""
+    layer = small_layer(seed=seed, B=B, Hq=Hq, Hkv=Hkv, n=n_cap, L=L, P=P, k=k, kv_dtype=kv_dtype,
+                        seq_len=lens)
+    table, nblocks = wl.make_block_table(seed, np.full(B, n_cap), page)
+    full = np.full(B, n_cap, dtype=np.int32)
+    Kp = wl.to_paged(layer.K, full, table, nblocks, page)
+    Vp = wl.to_paged(layer.V, full, table, nblocks, page)
+    p = sk.make_params(layer.d, Hq, Hkv, L, P, sk.BF16 if kv_dtype == wl.BF16 else sk.F32, B, n_cap,
+                       int(np.max(k)), page, table.shape[1], nblocks)
+    return layer, table, nblocks, Kp, Vp, sk.Context(p)
+
+
+def paged_codes_to_logical(codes_p, table, n_cap, page):
+    """[blocks, Hkv, page, Lpad] -> [B, Hkv, n_cap, Lpad] following the block table."""
+    B = table.shape[0]
+    out = np.zeros((B, codes_p.shape[1], n_cap, codes_p.shape[3]), dtype=codes_p.dtype)
+    for b in range(B):
+        for i in range(n_cap // page):
+            out[b, :, i * page:(i + 1) * page] = codes_p[table[b, i]]
+    return out
+
+
+def test_paged_chain_with_appends_across_page_boundaries():
+    """Batched paged decode: prefill-hash ragged lengths, then several fused decode steps that
+    append one key per sequence (crossing 16-token pages), all checked against the oracle on
+    the logical layout."""
+    _need_gpu()
+    B, Hq, Hkv, L, P, page, steps = 3, 8, 2, 64, 8, 16, 5
+    n_cap = 1024
+    start = np.array([1000 - 3, 517, 30], dtype=np.int32)      # 997 -> crosses the 1008 page edge
+    kk = np.array([64, 48, 40], dtype=np.int32)
+    layer, table, nblocks, Kp, Vp, ctx = paged_setup(71, B, Hq, Hkv, n_cap, L, P, start + steps, kk, page)
+    Kd, Vd = hz.dev(Kp, layer.kv_dtype), hz.dev(Vp, layer.kv_dtype)
+    qd, Wd = hz.dev(layer.q, layer.kv_dtype), hz.dev(layer.W, layer.kv_dtype)
+    bt = hz.i32(table)
+    Lpad = hz.lpad_of(L)
+    codes = torch.zeros((nblocks, Hkv, page, Lpad), dtype=torch.uint8, device="cuda")
+    scores = torch.zeros((B, Hkv, n_cap), dtype=torch.float32, device="cuda")
+    idx = torch.zeros((B, Hkv, int(kk.max())), dtype=torch.int32, device="cuda")
+    nsel = torch.zeros((B, Hkv), dtype=torch.int32, device="cuda")
+    out = torch.zeros((B, Hq, layer.d), dtype=torch.float32, device="cuda")
+    ctx.hash_keys(Kd, Wd, hz.i32(np.zeros(B)), hz.i32(start), B, int(start.max()), codes, block_table=bt)
+    for s in range(steps):
+        ctx.decode_step(qd, Kd, Vd, codes, Wd, 0.5, hz.i32(start + s), hz.i32(kk), B, 1.0, scores, idx, nsel,
+                        out, block_table=bt)
+    torch.cuda.synchronize()
+    logical = paged_codes_to_logical(codes.cpu().numpy(), table, n_cap, page)
+    check_chain(layer, logical, scores.cpu().numpy(), idx.cpu().numpy(), nsel.cpu().numpy(),
+                out.cpu().numpy(), atol=1e-4)
+    # the separate calls agree with the fused step on paged storage too
+    scores2 = torch.zeros_like(scores); idx2 = torch.zeros_like(idx); nsel2 = torch.zeros_like(nsel)
+    out2 = torch.zeros_like(out)
+    ln = hz.i32(start + steps)
+    ctx.score(qd, codes, Wd, 0.5, ln, B, scores2, block_table=bt)
+    ctx.topk_select(scores2, ln, hz.i32(kk), B, idx2, nsel2)
+    ctx.sparse_decode(qd, Kd, Vd, idx2, nsel2, B, 1.0, out2, block_table=bt)
+    torch.cuda.synchronize()
+    assert torch.equal(scores, scores2) and torch.equal(idx, idx2) and torch.equal(out, out2)
+    ctx.close()
+
+
+def test_paged_absent_block_is_masked_not_faulted():
+    """A block-table entry outside the pool marks its tokens absent: they score -inf, are
+    never selected, and nothing out of bounds is touched."""
+    _need_gpu()
+    B, Hq, Hkv, L, P, page = 1, 4, 1, 32, 8, 16
+    n_cap = 256
+    lens = np.array([256], dtype=np.int32)
+    layer, table, nblocks, Kp, Vp, ctx = paged_setup(72, B, Hq, Hkv, n_cap, L, P, lens, np.array([32]), page)
+    table = table.copy()
+    table[0, 5] = -1                 # tokens 80..95 have no block
+    table[0, 9] = nblocks + 7        # tokens 144..159 point outside the pool
+    Kd, Vd = hz.dev(Kp, layer.kv_dtype), hz.dev(Vp, layer.kv_dtype)
+    qd, Wd = hz.dev(layer.q, layer.kv_dtype), hz.dev(layer.W, layer.kv_dtype)
+    bt = hz.i32(table)
+    codes = torch.zeros((nblocks, Hkv, page, hz.lpad_of(L)), dtype=torch.uint8, device="cuda")
+    scores = torch.zeros((B, Hkv, n_cap), dtype=torch.float32, device="cuda")
+    idx = torch.zeros((B, Hkv, 32), dtype=torch.int32, device="cuda")
+    nsel = torch.zeros((B, Hkv), dtype=torch.int32, device="cuda")
+    out = torch.zeros((B, Hq, layer.d), dtype=torch.float32, device="cuda")
+    ctx.hash_keys(Kd, Wd, hz.i32([0]), hz.i32(lens), B, 256, codes, block_table=bt)
+    ctx.score(qd, codes, Wd, 0.5, hz.i32(lens), B, scores, block_table=bt)
+    ctx.topk_select(scores, hz.i32(lens), hz.i32([32]), B, idx, nsel)
+    ctx.sparse_decode(qd, Kd, Vd, idx, nsel, B, 1.0, out, block_table=bt)
+    torch.cuda.synchronize()
+    s = scores.cpu().numpy()[0, 0]
+    assert np.isneginf(s[80:96]).all() and np.isneginf(s[144:160]).all()
+    assert np.isfinite(np.delete(s, np.r_[80:96, 144:160])).all()
+    sel = idx.cpu().numpy()[0, 0]
+    assert not (set(sel.tolist()) & set(range(80, 96)) | set(sel.tolist()) & set(range(144, 160)))
+    assert np.isfinite(out.cpu().numpy()).all()
+    ctx.close()
+
+
+# ------------------------------------------------------------------ the (L, P) sweep of configs[4]
+
+@pytest.mark.parametrize("L", [16, 32, 64, 128])
+@pytest.mark.parametrize("P", [4, 8, 10])
+def test_sweep_hash_then_score(L, P):
+    """configs[4] grid at reduced n: prefill hash (MFMA), append-hash one row, score; ids
+    bit-exact and scores within 1e-5 of the oracle run on the GPU's ids."""
+    _need_gpu()
+    n = 2048
+    layer = small_layer(seed=81, B=2, Hq=8, Hkv=2, n=n, L=L, P=P, k=64, seq_len=[n, n - 100])
+    ctx = hz.make_ctx(layer)
+    Kd, Wd, qd = (hz.dev(x, layer.kv_dtype) for x in (layer.K, layer.W, layer.q))
+    codes = torch.zeros((2, 2, n, hz.lpad_of(L)), dtype=hz.torch_code_dtype(P), device="cuda")
+    scores = torch.zeros((2, 2, n), dtype=torch.float32, device="cuda")
+    ctx.hash_keys(Kd, Wd, hz.i32([0, 0]), hz.i32([n - 1, n - 101]), 2, n, codes)     # prefill
+    ctx.hash_keys(Kd, Wd, hz.i32([n - 1, n - 101]), hz.i32([1, 1]), 2, 1, codes)     # append
+    ctx.score(qd, codes, Wd, 0.5, hz.i32(layer.seq_len), 2, scores)
+    torch.cuda.synchronize()
+    raw = codes.cpu().numpy().view(hz.code_dtype(P))
+    got_s = scores.cpu().numpy()
+    for b in range(2):
+        ln = int(layer.seq_len[b])
+        for h in range(2):
+            want, near = hz.oracle_codes(layer, b, h, rows=slice(0, ln))
+            got = hz.codes_to_natural(raw[b, h, :ln], L)
+            assert not ((got != want) & ~near).any()
+            want_s = hz.oracle_scores(layer, b, h, np.pad(got, ((0, n - ln), (0, 0))))
+            live = np.isfinite(want_s)
+            assert np.max(np.abs(got_s[b, h][live] - want_s[live]) / want_s[live]) <= 1e-5
+            assert np.isneginf(got_s[b, h][~live]).all()
+    ctx.close()
