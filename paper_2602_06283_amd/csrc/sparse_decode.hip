@@ -9,6 +9,16 @@
 
 namespace sk {
 
+#ifdef SK_DEBUG_CLOCKS
+__device__ long long sk_dbg3[64];
+#define SK_STAMP3(i) do { if (threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.y == 0) sk_dbg3[i] = wall_clock64(); } while (0)
+extern "C" int socket_debug_clocks3(long long *out) {
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(sk_dbg3), sizeof(long long) * 64);
+}
+#else
+#define SK_STAMP3(i) ((void)0)
+#endif
+
 struct DecodeArgs {
     const void *q;
     const void *K;
@@ -22,6 +32,39 @@ struct DecodeArgs {
     float scale;
     int Hq, max_k, n_split, out_dtype;
 };
+
+// ---- cross-lane sums without LDS traffic -------------------------------------------------
+template <int CTRL> __device__ __forceinline__ float dpp_f32(float v) {
+    return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+// sum over lanes differing in bit 4 (adjacent 16-lane rows) / bit 5 (wavefront halves)
+__device__ __forceinline__ float xor16_sum(float v) {
+    auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float xor32_sum(float v) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+// sum over the LPR adjacent lanes that share a row; every lane ends with the total
+template <int LPR> __device__ __forceinline__ float row_sum(float v) {
+    if (LPR >= 16) {
+        v += dpp_f32<0x128>(v);      // row_ror:8
+        v += dpp_f32<0x124>(v);      // row_ror:4
+    } else {
+        v += dpp_f32<0x141>(v);      // row_half_mirror: lane t <-> 7 - t inside each group of 8
+    }
+    v += dpp_f32<0x4E>(v);           // quad_perm [2,3,0,1]
+    v += dpp_f32<0xB1>(v);           // quad_perm [1,0,3,2]
+    if (LPR >= 32) v = xor16_sum(v);
+    return v;
+}
+// sum over the 64/LPR row slots of a wavefront (lanes with the same position inside a row)
+template <int LPR> __device__ __forceinline__ float slot_sum(float v) {
+    if (LPR <= 8) v += __shfl_xor(v, 8);
+    if (LPR <= 16) v = xor16_sum(v);
+    return xor32_sum(v);
+}
 
 template <typename T> struct Row8;     // 8 consecutive elements of a K/V row as floats
 template <> struct Row8<uint16_t> {
@@ -74,6 +117,7 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(DecodeArg
     const int r_end = min(a.max_k, r_begin + per);
     const int32_t *idx = a.idx + (int64_t)bh * a.max_k;
 
+    SK_STAMP3(0);
     float qf[G][8];
 #pragma unroll
     for (int g = 0; g < G; ++g) {
@@ -105,6 +149,7 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(DecodeArg
             s_row[tid] = row;
         }
         __syncthreads();
+        SK_STAMP3(1);
 
         // ---- gather this chunk's K and V rows together (one memory latency, not two)
         Row8<T> kr[NPASS], vr[NPASS];
@@ -123,6 +168,7 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(DecodeArg
         // ---- logits: scale * k.q for every query head of the group
 #pragma unroll
         for (int p = 0; p < NPASS; ++p) {
+            if (p == 0) SK_STAMP3(2);
             float kf[8];
             kr[p].get(kf);
 #pragma unroll
@@ -130,12 +176,12 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(DecodeArg
                 float dot = 0.0f;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) dot = fmaf(kf[e], qf[g][e], dot);
-#pragma unroll
-                for (int off = 1; off < LPR; off <<= 1) dot += __shfl_xor(dot, off);
+                dot = row_sum<LPR>(dot);
                 if (sub == 0) s_p[g][p * RPP + wave * RPW + rl] = rows[p] >= 0 ? dot * a.scale : ninf;
             }
         }
         __syncthreads();
+        SK_STAMP3(3);
 
         // ---- running softmax statistics, one wavefront per query head at a time
         for (int g = wave; g < G; g += NWAVE) {
@@ -158,6 +204,7 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(DecodeArg
             }
         }
         __syncthreads();
+        SK_STAMP3(4);
 
         // ---- weighted value rows
 #pragma unroll
@@ -180,14 +227,13 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(DecodeArg
         __syncthreads();
     }
 
+    SK_STAMP3(5);
     // ---- combine the row slots of a wavefront, then the wavefronts
 #pragma unroll
     for (int g = 0; g < G; ++g)
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            float v = acc[g][e];
-#pragma unroll
-            for (int off = LPR; off < 64; off <<= 1) v += __shfl_xor(v, off);
+            const float v = slot_sum<LPR>(acc[g][e]);
             if (rl == 0) s_red[wave][g][sub * 8 + e] = v;
         }
     __syncthreads();
@@ -203,6 +249,7 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(DecodeArg
         part[((int64_t)tid * a.n_split + split) * (D + 2) + 0] = s_m[tid];
         part[((int64_t)tid * a.n_split + split) * (D + 2) + 1] = s_l[tid];
     }
+    SK_STAMP3(6);
 }
 
 // Merge of the split-K partial results of one query head: out = sum_s w_s acc_s / sum_s w_s l_s
