@@ -39,9 +39,11 @@ def main():
     ap.add_argument("--workload", default="128k", choices=sorted(WORKLOADS))
     ap.add_argument("--layers", type=int, default=32)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--only", default="", choices=["", "score"],
-                    help="profiling aid: 'score' runs just the scoring kernel over all layers "
-                         "(plus a plain 256 MiB copy that calibrates rocprofv3's HBM byte counters)")
+    ap.add_argument("--only", default="", choices=["", "score", "step"],
+                    help="profiling aids: 'score' runs just the scoring kernel over all layers "
+                         "(plus a plain 256 MiB copy that calibrates rocprofv3's HBM byte counters); "
+                         "'step' runs the prefill and the timed fused steps and nothing else, so a "
+                         "kernel trace holds the step's own kernels only")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -154,6 +156,10 @@ def main():
         ms_per_step = wall_ms / args.steps
         ev_ms_per_step = a.elapsed_time(b) / args.steps
         assert int(nsel.min()) == k and int(length[0]) <= n_alloc
+        if args.only == "step":
+            print(json.dumps({"only": "step", "ctx": n, "layers": NL, "steps": args.steps,
+                              "ms_per_step": ms_per_step, "layer_step_us": ms_per_step * 1e3 / NL}))
+            return
 
         # ---------------- per-stage times: each stage alone, all layers back to back ------
         def stage_graph(body):

@@ -31,6 +31,7 @@ struct ProjectArgs {
     const void *q;          // [B, Hq, d]; null = no soft hash
     const void *W;          // [Hkv, d, L*P]
     float *tables;
+    float *tstats;          // [B*Hkv][Lpad]: mean squared deviation of each table's entries from 1/R
     double tau;
     double x_scale;         // 2 / (sqrt(d) * tau)
     const void *K;          // key cache; null = no append hash
@@ -39,13 +40,29 @@ struct ProjectArgs {
     const int32_t *count;   // optional [B]: append only where count[b] >= 1
     int32_t *len_out;       // optional [B]: pos[b] + 1
     RowMap map;
-    int d, G, Hkv, Hq, L, P, LP, Lpad, S, cb, rounds, R, mode, Plo, Phi, Rlo, Rhi, table_rows, tpw;
+    int d, G, Hkv, Hq, L, P, LP, Lpad, S, cb, rounds, R, mode, Plo, Phi, Rlo, Rhi, table_rows;
+    int cols_magic;         // ceil(2^16 / P): x / P == (x * cols_magic) >> 16 for x < 2^12
     int64_t table_words;
 };
 
 template <typename T> __device__ __forceinline__ float elem_to_f32(T v);
 template <> __device__ __forceinline__ float elem_to_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ float elem_to_f32<uint16_t>(uint16_t v) { return bf16_to_f32(v); }
+
+// the 16 / sizeof(T) elements of a 16-byte vector as floats
+template <typename T> __device__ __forceinline__ void vec_to_f32(const uint4 &v, float *f);
+template <> __device__ __forceinline__ void vec_to_f32<float>(const uint4 &v, float *f) {
+    f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y);
+    f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
+}
+template <> __device__ __forceinline__ void vec_to_f32<uint16_t>(const uint4 &v, float *f) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        f[2 * i] = __uint_as_float(w[i] << 16);
+        f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+}
 
 // 1/x for x in [1, 2]: hardware estimate plus two Newton steps (relative error < 1e-15)
 __device__ __forceinline__ double rcp64(double x) {
@@ -55,76 +72,151 @@ __device__ __forceinline__ double rcp64(double x) {
     return r;
 }
 
-__device__ __forceinline__ double shfl_xor_f64(double v, int mask) {
-    int lo = __double2loint(v), hi = __double2hiint(v);
-    lo = __shfl_xor(lo, mask);
-    hi = __shfl_xor(hi, mask);
+template <int CTRL> __device__ __forceinline__ double dpp_f64(double v) {
+    const int lo = __builtin_amdgcn_mov_dpp(__double2loint(v), CTRL, 0xF, 0xF, true);
+    const int hi = __builtin_amdgcn_mov_dpp(__double2hiint(v), CTRL, 0xF, 0xF, true);
     return __hiloint2double(hi, lo);
 }
+// sum over groups of n adjacent lanes, n = 1, 2, 4, 8 or 16 (uniform over the wavefront)
+__device__ __forceinline__ double group_sum_f64(double v, int n) {
+    if (n >= 16) {
+        v += dpp_f64<0x128>(v);      // row_ror:8
+        v += dpp_f64<0x124>(v);      // row_ror:4
+    } else if (n >= 8) {
+        v += dpp_f64<0x141>(v);      // row_half_mirror
+    }
+    if (n >= 4) v += dpp_f64<0x4E>(v);
+    if (n >= 2) v += dpp_f64<0xB1>(v);
+    return v;
+}
+
+constexpr int kPlanePad = 16;        // per-plane sigmoids are kept [g][16]; planes >= P hold 1
 
 // One workgroup projects onto the P hyperplanes of ONE table of one KV head:
 //   - the G queries of the head's group, in fp64, giving that table's bucket probabilities
 //     (Alg. 2; the softmax over corners is evaluated as a product of per-plane sigmoids);
 //   - optionally the key appended at position pos[b], in fp32 FMA, giving its bucket id for
 //     that table (Alg. 1 on one row).
-// The kernel is a chain of short dependent phases, so each phase is spread over as many
-// threads as it has independent work: every dot product is cut into TPP channel ranges that
-// adjacent lanes sum with shuffles.
-template <typename T>
+// The kernel is a chain of short dependent phases bounded by memory and LDS latency, so every
+// phase issues all of its independent loads before the first use, and every dot product is
+// cut into channel ranges that adjacent lanes sum with DPP moves.
+template <typename T, int G>
 __global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
     extern __shared__ double sm64[];
+    constexpr int EPV = 16 / (int)sizeof(T);                 // elements per 16-byte vector
     const int tid = threadIdx.x;
-    const int l = blockIdx.x, h = blockIdx.y, b = blockIdx.z;   // table, KV head, sequence
-    const int cols = a.P;
+    // Workgroups go to the 8 XCDs round-robin; the 8 tables whose columns of W share 128-byte
+    // lines are given to workgroups of one XCD, so each line is fetched into one L2 only.
+    const int x = blockIdx.x;
+    const int l = (x & 7) * (a.Lpad >> 3) + (x >> 3);        // table (Lpad is a multiple of 16)
+    const int h = blockIdx.y, b = blockIdx.z;                // KV head, sequence
+    const int cols = a.P, d = a.d;
     const int col0 = l * a.P;
     const bool live = l < a.L;                               // tables >= L are padding: zero rows
     const bool soft = a.q != nullptr, app = a.K != nullptr;
 
-    double *qd = sm64;                                       // [G][d]
-    double *sp = qd + a.G * a.d;                             // [G][P] sigmoid(+2u/tau)
-    double *sn = sp + a.G * a.P;                             // [G][P] sigmoid(-2u/tau)
-    double *half = sn + a.G * a.P;                           // [G][Rlo+Rhi] (direct mode)
-    const int hrows = a.Rlo + a.Rhi;
-    const int nhalf = a.mode == kDirect ? a.G * hrows : 0;
-    float *kf = (float *)(half + nhalf);                     // [d]
-    uint32_t *sgn = (uint32_t *)(kf + a.d);                  // [16] sign bits of the key's projections
-    T *w = (T *)(sgn + 16);                                  // [d][P]
+    // Plane j lives in slot j, except that the high planes of the factor form start at slot 8:
+    // any product over 8 consecutive slots then needs no bounds (an unused slot holds 1).
+    double *sig = sm64;                                      // [G][16 slots][2] sigmoid(-2u/tau), sigmoid(+2u/tau)
+    double *qd = sig + G * kPlanePad * 2;                    // [G][d]  queries
+    double *wd = qd + G * d;                                 // [P][d]  W slab, transposed
+    float *wf = (float *)(wd + cols * d);                    // [P][d]  the same in fp32 (key path)
+    float *kf = wf + cols * d;                               // [d]
+    uint32_t *sgn = (uint32_t *)(kf + d);                    // [16] sign bits of the key's projections
+    float *s_dev = (float *)(sgn + 16);                      // [4]
     SK_STAMP2(0);
 
-    // ---- the table's slab of W, the queries and the key row -> LDS, all loads in flight at once
-    constexpr int NB = 8;
-    if (live) {
-        const T *Wg = (const T *)a.W + (int64_t)h * a.d * a.LP + col0;
-        const int total = a.d * cols;
-        for (int i0 = tid; i0 < total; i0 += NB * 256) {
-            T v[NB];
-#pragma unroll
-            for (int j = 0; j < NB; ++j) {
-                const int i = i0 + j * 256;
-                if (i < total) v[j] = Wg[(int64_t)(i / cols) * a.LP + i % cols];
-            }
-#pragma unroll
-            for (int j = 0; j < NB; ++j) {
-                const int i = i0 + j * 256;
-                if (i < total) w[i] = v[j];
-            }
-        }
-    }
-    if (soft) {
-        for (int i = tid; i < a.G * a.d; i += 256) {
-            int g = i / a.d, c = i - g * a.d;
-            qd[i] = (double)elem_to_f32<T>(((const T *)a.q)[((int64_t)b * a.Hq + h * a.G + g) * a.d + c]);
-        }
-    }
+    // ---- every global load of the kernel is issued here, before the first one is used
     int tok = 0;
-    int64_t krow = -1;
+    bool wanted = false;
     if (app) {
         tok = a.pos[b];
-        const bool wanted = a.count == nullptr || a.count[b] >= 1;
+        wanted = a.count == nullptr || a.count[b] >= 1;
+    }
+    const T *Wg = (const T *)a.W + (int64_t)h * d * a.LP + col0;
+    const int row_bytes = cols * (int)sizeof(T);
+    const bool wvec = (row_bytes & 15) == 0 && ((a.LP * (int)sizeof(T)) & 15) == 0;
+    const int nvec = row_bytes >> 4;                         // 16-byte vectors per channel (vector path)
+    constexpr int WV = 4, WE = 16;
+    uint4 wv[WV];
+    T we[WE];
+    if (live && wvec) {
+#pragma unroll
+        for (int j = 0; j < WV; ++j) {
+            const int i = tid + j * 256;
+            if (i < d * nvec) wv[j] = *(const uint4 *)(Wg + (int64_t)(i / nvec) * a.LP + (i % nvec) * EPV);
+        }
+    } else if (live) {
+#pragma unroll
+        for (int j = 0; j < WE; ++j) {
+            const int i = tid + j * 256;
+            if (i < d * cols) we[j] = Wg[(int64_t)(i / cols) * a.LP + i % cols];
+        }
+    }
+    constexpr int QV = (G * 256 * (int)sizeof(T) / 16 + 255) / 256;   // d <= 256
+    uint4 qv[QV];
+    const int nq = G * d / EPV;
+    if (soft && live) {
+        const T *qg = (const T *)a.q + ((int64_t)b * a.Hq + h * G) * d;
+#pragma unroll
+        for (int j = 0; j < QV; ++j) {
+            const int i = tid + j * 256;
+            if (i < nq) qv[j] = *(const uint4 *)(qg + i * EPV);
+        }
+    }
+    int64_t krow = -1;
+    uint4 kv = make_uint4(0, 0, 0, 0);
+    if (app) {
         if (wanted && tok >= 0 && tok < a.map.max_n) krow = a.map.row(b, h, tok);
-        for (int c = tid; c < a.d; c += 256)
-            kf[c] = krow >= 0 ? elem_to_f32<T>(((const T *)a.K)[krow * a.d + c]) : 0.0f;
-        if (a.len_out && l == 0 && h == 0 && tid == 0) a.len_out[b] = tok + 1;
+        if (krow >= 0 && live && tid < d / EPV) kv = *(const uint4 *)((const T *)a.K + krow * d + tid * EPV);
+        if (a.len_out && x == 0 && h == 0 && tid == 0) a.len_out[b] = tok + 1;
+    }
+
+    // ---- into LDS as fp32 / fp64, W transposed to [plane][channel]
+    if (live && wvec) {
+#pragma unroll
+        for (int j = 0; j < WV; ++j) {
+            const int i = tid + j * 256;
+            if (i < d * nvec) {
+                float f[EPV];
+                vec_to_f32<T>(wv[j], f);
+                const int c = i / nvec, p0 = (i % nvec) * EPV;
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) {
+                    wf[(p0 + e) * d + c] = f[e];
+                    wd[(p0 + e) * d + c] = (double)f[e];
+                }
+            }
+        }
+    } else if (live) {
+#pragma unroll
+        for (int j = 0; j < WE; ++j) {
+            const int i = tid + j * 256;
+            if (i < d * cols) {
+                const float f = elem_to_f32<T>(we[j]);
+                wf[(i % cols) * d + i / cols] = f;
+                wd[(i % cols) * d + i / cols] = (double)f;
+            }
+        }
+    }
+    if (soft && live) {
+#pragma unroll
+        for (int j = 0; j < QV; ++j) {
+            const int i = tid + j * 256;
+            if (i < nq) {
+                float f[EPV];
+                vec_to_f32<T>(qv[j], f);
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) qd[i * EPV + e] = (double)f[e];
+            }
+        }
+        if (tid < G * kPlanePad * 2) sig[tid] = 1.0;
+    }
+    if (app && tid < d / EPV) {
+        float f[EPV];
+        vec_to_f32<T>(kv, f);
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) kf[tid * EPV + e] = f[e];
     }
     if (tid < 16) sgn[tid] = 0;
     __syncthreads();
@@ -133,114 +225,145 @@ __global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
     // ---- appended key: 16 lanes per hyperplane, fp32 FMA over a 16th of the channels each
     if (app && live) {
         const int pl = tid >> 4, part = tid & 15;            // 16 planes x 16 parts = 256 threads
+        const int per = d >> 4;                              // 4, 8 or 16 channels
         float acc = 0.0f;
         if (pl < cols) {
-            const int per = a.d >> 4;
-            for (int c = part * per; c < (part + 1) * per; ++c) acc = fmaf(kf[c], elem_to_f32<T>(w[c * cols + pl]), acc);
+            // lane `part` takes channel quads part, part+16, ...: the 16 lanes of a plane read
+            // 256 contiguous bytes at a time, free of bank conflicts
+            const float4 *k4 = (const float4 *)kf + part;
+            const float4 *w4 = (const float4 *)(wf + pl * d) + part;
+            for (int c = 0; c < per / 4; ++c) {
+                const float4 kk = k4[c * 16], ww = w4[c * 16];
+                acc = fmaf(kk.x, ww.x, acc);
+                acc = fmaf(kk.y, ww.y, acc);
+                acc = fmaf(kk.z, ww.z, acc);
+                acc = fmaf(kk.w, ww.w, acc);
+            }
         }
-#pragma unroll
-        for (int m = 8; m > 0; m >>= 1) acc += __shfl_xor(acc, m);
+        acc = row_sum<16>(acc);
         if (pl < cols && part == 0) sgn[pl] = acc >= 0.0f ? 1u : 0u;
     }
-    // ---- queries: fp64 dot products, TPP lanes each; then u = tanh(z)/sqrt(d) and the
+    SK_STAMP2(8);
+    // ---- queries: fp64 dot products, tpp lanes each; then u = tanh(z)/sqrt(d) and the
     //      per-plane sigmoids of +-2u/tau
     if (soft && live) {
-        const int npairs = a.G * cols;                       // <= 128
-        int tpp = 1;
-        while (tpp * 2 * npairs <= 256 && tpp < 32 && (a.d / (tpp * 2)) >= 2) tpp *= 2;
-        const int pair = tid / tpp, part = tid % tpp;
-        double z = 0.0;
-        if (pair < npairs) {
-            const int g = pair / cols, j = pair - g * cols;
-            const int per = a.d / tpp;
-            const double *qg = qd + g * a.d + part * per;
-            const T *wj = w + (part * per) * cols + j;
-            double z0 = 0.0, z1 = 0.0;
-            for (int c0 = 0; c0 < per; c0 += 8) {            // 8 channels' LDS reads issued together
-                T wv[8];
-                double qv[8];
+        const int npairs = G * cols;                         // <= 128
+        int lg = 0;                                          // log2 of the lanes per dot product,
+        while ((2 << lg) * npairs <= 256 && lg < 4 && (d >> (lg + 1)) >= 8) ++lg;   // >= 8 channels each
+        const int tpp = 1 << lg;
+        const int pair = tid >> lg, part = tid & (tpp - 1);
+        const bool mine = pair < npairs;
+        const int g = mine ? (pair * a.cols_magic) >> 16 : 0;   // pair / cols
+        const int j = mine ? pair - g * cols : 0;
+        const int per = d >> lg;                             // a multiple of 8
+        // lane `part` takes channel pairs part, part+tpp, ...: the lanes of a dot product read
+        // contiguous bytes, free of bank conflicts
+        const double2 *q2 = (const double2 *)(qd + g * d) + part;
+        const double2 *w2 = (const double2 *)(wd + j * d) + part;
+        double z0 = 0.0, z1 = 0.0;
+        for (int c0 = 0; c0 < per / 8; ++c0) {               // 8 channels' LDS reads issued together
+            double2 wv2[4], qv2[4];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const bool in = c0 + e < per;
-                    wv[e] = in ? wj[(c0 + e) * cols] : (T)0;
-                    qv[e] = in ? qg[c0 + e] : 0.0;
-                }
-#pragma unroll
-                for (int e = 0; e < 8; e += 2) {
-                    z0 = fma((double)elem_to_f32<T>(wv[e]), qv[e], z0);
-                    z1 = fma((double)elem_to_f32<T>(wv[e + 1]), qv[e + 1], z1);
-                }
+            for (int e = 0; e < 4; ++e) {
+                wv2[e] = w2[(4 * c0 + e) << lg];
+                qv2[e] = q2[(4 * c0 + e) << lg];
             }
-            z = z0 + z1;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                z0 = fma(wv2[e].x, qv2[e].x, z0);
+                z1 = fma(wv2[e].y, qv2[e].y, z1);
+            }
         }
-        for (int m = tpp >> 1; m > 0; m >>= 1) z += shfl_xor_f64(z, m);
-        if (pair < npairs && part == 0) {
+        SK_STAMP2(9);
+        const double z = group_sum_f64(z0 + z1, tpp);
+        SK_STAMP2(10);
+        if (mine && part == 0) {
             // tanh|z| = (1 - t)/(1 + t) with t = exp(-2|z|); sigmoid(+-x) from e = exp(-|x|)
             const double t = exp(-2.0 * fabs(z));
             const double th = (1.0 - t) * rcp64(1.0 + t);
             const double e = exp(-a.x_scale * th);           // x = 2 tanh|z| / (sqrt(d) tau) >= 0
             const double big = rcp64(1.0 + e), small = e * big;
-            sp[pair] = z >= 0.0 ? big : small;                // [g][pl]
-            sn[pair] = z >= 0.0 ? small : big;
+            const int slot = (a.mode == kFactor && j >= a.Plo) ? 8 + j - a.Plo : j;
+            sig[(g * kPlanePad + slot) * 2 + 1] = z >= 0.0 ? big : small;
+            sig[(g * kPlanePad + slot) * 2] = z >= 0.0 ? small : big;
         }
+        SK_STAMP2(11);
     }
     __syncthreads();
     SK_STAMP2(2);
 
-    if (app && krow >= 0 && tid == 0 && l < a.Lpad) {
+    // the appended key's bucket id for this table, written by one thread
+    auto write_code = [&]() {
         uint32_t code = 0;
-        if (live)
-            for (int pl = 0; pl < cols; ++pl) code |= sgn[pl] << pl;
+        if (live) {
+            uint4 sg[4];                             // all 16 sign words in one LDS round trip
+#pragma unroll
+            for (int i = 0; i < 4; ++i) sg[i] = ((const uint4 *)sgn)[i];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                code |= (sg[i].x << (4 * i)) | (sg[i].y << (4 * i + 1)) | (sg[i].z << (4 * i + 2)) | (sg[i].w << (4 * i + 3));
+        }
         const int64_t at = krow * a.Lpad + code_pos(l, tok, a.S);
         if (a.cb == 1) ((uint8_t *)a.codes)[at] = (uint8_t)code;
         else ((uint16_t *)a.codes)[at] = (uint16_t)code;
+    };
+    const bool code_due = app && krow >= 0;
+    if (!soft) {
+        if (code_due && tid == 0) write_code();
+        return;
     }
-    if (!soft) return;
     SK_STAMP2(3);
 
     const int lw = a.Lpad < 64 ? a.Lpad : 64;        // distinct tables per 64-word row
     const int copies = 64 / lw;
     const int c64 = l >> 6, lp = l & 63;
     float *Tg = a.tables + ((int64_t)b * a.Hkv + h) * a.table_words;
-    // products over the low and the high planes: p(r) = lo[r & (Rlo-1)] * hi[r >> Plo]
-    auto half_product = [&](int g, int row) -> double {
-        double p = 1.0;
-        if (row < a.Rlo) {
-            for (int pl = 0; pl < a.Plo; ++pl) p *= ((row >> pl) & 1) ? sp[g * cols + pl] : sn[g * cols + pl];
-        } else {
-            const int rh = row - a.Rlo;
-            for (int pl = 0; pl < a.Phi; ++pl)
-                p *= ((rh >> pl) & 1) ? sp[g * cols + a.Plo + pl] : sn[g * cols + a.Plo + pl];
-        }
-        return p;
+    // product over the 8 slots s0 .. s0+7 of the sigmoid picked by the bits of `bits` (bits of
+    // unused slots are 0 and pick a stored 1); the 8 LDS reads are independent
+    auto plane_product = [&](int g, int s0, int bits) -> double {
+        double f[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) f[i] = sig[(g * kPlanePad + s0 + i) * 2 + ((bits >> i) & 1)];
+        return ((f[0] * f[1]) * (f[2] * f[3])) * ((f[4] * f[5]) * (f[6] * f[7]));
     };
     if (a.mode == kDirect) {
-        if (live) {
-            for (int i = tid; i < a.G * hrows; i += 256) half[i] = half_product(i / hrows, i % hrows);   // [g][row]
-        }
-        __syncthreads();
-        SK_STAMP2(4);
-        const double inv_g = 1.0 / (double)a.G;
+        // p(r) over all P <= 8 planes, averaged over the G queries: one entry per thread
+        const double inv_g = 1.0 / (double)G, inv_r = 1.0 / (double)a.R;
+        float dev2 = 0.0f;
         for (int r = tid; r < a.R; r += 256) {
             double mean = 0.0;
             if (live) {
-                for (int g = 0; g < a.G; ++g) mean += half[g * hrows + (r & (a.Rlo - 1))] * half[g * hrows + a.Rlo + (r >> a.Plo)];
+#pragma unroll
+                for (int g = 0; g < G; ++g) mean += plane_product(g, 0, r);
                 mean *= inv_g;
+                const double dv = mean - inv_r;      // a table's entries sum to 1: their mean is 1/R
+                dev2 += (float)(dv * dv);
             }
             for (int cp = 0; cp < copies; ++cp) Tg[((int64_t)c64 * a.R + r) * 64 + lp + cp * lw] = (float)mean;
         }
+        // spread of this table's entries, from which the scoring pass sizes its histogram bins
+        dev2 = row_sum<64>(dev2);
+        if ((tid & 63) == 0) s_dev[tid >> 6] = dev2;
+        __syncthreads();
+        if (tid == 0)
+            a.tstats[((int64_t)b * a.Hkv + h) * a.Lpad + l] =
+                (float)((double)(s_dev[0] + s_dev[1] + s_dev[2] + s_dev[3]) * inv_r);
+        if (code_due && tid == 64) write_code();     // off the first wavefront's path
         SK_STAMP2(5);
     } else {
-        for (int i = tid; i < hrows * a.G; i += 256) {
-            int row = i % hrows, g = i / hrows;
+        // products over the low and the high planes: p(r) = lo[r & (Rlo-1)] * hi[r >> Plo]
+        const int hrows = a.Rlo + a.Rhi;
+        for (int i = tid; i < hrows * G; i += 256) {
+            const int row = i % hrows, g = i / hrows;
             double p = 0.0;
             if (live) {
-                p = half_product(g, row);
-                if (row < a.Rlo) p /= (double)a.G;    // the 1/G of the group mean rides on the low factor
+                p = row < a.Rlo ? plane_product(g, 0, row) / (double)G   // the 1/G of the group mean rides on the low factor
+                                : plane_product(g, 8, row - a.Rlo);
             }
             for (int cp = 0; cp < copies; ++cp)
                 Tg[(((int64_t)g * a.rounds + c64) * hrows + row) * 64 + lp + cp * lw] = (float)p;
         }
+        if (code_due && tid == 64) write_code();
     }
 }
 
@@ -252,9 +375,12 @@ struct ScoreArgs {
     const float *vnorm;
     const int32_t *seq_len;
     float *scores;
-    uint32_t *hist;          // optional [B*Hkv][kHistBins]: leading-digit histogram of the scores
+    uint32_t *hist;          // optional [B*Hkv][kHistBins]: first-level histogram of the scores
+    const float *tstats;     // [B*Hkv][Lpad] per-table spread (adaptive histogram only)
+    uint32_t *thr;           // [B*Hkv][kThrStride] threshold records: receives the binning
+    int hist_mode;           // HistMode of `hist`
     RowMap map;
-    int Lpad, rounds, R, G, Plo, Rlo, table_rows;
+    int L, Lpad, rounds, R, G, Plo, Rlo, table_rows;
     int64_t table_words;
 };
 
@@ -377,6 +503,8 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
     const int nround = (seq / CKEYS) / stride;
     const int left0 = nround * stride * CKEYS;       // first key of the leftover region
     const bool has_table = seq > 0;
+    const bool adaptive = a.hist_mode == kHistAdaptive;
+    float bin_lo = 0.0f, bin_inv = 0.0f;             // adaptive histogram bins, set once the table is in
 
     const int sub = lane % S, kk = lane / S;
     const int lw = a.Lpad < 64 ? a.Lpad : 64;
@@ -385,6 +513,9 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
     for (int s = 0; s < 16; ++s) woff[s] = 4u * (uint32_t)(sub + S * ((kk + s) & 15) + lw * (kk >> 4));
     const uint32_t tbase = (uint32_t)(size_t)(lds_float_t *)tbl;
     uint32_t *lhist = (uint32_t *)(tbl + a.table_words);
+    // (no static __shared__ in this kernel: the table has to sit at LDS address 0 for the
+    // fast address path)
+    float *s_bin = (float *)(lhist + kHistBins);     // [2], present with a histogram only
     const char *codes_bh = (const char *)a.codes + (bh * max_n * (int64_t)a.Lpad + sub * 16) * CB;
 
     // address of this lane's 16 ids of key `key`, round c; dead = the token's block is absent
@@ -415,7 +546,11 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
                 if (dd) v = ninf;
                 else if (vn) v *= vn[key];
                 out[key] = v;
-                if (a.hist && v > ninf) atomicAdd(&lhist[score_order_key(v) >> (32 - kHistBits)], 1u);
+                if (a.hist && v > ninf) {
+                    const uint32_t bin = adaptive ? score_bin(v, bin_lo, bin_inv)
+                                                  : score_order_key(v) >> (32 - kHistBits);
+                    atomicAdd(&lhist[bin], 1u);
+                }
             }
         }
     };
@@ -429,6 +564,11 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
     CodeVec<CB> setA[U], setB[U];
     bool deadA[U], deadB[U];
     if (PREFETCH && nround > 0) load_set(setA, deadA, chunk_base(0));
+    // Adaptive histogram: if the keys' bucket ids were uniform, a score would have mean L/R and
+    // variance sum_l var_l; bins are laid from four deviations below that mean upwards.
+    float var_part = 0.0f;
+    if (adaptive && wave == 0)
+        for (int l = lane; l < a.Lpad; l += 64) var_part += a.tstats[bh * a.Lpad + l];
     if (has_table) {            // bucket-probability table -> LDS
         const float4 *src = (const float4 *)(a.tables + bh * a.table_words);
         float4 *dst = (float4 *)tbl;
@@ -450,7 +590,24 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
         if (a.hist)
             for (int i = tid; i < kHistBins; i += kScoreThreads) lhist[i] = 0;
     }
+    if (adaptive && wave == 0) {
+        const float mu = (float)a.L / (float)a.R;
+        const float sigma = fmaxf(sqrtf(row_sum<64>(var_part)), fmaxf(mu * 1e-6f, 1e-30f));
+        const float lo = mu - 4.0f * sigma, inv = 1.0f / (4.0f * sigma);
+        if (lane == 0) {
+            s_bin[0] = lo;
+            s_bin[1] = inv;
+            if (blockIdx.x == 0) {       // the select's sweep bins with the very same pair
+                a.thr[bh * kThrStride + kThrBinLo] = __float_as_uint(lo);
+                a.thr[bh * kThrStride + kThrBinInv] = __float_as_uint(inv);
+            }
+        }
+    }
     __syncthreads();
+    if (adaptive) {
+        bin_lo = s_bin[0];
+        bin_inv = s_bin[1];
+    }
 
     // ---- whole chunks: branch-free, the next chunk's loads in flight during the look-ups
     auto full_chunks = [&](auto base0) {
@@ -568,7 +725,7 @@ int launch_project(socket_ctx *ctx, const void *q, const void *proj, float tau, 
                    int32_t *len_out, int batch, hipStream_t st) {
     const Geometry &g = ctx->g;
     ProjectArgs a;
-    a.q = q; a.W = proj; a.tables = ctx->tables; a.tau = (double)tau;
+    a.q = q; a.W = proj; a.tables = ctx->tables; a.tstats = ctx->tstats; a.tau = (double)tau;
     a.x_scale = 2.0 / (sqrt((double)g.d) * (double)tau);
     a.K = K; a.codes = codes; a.pos = pos; a.count = count; a.len_out = len_out;
     a.map = RowMap{block_table, g.Hkv, g.max_n, g.page, g.max_blocks, g.num_blocks};
@@ -576,21 +733,22 @@ int launch_project(socket_ctx *ctx, const void *q, const void *proj, float tau, 
     a.Lpad = g.Lpad; a.S = g.S; a.cb = g.cb; a.rounds = g.rounds; a.R = g.R; a.mode = g.mode;
     a.Plo = g.Plo; a.Phi = g.Phi; a.Rlo = g.Rlo; a.Rhi = g.Rhi; a.table_rows = g.table_rows;
     a.table_words = g.table_words;
-    a.tpw = 1;
-    const int nhalf = g.mode == kDirect ? g.G * (g.Rlo + g.Rhi) : 0;
-    const int esize = g.kv_dtype == SOCKET_F32 ? 4 : 2;
-    size_t lds = (size_t)(g.G * g.d + 2 * g.G * g.P + nhalf) * sizeof(double) + (size_t)g.d * 4 + 64 +
-                 (size_t)g.d * g.P * esize;
+    a.cols_magic = (65536 + g.P - 1) / g.P;
+    const size_t lds = (size_t)(2 * g.G * kPlanePad + g.G * g.d + g.P * g.d) * sizeof(double) +
+                       (size_t)(g.P * g.d + g.d) * 4 + 64 + 16;
     dim3 grid(g.Lpad, g.Hkv, batch);
-    if (g.kv_dtype == SOCKET_F32) {
-        if (lds > 64 * 1024 && hipFuncSetAttribute((const void *)project_kernel<float>,
-                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return SOCKET_EHIP;
-        hipLaunchKernelGGL(project_kernel<float>, grid, dim3(256), lds, st, a);
-    } else {
-        if (lds > 64 * 1024 && hipFuncSetAttribute((const void *)project_kernel<uint16_t>,
-                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return SOCKET_EHIP;
-        hipLaunchKernelGGL(project_kernel<uint16_t>, grid, dim3(256), lds, st, a);
+    typedef void (*project_fn_t)(ProjectArgs);
+    project_fn_t fn = nullptr;
+    const bool f32 = g.kv_dtype == SOCKET_F32;
+    switch (g.G) {
+        case 1: fn = f32 ? project_kernel<float, 1> : project_kernel<uint16_t, 1>; break;
+        case 2: fn = f32 ? project_kernel<float, 2> : project_kernel<uint16_t, 2>; break;
+        case 4: fn = f32 ? project_kernel<float, 4> : project_kernel<uint16_t, 4>; break;
+        case 8: fn = f32 ? project_kernel<float, 8> : project_kernel<uint16_t, 8>; break;
+        default: return SOCKET_EUNSUPPORTED;
     }
+    if (set_lds_limit((const void *)fn, lds) != SOCKET_OK) return SOCKET_EHIP;
+    hipLaunchKernelGGL(fn, grid, dim3(256), lds, st, a);
     return record_hip(ctx, hipGetLastError());
 }
 
@@ -601,9 +759,16 @@ int launch_soft_hash(socket_ctx *ctx, const void *q, const void *proj, float tau
 
 int launch_score_keys(socket_ctx *ctx, const void *codes, const float *vnorm,
                       const int32_t *block_table, const int32_t *seq_len, int batch, float *scores,
-                      bool with_hist, hipStream_t st) {
+                      bool want_hist, int *hist_mode, hipStream_t st) {
     const Geometry &g = ctx->g;
     ScoreArgs a;
+    // The adaptive bins are sized from the tables alone, so they need unweighted scores and
+    // the one-entry-per-bucket table form the spread was taken from.
+    const int mode = !want_hist ? kHistNone
+                     : (vnorm == nullptr && g.mode == kDirect) ? kHistAdaptive : kHistDigit;
+    if (hist_mode) *hist_mode = mode;
+    a.hist_mode = mode; a.tstats = ctx->tstats; a.L = g.L;
+    a.thr = ctx->counters + (int64_t)g.max_batch * g.Hkv * kCounterStride;
     a.codes = codes; a.tables = ctx->tables; a.vnorm = vnorm; a.seq_len = seq_len; a.scores = scores;
     a.map = RowMap{block_table, g.Hkv, g.max_n, g.page, g.max_blocks, g.num_blocks};
     a.Lpad = g.Lpad; a.rounds = g.rounds; a.R = g.R; a.G = g.G; a.Plo = g.Plo; a.Rlo = g.Rlo;
@@ -618,8 +783,8 @@ int launch_score_keys(socket_ctx *ctx, const void *codes, const float *vnorm,
     if (per_bh < 1) per_bh = 1;
     if (per_bh > nchunks) per_bh = nchunks;
     dim3 grid(per_bh, g.Hkv, batch);
-    a.hist = with_hist ? ctx->hist : nullptr;
-    size_t lds = (size_t)g.table_words * 4 + (a.hist ? kHistBins * 4 : 0);
+    a.hist = want_hist ? ctx->hist : nullptr;
+    size_t lds = (size_t)g.table_words * 4 + (a.hist ? kHistBins * 4 + 16 : 0);
     score_fn_t fn = pick_score(g);
     if (!fn) return SOCKET_EUNSUPPORTED;
     // more than 64 KB of dynamic LDS has to be allowed per kernel before the launch

@@ -111,14 +111,16 @@ int socket_create(socket_ctx **out, const socket_params *p) {
     }
     const int64_t BH = (int64_t)g.max_batch * g.Hkv;
     const int64_t sz_tables = BH * g.table_words * 4;
+    const int64_t sz_tstats = BH * g.Lpad * 4;
     const int64_t sz_hist = 2 * BH * kHistBins * 4;   // first- and second-digit histograms
     const int64_t sz_cnt = BH * (kCounterStride + kThrStride) * 4;
     const int64_t sz_cand = BH * g.max_n * 4;
     const int64_t sz_staged = BH * g.max_k * 4;
     const int64_t sz_seq = (int64_t)g.max_batch * 4;
     const int64_t sz_part = (int64_t)g.max_batch * g.Hq * g.n_split * (g.d + 2) * 4;
-    ctx->scratch_bytes = sz_tables + sz_hist + sz_cnt + 2 * sz_cand + sz_staged + sz_part + sz_seq;
+    ctx->scratch_bytes = sz_tables + sz_tstats + sz_hist + sz_cnt + 2 * sz_cand + sz_staged + sz_part + sz_seq;
     bool ok = hipMalloc((void **)&ctx->tables, sz_tables) == hipSuccess &&
+              hipMalloc((void **)&ctx->tstats, sz_tstats) == hipSuccess &&
               hipMalloc((void **)&ctx->hist, sz_hist) == hipSuccess &&
               hipMalloc((void **)&ctx->counters, sz_cnt) == hipSuccess &&
               hipMalloc((void **)&ctx->cand_key, sz_cand) == hipSuccess &&
@@ -129,6 +131,7 @@ int socket_create(socket_ctx **out, const socket_params *p) {
     // Histograms and counters must start at zero; the kernels that use them leave them
     // at zero again, so this is the only clear (and it is outside any graph capture).
     ok = ok && hipMemset(ctx->hist, 0, sz_hist) == hipSuccess &&
+         hipMemset(ctx->tstats, 0, sz_tstats) == hipSuccess &&
          hipMemset(ctx->counters, 0, sz_cnt) == hipSuccess &&
          hipDeviceSynchronize() == hipSuccess;
     if (!ok) {
@@ -142,7 +145,7 @@ int socket_create(socket_ctx **out, const socket_params *p) {
 
 int socket_destroy(socket_ctx *ctx) {
     if (!ctx) return SOCKET_EINVAL;
-    void *bufs[] = {ctx->tables, ctx->hist, ctx->counters, ctx->cand_key, ctx->cand_idx, ctx->staged, ctx->partials, ctx->seq_scratch};
+    void *bufs[] = {ctx->tables, ctx->tstats, ctx->hist, ctx->counters, ctx->cand_key, ctx->cand_idx, ctx->staged, ctx->partials, ctx->seq_scratch};
     for (void *b : bufs)
         if (b) (void)hipFree(b);
     delete ctx;
@@ -178,7 +181,7 @@ int socket_score(socket_ctx *ctx, const void *q, const void *codes, const void *
     if (!(tau > 0.0f) || !(tau < 3.0e38f)) return SOCKET_EINVAL;
     int rc = launch_soft_hash(ctx, q, proj, tau, batch, (hipStream_t)stream);
     if (rc != SOCKET_OK) return rc;
-    return launch_score_keys(ctx, codes, vnorm, block_table, seq_len, batch, scores, false, (hipStream_t)stream);
+    return launch_score_keys(ctx, codes, vnorm, block_table, seq_len, batch, scores, false, nullptr, (hipStream_t)stream);
 }
 
 int socket_soft_hash(socket_ctx *ctx, const void *q, const void *proj, float tau, int32_t batch,
@@ -194,7 +197,7 @@ int socket_score_keys(socket_ctx *ctx, const void *codes, const float *vnorm,
                       float *scores, void *stream) {
     if (!ctx || !codes || !seq_len || !scores) return SOCKET_EINVAL;
     if (!batch_ok(ctx, batch) || !paging_ok(ctx, block_table)) return SOCKET_EINVAL;
-    return launch_score_keys(ctx, codes, vnorm, block_table, seq_len, batch, scores, false, (hipStream_t)stream);
+    return launch_score_keys(ctx, codes, vnorm, block_table, seq_len, batch, scores, false, nullptr, (hipStream_t)stream);
 }
 
 int socket_topk_select(socket_ctx *ctx, const float *scores, const int32_t *seq_len,
@@ -202,7 +205,7 @@ int socket_topk_select(socket_ctx *ctx, const float *scores, const int32_t *seq_
                        void *stream) {
     if (!ctx || !scores || !seq_len || !k || !idx || !n_selected) return SOCKET_EINVAL;
     if (!batch_ok(ctx, batch)) return SOCKET_EINVAL;
-    return launch_topk(ctx, scores, seq_len, k, batch, idx, n_selected, false, (hipStream_t)stream);
+    return launch_topk(ctx, scores, seq_len, k, batch, idx, n_selected, sk::kHistNone, (hipStream_t)stream);
 }
 
 int socket_decode_step(socket_ctx *ctx, const void *q, const void *K, const void *V, void *codes,
@@ -222,10 +225,11 @@ int socket_decode_step(socket_ctx *ctx, const void *q, const void *K, const void
     int rc = launch_project(ctx, q, proj, tau, K, codes, block_table, pos, nullptr, len, batch, st);
     if (rc != SOCKET_OK) return rc;
     // 2. score every key; the leading-digit histogram of the scores comes out of the same pass
-    rc = launch_score_keys(ctx, codes, vnorm, block_table, len, batch, scores, true, st);
+    int hist_mode = sk::kHistNone;
+    rc = launch_score_keys(ctx, codes, vnorm, block_table, len, batch, scores, true, &hist_mode, st);
     if (rc != SOCKET_OK) return rc;
     // 3. select, 4. attend
-    rc = launch_topk(ctx, scores, len, k, batch, idx, n_selected, true, st);
+    rc = launch_topk(ctx, scores, len, k, batch, idx, n_selected, hist_mode, st);
     if (rc != SOCKET_OK) return rc;
     return launch_sparse_decode(ctx, q, K, V, idx, n_selected, block_table, batch, scale, out_dtype,
                                 out, st);

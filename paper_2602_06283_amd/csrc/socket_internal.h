@@ -23,7 +23,9 @@ constexpr int kScoreU = SK_SCORE_U;          // 16-byte loads a lane keeps in fl
 constexpr int kDecodeThreads = 256;
 constexpr int kDecodeChunk = 64;     // selected rows a decode workgroup handles per pass
 constexpr int kCounterStride = 16;   // uint32 counters per (sequence, KV head)
-constexpr int kThrStride = 8;        // uint32 words of the top-k threshold record per (sequence, KV head)
+constexpr int kThrStride = 16;       // uint32 words of the top-k threshold record per (sequence, KV head)
+constexpr int kThrBinLo = 8;         // words of the record that hold the adaptive binning (float bits): offset,
+constexpr int kThrBinInv = 9;        // and reciprocal width
 
 // How the L x R bucket probabilities of one KV head are laid out for the scoring kernel.
 //   direct : one entry per (table, bucket), already averaged over the G query heads:
@@ -32,6 +34,14 @@ constexpr int kThrStride = 8;        // uint32 words of the top-k threshold reco
 //            query head: F[g][c][Rlo + Rhi][64] floats (rows < Rlo are A, the rest B).
 // In both, word w of the 64 holds table l' = w % min(Lpad, 64); tables >= L hold 0.
 enum TableMode { kDirect = 0, kFactor = 1 };
+
+// What the context's first-level histogram holds when the top-k select starts.
+//   none     : nothing, the select histograms the scores itself
+//   digit    : counts per leading 11-bit digit of the order-preserving score key
+//   adaptive : counts per bin of score_bin() with the (offset, reciprocal width) pair stored in
+//              the threshold record; the bins are narrow where the scores are dense, so the
+//              threshold bin alone already isolates a short candidate list
+enum HistMode { kHistNone = 0, kHistDigit = 1, kHistAdaptive = 2 };
 
 struct Geometry {
     int d, Hq, Hkv, G, L, P, R;
@@ -56,6 +66,7 @@ struct socket_ctx {
     int last_hip_error;
     int64_t scratch_bytes;
     float *tables;        // [max_batch*Hkv][table_words]
+    float *tstats;        // [max_batch*Hkv][Lpad] spread of each table's bucket probabilities
     uint32_t *hist;       // [2][max_batch*Hkv][kHistBins]
     uint32_t *counters;   // [max_batch*Hkv][kCounterStride] counters, then [max_batch*Hkv][kThrStride] records
     uint32_t *cand_key;   // [max_batch*Hkv][max_n]
@@ -80,13 +91,14 @@ int launch_project(socket_ctx *ctx, const void *q, const void *proj, float tau, 
                    int32_t *len_out, int batch, hipStream_t st);
 int launch_soft_hash(socket_ctx *ctx, const void *q, const void *proj, float tau, int batch,
                      hipStream_t st);
-// with_hist: also accumulate the leading-digit histogram of the scores into the context
+// want_hist: also accumulate a first-level histogram of the scores into the context; returns
+// in *hist_mode which kind (HistMode) it left there
 int launch_score_keys(socket_ctx *ctx, const void *codes, const float *vnorm,
                       const int32_t *block_table, const int32_t *seq_len, int batch, float *scores,
-                      bool with_hist, hipStream_t st);
-// have_hist: the context's histogram already holds the leading digits of `scores`
+                      bool want_hist, int *hist_mode, hipStream_t st);
+// hist_mode: what the context's histogram already holds about `scores` (HistMode)
 int launch_topk(socket_ctx *ctx, const float *scores, const int32_t *seq_len, const int32_t *k,
-                int batch, int32_t *idx, int32_t *n_selected, bool have_hist, hipStream_t st);
+                int batch, int32_t *idx, int32_t *n_selected, int hist_mode, hipStream_t st);
 int launch_sparse_decode(socket_ctx *ctx, const void *q, const void *K, const void *V,
                          const int32_t *idx, const int32_t *n_selected, const int32_t *block_table,
                          int batch, float scale, int out_dtype, void *out, hipStream_t st);
@@ -102,6 +114,45 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
     if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);  // NaN stays NaN
     u += 0x7fffu + ((u >> 16) & 1u);
     return (uint16_t)(u >> 16);
+}
+
+// ---- cross-lane sums without LDS traffic
+template <int CTRL> __device__ __forceinline__ float dpp_f32(float v) {
+    return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+// sum over lanes differing in bit 4 (adjacent 16-lane rows) / bit 5 (wavefront halves)
+__device__ __forceinline__ float xor16_sum(float v) {
+    auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float xor32_sum(float v) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+// sum over the LPR adjacent lanes that share a row (LPR = 8, 16, 32 or 64); every lane ends
+// with the total
+template <int LPR> __device__ __forceinline__ float row_sum(float v) {
+    if (LPR >= 16) {
+        v += dpp_f32<0x128>(v);      // row_ror:8
+        v += dpp_f32<0x124>(v);      // row_ror:4
+    } else {
+        v += dpp_f32<0x141>(v);      // row_half_mirror: lane t <-> 7 - t inside each group of 8
+    }
+    v += dpp_f32<0x4E>(v);           // quad_perm [2,3,0,1]
+    v += dpp_f32<0xB1>(v);           // quad_perm [1,0,3,2]
+    if (LPR >= 32) v = xor16_sum(v);
+    if (LPR >= 64) v = xor32_sum(v);
+    return v;
+}
+
+// Adaptive first-level bin of a score: the leading bits of 1 + max(v - lo, 0) * inv read as a
+// float, i.e. 512 equal bins per octave of that quantity over four octaves, the last bin
+// taking everything beyond.  Non-decreasing in v for any (lo, inv), which is all the exact
+// select needs; how well the bins fit the scores only decides how short the candidate list is.
+__device__ __forceinline__ uint32_t score_bin(float v, float lo, float inv) {
+    const float y = fmaf(fmaxf(v - lo, 0.0f), inv, 1.0f);
+    const uint32_t bin = (__float_as_uint(y) - 0x3f800000u) >> 14;
+    return bin < (uint32_t)(kHistBins - 1) ? bin : (uint32_t)(kHistBins - 1);
 }
 
 // Table whose id is stored at position pos of token t's code row.

@@ -33,32 +33,6 @@ struct DecodeArgs {
     int Hq, max_k, n_split, out_dtype;
 };
 
-// ---- cross-lane sums without LDS traffic -------------------------------------------------
-template <int CTRL> __device__ __forceinline__ float dpp_f32(float v) {
-    return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), CTRL, 0xF, 0xF, true));
-}
-// sum over lanes differing in bit 4 (adjacent 16-lane rows) / bit 5 (wavefront halves)
-__device__ __forceinline__ float xor16_sum(float v) {
-    auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-__device__ __forceinline__ float xor32_sum(float v) {
-    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-// sum over the LPR adjacent lanes that share a row; every lane ends with the total
-template <int LPR> __device__ __forceinline__ float row_sum(float v) {
-    if (LPR >= 16) {
-        v += dpp_f32<0x128>(v);      // row_ror:8
-        v += dpp_f32<0x124>(v);      // row_ror:4
-    } else {
-        v += dpp_f32<0x141>(v);      // row_half_mirror: lane t <-> 7 - t inside each group of 8
-    }
-    v += dpp_f32<0x4E>(v);           // quad_perm [2,3,0,1]
-    v += dpp_f32<0xB1>(v);           // quad_perm [1,0,3,2]
-    if (LPR >= 32) v = xor16_sum(v);
-    return v;
-}
 // sum over the 64/LPR row slots of a wavefront (lanes with the same position inside a row)
 template <int LPR> __device__ __forceinline__ float slot_sum(float v) {
     if (LPR <= 8) v += __shfl_xor(v, 8);

@@ -12,6 +12,9 @@
 //                       remaining score bits and then on the token position (smaller position
 //                       wins a tie), and writes the selection in ascending position order
 //                       through an LDS bitmap.  Leaves histograms and counters at zero.
+// When the scoring pass has left an adaptive histogram (bins sized from the bucket-probability
+// tables, a few dozen scores in the threshold bin), topk_filter_kernel<true> finds the
+// threshold bin itself and sweeps with it, and the two histogram kernels are skipped.
 // Stages talk through global memory across kernel boundaries only: no workgroup waits on
 // another and no fence is needed.  LDS arrays that a thread walks in runs of PER consecutive
 // words carry one pad word per run, which makes those walks free of bank conflicts.
@@ -37,7 +40,8 @@ constexpr int kPer = 8;                          // scores per thread in a sweep
 constexpr int kSlice = kTopkThreads * kPer;      // scores per workgroup
 constexpr int kRankMax = 2 * kTopkThreads;       // candidates the all-pairs ranking handles
 // threshold record: [0] k_eff, [1] first digit, [2] scores above it, [3] scores in it,
-//                   [4] second digit, [5] scores selected outright, [6] candidates
+//                   [4] second digit, [5] scores selected outright, [6] candidates,
+//                   [kThrBinLo], [kThrBinInv] adaptive binning written by the scoring pass
 
 struct TopkArgs {
     const float *scores;
@@ -53,6 +57,7 @@ struct TopkArgs {
     int32_t *cand_idx;
     int32_t *staged;
     int Hkv, max_n, max_k;
+    int adaptive;         // candidates share an adaptive bin, not the two leading digits
 };
 
 // Order-preserving map from fp32 to uint32 (larger float -> larger key).
@@ -211,7 +216,10 @@ __global__ __launch_bounds__(kTopkThreads) void topk_hist2_kernel(TopkArgs a) {
         if (h2[j]) atomicAdd(&gh2[j], h2[j]);
 }
 
-// Second threshold digit, then the sweep.
+// Threshold, then the sweep.  ADAPT = false: the second threshold digit from the histogram of
+// topk_hist2_kernel, lead = the two leading digits of the score key.  ADAPT = true: the
+// threshold bin of the adaptive histogram, lead = that bin.
+template <bool ADAPT>
 __global__ __launch_bounds__(kTopkThreads) void topk_filter_kernel(TopkArgs a) {
     constexpr int PER = kHistBins / kTopkThreads;
     __shared__ uint32_t h[padded_size<kHistBins, PER>()];
@@ -224,26 +232,57 @@ __global__ __launch_bounds__(kTopkThreads) void topk_filter_kernel(TopkArgs a) {
     const int i = key0 + tid * kPer;
     float e[kPer];
     load_scores(a.scores + (int64_t)bh * a.max_n, i, a.max_n, e);
-    const uint32_t *gh2 = a.hist2 + (int64_t)bh * kHistBins;
+    const uint32_t *gh = (ADAPT ? a.hist : a.hist2) + (int64_t)bh * kHistBins;
     uint32_t c2[PER];
 #pragma unroll
-    for (int j = 0; j < PER; ++j) c2[j] = gh2[tid + j * kTopkThreads];
+    for (int j = 0; j < PER; ++j) c2[j] = gh[tid + j * kTopkThreads];
     uint32_t *thr = a.thr + (int64_t)bh * kThrStride;
-    const uint32_t k_eff = thr[0], tb1 = thr[1], above1 = thr[2];
     const int key1 = min(key0 + kSlice, clamp_len(a.seq_len[b], a.max_n));
-    if (k_eff == 0) return;
-    if (key0 >= key1 && blockIdx.x != 0) return;
+    uint32_t k_eff, pair, above, n_cand;
+    float bin_lo = 0.0f, bin_inv = 0.0f;
+    if (ADAPT) {
+        bin_lo = __uint_as_float(thr[kThrBinLo]);
+        bin_inv = __uint_as_float(thr[kThrBinInv]);
+        const uint32_t kreq = (uint32_t)clamp_len(a.k[b], a.max_k);
+        if (key0 >= key1 && blockIdx.x != 0) return;   // workgroup 0 always publishes the record
 #pragma unroll
-    for (int j = 0; j < PER; ++j) h[padded<PER>(tid + j * kTopkThreads)] = c2[j];
-    if (tid < 4) res[tid] = 0;
-    __syncthreads();
-    find_threshold<kHistBins>(h, k_eff - above1, res, tmp);    // 1 <= k_eff - above1 <= scores in tb1
-    const uint32_t tb2 = res[0], above = above1 + res[1], n_cand = res[2];
-    if (blockIdx.x == 0 && tid == 0) {
-        thr[4] = tb2; thr[5] = above; thr[6] = n_cand;
+        for (int j = 0; j < PER; ++j) h[padded<PER>(tid + j * kTopkThreads)] = c2[j];
+        if (tid < 4) res[tid] = 0;
+        __syncthreads();
+        // a target beyond the number of valid scores finds nothing; res[3] then gives that number
+        find_threshold<kHistBins>(h, kreq, res, tmp);
+        k_eff = kreq;
+        const uint32_t valid = res[3];
+        if (valid < kreq) {                             // fewer valid scores than asked for: take all
+            k_eff = valid;
+            if (valid > 0) {
+                __syncthreads();
+                find_threshold<kHistBins>(h, valid, res, tmp);
+            }
+        }
+        pair = res[0]; above = res[1]; n_cand = res[2];
+        if (blockIdx.x == 0 && tid == 0) {
+            thr[0] = k_eff; thr[5] = k_eff ? above : 0u; thr[6] = k_eff ? n_cand : 0u;
+        }
+        if (k_eff == 0) return;
+    } else {
+        k_eff = thr[0];
+        const uint32_t tb1 = thr[1], above1 = thr[2];
+        if (k_eff == 0) return;
+        if (key0 >= key1 && blockIdx.x != 0) return;
+#pragma unroll
+        for (int j = 0; j < PER; ++j) h[padded<PER>(tid + j * kTopkThreads)] = c2[j];
+        if (tid < 4) res[tid] = 0;
+        __syncthreads();
+        find_threshold<kHistBins>(h, k_eff - above1, res, tmp);    // 1 <= k_eff - above1 <= scores in tb1
+        const uint32_t tb2 = res[0];
+        above = above1 + res[1]; n_cand = res[2];
+        if (blockIdx.x == 0 && tid == 0) {
+            thr[4] = tb2; thr[5] = above; thr[6] = n_cand;
+        }
+        pair = (tb1 << kHistBits) | tb2;                           // the 2*kHistBits leading bits
     }
     if (key0 >= key1) return;
-    const uint32_t pair = (tb1 << kHistBits) | tb2;            // the 2*kHistBits leading bits
     uint32_t *cnt = a.counters + (int64_t)bh * kCounterStride;
     uint32_t *ckey = a.cand_key + (int64_t)bh * a.max_n;
     int32_t *cidx = a.cand_idx + (int64_t)bh * a.max_n;
@@ -257,7 +296,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_filter_kernel(TopkArgs a) {
     for (int j = 0; j < kPer; ++j) {
         const bool ok = i + j < key1 && selectable(e[j]);
         keys[j] = order_key(e[j]);
-        const uint32_t lead = keys[j] >> kDigit2Shift;
+        const uint32_t lead = ADAPT ? score_bin(e[j], bin_lo, bin_inv) : keys[j] >> kDigit2Shift;
         if (ok && lead > pair) flags |= 1u << j;
         if (ok && lead == pair) flags |= 1u << (16 + j);
     }
@@ -282,16 +321,19 @@ __global__ __launch_bounds__(kTopkThreads) void topk_filter_kernel(TopkArgs a) {
     }
 }
 
-// Refinement digits of a candidate below the two leading digits (long candidate lists only):
-//   level 0: the remaining low score bits
-//   level 1..3: bits 30..19, 18..7, 6..0 of (2^31-1 - position), so a smaller position ranks higher
-constexpr int kLevels = 4;
+// Refinement digits of a candidate (long candidate lists only):
+//   level 0..2: the first, the second and the remaining low digit of the score key (candidates
+//               that came through the two-digit threshold agree on levels 0 and 1)
+//   level 3..5: bits 30..19, 18..7, 6..0 of (2^31-1 - position), so a smaller position ranks higher
+constexpr int kLevels = 6;
 __device__ __forceinline__ uint32_t refine_digit(int level, uint32_t key, int32_t pos) {
     uint32_t inv = 0x7fffffffu - (uint32_t)pos;
     switch (level) {
-        case 0: return key & ((1u << kDigit2Shift) - 1u);
-        case 1: return (inv >> 19) & 0xfffu;
-        case 2: return (inv >> 7) & 0xfffu;
+        case 0: return key >> kLowBits;
+        case 1: return digit2(key);
+        case 2: return key & ((1u << kDigit2Shift) - 1u);
+        case 3: return (inv >> 19) & 0xfffu;
+        case 4: return (inv >> 7) & 0xfffu;
         default: return inv & 0x7fu;
     }
 }
@@ -367,9 +409,13 @@ __global__ __launch_bounds__(kTopkThreads) void topk_resolve_kernel(TopkArgs a) 
             }
         };
         uint32_t need = need0, remaining = n_cand;
-        if (tid == 0) s_count = above;            // next free staging slot
+        if (tid == 0) {
+            s_count = above;                      // next free staging slot
+            chosen[0] = thr[1];                   // the digits every two-digit candidate has
+            chosen[1] = thr[4];
+        }
         __syncthreads();
-        int level = 0;
+        int level = a.adaptive ? 0 : 2;
         while (need > 0 && need < remaining && level < kLevels) {
             for (int i = tid; i < padded_size<kRefineBins, RPER>(); i += kTopkThreads) h[i] = 0;
             if (tid < 4) res[tid] = 0;
@@ -473,19 +519,23 @@ extern "C" int socket_debug_clocks(long long *out) {
 #endif
 
 int launch_topk(socket_ctx *ctx, const float *scores, const int32_t *seq_len, const int32_t *k,
-                int batch, int32_t *idx, int32_t *n_selected, bool have_hist, hipStream_t st) {
+                int batch, int32_t *idx, int32_t *n_selected, int hist_mode, hipStream_t st) {
     const Geometry &g = ctx->g;
     TopkArgs a;
     a.scores = scores; a.seq_len = seq_len; a.k = k; a.idx = idx; a.n_selected = n_selected;
     const int64_t BHmax = (int64_t)g.max_batch * g.Hkv;
     a.hist = ctx->hist; a.hist2 = ctx->hist + BHmax * kHistBins; a.thr = ctx->counters + BHmax * kCounterStride;
     a.counters = ctx->counters; a.cand_key = ctx->cand_key; a.cand_idx = ctx->cand_idx; a.staged = ctx->staged;
-    a.Hkv = g.Hkv; a.max_n = g.max_n; a.max_k = g.max_k;
+    a.Hkv = g.Hkv; a.max_n = g.max_n; a.max_k = g.max_k; a.adaptive = hist_mode == kHistAdaptive;
     const int BH = batch * g.Hkv;
     dim3 grid((g.max_n + kSlice - 1) / kSlice, BH);
-    if (!have_hist) hipLaunchKernelGGL(topk_hist_kernel, grid, dim3(kTopkThreads), 0, st, a);
-    hipLaunchKernelGGL(topk_hist2_kernel, grid, dim3(kTopkThreads), 0, st, a);
-    hipLaunchKernelGGL(topk_filter_kernel, grid, dim3(kTopkThreads), 0, st, a);
+    if (hist_mode == kHistAdaptive) {
+        hipLaunchKernelGGL(topk_filter_kernel<true>, grid, dim3(kTopkThreads), 0, st, a);
+    } else {
+        if (hist_mode == kHistNone) hipLaunchKernelGGL(topk_hist_kernel, grid, dim3(kTopkThreads), 0, st, a);
+        hipLaunchKernelGGL(topk_hist2_kernel, grid, dim3(kTopkThreads), 0, st, a);
+        hipLaunchKernelGGL(topk_filter_kernel<false>, grid, dim3(kTopkThreads), 0, st, a);
+    }
     constexpr size_t kResolveLds = 2 * (size_t)padded_size<kBitmapWords, kBitmapWords / kTopkThreads>() * 4;
     static bool lds_raised = false;   // 68 KB of dynamic LDS has to be allowed once per process
     if (!lds_raised) {
