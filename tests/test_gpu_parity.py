@@ -540,6 +540,67 @@ def test_decode_step_equals_separate_calls_and_oracle(kv_dtype, L, P, G):
     ctx.close()
 
 
+@pytest.mark.parametrize("case", ["ties_cold", "ties_flat", "take_all", "k_one", "value_norms", "large"])
+def test_decode_step_select_paths_agree(case):
+    """Inside socket_decode_step the select starts from the histogram the scoring pass leaves
+    (bins sized from the bucket-probability tables when the scores are unweighted); the
+    separate socket_topk_select call histograms leading digits of the scores itself.  Both are
+    exact, so they must pick the same tokens - also when nearly all scores tie (tau -> 0 makes
+    them collision counts, tau -> inf makes them all L/R), when k covers the whole sequence,
+    and with value norms (which switch the fused step back to the digit histogram)."""
+    _need_gpu()
+    cfg = {
+        "ties_cold": dict(n=6000, k=[300, 777], tau=1e-4, lens=[6000, 4100]),
+        "ties_flat": dict(n=6000, k=[300, 64], tau=1e4, lens=[5000, 6000]),
+        "take_all": dict(n=3000, k=[2999, 3024], tau=0.5, lens=[2999, 1500]),
+        "k_one": dict(n=3000, k=[1, 2], tau=0.5, lens=[3000, 2]),
+        "value_norms": dict(n=6000, k=[256, 100], tau=0.5, lens=[6000, 3333]),
+        "large": dict(n=40000, k=[1024, 512], tau=0.5, lens=[40000, 23456]),
+    }[case]
+    B, Hkv, G, L, P = 2, 2, 4, 64, 8
+    n = (cfg["n"] + 31) // 16 * 16
+    lens = np.array(cfg["lens"], dtype=np.int32)
+    layer = small_layer(seed=71, B=B, Hq=Hkv * G, Hkv=Hkv, n=n, L=L, P=P, k=cfg["k"], seq_len=lens, tau=cfg["tau"])
+    ctx = hz.make_ctx(layer)
+    Kd, Vd, qd, Wd = (hz.dev(x, layer.kv_dtype) for x in (layer.K, layer.V, layer.q, layer.W))
+    max_k = int(layer.k.max())
+    vn = None
+    if case == "value_norms":
+        vn = torch.from_numpy(np.stack([np.stack([oracle.value_norms(layer.V[b, h]) for h in range(Hkv)])
+                                        for b in range(B)]).astype(np.float32)).cuda()
+
+    def fresh():
+        return dict(codes=torch.zeros((B, Hkv, n, hz.lpad_of(L)), dtype=hz.torch_code_dtype(P), device="cuda"),
+                    scores=torch.zeros((B, Hkv, n), dtype=torch.float32, device="cuda"),
+                    idx=torch.zeros((B, Hkv, max_k), dtype=torch.int32, device="cuda"),
+                    nsel=torch.zeros((B, Hkv), dtype=torch.int32, device="cuda"),
+                    out=torch.zeros((B, layer.Hq, layer.d), dtype=torch.float32, device="cuda"))
+    a, f = fresh(), fresh()
+    kk, zero, one = hz.i32(layer.k), hz.i32(np.zeros(B)), hz.i32(np.ones(B))
+    start = lens - 1                                   # the step appends the last token of each sequence
+    for t in (a, f):
+        ctx.hash_keys(Kd, Wd, zero, hz.i32(start), B, n, t["codes"])
+    pos, ln = hz.i32(start), hz.i32(lens)
+    ctx.hash_keys(Kd, Wd, pos, one, B, 1, a["codes"])
+    ctx.score(qd, a["codes"], Wd, layer.tau, ln, B, a["scores"], vnorm=vn)
+    ctx.topk_select(a["scores"], ln, kk, B, a["idx"], a["nsel"])
+    ctx.sparse_decode(qd, Kd, Vd, a["idx"], a["nsel"], B, 1.0, a["out"])
+    for rep in range(2):                               # twice: the step must leave its scratch clean
+        ctx.decode_step(qd, Kd, Vd, f["codes"], Wd, layer.tau, pos, kk, B, 1.0, f["scores"], f["idx"], f["nsel"],
+                        f["out"], vnorm=vn)
+        torch.cuda.synchronize()
+        for key in a:
+            assert torch.equal(a[key], f[key]), (rep, key)
+    # and the selection is the oracle's on the GPU's own scores (exact, ties to the smaller position)
+    sc, idx, nsel = (f[key].cpu().numpy() for key in ("scores", "idx", "nsel"))
+    for b in range(B):
+        for h in range(Hkv):
+            want_idx, cnt = oracle.topk(sc[b, h].astype(np.float64), min(int(layer.k[b]), int(lens[b])))
+            assert nsel[b, h] == cnt
+            assert (np.sort(want_idx[:cnt]) == idx[b, h, :cnt]).all()
+    ctx.close()
+
+
 # ------------------------------------------------------------------ paged K/V/ids (configs[3] layout)
 
 def paged_setup(seed, B, Hq, Hkv, n_cap, L, P, lens, k, page=16, kv_dtype=wl.BF16):
