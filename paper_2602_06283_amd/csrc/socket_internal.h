@@ -145,6 +145,18 @@ template <int LPR> __device__ __forceinline__ float row_sum(float v) {
     return v;
 }
 
+// max over the 64 lanes of a wavefront; every lane ends with it
+__device__ __forceinline__ float wave_max(float v) {
+    v = fmaxf(v, dpp_f32<0x128>(v));
+    v = fmaxf(v, dpp_f32<0x124>(v));
+    v = fmaxf(v, dpp_f32<0x4E>(v));
+    v = fmaxf(v, dpp_f32<0xB1>(v));
+    auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
 // Adaptive first-level bin of a score: the leading bits of 1 + max(v - lo, 0) * inv read as a
 // float, i.e. 512 equal bins per octave of that quantity over four octaves, the last bin
 // taking everything beyond.  Non-decreasing in v for any (lo, inv), which is all the exact

@@ -33,18 +33,12 @@ struct DecodeArgs {
     int Hq, max_k, n_split, out_dtype;
 };
 
-// sum over the 64/LPR row slots of a wavefront (lanes with the same position inside a row)
-template <int LPR> __device__ __forceinline__ float slot_sum(float v) {
-    if (LPR <= 8) v += __shfl_xor(v, 8);
-    if (LPR <= 16) v = xor16_sum(v);
-    return xor32_sum(v);
-}
-
 template <typename T> struct Row8;     // 8 consecutive elements of a K/V row as floats
 template <> struct Row8<uint16_t> {
     uint4 raw;
     __device__ __forceinline__ void load(const void *p) { raw = *(const uint4 *)p; }
     __device__ __forceinline__ void zero() { raw = make_uint4(0, 0, 0, 0); }
+    __device__ __forceinline__ void store(void *p) const { *(uint4 *)p = raw; }
     __device__ __forceinline__ void get(float *f) const {
         const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
@@ -58,10 +52,18 @@ template <> struct Row8<float> {
     float4 a, b;
     __device__ __forceinline__ void load(const void *p) { a = ((const float4 *)p)[0]; b = ((const float4 *)p)[1]; }
     __device__ __forceinline__ void zero() { a = make_float4(0, 0, 0, 0); b = a; }
+    __device__ __forceinline__ void store(void *p) const { ((float4 *)p)[0] = a; ((float4 *)p)[1] = b; }
     __device__ __forceinline__ void get(float *f) const {
         f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
     }
 };
+
+// two adjacent elements of an LDS row as floats
+__device__ __forceinline__ float2 pair_f32(const uint16_t *p) {
+    const uint32_t w = *(const uint32_t *)p;
+    return make_float2(__uint_as_float(w << 16), __uint_as_float(w & 0xffff0000u));
+}
+__device__ __forceinline__ float2 pair_f32(const float *p) { return *(const float2 *)p; }
 
 template <typename T, int D, int G>
 __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(DecodeArgs a) {
@@ -72,16 +74,27 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(DecodeArg
     constexpr int CH = kDecodeChunk;
     constexpr int NPASS = CH / RPP;
     static_assert(CH % RPP == 0, "chunk must be whole passes");
+    // The value rows of a chunk go through LDS (at most 32 KB at a time), where every thread
+    // owns two adjacent output channels of GPG query heads and walks the rows itself: no
+    // cross-lane sums in the value product.
+    constexpr int ROWB = D * (int)sizeof(T);
+    constexpr int VROWS = CH * ROWB <= 32768 ? CH : 32768 / ROWB;
+    constexpr int VROUNDS = CH / VROWS, PPR = VROWS / RPP;      // passes per round
+    static_assert(VROWS % RPP == 0 && VROWS % 4 == 0, "a round is whole passes");
+    constexpr int CPAIRS = D / 2;                    // channel pairs
+    constexpr int NG = kDecodeThreads / CPAIRS;      // thread groups, each covering all channels
+    constexpr int GPG = (G + NG - 1) / NG;           // query heads per group
 
-    __shared__ float s_p[G][CH];                     // logits, then softmax numerators
+    __shared__ __align__(16) float s_p[G][CH];       // logits, then softmax numerators
     __shared__ int64_t s_row[CH];                    // K/V row of each chunk entry (-1 = none)
     __shared__ float s_m[G], s_l[G], s_corr[G];
-    __shared__ float s_red[NWAVE][G][D];
+    __shared__ __align__(16) T s_v[VROWS][D];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int bh = b * a.map.Hkv + h;
     const int sub = lane % LPR, rl = lane / LPR;     // this lane's 8-element slice and row slot
+    const int cp = tid % CPAIRS, g0 = (tid / CPAIRS) * GPG;   // this thread's channel pair and first query head
     const float ninf = -__builtin_inff();
 
     // Splits own fixed slices of the max_k-long index row, so the index loads do not have to
@@ -99,11 +112,9 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(DecodeArg
         r.load((const T *)a.q + ((int64_t)b * a.Hq + h * G + g) * D + sub * 8);
         r.get(qf[g]);
     }
-    float acc[G][8];
+    float acc[GPG][2];
 #pragma unroll
-    for (int g = 0; g < G; ++g)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[g][e] = 0.0f;
+    for (int gg = 0; gg < GPG; ++gg) acc[gg][0] = acc[gg][1] = 0.0f;
     if (tid < G) {
         s_m[tid] = ninf;
         s_l[tid] = 0.0f;
@@ -154,21 +165,20 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(DecodeArg
                 if (sub == 0) s_p[g][p * RPP + wave * RPW + rl] = rows[p] >= 0 ? dot * a.scale : ninf;
             }
         }
+        if (VROUNDS == 1) {                          // the value rows ride along with the logits
+#pragma unroll
+            for (int p = 0; p < NPASS; ++p) vr[p].store(&s_v[p * RPP + wave * RPW + rl][sub * 8]);
+        }
         __syncthreads();
         SK_STAMP3(3);
 
         // ---- running softmax statistics, one wavefront per query head at a time
         for (int g = wave; g < G; g += NWAVE) {
-            float v = s_p[g][lane];                  // CH == 64 == wavefront size
-            float cmax = v;
-#pragma unroll
-            for (int off = 32; off > 0; off >>= 1) cmax = fmaxf(cmax, __shfl_xor(cmax, off));
+            const float v = s_p[g][lane];            // CH == 64 == wavefront size
             const float m_old = s_m[g];
-            const float m_new = fmaxf(m_old, cmax);
+            const float m_new = fmaxf(m_old, wave_max(v));
             const float p = (v == ninf) ? 0.0f : expf(v - m_new);
-            float sum = p;
-#pragma unroll
-            for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+            const float sum = row_sum<64>(p);
             const float corr = (m_old == ninf) ? 0.0f : expf(m_old - m_new);
             s_p[g][lane] = p;
             if (lane == 0) {
@@ -182,42 +192,62 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(DecodeArg
 
         // ---- weighted value rows
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-            const float corr = s_corr[g];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[g][e] *= corr;
+        for (int gg = 0; gg < GPG; ++gg) {
+            if (g0 + gg < G) {
+                const float corr = s_corr[g0 + gg];
+                acc[gg][0] *= corr;
+                acc[gg][1] *= corr;
+            }
         }
 #pragma unroll
-        for (int p = 0; p < NPASS; ++p) {
-            float vf[8];
-            vr[p].get(vf);
+        for (int round = 0; round < VROUNDS; ++round) {
+            if (VROUNDS > 1) {
+                if (round > 0) __syncthreads();      // the previous round's rows have been consumed
 #pragma unroll
-            for (int g = 0; g < G; ++g) {
-                const float w = s_p[g][p * RPP + wave * RPW + rl];
+                for (int p = 0; p < PPR; ++p)
+                    vr[round * PPR + p].store(&s_v[p * RPP + wave * RPW + rl][sub * 8]);
+                __syncthreads();
+            }
+            if (g0 < G) {
+                constexpr int RB = 16;               // rows whose LDS reads are issued together
+                static_assert(VROWS % RB == 0, "whole row batches");
+                for (int r = 0; r < VROWS; r += RB) {
+                    float2 v2[RB];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) acc[g][e] = fmaf(w, vf[e], acc[g][e]);
+                    for (int j = 0; j < RB; ++j) v2[j] = pair_f32(&s_v[r + j][2 * cp]);
+#pragma unroll
+                    for (int gg = 0; gg < GPG; ++gg) {
+                        if (g0 + gg < G) {
+                            float4 w[RB / 4];
+#pragma unroll
+                            for (int j = 0; j < RB / 4; ++j) w[j] = *(const float4 *)&s_p[g0 + gg][round * VROWS + r + 4 * j];
+#pragma unroll
+                            for (int j = 0; j < RB / 4; ++j) {
+                                acc[gg][0] = fmaf(w[j].x, v2[4 * j].x, acc[gg][0]);
+                                acc[gg][1] = fmaf(w[j].x, v2[4 * j].y, acc[gg][1]);
+                                acc[gg][0] = fmaf(w[j].y, v2[4 * j + 1].x, acc[gg][0]);
+                                acc[gg][1] = fmaf(w[j].y, v2[4 * j + 1].y, acc[gg][1]);
+                                acc[gg][0] = fmaf(w[j].z, v2[4 * j + 2].x, acc[gg][0]);
+                                acc[gg][1] = fmaf(w[j].z, v2[4 * j + 2].y, acc[gg][1]);
+                                acc[gg][0] = fmaf(w[j].w, v2[4 * j + 3].x, acc[gg][0]);
+                                acc[gg][1] = fmaf(w[j].w, v2[4 * j + 3].y, acc[gg][1]);
+                            }
+                        }
+                    }
+                }
             }
         }
         __syncthreads();
     }
 
     SK_STAMP3(5);
-    // ---- combine the row slots of a wavefront, then the wavefronts
-#pragma unroll
-    for (int g = 0; g < G; ++g)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const float v = slot_sum<LPR>(acc[g][e]);
-            if (rl == 0) s_red[wave][g][sub * 8 + e] = v;
-        }
-    __syncthreads();
+    // ---- this split's partial result: (max, sum, weighted value sum) per query head
     float *part = a.partials + ((int64_t)(b * a.Hq + h * G) * a.n_split) * (D + 2);
-    for (int i = tid; i < G * D; i += kDecodeThreads) {
-        int g = i / D, c = i - g * D;
-        float v = 0.0f;
 #pragma unroll
-        for (int w = 0; w < NWAVE; ++w) v += s_red[w][g][c];
-        part[((int64_t)g * a.n_split + split) * (D + 2) + 2 + c] = v;
+    for (int gg = 0; gg < GPG; ++gg) {
+        const int g = g0 + gg;
+        if (g < G)
+            *(float2 *)&part[((int64_t)g * a.n_split + split) * (D + 2) + 2 + 2 * cp] = make_float2(acc[gg][0], acc[gg][1]);
     }
     if (tid < G) {
         part[((int64_t)tid * a.n_split + split) * (D + 2) + 0] = s_m[tid];
@@ -239,20 +269,18 @@ __global__ __launch_bounds__(D) void decode_merge_kernel(DecodeArgs a) {
     const int64_t head = (int64_t)b * a.Hq + h * G + g;
     const float *part = a.partials + head * a.n_split * (D + 2);
     const float ninf = -__builtin_inff();
+    // the first wavefront weighs the splits: its (max, sum) loads go out first, so that the
+    // weights are ready when the value sums arrive
+    const bool live = c < 64 && c < a.n_split;
+    const float m = live ? part[(int64_t)c * (D + 2)] : ninf;
+    const float l = live ? part[(int64_t)c * (D + 2) + 1] : 0.0f;
     float acc[64];
 #pragma unroll
     for (int s = 0; s < 64; ++s) acc[s] = s < a.n_split ? part[(int64_t)s * (D + 2) + 2 + c] : 0.0f;
-    if (c < 64) {                                    // the first wavefront weighs the splits
-        const bool live = c < a.n_split;
-        const float m = live ? part[(int64_t)c * (D + 2)] : ninf;
-        const float l = live ? part[(int64_t)c * (D + 2) + 1] : 0.0f;
-        float top = m;
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) top = fmaxf(top, __shfl_xor(top, off));
+    if (c < 64) {
+        const float top = wave_max(m);
         const float w = (m == ninf) ? 0.0f : expf(m - top);
-        float den = w * l;
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) den += __shfl_xor(den, off);
+        const float den = row_sum<64>(w * l);
         s_w[c] = w;
         if (c == 0) s_den = den;
     }
