@@ -540,27 +540,35 @@ def test_decode_step_equals_separate_calls_and_oracle(kv_dtype, L, P, G):
     ctx.close()
 
 
-@pytest.mark.parametrize("case", ["ties_cold", "ties_flat", "take_all", "k_one", "value_norms", "large"])
+@pytest.mark.parametrize("case", ["ties_cold", "ties_cold_small_k", "ties_flat", "all_equal", "take_all", "k_one",
+                                  "value_norms", "large", "large_tiny_k"])
 def test_decode_step_select_paths_agree(case):
-    """Inside socket_decode_step the select starts from the histogram the scoring pass leaves
-    (bins sized from the bucket-probability tables when the scores are unweighted); the
-    separate socket_topk_select call histograms leading digits of the scores itself.  Both are
-    exact, so they must pick the same tokens - also when nearly all scores tie (tau -> 0 makes
-    them collision counts, tau -> inf makes them all L/R), when k covers the whole sequence,
-    and with value norms (which switch the fused step back to the digit histogram)."""
+    """Inside socket_decode_step the select starts from what the scoring pass leaves: a
+    histogram with bins sized from the bucket-probability tables when the scores are
+    unweighted, and, when k is a small part of the sequence, lists of the scores above a guessed
+    bin.  The separate socket_topk_select call histograms leading digits of the scores itself.
+    All are exact, so they must pick the same tokens - also when nearly all scores tie (tau -> 0
+    makes them collision counts, tau -> inf makes them all L/R, identical keys make them one
+    value), when k covers the whole sequence, and with value norms (which switch the fused step
+    back to the digit histogram)."""
     _need_gpu()
     cfg = {
         "ties_cold": dict(n=6000, k=[300, 777], tau=1e-4, lens=[6000, 4100]),
+        "ties_cold_small_k": dict(n=6000, k=[300, 64], tau=1e-4, lens=[6000, 4100]),
         "ties_flat": dict(n=6000, k=[300, 64], tau=1e4, lens=[5000, 6000]),
+        "all_equal": dict(n=6000, k=[100, 37], tau=0.5, lens=[6000, 2500]),
         "take_all": dict(n=3000, k=[2999, 3024], tau=0.5, lens=[2999, 1500]),
         "k_one": dict(n=3000, k=[1, 2], tau=0.5, lens=[3000, 2]),
         "value_norms": dict(n=6000, k=[256, 100], tau=0.5, lens=[6000, 3333]),
         "large": dict(n=40000, k=[1024, 512], tau=0.5, lens=[40000, 23456]),
+        "large_tiny_k": dict(n=40000, k=[16, 1], tau=0.5, lens=[40000, 300]),
     }[case]
     B, Hkv, G, L, P = 2, 2, 4, 64, 8
     n = (cfg["n"] + 31) // 16 * 16
     lens = np.array(cfg["lens"], dtype=np.int32)
     layer = small_layer(seed=71, B=B, Hq=Hkv * G, Hkv=Hkv, n=n, L=L, P=P, k=cfg["k"], seq_len=lens, tau=cfg["tau"])
+    if case == "all_equal":                            # every key the same: all scores tie exactly
+        layer.K[:] = layer.K[:, :, :1, :]
     ctx = hz.make_ctx(layer)
     Kd, Vd, qd, Wd = (hz.dev(x, layer.kv_dtype) for x in (layer.K, layer.V, layer.q, layer.W))
     max_k = int(layer.k.max())
