@@ -147,12 +147,17 @@ __global__ __launch_bounds__(256) void hash_rows_kernel(HashArgs a) {
 // ---------------------------------------------------------------------------------------
 // bf16 MFMA kernel.  512 threads = 8 waves; wave w owns projection columns
 // [64w, 64w+64) of the workgroup's column chunk and keeps that slab of W in registers
-// for the whole kernel.  The workgroup walks its rows in tiles of 64 keys.
+// for the whole kernel.  The workgroup walks its rows in tiles of 64 keys, staged through
+// LDS; a tile is multiplied as two halves of 32 keys so that the accumulators take 32
+// registers and two workgroups fit a CU.
 // MFMA operands: A = W^T (32 planes x 16 channels), B = K^T (16 channels x 32 keys), so
 // lane (key n, half g) of the accumulator holds planes 8a + 4g + b (a,b in 0..3) of key n.
+// One barrier per tile: the bit matrix is double-buffered and the row bookkeeping
+// triple-buffered, so the waves that have finished a tile's products pack its ids while the
+// others still multiply, and nobody waits a second time.
 // ---------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(512) void hash_mfma_kernel(HashArgs a) {
+__global__ __launch_bounds__(512, D <= 128 ? 4 : 2) void hash_mfma_kernel(HashArgs a) {
     constexpr int KS = D / 16;                 // MFMA k-steps
     constexpr int TILE = 64;                   // keys per tile
     constexpr int KSTRIDE = D * 2 + 16;        // bytes per staged key row (padded)
@@ -160,9 +165,9 @@ __global__ __launch_bounds__(512) void hash_mfma_kernel(HashArgs a) {
     extern __shared__ uint32_t smem[];
     char *const kbase = (char *)smem;                  // two staged key tiles
     auto ktile = [&](int bf) { return kbase + bf * (TILE * KSTRIDE); };
-    uint32_t *bits = smem + 2 * TILE * KSTRIDE / 4;   // [TILE][BSTRIDE]
-    int *tok = (int *)(bits + TILE * BSTRIDE);        // [2][TILE]
-    int64_t *grow = (int64_t *)(tok + 2 * TILE);      // [2][TILE]
+    uint32_t *bits = smem + 2 * TILE * KSTRIDE / 4;   // [2][TILE][BSTRIDE]
+    int *tok = (int *)(bits + 2 * TILE * BSTRIDE);    // [3][TILE]
+    int64_t *grow = (int64_t *)(tok + 4 * TILE);      // [3][TILE] (8-byte aligned)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int chunk = blockIdx.y % a.n_chunks, h = blockIdx.y / a.n_chunks, b = blockIdx.z;
@@ -202,15 +207,14 @@ __global__ __launch_bounds__(512) void hash_mfma_kernel(HashArgs a) {
     const int srow = tid >> 3, sseg = tid & 7;
     uint4 stage[SEG / 16];
 
-    auto fetch = [&](int tile_r0, int buf) {
-        // resolve rows of this tile (first 64 threads), then load this thread's segment
+    auto fetch = [&](int tile_r0, int slot) {  // slot: which third of the row bookkeeping
         int r = tile_r0 + srow;
         int t = begin + r;
         bool live = r < wg_r1 && t >= 0 && t < a.map.max_n;
         int64_t g = live ? a.map.row(b, h, t) : -1;
         if (sseg == 0) {
-            tok[buf * TILE + srow] = t;
-            grow[buf * TILE + srow] = g;
+            tok[slot * TILE + srow] = t;
+            grow[slot * TILE + srow] = g;
         }
         const char *src = (const char *)a.K + g * (int64_t)(D * 2) + sseg * SEG;
 #pragma unroll
@@ -223,67 +227,247 @@ __global__ __launch_bounds__(512) void hash_mfma_kernel(HashArgs a) {
         for (int v = 0; v < SEG / 16; ++v) ((uint4 *)dst)[v] = stage[v];
     };
 
+    // ids of P = 8 planes are the bytes of a bit row, and the rotated order moves whole bytes:
+    // position 64c + 16 sub + s of token t holds table 64c + sub + 4 ((t + s) mod 16)
+    const bool byte_ids = a.P == 8 && a.S == 4 && (a.tables_per_chunk == 64 || a.n_chunks == 1);
+    const bool whole = a.n_chunks == 1 || (a.tables_per_chunk & 63) == 0;
+
     fetch(wg_r0, 0);
     commit(0);
     __syncthreads();
 
-    int buf = 0;
-    for (int tile_r0 = wg_r0; tile_r0 < wg_r1; tile_r0 += TILE, buf ^= 1) {
+    int buf = 0, slot = 0;
+    for (int tile_r0 = wg_r0; tile_r0 < wg_r1; tile_r0 += TILE) {
         const bool more = tile_r0 + TILE < wg_r1;
-        if (more) fetch(tile_r0 + TILE, buf ^ 1);
+        const int nslot = slot == 2 ? 0 : slot + 1;
+        if (more) fetch(tile_r0 + TILE, nslot);
+        uint32_t *bt = bits + buf * (TILE * BSTRIDE);
 
-        // ---- MFMA: acc[mb][nb] = W^T slab (32 planes) x K^T (32 keys)
-        floatx16_t acc[2][2];
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-            for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) acc[mb][nb][i] = 0.0f;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            bf16x8_t kf[2];
-#pragma unroll
-            for (int nb = 0; nb < 2; ++nb) {
-                const char *src = ktile(buf) + (nb * 32 + (lane & 31)) * KSTRIDE + ks * 32 + (lane >> 5) * 16;
-                kf[nb] = *(const bf16x8_t *)src;
-            }
+        for (int nb = 0; nb < 2; ++nb) {
+            // ---- MFMA: acc[mb] = W^T slab (32 planes) x K^T (32 keys)
+            floatx16_t acc[2];
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-                for (int nb = 0; nb < 2; ++nb)
-                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfrag[mb][ks], kf[nb], acc[mb][nb], 0, 0, 0);
-        }
-
-        // ---- sign bits: accumulator i of lane (n, g) is plane 8*(i/4) + 4g + i%4.
-        //      Funnel-shift the 16 sign bits into one 16-bit value per lane, exchange with
-        //      the other half-wave, and interleave nibbles into the 32 planes of the block.
+                for (int i = 0; i < 16; ++i) acc[mb][i] = 0.0f;
+            const char *src = ktile(buf) + (nb * 32 + (lane & 31)) * KSTRIDE + (lane >> 5) * 16;
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb) {
+            for (int ks = 0; ks < KS; ++ks) {
+                const bf16x8_t kf = *(const bf16x8_t *)(src + ks * 32);
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfrag[0][ks], kf, acc[0], 0, 0, 0);
+                acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfrag[1][ks], kf, acc[1], 0, 0, 0);
+            }
+            // ---- sign bits: accumulator i of lane (n, g) is plane 8*(i/4) + 4g + i%4.
+            //      Funnel-shift the 16 sign bits into one 16-bit value per lane, exchange with
+            //      the other half-wave, and interleave nibbles into the 32 planes of the block.
 #pragma unroll
-            for (int nb = 0; nb < 2; ++nb) {
-                uint32_t neg = __float_as_uint(acc[mb][nb][15]) >> 31;
+            for (int mb = 0; mb < 2; ++mb) {
+                uint32_t neg = __float_as_uint(acc[mb][15]) >> 31;
 #pragma unroll
                 for (int i = 14; i >= 0; --i)
-                    neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(acc[mb][nb][i]), 31);
+                    neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(acc[mb][i]), 31);
                 neg &= 0xffffu;                         // bit 4a+b = sign of plane 8a+4g+b
-                uint32_t other = __shfl_xor((int)neg, 32);
-                uint32_t lo = (lane < 32) ? neg : other, hi = (lane < 32) ? other : neg;
+                auto both = __builtin_amdgcn_permlane32_swap(neg, neg, false, false);
+                uint32_t lo = both[0], hi = both[1];    // the g = 0 and g = 1 halves of key n, in every lane
                 lo = (lo | (lo << 8)) & 0x00ff00ffu;
                 lo = (lo | (lo << 4)) & 0x0f0f0f0fu;
                 hi = (hi | (hi << 8)) & 0x00ff00ffu;
                 hi = (hi | (hi << 4)) & 0x0f0f0f0fu;
-                uint32_t word = ~(lo | (hi << 4));      // bit p = 1 when plane p projects >= 0
-                if (lane < 32) bits[(nb * 32 + lane) * BSTRIDE + wave * 2 + mb] = word;
+                const uint32_t word = ~(lo | (hi << 4)); // bit p = 1 when plane p projects >= 0
+                if (lane < 32) bt[(nb * 32 + lane) * BSTRIDE + wave * 2 + mb] = word;
             }
         }
-        __syncthreads();   // bit matrix complete; every wave is done reading this key tile
-
-        const bool whole = a.n_chunks == 1 || (a.tables_per_chunk & 63) == 0;
-        pack_codes(bits, BSTRIDE, TILE, tok + buf * TILE, grow + buf * TILE, a.codes, a.L, a.P,
-                   a.Lpad, a.S, a.cb, first_table, ntab, whole, tid, 512);
         if (more) commit(buf ^ 1);
-        __syncthreads();   // next tile staged; bit matrix free again
+        __syncthreads();   // bit matrix complete, next tile staged, every wave done with this key tile
+
+        const int *tk = tok + slot * TILE;
+        const int64_t *gr = grow + slot * TILE;
+        if (byte_ids) {
+            // thread -> (row, 16-position group, half of it): 8 ids = 8 byte reads, one 8-byte store
+            const int r = tid >> 3, sub = (tid >> 1) & 3, half = tid & 1;
+            const int64_t g = gr[r];
+            if (g >= 0) {
+                const int t = tk[r];
+                const uint8_t *rowb = (const uint8_t *)(bt + r * BSTRIDE);
+                uint32_t out[2] = {0u, 0u};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int tbl = sub + 4 * ((t + half * 8 + e) & 15);     // chunk-local table
+                    const uint32_t id = tbl < ntab ? rowb[tbl] : 0u;
+                    out[e >> 2] |= id << (8 * (e & 3));
+                }
+                const int pos0 = (first_table >> 6) << 6;
+                *(uint2 *)((char *)a.codes + g * (int64_t)a.Lpad + pos0 + sub * 16 + half * 8) = make_uint2(out[0], out[1]);
+            }
+        } else {
+            pack_codes(bt, BSTRIDE, TILE, tk, gr, a.codes, a.L, a.P, a.Lpad, a.S, a.cb, first_table, ntab,
+                       whole, tid, 512);
+        }
+        buf ^= 1;
+        slot = nslot;
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// bf16 MFMA kernel for 8-plane tables (one-byte ids), d <= 128, L >= 64: the fast path.
+// A workgroup keeps the W slab of one 64-table chunk (512 columns) in LDS, already cut into
+// MFMA A-operand fragments, and each of its 16 wavefronts works on 64-key blocks of its own:
+// the keys go from memory straight into B-operand registers, so there is no staging, no
+// barrier in the main loop, and the wavefronts drift apart - some multiply while others pack.
+//
+// Column order.  Position 16 sub + s of token t holds table sub + 4 ((t + s) mod 16).  The
+// 32-column block p = 4 sub + q therefore holds tables sub + 4 (4q + e), e = 0..3: after four
+// blocks the wavefront has, for each key, the 16 ids of position group `sub` in table order
+// j = 4q + e as the 16 bytes of four sign words, and the stored group is those bytes rotated
+// by t mod 16.
+// Row order inside a block.  MFMA operands: A = W^T (32 rows x 16 channels), B = K^T
+// (16 channels x 32 keys); accumulator i of lane (key n, half g) is row 8 (i/4) + 4g + i%4.
+// Row m is given plane (table e, plane pl) with 8e + pl = 16 g + i, so that the 16 sign bits a
+// lane collects from its accumulators are, in order, one half of the key's 32-bit sign word.
+// hash_wfrag_kernel lays W out that way once per call; the main kernel copies it into LDS.
+// ---------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void hash_wfrag_kernel(HashArgs a, uint4 *wfrag) {
+    constexpr int KS = D / 16;
+    const int p = blockIdx.x, chunk = blockIdx.y % a.n_chunks, h = blockIdx.y / a.n_chunks;
+    const int first_table = chunk * 64;
+    const int ntab = min(64, a.L - first_table);
+    const int sub = p >> 2, q = p & 3;
+    const uint16_t *W = (const uint16_t *)a.W + (int64_t)h * D * a.LP;
+    uint4 *dst = wfrag + ((int64_t)blockIdx.y * 16 + p) * KS * 64;
+    for (int f = threadIdx.x; f < KS * 64; f += 256) {
+        const int ks = f >> 6, lane = f & 63;
+        const int g = lane >> 5, m = lane & 31;
+        const int bit = 16 * ((m >> 2) & 1) + 4 * (m >> 3) + (m & 3);
+        const int tt = sub + 4 * (4 * q + (bit >> 3));         // chunk-local table
+        const int col = (first_table + tt) * 8 + (bit & 7);
+        uint32_t w[4] = {0u, 0u, 0u, 0u};
+        if (tt < ntab) {
+            uint16_t e[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) e[i] = W[(int64_t)(ks * 16 + g * 8 + i) * a.LP + col];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) w[i >> 1] |= (uint32_t)e[i] << (16 * (i & 1));
+        }
+        dst[f] = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
+template <int V> struct IntTag { static constexpr int value = V; };
+
+#ifndef SK_HASH8_THREADS
+#define SK_HASH8_THREADS 1024
+#endif
+constexpr int kHash8Threads = SK_HASH8_THREADS;
+
+template <int D>
+__global__ __launch_bounds__(kHash8Threads) void hash_mfma8_kernel(HashArgs a, const uint4 *wfrag) {
+    constexpr int KS = D / 16;                 // MFMA k-steps
+    constexpr int NCB = 16;                    // 32-column blocks of a chunk
+    constexpr int NW = kHash8Threads / 64;
+    extern __shared__ uint32_t smem[];
+    uint4 *wl = (uint4 *)smem;                         // [NCB][KS][64 lanes] A fragments
+    uint32_t *bits = smem + NCB * KS * 64 * 4;         // [NW waves][64 keys][4 words]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int chunk = blockIdx.y % a.n_chunks, h = blockIdx.y / a.n_chunks, b = blockIdx.z;
+    const int count = a.row_count[b];
+    const int begin = a.row_begin[b];
+    const int first_table = chunk * 64;
+    const int ntab = min(64, a.L - first_table);
+
+    // ---- W slab -> LDS
+    {
+        const uint4 *src = wfrag + (int64_t)blockIdx.y * NCB * KS * 64;
+        constexpr int N = NCB * KS * 64, PER = N / kHash8Threads, NB = PER < 8 ? PER : 8;
+        static_assert(N % kHash8Threads == 0 && PER % NB == 0, "whole batches of copies per thread");
+#pragma unroll 1
+        for (int u0 = 0; u0 < PER; u0 += NB) {
+            uint4 v[NB];
+#pragma unroll
+            for (int u = 0; u < NB; ++u) v[u] = src[tid + (u0 + u) * kHash8Threads];
+#pragma unroll
+            for (int u = 0; u < NB; ++u) wl[tid + (u0 + u) * kHash8Threads] = v[u];
+        }
+    }
+    __syncthreads();
+
+    uint32_t *mybits = bits + wave * 256;
+    const int n = lane & 31, g = lane >> 5;
+    const char *Kb = (const char *)a.K;
+    char *Cb = (char *)a.codes;
+
+    auto key_row = [&](int r) -> int64_t {
+        const int t = begin + r;
+        return (r < count && t >= 0 && t < a.map.max_n) ? a.map.row(b, h, t) : -1;
+    };
+    // Branch-free: a key that does not exist reads row 0 of the cache instead (its ids are never
+    // stored).
+    bf16x8_t kf[2][KS];
+    auto load_keys = [&](int r0) {
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) {
+            const int64_t row = key_row(r0 + nb * 32 + n);
+            const char *src = Kb + (row >= 0 ? row : 0) * (int64_t)(D * 2) + g * 16;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) kf[nb][ks] = *(const bf16x8_t *)(src + ks * 32);
+        }
+    };
+    // 32 sign bits of one key from the accumulators of a 32-row block: bit p = 1 when the
+    // projection onto plane p is >= 0.  A lane's 16 accumulators are bits 16g .. 16g+15.
+    auto sign_word = [&](const floatx16_t &acc) -> uint32_t {
+        uint32_t neg = __float_as_uint(acc[15]) >> 31;
+#pragma unroll
+        for (int i = 14; i >= 0; --i) neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(acc[i]), 31);
+        auto both = __builtin_amdgcn_permlane32_swap(neg, neg, false, false);   // g = 0 and g = 1 halves, in every lane
+        return ~(both[0] | (both[1] << 16));
+    };
+
+    // 64-key blocks are dealt to the wavefronts of the whole launch round-robin
+    const int nblocks = (count + 63) >> 6;
+    const int stride = gridDim.x * NW;
+    int blk = blockIdx.x * NW + wave;
+    if (blk < nblocks) load_keys(blk * 64);
+    for (; blk < nblocks; blk += stride) {
+        const int r0 = blk * 64;
+        const int64_t prow = key_row(r0 + lane);        // the key this lane packs
+        const int rot = (begin + r0 + lane) & 15;
+#pragma unroll 1
+        for (int p = 0; p < NCB; ++p) {
+            const int sub = p >> 2, q = p & 3;
+            const uint4 *af = wl + (p * KS) * 64 + lane;
+            floatx16_t acc0, acc1;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc0[i] = acc1[i] = 0.0f;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                union { uint4 u; bf16x8_t v; } fa;
+                fa.u = af[ks * 64];
+                acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa.v, kf[0][ks], acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa.v, kf[1][ks], acc1, 0, 0, 0);
+            }
+            // bytes whose table (sub + 4 (4q + e)) lies beyond the chunk's live tables stay zero
+            const int nlive = (ntab - sub - 16 * q + 3) >> 2;            // live tables among e = 0..3
+            const uint32_t live_mask = nlive >= 4 ? 0xffffffffu : nlive <= 0 ? 0u : (1u << (8 * nlive)) - 1u;
+            const uint32_t w0 = sign_word(acc0), w1 = sign_word(acc1);
+            mybits[lane * 4 + q] = (lane < 32 ? w0 : w1) & live_mask;   // lane = key n or 32 + n
+            if (q == 3) {
+                // ---- the 16 ids of position group `sub`, rotated by the token position
+                const uint4 wv = *(const uint4 *)(mybits + lane * 4);
+                const bool r1 = rot & 4, r2 = rot & 8;
+                const uint32_t y0 = r1 ? wv.y : wv.x, y1 = r1 ? wv.z : wv.y, y2 = r1 ? wv.w : wv.z, y3 = r1 ? wv.x : wv.w;
+                const uint32_t x0 = r2 ? y2 : y0, x1 = r2 ? y3 : y1, x2 = r2 ? y0 : y2, x3 = r2 ? y1 : y3;
+                const uint32_t sh = rot & 3;
+                uint4 o;
+                o.x = __builtin_amdgcn_alignbyte(x1, x0, sh);
+                o.y = __builtin_amdgcn_alignbyte(x2, x1, sh);
+                o.z = __builtin_amdgcn_alignbyte(x3, x2, sh);
+                o.w = __builtin_amdgcn_alignbyte(x0, x3, sh);
+                if (prow >= 0) *(uint4 *)(Cb + prow * (int64_t)a.Lpad + first_table + sub * 16) = o;
+            }
+        }
+        if (blk + stride < nblocks) load_keys((blk + stride) * 64);
     }
 }
 
@@ -305,6 +489,30 @@ static int launch_rows(const HashArgs &a, int Hkv, int batch, int max_rows, hipS
 }
 
 template <int D>
+static int launch_mfma8(HashArgs a, uint4 *wfrag, int Hkv, int batch, int max_rows, hipStream_t st) {
+    constexpr int NW = kHash8Threads / 64;
+    a.tables_per_chunk = 64;
+    a.n_chunks = (a.L + 63) / 64;
+    // W as MFMA fragments, once per call
+    hipLaunchKernelGGL((hash_wfrag_kernel<D>), dim3(16, Hkv * a.n_chunks), dim3(256), 0, st, a, wfrag);
+    // one workgroup per CU (the W slab fills most of its LDS); each wavefront takes 64-key blocks
+    int per = 256 / (Hkv * a.n_chunks * batch);
+    const int nblocks = (max_rows + 63) / 64;
+    if (per > (nblocks + NW - 1) / NW) per = (nblocks + NW - 1) / NW;
+    if (per < 1) per = 1;
+    const size_t lds = (size_t)16 * (D / 16) * 64 * 16 + (size_t)NW * 64 * 16;
+    static bool raised = false;     // more than 64 KB of dynamic LDS has to be allowed once per process
+    if (!raised) {
+        if (hipFuncSetAttribute((const void *)hash_mfma8_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds) != hipSuccess) return SOCKET_EHIP;
+        raised = true;
+    }
+    dim3 grid(per, Hkv * a.n_chunks, batch);
+    hipLaunchKernelGGL((hash_mfma8_kernel<D>), grid, dim3(kHash8Threads), lds, st, a, (const uint4 *)wfrag);
+    return SOCKET_OK;
+}
+
+template <int D>
 static int launch_mfma(HashArgs a, int Hkv, int batch, int max_rows, hipStream_t st) {
     constexpr int TILE = 64, KSTRIDE = D * 2 + 16, BSTRIDE = 17;
     a.tables_per_chunk = 512 / a.P;
@@ -317,7 +525,7 @@ static int launch_mfma(HashArgs a, int Hkv, int batch, int max_rows, hipStream_t
     rows = (rows + TILE - 1) / TILE * TILE;
     if (rows < 1024) rows = 1024;
     a.rows_per_wg = rows;
-    size_t lds = 2 * TILE * KSTRIDE + TILE * BSTRIDE * 4 + 2 * TILE * 4 + 2 * TILE * 8;
+    size_t lds = 2 * TILE * KSTRIDE + 2 * TILE * BSTRIDE * 4 + 4 * TILE * 4 + 3 * TILE * 8;
     dim3 grid((max_rows + rows - 1) / rows, Hkv * a.n_chunks, batch);
     hipLaunchKernelGGL((hash_mfma_kernel<D>), grid, dim3(512), lds, st, a);
     return SOCKET_OK;
@@ -342,9 +550,12 @@ int launch_hash_keys(socket_ctx *ctx, const void *K, const void *proj, const int
     } else if (max_rows < 64) {
         rc = launch_rows<uint16_t>(a, g.Hkv, batch, max_rows, st);
     } else {
+        const bool fast8 = ctx->wfrag != nullptr;      // one-byte ids, whole 64-table chunks, d <= 128
         switch (g.d) {
-            case 64: rc = launch_mfma<64>(a, g.Hkv, batch, max_rows, st); break;
-            case 128: rc = launch_mfma<128>(a, g.Hkv, batch, max_rows, st); break;
+            case 64: rc = fast8 ? launch_mfma8<64>(a, (uint4 *)ctx->wfrag, g.Hkv, batch, max_rows, st)
+                                : launch_mfma<64>(a, g.Hkv, batch, max_rows, st); break;
+            case 128: rc = fast8 ? launch_mfma8<128>(a, (uint4 *)ctx->wfrag, g.Hkv, batch, max_rows, st)
+                                 : launch_mfma<128>(a, g.Hkv, batch, max_rows, st); break;
             case 256: rc = launch_mfma<256>(a, g.Hkv, batch, max_rows, st); break;
             default: return SOCKET_EUNSUPPORTED;
         }

@@ -549,11 +549,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
                 if (a.hist && v > ninf) {
                     const uint32_t bin = adaptive ? score_bin(v, bin_lo, bin_inv)
                                                   : score_order_key(v) >> (32 - kHistBits);
-#ifndef SK_NO_LATOMIC
                     atomicAdd(&lhist[bin], 1u);
-#else
-                    if (bin == 0xffffffffu) lhist[0] = 1;
-#endif
                 }
             }
         }
@@ -688,11 +684,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
         __syncthreads();
         uint32_t *gh = a.hist + bh * kHistBins;
         for (int i = tid; i < kHistBins; i += kScoreThreads)
-#ifndef SK_NO_FLUSH
             if (lhist[i]) atomicAdd(&gh[i], lhist[i]);
-#else
-            if (lhist[i] == 0xffffffffu) gh[i] = 1;
-#endif
     }
 }
 

@@ -112,15 +112,19 @@ int socket_create(socket_ctx **out, const socket_params *p) {
     const int64_t BH = (int64_t)g.max_batch * g.Hkv;
     const int64_t sz_tables = BH * g.table_words * 4;
     const int64_t sz_tstats = BH * g.Lpad * 4;
+    // fast prefill hash: bf16 keys, 8-plane tables, whole 64-table chunks, W slab of a chunk fits LDS
+    const bool fast_hash = g.kv_dtype == SOCKET_BF16 && g.P == 8 && g.L >= 64 && g.d <= 128;
+    const int64_t sz_wfrag = fast_hash ? (int64_t)g.Hkv * ((g.L + 63) / 64) * g.d * 1024 : 0;
     const int64_t sz_hist = 2 * BH * kHistBins * 4;   // first- and second-digit histograms
     const int64_t sz_cnt = BH * (kCounterStride + kThrStride) * 4;
     const int64_t sz_cand = BH * g.max_n * 4;
     const int64_t sz_staged = BH * g.max_k * 4;
     const int64_t sz_seq = (int64_t)g.max_batch * 4;
     const int64_t sz_part = (int64_t)g.max_batch * g.Hq * g.n_split * (g.d + 2) * 4;
-    ctx->scratch_bytes = sz_tables + sz_tstats + sz_hist + sz_cnt + 2 * sz_cand + sz_staged + sz_part + sz_seq;
+    ctx->scratch_bytes = sz_wfrag + sz_tables + sz_tstats + sz_hist + sz_cnt + 2 * sz_cand + sz_staged + sz_part + sz_seq;
     bool ok = hipMalloc((void **)&ctx->tables, sz_tables) == hipSuccess &&
               hipMalloc((void **)&ctx->tstats, sz_tstats) == hipSuccess &&
+              (!fast_hash || hipMalloc(&ctx->wfrag, sz_wfrag) == hipSuccess) &&
               hipMalloc((void **)&ctx->hist, sz_hist) == hipSuccess &&
               hipMalloc((void **)&ctx->counters, sz_cnt) == hipSuccess &&
               hipMalloc((void **)&ctx->cand_key, sz_cand) == hipSuccess &&
@@ -145,7 +149,7 @@ int socket_create(socket_ctx **out, const socket_params *p) {
 
 int socket_destroy(socket_ctx *ctx) {
     if (!ctx) return SOCKET_EINVAL;
-    void *bufs[] = {ctx->tables, ctx->tstats, ctx->hist, ctx->counters, ctx->cand_key, ctx->cand_idx, ctx->staged, ctx->partials, ctx->seq_scratch};
+    void *bufs[] = {ctx->tables, ctx->tstats, ctx->wfrag, ctx->hist, ctx->counters, ctx->cand_key, ctx->cand_idx, ctx->staged, ctx->partials, ctx->seq_scratch};
     for (void *b : bufs)
         if (b) (void)hipFree(b);
     delete ctx;

@@ -67,6 +67,7 @@ struct socket_ctx {
     int64_t scratch_bytes;
     float *tables;        // [max_batch*Hkv][table_words]
     float *tstats;        // [max_batch*Hkv][Lpad] spread of each table's bucket probabilities
+    void *wfrag;          // W cut into MFMA fragments for the fast prefill hash (null when that path does not apply)
     uint32_t *hist;       // [2][max_batch*Hkv][kHistBins]
     uint32_t *counters;   // [max_batch*Hkv][kCounterStride] counters, then [max_batch*Hkv][kThrStride] records
     uint32_t *cand_key;   // [max_batch*Hkv][max_n]
