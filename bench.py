@@ -22,7 +22,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 
-MEASURED_SCORE_TRAFFIC = {("128k", 32): 73862 * 1024}   # bytes per score_kernel launch
+MEASURED_SCORE_TRAFFIC = {("128k", 32): 73876 * 1024}   # bytes per score_kernel launch
 
 WORKLOADS = {
     # name: (n, k, seed)   -- BASELINE configs[2] and configs[1]
