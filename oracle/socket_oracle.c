@@ -263,6 +263,22 @@ int socket_oracle_dense_decode(const float *q, const float *K, const float *V, l
 }
 
 /* Alg. 1 also returns the value norms ||v_j||_2 that Alg. 3 ranks with. */
+/* ------------------------------------------------------------------------- *
+ * Sink and local-window tokens (Experiments, evaluation protocol: a small number
+ * of sink and local window tokens is always kept).  The first n_sink and the
+ * last n_window of the seq_len valid tokens get the score +inf, so that the TopK
+ * step takes them first; they count towards k.  A masked token (-inf) stays
+ * masked.  scores [n] is updated in place.
+ * ------------------------------------------------------------------------- */
+int socket_oracle_force_tokens(double *scores, long n, long seq_len, long n_sink, long n_window) {
+    if (!scores || n < 0 || seq_len < 0 || seq_len > n || n_sink < 0 || n_window < 0) return ORACLE_EINVAL;
+    for (long j = 0; j < seq_len; ++j) {
+        int forced = (j < n_sink) || (j >= seq_len - n_window);
+        if (forced && scores[j] != -INFINITY) scores[j] = INFINITY;
+    }
+    return ORACLE_OK;
+}
+
 int socket_oracle_value_norms(const float *V, long n, int d, float *vnorm) {
     if (!V || !vnorm || n < 0 || d <= 0) return ORACLE_EINVAL;
     for (long j = 0; j < n; ++j) {

@@ -157,6 +157,17 @@ def dense_decode(q, K, V, scale=1.0):
     return y
 
 
+def force_tokens(scores, seq_len, n_sink, n_window):
+    """Sink / local-window override: +inf for the first n_sink and last n_window valid tokens.
+    scores float64 [n] -> new float64 [n]."""
+    out = np.ascontiguousarray(scores, dtype=np.float64).copy()
+    rc = _lib().socket_oracle_force_tokens(
+        _p(out, ctypes.c_double), ctypes.c_long(out.shape[0]), ctypes.c_long(int(seq_len)),
+        ctypes.c_long(int(n_sink)), ctypes.c_long(int(n_window)))
+    _check(rc, "force_tokens")
+    return out
+
+
 def value_norms(V):
     """||v_j||_2 as returned by Alg. 1.  V [n,d] -> float32 [n]."""
     V = _f32(V)

@@ -381,6 +381,31 @@ def test_value_norms():
     np.testing.assert_allclose(oracle.value_norms(V), np.linalg.norm(V.astype(np.float64), axis=1), rtol=1e-6)
 
 
+def test_forced_sink_and_window_tokens():
+    """Experiments section: sink and local-window tokens are always kept.  Brute force: the
+    forced positions are exactly [0, n_sink) and [seq_len - n_window, seq_len); they win the
+    TopK step ahead of any finite score, in position order; masked tokens stay masked; tokens
+    beyond seq_len are untouched."""
+    rng = _rng(55)
+    n, seq = 50, 41
+    s = rng.standard_normal(n)
+    s[3] = -np.inf                      # a masked sink token
+    s[seq:] = -np.inf
+    out = oracle.force_tokens(s, seq, 4, 6)
+    forced = [j for j in range(seq) if (j < 4 or j >= seq - 6) and j != 3]
+    assert np.isposinf(out[forced]).all() and np.isneginf(out[3])
+    rest = [j for j in range(n) if j not in forced]
+    assert (out[rest] == s[rest]).all()
+    sel, cnt = oracle.topk(out, 12)
+    assert cnt == 12 and sorted(sel[:9].tolist()) == forced and sel[:9].tolist() == forced
+    best_free = [j for j in np.argsort(-s[:seq], kind="stable") if j not in forced and j != 3][:3]
+    assert sel[9:12].tolist() == best_free
+    # windows that overlap or exceed the sequence force every valid token, nothing else
+    all_forced = oracle.force_tokens(rng.standard_normal(n), 10, 8, 8)
+    assert np.isposinf(all_forced[:10]).all() and np.isfinite(all_forced[10:]).all()
+    assert (oracle.force_tokens(s, seq, 0, 0) == s).all()
+
+
 # ------------------------------------------------------------------ planted mistakes are caught
 
 def test_pins_catch_bit_order_mismatch():
