@@ -184,6 +184,25 @@ def main():
             g.close()
         cur_len = int(length[0])
 
+        # ---------------- the paper's evaluation protocol on the same step -----------------
+        # value-norm weighted ranking (Alg. 3) and 4 sink + 124 local-window tokens always kept
+        vns = [torch.empty((1, Hkv, n_alloc), dtype=torch.float32, device="cuda") for _ in layers]
+        n_all = torch.full((1,), n_alloc, dtype=torch.int32, device="cuda")
+
+        def norms():
+            for (K, V, q, W, codes), vn in zip(layers, vns):
+                ctx.value_norms(V, zero, n_all, 1, n_alloc, vn)
+        t_norms_ms = timed(norms, 2)
+        ctx.set_forced_tokens(4, 124)
+
+        def protocol_step():
+            for li, ((K, V, q, W, codes), vn) in enumerate(zip(layers, vns)):
+                ctx.decode_step(q, K, V, codes, W, tau, pos, k_t, 1, 1.0, scores, idx, nsel, out[li], vnorm=vn)
+        g = capture(protocol_step)
+        stage_us["fused_decode_step_value_norms_sink_window"] = timed(g.launch, 10) * 1e3 / NL
+        g.close()
+        ctx.set_forced_tokens(0, 0)
+
     # ---------------- roofline of the dominant kernel (scoring) -------------------------
     # algorithmic bytes per launch: every bucket id read once + one fp32 score written per key
     score_bytes = Hkv * cur_len * (Lpad * 1 + 4)
@@ -223,6 +242,8 @@ def main():
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": score_gbs / HBM_PEAK_GBS,
                      "traffic": traffic, "algorithmic_bytes": score_bytes,
                      "avg_launch_us": stage_us["score"]},
+        "value_norms_prefill": {"us_per_layer": t_norms_ms * 1e3 / NL,
+                                "gbs": Hkv * n_alloc * (d * 2 + 4) / (t_norms_ms * 1e-3 / NL) / 1e9},
         "hash_prefill": {"ms_per_layer": t_prefill_ms / NL,
                          "tflops": hash_flops / (t_prefill_ms * 1e-3) / 1e12,
                          "mfma_util": hash_flops / (t_prefill_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,

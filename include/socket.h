@@ -126,6 +126,29 @@ int socket_hash_keys(socket_ctx *ctx, const void *K, const void *proj,
                      void *codes, void *stream);
 
 /*
+ * Value norms (Alg. 1 keeps ||v_j||_2 next to the bucket ids; Alg. 3 ranks tokens by
+ * soft score x value norm).  For each sequence b < batch and every KV head,
+ *     vnorm[b,h,t] = ||V[b,h,t,:]||_2      for t = row_begin[b] .. row_begin[b]+row_count[b]-1
+ * (fp32 sum of squares).  Same row-range arguments as socket_hash_keys: prefill passes
+ * (0, n), a decode step passes (n, 1) for the appended value row before it scores.
+ * vnorm: device float32 [B, Hkv, max_n] in logical token order, for paged caches too.
+ */
+int socket_value_norms(socket_ctx *ctx, const void *V, const int32_t *block_table,
+                       const int32_t *row_begin, const int32_t *row_count, int32_t batch,
+                       int32_t max_rows, float *vnorm, void *stream);
+
+/*
+ * Sink and local-window tokens (Experiments section, evaluation protocol: a small number of
+ * sink and local window tokens, e.g. 128, is always kept).  From this call on, every scoring
+ * call on this context (socket_score, socket_score_keys, socket_decode_step) gives the score
+ * +inf to the first n_sink and to the last n_window of a sequence's seq_len tokens, so that
+ * the TopK step takes them first, in position order; they count towards k.  Tokens whose
+ * block is absent stay -inf.  (0, 0), the state after socket_create, switches it off.
+ * Host-side state: it takes effect for calls issued (or captured) after it returns.
+ */
+int socket_set_forced_tokens(socket_ctx *ctx, int32_t n_sink, int32_t n_window);
+
+/*
  * Alg. 2 + Alg. 5 (SoftBucketProbs, SoftHashCollisionScores; Eq. 3, soft score).
  * Soft-hashes each query into its L x R bucket probabilities
  * (u = tanh(W q)/sqrt(d), softmax of u.c_r/tau over the R corners; evaluated in
@@ -185,9 +208,10 @@ int socket_sparse_decode(socket_ctx *ctx, const void *q, const void *K, const vo
  *     socket_score with seq_len = pos + 1                (Alg. 2 + Alg. 5)
  *     socket_topk_select with seq_len = pos + 1          (Alg. 3, TopK)
  *     socket_sparse_decode                               (Eq. 2)
- * in four launches instead of seven: the appended key's hash shares a launch with the
- * queries' soft hash, and the scoring pass also produces the histogram that the selection
- * starts from.  Results are bit-identical to the separate calls.
+ * in six kernels instead of nine: the appended key's hash shares a launch with the queries'
+ * soft hash, and the scoring pass also produces the histogram that the selection starts
+ * from.  Results are bit-identical to the separate calls.  With value norms the caller
+ * updates vnorm for the appended row first (socket_value_norms with max_rows = 1).
  * pos, k: device int32 [batch].
  */
 int socket_decode_step(socket_ctx *ctx, const void *q, const void *K, const void *V, void *codes,

@@ -379,6 +379,7 @@ struct ScoreArgs {
     const float *tstats;     // [B*Hkv][Lpad] per-table spread (adaptive histogram only)
     uint32_t *thr;           // [B*Hkv][kThrStride] threshold records: receives the binning
     int hist_mode;           // HistMode of `hist`
+    int n_sink, n_window;    // the first n_sink and last n_window tokens of a sequence score +inf
     RowMap map;
     int L, Lpad, rounds, R, G, Plo, Rlo, table_rows;
     int64_t table_words;
@@ -543,8 +544,12 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
             }
             const int key = base + (j * S + sub) * KPW + kk;
             if (key < max_n) {
-                if (dd) v = ninf;
-                else if (vn) v *= vn[key];
+                if (dd) {
+                    v = ninf;
+                } else {
+                    if (vn) v *= vn[key];
+                    if (key < a.n_sink || key >= seq - a.n_window) v = __builtin_inff();   // sink / local window
+                }
                 out[key] = v;
                 if (a.hist && v > ninf) {
                     const uint32_t bin = adaptive ? score_bin(v, bin_lo, bin_inv)
@@ -768,6 +773,7 @@ int launch_score_keys(socket_ctx *ctx, const void *codes, const float *vnorm,
                      : (vnorm == nullptr && g.mode == kDirect) ? kHistAdaptive : kHistDigit;
     if (hist_mode) *hist_mode = mode;
     a.hist_mode = mode; a.tstats = ctx->tstats; a.L = g.L;
+    a.n_sink = ctx->n_sink; a.n_window = ctx->n_window;
     a.thr = ctx->counters + (int64_t)g.max_batch * g.Hkv * kCounterStride;
     a.codes = codes; a.tables = ctx->tables; a.vnorm = vnorm; a.seq_len = seq_len; a.scores = scores;
     a.map = RowMap{block_table, g.Hkv, g.max_n, g.page, g.max_blocks, g.num_blocks};

@@ -177,6 +177,24 @@ int socket_hash_keys(socket_ctx *ctx, const void *K, const void *proj, const int
                             (hipStream_t)stream);
 }
 
+int socket_value_norms(socket_ctx *ctx, const void *V, const int32_t *block_table,
+                       const int32_t *row_begin, const int32_t *row_count, int32_t batch,
+                       int32_t max_rows, float *vnorm, void *stream) {
+    if (!ctx || !V || !row_begin || !row_count || !vnorm) return SOCKET_EINVAL;
+    if (!batch_ok(ctx, batch) || !paging_ok(ctx, block_table)) return SOCKET_EINVAL;
+    if (max_rows < 0 || max_rows > ctx->g.max_n) return SOCKET_EINVAL;
+    if (max_rows == 0) return SOCKET_OK;
+    return launch_value_norms(ctx, V, block_table, row_begin, row_count, batch, max_rows, vnorm,
+                              (hipStream_t)stream);
+}
+
+int socket_set_forced_tokens(socket_ctx *ctx, int32_t n_sink, int32_t n_window) {
+    if (!ctx || n_sink < 0 || n_window < 0) return SOCKET_EINVAL;
+    ctx->n_sink = n_sink;
+    ctx->n_window = n_window;
+    return SOCKET_OK;
+}
+
 int socket_score(socket_ctx *ctx, const void *q, const void *codes, const void *proj, float tau,
                  const float *vnorm, const int32_t *block_table, const int32_t *seq_len,
                  int32_t batch, float *scores, void *stream) {

@@ -65,6 +65,7 @@ struct socket_ctx {
     int device;
     int last_hip_error;
     int64_t scratch_bytes;
+    int n_sink, n_window; // tokens at either end of a sequence that scoring forces into the selection
     float *tables;        // [max_batch*Hkv][table_words]
     float *tstats;        // [max_batch*Hkv][Lpad] spread of each table's bucket probabilities
     void *wfrag;          // W cut into MFMA fragments for the fast prefill hash (null when that path does not apply)
@@ -100,6 +101,9 @@ int launch_score_keys(socket_ctx *ctx, const void *codes, const float *vnorm,
 // hist_mode: what the context's histogram already holds about `scores` (HistMode)
 int launch_topk(socket_ctx *ctx, const float *scores, const int32_t *seq_len, const int32_t *k,
                 int batch, int32_t *idx, int32_t *n_selected, int hist_mode, hipStream_t st);
+int launch_value_norms(socket_ctx *ctx, const void *V, const int32_t *block_table,
+                       const int32_t *row_begin, const int32_t *row_count, int batch, int max_rows,
+                       float *vnorm, hipStream_t st);
 int launch_sparse_decode(socket_ctx *ctx, const void *q, const void *K, const void *V,
                          const int32_t *idx, const int32_t *n_selected, const int32_t *block_table,
                          int batch, float scale, int out_dtype, void *out, hipStream_t st);
@@ -167,6 +171,32 @@ __device__ __forceinline__ uint32_t score_bin(float v, float lo, float inv) {
     const uint32_t bin = (__float_as_uint(y) - 0x3f800000u) >> 14;
     return bin < (uint32_t)(kHistBins - 1) ? bin : (uint32_t)(kHistBins - 1);
 }
+
+// 8 consecutive elements of a K/V row as floats
+template <typename T> struct Row8;
+template <> struct Row8<uint16_t> {
+    uint4 raw;
+    __device__ __forceinline__ void load(const void *p) { raw = *(const uint4 *)p; }
+    __device__ __forceinline__ void zero() { raw = make_uint4(0, 0, 0, 0); }
+    __device__ __forceinline__ void store(void *p) const { *(uint4 *)p = raw; }
+    __device__ __forceinline__ void get(float *f) const {
+        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            f[2 * i] = __uint_as_float(w[i] << 16);
+            f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+};
+template <> struct Row8<float> {
+    float4 a, b;
+    __device__ __forceinline__ void load(const void *p) { a = ((const float4 *)p)[0]; b = ((const float4 *)p)[1]; }
+    __device__ __forceinline__ void zero() { a = make_float4(0, 0, 0, 0); b = a; }
+    __device__ __forceinline__ void store(void *p) const { ((float4 *)p)[0] = a; ((float4 *)p)[1] = b; }
+    __device__ __forceinline__ void get(float *f) const {
+        f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+    }
+};
 
 // Table whose id is stored at position pos of token t's code row.
 __device__ __forceinline__ int table_at(int pos, int t, int S) {

@@ -33,31 +33,6 @@ struct DecodeArgs {
     int Hq, max_k, n_split, out_dtype;
 };
 
-template <typename T> struct Row8;     // 8 consecutive elements of a K/V row as floats
-template <> struct Row8<uint16_t> {
-    uint4 raw;
-    __device__ __forceinline__ void load(const void *p) { raw = *(const uint4 *)p; }
-    __device__ __forceinline__ void zero() { raw = make_uint4(0, 0, 0, 0); }
-    __device__ __forceinline__ void store(void *p) const { *(uint4 *)p = raw; }
-    __device__ __forceinline__ void get(float *f) const {
-        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            f[2 * i] = __uint_as_float(w[i] << 16);
-            f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
-        }
-    }
-};
-template <> struct Row8<float> {
-    float4 a, b;
-    __device__ __forceinline__ void load(const void *p) { a = ((const float4 *)p)[0]; b = ((const float4 *)p)[1]; }
-    __device__ __forceinline__ void zero() { a = make_float4(0, 0, 0, 0); b = a; }
-    __device__ __forceinline__ void store(void *p) const { ((float4 *)p)[0] = a; ((float4 *)p)[1] = b; }
-    __device__ __forceinline__ void get(float *f) const {
-        f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
-    }
-};
-
 // two adjacent elements of an LDS row as floats
 __device__ __forceinline__ float2 pair_f32(const uint16_t *p) {
     const uint32_t w = *(const uint32_t *)p;

@@ -609,6 +609,92 @@ def test_decode_step_select_paths_agree(case):
     ctx.close()
 
 
+# ------------------------------------------------------------------ value norms, sink / window tokens
+
+@pytest.mark.parametrize("kv_dtype,d", [(wl.BF16, 128), (wl.F32, 64), (wl.BF16, 256)])
+def test_value_norms_match_oracle(kv_dtype, d):
+    """socket_value_norms over a prefill range and over one appended row; rows outside the
+    range are left alone.  fp32 sum of d squares against the oracle's fp64: <= 2e-6 relative."""
+    _need_gpu()
+    B, Hkv, n = 2, 2, 1000 + 8
+    layer = small_layer(seed=81, B=B, Hq=Hkv, Hkv=Hkv, d=d, n=n, L=16, P=4, k=8, kv_dtype=kv_dtype)
+    ctx = hz.make_ctx(layer)
+    Vd = hz.dev(layer.V, kv_dtype)
+    vn = torch.full((B, Hkv, n), -1.0, dtype=torch.float32, device="cuda")
+    begin, count = np.array([0, 5], dtype=np.int32), np.array([777, 640], dtype=np.int32)
+    ctx.value_norms(Vd, hz.i32(begin), hz.i32(count), B, 777, vn)
+    ctx.value_norms(Vd, hz.i32(np.array([900, 901])), hz.i32(np.array([1, 1])), B, 1, vn)
+    got = vn.cpu().numpy()
+    for b in range(B):
+        for h in range(Hkv):
+            want = oracle.value_norms(layer.V[b, h])
+            touched = np.zeros(n, dtype=bool)
+            touched[begin[b]:begin[b] + count[b]] = True
+            touched[900 + b] = True
+            assert np.abs(got[b, h][touched] - want[touched]).max() <= 2e-6 * want.max()
+            assert (got[b, h][~touched] == -1.0).all()
+    ctx.close()
+
+
+def test_forced_sink_and_window_tokens_through_the_chain():
+    """socket_set_forced_tokens: the scores of the first n_sink and last n_window tokens of each
+    sequence are +inf (others unchanged), the selection contains them all, and the fused step
+    agrees with the separate calls and with the oracle's TopK on the same scores."""
+    _need_gpu()
+    B, Hkv, G, L, P = 2, 2, 4, 64, 8
+    n = 5008
+    lens = np.array([5000, 1203], dtype=np.int32)
+    layer = small_layer(seed=82, B=B, Hq=Hkv * G, Hkv=Hkv, n=n, L=L, P=P, k=[200, 150], seq_len=lens)
+    ctx = hz.make_ctx(layer)
+    Kd, Vd, qd, Wd = (hz.dev(x, layer.kv_dtype) for x in (layer.K, layer.V, layer.q, layer.W))
+    max_k = int(layer.k.max())
+
+    def fresh():
+        return dict(codes=torch.zeros((B, Hkv, n, hz.lpad_of(L)), dtype=torch.uint8, device="cuda"),
+                    scores=torch.zeros((B, Hkv, n), dtype=torch.float32, device="cuda"),
+                    idx=torch.zeros((B, Hkv, max_k), dtype=torch.int32, device="cuda"),
+                    nsel=torch.zeros((B, Hkv), dtype=torch.int32, device="cuda"),
+                    out=torch.zeros((B, layer.Hq, layer.d), dtype=torch.float32, device="cuda"))
+    a, f = fresh(), fresh()
+    kk, zero, one = hz.i32(layer.k), hz.i32(np.zeros(B)), hz.i32(np.ones(B))
+    start = lens - 1
+    for t in (a, f):
+        ctx.hash_keys(Kd, Wd, zero, hz.i32(start), B, n, t["codes"])
+    pos, ln = hz.i32(start), hz.i32(lens)
+    ctx.hash_keys(Kd, Wd, pos, one, B, 1, a["codes"])
+    ctx.score(qd, a["codes"], Wd, 0.5, ln, B, a["scores"])
+    plain = a["scores"].cpu().numpy().copy()
+
+    n_sink, n_window = 4, 124
+    ctx.set_forced_tokens(n_sink, n_window)
+    ctx.score(qd, a["codes"], Wd, 0.5, ln, B, a["scores"])
+    ctx.topk_select(a["scores"], ln, kk, B, a["idx"], a["nsel"])
+    ctx.sparse_decode(qd, Kd, Vd, a["idx"], a["nsel"], B, 1.0, a["out"])
+    ctx.decode_step(qd, Kd, Vd, f["codes"], Wd, 0.5, pos, kk, B, 1.0, f["scores"], f["idx"], f["nsel"], f["out"])
+    torch.cuda.synchronize()
+    for key in a:
+        assert torch.equal(a[key], f[key]), key
+    sc, idx, nsel = (f[key].cpu().numpy() for key in ("scores", "idx", "nsel"))
+    for b in range(B):
+        for h in range(Hkv):
+            want = oracle.force_tokens(plain[b, h].astype(np.float64), int(lens[b]), n_sink, n_window)
+            assert (sc[b, h] == want.astype(np.float32)).all()          # +inf where forced, untouched elsewhere
+            want_idx, cnt = oracle.topk(want, int(layer.k[b]))
+            assert nsel[b, h] == cnt
+            assert (np.sort(want_idx[:cnt]) == idx[b, h, :cnt]).all()
+            forced = set(range(n_sink)) | set(range(int(lens[b]) - n_window, int(lens[b])))
+            assert forced <= set(idx[b, h, :cnt].tolist())
+    # more forced tokens than k: the k smallest positions among them are kept
+    ctx.set_forced_tokens(300, 300)
+    ctx.decode_step(qd, Kd, Vd, f["codes"], Wd, 0.5, pos, kk, B, 1.0, f["scores"], f["idx"], f["nsel"], f["out"])
+    torch.cuda.synchronize()
+    assert (f["idx"][0, 0, :200].cpu().numpy() == np.arange(200)).all()
+    ctx.set_forced_tokens(0, 0)
+    ctx.score(qd, a["codes"], Wd, 0.5, ln, B, a["scores"])
+    assert (a["scores"].cpu().numpy() == plain).all()
+    ctx.close()
+
+
 # ------------------------------------------------------------------ paged K/V/ids (configs[3] layout)
 
 def paged_setup(seed, B, Hq, Hkv, n_cap, L, P, lens, k, page=16, kv_dtype=wl.BF16):
