@@ -184,6 +184,11 @@ def main():
             g.close()
         cur_len = int(length[0])
 
+        # ---------------- dense attention over the whole context on the same GPU (Eq. 1) ----
+        g = stage_graph(lambda li, K, V, q, W, codes: ctx.dense_decode(q, K, V, length, 1, 1.0, out[li]))
+        stage_us["dense_decode_baseline"] = timed(g.launch, 5) * 1e3 / NL
+        g.close()
+
         # ---------------- the paper's evaluation protocol on the same step -----------------
         # value-norm weighted ranking (Alg. 3) and 4 sink + 124 local-window tokens always kept
         vns = [torch.empty((1, Hkv, n_alloc), dtype=torch.float32, device="cuda") for _ in layers]
@@ -242,6 +247,9 @@ def main():
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": score_gbs / HBM_PEAK_GBS,
                      "traffic": traffic, "algorithmic_bytes": score_bytes,
                      "avg_launch_us": stage_us["score"]},
+        "dense_baseline": {"us_per_layer": stage_us["dense_decode_baseline"],
+                           "gbs": Hkv * cur_len * 4 * d / (stage_us["dense_decode_baseline"] * 1e-6) / 1e9,
+                           "sparse_step_speedup": stage_us["dense_decode_baseline"] / stage_us["fused_decode_step"]},
         "value_norms_prefill": {"us_per_layer": t_norms_ms * 1e3 / NL,
                                 "gbs": Hkv * n_alloc * (d * 2 + 4) / (t_norms_ms * 1e-3 / NL) / 1e9},
         "hash_prefill": {"ms_per_layer": t_prefill_ms / NL,

@@ -202,6 +202,16 @@ int socket_sparse_decode(socket_ctx *ctx, const void *q, const void *K, const vo
                          int32_t out_dtype, void *out, void *stream);
 
 /*
+ * Eq. 1 (dense softmax attention over every token t < seq_len[b]), with the same split-K
+ * kernels as socket_sparse_decode: the reference the sparse path is compared against on the
+ * same GPU (the paper's throughput figures are relative to dense decoding).  An empty
+ * sequence gives zeros.  seq_len: device int32 [batch].
+ */
+int socket_dense_decode(socket_ctx *ctx, const void *q, const void *K, const void *V,
+                        const int32_t *block_table, const int32_t *seq_len, int32_t batch,
+                        float scale, int32_t out_dtype, void *out, void *stream);
+
+/*
  * One decode step for one attention layer, fused: the caller has already written the new
  * key/value rows at position pos[b] of K and V.  Equivalent to
  *     socket_hash_keys(rows pos[b] .. pos[b])            (Alg. 1 on the appended key)

@@ -54,6 +54,7 @@ def lib():
         L.socket_score_keys.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp]
         L.socket_topk_select.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp]
         L.socket_sparse_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, f32, i32, vp, vp]
+        L.socket_dense_decode.argtypes = [vp, vp, vp, vp, vp, vp, i32, f32, i32, vp, vp]
         L.socket_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, i32, f32, vp, vp, vp,
                                          i32, vp, vp]
         L.socket_strerror.argtypes = [ctypes.c_int]
@@ -70,7 +71,7 @@ def lib():
 EXPORTS = ("socket_validate_params", "socket_codes_per_token", "socket_code_position",
            "socket_create", "socket_destroy", "socket_scratch_bytes", "socket_hash_keys",
            "socket_value_norms", "socket_set_forced_tokens",
-           "socket_score", "socket_soft_hash", "socket_score_keys", "socket_topk_select", "socket_sparse_decode", "socket_decode_step", "socket_strerror",
+           "socket_score", "socket_soft_hash", "socket_score_keys", "socket_topk_select", "socket_sparse_decode", "socket_dense_decode", "socket_decode_step", "socket_strerror",
            "socket_last_hip_error", "socket_graph_begin", "socket_graph_end",
            "socket_graph_launch", "socket_graph_destroy")
 
@@ -183,6 +184,11 @@ class Context:
                                                float(scale), out_dtype, _ptr(out), _stream(stream)),
                     "socket_sparse_decode")
 
+    def dense_decode(self, q, K, V, seq_len, batch, scale, out, block_table=None, stream=None):
+        out_dtype = F32 if out.dtype == torch.float32 else BF16
+        self._check(lib().socket_dense_decode(self._h, _ptr(q), _ptr(K), _ptr(V), _ptr(block_table),
+                                              _ptr(seq_len), batch, float(scale), out_dtype, _ptr(out),
+                                              _stream(stream)), "socket_dense_decode")
 
     def decode_step(self, q, K, V, codes, proj, tau, pos, k, batch, scale, scores, idx, n_selected, out,
                     vnorm=None, block_table=None, stream=None):

@@ -120,7 +120,7 @@ int socket_create(socket_ctx **out, const socket_params *p) {
     const int64_t sz_cand = BH * g.max_n * 4;
     const int64_t sz_staged = BH * g.max_k * 4;
     const int64_t sz_seq = (int64_t)g.max_batch * 4;
-    const int64_t sz_part = (int64_t)g.max_batch * g.Hq * g.n_split * (g.d + 2) * 4;
+    const int64_t sz_part = (int64_t)g.max_batch * g.Hq * (g.n_split > kDenseSplits ? g.n_split : kDenseSplits) * (g.d + 2) * 4;
     ctx->scratch_bytes = sz_wfrag + sz_tables + sz_tstats + sz_hist + sz_cnt + 2 * sz_cand + sz_staged + sz_part + sz_seq;
     bool ok = hipMalloc((void **)&ctx->tables, sz_tables) == hipSuccess &&
               hipMalloc((void **)&ctx->tstats, sz_tstats) == hipSuccess &&
@@ -228,6 +228,16 @@ int socket_topk_select(socket_ctx *ctx, const float *scores, const int32_t *seq_
     if (!ctx || !scores || !seq_len || !k || !idx || !n_selected) return SOCKET_EINVAL;
     if (!batch_ok(ctx, batch)) return SOCKET_EINVAL;
     return launch_topk(ctx, scores, seq_len, k, batch, idx, n_selected, sk::kHistNone, (hipStream_t)stream);
+}
+
+int socket_dense_decode(socket_ctx *ctx, const void *q, const void *K, const void *V,
+                        const int32_t *block_table, const int32_t *seq_len, int32_t batch,
+                        float scale, int32_t out_dtype, void *out, void *stream) {
+    if (!ctx || !q || !K || !V || !seq_len || !out) return SOCKET_EINVAL;
+    if (!batch_ok(ctx, batch) || !paging_ok(ctx, block_table)) return SOCKET_EINVAL;
+    if (out_dtype != SOCKET_F32 && out_dtype != SOCKET_BF16) return SOCKET_EINVAL;
+    return launch_dense_decode(ctx, q, K, V, block_table, seq_len, batch, scale, out_dtype, out,
+                               (hipStream_t)stream);
 }
 
 int socket_decode_step(socket_ctx *ctx, const void *q, const void *K, const void *V, void *codes,

@@ -22,6 +22,7 @@ constexpr int kScoreThreads = SK_SCORE_THREADS;
 constexpr int kScoreU = SK_SCORE_U;          // 16-byte loads a lane keeps in flight
 constexpr int kDecodeThreads = 256;
 constexpr int kDecodeChunk = 64;     // selected rows a decode workgroup handles per pass
+constexpr int kDenseSplits = 64;     // splits per (sequence, KV head) of the dense attention baseline
 constexpr int kCounterStride = 16;   // uint32 counters per (sequence, KV head)
 constexpr int kThrStride = 16;       // uint32 words of the top-k threshold record per (sequence, KV head)
 constexpr int kThrBinLo = 8;         // words of the record that hold the adaptive binning (float bits): offset,
@@ -101,6 +102,9 @@ int launch_score_keys(socket_ctx *ctx, const void *codes, const float *vnorm,
 // hist_mode: what the context's histogram already holds about `scores` (HistMode)
 int launch_topk(socket_ctx *ctx, const float *scores, const int32_t *seq_len, const int32_t *k,
                 int batch, int32_t *idx, int32_t *n_selected, int hist_mode, hipStream_t st);
+int launch_dense_decode(socket_ctx *ctx, const void *q, const void *K, const void *V,
+                        const int32_t *block_table, const int32_t *seq_len, int batch, float scale,
+                        int out_dtype, void *out, hipStream_t st);
 int launch_value_norms(socket_ctx *ctx, const void *V, const int32_t *block_table,
                        const int32_t *row_begin, const int32_t *row_count, int batch, int max_rows,
                        float *vnorm, hipStream_t st);

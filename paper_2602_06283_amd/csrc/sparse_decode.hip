@@ -31,6 +31,7 @@ struct DecodeArgs {
     RowMap map;
     float scale;
     int Hq, max_k, n_split, out_dtype;
+    const int32_t *seq_len;   // dense variant only
 };
 
 // two adjacent elements of an LDS row as floats
@@ -40,7 +41,10 @@ __device__ __forceinline__ float2 pair_f32(const uint16_t *p) {
 }
 __device__ __forceinline__ float2 pair_f32(const float *p) { return *(const float2 *)p; }
 
-template <typename T, int D, int G>
+// DENSE = false: the rows are the selected tokens idx[...] (Eq. 2).  DENSE = true: the rows
+// are all tokens below seq_len (Eq. 1), each split takes a contiguous range of them, and the
+// next chunk's rows are loaded while the current chunk is worked on.
+template <typename T, int D, int G, bool DENSE>
 __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(DecodeArgs a) {
     constexpr int LPR = D / 8;                       // lanes per row
     constexpr int RPW = 64 / LPR;                    // rows per wavefront pass
@@ -73,11 +77,18 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(DecodeArg
     const float ninf = -__builtin_inff();
 
     // Splits own fixed slices of the max_k-long index row, so the index loads do not have to
-    // wait for the selected count; entries at or beyond the count are ignored.
-    const int per = (a.max_k + a.n_split - 1) / a.n_split;
+    // wait for the selected count; entries at or beyond the count are ignored.  (Dense: whole
+    // chunks of the sequence.)
+    int total = a.max_k;
+    if (DENSE) {
+        total = a.seq_len[b];
+        total = total < 0 ? 0 : (total > a.map.max_n ? a.map.max_n : total);
+    }
+    const int per = DENSE ? (((total + CH - 1) / CH + a.n_split - 1) / a.n_split) * CH
+                          : (total + a.n_split - 1) / a.n_split;
     const int r_begin = split * per;
-    const int r_end = min(a.max_k, r_begin + per);
-    const int32_t *idx = a.idx + (int64_t)bh * a.max_k;
+    const int r_end = min(total, r_begin + per);
+    const int32_t *idx = DENSE ? nullptr : a.idx + (int64_t)bh * a.max_k;
 
     SK_STAMP3(0);
     float qf[G][8];
@@ -96,33 +107,54 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(DecodeArg
     }
     __syncthreads();
 
-    for (int c0 = r_begin; c0 < r_end; c0 += CH) {
-        // ---- rows of this chunk
-        if (tid < CH) {
-            int r = c0 + tid;
-            int64_t row = -1;
-            if (r < r_end) {
-                int t = idx[r];
-                int nsel = a.n_selected[bh];
-                if (r < nsel && t >= 0 && t < a.map.max_n) row = a.map.row(b, h, t);
-            }
-            s_row[tid] = row;
-        }
-        __syncthreads();
-        SK_STAMP3(1);
-
-        // ---- gather this chunk's K and V rows together (one memory latency, not two)
-        Row8<T> kr[NPASS], vr[NPASS];
-        int64_t rows[NPASS];
+    Row8<T> kr[NPASS], vr[NPASS], kn[NPASS], vn[NPASS];
+    int64_t rows[NPASS], rown[NPASS];
+    // dense: this lane's rows of the chunk starting at c0, straight from the token positions
+    auto load_dense = [&](int c0, Row8<T> *kd, Row8<T> *vd, int64_t *rd) {
 #pragma unroll
         for (int p = 0; p < NPASS; ++p) {
-            rows[p] = s_row[p * RPP + wave * RPW + rl];
-            if (rows[p] >= 0) {
-                kr[p].load((const T *)a.K + rows[p] * D + sub * 8);
-                vr[p].load((const T *)a.V + rows[p] * D + sub * 8);
+            const int t = c0 + p * RPP + wave * RPW + rl;
+            rd[p] = t < r_end ? a.map.row(b, h, t) : -1;
+            if (rd[p] >= 0) {
+                kd[p].load((const T *)a.K + rd[p] * D + sub * 8);
+                vd[p].load((const T *)a.V + rd[p] * D + sub * 8);
             } else {
-                kr[p].zero();
-                vr[p].zero();
+                kd[p].zero();
+                vd[p].zero();
+            }
+        }
+    };
+    if (DENSE && r_begin < r_end) load_dense(r_begin, kr, vr, rows);
+
+    for (int c0 = r_begin; c0 < r_end; c0 += CH) {
+        if (DENSE) {
+            if (c0 + CH < r_end) load_dense(c0 + CH, kn, vn, rown);
+        } else {
+            // ---- rows of this chunk
+            if (tid < CH) {
+                int r = c0 + tid;
+                int64_t row = -1;
+                if (r < r_end) {
+                    int t = idx[r];
+                    int nsel = a.n_selected[bh];
+                    if (r < nsel && t >= 0 && t < a.map.max_n) row = a.map.row(b, h, t);
+                }
+                s_row[tid] = row;
+            }
+            __syncthreads();
+            SK_STAMP3(1);
+
+            // ---- gather this chunk's K and V rows together (one memory latency, not two)
+#pragma unroll
+            for (int p = 0; p < NPASS; ++p) {
+                rows[p] = s_row[p * RPP + wave * RPW + rl];
+                if (rows[p] >= 0) {
+                    kr[p].load((const T *)a.K + rows[p] * D + sub * 8);
+                    vr[p].load((const T *)a.V + rows[p] * D + sub * 8);
+                } else {
+                    kr[p].zero();
+                    vr[p].zero();
+                }
             }
         }
         // ---- logits: scale * k.q for every query head of the group
@@ -213,6 +245,14 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(DecodeArg
             }
         }
         __syncthreads();
+        if (DENSE) {
+#pragma unroll
+            for (int p = 0; p < NPASS; ++p) {
+                kr[p] = kn[p];
+                vr[p] = vn[p];
+                rows[p] = rown[p];
+            }
+        }
     }
 
     SK_STAMP3(5);
@@ -270,26 +310,56 @@ __global__ __launch_bounds__(D) void decode_merge_kernel(DecodeArgs a) {
     else ((uint16_t *)a.out)[head * D + c] = f32_to_bf16_rne(y);
 }
 
-template <typename T, int D>
+template <typename T, int D, bool DENSE>
 static int launch_decode_g(const DecodeArgs &a, int G, dim3 grid, hipStream_t st) {
     switch (G) {
-        case 1: hipLaunchKernelGGL((sparse_decode_kernel<T, D, 1>), grid, dim3(kDecodeThreads), 0, st, a); break;
-        case 2: hipLaunchKernelGGL((sparse_decode_kernel<T, D, 2>), grid, dim3(kDecodeThreads), 0, st, a); break;
-        case 4: hipLaunchKernelGGL((sparse_decode_kernel<T, D, 4>), grid, dim3(kDecodeThreads), 0, st, a); break;
-        case 8: hipLaunchKernelGGL((sparse_decode_kernel<T, D, 8>), grid, dim3(kDecodeThreads), 0, st, a); break;
+        case 1: hipLaunchKernelGGL((sparse_decode_kernel<T, D, 1, DENSE>), grid, dim3(kDecodeThreads), 0, st, a); break;
+        case 2: hipLaunchKernelGGL((sparse_decode_kernel<T, D, 2, DENSE>), grid, dim3(kDecodeThreads), 0, st, a); break;
+        case 4: hipLaunchKernelGGL((sparse_decode_kernel<T, D, 4, DENSE>), grid, dim3(kDecodeThreads), 0, st, a); break;
+        case 8: hipLaunchKernelGGL((sparse_decode_kernel<T, D, 8, DENSE>), grid, dim3(kDecodeThreads), 0, st, a); break;
         default: return SOCKET_EUNSUPPORTED;
     }
     return SOCKET_OK;
 }
 
-template <typename T>
+template <typename T, bool DENSE>
 static int launch_decode_d(const DecodeArgs &a, int D, int G, dim3 grid, hipStream_t st) {
     switch (D) {
-        case 64: return launch_decode_g<T, 64>(a, G, grid, st);
-        case 128: return launch_decode_g<T, 128>(a, G, grid, st);
-        case 256: return launch_decode_g<T, 256>(a, G, grid, st);
+        case 64: return launch_decode_g<T, 64, DENSE>(a, G, grid, st);
+        case 128: return launch_decode_g<T, 128, DENSE>(a, G, grid, st);
+        case 256: return launch_decode_g<T, 256, DENSE>(a, G, grid, st);
         default: return SOCKET_EUNSUPPORTED;
     }
+}
+
+static int launch_merge(const DecodeArgs &a, const Geometry &g, int batch, hipStream_t st) {
+    dim3 mgrid(g.G, g.Hkv, batch);
+    switch (g.d) {
+        case 64: hipLaunchKernelGGL(decode_merge_kernel<64>, mgrid, dim3(64), 0, st, a); break;
+        case 128: hipLaunchKernelGGL(decode_merge_kernel<128>, mgrid, dim3(128), 0, st, a); break;
+        case 256: hipLaunchKernelGGL(decode_merge_kernel<256>, mgrid, dim3(256), 0, st, a); break;
+        default: return SOCKET_EUNSUPPORTED;
+    }
+    return SOCKET_OK;
+}
+
+// Eq. 1: every token below seq_len, 64 splits per (sequence, KV head)
+int launch_dense_decode(socket_ctx *ctx, const void *q, const void *K, const void *V,
+                        const int32_t *block_table, const int32_t *seq_len, int batch, float scale,
+                        int out_dtype, void *out, hipStream_t st) {
+    const Geometry &g = ctx->g;
+    DecodeArgs a;
+    a.q = q; a.K = K; a.V = V; a.idx = nullptr; a.n_selected = nullptr; a.seq_len = seq_len;
+    a.partials = ctx->partials; a.counters = ctx->counters; a.out = out;
+    a.map = RowMap{block_table, g.Hkv, g.max_n, g.page, g.max_blocks, g.num_blocks};
+    a.scale = scale; a.Hq = g.Hq; a.max_k = g.max_k; a.n_split = kDenseSplits; a.out_dtype = out_dtype;
+    dim3 grid(kDenseSplits, g.Hkv, batch);
+    int rc = g.kv_dtype == SOCKET_F32 ? launch_decode_d<float, true>(a, g.d, g.G, grid, st)
+                                      : launch_decode_d<uint16_t, true>(a, g.d, g.G, grid, st);
+    if (rc != SOCKET_OK) return rc;
+    rc = launch_merge(a, g, batch, st);
+    if (rc != SOCKET_OK) return rc;
+    return record_hip(ctx, hipGetLastError());
 }
 
 int launch_sparse_decode(socket_ctx *ctx, const void *q, const void *K, const void *V,
@@ -301,17 +371,13 @@ int launch_sparse_decode(socket_ctx *ctx, const void *q, const void *K, const vo
     a.partials = ctx->partials; a.counters = ctx->counters; a.out = out;
     a.map = RowMap{block_table, g.Hkv, g.max_n, g.page, g.max_blocks, g.num_blocks};
     a.scale = scale; a.Hq = g.Hq; a.max_k = g.max_k; a.n_split = g.n_split; a.out_dtype = out_dtype;
+    a.seq_len = nullptr;
     dim3 grid(g.n_split, g.Hkv, batch);
-    int rc = g.kv_dtype == SOCKET_F32 ? launch_decode_d<float>(a, g.d, g.G, grid, st)
-                                      : launch_decode_d<uint16_t>(a, g.d, g.G, grid, st);
+    int rc = g.kv_dtype == SOCKET_F32 ? launch_decode_d<float, false>(a, g.d, g.G, grid, st)
+                                      : launch_decode_d<uint16_t, false>(a, g.d, g.G, grid, st);
     if (rc != SOCKET_OK) return rc;
-    dim3 mgrid(g.G, g.Hkv, batch);
-    switch (g.d) {
-        case 64: hipLaunchKernelGGL(decode_merge_kernel<64>, mgrid, dim3(64), 0, st, a); break;
-        case 128: hipLaunchKernelGGL(decode_merge_kernel<128>, mgrid, dim3(128), 0, st, a); break;
-        case 256: hipLaunchKernelGGL(decode_merge_kernel<256>, mgrid, dim3(256), 0, st, a); break;
-        default: return SOCKET_EUNSUPPORTED;
-    }
+    rc = launch_merge(a, g, batch, st);
+    if (rc != SOCKET_OK) return rc;
     return record_hip(ctx, hipGetLastError());
 }
 

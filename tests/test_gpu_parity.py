@@ -609,6 +609,30 @@ def test_decode_step_select_paths_agree(case):
     ctx.close()
 
 
+# ------------------------------------------------------------------ dense baseline (Eq. 1)
+
+@pytest.mark.parametrize("kv_dtype,d,G", [(wl.BF16, 128, 4), (wl.F32, 64, 1), (wl.BF16, 256, 2)])
+def test_dense_decode_matches_oracle(kv_dtype, d, G):
+    """socket_dense_decode = Eq. 1 over every token below seq_len: ragged lengths (several
+    chunks per split, a partial last chunk, a sequence shorter than one chunk, an empty one)."""
+    _need_gpu()
+    B, Hkv, n = 4, 2, 9000 + 8
+    lens = np.array([9000, 4097, 37, 0], dtype=np.int32)
+    layer = small_layer(seed=91, B=B, Hq=Hkv * G, Hkv=Hkv, d=d, n=n, L=16, P=4, k=8, kv_dtype=kv_dtype, seq_len=lens)
+    ctx = hz.make_ctx(layer)
+    Kd, Vd, qd = (hz.dev(x, kv_dtype) for x in (layer.K, layer.V, layer.q))
+    out = torch.full((B, layer.Hq, d), 7.0, dtype=torch.float32, device="cuda")
+    ctx.dense_decode(qd, Kd, Vd, hz.i32(lens), B, 1.0, out)
+    got = out.cpu().numpy()
+    for b in range(B):
+        for hq in range(layer.Hq):
+            h = hq // G
+            ln = int(lens[b])
+            want = oracle.dense_decode(layer.q[b, hq], layer.K[b, h, :ln], layer.V[b, h, :ln]) if ln else np.zeros(d)
+            assert np.abs(got[b, hq] - want).max() <= 1e-4, (b, hq)
+    ctx.close()
+
+
 # ------------------------------------------------------------------ value norms, sink / window tokens
 
 @pytest.mark.parametrize("kv_dtype,d", [(wl.BF16, 128), (wl.F32, 64), (wl.BF16, 256)])
