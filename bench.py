@@ -184,6 +184,29 @@ def main():
             g.close()
         cur_len = int(length[0])
 
+        # ---------------- how good is the selection?  (evaluation only, layer 0) ------------
+        # Against exact q.k on the same synthetic layer: share of each query head's softmax
+        # mass that the selected tokens carry, and precision of the selected set against the
+        # exact top-k of the group-mean logit.  Soft scores vs the hard collision count (Eq. 3).
+        def selection_quality(hard):
+            K0, V0, q0, W0, codes0 = layers[0]
+            if hard:
+                ctx.hard_hash(q0, W0, 1)
+                ctx.score_keys(codes0, length, 1, scores)
+            else:
+                ctx.score(q0, codes0, W0, tau, length, 1, scores)
+            ctx.topk_select(scores, length, k_t, 1, idx, nsel)
+            stream.synchronize()
+            G = Hq // Hkv
+            logits = torch.einsum("hgd,hnd->hgn", q0[0].float().view(Hkv, G, d), K0[0, :, :cur_len].float())
+            mass = torch.softmax(logits, dim=-1)
+            sel = idx[0].long()                                          # [Hkv, k]
+            got_mass = torch.gather(mass, 2, sel[:, None, :].expand(-1, G, -1)).sum(-1)   # [Hkv, G]
+            exact = torch.topk(logits.mean(1), k, dim=-1).indices        # [Hkv, k]
+            hits = sum(len(set(sel[h].tolist()) & set(exact[h].tolist())) for h in range(Hkv))
+            return {"softmax_mass_kept": float(got_mass.mean()), "precision_vs_exact_topk": hits / (Hkv * k)}
+        quality = {"soft": selection_quality(False), "hard": selection_quality(True)}
+
         # ---------------- dense attention over the whole context on the same GPU (Eq. 1) ----
         g = stage_graph(lambda li, K, V, q, W, codes: ctx.dense_decode(q, K, V, length, 1, 1.0, out[li]))
         stage_us["dense_decode_baseline"] = timed(g.launch, 5) * 1e3 / NL
@@ -213,7 +236,7 @@ def main():
     score_bytes = Hkv * cur_len * (Lpad * 1 + 4)
     score_gbs = score_bytes / (stage_us["score"] * 1e-6) / 1e9
     chain_bytes = Hkv * (cur_len * (Lpad + 8) + k * (4 * d + 8))
-    chain_us = stage_us["score"] + stage_us["topk"] + stage_us["sparse_decode"]
+    chain_us = stage_us["fused_decode_step"]
     # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by a plain copy of
     # known size (profiles/score_kernel_128k.md); not measured for other workloads
     traffic = MEASURED_SCORE_TRAFFIC.get((args.workload, NL))
@@ -240,13 +263,14 @@ def main():
         "keys_scored_per_s": Hkv * cur_len / (stage_us["score"] * 1e-6),
         "layer_step_us": ms_per_step * 1e3 / NL,
         "stage_us_per_layer": stage_us,
-        "chain": {"score_topk_decode_us": chain_us, "algorithmic_bytes": chain_bytes,
+        "chain": {"fused_step_us": chain_us, "algorithmic_bytes": chain_bytes,
                   "gbs": chain_bytes / (chain_us * 1e-6) / 1e9,
                   "frac_of_hbm_peak": chain_bytes / (chain_us * 1e-6) / 1e9 / HBM_PEAK_GBS},
         "roofline": {"kernel": "score_kernel", "bound": "hbm", "achieved": score_gbs,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": score_gbs / HBM_PEAK_GBS,
                      "traffic": traffic, "algorithmic_bytes": score_bytes,
                      "avg_launch_us": stage_us["score"]},
+        "selection_quality_layer0": quality,
         "dense_baseline": {"us_per_layer": stage_us["dense_decode_baseline"],
                            "gbs": Hkv * cur_len * 4 * d / (stage_us["dense_decode_baseline"] * 1e-6) / 1e9,
                            "sparse_step_speedup": stage_us["dense_decode_baseline"] / stage_us["fused_decode_step"]},

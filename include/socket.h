@@ -172,6 +172,15 @@ int socket_score(socket_ctx *ctx, const void *q, const void *codes, const void *
  */
 int socket_soft_hash(socket_ctx *ctx, const void *q, const void *proj, float tau, int32_t batch,
                      void *stream);
+/*
+ * Eq. 3, hard form (the traditional LSH scorer the paper compares against): instead of the
+ * graded probabilities, the context's tables get 1 at the query's own bucket of every table
+ * and 0 elsewhere (averaged over the G queries of a group), so that a following
+ * socket_score_keys returns the collision count  #{ l : b_j^(l) = b_q^(l) }  (its group mean).
+ * The query's bucket follows the same sign rule as socket_hash_keys, on the fp64 projection.
+ */
+int socket_hard_hash(socket_ctx *ctx, const void *q, const void *proj, int32_t batch, void *stream);
+
 int socket_score_keys(socket_ctx *ctx, const void *codes, const float *vnorm,
                       const int32_t *block_table, const int32_t *seq_len, int32_t batch,
                       float *scores, void *stream);

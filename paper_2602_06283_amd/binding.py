@@ -51,6 +51,7 @@ def lib():
         L.socket_set_forced_tokens.argtypes = [vp, i32, i32]
         L.socket_score.argtypes = [vp, vp, vp, vp, f32, vp, vp, vp, i32, vp, vp]
         L.socket_soft_hash.argtypes = [vp, vp, vp, f32, i32, vp]
+        L.socket_hard_hash.argtypes = [vp, vp, vp, i32, vp]
         L.socket_score_keys.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp]
         L.socket_topk_select.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp]
         L.socket_sparse_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, f32, i32, vp, vp]
@@ -71,7 +72,7 @@ def lib():
 EXPORTS = ("socket_validate_params", "socket_codes_per_token", "socket_code_position",
            "socket_create", "socket_destroy", "socket_scratch_bytes", "socket_hash_keys",
            "socket_value_norms", "socket_set_forced_tokens",
-           "socket_score", "socket_soft_hash", "socket_score_keys", "socket_topk_select", "socket_sparse_decode", "socket_dense_decode", "socket_decode_step", "socket_strerror",
+           "socket_score", "socket_soft_hash", "socket_hard_hash", "socket_score_keys", "socket_topk_select", "socket_sparse_decode", "socket_dense_decode", "socket_decode_step", "socket_strerror",
            "socket_last_hip_error", "socket_graph_begin", "socket_graph_end",
            "socket_graph_launch", "socket_graph_destroy")
 
@@ -165,6 +166,10 @@ class Context:
     def soft_hash(self, q, proj, tau, batch, stream=None):
         self._check(lib().socket_soft_hash(self._h, _ptr(q), _ptr(proj), float(tau), batch,
                                            _stream(stream)), "socket_soft_hash")
+
+    def hard_hash(self, q, proj, batch, stream=None):
+        self._check(lib().socket_hard_hash(self._h, _ptr(q), _ptr(proj), batch, _stream(stream)),
+                    "socket_hard_hash")
 
     def score_keys(self, codes, seq_len, batch, scores, vnorm=None, block_table=None, stream=None):
         self._check(lib().socket_score_keys(self._h, _ptr(codes), _ptr(vnorm), _ptr(block_table),

@@ -34,6 +34,7 @@ struct ProjectArgs {
     float *tstats;          // [B*Hkv][Lpad]: mean squared deviation of each table's entries from 1/R
     double tau;
     double x_scale;         // 2 / (sqrt(d) * tau)
+    int hard;               // 1: one-hot tables (the query's own bucket), Eq. 3's hard count
     const void *K;          // key cache; null = no append hash
     void *codes;
     const int32_t *pos;     // [B] position of the appended key (append hash only)
@@ -282,7 +283,11 @@ __global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
             const double t = exp(-2.0 * fabs(z));
             const double th = (1.0 - t) * rcp64(1.0 + t);
             const double e = exp(-a.x_scale * th);           // x = 2 tanh|z| / (sqrt(d) tau) >= 0
-            const double big = rcp64(1.0 + e), small = e * big;
+            double big = rcp64(1.0 + e), small = e * big;
+            if (a.hard) {                            // the limit tau -> 0: all mass on the query's side of the plane
+                big = 1.0;
+                small = 0.0;
+            }
             const int slot = (a.mode == kFactor && j >= a.Plo) ? 8 + j - a.Plo : j;
             sig[(g * kPlanePad + slot) * 2 + 1] = z >= 0.0 ? big : small;
             sig[(g * kPlanePad + slot) * 2] = z >= 0.0 ? small : big;
@@ -730,6 +735,8 @@ int launch_project(socket_ctx *ctx, const void *q, const void *proj, float tau, 
                    int32_t *len_out, int batch, hipStream_t st) {
     const Geometry &g = ctx->g;
     ProjectArgs a;
+    a.hard = tau <= 0.0f;                            // internal convention of launch_hard_hash
+    if (a.hard) tau = 1.0f;
     a.q = q; a.W = proj; a.tables = ctx->tables; a.tstats = ctx->tstats; a.tau = (double)tau;
     a.x_scale = 2.0 / (sqrt((double)g.d) * (double)tau);
     a.K = K; a.codes = codes; a.pos = pos; a.count = count; a.len_out = len_out;
@@ -755,6 +762,10 @@ int launch_project(socket_ctx *ctx, const void *q, const void *proj, float tau, 
     if (set_lds_limit((const void *)fn, lds) != SOCKET_OK) return SOCKET_EHIP;
     hipLaunchKernelGGL(fn, grid, dim3(256), lds, st, a);
     return record_hip(ctx, hipGetLastError());
+}
+
+int launch_hard_hash(socket_ctx *ctx, const void *q, const void *proj, int batch, hipStream_t st) {
+    return launch_project(ctx, q, proj, 0.0f, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, batch, st);
 }
 
 int launch_soft_hash(socket_ctx *ctx, const void *q, const void *proj, float tau, int batch,

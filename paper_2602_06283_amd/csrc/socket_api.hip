@@ -214,6 +214,12 @@ int socket_soft_hash(socket_ctx *ctx, const void *q, const void *proj, float tau
     return launch_soft_hash(ctx, q, proj, tau, batch, (hipStream_t)stream);
 }
 
+int socket_hard_hash(socket_ctx *ctx, const void *q, const void *proj, int32_t batch, void *stream) {
+    if (!ctx || !q || !proj) return SOCKET_EINVAL;
+    if (!batch_ok(ctx, batch)) return SOCKET_EINVAL;
+    return launch_hard_hash(ctx, q, proj, batch, (hipStream_t)stream);
+}
+
 int socket_score_keys(socket_ctx *ctx, const void *codes, const float *vnorm,
                       const int32_t *block_table, const int32_t *seq_len, int32_t batch,
                       float *scores, void *stream) {

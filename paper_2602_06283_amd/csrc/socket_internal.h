@@ -92,6 +92,7 @@ int launch_hash_keys(socket_ctx *ctx, const void *K, const void *proj, const int
 int launch_project(socket_ctx *ctx, const void *q, const void *proj, float tau, const void *K,
                    void *codes, const int32_t *block_table, const int32_t *pos, const int32_t *count,
                    int32_t *len_out, int batch, hipStream_t st);
+int launch_hard_hash(socket_ctx *ctx, const void *q, const void *proj, int batch, hipStream_t st);
 int launch_soft_hash(socket_ctx *ctx, const void *q, const void *proj, float tau, int batch,
                      hipStream_t st);
 // want_hist: also accumulate a first-level histogram of the scores into the context; returns

@@ -609,6 +609,44 @@ def test_decode_step_select_paths_agree(case):
     ctx.close()
 
 
+# ------------------------------------------------------------------ hard LSH scorer (Eq. 3, hard form)
+
+@pytest.mark.parametrize("L,P,G", [(64, 8, 4), (300, 2, 1), (60, 10, 2)])
+def test_hard_hash_gives_collision_counts(L, P, G):
+    """socket_hard_hash + socket_score_keys = the group mean of the collision counts between
+    each key's bucket ids and each query's own bucket ids (Eq. 3, hard).  The counts are small
+    integers over G, so the comparison is exact unless a query projection lies within 1e-4 of
+    zero (then that table may differ; such queries are skipped)."""
+    _need_gpu()
+    B, Hkv, n = 2, 2, 3000 + 8
+    layer = small_layer(seed=95, B=B, Hq=Hkv * G, Hkv=Hkv, n=n, L=L, P=P, k=16, seq_len=[3000, 1777])
+    ctx = hz.make_ctx(layer)
+    codes = run_hash(ctx, layer, np.zeros(B), layer.seq_len, n)
+    nat = [[hz.codes_to_natural(codes.cpu().numpy().view(hz.code_dtype(P))[b, h], L) for h in range(Hkv)] for b in range(B)]
+    qd, Wd = hz.dev(layer.q, layer.kv_dtype), hz.dev(layer.W, layer.kv_dtype)
+    scores = torch.zeros((B, Hkv, n), dtype=torch.float32, device="cuda")
+    ctx.hard_hash(qd, Wd, B)
+    ctx.score_keys(codes, hz.i32(layer.seq_len), B, scores)
+    got = scores.cpu().numpy()
+    checked = 0
+    for b in range(B):
+        ln = int(layer.seq_len[b])
+        for h in range(Hkv):
+            want = np.zeros(n)
+            clean = True
+            for g in range(G):
+                qc, near = oracle.hash_keys(layer.q[b, h * G + g][None], layer.W[h], L, P)
+                clean = clean and not near.any()
+                want += oracle.hard_score(nat[b][h].astype(np.uint16), qc[0])
+            if not clean:
+                continue
+            checked += 1
+            assert (got[b, h, :ln] == (want[:ln] / G).astype(np.float32)).all()
+            assert np.isneginf(got[b, h, ln:]).all()
+    assert checked >= 1
+    ctx.close()
+
+
 # ------------------------------------------------------------------ dense baseline (Eq. 1)
 
 @pytest.mark.parametrize("kv_dtype,d,G", [(wl.BF16, 128, 4), (wl.F32, 64, 1), (wl.BF16, 256, 2)])
