@@ -70,6 +70,7 @@ def check_codes(layer, codes_t, rows_of):
     (wl.BF16, 3000 // 16 * 16 + 16, 64, 8),   # MFMA kernel, several 64-row tiles, ragged count below
     (wl.BF16, 2048, 16, 4),
     (wl.BF16, 2048, 128, 8),    # two column chunks of 64 tables
+    (wl.BF16, 1024, 100, 8),    # second chunk with 36 live tables: the rest of the row holds 0
     (wl.BF16, 1024, 64, 10),    # uint16 ids, chunks that split a 64-table group
     (wl.BF16, 1024, 60, 10),    # the paper's main (P, L)
     (wl.BF16, 1024, 24, 5),
@@ -110,11 +111,28 @@ def test_hash_keys_append_one_row(kv_dtype, P):
 
 def test_hash_keys_d64_and_d256():
     _need_gpu()
-    for d in (64, 256):
-        layer = small_layer(seed=13, B=1, Hq=2, Hkv=2, d=d, n=1024, L=32, P=8, k=16)
+    for d, L in ((64, 32), (256, 32), (64, 64), (256, 64)):     # L = 64, d = 64: the byte-id MFMA kernel
+        layer = small_layer(seed=13, B=1, Hq=2, Hkv=2, d=d, n=1024, L=L, P=8, k=16)
         ctx = hz.make_ctx(layer)
         codes = run_hash(ctx, layer, [0], [1024], 1024)
         check_codes(layer, codes, lambda b: (0, 1024))
+        ctx.close()
+
+
+def test_hash_keys_unaligned_row_ranges_through_the_mfma_kernels():
+    """Ranges of 64+ rows that start at odd positions (the id rotation follows the token
+    position, not the row's place in the launch), with different lengths per sequence."""
+    _need_gpu()
+    for L, P in ((64, 8), (128, 8), (60, 10)):
+        layer = small_layer(seed=14, B=2, Hq=4, Hkv=2, n=1024, L=L, P=P, k=16)
+        ctx = hz.make_ctx(layer)
+        begins, counts = [5, 77], [200, 131]
+        codes = run_hash(ctx, layer, begins, counts, 200)
+        check_codes(layer, codes, lambda b: (begins[b], counts[b]))
+        raw = codes.cpu().numpy().view(hz.code_dtype(P))
+        fill = 0x55 if P <= 8 else 0x5555
+        for b in range(2):
+            assert (raw[b, :, :begins[b]] == fill).all() and (raw[b, :, begins[b] + counts[b]:] == fill).all()
         ctx.close()
 
 
