@@ -31,7 +31,9 @@ struct ProjectArgs {
     const void *q;          // [B, Hq, d]; null = no soft hash
     const void *W;          // [Hkv, d, L*P]
     float *tables;
-    float *tstats;          // [B*Hkv][Lpad]: mean squared deviation of each table's entries from 1/R
+    float *tstats;          // [B*Hkv][Lpad][3]: mean squared deviation of each table's entries from 1/R;
+                            // sum and sum of squares of 256 sampled value norms
+    const float *vnorm;     // optional [B, Hkv, max_n]: value norms to sample (with the append hash only)
     double tau;
     double x_scale;         // 2 / (sqrt(d) * tau)
     int hard;               // 1: one-hot tables (the query's own bucket), Eq. 3's hard count
@@ -124,7 +126,7 @@ __global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
     float *wf = (float *)(wd + cols * d);                    // [P][d]  the same in fp32 (key path)
     float *kf = wf + cols * d;                               // [d]
     uint32_t *sgn = (uint32_t *)(kf + d);                    // [16] sign bits of the key's projections
-    float *s_dev = (float *)(sgn + 16);                      // [4]
+    float *s_dev = (float *)(sgn + 16);                      // [12]
     SK_STAMP2(0);
 
     // ---- every global load of the kernel is issued here, before the first one is used
@@ -171,6 +173,16 @@ __global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
         if (wanted && tok >= 0 && tok < a.map.max_n) krow = a.map.row(b, h, tok);
         if (krow >= 0 && live && tid < d / EPV) kv = *(const uint4 *)((const T *)a.K + krow * d + tid * EPV);
         if (a.len_out && x == 0 && h == 0 && tid == 0) a.len_out[b] = tok + 1;
+    }
+    // 256 value norms spread over the sequence (tok + 1 tokens): their mean and spread scale the
+    // histogram bins of the weighted scores
+    float nu = 0.0f;
+    const bool sampling = a.vnorm != nullptr && app && soft && live && tok >= 0 && tok < a.map.max_n;
+    if (sampling) {
+        const int seq = tok + 1;
+        int t = (int)((float)(l * 256 + tid) * ((float)seq / (float)(a.L * 256)));
+        t = t < seq ? t : seq - 1;
+        nu = a.vnorm[((int64_t)b * a.Hkv + h) * a.map.max_n + t];
     }
 
     // ---- into LDS as fp32 / fp64, W transposed to [plane][channel]
@@ -348,11 +360,18 @@ __global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
         }
         // spread of this table's entries, from which the scoring pass sizes its histogram bins
         dev2 = row_sum<64>(dev2);
-        if ((tid & 63) == 0) s_dev[tid >> 6] = dev2;
+        const float nu1 = row_sum<64>(nu), nu2 = row_sum<64>(nu * nu);
+        if ((tid & 63) == 0) {
+            s_dev[tid >> 6] = dev2;
+            s_dev[4 + (tid >> 6)] = nu1;
+            s_dev[8 + (tid >> 6)] = nu2;
+        }
         __syncthreads();
-        if (tid == 0)
-            a.tstats[((int64_t)b * a.Hkv + h) * a.Lpad + l] =
-                (float)((double)(s_dev[0] + s_dev[1] + s_dev[2] + s_dev[3]) * inv_r);
+        if (tid < 3) {
+            const float *part = s_dev + 4 * tid;
+            const double sum = (double)(part[0] + part[1] + part[2] + part[3]);
+            a.tstats[(((int64_t)b * a.Hkv + h) * a.Lpad + l) * 3 + tid] = (float)(tid == 0 ? sum * inv_r : sum);
+        }
         if (code_due && tid == 64) write_code();     // off the first wavefront's path
         SK_STAMP2(5);
     } else {
@@ -381,7 +400,7 @@ struct ScoreArgs {
     const int32_t *seq_len;
     float *scores;
     uint32_t *hist;          // optional [B*Hkv][kHistBins]: first-level histogram of the scores
-    const float *tstats;     // [B*Hkv][Lpad] per-table spread (adaptive histogram only)
+    const float *tstats;     // [B*Hkv][Lpad][3] per-table spread, sampled value norms (adaptive histogram only)
     uint32_t *thr;           // [B*Hkv][kThrStride] threshold records: receives the binning
     int hist_mode;           // HistMode of `hist`
     int n_sink, n_window;    // the first n_sink and last n_window tokens of a sequence score +inf
@@ -537,7 +556,17 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
     };
     // Passes u = 0..U-1 of a wavefront cover keys base + u*KPW + kk.  Lane `sub` of a key's
     // group writes the results of passes sub, sub+S, ...
-    auto emit = [&](int base, const float *sum, const bool *dead) {
+    // value-norm weights of the keys this lane emits for a chunk (fetched with the ids, so that
+    // their latency is hidden the same way)
+    constexpr int EPL = U / S;
+    auto load_weights = [&](float *w, int base) {
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) {
+            const int key = base + (j * S + sub) * KPW + kk;
+            w[j] = (vn && key < seq) ? vn[key] : 1.0f;
+        }
+    };
+    auto emit = [&](int base, const float *sum, const bool *dead, const float *w) {
 #pragma unroll
         for (int j = 0; j < U / S; ++j) {
             float v = sum[j * S];
@@ -552,7 +581,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
                 if (dd) {
                     v = ninf;
                 } else {
-                    if (vn) v *= vn[key];
+                    v *= w[j];
                     if (key < a.n_sink || key >= seq - a.n_window) v = __builtin_inff();   // sink / local window
                 }
                 out[key] = v;
@@ -564,21 +593,28 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
             }
         }
     };
-    auto load_set = [&](CodeVec<CB> *cv, bool *dead, int base) {
+    auto load_set = [&](CodeVec<CB> *cv, bool *dead, float *w, int base) {
 #pragma unroll
         for (int u = 0; u < U; ++u) cv[u].load(code_ptr(base + u * KPW + kk, 0, dead[u]));
+        load_weights(w, base);
     };
     auto chunk_base = [&](int r) { return (r * stride + (int)blockIdx.x) * CKEYS + wave * WKEYS; };
 
     constexpr bool PREFETCH = ONE_ROUND;
     CodeVec<CB> setA[U], setB[U];
     bool deadA[U], deadB[U];
-    if (PREFETCH && nround > 0) load_set(setA, deadA, chunk_base(0));
+    float wgtA[EPL], wgtB[EPL];
+    if (PREFETCH && nround > 0) load_set(setA, deadA, wgtA, chunk_base(0));
     // Adaptive histogram: if the keys' bucket ids were uniform, a score would have mean L/R and
     // variance sum_l var_l; bins are laid from four deviations below that mean upwards.
-    float var_part = 0.0f;
+    float var_part = 0.0f, nu1_part = 0.0f, nu2_part = 0.0f;
     if (adaptive && wave == 0)
-        for (int l = lane; l < a.Lpad; l += 64) var_part += a.tstats[bh * a.Lpad + l];
+        for (int l = lane; l < a.Lpad; l += 64) {
+            const float *ts = a.tstats + (bh * a.Lpad + l) * 3;
+            var_part += ts[0];
+            nu1_part += ts[1];
+            nu2_part += ts[2];
+        }
     if (has_table) {            // bucket-probability table -> LDS
         const float4 *src = (const float4 *)(a.tables + bh * a.table_words);
         float4 *dst = (float4 *)tbl;
@@ -601,8 +637,17 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
             for (int i = tid; i < kHistBins; i += kScoreThreads) lhist[i] = 0;
     }
     if (adaptive && wave == 0) {
-        const float mu = (float)a.L / (float)a.R;
-        const float sigma = fmaxf(sqrtf(row_sum<64>(var_part)), fmaxf(mu * 1e-6f, 1e-30f));
+        float mu = (float)a.L / (float)a.R;
+        float var = row_sum<64>(var_part);
+        const float nu1 = row_sum<64>(nu1_part), nu2 = row_sum<64>(nu2_part);
+        if (vn) {
+            // weighted scores nu * s, nu and s taken as independent: moments of the product
+            const float cnt = (float)(a.L * 256);
+            const float mnu = nu1 / cnt, vnu = fmaxf(nu2 / cnt - mnu * mnu, 0.0f);
+            var = mnu * mnu * var + mu * mu * vnu + vnu * var;
+            mu *= mnu;
+        }
+        const float sigma = fmaxf(sqrtf(var), fmaxf(mu * 1e-6f, 1e-30f));
         const float lo = mu - 4.0f * sigma, inv = 1.0f / (4.0f * sigma);
         if (lane == 0) {
             s_bin[0] = lo;
@@ -622,27 +667,28 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
     // ---- whole chunks: branch-free, the next chunk's loads in flight during the look-ups
     auto full_chunks = [&](auto base0) {
         constexpr bool BASE0 = decltype(base0)::value;
-        auto process = [&](const CodeVec<CB> *cv, const bool *dead, int base) {
+        auto process = [&](const CodeVec<CB> *cv, const bool *dead, const float *w, int base) {
             float sum[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) sum[u] = group_sum<S>(gather16<CB, MODE, BASE0, BASE0 && ONE_ROUND>(cv[u], tbase, woff, 0, a));
-            emit(base, sum, dead);
+            emit(base, sum, dead, w);
         };
         if (PREFETCH) {
             int r = 0;
             while (r < nround) {
-                if (r + 1 < nround) load_set(setB, deadB, chunk_base(r + 1));
-                process(setA, deadA, chunk_base(r));
+                if (r + 1 < nround) load_set(setB, deadB, wgtB, chunk_base(r + 1));
+                process(setA, deadA, wgtA, chunk_base(r));
                 if (++r >= nround) break;
-                if (r + 1 < nround) load_set(setA, deadA, chunk_base(r + 1));
-                process(setB, deadB, chunk_base(r));
+                if (r + 1 < nround) load_set(setA, deadA, wgtA, chunk_base(r + 1));
+                process(setB, deadB, wgtB, chunk_base(r));
                 ++r;
             }
         } else {
             for (int r = 0; r < nround; ++r) {
                 const int base = chunk_base(r);
-                float sum[U];
+                float sum[U], w[EPL];
                 bool dead[U];
+                load_weights(w, base);
 #pragma unroll
                 for (int u = 0; u < U; ++u) sum[u] = 0.0f;
                 for (int c = 0; c < a.rounds; ++c) {
@@ -654,7 +700,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u) sum[u] = group_sum<S>(sum[u]);
-                emit(base, sum, dead);
+                emit(base, sum, dead, w);
             }
         }
     };
@@ -665,9 +711,10 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
     const int npass = (max_n - left0 + KPW - 1) / KPW;
     for (int p0 = ((int)blockIdx.x * NW + wave) * U; p0 < npass; p0 += stride * NW * U) {
         const int base = left0 + p0 * KPW;
-        float sum[U];
+        float sum[U], w[EPL];
         bool dead[U];
         CodeVec<CB> cv[U];
+        load_weights(w, base);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             sum[u] = 0.0f;
@@ -687,7 +734,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) sum[u] = group_sum<S>(sum[u]);   // every lane of a key's group takes part
-        emit(base, sum, dead);
+        emit(base, sum, dead, w);
     }
 
     if (a.hist && has_table) {
@@ -732,9 +779,11 @@ static int set_lds_limit(const void *fn, size_t lds) {
 
 int launch_project(socket_ctx *ctx, const void *q, const void *proj, float tau, const void *K,
                    void *codes, const int32_t *block_table, const int32_t *pos, const int32_t *count,
-                   int32_t *len_out, int batch, hipStream_t st) {
+                   int32_t *len_out, int batch, hipStream_t st, const float *vnorm) {
     const Geometry &g = ctx->g;
     ProjectArgs a;
+    a.vnorm = (q && K && g.mode == kDirect) ? vnorm : nullptr;
+    ctx->vnorm_sampled = a.vnorm;
     a.hard = tau <= 0.0f;                            // internal convention of launch_hard_hash
     if (a.hard) tau = 1.0f;
     a.q = q; a.W = proj; a.tables = ctx->tables; a.tstats = ctx->tstats; a.tau = (double)tau;
@@ -747,7 +796,7 @@ int launch_project(socket_ctx *ctx, const void *q, const void *proj, float tau, 
     a.table_words = g.table_words;
     a.cols_magic = (65536 + g.P - 1) / g.P;
     const size_t lds = (size_t)(2 * g.G * kPlanePad + g.G * g.d + g.P * g.d) * sizeof(double) +
-                       (size_t)(g.P * g.d + g.d) * 4 + 64 + 16;
+                       (size_t)(g.P * g.d + g.d) * 4 + 64 + 48;
     dim3 grid(g.Lpad, g.Hkv, batch);
     typedef void (*project_fn_t)(ProjectArgs);
     project_fn_t fn = nullptr;
@@ -778,10 +827,11 @@ int launch_score_keys(socket_ctx *ctx, const void *codes, const float *vnorm,
                       bool want_hist, int *hist_mode, hipStream_t st) {
     const Geometry &g = ctx->g;
     ScoreArgs a;
-    // The adaptive bins are sized from the tables alone, so they need unweighted scores and
-    // the one-entry-per-bucket table form the spread was taken from.
+    // The adaptive bins are sized from the one-entry-per-bucket tables (and, for weighted
+    // scores, from the value norms the projection pass sampled: only if it sampled these).
     const int mode = !want_hist ? kHistNone
-                     : (vnorm == nullptr && g.mode == kDirect) ? kHistAdaptive : kHistDigit;
+                     : (g.mode == kDirect && (vnorm == nullptr || vnorm == ctx->vnorm_sampled)) ? kHistAdaptive
+                                                                                              : kHistDigit;
     if (hist_mode) *hist_mode = mode;
     a.hist_mode = mode; a.tstats = ctx->tstats; a.L = g.L;
     a.n_sink = ctx->n_sink; a.n_window = ctx->n_window;

@@ -111,7 +111,7 @@ int socket_create(socket_ctx **out, const socket_params *p) {
     }
     const int64_t BH = (int64_t)g.max_batch * g.Hkv;
     const int64_t sz_tables = BH * g.table_words * 4;
-    const int64_t sz_tstats = BH * g.Lpad * 4;
+    const int64_t sz_tstats = BH * g.Lpad * 3 * 4;
     // fast prefill hash: bf16 keys, 8-plane tables, whole 64-table chunks, W slab of a chunk fits LDS
     const bool fast_hash = g.kv_dtype == SOCKET_BF16 && g.P == 8 && g.L >= 64 && g.d <= 128;
     const int64_t sz_wfrag = fast_hash ? (int64_t)g.Hkv * ((g.L + 63) / 64) * g.d * 1024 : 0;
@@ -260,7 +260,7 @@ int socket_decode_step(socket_ctx *ctx, const void *q, const void *K, const void
     hipStream_t st = (hipStream_t)stream;
     int32_t *len = ctx->seq_scratch;
     // 1. hash the appended key and soft-hash the queries (one launch); len = pos + 1
-    int rc = launch_project(ctx, q, proj, tau, K, codes, block_table, pos, nullptr, len, batch, st);
+    int rc = launch_project(ctx, q, proj, tau, K, codes, block_table, pos, nullptr, len, batch, st, vnorm);
     if (rc != SOCKET_OK) return rc;
     // 2. score every key; the leading-digit histogram of the scores comes out of the same pass
     int hist_mode = sk::kHistNone;

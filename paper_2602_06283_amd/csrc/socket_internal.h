@@ -68,7 +68,8 @@ struct socket_ctx {
     int64_t scratch_bytes;
     int n_sink, n_window; // tokens at either end of a sequence that scoring forces into the selection
     float *tables;        // [max_batch*Hkv][table_words]
-    float *tstats;        // [max_batch*Hkv][Lpad] spread of each table's bucket probabilities
+    float *tstats;        // [max_batch*Hkv][Lpad][3] spread of each table's bucket probabilities, sampled value norms
+    const float *vnorm_sampled;   // the value-norm array the last projection pass sampled (or null)
     void *wfrag;          // W cut into MFMA fragments for the fast prefill hash (null when that path does not apply)
     uint32_t *hist;       // [2][max_batch*Hkv][kHistBins]
     uint32_t *counters;   // [max_batch*Hkv][kCounterStride] counters, then [max_batch*Hkv][kThrStride] records
@@ -91,7 +92,7 @@ int launch_hash_keys(socket_ctx *ctx, const void *K, const void *proj, const int
 // q null = append hash only; K null = soft hash only
 int launch_project(socket_ctx *ctx, const void *q, const void *proj, float tau, const void *K,
                    void *codes, const int32_t *block_table, const int32_t *pos, const int32_t *count,
-                   int32_t *len_out, int batch, hipStream_t st);
+                   int32_t *len_out, int batch, hipStream_t st, const float *vnorm = nullptr);
 int launch_hard_hash(socket_ctx *ctx, const void *q, const void *proj, int batch, hipStream_t st);
 int launch_soft_hash(socket_ctx *ctx, const void *q, const void *proj, float tau, int batch,
                      hipStream_t st);

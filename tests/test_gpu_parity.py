@@ -559,7 +559,7 @@ def test_decode_step_equals_separate_calls_and_oracle(kv_dtype, L, P, G):
 
 
 @pytest.mark.parametrize("case", ["ties_cold", "ties_cold_small_k", "ties_flat", "all_equal", "take_all", "k_one",
-                                  "value_norms", "large", "large_tiny_k"])
+                                  "value_norms", "value_norms_heavy", "large", "large_tiny_k"])
 def test_decode_step_select_paths_agree(case):
     """Inside socket_decode_step the select starts from what the scoring pass leaves: a
     histogram with bins sized from the bucket-probability tables when the scores are
@@ -567,8 +567,8 @@ def test_decode_step_select_paths_agree(case):
     bin.  The separate socket_topk_select call histograms leading digits of the scores itself.
     All are exact, so they must pick the same tokens - also when nearly all scores tie (tau -> 0
     makes them collision counts, tau -> inf makes them all L/R, identical keys make them one
-    value), when k covers the whole sequence, and with value norms (which switch the fused step
-    back to the digit histogram)."""
+    value), when k covers the whole sequence, and with value norms (bins then also scaled by a
+    sample of the norms), well behaved or spread over five decades."""
     _need_gpu()
     cfg = {
         "ties_cold": dict(n=6000, k=[300, 777], tau=1e-4, lens=[6000, 4100]),
@@ -578,6 +578,7 @@ def test_decode_step_select_paths_agree(case):
         "take_all": dict(n=3000, k=[2999, 3024], tau=0.5, lens=[2999, 1500]),
         "k_one": dict(n=3000, k=[1, 2], tau=0.5, lens=[3000, 2]),
         "value_norms": dict(n=6000, k=[256, 100], tau=0.5, lens=[6000, 3333]),
+        "value_norms_heavy": dict(n=6000, k=[256, 100], tau=0.5, lens=[6000, 3333]),
         "large": dict(n=40000, k=[1024, 512], tau=0.5, lens=[40000, 23456]),
         "large_tiny_k": dict(n=40000, k=[16, 1], tau=0.5, lens=[40000, 300]),
     }[case]
@@ -594,6 +595,11 @@ def test_decode_step_select_paths_agree(case):
     if case == "value_norms":
         vn = torch.from_numpy(np.stack([np.stack([oracle.value_norms(layer.V[b, h]) for h in range(Hkv)])
                                         for b in range(B)]).astype(np.float32)).cuda()
+    if case == "value_norms_heavy":                    # weights over five decades, some exactly 0
+        rng = np.random.default_rng(72)
+        w = np.exp(2.5 * rng.standard_normal((B, Hkv, n))).astype(np.float32)
+        w[:, :, ::97] = 0.0
+        vn = torch.from_numpy(w).cuda()
 
     def fresh():
         return dict(codes=torch.zeros((B, Hkv, n, hz.lpad_of(L)), dtype=hz.torch_code_dtype(P), device="cuda"),
