@@ -156,6 +156,18 @@ template <int LPR> __device__ __forceinline__ float row_sum(float v) {
     return v;
 }
 
+// inclusive prefix sum over the 64 lanes of a wavefront: shifts inside the 16-lane rows, then
+// the row totals carried over with the two row broadcasts
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x) {
+    x += __builtin_amdgcn_update_dpp(0u, x, 0x111, 0xF, 0xF, true);     // row_shr:1
+    x += __builtin_amdgcn_update_dpp(0u, x, 0x112, 0xF, 0xF, true);     // row_shr:2
+    x += __builtin_amdgcn_update_dpp(0u, x, 0x114, 0xF, 0xF, true);     // row_shr:4
+    x += __builtin_amdgcn_update_dpp(0u, x, 0x118, 0xF, 0xF, true);     // row_shr:8
+    x += __builtin_amdgcn_update_dpp(0u, x, 0x142, 0xA, 0xF, false);    // row_bcast:15 into rows 1 and 3
+    x += __builtin_amdgcn_update_dpp(0u, x, 0x143, 0xC, 0xF, false);    // row_bcast:31 into rows 2 and 3
+    return x;
+}
+
 // max over the 64 lanes of a wavefront; every lane ends with it
 __device__ __forceinline__ float wave_max(float v) {
     v = fmaxf(v, dpp_f32<0x128>(v));

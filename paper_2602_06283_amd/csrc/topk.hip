@@ -75,12 +75,7 @@ template <int N, int PER> constexpr int padded_size() { return N + N / PER; }
 // Exclusive prefix sum over the 512 threads of a block; *total gets the block sum.
 __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *total, uint32_t *tmp) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    uint32_t x = v;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        uint32_t y = __shfl_up(x, off);
-        if (lane >= off) x += y;
-    }
+    const uint32_t x = wave_incl_scan(v);
     if (lane == 63) tmp[wave] = x;
     __syncthreads();
     uint32_t base = 0, sum = 0;
