@@ -36,7 +36,7 @@
  *            of table l (the paper's W^(l), row i)
  *   codes    same token layout as K with d replaced by Lpad:
  *            [B, Hkv, max_n, Lpad] or [num_blocks, Hkv, page_size, Lpad];
- *            element uint8 when P <= 8, uint16 otherwise.
+ *            element uint8 when P <= 8, uint16 when P >= 11 (P = 9, 10: packed, below).
  *            Lpad = 16, 32 or 64 (the smallest that holds L) when L <= 64, else L
  *            rounded up to a multiple of 64.  The L bucket ids of token t are
  *            stored in a rotated order chosen so that the scoring kernel's table
@@ -45,6 +45,18 @@
  *                64*c + (l' % S)*16 + ((l' / S - t) mod 16).
  *            socket_code_position() returns that position.  Positions that map to
  *            tables >= L hold 0.
+ *            P = 9 and P = 10 use a packed form instead, 10 bits per id (the paper counts
+ *            600 bits per token for (P, L) = (10, 60); here 640 with Lpad = 64): tokens
+ *            are stored in tiles of 16, [.., Hkv, max_n/16, 20*Lpad] bytes (paged:
+ *            [num_blocks, Hkv, page_size/16, 20*Lpad]).  With GT = min(Lpad, 32) and
+ *            S = GT/16 a tile holds Lpad/GT group blocks of 20*GT bytes, group c covering
+ *            tables c*GT .. c*GT+GT-1.  The ids of a token's group form S strings of 160
+ *            bits (little-endian), string `sub` holding, in bits [10 s, 10 s + 10), the id
+ *            of table c*GT + sub + S*((t + s) mod 16), s = 0..15 (the rotation above).
+ *            A block keeps bytes 0..15 of the strings in 16 rows (token t mod 16) of GT
+ *            bytes, string `sub` at byte 16*sub, followed by 16 rows of GT/4 bytes with
+ *            bytes 16..19 of the strings, string `sub` at byte 4*sub.
+ *            socket_codes_bytes() and socket_code_location() describe all three forms.
  *   bucket id: bit i is 1 when hyperplane i gives a projection >= 0.
  *   scores   [B, Hkv, max_n] float32, logical token order; -inf for t >= seq_len
  *   idx      [B, Hkv, max_k] int32 logical token positions in ascending order,
@@ -99,6 +111,18 @@ int32_t socket_codes_per_token(int32_t L);
 
 /* Position of table l's bucket id inside token t's Lpad-long code row. */
 int32_t socket_code_position(int32_t L, int32_t l, int32_t t);
+
+/* Bytes of bucket-id storage for `tokens` tokens (a multiple of 16) of one (sequence or
+ * block, KV head); -1 for arguments out of range. */
+int64_t socket_codes_bytes(int32_t L, int32_t P, int64_t tokens);
+
+/* Where the bucket id of table l (< Lpad) of token t is kept, as byte offsets from the start
+ * of the (sequence or block, KV head) slab: with B0 the byte at *lo_byte and B1 the byte at
+ * *hi_byte (taken as 0 when *hi_byte = -1, which is the case for P <= 8),
+ *     id = ((B0 | B1 << 8) >> *hi_shift) & (2^P - 1).
+ * Host-only; 0 or SOCKET_EINVAL. */
+int socket_code_location(int32_t L, int32_t P, int32_t l, int32_t t, int64_t *lo_byte,
+                         int64_t *hi_byte, int32_t *hi_shift);
 
 /* Create / destroy a context on the current HIP device.  Creation allocates the
  * scratch (bucket-probability tables, radix histograms, candidate lists,

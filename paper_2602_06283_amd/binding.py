@@ -42,6 +42,10 @@ def lib():
         L.socket_validate_params.argtypes = [ctypes.POINTER(Params)]
         L.socket_codes_per_token.argtypes = [i32]
         L.socket_code_position.argtypes = [i32, i32, i32]
+        L.socket_codes_bytes.argtypes = [i32, i32, ctypes.c_int64]
+        L.socket_codes_bytes.restype = ctypes.c_int64
+        L.socket_code_location.argtypes = [i32, i32, i32, i32, ctypes.POINTER(ctypes.c_int64),
+                                           ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(i32)]
         L.socket_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(Params)]
         L.socket_destroy.argtypes = [vp]
         L.socket_scratch_bytes.argtypes = [vp]
@@ -70,6 +74,7 @@ def lib():
 
 
 EXPORTS = ("socket_validate_params", "socket_codes_per_token", "socket_code_position",
+           "socket_codes_bytes", "socket_code_location",
            "socket_create", "socket_destroy", "socket_scratch_bytes", "socket_hash_keys",
            "socket_value_norms", "socket_set_forced_tokens",
            "socket_score", "socket_soft_hash", "socket_hard_hash", "socket_score_keys", "socket_topk_select", "socket_sparse_decode", "socket_dense_decode", "socket_decode_step", "socket_strerror",
@@ -97,6 +102,19 @@ def codes_per_token(L: int) -> int:
 
 def code_position(L: int, l: int, t: int) -> int:
     return lib().socket_code_position(L, l, t)
+
+
+def codes_bytes(L: int, P: int, tokens: int) -> int:
+    return lib().socket_codes_bytes(L, P, tokens)
+
+
+def code_location(L: int, P: int, l: int, t: int):
+    """(lo_byte, hi_byte, hi_shift) of table l's bucket id of token t; see socket.h."""
+    lo, hi, sh = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int32()
+    rc = lib().socket_code_location(L, P, l, t, ctypes.byref(lo), ctypes.byref(hi), ctypes.byref(sh))
+    if rc != OK:
+        raise SocketError(rc, "socket_code_location")
+    return lo.value, hi.value, sh.value
 
 
 def _ptr(t):

@@ -24,6 +24,7 @@ struct HashArgs {
     const int32_t *row_count;
     RowMap map;
     int d, L, P, LP, Lpad, S, cb;
+    int GT;                // tables per group of the packed 10-bit layout, 0 = unpacked ids
     int rows_per_wg;
     int tables_per_chunk;  // tables one workgroup covers (mfma kernel)
     int n_chunks;
@@ -76,6 +77,40 @@ __device__ __forceinline__ void pack_codes(const uint32_t *bits, int stride, int
             if (cb == 1) ((uint8_t *)codes)[at] = (uint8_t)code;
             else ((uint16_t *)codes)[at] = (uint16_t)code;
         }
+    }
+}
+
+// The same for the packed 10-bit layout: the workgroup owns groups g0 .. g0+ngrp-1 of GT
+// tables whole, and every thread builds one aligned dword of a token's 160-bit id string
+// (parts of the four or five ids that overlap it).
+__device__ __forceinline__ void pack_codes_packed(const uint32_t *bits, int stride, int nrows,
+                                                  const int *tok, const int64_t *grow, void *codes,
+                                                  int L, int P, int Lpad, int GT, int first_table,
+                                                  int ntab, int ngrp, int tid, int nthreads) {
+    const int S = GT >> 4;
+    const int g0 = first_table / GT;
+    const int per_row = ngrp * S * 5;                // dwords per token
+    for (int i = tid; i < nrows * per_row; i += nthreads) {
+        const int r = i / per_row;
+        int u = i - r * per_row;
+        if (grow[r] < 0) continue;
+        const int gl = u / (S * 5);
+        u -= gl * (S * 5);
+        const int sub = u / 5, wi = u - sub * 5;     // string, dword of the string
+        const int grp = g0 + gl, t = tok[r];
+        const uint32_t *row = bits + r * stride;
+        uint32_t word = 0;
+        const int s0 = (32 * wi) / 10;               // first id that reaches into this dword
+#pragma unroll
+        for (int e = 0; e < 5; ++e) {
+            const int sidx = s0 + e, at = 10 * sidx - 32 * wi;   // bit of the dword where the id starts
+            if (sidx > 15 || at >= 32) break;
+            const int l = grp * GT + packed_table_at(sub * 16 + sidx, t, S);
+            uint32_t id = 0;
+            if (l < L && l >= first_table && l < first_table + ntab) id = bit_field(row, (l - first_table) * P, P);
+            word |= at >= 0 ? id << at : id >> -at;
+        }
+        *(uint32_t *)((char *)codes + packed_word(grow[r], grp, sub, wi, Lpad, GT)) = word;
     }
 }
 
@@ -141,7 +176,10 @@ __global__ __launch_bounds__(256) void hash_rows_kernel(HashArgs a) {
         }
     }
     __syncthreads();
-    pack_codes(bits, bw, ROWS, tok, grow, a.codes, a.L, a.P, a.Lpad, a.S, a.cb, 0, a.L, true, tid, 256);
+    if (a.GT)
+        pack_codes_packed(bits, bw, ROWS, tok, grow, a.codes, a.L, a.P, a.Lpad, a.GT, 0, a.L, a.Lpad / a.GT, tid, 256);
+    else
+        pack_codes(bits, bw, ROWS, tok, grow, a.codes, a.L, a.P, a.Lpad, a.S, a.cb, 0, a.L, true, tid, 256);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -178,7 +216,7 @@ __global__ __launch_bounds__(512, D <= 128 ? 4 : 2) void hash_mfma_kernel(HashAr
     const int begin = a.row_begin[b];
 
     const int first_table = chunk * a.tables_per_chunk;
-    const int ntab = min(a.tables_per_chunk, a.L - first_table);
+    const int ntab = max(0, min(a.tables_per_chunk, a.L - first_table));   // 0: a group of padding tables only
     const int ncols = ntab * a.P;              // live columns of this chunk (<= 512)
     const int col0 = first_table * a.P;
 
@@ -300,6 +338,9 @@ __global__ __launch_bounds__(512, D <= 128 ? 4 : 2) void hash_mfma_kernel(HashAr
                 const int pos0 = (first_table >> 6) << 6;
                 *(uint2 *)((char *)a.codes + g * (int64_t)a.Lpad + pos0 + sub * 16 + half * 8) = make_uint2(out[0], out[1]);
             }
+        } else if (a.GT) {
+            pack_codes_packed(bt, BSTRIDE, TILE, tk, gr, a.codes, a.L, a.P, a.Lpad, a.GT, first_table, ntab, 1,
+                              tid, 512);
         } else {
             pack_codes(bt, BSTRIDE, TILE, tk, gr, a.codes, a.L, a.P, a.Lpad, a.S, a.cb, first_table, ntab,
                        whole, tid, 512);
@@ -515,9 +556,16 @@ static int launch_mfma8(HashArgs a, uint4 *wfrag, int Hkv, int batch, int max_ro
 template <int D>
 static int launch_mfma(HashArgs a, int Hkv, int batch, int max_rows, hipStream_t st) {
     constexpr int TILE = 64, KSTRIDE = D * 2 + 16, BSTRIDE = 17;
-    a.tables_per_chunk = 512 / a.P;
-    if (a.tables_per_chunk > a.L) a.tables_per_chunk = a.L;
-    a.n_chunks = (a.L + a.tables_per_chunk - 1) / a.tables_per_chunk;
+    if (a.GT) {
+        // packed ids: a workgroup owns whole groups of GT tables (the high bits of four ids
+        // share a byte), padding groups included
+        a.tables_per_chunk = a.GT;
+        a.n_chunks = a.Lpad / a.GT;
+    } else {
+        a.tables_per_chunk = 512 / a.P;
+        if (a.tables_per_chunk > a.L) a.tables_per_chunk = a.L;
+        a.n_chunks = (a.L + a.tables_per_chunk - 1) / a.tables_per_chunk;
+    }
     // rows per workgroup: enough workgroups to fill 256 CUs, at least 1024 rows each so the
     // one-time load of the W slab is amortised
     int64_t total = (int64_t)max_rows * Hkv * batch * a.n_chunks;
@@ -539,6 +587,7 @@ int launch_hash_keys(socket_ctx *ctx, const void *K, const void *proj, const int
     a.K = K; a.W = proj; a.codes = codes; a.row_begin = row_begin; a.row_count = row_count;
     a.map = RowMap{block_table, g.Hkv, g.max_n, g.page, g.max_blocks, g.num_blocks};
     a.d = g.d; a.L = g.L; a.P = g.P; a.LP = g.L * g.P; a.Lpad = g.Lpad; a.S = g.S; a.cb = g.cb;
+    a.GT = g.mode == kSplit ? g.GT : 0;
     a.rows_per_wg = 0; a.tables_per_chunk = g.L; a.n_chunks = 1;
     int rc;
     if (max_rows == 1) {

@@ -44,6 +44,7 @@ struct ProjectArgs {
     int32_t *len_out;       // optional [B]: pos[b] + 1
     RowMap map;
     int d, G, Hkv, Hq, L, P, LP, Lpad, S, cb, rounds, R, mode, Plo, Phi, Rlo, Rhi, table_rows;
+    int GT;                 // split mode: tables per group
     int cols_magic;         // ceil(2^16 / P): x / P == (x * cols_magic) >> 16 for x < 2^12
     int64_t table_words;
 };
@@ -320,6 +321,21 @@ __global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
             for (int i = 0; i < 4; ++i)
                 code |= (sg[i].x << (4 * i)) | (sg[i].y << (4 * i + 1)) | (sg[i].z << (4 * i + 2)) | (sg[i].w << (4 * i + 3));
         }
+        if (a.mode == kSplit) {
+            // packed ids: the 10 bits sit in one or two dwords that other tables (other
+            // workgroups) write too, so they are cleared and set with atomics
+            const int grp = l / a.GT, j = packed_pos(l % a.GT, tok, a.S);
+            const int sub = j >> 4, bit = 10 * (j & 15), wi = bit >> 5, sh = bit & 31;
+            uint32_t *w0 = (uint32_t *)((char *)a.codes + packed_word(krow, grp, sub, wi, a.Lpad, a.GT));
+            atomicAnd(w0, ~(0x3ffu << sh));
+            atomicOr(w0, code << sh);
+            if (sh > 22) {
+                uint32_t *w1 = (uint32_t *)((char *)a.codes + packed_word(krow, grp, sub, wi + 1, a.Lpad, a.GT));
+                atomicAnd(w1, ~(0x3ffu >> (32 - sh)));
+                atomicOr(w1, code >> (32 - sh));
+            }
+            return;
+        }
         const int64_t at = krow * a.Lpad + code_pos(l, tok, a.S);
         if (a.cb == 1) ((uint8_t *)a.codes)[at] = (uint8_t)code;
         else ((uint16_t *)a.codes)[at] = (uint16_t)code;
@@ -343,18 +359,25 @@ __global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
         for (int i = 0; i < 8; ++i) f[i] = sig[(g * kPlanePad + s0 + i) * 2 + ((bits >> i) & 1)];
         return ((f[0] * f[1]) * (f[2] * f[3])) * ((f[4] * f[5]) * (f[6] * f[7]));
     };
-    if (a.mode == kDirect) {
-        // p(r) over all P <= 8 planes, averaged over the G queries: one entry per thread
+    if (a.mode == kDirect || a.mode == kSplit) {
+        // p(r) over all planes, averaged over the G queries: one entry per thread and pass
+        // (planes 8 and 9 of the split form sit in slots 8 and 9)
         const double inv_g = 1.0 / (double)G, inv_r = 1.0 / (double)a.R;
+        const bool split = a.mode == kSplit;
         float dev2 = 0.0f;
         for (int r = tid; r < a.R; r += 256) {
             double mean = 0.0;
             if (live) {
 #pragma unroll
-                for (int g = 0; g < G; ++g) mean += plane_product(g, 0, r);
+                for (int g = 0; g < G; ++g)
+                    mean += split ? plane_product(g, 0, r & 255) * plane_product(g, 8, r >> 8) : plane_product(g, 0, r);
                 mean *= inv_g;
                 const double dv = mean - inv_r;      // a table's entries sum to 1: their mean is 1/R
                 dev2 += (float)(dv * dv);
+            }
+            if (split) {
+                Tg[((int64_t)(l / a.GT) * a.R + r) * a.GT + l % a.GT] = (float)mean;
+                continue;
             }
             for (int cp = 0; cp < copies; ++cp) Tg[((int64_t)c64 * a.R + r) * 64 + lp + cp * lw] = (float)mean;
         }
@@ -745,6 +768,276 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// Split tables (P = 9, 10; packed 10-bit ids).  The one-entry-per-bucket table of 64 tables
+// does not fit in LDS, so a workgroup (one per CU, 16 wavefronts) goes through the groups of
+// GT = 16 S tables one after the other: group table -> LDS, then every key it owns adds the
+// group's look-ups to the partial sum it left in `scores` during the previous group.  A
+// wavefront takes U passes of 64/S keys at a time, the same keys in every group; a lane reads
+// 16 low bytes and one dword of high-bit pairs per key and group.  The last group applies
+// weights, forced tokens and the mask, and feeds the histogram.
+// ---------------------------------------------------------------------------------------
+#ifndef SK_SPLIT_THREADS
+#define SK_SPLIT_THREADS 512
+#endif
+constexpr int kSplitThreads = SK_SPLIT_THREADS;
+
+// bins of the adaptive histogram, from the per-table spreads the projection pass left (and, for
+// weighted scores, from the value norms it sampled); called by one whole wavefront
+__device__ __forceinline__ void adaptive_bin_params(const ScoreArgs &a, int64_t bh, int lane, bool weighted,
+                                                    float *lo, float *inv) {
+    float var_part = 0.0f, nu1_part = 0.0f, nu2_part = 0.0f;
+    for (int l = lane; l < a.Lpad; l += 64) {
+        const float *ts = a.tstats + (bh * a.Lpad + l) * 3;
+        var_part += ts[0];
+        nu1_part += ts[1];
+        nu2_part += ts[2];
+    }
+    float mu = (float)a.L / (float)a.R;
+    float var = row_sum<64>(var_part);
+    const float nu1 = row_sum<64>(nu1_part), nu2 = row_sum<64>(nu2_part);
+    if (weighted) {          // weighted scores nu * s, nu and s taken as independent: moments of the product
+        const float cnt = (float)(a.L * 256);
+        const float mnu = nu1 / cnt, vnu = fmaxf(nu2 / cnt - mnu * mnu, 0.0f);
+        var = mnu * mnu * var + mu * mu * vnu + vnu * var;
+        mu *= mnu;
+    }
+    const float sigma = fmaxf(sqrtf(var), fmaxf(mu * 1e-6f, 1e-30f));
+    *lo = mu - 4.0f * sigma;
+    *inv = 1.0f / (4.0f * sigma);
+}
+
+// ids of the U keys a lane works on in one turn, with what the keys it emits carry over
+template <int U, int EPL> struct SplitSet {
+    uint4 main[U];                                   // words 0..3 and word 4 of the 160-bit strings
+    uint32_t tail[U];
+    bool dead[U];
+    float carry[EPL], w[EPL];
+};
+
+template <int S, bool PAGED>
+__global__ __launch_bounds__(kSplitThreads) void score_split_kernel(ScoreArgs a) {
+    extern __shared__ float tbl[];
+    constexpr int GT = 16 * S;                       // tables per group
+    constexpr int KPW = 64 / S;                      // keys per wavefront pass
+    constexpr int NW = kSplitThreads / 64;
+    constexpr int U = 4;                             // passes a wavefront takes per turn
+    constexpr int EPL = U / S;                       // results a lane emits per turn
+    constexpr int TP = 8192 / kSplitThreads;         // float4 of a group table each thread moves (at most 128 KB in all)
+    typedef SplitSet<U, EPL> Set;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int h = blockIdx.y, b = blockIdx.z;
+    const int64_t bh = (int64_t)b * a.map.Hkv + h;
+    const int max_n = a.map.max_n;
+    int seq = a.seq_len[b];
+    seq = seq < 0 ? 0 : (seq > max_n ? max_n : seq);
+    float *out = a.scores + bh * max_n;
+    const float *vn = a.vnorm ? a.vnorm + bh * max_n : nullptr;
+    const float ninf = -__builtin_inff();
+    const bool adaptive = a.hist_mode == kHistAdaptive;
+    const int sub = lane % S, kk = lane / S;
+    uint32_t woff[16];                               // byte offset of this lane's table in a GT-float row
+#pragma unroll
+    for (int s = 0; s < 16; ++s) woff[s] = 4u * (uint32_t)(sub + S * ((kk + s) & 15));
+    const int group_words = a.R * GT;
+    const int n4 = group_words >> 2;                 // <= TP * kSplitThreads
+    uint32_t *lhist = (uint32_t *)(tbl + group_words);
+    float *s_bin = (float *)(lhist + kHistBins);     // [2], present with a histogram only
+    const char *cb = (const char *)a.codes;
+    float bin_lo = 0.0f, bin_inv = 0.0f;
+
+    // A wavefront's turns: U passes of KPW keys each, the same keys in every group; turn w of
+    // the kernel is turn w % nturn of group w / nturn.  Turns cover the keys below seq only (the
+    // rest of the row is filled with -inf at the end), and inside a turn nothing branches on a
+    // key being absent: its loads go to a row that exists and its result is dropped, so that
+    // the number of loads in flight is fixed and a set can be waited for while the next one is
+    // still on its way.
+    const int npass = (seq + KPW - 1) / KPW;
+    const int stride = gridDim.x * NW * U;
+    const int first_p0 = ((int)blockIdx.x * NW + wave) * U;
+    const int nturn = first_p0 < npass ? (npass - first_p0 + stride - 1) / stride : 0;
+    const int total = nturn * a.rounds;
+    const float *wsrc = vn ? vn : out;               // weights, or anything loadable
+
+    // this lane's part of a string address that does not change from turn to turn: its token's
+    // tile among the tiles of a pass, its row in the tile, its string in the row
+    const uint32_t lane_main = (uint32_t)((kk >> 4) * (int)packed_tile_bytes(a.Lpad) + (kk & 15) * GT + sub * 16);
+    const uint32_t lane_tail = (uint32_t)((kk >> 4) * (int)packed_tile_bytes(a.Lpad) + 16 * GT + (kk & 15) * (GT >> 2) + sub * 4);
+    auto load_set = [&](Set &st, int w) __attribute__((always_inline)) {
+        const int grp = w / nturn, base = (first_p0 + (w - grp * nturn) * stride) * KPW;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int key = base + u * KPW + kk;
+            st.dead[u] = key >= seq;
+            typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+            u4 t;
+            if (PAGED) {
+                int64_t row = a.map.row(b, h, st.dead[u] ? 0 : key);
+                st.dead[u] = st.dead[u] || row < 0;
+                row = row < 0 ? 0 : row;
+                t = __builtin_nontemporal_load((const u4 *)(cb + packed_word(row, grp, sub, 0, a.Lpad, GT)));
+                st.tail[u] = __builtin_nontemporal_load((const uint32_t *)(cb + packed_word(row, grp, sub, 4, a.Lpad, GT)));
+            } else {
+                // one address for the whole pass (its first token starts a tile), plus the lane's
+                // own offset; a key beyond the row's capacity reads the pass's first token instead
+                const char *pass = cb + packed_main_row(bh * max_n + base + u * KPW, grp, a.Lpad, GT);
+                const bool inside = key < max_n;
+                t = __builtin_nontemporal_load((const u4 *)(pass + (inside ? lane_main : 0u)));
+                st.tail[u] = __builtin_nontemporal_load((const uint32_t *)(pass + (inside ? lane_tail : (uint32_t)(16 * GT))));
+            }
+            st.main[u] = make_uint4(t.x, t.y, t.z, t.w);
+        }
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) {
+            int key = base + (j * S + sub) * KPW + kk;
+            key = key < seq ? key : 0;
+            // (with a single turn per group the partial sums are written by the turn that is
+            // still ahead when this runs: process() fetches them itself then)
+            st.carry[j] = out[key];
+            st.w[j] = wsrc[key];
+        }
+    };
+    auto process = [&](const Set &st, int w) __attribute__((always_inline)) {
+        const int grp = w / nturn, base = (first_p0 + (w - grp * nturn) * stride) * KPW;
+        const bool first = grp == 0, last = grp == a.rounds - 1;
+        float sum[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t sw[5] = {st.main[u].x, st.main[u].y, st.main[u].z, st.main[u].w, st.tail[u]};
+            float p[16];
+#pragma unroll
+            for (int s = 0; s < 16; ++s) {
+                // id s = bits [10 s, 10 s + 10) of the string; its table entry is at id * (4 GT) + woff
+                constexpr uint32_t kIdMask = 0x3ffu * (uint32_t)(GT * 4);
+                const int wi = (10 * s) >> 5, sh = (10 * s) & 31;
+                uint32_t x;                          // the id, shifted left by log2(4 GT), plus other bits
+                constexpr int LG = S == 2 ? 7 : 6;
+                if (sh > 22) x = __builtin_amdgcn_alignbit(sw[wi + 1], sw[wi], sh - LG);   // sh - LG > 0 here
+                else if (sh >= LG) x = sw[wi] >> (sh - LG);
+                else x = sw[wi] << (LG - sh);
+                p[s] = lds_read((x & kIdMask) | woff[s]);     // the table starts at LDS address 0
+            }
+            float acc0 = p[0], acc1 = p[1];
+#pragma unroll
+            for (int s = 2; s < 16; s += 2) {
+                acc0 += p[s];
+                acc1 += p[s + 1];
+            }
+            sum[u] = group_sum<S>(acc0 + acc1);
+        }
+        // lane `sub` of a key's group emits the results of passes sub, sub+S, ...
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) {
+            float v = sum[j * S];
+            bool dd = st.dead[j * S];
+#pragma unroll
+            for (int t = 1; t < S; ++t) {
+                v = sub == t ? sum[j * S + t] : v;
+                dd = sub == t ? st.dead[j * S + t] : dd;
+            }
+            const int key = base + (j * S + sub) * KPW + kk;
+            if (key >= seq) continue;
+            if (!first) v += nturn == 1 ? out[key] : st.carry[j];
+            if (!last) {
+                if (!dd) out[key] = v;
+                continue;
+            }
+            if (dd) {
+                v = ninf;
+            } else {
+                if (vn) v *= st.w[j];
+                if (key < a.n_sink || key >= seq - a.n_window) v = __builtin_inff();   // sink / local window
+            }
+            out[key] = v;
+            if (a.hist && v > ninf) {
+                const uint32_t bin = adaptive ? score_bin(v, bin_lo, bin_inv)
+                                              : score_order_key(v) >> (32 - kHistBits);
+                atomicAdd(&lhist[bin], 1u);
+            }
+        }
+    };
+    // a group's table goes through registers, so that its loads can be in flight while the
+    // previous group's last turn still reads the table in LDS
+    float4 tp[TP];
+    auto table_fetch = [&](int grp) __attribute__((always_inline)) {
+        const float4 *src = (const float4 *)(a.tables + bh * a.table_words + (int64_t)grp * group_words);
+#pragma unroll
+        for (int j = 0; j < TP; ++j) {
+            const int i = tid + j * kSplitThreads;
+            tp[j] = i < n4 ? src[i] : make_float4(0, 0, 0, 0);
+        }
+    };
+    auto table_commit = [&]() __attribute__((always_inline)) {
+        float4 *dst = (float4 *)tbl;
+#pragma unroll
+        for (int j = 0; j < TP; ++j) {
+            const int i = tid + j * kSplitThreads;
+            if (i < n4) dst[i] = tp[j];
+        }
+    };
+
+    // beyond the sequence: -inf
+    for (int key = seq + (int)blockIdx.x * kSplitThreads + tid; key < max_n; key += (int)gridDim.x * kSplitThreads)
+        out[key] = ninf;
+    Set setA, setB;
+    if (total > 0) load_set(setA, 0);
+    if (seq > 0) {
+        table_fetch(0);
+        table_commit();
+    }
+    if (a.hist) {
+        for (int i = tid; i < kHistBins; i += kSplitThreads) lhist[i] = 0;
+        if (adaptive && wave == 0) {
+            float lo, inv;
+            adaptive_bin_params(a, bh, lane, vn != nullptr, &lo, &inv);
+            if (lane == 0) {
+                s_bin[0] = lo;
+                s_bin[1] = inv;
+                if (blockIdx.x == 0) {               // the select's sweep bins with the very same pair
+                    a.thr[bh * kThrStride + kThrBinLo] = __float_as_uint(lo);
+                    a.thr[bh * kThrStride + kThrBinInv] = __float_as_uint(inv);
+                }
+            }
+        }
+    }
+    __syncthreads();
+    if (adaptive) {
+        bin_lo = s_bin[0];
+        bin_inv = s_bin[1];
+    }
+
+    // Group by group; inside a group the next turn's ids are requested before the current
+    // turn is worked on (the last turn of a group requests the first of the next group), two
+    // register sets taking turns.  Between groups every wavefront meets to swap the table.
+    int w = 0;
+    for (int grp = 0; grp < a.rounds; ++grp) {
+        if (grp > 0) {
+            __syncthreads();                         // every wavefront is done with the previous group's table
+            table_fetch(grp);
+            table_commit();
+            __syncthreads();
+        }
+        const int end = (grp + 1) * nturn;
+        while (w < end) {
+            if (w + 1 < total) load_set(setB, w + 1);
+            process(setA, w);
+            if (++w >= end) {                        // (the sets swap names when a group has an odd number of turns)
+                Set t = setA; setA = setB; setB = t;
+                break;
+            }
+            if (w + 1 < total) load_set(setA, w + 1);
+            process(setB, w);
+            ++w;
+        }
+    }
+    if (a.hist && seq > 0) {
+        __syncthreads();
+        uint32_t *gh = a.hist + bh * kHistBins;
+        for (int i = tid; i < kHistBins; i += kSplitThreads)
+            if (lhist[i]) atomicAdd(&gh[i], lhist[i]);
+    }
+}
+
 typedef void (*score_fn_t)(ScoreArgs);
 
 template <int S, int CB, int MODE>
@@ -782,7 +1075,7 @@ int launch_project(socket_ctx *ctx, const void *q, const void *proj, float tau, 
                    int32_t *len_out, int batch, hipStream_t st, const float *vnorm) {
     const Geometry &g = ctx->g;
     ProjectArgs a;
-    a.vnorm = (q && K && g.mode == kDirect) ? vnorm : nullptr;
+    a.vnorm = (q && K && g.mode != kFactor) ? vnorm : nullptr;
     ctx->vnorm_sampled = a.vnorm;
     a.hard = tau <= 0.0f;                            // internal convention of launch_hard_hash
     if (a.hard) tau = 1.0f;
@@ -793,7 +1086,7 @@ int launch_project(socket_ctx *ctx, const void *q, const void *proj, float tau, 
     a.d = g.d; a.G = g.G; a.Hkv = g.Hkv; a.Hq = g.Hq; a.L = g.L; a.P = g.P; a.LP = g.L * g.P;
     a.Lpad = g.Lpad; a.S = g.S; a.cb = g.cb; a.rounds = g.rounds; a.R = g.R; a.mode = g.mode;
     a.Plo = g.Plo; a.Phi = g.Phi; a.Rlo = g.Rlo; a.Rhi = g.Rhi; a.table_rows = g.table_rows;
-    a.table_words = g.table_words;
+    a.table_words = g.table_words; a.GT = g.GT;
     a.cols_magic = (65536 + g.P - 1) / g.P;
     const size_t lds = (size_t)(2 * g.G * kPlanePad + g.G * g.d + g.P * g.d) * sizeof(double) +
                        (size_t)(g.P * g.d + g.d) * 4 + 64 + 48;
@@ -830,7 +1123,7 @@ int launch_score_keys(socket_ctx *ctx, const void *codes, const float *vnorm,
     // The adaptive bins are sized from the one-entry-per-bucket tables (and, for weighted
     // scores, from the value norms the projection pass sampled: only if it sampled these).
     const int mode = !want_hist ? kHistNone
-                     : (g.mode == kDirect && (vnorm == nullptr || vnorm == ctx->vnorm_sampled)) ? kHistAdaptive
+                     : (g.mode != kFactor && (vnorm == nullptr || vnorm == ctx->vnorm_sampled)) ? kHistAdaptive
                                                                                               : kHistDigit;
     if (hist_mode) *hist_mode = mode;
     a.hist_mode = mode; a.tstats = ctx->tstats; a.L = g.L;
@@ -840,6 +1133,31 @@ int launch_score_keys(socket_ctx *ctx, const void *codes, const float *vnorm,
     a.map = RowMap{block_table, g.Hkv, g.max_n, g.page, g.max_blocks, g.num_blocks};
     a.Lpad = g.Lpad; a.rounds = g.rounds; a.R = g.R; a.G = g.G; a.Plo = g.Plo; a.Rlo = g.Rlo;
     a.table_rows = g.table_rows; a.table_words = g.table_words;
+    if (g.mode == kSplit) {
+        // one workgroup per CU (a group table fills most of its LDS)
+        const int keys_per_turn = (kSplitThreads / 64) * 4 * (64 / g.S);
+        int per_bh = 256 / (batch * g.Hkv);
+        const int turns = (g.max_n + keys_per_turn - 1) / keys_per_turn;
+        if (per_bh > turns) per_bh = turns;
+        if (per_bh < 1) per_bh = 1;
+        a.hist = want_hist ? ctx->hist : nullptr;
+        const size_t lds = (size_t)g.R * g.GT * 4 + (a.hist ? kHistBins * 4 + 16 : 0);
+        const bool paged = g.page > 0;
+        score_fn_t fn = g.S == 1 ? (paged ? score_split_kernel<1, true> : score_split_kernel<1, false>)
+                                 : (paged ? score_split_kernel<2, true> : score_split_kernel<2, false>);
+        if (set_lds_limit((const void *)fn, lds) != SOCKET_OK) return SOCKET_EHIP;
+        // the kernel forms its table addresses from LDS address 0: it must own no static LDS
+        static int static_lds[4] = {-1, -1, -1, -1};          // per kernel variant, asked once
+        int &mine = static_lds[(g.S == 1 ? 0 : 2) + (paged ? 1 : 0)];
+        if (mine < 0) {
+            hipFuncAttributes attr;
+            if (hipFuncGetAttributes(&attr, (const void *)fn) != hipSuccess) return SOCKET_EHIP;
+            mine = (int)attr.sharedSizeBytes;
+        }
+        if (mine != 0) return SOCKET_EUNSUPPORTED;
+        hipLaunchKernelGGL(fn, dim3(per_bh, g.Hkv, batch), dim3(kSplitThreads), lds, st, a);
+        return record_hip(ctx, hipGetLastError());
+    }
     // Two resident workgroups per CU over the whole launch, chunks dealt round-robin.
     const int ckeys = (kScoreThreads / 64) * kScoreU * (64 / g.S);
     const int nchunks = (g.max_n + ckeys - 1) / ckeys;

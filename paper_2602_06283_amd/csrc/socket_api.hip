@@ -45,11 +45,21 @@ int fill_geometry(const socket_params *p, Geometry *g) {
     int64_t direct = (int64_t)g->rounds * g->R * 256;
     g->Plo = (p->P + 1) / 2; g->Phi = p->P - g->Plo;
     g->Rlo = 1 << g->Plo; g->Rhi = 1 << g->Phi;
+    g->GT = 0;
     int64_t factor = (int64_t)G * g->rounds * (g->Rlo + g->Rhi) * 256;
     if (p->P <= 8 && direct <= 128 * 1024) {
         g->mode = kDirect;
         g->table_rows = g->R;
         g->table_words = (int64_t)g->rounds * g->R * 64;
+    } else if (p->P == 9 || p->P == 10) {
+        // packed ids, one table per (table, bucket), scored group by group
+        g->mode = kSplit;
+        g->cb = 0;
+        g->GT = g->Lpad < 32 ? g->Lpad : 32;
+        g->S = g->GT / 16;
+        g->rounds = g->Lpad / g->GT;
+        g->table_rows = g->R;
+        g->table_words = (int64_t)g->rounds * g->R * g->GT;
     } else if (p->P >= 2 && factor <= budget) {
         g->mode = kFactor;
         g->table_rows = g->Rlo + g->Rhi;
@@ -91,6 +101,37 @@ int32_t socket_code_position(int32_t L, int32_t l, int32_t t) {
     int sub = lp % S, m = lp / S;
     int s = ((m - t) % 16 + 16) % 16;
     return 64 * c + sub * 16 + s;
+}
+
+static bool packed_ids(int P) { return P == 9 || P == 10; }
+
+int64_t socket_codes_bytes(int32_t L, int32_t P, int64_t tokens) {
+    const int Lpad = pad_codes(L);
+    if (Lpad < 0 || P < 1 || P > 16 || tokens < 0 || tokens % 16) return -1;
+    if (packed_ids(P)) return tokens / 16 * packed_tile_bytes(Lpad);
+    return tokens * Lpad * (P <= 8 ? 1 : 2);
+}
+
+int socket_code_location(int32_t L, int32_t P, int32_t l, int32_t t, int64_t *lo_byte,
+                         int64_t *hi_byte, int32_t *hi_shift) {
+    const int Lpad = pad_codes(L);
+    if (Lpad < 0 || P < 1 || P > 16 || l < 0 || l >= Lpad || t < 0 || !lo_byte || !hi_byte || !hi_shift)
+        return SOCKET_EINVAL;
+    if (packed_ids(P)) {
+        const int GT = Lpad < 32 ? Lpad : 32, S = GT / 16;
+        const int grp = l / GT, j = packed_pos(l % GT, t, S);
+        const int sub = j >> 4, bit = 10 * (j & 15);           // bit of the 160-bit string where the id starts
+        const int b0 = bit >> 3, b1 = b0 + 1;                   // the two bytes of the string that hold it
+        *lo_byte = packed_word(t, grp, sub, b0 >> 2, Lpad, GT) + (b0 & 3);
+        *hi_byte = packed_word(t, grp, sub, b1 >> 2, Lpad, GT) + (b1 & 3);
+        *hi_shift = bit & 7;
+        return SOCKET_OK;
+    }
+    const int cb = P <= 8 ? 1 : 2;
+    *lo_byte = ((int64_t)t * Lpad + socket_code_position(L, l, t)) * cb;
+    *hi_byte = cb == 2 ? *lo_byte + 1 : -1;
+    *hi_shift = 0;
+    return SOCKET_OK;
 }
 
 int socket_create(socket_ctx **out, const socket_params *p) {

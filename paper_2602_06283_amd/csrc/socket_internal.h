@@ -34,7 +34,12 @@ constexpr int kThrBinInv = 9;        // and reciprocal width
 //   factor : bucket id split into low/high bit fields, p(r) = A[r_lo] * B[r_hi], kept per
 //            query head: F[g][c][Rlo + Rhi][64] floats (rows < Rlo are A, the rest B).
 // In both, word w of the 64 holds table l' = w % min(Lpad, 64); tables >= L hold 0.
-enum TableMode { kDirect = 0, kFactor = 1 };
+//   split  : P = 9 or 10 (up to 1024 buckets): one entry per (table, bucket) as in `direct`,
+//            but too large for LDS as a whole, so it is cut by tables into groups of
+//            GT = min(Lpad, 32): T[group][r][GT] floats; the scoring kernel takes the groups
+//            one after the other (a 32-table group of 1024 buckets is 128 KB).  Goes with the
+//            packed 10-bit id layout (see socket.h).
+enum TableMode { kDirect = 0, kFactor = 1, kSplit = 2 };
 
 // What the context's first-level histogram holds when the top-k select starts.
 //   none     : nothing, the select histograms the scores itself
@@ -47,9 +52,11 @@ enum HistMode { kHistNone = 0, kHistDigit = 1, kHistAdaptive = 2 };
 struct Geometry {
     int d, Hq, Hkv, G, L, P, R;
     int Lpad;        // codes per token
-    int S;           // lanes that share one token's 64 codes of a chunk (Lpad<64: Lpad/16, else 4)
-    int rounds;      // 64-table chunks per token
-    int cb;          // bytes per code
+    int S;           // lanes that share one token's 64 codes of a chunk (Lpad<64: Lpad/16, else 4);
+                     // split mode: lanes that share one token's GT codes of a group (GT/16)
+    int rounds;      // 64-table chunks per token (split mode: GT-table groups per token)
+    int cb;          // bytes per code; 0 = packed 10-bit ids (split mode)
+    int GT;          // split mode: tables per group
     int mode;        // TableMode
     int Plo, Phi, Rlo, Rhi;
     int table_rows;  // rows of 64 floats per chunk (direct: R, factor: Rlo+Rhi)
@@ -235,6 +242,37 @@ __device__ __forceinline__ uint32_t bit_field(const uint32_t *row, int bitpos, i
 __device__ __forceinline__ int code_pos(int l, int t, int S) {
     int c = l >> 6, lp = l & 63;
     return (c << 6) + (lp % S) * 16 + ((lp / S - t) & 15);
+}
+
+// ---- packed 10-bit ids (split mode).  Tokens are stored in tiles of 16; a tile holds, for each
+// group of GT tables, a block of 20*GT bytes.  The 16 ids that one lane of the scoring kernel
+// looks up - those of position group `sub` (GT/16 of them per group) of one token - are one
+// 160-bit little-endian string, id s in bits [10 s, 10 s + 10).  The block keeps the first
+// 16 bytes of every string in 16 "main" rows (token t mod 16) of GT bytes, string `sub` at
+// byte 16 sub, and the last 4 bytes in 16 "tail" rows of GT/4 bytes, string `sub` at byte
+// 4 sub: a wavefront reads both as contiguous runs.  Inside a string the ids are rotated like
+// the unpacked layouts: id s of string `sub` of token t belongs to table
+// group*GT + sub + S ((t + s) mod 16), S = GT/16.
+__host__ __device__ __forceinline__ int64_t packed_tile_bytes(int Lpad) { return 20 * (int64_t)Lpad; }
+// byte offset of the main row / the tail row of token row `row`, group `grp`
+__host__ __device__ __forceinline__ int64_t packed_main_row(int64_t row, int grp, int Lpad, int GT) {
+    return (row >> 4) * packed_tile_bytes(Lpad) + (int64_t)grp * 20 * GT + (row & 15) * GT;
+}
+__host__ __device__ __forceinline__ int64_t packed_tail_row(int64_t row, int grp, int Lpad, int GT) {
+    return (row >> 4) * packed_tile_bytes(Lpad) + (int64_t)grp * 20 * GT + 16 * GT + (row & 15) * (GT >> 2);
+}
+// byte offset, inside the (sequence or block, KV head) slab, of 32-bit word i (0..4) of string
+// `sub` of token row `row`, group `grp`
+__host__ __device__ __forceinline__ int64_t packed_word(int64_t row, int grp, int sub, int i, int Lpad, int GT) {
+    return i < 4 ? packed_main_row(row, grp, Lpad, GT) + sub * 16 + 4 * i
+                 : packed_tail_row(row, grp, Lpad, GT) + sub * 4;
+}
+// table (within its group) of id j = 16 sub + s of token t; and the inverse
+__host__ __device__ __forceinline__ int packed_table_at(int j, int t, int S) {
+    return (j >> 4) + S * ((t + (j & 15)) & 15);
+}
+__host__ __device__ __forceinline__ int packed_pos(int tl, int t, int S) {
+    return (tl % S) * 16 + ((tl / S - t) & 15);
 }
 
 // Row index (in units of rows of the [.., Hkv, tokens, width] tensor) of token t of

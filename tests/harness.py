@@ -31,29 +31,39 @@ def lpad_of(L: int) -> int:
     return (L + 63) // 64 * 64
 
 
-def positions(L: int, n: int) -> np.ndarray:
+def packed(P: int) -> bool:
+    """P = 9 and 10 keep their ids in the packed 10-bit layout (see socket.h)."""
+    return P in (9, 10)
+
+
+def positions(L: int, n: int, P: int = 8) -> np.ndarray:
     """pos[t, l] = where table l's id sits in token t's Lpad-long code row (see socket.h)."""
     Lpad = lpad_of(L)
-    S = 4 if Lpad >= 64 else Lpad // 16
     l = np.arange(L)[None, :]
     t = np.arange(n)[:, None]
+    if packed(P):                       # groups of GT tables, S = GT/16 position groups each
+        GT = min(Lpad, 32)
+        S = GT // 16
+        c, lp = l // GT, l % GT
+        return GT * c + (lp % S) * 16 + ((lp // S - t) % 16)
+    S = 4 if Lpad >= 64 else Lpad // 16
     c = l // 64 if Lpad >= 64 else np.zeros_like(l)
     lp = l - 64 * c
     return 64 * c + (lp % S) * 16 + ((lp // S - t) % 16)
 
 
-def codes_to_natural(codes: np.ndarray, L: int, t0: int = 0) -> np.ndarray:
-    """[..., n, Lpad] in the library's order -> [..., n, L]; row i is token t0 + i."""
+def codes_to_natural(codes: np.ndarray, L: int, t0: int = 0, P: int = 8) -> np.ndarray:
+    """[..., n, Lpad] code rows in the library's order -> [..., n, L]; row i is token t0 + i."""
     n = codes.shape[-2]
-    pos = positions(L, t0 + n)[t0:]
+    pos = positions(L, t0 + n, P)[t0:]
     return np.take_along_axis(codes, np.broadcast_to(pos, codes.shape[:-1] + (L,)), axis=-1)
 
 
-def codes_from_natural(nat: np.ndarray, L: int, dtype) -> np.ndarray:
-    """[..., n, L] -> [..., n, Lpad] in the library's order (padding positions 0)."""
+def codes_from_natural(nat: np.ndarray, L: int, dtype, P: int = 8) -> np.ndarray:
+    """[..., n, L] -> [..., n, Lpad] code rows in the library's order (padding positions 0)."""
     n = nat.shape[-2]
     out = np.zeros(nat.shape[:-1] + (lpad_of(L),), dtype=dtype)
-    pos = positions(L, n)
+    pos = positions(L, n, P)
     np.put_along_axis(out, np.broadcast_to(pos, nat.shape), nat.astype(dtype), axis=-1)
     return out
 
@@ -63,7 +73,73 @@ def code_dtype(P: int):
 
 
 def torch_code_dtype(P: int):
-    return torch.uint8 if P <= 8 else torch.int16
+    return torch.uint8 if P <= 8 or packed(P) else torch.int16
+
+
+def fill_id(P: int) -> int:
+    """What an id reads as where the buffer still holds the 0x55 fill bytes."""
+    return 0x55 if P <= 8 else (0x155 if packed(P) else 0x5555)
+
+
+def new_codes(lead, n: int, L: int, P: int, fill: int = 0) -> torch.Tensor:
+    """Device bucket-id buffer for `lead` (sequences or blocks, KV heads) x n tokens, every
+    byte = fill.  Unpacked: [*lead, n, Lpad] uint8 / int16; packed: [*lead, n/16, 20*Lpad] bytes."""
+    Lpad = lpad_of(L)
+    if packed(P):
+        assert n % 16 == 0
+        return torch.full(tuple(lead) + (n // 16, 20 * Lpad), fill, dtype=torch.uint8, device="cuda")
+    if P <= 8:
+        return torch.full(tuple(lead) + (n, Lpad), fill, dtype=torch.uint8, device="cuda")
+    return torch.full(tuple(lead) + (n, Lpad), fill | (fill << 8), dtype=torch.int32, device="cuda").to(torch.int16)
+
+
+def rows_from_device(raw, L: int, P: int) -> np.ndarray:
+    """Bucket-id buffer in the library's storage form (tensor or array, shaped as new_codes
+    makes it) -> code rows [..., n, Lpad]."""
+    if isinstance(raw, torch.Tensor):
+        raw = raw.cpu().numpy()
+    if not packed(P):
+        return raw.view(code_dtype(P))
+    Lpad = lpad_of(L)
+    GT = min(Lpad, 32)
+    S = GT // 16
+    lead, tiles = raw.shape[:-2], raw.shape[-2]
+    rows = np.zeros(lead + (tiles, 16, Lpad), dtype=np.uint16)
+    weights = (1 << np.arange(10)).astype(np.uint16)
+    for g in range(Lpad // GT):
+        blk = raw[..., g * 20 * GT:(g + 1) * 20 * GT]
+        main = blk[..., :16 * GT].reshape(lead + (tiles, 16, S, 16))
+        tail = blk[..., 16 * GT:].reshape(lead + (tiles, 16, S, 4))
+        string = np.concatenate([main, tail], axis=-1)                  # 20 bytes = 16 ids of 10 bits
+        bits = np.unpackbits(string, axis=-1, bitorder="little").reshape(lead + (tiles, 16, S, 16, 10))
+        ids = (bits.astype(np.uint16) * weights).sum(axis=-1).astype(np.uint16)
+        rows[..., g * GT:(g + 1) * GT] = ids.reshape(lead + (tiles, 16, GT))
+    return rows.reshape(lead + (tiles * 16, Lpad))
+
+
+def rows_to_device(rows: np.ndarray, L: int, P: int) -> torch.Tensor:
+    return torch.from_numpy(rows_to_storage(rows, L, P)).cuda()
+
+
+def rows_to_storage(rows: np.ndarray, L: int, P: int) -> np.ndarray:
+    """Code rows [..., n, Lpad] -> the library's storage form (host array; int16 for two-byte ids)."""
+    if not packed(P):
+        r = np.ascontiguousarray(rows.astype(code_dtype(P)))
+        return r.view(np.uint8 if P <= 8 else np.int16)
+    Lpad = lpad_of(L)
+    GT = min(Lpad, 32)
+    S = GT // 16
+    lead, n = rows.shape[:-2], rows.shape[-2]
+    assert n % 16 == 0 and rows.shape[-1] == Lpad
+    r = rows.reshape(lead + (n // 16, 16, Lpad)).astype(np.uint16)
+    raw = np.zeros(lead + (n // 16, 20 * Lpad), dtype=np.uint8)
+    for g in range(Lpad // GT):
+        ids = r[..., g * GT:(g + 1) * GT].reshape(lead + (n // 16, 16, S, 16))
+        bits = ((ids[..., None] >> np.arange(10).astype(np.uint16)) & 1).astype(np.uint8)
+        string = np.packbits(bits.reshape(lead + (n // 16, 16, S, 160)), axis=-1, bitorder="little")
+        raw[..., g * 20 * GT:g * 20 * GT + 16 * GT] = string[..., :16].reshape(lead + (n // 16, 16 * GT))
+        raw[..., g * 20 * GT + 16 * GT:(g + 1) * 20 * GT] = string[..., 16:].reshape(lead + (n // 16, 4 * GT))
+    return raw
 
 
 def make_ctx(layer: wl.Layer, max_k=None, page=0, max_blocks=0, num_blocks=0, max_n=None):

@@ -79,11 +79,40 @@ def test_code_layout_matches_documented_formula():
 
 def test_layout_round_trip():
     rng = np.random.default_rng(5)
-    for L, P in ((24, 8), (64, 8), (128, 4), (60, 10)):
-        nat = rng.integers(0, 1 << P, size=(2, 50, L)).astype(harness.code_dtype(P))
-        lay = harness.codes_from_natural(nat, L, harness.code_dtype(P))
+    for L, P in ((24, 8), (64, 8), (128, 4), (60, 10), (16, 9), (100, 10), (40, 12)):
+        nat = rng.integers(0, 1 << P, size=(2, 48, L)).astype(harness.code_dtype(P))
+        lay = harness.codes_from_natural(nat, L, harness.code_dtype(P), P=P)
         assert lay.shape[-1] == harness.lpad_of(L)
-        assert (harness.codes_to_natural(lay, L) == nat).all()
+        assert (harness.codes_to_natural(lay, L, P=P) == nat).all()
+        store = harness.rows_to_storage(lay, L, P)
+        assert store.nbytes == 2 * sk.codes_bytes(L, P, 48)
+        assert (harness.rows_from_device(store, L, P) == lay).all()
+
+
+def test_code_location_describes_every_storage_form():
+    """socket_code_location against the harness's own packing of random ids: one-byte ids,
+    two-byte ids and the packed 10-bit form (whose tiles and groups it has to walk)."""
+    rng = np.random.default_rng(6)
+    for L, P in ((64, 8), (24, 5), (60, 10), (64, 9), (16, 10), (128, 10), (40, 12)):
+        n = 48
+        nat = rng.integers(0, 1 << P, size=(n, L)).astype(harness.code_dtype(P))
+        lay = harness.codes_from_natural(nat, L, harness.code_dtype(P), P=P)
+        flat = harness.rows_to_storage(lay, L, P).reshape(-1).view(np.uint8)
+        assert flat.size == sk.codes_bytes(L, P, n)
+        seen = set()
+        for t in (0, 1, 15, 16, 17, 31, 47):
+            for l in range(L):
+                lo, hi, sh = sk.code_location(L, P, l, t)
+                got = int(flat[lo])
+                if P > 8:
+                    got = ((got | int(flat[hi]) << 8) >> sh) & ((1 << P) - 1)
+                else:
+                    assert hi == -1 and sh == 0
+                assert got == int(nat[t, l]), (L, P, l, t)
+                seen.add((lo, hi, sh))
+        assert len(seen) == 7 * L                      # no two ids share their bits
+    assert sk.codes_bytes(64, 10, 15) == -1 and sk.codes_bytes(64, 10, 32) == 2 * 20 * 64
+    assert sk.codes_bytes(64, 8, 32) == 32 * 64 and sk.codes_bytes(64, 12, 32) == 32 * 64 * 2
 
 
 def test_null_arguments_are_rejected_without_a_gpu():

@@ -32,10 +32,8 @@ def small_layer(seed=7, B=2, Hq=8, Hkv=2, d=128, n=1024, L=64, P=8, k=96, kv_dty
 def run_hash(ctx, layer, row_begin, row_count, max_rows, codes=None):
     Kd = hz.dev(layer.K, layer.kv_dtype)
     Wd = hz.dev(layer.W, layer.kv_dtype)
-    Lpad = hz.lpad_of(layer.L)
     if codes is None:
-        codes = torch.full((layer.B, layer.Hkv, layer.n, Lpad), 0x55 if layer.P <= 8 else 0x5555,
-                           dtype=hz.torch_code_dtype(layer.P), device="cuda")
+        codes = hz.new_codes((layer.B, layer.Hkv), layer.n, layer.L, layer.P, fill=0x55)
     ctx.hash_keys(Kd, Wd, hz.i32(row_begin), hz.i32(row_count), layer.B, max_rows, codes)
     torch.cuda.synchronize()
     return codes
@@ -43,20 +41,20 @@ def run_hash(ctx, layer, row_begin, row_count, max_rows, codes=None):
 
 def check_codes(layer, codes_t, rows_of):
     """rows_of(b) -> (start, count) of the rows that were hashed for sequence b."""
-    raw = codes_t.cpu().numpy().view(hz.code_dtype(layer.P))
+    raw = hz.rows_from_device(codes_t, layer.L, layer.P)
     exempt = total = 0
     for b in range(layer.B):
         lo, cnt = rows_of(b)
         for h in range(layer.Hkv):
             want, near = hz.oracle_codes(layer, b, h, rows=slice(lo, lo + cnt))
-            got = hz.codes_to_natural(raw[b, h, lo:lo + cnt], layer.L, t0=lo)
+            got = hz.codes_to_natural(raw[b, h, lo:lo + cnt], layer.L, t0=lo, P=layer.P)
             bad = (got != want) & ~near
             assert not bad.any(), (b, h, np.argwhere(bad)[:5], got[bad][:5], want[bad][:5])
             exempt += int(near.sum())
             total += want.size
             # padding positions hold zero
             lay = raw[b, h, lo:lo + cnt]
-            pos = hz.positions(layer.L, lo + cnt)[lo:]
+            pos = hz.positions(layer.L, lo + cnt, layer.P)[lo:]
             padmask = np.ones_like(lay, dtype=bool)
             np.put_along_axis(padmask, pos, False, axis=-1)
             assert (lay[padmask] == 0).all()
@@ -86,13 +84,12 @@ def test_hash_keys_prefill(kv_dtype, n, L, P):
     exempt, total = check_codes(layer, codes, lambda b: (0, counts[b]))
     assert exempt < 1e-3 * total + 5
     # rows beyond row_count were not touched
-    raw = codes.cpu().numpy().view(hz.code_dtype(P))
-    fill = 0x55 if P <= 8 else 0x5555
-    assert (raw[1, :, counts[1]:] == fill).all()
+    raw = hz.rows_from_device(codes, L, P)
+    assert (raw[1, :, counts[1]:] == hz.fill_id(P)).all()
     ctx.close()
 
 
-@pytest.mark.parametrize("kv_dtype,P", [(wl.BF16, 8), (wl.F32, 8), (wl.BF16, 10)])
+@pytest.mark.parametrize("kv_dtype,P", [(wl.BF16, 8), (wl.F32, 8), (wl.BF16, 10), (wl.F32, 9), (wl.BF16, 12)])
 def test_hash_keys_append_one_row(kv_dtype, P):
     _need_gpu()
     layer = small_layer(seed=12, B=3, Hq=4, Hkv=2, n=512, L=64, P=P, kv_dtype=kv_dtype, k=16)
@@ -100,8 +97,8 @@ def test_hash_keys_append_one_row(kv_dtype, P):
     begins = [100, 511, 37]
     codes = run_hash(ctx, layer, begins, [1, 1, 1], 1)
     check_codes(layer, codes, lambda b: (begins[b], 1))
-    raw = codes.cpu().numpy().view(hz.code_dtype(P))
-    fill = 0x55 if P <= 8 else 0x5555
+    raw = hz.rows_from_device(codes, layer.L, P)
+    fill = hz.fill_id(P)
     assert (raw[0, :, :100] == fill).all() and (raw[0, :, 101:] == fill).all()
     # a short unaligned range goes through the 16-row kernel
     codes = run_hash(ctx, layer, [3, 490, 0], [21, 22, 0], 22)
@@ -129,8 +126,8 @@ def test_hash_keys_unaligned_row_ranges_through_the_mfma_kernels():
         begins, counts = [5, 77], [200, 131]
         codes = run_hash(ctx, layer, begins, counts, 200)
         check_codes(layer, codes, lambda b: (begins[b], counts[b]))
-        raw = codes.cpu().numpy().view(hz.code_dtype(P))
-        fill = 0x55 if P <= 8 else 0x5555
+        raw = hz.rows_from_device(codes, L, P)
+        fill = hz.fill_id(P)
         for b in range(2):
             assert (raw[b, :, :begins[b]] == fill).all() and (raw[b, :, begins[b] + counts[b]:] == fill).all()
         ctx.close()
@@ -140,8 +137,8 @@ def test_hash_keys_unaligned_row_ranges_through_the_mfma_kernels():
 
 def run_score(ctx, layer, codes_nat, tau, vnorm=None, seq_len=None, q=None):
     """codes_nat [B,Hkv,n,L] from the oracle, re-laid out for the library."""
-    lay = hz.codes_from_natural(codes_nat, layer.L, hz.code_dtype(layer.P))
-    codes_t = torch.from_numpy(lay.view(np.uint8 if layer.P <= 8 else np.int16)).cuda()
+    lay = hz.codes_from_natural(codes_nat, layer.L, hz.code_dtype(layer.P), P=layer.P)
+    codes_t = hz.rows_to_device(lay, layer.L, layer.P)
     qd = hz.dev(layer.q if q is None else q, layer.kv_dtype)
     Wd = hz.dev(layer.W, layer.kv_dtype)
     scores = torch.full((layer.B, layer.Hkv, layer.n), 123.0, dtype=torch.float32, device="cuda")
@@ -175,7 +172,9 @@ def check_scores(layer, got, codes_nat, tau, vnorm=None, seq_len=None, q=None, r
 
 
 @pytest.mark.parametrize("L,P,G", [(64, 8, 4), (32, 8, 1), (16, 4, 2), (128, 8, 4), (60, 10, 4),
-                                   (64, 10, 1), (24, 5, 8), (128, 4, 4), (200, 2, 1)])
+                                   (64, 10, 1), (24, 5, 8), (128, 4, 4), (200, 2, 1),
+                                   (16, 10, 2), (100, 9, 8),      # packed ids: one 16-table group; four groups
+                                   (40, 12, 2), (64, 11, 4)])     # two-byte ids, factored tables
 def test_score_matches_oracle(L, P, G):
     _need_gpu()
     n = 2048 + 16
@@ -404,7 +403,7 @@ def chain(ctx, layer, tau=0.5, out_dtype=torch.float32, graph=False):
     B, Hkv, n = layer.B, layer.Hkv, layer.n
     max_k = ctx.params.max_k
     Kd, Vd, qd, Wd = (hz.dev(x, layer.kv_dtype) for x in (layer.K, layer.V, layer.q, layer.W))
-    codes = torch.zeros((B, Hkv, n, hz.lpad_of(layer.L)), dtype=hz.torch_code_dtype(layer.P), device="cuda")
+    codes = hz.new_codes((B, Hkv), n, layer.L, layer.P)
     scores = torch.zeros((B, Hkv, n), dtype=torch.float32, device="cuda")
     idx = torch.zeros((B, Hkv, max_k), dtype=torch.int32, device="cuda")
     nsel = torch.zeros((B, Hkv), dtype=torch.int32, device="cuda")
@@ -440,15 +439,15 @@ def chain(ctx, layer, tau=0.5, out_dtype=torch.float32, graph=False):
     return results
 
 
-def check_chain(layer, codes, scores, idx, nsel, out, atol):
-    raw = codes.view(hz.code_dtype(layer.P))
+def check_chain(layer, codes, scores, idx, nsel, out, atol, codes_are_rows=False):
+    raw = codes if codes_are_rows else hz.rows_from_device(codes, layer.L, layer.P)
     G = layer.G
     margin_members = 0
     for b in range(layer.B):
         ln = int(layer.seq_len[b])
         for h in range(layer.Hkv):
             want_codes, near = hz.oracle_codes(layer, b, h, rows=slice(0, ln))
-            got_codes = hz.codes_to_natural(raw[b, h, :ln], layer.L)
+            got_codes = hz.codes_to_natural(raw[b, h, :ln], layer.L, P=layer.P)
             assert not ((got_codes != want_codes) & ~near).any()
             # downstream stages are checked against the oracle run on the GPU's own ids
             want_s = hz.oracle_scores(layer, b, h, np.pad(got_codes, ((0, layer.n - ln), (0, 0))))
@@ -519,7 +518,8 @@ def test_runs_are_bitwise_repeatable():
 
 # ------------------------------------------------------------------ fused decode step
 
-@pytest.mark.parametrize("kv_dtype,L,P,G", [(wl.BF16, 64, 8, 4), (wl.F32, 32, 8, 1), (wl.BF16, 60, 10, 4)])
+@pytest.mark.parametrize("kv_dtype,L,P,G", [(wl.BF16, 64, 8, 4), (wl.F32, 32, 8, 1), (wl.BF16, 60, 10, 4),
+                                            (wl.BF16, 40, 12, 2), (wl.F32, 16, 9, 1)])
 def test_decode_step_equals_separate_calls_and_oracle(kv_dtype, L, P, G):
     """socket_decode_step must give, bit for bit, what the four separate calls give, for a
     few consecutive steps; the last step is also checked against the oracle."""
@@ -534,7 +534,7 @@ def test_decode_step_equals_separate_calls_and_oracle(kv_dtype, L, P, G):
     max_k = int(layer.k.max())
 
     def fresh():
-        return dict(codes=torch.zeros((B, Hkv, n, hz.lpad_of(L)), dtype=hz.torch_code_dtype(P), device="cuda"),
+        return dict(codes=hz.new_codes((B, Hkv), n, L, P),
                     scores=torch.zeros((B, Hkv, n), dtype=torch.float32, device="cuda"),
                     idx=torch.zeros((B, Hkv, max_k), dtype=torch.int32, device="cuda"),
                     nsel=torch.zeros((B, Hkv), dtype=torch.int32, device="cuda"),
@@ -602,7 +602,7 @@ def test_decode_step_select_paths_agree(case):
         vn = torch.from_numpy(w).cuda()
 
     def fresh():
-        return dict(codes=torch.zeros((B, Hkv, n, hz.lpad_of(L)), dtype=hz.torch_code_dtype(P), device="cuda"),
+        return dict(codes=hz.new_codes((B, Hkv), n, L, P),
                     scores=torch.zeros((B, Hkv, n), dtype=torch.float32, device="cuda"),
                     idx=torch.zeros((B, Hkv, max_k), dtype=torch.int32, device="cuda"),
                     nsel=torch.zeros((B, Hkv), dtype=torch.int32, device="cuda"),
@@ -646,7 +646,8 @@ def test_hard_hash_gives_collision_counts(L, P, G):
     layer = small_layer(seed=95, B=B, Hq=Hkv * G, Hkv=Hkv, n=n, L=L, P=P, k=16, seq_len=[3000, 1777])
     ctx = hz.make_ctx(layer)
     codes = run_hash(ctx, layer, np.zeros(B), layer.seq_len, n)
-    nat = [[hz.codes_to_natural(codes.cpu().numpy().view(hz.code_dtype(P))[b, h], L) for h in range(Hkv)] for b in range(B)]
+    rows = hz.rows_from_device(codes, L, P)
+    nat = [[hz.codes_to_natural(rows[b, h], L, P=P) for h in range(Hkv)] for b in range(B)]
     qd, Wd = hz.dev(layer.q, layer.kv_dtype), hz.dev(layer.W, layer.kv_dtype)
     scores = torch.zeros((B, Hkv, n), dtype=torch.float32, device="cuda")
     ctx.hard_hash(qd, Wd, B)
@@ -797,7 +798,7 @@ def paged_setup(seed, B, Hq, Hkv, n_cap, L, P, lens, k, page=16, kv_dtype=wl.BF1
 
 
 def paged_codes_to_logical(codes_p, table, n_cap, page):
-    """[blocks, Hkv, page, Lpad] -> [B, Hkv, n_cap, Lpad] following the block table."""
+    """code rows [blocks, Hkv, page, Lpad] -> [B, Hkv, n_cap, Lpad] following the block table."""
     B = table.shape[0]
     out = np.zeros((B, codes_p.shape[1], n_cap, codes_p.shape[3]), dtype=codes_p.dtype)
     for b in range(B):
@@ -806,12 +807,13 @@ def paged_codes_to_logical(codes_p, table, n_cap, page):
     return out
 
 
-def test_paged_chain_with_appends_across_page_boundaries():
+@pytest.mark.parametrize("L,P,page", [(64, 8, 16), (60, 10, 16), (64, 10, 32)])
+def test_paged_chain_with_appends_across_page_boundaries(L, P, page):
     """Batched paged decode: prefill-hash ragged lengths, then several fused decode steps that
-    append one key per sequence (crossing 16-token pages), all checked against the oracle on
+    append one key per sequence (crossing page edges), all checked against the oracle on
     the logical layout."""
     _need_gpu()
-    B, Hq, Hkv, L, P, page, steps = 3, 8, 2, 64, 8, 16, 5
+    B, Hq, Hkv, steps = 3, 8, 2, 5
     n_cap = 1024
     start = np.array([1000 - 3, 517, 30], dtype=np.int32)      # 997 -> crosses the 1008 page edge
     kk = np.array([64, 48, 40], dtype=np.int32)
@@ -819,8 +821,7 @@ def test_paged_chain_with_appends_across_page_boundaries():
     Kd, Vd = hz.dev(Kp, layer.kv_dtype), hz.dev(Vp, layer.kv_dtype)
     qd, Wd = hz.dev(layer.q, layer.kv_dtype), hz.dev(layer.W, layer.kv_dtype)
     bt = hz.i32(table)
-    Lpad = hz.lpad_of(L)
-    codes = torch.zeros((nblocks, Hkv, page, Lpad), dtype=torch.uint8, device="cuda")
+    codes = hz.new_codes((nblocks, Hkv), page, L, P)
     scores = torch.zeros((B, Hkv, n_cap), dtype=torch.float32, device="cuda")
     idx = torch.zeros((B, Hkv, int(kk.max())), dtype=torch.int32, device="cuda")
     nsel = torch.zeros((B, Hkv), dtype=torch.int32, device="cuda")
@@ -830,9 +831,9 @@ def test_paged_chain_with_appends_across_page_boundaries():
         ctx.decode_step(qd, Kd, Vd, codes, Wd, 0.5, hz.i32(start + s), hz.i32(kk), B, 1.0, scores, idx, nsel,
                         out, block_table=bt)
     torch.cuda.synchronize()
-    logical = paged_codes_to_logical(codes.cpu().numpy(), table, n_cap, page)
+    logical = paged_codes_to_logical(hz.rows_from_device(codes, L, P), table, n_cap, page)
     check_chain(layer, logical, scores.cpu().numpy(), idx.cpu().numpy(), nsel.cpu().numpy(),
-                out.cpu().numpy(), atol=1e-4)
+                out.cpu().numpy(), atol=1e-4, codes_are_rows=True)
     # the separate calls agree with the fused step on paged storage too
     scores2 = torch.zeros_like(scores); idx2 = torch.zeros_like(idx); nsel2 = torch.zeros_like(nsel)
     out2 = torch.zeros_like(out)
@@ -890,19 +891,19 @@ def test_sweep_hash_then_score(L, P):
     layer = small_layer(seed=81, B=2, Hq=8, Hkv=2, n=n, L=L, P=P, k=64, seq_len=[n, n - 100])
     ctx = hz.make_ctx(layer)
     Kd, Wd, qd = (hz.dev(x, layer.kv_dtype) for x in (layer.K, layer.W, layer.q))
-    codes = torch.zeros((2, 2, n, hz.lpad_of(L)), dtype=hz.torch_code_dtype(P), device="cuda")
+    codes = hz.new_codes((2, 2), n, L, P)
     scores = torch.zeros((2, 2, n), dtype=torch.float32, device="cuda")
     ctx.hash_keys(Kd, Wd, hz.i32([0, 0]), hz.i32([n - 1, n - 101]), 2, n, codes)     # prefill
     ctx.hash_keys(Kd, Wd, hz.i32([n - 1, n - 101]), hz.i32([1, 1]), 2, 1, codes)     # append
     ctx.score(qd, codes, Wd, 0.5, hz.i32(layer.seq_len), 2, scores)
     torch.cuda.synchronize()
-    raw = codes.cpu().numpy().view(hz.code_dtype(P))
+    raw = hz.rows_from_device(codes, L, P)
     got_s = scores.cpu().numpy()
     for b in range(2):
         ln = int(layer.seq_len[b])
         for h in range(2):
             want, near = hz.oracle_codes(layer, b, h, rows=slice(0, ln))
-            got = hz.codes_to_natural(raw[b, h, :ln], L)
+            got = hz.codes_to_natural(raw[b, h, :ln], L, P=P)
             assert not ((got != want) & ~near).any()
             want_s = hz.oracle_scores(layer, b, h, np.pad(got, ((0, n - ln), (0, 0))))
             live = np.isfinite(want_s)
