@@ -778,7 +778,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
 // weights, forced tokens and the mask, and feeds the histogram.
 // ---------------------------------------------------------------------------------------
 #ifndef SK_SPLIT_THREADS
-#define SK_SPLIT_THREADS 512
+#define SK_SPLIT_THREADS 1024
 #endif
 constexpr int kSplitThreads = SK_SPLIT_THREADS;
 
@@ -821,11 +821,15 @@ __global__ __launch_bounds__(kSplitThreads) void score_split_kernel(ScoreArgs a)
     constexpr int GT = 16 * S;                       // tables per group
     constexpr int KPW = 64 / S;                      // keys per wavefront pass
     constexpr int NW = kSplitThreads / 64;
-    constexpr int U = 4;                             // passes a wavefront takes per turn
+#ifndef SK_SPLIT_U
+#define SK_SPLIT_U 2
+#endif
+    constexpr int U = SK_SPLIT_U;                    // passes a wavefront takes per turn
     constexpr int EPL = U / S;                       // results a lane emits per turn
     constexpr int TP = 8192 / kSplitThreads;         // float4 of a group table each thread moves (at most 128 KB in all)
     typedef SplitSet<U, EPL> Set;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // in a scalar register: so is all turn bookkeeping
     const int h = blockIdx.y, b = blockIdx.z;
     const int64_t bh = (int64_t)b * a.map.Hkv + h;
     const int max_n = a.map.max_n;
@@ -846,25 +850,24 @@ __global__ __launch_bounds__(kSplitThreads) void score_split_kernel(ScoreArgs a)
     const char *cb = (const char *)a.codes;
     float bin_lo = 0.0f, bin_inv = 0.0f;
 
-    // A wavefront's turns: U passes of KPW keys each, the same keys in every group; turn w of
-    // the kernel is turn w % nturn of group w / nturn.  Turns cover the keys below seq only (the
-    // rest of the row is filled with -inf at the end), and inside a turn nothing branches on a
-    // key being absent: its loads go to a row that exists and its result is dropped, so that
-    // the number of loads in flight is fixed and a set can be waited for while the next one is
-    // still on its way.
+    // A wavefront's turns: U passes of KPW keys each, the same keys in every group.  Turns
+    // cover the keys below seq only (the rest of the row is filled with -inf), and inside a
+    // turn nothing branches on a key being absent: its loads go to a row that exists and its
+    // result is dropped, so that the number of loads in flight is fixed and a set can be waited
+    // for while the next one is still on its way.
     const int npass = (seq + KPW - 1) / KPW;
     const int stride = gridDim.x * NW * U;
     const int first_p0 = ((int)blockIdx.x * NW + wave) * U;
     const int nturn = first_p0 < npass ? (npass - first_p0 + stride - 1) / stride : 0;
-    const int total = nturn * a.rounds;
     const float *wsrc = vn ? vn : out;               // weights, or anything loadable
 
     // this lane's part of a string address that does not change from turn to turn: its token's
     // tile among the tiles of a pass, its row in the tile, its string in the row
     const uint32_t lane_main = (uint32_t)((kk >> 4) * (int)packed_tile_bytes(a.Lpad) + (kk & 15) * GT + sub * 16);
     const uint32_t lane_tail = (uint32_t)((kk >> 4) * (int)packed_tile_bytes(a.Lpad) + 16 * GT + (kk & 15) * (GT >> 2) + sub * 4);
-    auto load_set = [&](Set &st, int w) __attribute__((always_inline)) {
-        const int grp = w / nturn, base = (first_p0 + (w - grp * nturn) * stride) * KPW;
+    // (grp, tix): group and turn inside the group
+    auto load_set = [&](Set &st, int grp, int tix) __attribute__((always_inline)) {
+        const int base = (first_p0 + tix * stride) * KPW;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int key = base + u * KPW + kk;
@@ -897,8 +900,8 @@ __global__ __launch_bounds__(kSplitThreads) void score_split_kernel(ScoreArgs a)
             st.w[j] = wsrc[key];
         }
     };
-    auto process = [&](const Set &st, int w) __attribute__((always_inline)) {
-        const int grp = w / nturn, base = (first_p0 + (w - grp * nturn) * stride) * KPW;
+    auto process = [&](const Set &st, int grp, int tix) __attribute__((always_inline)) {
+        const int base = (first_p0 + tix * stride) * KPW;
         const bool first = grp == 0, last = grp == a.rounds - 1;
         float sum[U];
 #pragma unroll
@@ -980,7 +983,7 @@ __global__ __launch_bounds__(kSplitThreads) void score_split_kernel(ScoreArgs a)
     for (int key = seq + (int)blockIdx.x * kSplitThreads + tid; key < max_n; key += (int)gridDim.x * kSplitThreads)
         out[key] = ninf;
     Set setA, setB;
-    if (total > 0) load_set(setA, 0);
+    if (nturn > 0) load_set(setA, 0, 0);
     if (seq > 0) {
         table_fetch(0);
         table_commit();
@@ -1009,7 +1012,7 @@ __global__ __launch_bounds__(kSplitThreads) void score_split_kernel(ScoreArgs a)
     // Group by group; inside a group the next turn's ids are requested before the current
     // turn is worked on (the last turn of a group requests the first of the next group), two
     // register sets taking turns.  Between groups every wavefront meets to swap the table.
-    int w = 0;
+    // (A wavefront without keys still helps to move the tables and keeps the barriers matched.)
     for (int grp = 0; grp < a.rounds; ++grp) {
         if (grp > 0) {
             __syncthreads();                         // every wavefront is done with the previous group's table
@@ -1017,17 +1020,20 @@ __global__ __launch_bounds__(kSplitThreads) void score_split_kernel(ScoreArgs a)
             table_commit();
             __syncthreads();
         }
-        const int end = (grp + 1) * nturn;
-        while (w < end) {
-            if (w + 1 < total) load_set(setB, w + 1);
-            process(setA, w);
-            if (++w >= end) {                        // (the sets swap names when a group has an odd number of turns)
+        const bool more = grp + 1 < a.rounds;
+        int tix = 0;
+        while (tix < nturn) {
+            if (tix + 1 < nturn) load_set(setB, grp, tix + 1);
+            else if (more) load_set(setB, grp + 1, 0);
+            process(setA, grp, tix);
+            if (++tix >= nturn) {                    // (the sets swap names when a group has an odd number of turns)
                 Set t = setA; setA = setB; setB = t;
                 break;
             }
-            if (w + 1 < total) load_set(setA, w + 1);
-            process(setB, w);
-            ++w;
+            if (tix + 1 < nturn) load_set(setA, grp, tix + 1);
+            else if (more) load_set(setA, grp + 1, 0);
+            process(setB, grp, tix);
+            ++tix;
         }
     }
     if (a.hist && seq > 0) {
@@ -1135,7 +1141,7 @@ int launch_score_keys(socket_ctx *ctx, const void *codes, const float *vnorm,
     a.table_rows = g.table_rows; a.table_words = g.table_words;
     if (g.mode == kSplit) {
         // one workgroup per CU (a group table fills most of its LDS)
-        const int keys_per_turn = (kSplitThreads / 64) * 4 * (64 / g.S);
+        const int keys_per_turn = (kSplitThreads / 64) * SK_SPLIT_U * (64 / g.S);
         int per_bh = 256 / (batch * g.Hkv);
         const int turns = (g.max_n + keys_per_turn - 1) / keys_per_turn;
         if (per_bh > turns) per_bh = turns;
