@@ -38,6 +38,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="128k", choices=sorted(WORKLOADS))
     ap.add_argument("--layers", type=int, default=32)
+    ap.add_argument("--L", type=int, default=64, help="hash tables (headline: 64)")
+    ap.add_argument("--P", type=int, default=8, help="hyperplanes per table (headline: 8; the paper's main runs: P=10, L=60)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only", default="", choices=["", "score", "step"],
                     help="profiling aids: 'score' runs just the scoring kernel over all layers "
@@ -58,11 +60,11 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
     n, k, seed = WORKLOADS[args.workload]
-    Hq, Hkv, d, L, P, tau = 32, 8, 128, 64, 8, 0.5
+    Hq, Hkv, d, L, P, tau = 32, 8, 128, args.L, args.P, 0.5
     NL = args.layers
     extra = args.steps + args.warmup + 64
     n_alloc = (n + extra + 15) // 16 * 16
-    Lpad = sk.codes_per_token(L)
+    id_bytes = sk.codes_bytes(L, P, 16) / 16       # bytes of bucket ids per key and KV head
 
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
@@ -70,7 +72,7 @@ def main():
         layers = []
         for li in range(NL):
             K, V, q, W = wl.device_layer(seed + 100 * li, Hq, Hkv, d, n, n_alloc, L, P)
-            codes = torch.zeros((1, Hkv, n_alloc, Lpad), dtype=torch.uint8, device="cuda")
+            codes = torch.zeros((1, Hkv, sk.codes_bytes(L, P, n_alloc)), dtype=torch.uint8, device="cuda")
             layers.append((K, V, q, W, codes))
         scores = torch.zeros((1, Hkv, n_alloc), dtype=torch.float32, device="cuda")
         idx = torch.zeros((1, Hkv, k), dtype=torch.int32, device="cuda")
@@ -112,7 +114,7 @@ def main():
                 ctx.hash_keys(K, W, zero, n_t, 1, n, codes)
         t_prefill_ms = timed(prefill, 2)
         hash_flops = 2.0 * NL * Hkv * n * d * L * P
-        hash_bytes = NL * Hkv * n * (d * 2 + Lpad)
+        hash_bytes = NL * Hkv * n * (d * 2 + id_bytes)
         # the rows that decode steps will append get hashed inside the step
 
         if args.only == "score":
@@ -129,8 +131,8 @@ def main():
                 dst.copy_(src)           # 256 MiB read + 256 MiB written: counter calibration
             stream.synchronize()
             print(json.dumps({"only": "score", "ctx": n, "layers": NL, "avg_launch_us": us,
-                              "algorithmic_bytes": Hkv * n * (Lpad + 4),
-                              "gbs": Hkv * n * (Lpad + 4) / (us * 1e-6) / 1e9,
+                              "algorithmic_bytes": Hkv * n * (id_bytes + 4),
+                              "gbs": Hkv * n * (id_bytes + 4) / (us * 1e-6) / 1e9,
                               "calibration_copy_bytes_each_way": src.numel() * 4}))
             return
 
@@ -233,13 +235,13 @@ def main():
 
     # ---------------- roofline of the dominant kernel (scoring) -------------------------
     # algorithmic bytes per launch: every bucket id read once + one fp32 score written per key
-    score_bytes = Hkv * cur_len * (Lpad * 1 + 4)
+    score_bytes = Hkv * cur_len * (id_bytes + 4)
     score_gbs = score_bytes / (stage_us["score"] * 1e-6) / 1e9
-    chain_bytes = Hkv * (cur_len * (Lpad + 8) + k * (4 * d + 8))
+    chain_bytes = Hkv * (cur_len * (id_bytes + 8) + k * (4 * d + 8))
     chain_us = stage_us["fused_decode_step"]
     # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by a plain copy of
     # known size (profiles/score_kernel_128k.md); not measured for other workloads
-    traffic = MEASURED_SCORE_TRAFFIC.get((args.workload, NL))
+    traffic = MEASURED_SCORE_TRAFFIC.get((args.workload, NL)) if (L, P) == (64, 8) else None
 
     result = {
         "metric": "decode_steps_per_s",
@@ -256,7 +258,7 @@ def main():
         "data": "synthetic",
         "config": {
             "workload": f"llama3-8b-shaped decode attention, batch 1, ctx {n}, {NL} layers per step "
-                        f"(Hq=32, Hkv=8, d=128, bf16 KV, L=64, P=8, tau=0.5, top-k={k})",
+                        f"(Hq=32, Hkv=8, d=128, bf16 KV, L={L}, P={P}, tau=0.5, top-k={k})",
             "ctx": n, "layers": NL, "L": L, "P": P, "k": k, "graph": "one HIP graph per step",
         },
         "ms_per_step_events": ev_ms_per_step,
@@ -266,7 +268,7 @@ def main():
         "chain": {"fused_step_us": chain_us, "algorithmic_bytes": chain_bytes,
                   "gbs": chain_bytes / (chain_us * 1e-6) / 1e9,
                   "frac_of_hbm_peak": chain_bytes / (chain_us * 1e-6) / 1e9 / HBM_PEAK_GBS},
-        "roofline": {"kernel": "score_kernel", "bound": "hbm", "achieved": score_gbs,
+        "roofline": {"kernel": "score_kernel" if P <= 8 else "score_split_kernel", "bound": "hbm", "achieved": score_gbs,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": score_gbs / HBM_PEAK_GBS,
                      "traffic": traffic, "algorithmic_bytes": score_bytes,
                      "avg_launch_us": stage_us["score"]},
@@ -302,7 +304,9 @@ def cpu_baseline(layer0, k, n, Hq, Hkv, d, L, P, tau, NL, budget_s):
     Vh = V[0, :, :n + 1].float().cpu().numpy()
     qh = q[0].float().cpu().numpy()
     Wh = W.float().cpu().numpy()
-    nat = hz.codes_to_natural(codes[0, :, :n + 1].cpu().numpy(), L).astype(np.uint16)
+    rows = hz.rows_from_device(codes.view(1, Hkv, -1, hz.lpad_of(L) * (1 if P <= 8 else 2)) if not hz.packed(P)
+                               else codes.view(1, Hkv, -1, 20 * hz.lpad_of(L)), L, P)
+    nat = hz.codes_to_natural(rows[0, :, :n + 1], L, P=P).astype(np.uint16)
     G = Hq // Hkv
 
     def layer_step():

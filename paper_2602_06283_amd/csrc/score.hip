@@ -364,13 +364,24 @@ __global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
         // (planes 8 and 9 of the split form sit in slots 8 and 9)
         const double inv_g = 1.0 / (double)G, inv_r = 1.0 / (double)a.R;
         const bool split = a.mode == kSplit;
+        // split form: the products over planes 0..7 for each low byte of the id and over planes
+        // 8, 9 for its two high bits, once per query head; an entry is then one product of two
+        constexpr int kAb = 256 + 4;
+        double *ab = (double *)(s_dev + 12);         // [G][kAb]
+        if (split) {
+            for (int i = tid; i < G * kAb; i += 256) {
+                const int g = i / kAb, r = i - g * kAb;
+                ab[i] = !live ? 0.0 : r < 256 ? plane_product(g, 0, r) : plane_product(g, 8, r - 256);
+            }
+            __syncthreads();
+        }
         float dev2 = 0.0f;
         for (int r = tid; r < a.R; r += 256) {
             double mean = 0.0;
             if (live) {
 #pragma unroll
                 for (int g = 0; g < G; ++g)
-                    mean += split ? plane_product(g, 0, r & 255) * plane_product(g, 8, r >> 8) : plane_product(g, 0, r);
+                    mean += split ? ab[g * kAb + (r & 255)] * ab[g * kAb + 256 + (r >> 8)] : plane_product(g, 0, r);
                 mean *= inv_g;
                 const double dv = mean - inv_r;      // a table's entries sum to 1: their mean is 1/R
                 dev2 += (float)(dv * dv);
@@ -1095,7 +1106,8 @@ int launch_project(socket_ctx *ctx, const void *q, const void *proj, float tau, 
     a.table_words = g.table_words; a.GT = g.GT;
     a.cols_magic = (65536 + g.P - 1) / g.P;
     const size_t lds = (size_t)(2 * g.G * kPlanePad + g.G * g.d + g.P * g.d) * sizeof(double) +
-                       (size_t)(g.P * g.d + g.d) * 4 + 64 + 48;
+                       (size_t)(g.P * g.d + g.d) * 4 + 64 + 48 +
+                       (g.mode == kSplit ? (size_t)g.G * (256 + 4) * sizeof(double) : 0);
     dim3 grid(g.Lpad, g.Hkv, batch);
     typedef void (*project_fn_t)(ProjectArgs);
     project_fn_t fn = nullptr;
