@@ -184,6 +184,12 @@ def main():
             g = stage_graph(body)
             stage_us[name] = timed(g.launch, 10) * 1e3 / NL     # microseconds per launch
             g.close()
+        # the same step with the selection ordered before the attention (bit-repeatable output)
+        ctx.set_deterministic(True)
+        g = stage_graph(stages["fused_decode_step"])
+        stage_us["fused_decode_step_deterministic"] = timed(g.launch, 10) * 1e3 / NL
+        g.close()
+        ctx.set_deterministic(False)
         cur_len = int(length[0])
 
         # ---------------- how good is the selection?  (evaluation only, layer 0) ------------

@@ -236,6 +236,12 @@ int socket_set_forced_tokens(socket_ctx *ctx, int32_t n_sink, int32_t n_window) 
     return SOCKET_OK;
 }
 
+int socket_set_deterministic(socket_ctx *ctx, int32_t on) {
+    if (!ctx) return SOCKET_EINVAL;
+    ctx->deterministic = on != 0;
+    return SOCKET_OK;
+}
+
 int socket_score(socket_ctx *ctx, const void *q, const void *codes, const void *proj, float tau,
                  const float *vnorm, const int32_t *block_table, const int32_t *seq_len,
                  int32_t batch, float *scores, void *stream) {
@@ -308,10 +314,17 @@ int socket_decode_step(socket_ctx *ctx, const void *q, const void *K, const void
     rc = launch_score_keys(ctx, codes, vnorm, block_table, len, batch, scores, true, &hist_mode, st);
     if (rc != SOCKET_OK) return rc;
     // 3. select, 4. attend
-    rc = launch_topk(ctx, scores, len, k, batch, idx, n_selected, hist_mode, st);
+    if (ctx->deterministic) {
+        rc = launch_topk(ctx, scores, len, k, batch, idx, n_selected, hist_mode, st);
+        if (rc != SOCKET_OK) return rc;
+        return launch_sparse_decode(ctx, q, K, V, idx, n_selected, block_table, batch, scale, out_dtype,
+                                    out, st);
+    }
+    //    (the attention starts from the sweep's unordered lists; the index row is ordered beside the merge)
+    rc = launch_topk_sweep(ctx, scores, len, k, batch, idx, n_selected, hist_mode, st);
     if (rc != SOCKET_OK) return rc;
-    return launch_sparse_decode(ctx, q, K, V, idx, n_selected, block_table, batch, scale, out_dtype,
-                                out, st);
+    return launch_sweep_decode(ctx, q, K, V, scores, len, k, idx, n_selected, hist_mode, block_table,
+                               batch, scale, out_dtype, out, st);
 }
 
 int socket_sparse_decode(socket_ctx *ctx, const void *q, const void *K, const void *V,

@@ -74,6 +74,7 @@ struct socket_ctx {
     int last_hip_error;
     int64_t scratch_bytes;
     int n_sink, n_window; // tokens at either end of a sequence that scoring forces into the selection
+    int deterministic;    // the fused decode step orders the selection before it attends (bit-repeatable output)
     float *tables;        // [max_batch*Hkv][table_words]
     float *tstats;        // [max_batch*Hkv][Lpad][3] spread of each table's bucket probabilities, sampled value norms
     const float *vnorm_sampled;   // the value-norm array the last projection pass sampled (or null)
@@ -111,6 +112,14 @@ int launch_score_keys(socket_ctx *ctx, const void *codes, const float *vnorm,
 // hist_mode: what the context's histogram already holds about `scores` (HistMode)
 int launch_topk(socket_ctx *ctx, const float *scores, const int32_t *seq_len, const int32_t *k,
                 int batch, int32_t *idx, int32_t *n_selected, int hist_mode, hipStream_t st);
+// the select up to its sweep (threshold + unordered lists); launch_sweep_decode continues from it
+int launch_topk_sweep(socket_ctx *ctx, const float *scores, const int32_t *seq_len, const int32_t *k,
+                      int batch, int32_t *idx, int32_t *n_selected, int hist_mode, hipStream_t st);
+// Eq. 2 from the sweep's lists, then the split merge beside the ordering of the index row
+int launch_sweep_decode(socket_ctx *ctx, const void *q, const void *K, const void *V,
+                        const float *scores, const int32_t *seq_len, const int32_t *k,
+                        int32_t *idx, int32_t *n_selected, int hist_mode, const int32_t *block_table,
+                        int batch, float scale, int out_dtype, void *out, hipStream_t st);
 int launch_dense_decode(socket_ctx *ctx, const void *q, const void *K, const void *V,
                         const int32_t *block_table, const int32_t *seq_len, int batch, float scale,
                         int out_dtype, void *out, hipStream_t st);

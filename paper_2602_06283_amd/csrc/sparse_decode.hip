@@ -5,19 +5,40 @@
 // K and V rows, and writes one partial result per split; a second small kernel merges them.
 // Logits use no 1/sqrt(d) unless the caller passes one as `scale`; with unit-variance data
 // they reach +-100, so everything is max-subtracted.
-#include "socket_internal.h"
+//
+// A split owns a fixed range of slots of the selection.  Given the ordered index row, slot r
+// is entry r of that row.  The fused decode step can also start from the unordered lists the
+// select's sweep leaves, without waiting for the ordered row: slot r below the number of
+// positions selected outright is entry r of that list, the slots after them go to the
+// candidates of the threshold bin that make the cut, best first (the workgroups that own such
+// slots rank the few candidates themselves).  The same tokens either way; which split a token
+// lands in then depends on the order in which the sweep's workgroups reserved their list
+// space, so the last bits of the output can differ from run to run.  The ordering of the
+// index row for the caller (topk_resolve_body) then runs beside the merge of the splits, as
+// extra workgroups of that launch.
+#include "topk_device.h"
 
 namespace sk {
 
 #ifdef SK_DEBUG_CLOCKS
 __device__ long long sk_dbg3[64];
-#define SK_STAMP3(i) do { if (threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.y == 0) sk_dbg3[i] = wall_clock64(); } while (0)
+#define SK_STAMP3(i) do { if (threadIdx.x == 0 && split == 0 && h == 0 && b == 0) sk_dbg3[i] = wall_clock64(); } while (0)
 extern "C" int socket_debug_clocks3(long long *out) {
     return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(sk_dbg3), sizeof(long long) * 64);
 }
 #else
 #define SK_STAMP3(i) ((void)0)
 #endif
+
+// where a workgroup's rows come from
+enum RowSource {
+    kRowsIdx = 0,      // its slice of the ordered row idx[b, h, :n_selected]               (Eq. 2)
+    kRowsSweep = 1,    // what the select's sweep left: staged positions + ranked candidates (Eq. 2)
+    kRowsDense = 2,    // every token below seq_len, contiguous ranges                      (Eq. 1)
+};
+constexpr int kSweepCand = kDecodeThreads;        // candidates a decode workgroup ranks itself (one
+                                                  // per thread); a head with more is attended from
+                                                  // the ordered row by its ordering workgroup
 
 struct DecodeArgs {
     const void *q;
@@ -32,6 +53,11 @@ struct DecodeArgs {
     float scale;
     int Hq, max_k, n_split, out_dtype;
     const int32_t *seq_len;   // dense variant only
+    // kRowsSweep: the lists and the threshold record of the select's sweep
+    const int32_t *staged;
+    const uint32_t *cand_key;
+    const int32_t *cand_idx;
+    const uint32_t *thr;
 };
 
 // two adjacent elements of an LDS row as floats
@@ -41,11 +67,19 @@ __device__ __forceinline__ float2 pair_f32(const uint16_t *p) {
 }
 __device__ __forceinline__ float2 pair_f32(const float *p) { return *(const float2 *)p; }
 
-// DENSE = false: the rows are the selected tokens idx[...] (Eq. 2).  DENSE = true: the rows
-// are all tokens below seq_len (Eq. 1), each split takes a contiguous range of them, and the
-// next chunk's rows are loaded while the current chunk is worked on.
-template <typename T, int D, int G, bool DENSE>
-__global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(DecodeArgs a) {
+// dynamic LDS of decode_body: the value tile
+template <typename T, int D> constexpr size_t decode_lds_bytes() {
+    constexpr int ROWB = D * (int)sizeof(T);
+    constexpr int VROWS = kDecodeChunk * ROWB <= 32768 ? kDecodeChunk : 32768 / ROWB;
+    return (size_t)VROWS * ROWB;
+}
+
+// One split of one (sequence, KV head), run by the first kDecodeThreads threads of a workgroup.
+// SRC says where the rows come from (RowSource).  `dyn` is decode_lds_bytes() of LDS.  Returns
+// true when nothing was done: kRowsSweep with more candidates than a workgroup ranks.
+template <typename T, int D, int G, int SRC>
+__device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int h, int b, char *dyn) {
+    constexpr bool DENSE = SRC == kRowsDense;
     constexpr int LPR = D / 8;                       // lanes per row
     constexpr int RPW = 64 / LPR;                    // rows per wavefront pass
     constexpr int NWAVE = kDecodeThreads / 64;
@@ -67,37 +101,59 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(DecodeArg
     __shared__ __align__(16) float s_p[G][CH];       // logits, then softmax numerators
     __shared__ int64_t s_row[CH];                    // K/V row of each chunk entry (-1 = none)
     __shared__ float s_m[G], s_l[G], s_corr[G];
-    __shared__ __align__(16) T s_v[VROWS][D];
+    __shared__ int32_t s_cpos[SRC == kRowsSweep ? kSweepCand : 1];   // candidates that make the cut, best first
+    T (*s_v)[D] = (T (*)[D])dyn;                     // [VROWS][D]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int bh = b * a.map.Hkv + h;
     const int sub = lane % LPR, rl = lane / LPR;     // this lane's 8-element slice and row slot
     const int cp = tid % CPAIRS, g0 = (tid / CPAIRS) * GPG;   // this thread's channel pair and first query head
     const float ninf = -__builtin_inff();
 
-    // Splits own fixed slices of the max_k-long index row, so the index loads do not have to
-    // wait for the selected count; entries at or beyond the count are ignored.  (Dense: whole
-    // chunks of the sequence.)
-    int total = a.max_k;
-    if (DENSE) {
-        total = a.seq_len[b];
-        total = total < 0 ? 0 : (total > a.map.max_n ? a.map.max_n : total);
-    }
-    const int per = DENSE ? (((total + CH - 1) / CH + a.n_split - 1) / a.n_split) * CH
-                          : (total + a.n_split - 1) / a.n_split;
+    // Splits own fixed ranges of the max_k slots, so no load has to wait for the selected
+    // count; slots at or beyond the count are ignored.  (Dense: whole chunks of the sequence.)
+    const int per = (a.max_k + a.n_split - 1) / a.n_split;
     const int r_begin = split * per;
-    const int r_end = min(total, r_begin + per);
-    const int32_t *idx = DENSE ? nullptr : a.idx + (int64_t)bh * a.max_k;
+    int r_end = min(a.max_k, r_begin + per);
 
+    // ---- every load that needs nothing else first, issued before anything waits: the queries,
+    //      the first chunk's list entries, the counts and (kRowsSweep) one candidate per thread
+    //      (the reads stay inside the buffers)
+    Row8<T> qr[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) qr[g].load((const T *)a.q + ((int64_t)b * a.Hq + h * G + g) * D + sub * 8);
+    const int32_t *list = nullptr;
+    int32_t first = -1;                              // the list entry of slot r_begin + tid
+    uint32_t pk = 0;
+    int32_t pp = 0;
+    int count = 0, above = 0, need = 0, n_cand = 0;  // list entries that count; kRowsSweep: see below
+    if (!DENSE) {
+        list = (SRC == kRowsSweep ? a.staged : a.idx) + (int64_t)bh * a.max_k;
+        if (tid < CH && r_begin + tid < r_end) first = list[r_begin + tid];
+    }
+    if (SRC == kRowsSweep) {
+        if (tid < a.map.max_n) {
+            pk = a.cand_key[(int64_t)bh * a.map.max_n + tid];
+            pp = a.cand_idx[(int64_t)bh * a.map.max_n + tid];
+        }
+        // slots [0, above): positions selected outright; [above, k_eff): the `need` best candidates
+        const uint32_t *thr = a.thr + (int64_t)bh * kThrStride;
+        const int k_eff = min((int)thr[0], a.max_k);
+        above = k_eff ? min((int)thr[5], k_eff) : 0;
+        n_cand = k_eff ? (int)thr[6] : 0;
+        need = k_eff - above;
+        count = above;
+        r_end = min(r_end, k_eff);
+    } else if (SRC == kRowsIdx) {
+        count = a.n_selected[bh];
+    }
     SK_STAMP3(0);
+    // too many candidates to rank here: the caller attends the head from the ordered row instead
+    if (SRC == kRowsSweep && n_cand > kSweepCand) return true;
     float qf[G][8];
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-        Row8<T> r;
-        r.load((const T *)a.q + ((int64_t)b * a.Hq + h * G + g) * D + sub * 8);
-        r.get(qf[g]);
-    }
+    for (int g = 0; g < G; ++g) qr[g].get(qf[g]);
+
     float acc[GPG][2];
 #pragma unroll
     for (int gg = 0; gg < GPG; ++gg) acc[gg][0] = acc[gg][1] = 0.0f;
@@ -105,45 +161,28 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(DecodeArg
         s_m[tid] = ninf;
         s_l[tid] = 0.0f;
     }
+
+    // ---- kRowsSweep, splits that own candidate slots: the `need` best candidates on (score,
+    //      then smaller position), by all-pairs ranking
+    if (SRC == kRowsSweep && need > 0 && r_end > above) {
+        unsigned long long *ck = (unsigned long long *)dyn;       // the value tile is not in use yet
+        if (tid < n_cand) ck[tid] = ((unsigned long long)pk << 32) | (0x7fffffffu - (uint32_t)pp);
+        __syncthreads();
+        if (tid < n_cand) {
+            const unsigned long long me = ck[tid];
+            int rank = 0;
+            for (int o = 0; o < n_cand; ++o) rank += ck[o] > me;
+            if (rank < need) s_cpos[rank] = pp;
+        }
+    }
     __syncthreads();
 
+    // one chunk of rows (s_row filled, or kr/vr/rows loaded for the dense source): logits,
+    // running softmax statistics, weighted value rows
     Row8<T> kr[NPASS], vr[NPASS], kn[NPASS], vn[NPASS];
     int64_t rows[NPASS], rown[NPASS];
-    // dense: this lane's rows of the chunk starting at c0, straight from the token positions
-    auto load_dense = [&](int c0, Row8<T> *kd, Row8<T> *vd, int64_t *rd) {
-#pragma unroll
-        for (int p = 0; p < NPASS; ++p) {
-            const int t = c0 + p * RPP + wave * RPW + rl;
-            rd[p] = t < r_end ? a.map.row(b, h, t) : -1;
-            if (rd[p] >= 0) {
-                kd[p].load((const T *)a.K + rd[p] * D + sub * 8);
-                vd[p].load((const T *)a.V + rd[p] * D + sub * 8);
-            } else {
-                kd[p].zero();
-                vd[p].zero();
-            }
-        }
-    };
-    if (DENSE && r_begin < r_end) load_dense(r_begin, kr, vr, rows);
-
-    for (int c0 = r_begin; c0 < r_end; c0 += CH) {
-        if (DENSE) {
-            if (c0 + CH < r_end) load_dense(c0 + CH, kn, vn, rown);
-        } else {
-            // ---- rows of this chunk
-            if (tid < CH) {
-                int r = c0 + tid;
-                int64_t row = -1;
-                if (r < r_end) {
-                    int t = idx[r];
-                    int nsel = a.n_selected[bh];
-                    if (r < nsel && t >= 0 && t < a.map.max_n) row = a.map.row(b, h, t);
-                }
-                s_row[tid] = row;
-            }
-            __syncthreads();
-            SK_STAMP3(1);
-
+    auto attend_chunk = [&]() __attribute__((always_inline)) {
+        if (!DENSE) {
             // ---- gather this chunk's K and V rows together (one memory latency, not two)
 #pragma unroll
             for (int p = 0; p < NPASS; ++p) {
@@ -245,13 +284,58 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(DecodeArg
             }
         }
         __syncthreads();
-        if (DENSE) {
+    };
+
+    if (DENSE) {
+        // Whole chunks of the sequence d_per split; the next chunk's rows are loaded while the
+        // current chunk is worked on.
+        int total = a.seq_len[b];
+        total = total < 0 ? 0 : (total > a.map.max_n ? a.map.max_n : total);
+        const int d_per = (((total + CH - 1) / CH + a.n_split - 1) / a.n_split) * CH;
+        const int d_begin = split * d_per;
+        const int d_end = min(total, d_begin + d_per);
+        auto load_dense = [&](int c0, Row8<T> *kd, Row8<T> *vd, int64_t *rd) __attribute__((always_inline)) {
+#pragma unroll
+            for (int p = 0; p < NPASS; ++p) {
+                const int t = c0 + p * RPP + wave * RPW + rl;
+                rd[p] = t < d_end ? a.map.row(b, h, t) : -1;
+                if (rd[p] >= 0) {
+                    kd[p].load((const T *)a.K + rd[p] * D + sub * 8);
+                    vd[p].load((const T *)a.V + rd[p] * D + sub * 8);
+                } else {
+                    kd[p].zero();
+                    vd[p].zero();
+                }
+            }
+        };
+        if (d_begin < d_end) load_dense(d_begin, kr, vr, rows);
+        for (int c0 = d_begin; c0 < d_end; c0 += CH) {
+            if (c0 + CH < d_end) load_dense(c0 + CH, kn, vn, rown);
+            attend_chunk();
 #pragma unroll
             for (int p = 0; p < NPASS; ++p) {
                 kr[p] = kn[p];
                 vr[p] = vn[p];
                 rows[p] = rown[p];
             }
+        }
+    } else {
+        // ---- this split's slots of the list
+        for (int c0 = r_begin; c0 < r_end; c0 += CH) {
+            if (tid < CH) {
+                const int r = c0 + tid;
+                int64_t row = -1;
+                if (r < r_end) {
+                    int t = -1;
+                    if (r < count) t = c0 == r_begin ? first : list[r];
+                    else if (SRC == kRowsSweep) t = s_cpos[r - above];
+                    if (t >= 0 && t < a.map.max_n) row = a.map.row(b, h, t);
+                }
+                s_row[tid] = row;
+            }
+            __syncthreads();
+            SK_STAMP3(1);
+            attend_chunk();
         }
     }
 
@@ -269,17 +353,25 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(DecodeArg
         part[((int64_t)tid * a.n_split + split) * (D + 2) + 1] = s_l[tid];
     }
     SK_STAMP3(6);
+    return false;
+}
+
+template <typename T, int D, int G, int SRC>
+__global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(DecodeArgs a) {
+    extern __shared__ __align__(16) char decode_lds[];
+    decode_body<T, D, G, SRC>(a, blockIdx.x, blockIdx.y, blockIdx.z, decode_lds);
 }
 
 // Merge of the split-K partial results of one query head: out = sum_s w_s acc_s / sum_s w_s l_s
-// with w_s = exp(m_s - max m).  One workgroup per query head, one thread per output channel;
-// every load of a thread is issued before the first use, so the kernel costs one memory
-// latency.  Runs as a kernel of its own after the partial pass: no fence, no signalling.
+// with w_s = exp(m_s - max m).  One thread per output channel (threads at or beyond D only
+// keep the barriers company); every load of a thread is issued before the first use, so the
+// merge costs one memory latency.  Runs in a launch after the partial pass: no fence, no
+// signalling.  `skip`: do everything but the store.
 template <int D>
-__global__ __launch_bounds__(D) void decode_merge_kernel(DecodeArgs a) {
+__device__ __forceinline__ void merge_body(const DecodeArgs &a, int g, int h, int b, bool skip) {
     __shared__ float s_w[64];
     __shared__ float s_den;
-    const int c = threadIdx.x, g = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int c = threadIdx.x;
     const int G = a.Hq / a.map.Hkv;
     const int64_t head = (int64_t)b * a.Hq + h * G + g;
     const float *part = a.partials + head * a.n_split * (D + 2);
@@ -291,7 +383,7 @@ __global__ __launch_bounds__(D) void decode_merge_kernel(DecodeArgs a) {
     const float l = live ? part[(int64_t)c * (D + 2) + 1] : 0.0f;
     float acc[64];
 #pragma unroll
-    for (int s = 0; s < 64; ++s) acc[s] = s < a.n_split ? part[(int64_t)s * (D + 2) + 2 + c] : 0.0f;
+    for (int s = 0; s < 64; ++s) acc[s] = s < a.n_split && c < D ? part[(int64_t)s * (D + 2) + 2 + c] : 0.0f;
     if (c < 64) {
         const float top = wave_max(m);
         const float w = (m == ninf) ? 0.0f : expf(m - top);
@@ -306,30 +398,98 @@ __global__ __launch_bounds__(D) void decode_merge_kernel(DecodeArgs a) {
         if (s < a.n_split) num = fmaf(s_w[s], acc[s], num);
     const float den = s_den;
     const float y = den > 0.0f ? num / den : 0.0f;
-    if (a.out_dtype == SOCKET_F32) ((float *)a.out)[head * D + c] = y;
-    else ((uint16_t *)a.out)[head * D + c] = f32_to_bf16_rne(y);
+    if (c < D && !skip) {
+        if (a.out_dtype == SOCKET_F32) ((float *)a.out)[head * D + c] = y;
+        else ((uint16_t *)a.out)[head * D + c] = f32_to_bf16_rne(y);
+    }
+    __syncthreads();                                 // s_w may be rewritten by a following call
 }
 
-template <typename T, int D, bool DENSE>
-static int launch_decode_g(const DecodeArgs &a, int G, dim3 grid, hipStream_t st) {
-    switch (G) {
-        case 1: hipLaunchKernelGGL((sparse_decode_kernel<T, D, 1, DENSE>), grid, dim3(kDecodeThreads), 0, st, a); break;
-        case 2: hipLaunchKernelGGL((sparse_decode_kernel<T, D, 2, DENSE>), grid, dim3(kDecodeThreads), 0, st, a); break;
-        case 4: hipLaunchKernelGGL((sparse_decode_kernel<T, D, 4, DENSE>), grid, dim3(kDecodeThreads), 0, st, a); break;
-        case 8: hipLaunchKernelGGL((sparse_decode_kernel<T, D, 8, DENSE>), grid, dim3(kDecodeThreads), 0, st, a); break;
-        default: return SOCKET_EUNSUPPORTED;
+template <int D>
+__global__ __launch_bounds__(D) void decode_merge_kernel(DecodeArgs a) {
+    merge_body<D>(a, blockIdx.x, blockIdx.y, blockIdx.z, false);
+}
+
+// The last launch of the fused decode step: the merge of the splits (workgroups 0 .. n_merge-1,
+// one per query head, the first D threads) beside the ordering of the index row (one workgroup
+// per (sequence, KV head), all kTopkThreads threads), which nothing on the way to the output
+// waits for.  A head whose threshold bin held more candidates than the decode workgroups rank
+// was left alone by them: its ordering workgroup then attends it from the ordered row, split
+// after split, and merges it too (mass ties only; slow and exact).
+template <typename T, int D, int G>
+__global__ __launch_bounds__(kTopkThreads) void merge_resolve_kernel(DecodeArgs a, TopkArgs t, int n_merge) {
+    extern __shared__ __align__(16) char decode_lds[];
+    const int id = blockIdx.x, tid = threadIdx.x;
+    if (id < n_merge) {
+        if (tid >= D) return;
+        const int g = id % G, hb = id / G, h = hb % a.map.Hkv, b = hb / a.map.Hkv;
+        const uint32_t *thr = t.thr + (int64_t)hb * kThrStride;
+        merge_body<D>(a, g, h, b, thr[0] != 0 && thr[6] > (uint32_t)kSweepCand);
+        return;
+    }
+    const int bh = id - n_merge, h = bh % a.map.Hkv, b = bh / a.map.Hkv;
+    const uint32_t *thr = t.thr + (int64_t)bh * kThrStride;
+    const bool redo = thr[0] != 0 && thr[6] > (uint32_t)kSweepCand;
+    topk_resolve_body(t, bh, (uint32_t *)decode_lds);
+    if (!redo) return;
+    __threadfence();
+    __syncthreads();                                 // the ordered row and its count are written
+    if (tid >= kDecodeThreads) return;
+    for (int s = 0; s < a.n_split; ++s) decode_body<T, D, G, kRowsIdx>(a, s, h, b, decode_lds);
+    __threadfence();
+    __syncthreads();                                 // and so are the head's partial results
+    for (int g = 0; g < G; ++g) merge_body<D>(a, g, h, b, false);
+}
+
+// which launch launch_decode makes: a RowSource, or
+constexpr int kMergeResolve = -1;                    // merge_resolve_kernel
+
+template <typename T, int D, int G, int WHAT>
+static int launch_decode_one(const DecodeArgs &a, const TopkArgs *t, dim3 grid, hipStream_t st) {
+    if constexpr (WHAT == kMergeResolve) {
+        constexpr size_t kLds = decode_lds_bytes<T, D>() > kResolveLds ? decode_lds_bytes<T, D>() : kResolveLds;
+        static bool lds_raised = false;   // more than 64 KB of dynamic LDS has to be allowed once per process
+        if (!lds_raised) {
+            if (hipFuncSetAttribute((const void *)merge_resolve_kernel<T, D, G>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds) != hipSuccess)
+                return SOCKET_EHIP;
+            lds_raised = true;
+        }
+        const int BH = (int)(grid.y * grid.z), n_merge = BH * G;
+        hipLaunchKernelGGL((merge_resolve_kernel<T, D, G>), dim3(n_merge + BH), dim3(kTopkThreads), kLds, st,
+                           a, *t, n_merge);
+    } else {
+        constexpr size_t kLds = decode_lds_bytes<T, D>();
+        hipLaunchKernelGGL((sparse_decode_kernel<T, D, G, WHAT>), grid, dim3(kDecodeThreads), kLds, st, a);
     }
     return SOCKET_OK;
 }
 
-template <typename T, bool DENSE>
-static int launch_decode_d(const DecodeArgs &a, int D, int G, dim3 grid, hipStream_t st) {
-    switch (D) {
-        case 64: return launch_decode_g<T, 64, DENSE>(a, G, grid, st);
-        case 128: return launch_decode_g<T, 128, DENSE>(a, G, grid, st);
-        case 256: return launch_decode_g<T, 256, DENSE>(a, G, grid, st);
+template <typename T, int D, int WHAT>
+static int launch_decode_g(const DecodeArgs &a, const TopkArgs *t, int G, dim3 grid, hipStream_t st) {
+    switch (G) {
+        case 1: return launch_decode_one<T, D, 1, WHAT>(a, t, grid, st);
+        case 2: return launch_decode_one<T, D, 2, WHAT>(a, t, grid, st);
+        case 4: return launch_decode_one<T, D, 4, WHAT>(a, t, grid, st);
+        case 8: return launch_decode_one<T, D, 8, WHAT>(a, t, grid, st);
         default: return SOCKET_EUNSUPPORTED;
     }
+}
+
+template <typename T, int WHAT>
+static int launch_decode_d(const DecodeArgs &a, const TopkArgs *t, int D, int G, dim3 grid, hipStream_t st) {
+    switch (D) {
+        case 64: return launch_decode_g<T, 64, WHAT>(a, t, G, grid, st);
+        case 128: return launch_decode_g<T, 128, WHAT>(a, t, G, grid, st);
+        case 256: return launch_decode_g<T, 256, WHAT>(a, t, G, grid, st);
+        default: return SOCKET_EUNSUPPORTED;
+    }
+}
+
+template <int WHAT>
+static int launch_decode(const DecodeArgs &a, const TopkArgs *t, const Geometry &g, dim3 grid, hipStream_t st) {
+    return g.kv_dtype == SOCKET_F32 ? launch_decode_d<float, WHAT>(a, t, g.d, g.G, grid, st)
+                                    : launch_decode_d<uint16_t, WHAT>(a, t, g.d, g.G, grid, st);
 }
 
 static int launch_merge(const DecodeArgs &a, const Geometry &g, int batch, hipStream_t st) {
@@ -343,40 +503,61 @@ static int launch_merge(const DecodeArgs &a, const Geometry &g, int batch, hipSt
     return SOCKET_OK;
 }
 
+static DecodeArgs decode_args(socket_ctx *ctx, const void *q, const void *K, const void *V,
+                              const int32_t *block_table, float scale, int out_dtype, void *out, int n_split) {
+    const Geometry &g = ctx->g;
+    DecodeArgs a;
+    a.q = q; a.K = K; a.V = V; a.idx = nullptr; a.n_selected = nullptr; a.seq_len = nullptr;
+    a.partials = ctx->partials; a.counters = ctx->counters; a.out = out;
+    a.map = RowMap{block_table, g.Hkv, g.max_n, g.page, g.max_blocks, g.num_blocks};
+    a.scale = scale; a.Hq = g.Hq; a.max_k = g.max_k; a.n_split = n_split; a.out_dtype = out_dtype;
+    a.staged = nullptr; a.cand_key = nullptr; a.cand_idx = nullptr; a.thr = nullptr;
+    return a;
+}
+
 // Eq. 1: every token below seq_len, 64 splits per (sequence, KV head)
 int launch_dense_decode(socket_ctx *ctx, const void *q, const void *K, const void *V,
                         const int32_t *block_table, const int32_t *seq_len, int batch, float scale,
                         int out_dtype, void *out, hipStream_t st) {
     const Geometry &g = ctx->g;
-    DecodeArgs a;
-    a.q = q; a.K = K; a.V = V; a.idx = nullptr; a.n_selected = nullptr; a.seq_len = seq_len;
-    a.partials = ctx->partials; a.counters = ctx->counters; a.out = out;
-    a.map = RowMap{block_table, g.Hkv, g.max_n, g.page, g.max_blocks, g.num_blocks};
-    a.scale = scale; a.Hq = g.Hq; a.max_k = g.max_k; a.n_split = kDenseSplits; a.out_dtype = out_dtype;
-    dim3 grid(kDenseSplits, g.Hkv, batch);
-    int rc = g.kv_dtype == SOCKET_F32 ? launch_decode_d<float, true>(a, g.d, g.G, grid, st)
-                                      : launch_decode_d<uint16_t, true>(a, g.d, g.G, grid, st);
+    DecodeArgs a = decode_args(ctx, q, K, V, block_table, scale, out_dtype, out, kDenseSplits);
+    a.seq_len = seq_len;
+    int rc = launch_decode<kRowsDense>(a, nullptr, g, dim3(kDenseSplits, g.Hkv, batch), st);
     if (rc != SOCKET_OK) return rc;
     rc = launch_merge(a, g, batch, st);
     if (rc != SOCKET_OK) return rc;
     return record_hip(ctx, hipGetLastError());
 }
 
+// Eq. 2 from the ordered index row
 int launch_sparse_decode(socket_ctx *ctx, const void *q, const void *K, const void *V,
                          const int32_t *idx, const int32_t *n_selected, const int32_t *block_table,
                          int batch, float scale, int out_dtype, void *out, hipStream_t st) {
     const Geometry &g = ctx->g;
-    DecodeArgs a;
-    a.q = q; a.K = K; a.V = V; a.idx = idx; a.n_selected = n_selected;
-    a.partials = ctx->partials; a.counters = ctx->counters; a.out = out;
-    a.map = RowMap{block_table, g.Hkv, g.max_n, g.page, g.max_blocks, g.num_blocks};
-    a.scale = scale; a.Hq = g.Hq; a.max_k = g.max_k; a.n_split = g.n_split; a.out_dtype = out_dtype;
-    a.seq_len = nullptr;
-    dim3 grid(g.n_split, g.Hkv, batch);
-    int rc = g.kv_dtype == SOCKET_F32 ? launch_decode_d<float, false>(a, g.d, g.G, grid, st)
-                                      : launch_decode_d<uint16_t, false>(a, g.d, g.G, grid, st);
+    DecodeArgs a = decode_args(ctx, q, K, V, block_table, scale, out_dtype, out, g.n_split);
+    a.idx = idx; a.n_selected = n_selected;
+    int rc = launch_decode<kRowsIdx>(a, nullptr, g, dim3(g.n_split, g.Hkv, batch), st);
     if (rc != SOCKET_OK) return rc;
     rc = launch_merge(a, g, batch, st);
+    if (rc != SOCKET_OK) return rc;
+    return record_hip(ctx, hipGetLastError());
+}
+
+// The tail of the fused decode step, after the select's sweep (launch_topk_sweep): Eq. 2 from
+// the sweep's lists, then the merge of the splits beside the ordering of the index row.
+int launch_sweep_decode(socket_ctx *ctx, const void *q, const void *K, const void *V,
+                        const float *scores, const int32_t *seq_len, const int32_t *k,
+                        int32_t *idx, int32_t *n_selected, int hist_mode, const int32_t *block_table,
+                        int batch, float scale, int out_dtype, void *out, hipStream_t st) {
+    const Geometry &g = ctx->g;
+    const TopkArgs t = topk_args(ctx, scores, seq_len, k, idx, n_selected, hist_mode);
+    DecodeArgs a = decode_args(ctx, q, K, V, block_table, scale, out_dtype, out, g.n_split);
+    a.idx = idx; a.n_selected = n_selected;
+    a.staged = t.staged; a.cand_key = t.cand_key; a.cand_idx = t.cand_idx; a.thr = t.thr;
+    const dim3 grid(g.n_split, g.Hkv, batch);
+    int rc = launch_decode<kRowsSweep>(a, nullptr, g, grid, st);
+    if (rc != SOCKET_OK) return rc;
+    rc = launch_decode<kMergeResolve>(a, &t, g, grid, st);
     if (rc != SOCKET_OK) return rc;
     return record_hip(ctx, hipGetLastError());
 }

@@ -518,11 +518,23 @@ def test_runs_are_bitwise_repeatable():
 
 # ------------------------------------------------------------------ fused decode step
 
+def same_step_results(a, f, deterministic, where):
+    """Fused step f against the separate calls a: ids, scores, selection and count bit for bit;
+    the attention output bit for bit in deterministic mode, else to rounding (same tokens, same
+    sum, but which split a token falls in is not fixed)."""
+    for key in a:
+        if key == "out" and not deterministic:
+            assert torch.allclose(a[key], f[key], rtol=1e-5, atol=1e-5), (where, key)
+        else:
+            assert torch.equal(a[key], f[key]), (where, key)
+
+
+@pytest.mark.parametrize("deterministic", [False, True])
 @pytest.mark.parametrize("kv_dtype,L,P,G", [(wl.BF16, 64, 8, 4), (wl.F32, 32, 8, 1), (wl.BF16, 60, 10, 4),
                                             (wl.BF16, 40, 12, 2), (wl.F32, 16, 9, 1)])
-def test_decode_step_equals_separate_calls_and_oracle(kv_dtype, L, P, G):
-    """socket_decode_step must give, bit for bit, what the four separate calls give, for a
-    few consecutive steps; the last step is also checked against the oracle."""
+def test_decode_step_equals_separate_calls_and_oracle(kv_dtype, L, P, G, deterministic):
+    """socket_decode_step must give what the four separate calls give (see same_step_results),
+    for a few consecutive steps; the last step is also checked against the oracle."""
     _need_gpu()
     n0, steps, B, Hkv = 3000, 3, 2, 2
     n = 3072
@@ -530,6 +542,7 @@ def test_decode_step_equals_separate_calls_and_oracle(kv_dtype, L, P, G):
                         seq_len=[n0 + steps, n0 - 500 + steps])
     start = np.array([n0, n0 - 500], dtype=np.int32)
     ctx = hz.make_ctx(layer)
+    ctx.set_deterministic(deterministic)
     Kd, Vd, qd, Wd = (hz.dev(x, layer.kv_dtype) for x in (layer.K, layer.V, layer.q, layer.W))
     max_k = int(layer.k.max())
 
@@ -551,16 +564,16 @@ def test_decode_step_equals_separate_calls_and_oracle(kv_dtype, L, P, G):
         ctx.sparse_decode(qd, Kd, Vd, a["idx"], a["nsel"], B, 1.0, a["out"])
         ctx.decode_step(qd, Kd, Vd, f["codes"], Wd, 0.5, pos, kk, B, 1.0, f["scores"], f["idx"], f["nsel"], f["out"])
         torch.cuda.synchronize()
-        for key in a:
-            assert torch.equal(a[key], f[key]), (s, key)
+        same_step_results(a, f, deterministic, s)
     res = tuple(f[key].cpu().numpy() for key in ("codes", "scores", "idx", "nsel")) + (f["out"].cpu().numpy(),)
     check_chain(layer, *res, atol=1e-4)
     ctx.close()
 
 
+@pytest.mark.parametrize("deterministic", [False, True])
 @pytest.mark.parametrize("case", ["ties_cold", "ties_cold_small_k", "ties_flat", "all_equal", "take_all", "k_one",
                                   "value_norms", "value_norms_heavy", "large", "large_tiny_k"])
-def test_decode_step_select_paths_agree(case):
+def test_decode_step_select_paths_agree(case, deterministic):
     """Inside socket_decode_step the select starts from what the scoring pass leaves: a
     histogram with bins sized from the bucket-probability tables when the scores are
     unweighted, and, when k is a small part of the sequence, lists of the scores above a guessed
@@ -568,7 +581,10 @@ def test_decode_step_select_paths_agree(case):
     All are exact, so they must pick the same tokens - also when nearly all scores tie (tau -> 0
     makes them collision counts, tau -> inf makes them all L/R, identical keys make them one
     value), when k covers the whole sequence, and with value norms (bins then also scaled by a
-    sample of the norms), well behaved or spread over five decades."""
+    sample of the norms), well behaved or spread over five decades.  Without the deterministic
+    switch the attention of the step starts from the select's unordered lists; threshold bins
+    with more candidates than a decode workgroup ranks (the tie cases) take the route through
+    the ordered row inside the last launch."""
     _need_gpu()
     cfg = {
         "ties_cold": dict(n=6000, k=[300, 777], tau=1e-4, lens=[6000, 4100]),
@@ -589,6 +605,7 @@ def test_decode_step_select_paths_agree(case):
     if case == "all_equal":                            # every key the same: all scores tie exactly
         layer.K[:] = layer.K[:, :, :1, :]
     ctx = hz.make_ctx(layer)
+    ctx.set_deterministic(deterministic)
     Kd, Vd, qd, Wd = (hz.dev(x, layer.kv_dtype) for x in (layer.K, layer.V, layer.q, layer.W))
     max_k = int(layer.k.max())
     vn = None
@@ -621,8 +638,7 @@ def test_decode_step_select_paths_agree(case):
         ctx.decode_step(qd, Kd, Vd, f["codes"], Wd, layer.tau, pos, kk, B, 1.0, f["scores"], f["idx"], f["nsel"],
                         f["out"], vnorm=vn)
         torch.cuda.synchronize()
-        for key in a:
-            assert torch.equal(a[key], f[key]), (rep, key)
+        same_step_results(a, f, deterministic, rep)
     # and the selection is the oracle's on the GPU's own scores (exact, ties to the smaller position)
     sc, idx, nsel = (f[key].cpu().numpy() for key in ("scores", "idx", "nsel"))
     for b in range(B):
@@ -759,8 +775,7 @@ def test_forced_sink_and_window_tokens_through_the_chain():
     ctx.sparse_decode(qd, Kd, Vd, a["idx"], a["nsel"], B, 1.0, a["out"])
     ctx.decode_step(qd, Kd, Vd, f["codes"], Wd, 0.5, pos, kk, B, 1.0, f["scores"], f["idx"], f["nsel"], f["out"])
     torch.cuda.synchronize()
-    for key in a:
-        assert torch.equal(a[key], f[key]), key
+    same_step_results(a, f, False, "forced")
     sc, idx, nsel = (f[key].cpu().numpy() for key in ("scores", "idx", "nsel"))
     for b in range(B):
         for h in range(Hkv):
@@ -842,7 +857,8 @@ def test_paged_chain_with_appends_across_page_boundaries(L, P, page):
     ctx.topk_select(scores2, ln, hz.i32(kk), B, idx2, nsel2)
     ctx.sparse_decode(qd, Kd, Vd, idx2, nsel2, B, 1.0, out2, block_table=bt)
     torch.cuda.synchronize()
-    assert torch.equal(scores, scores2) and torch.equal(idx, idx2) and torch.equal(out, out2)
+    assert torch.equal(scores, scores2) and torch.equal(idx, idx2) and torch.equal(nsel, nsel2)
+    assert torch.allclose(out, out2, rtol=1e-5, atol=1e-5)      # same tokens, another split of the sum
     ctx.close()
 
 
