@@ -649,6 +649,41 @@ def test_decode_step_select_paths_agree(case, deterministic):
     ctx.close()
 
 
+def test_decode_step_deterministic_route_is_bitwise_repeatable():
+    """With socket_set_deterministic the fused step gives the same bits on every run; without
+    it the attention output may differ in its last bits (the split a token falls in follows
+    the order in which the select's workgroups reserved list space) and nothing else may."""
+    _need_gpu()
+    B, Hkv, G, L, P, n = 2, 2, 4, 64, 8, 20000
+    lens = np.array([20000, 12345], dtype=np.int32)
+    layer = small_layer(seed=91, B=B, Hq=Hkv * G, Hkv=Hkv, n=n, L=L, P=P, k=[512, 300], seq_len=lens)
+    ctx = hz.make_ctx(layer)
+    Kd, Vd, qd, Wd = (hz.dev(x, layer.kv_dtype) for x in (layer.K, layer.V, layer.q, layer.W))
+    max_k = int(layer.k.max())
+    codes = hz.new_codes((B, Hkv), n, L, P)
+    kk, zero = hz.i32(layer.k), hz.i32(np.zeros(B))
+    ctx.hash_keys(Kd, Wd, zero, hz.i32(lens - 1), B, n, codes)
+    pos = hz.i32(lens - 1)
+
+    def run():
+        r = dict(scores=torch.zeros((B, Hkv, n), dtype=torch.float32, device="cuda"),
+                 idx=torch.zeros((B, Hkv, max_k), dtype=torch.int32, device="cuda"),
+                 nsel=torch.zeros((B, Hkv), dtype=torch.int32, device="cuda"),
+                 out=torch.zeros((B, layer.Hq, layer.d), dtype=torch.float32, device="cuda"))
+        ctx.decode_step(qd, Kd, Vd, codes, Wd, 0.5, pos, kk, B, 1.0, r["scores"], r["idx"], r["nsel"], r["out"])
+        torch.cuda.synchronize()
+        return r
+
+    ctx.set_deterministic(True)
+    ref = run()
+    for _ in range(3):
+        same_step_results(ref, run(), True, "deterministic")
+    ctx.set_deterministic(False)
+    for _ in range(3):
+        same_step_results(ref, run(), False, "fast")
+    ctx.close()
+
+
 # ------------------------------------------------------------------ hard LSH scorer (Eq. 3, hard form)
 
 @pytest.mark.parametrize("L,P,G", [(64, 8, 4), (300, 2, 1), (60, 10, 2)])
