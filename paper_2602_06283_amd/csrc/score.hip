@@ -104,7 +104,10 @@ constexpr int kPlanePad = 16;        // per-plane sigmoids are kept [g][16]; pla
 // The kernel is a chain of short dependent phases bounded by memory and LDS latency, so every
 // phase issues all of its independent loads before the first use, and every dot product is
 // cut into channel ranges that adjacent lanes sum with DPP moves.
-template <typename T, int G>
+// DW: the dword fetch of the W slab is compiled in (bf16 tables whose planes are whole dwords
+// but not whole 16-byte vectors, e.g. 10 planes); the other instantiations stay as lean as
+// they were.
+template <typename T, int G, bool DW>
 __global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
     extern __shared__ double sm64[];
     constexpr int EPV = 16 / (int)sizeof(T);                 // elements per 16-byte vector
@@ -139,10 +142,22 @@ __global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
     }
     const T *Wg = (const T *)a.W + (int64_t)h * d * a.LP + col0;
     const int row_bytes = cols * (int)sizeof(T);
+    // Three ways to fetch the slab: 16-byte vectors when a channel's planes are whole vectors
+    // (8 planes of bf16), dwords when they are whole dwords (10 planes of bf16: 5 each), else
+    // element by element.  i / n for i < 4096 and n <= 16 is a multiplication by ceil(2^16 / n).
     const bool wvec = (row_bytes & 15) == 0 && ((a.LP * (int)sizeof(T)) & 15) == 0;
+    const bool wdw = DW && !wvec && sizeof(T) == 2 && (row_bytes & 3) == 0 && ((a.LP * (int)sizeof(T)) & 3) == 0 &&
+                     ((col0 * (int)sizeof(T)) & 3) == 0;
     const int nvec = row_bytes >> 4;                         // 16-byte vectors per channel (vector path)
-    constexpr int WV = 4, WE = 16;
+    const int ndw = row_bytes >> 2;                          // dwords per channel (dword path)
+    auto div_small = [](int i, int n, int &rem) {
+        const int q = (int)(((uint32_t)i * ((65536u + (uint32_t)n - 1u) / (uint32_t)n)) >> 16);
+        rem = i - q * n;
+        return q;
+    };
+    constexpr int WV = 4, WD = DW ? 8 : 1, WE = 16;
     uint4 wv[WV];
+    uint32_t wq[WD];
     T we[WE];
     if (live && wvec) {
 #pragma unroll
@@ -150,11 +165,21 @@ __global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
             const int i = tid + j * 256;
             if (i < d * nvec) wv[j] = *(const uint4 *)(Wg + (int64_t)(i / nvec) * a.LP + (i % nvec) * EPV);
         }
+    } else if (live && wdw) {
+#pragma unroll
+        for (int j = 0; j < WD; ++j) {
+            const int i = tid + j * 256;
+            int part;
+            const int c = div_small(i, ndw, part);
+            if (i < d * ndw) wq[j] = *(const uint32_t *)((const char *)(Wg + (int64_t)c * a.LP) + part * 4);
+        }
     } else if (live) {
 #pragma unroll
         for (int j = 0; j < WE; ++j) {
             const int i = tid + j * 256;
-            if (i < d * cols) we[j] = Wg[(int64_t)(i / cols) * a.LP + i % cols];
+            int part;
+            const int c = div_small(i, cols, part);
+            if (i < d * cols) we[j] = Wg[(int64_t)c * a.LP + part];
         }
     }
     constexpr int QV = (G * 256 * (int)sizeof(T) / 16 + 255) / 256;   // d <= 256
@@ -202,14 +227,30 @@ __global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
                 }
             }
         }
+    } else if (live && wdw) {
+#pragma unroll
+        for (int j = 0; j < WD; ++j) {
+            const int i = tid + j * 256;
+            if (i < d * ndw) {
+                int part;
+                const int c = div_small(i, ndw, part);
+                const float f0 = __uint_as_float(wq[j] << 16), f1 = __uint_as_float(wq[j] & 0xffff0000u);   // two bf16
+                wf[(2 * part) * d + c] = f0;
+                wd[(2 * part) * d + c] = (double)f0;
+                wf[(2 * part + 1) * d + c] = f1;
+                wd[(2 * part + 1) * d + c] = (double)f1;
+            }
+        }
     } else if (live) {
 #pragma unroll
         for (int j = 0; j < WE; ++j) {
             const int i = tid + j * 256;
             if (i < d * cols) {
                 const float f = elem_to_f32<T>(we[j]);
-                wf[(i % cols) * d + i / cols] = f;
-                wd[(i % cols) * d + i / cols] = (double)f;
+                int part;
+                const int c = div_small(i, cols, part);
+                wf[part * d + c] = f;
+                wd[part * d + c] = (double)f;
             }
         }
     }
@@ -376,19 +417,37 @@ __global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
             __syncthreads();
         }
         float dev2 = 0.0f;
-        for (int r = tid; r < a.R; r += 256) {
+        if (split) {
+            // four consecutive buckets per thread, stored as one 16-byte piece: a group's table
+            // is kept as [bucket / 4][table][4] (the other tables of the group come from other
+            // workgroups, so longer contiguous runs per table mean fewer partial writes)
+            for (int r4 = tid; r4 < (a.R >> 2); r4 += 256) {
+                float v[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int r = 4 * r4 + j;
+                    double mean = 0.0;
+                    if (live) {
+#pragma unroll
+                        for (int g = 0; g < G; ++g) mean += ab[g * kAb + (r & 255)] * ab[g * kAb + 256 + (r >> 8)];
+                        mean *= inv_g;
+                        const double dv = mean - inv_r;
+                        dev2 += (float)(dv * dv);
+                    }
+                    v[j] = (float)mean;
+                }
+                *(float4 *)&Tg[(((int64_t)(l / a.GT) * (a.R >> 2) + r4) * a.GT + l % a.GT) * 4] =
+                    make_float4(v[0], v[1], v[2], v[3]);
+            }
+        }
+        for (int r = tid; r < a.R && !split; r += 256) {
             double mean = 0.0;
             if (live) {
 #pragma unroll
-                for (int g = 0; g < G; ++g)
-                    mean += split ? ab[g * kAb + (r & 255)] * ab[g * kAb + 256 + (r >> 8)] : plane_product(g, 0, r);
+                for (int g = 0; g < G; ++g) mean += plane_product(g, 0, r);
                 mean *= inv_g;
                 const double dv = mean - inv_r;      // a table's entries sum to 1: their mean is 1/R
                 dev2 += (float)(dv * dv);
-            }
-            if (split) {
-                Tg[((int64_t)(l / a.GT) * a.R + r) * a.GT + l % a.GT] = (float)mean;
-                continue;
             }
             for (int cp = 0; cp < copies; ++cp) Tg[((int64_t)c64 * a.R + r) * 64 + lp + cp * lw] = (float)mean;
         }
@@ -981,12 +1040,19 @@ __global__ __launch_bounds__(kSplitThreads) void score_split_kernel(ScoreArgs a)
             tp[j] = i < n4 ? src[i] : make_float4(0, 0, 0, 0);
         }
     };
+    // memory keeps a group's table as [bucket / 4][table][4]; LDS wants [bucket][table] (bank =
+    // table): piece i holds buckets 4 (i / GT) .. + 3 of table i % GT
     auto table_commit = [&]() __attribute__((always_inline)) {
-        float4 *dst = (float4 *)tbl;
 #pragma unroll
         for (int j = 0; j < TP; ++j) {
             const int i = tid + j * kSplitThreads;
-            if (i < n4) dst[i] = tp[j];
+            if (i < n4) {
+                float *dst = tbl + (4 * (i / GT)) * GT + i % GT;
+                dst[0] = tp[j].x;
+                dst[GT] = tp[j].y;
+                dst[2 * GT] = tp[j].z;
+                dst[3 * GT] = tp[j].w;
+            }
         }
     };
 
@@ -1112,11 +1178,12 @@ int launch_project(socket_ctx *ctx, const void *q, const void *proj, float tau, 
     typedef void (*project_fn_t)(ProjectArgs);
     project_fn_t fn = nullptr;
     const bool f32 = g.kv_dtype == SOCKET_F32;
+    const bool dw = !f32 && (g.P * 2) % 16 != 0 && (g.P * 2) % 4 == 0;    // see project_kernel
     switch (g.G) {
-        case 1: fn = f32 ? project_kernel<float, 1> : project_kernel<uint16_t, 1>; break;
-        case 2: fn = f32 ? project_kernel<float, 2> : project_kernel<uint16_t, 2>; break;
-        case 4: fn = f32 ? project_kernel<float, 4> : project_kernel<uint16_t, 4>; break;
-        case 8: fn = f32 ? project_kernel<float, 8> : project_kernel<uint16_t, 8>; break;
+        case 1: fn = f32 ? project_kernel<float, 1, false> : dw ? project_kernel<uint16_t, 1, true> : project_kernel<uint16_t, 1, false>; break;
+        case 2: fn = f32 ? project_kernel<float, 2, false> : dw ? project_kernel<uint16_t, 2, true> : project_kernel<uint16_t, 2, false>; break;
+        case 4: fn = f32 ? project_kernel<float, 4, false> : dw ? project_kernel<uint16_t, 4, true> : project_kernel<uint16_t, 4, false>; break;
+        case 8: fn = f32 ? project_kernel<float, 8, false> : dw ? project_kernel<uint16_t, 8, true> : project_kernel<uint16_t, 8, false>; break;
         default: return SOCKET_EUNSUPPORTED;
     }
     if (set_lds_limit((const void *)fn, lds) != SOCKET_OK) return SOCKET_EHIP;

@@ -36,7 +36,7 @@ constexpr int kThrBinInv = 9;        // and reciprocal width
 // In both, word w of the 64 holds table l' = w % min(Lpad, 64); tables >= L hold 0.
 //   split  : P = 9 or 10 (up to 1024 buckets): one entry per (table, bucket) as in `direct`,
 //            but too large for LDS as a whole, so it is cut by tables into groups of
-//            GT = min(Lpad, 32): T[group][r][GT] floats; the scoring kernel takes the groups
+//            GT = min(Lpad, 32): T[group][r / 4][GT][4] floats; the scoring kernel takes the groups
 //            one after the other (a 32-table group of 1024 buckets is 128 KB).  Goes with the
 //            packed 10-bit id layout (see socket.h).
 enum TableMode { kDirect = 0, kFactor = 1, kSplit = 2 };
