@@ -25,7 +25,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 MEASURED_SCORE_TRAFFIC = {("128k", 32): 73876 * 1024}   # bytes per score_kernel launch
 
 WORKLOADS = {
-    # name: (n, k, seed)   -- BASELINE configs[2] and configs[1]
+    # name: (n, k, seed)   -- the 128K roofline workload and the 32K one
     "128k": (131072, 2048, 1002),
     "32k": (32768, 1024, 1001),
 }

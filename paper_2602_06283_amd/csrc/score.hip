@@ -686,18 +686,35 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
             }
         }
     };
+    // (keys at or beyond the sequence, which only the leftover region has, read the last row
+    // of the buffer instead and are marked dead: every set is the same sequence of loads, so
+    // the number of loads in flight stays known)
     auto load_set = [&](CodeVec<CB> *cv, bool *dead, float *w, int base) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) cv[u].load(code_ptr(base + u * KPW + kk, 0, dead[u]));
+        for (int u = 0; u < U; ++u) {
+            const int key = base + u * KPW + kk;
+            cv[u].load(code_ptr(min(key, max_n - 1), 0, dead[u]));
+            dead[u] = dead[u] || key >= seq;
+        }
         load_weights(w, base);
     };
     auto chunk_base = [&](int r) { return (r * stride + (int)blockIdx.x) * CKEYS + wave * WKEYS; };
 
     constexpr bool PREFETCH = ONE_ROUND;
+    // The leftover region is taken U passes at a time per wavefront.  With PREFETCH a
+    // wavefront's first such set rides the ping-pong below as one more round (its loads in
+    // flight during the last whole chunk's look-ups) instead of costing a memory latency of
+    // its own at the end of the kernel: a sequence length that is not a whole number of rounds,
+    // the usual case while decoding, then costs what the next whole number would.
+    const int npass = (max_n - left0 + KPW - 1) / KPW;
+    const int p_first = ((int)blockIdx.x * NW + wave) * U;
+    const int left_base = left0 + p_first * KPW;
+    const int nr = nround + (PREFETCH && p_first < npass ? 1 : 0);
+    auto round_base = [&](int r) { return r < nround ? chunk_base(r) : left_base; };
     CodeVec<CB> setA[U], setB[U];
     bool deadA[U], deadB[U];
     float wgtA[EPL], wgtB[EPL];
-    if (PREFETCH && nround > 0) load_set(setA, deadA, wgtA, chunk_base(0));
+    if (PREFETCH && nr > 0) load_set(setA, deadA, wgtA, round_base(0));
     // Adaptive histogram: if the keys' bucket ids were uniform, a score would have mean L/R and
     // variance sum_l var_l; bins are laid from four deviations below that mean upwards.
     float var_part = 0.0f, nu1_part = 0.0f, nu2_part = 0.0f;
@@ -768,12 +785,12 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
         };
         if (PREFETCH) {
             int r = 0;
-            while (r < nround) {
-                if (r + 1 < nround) load_set(setB, deadB, wgtB, chunk_base(r + 1));
-                process(setA, deadA, wgtA, chunk_base(r));
-                if (++r >= nround) break;
-                if (r + 1 < nround) load_set(setA, deadA, wgtA, chunk_base(r + 1));
-                process(setB, deadB, wgtB, chunk_base(r));
+            while (r < nr) {
+                if (r + 1 < nr) load_set(setB, deadB, wgtB, round_base(r + 1));
+                process(setA, deadA, wgtA, round_base(r));
+                if (++r >= nr) break;
+                if (r + 1 < nr) load_set(setA, deadA, wgtA, round_base(r + 1));
+                process(setB, deadB, wgtB, round_base(r));
                 ++r;
             }
         } else {
@@ -800,9 +817,8 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
     if (tbase == 0) full_chunks(BoolTag<true>());
     else full_chunks(BoolTag<false>());
 
-    // ---- leftover keys and the -inf fill beyond the sequence, U passes at a time per wavefront
-    const int npass = (max_n - left0 + KPW - 1) / KPW;
-    for (int p0 = ((int)blockIdx.x * NW + wave) * U; p0 < npass; p0 += stride * NW * U) {
+    // ---- (the rest of) the leftover keys and the -inf fill beyond the sequence
+    for (int p0 = p_first + (nr > nround ? stride * NW * U : 0); p0 < npass; p0 += stride * NW * U) {
         const int base = left0 + p0 * KPW;
         float sum[U], w[EPL];
         bool dead[U];
