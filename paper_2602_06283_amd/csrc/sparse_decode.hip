@@ -36,9 +36,10 @@ enum RowSource {
     kRowsSweep = 1,    // what the select's sweep left: staged positions + ranked candidates (Eq. 2)
     kRowsDense = 2,    // every token below seq_len, contiguous ranges                      (Eq. 1)
 };
-constexpr int kSweepCand = kDecodeThreads;        // candidates a decode workgroup ranks itself (one
-                                                  // per thread); a head with more is attended from
-                                                  // the ordered row by its ordering workgroup
+constexpr int kCandPer = 2;                       // candidates per thread of a decode workgroup
+constexpr int kSweepCand = kCandPer * kDecodeThreads;   // candidates a decode workgroup ranks itself; a
+                                                  // head with more is attended from the ordered
+                                                  // row by its ordering workgroup
 
 struct DecodeArgs {
     const void *q;
@@ -124,17 +125,19 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
     for (int g = 0; g < G; ++g) qr[g].load((const T *)a.q + ((int64_t)b * a.Hq + h * G + g) * D + sub * 8);
     const int32_t *list = nullptr;
     int32_t first = -1;                              // the list entry of slot r_begin + tid
-    uint32_t pk = 0;
-    int32_t pp = 0;
+    uint32_t pk[kCandPer];
+    int32_t pp[kCandPer];
     int count = 0, above = 0, need = 0, n_cand = 0;  // list entries that count; kRowsSweep: see below
     if (!DENSE) {
         list = (SRC == kRowsSweep ? a.staged : a.idx) + (int64_t)bh * a.max_k;
         if (tid < CH && r_begin + tid < r_end) first = list[r_begin + tid];
     }
     if (SRC == kRowsSweep) {
-        if (tid < a.map.max_n) {
-            pk = a.cand_key[(int64_t)bh * a.map.max_n + tid];
-            pp = a.cand_idx[(int64_t)bh * a.map.max_n + tid];
+#pragma unroll
+        for (int j = 0; j < kCandPer; ++j) {
+            const int i = tid + j * kDecodeThreads;
+            pk[j] = i < a.map.max_n ? a.cand_key[(int64_t)bh * a.map.max_n + i] : 0u;
+            pp[j] = i < a.map.max_n ? a.cand_idx[(int64_t)bh * a.map.max_n + i] : 0;
         }
         // slots [0, above): positions selected outright; [above, k_eff): the `need` best candidates
         const uint32_t *thr = a.thr + (int64_t)bh * kThrStride;
@@ -166,13 +169,21 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
     //      then smaller position), by all-pairs ranking
     if (SRC == kRowsSweep && need > 0 && r_end > above) {
         unsigned long long *ck = (unsigned long long *)dyn;       // the value tile is not in use yet
-        if (tid < n_cand) ck[tid] = ((unsigned long long)pk << 32) | (0x7fffffffu - (uint32_t)pp);
+#pragma unroll
+        for (int j = 0; j < kCandPer; ++j) {
+            const int i = tid + j * kDecodeThreads;
+            if (i < n_cand) ck[i] = ((unsigned long long)pk[j] << 32) | (0x7fffffffu - (uint32_t)pp[j]);
+        }
         __syncthreads();
-        if (tid < n_cand) {
-            const unsigned long long me = ck[tid];
-            int rank = 0;
-            for (int o = 0; o < n_cand; ++o) rank += ck[o] > me;
-            if (rank < need) s_cpos[rank] = pp;
+#pragma unroll
+        for (int j = 0; j < kCandPer; ++j) {
+            const int i = tid + j * kDecodeThreads;
+            if (i < n_cand) {
+                const unsigned long long me = ck[i];
+                int rank = 0;
+                for (int o = 0; o < n_cand; ++o) rank += ck[o] > me;
+                if (rank < need) s_cpos[rank] = pp[j];
+            }
         }
     }
     __syncthreads();

@@ -572,7 +572,8 @@ def test_decode_step_equals_separate_calls_and_oracle(kv_dtype, L, P, G, determi
 
 @pytest.mark.parametrize("deterministic", [False, True])
 @pytest.mark.parametrize("case", ["ties_cold", "ties_cold_small_k", "ties_flat", "all_equal", "take_all", "k_one",
-                                  "value_norms", "value_norms_heavy", "large", "large_tiny_k"])
+                                  "value_norms", "value_norms_heavy", "large", "large_tiny_k", "tie_group_400",
+                                  "tie_group_700"])
 def test_decode_step_select_paths_agree(case, deterministic):
     """Inside socket_decode_step the select starts from what the scoring pass leaves: a
     histogram with bins sized from the bucket-probability tables when the scores are
@@ -597,6 +598,10 @@ def test_decode_step_select_paths_agree(case, deterministic):
         "value_norms_heavy": dict(n=6000, k=[256, 100], tau=0.5, lens=[6000, 3333]),
         "large": dict(n=40000, k=[1024, 512], tau=0.5, lens=[40000, 23456]),
         "large_tiny_k": dict(n=40000, k=[16, 1], tau=0.5, lens=[40000, 300]),
+        # a group of identical, well-scoring keys straddles the cut: that many candidates tie in
+        # the threshold bin (400: ranked by the attention workgroups; 700: the ordered route)
+        "tie_group_400": dict(n=6000, k=[300, 250], tau=0.5, lens=[6000, 5000]),
+        "tie_group_700": dict(n=6000, k=[300, 250], tau=0.5, lens=[6000, 5000]),
     }[case]
     B, Hkv, G, L, P = 2, 2, 4, 64, 8
     n = (cfg["n"] + 31) // 16 * 16
@@ -604,6 +609,11 @@ def test_decode_step_select_paths_agree(case, deterministic):
     layer = small_layer(seed=71, B=B, Hq=Hkv * G, Hkv=Hkv, n=n, L=L, P=P, k=cfg["k"], seq_len=lens, tau=cfg["tau"])
     if case == "all_equal":                            # every key the same: all scores tie exactly
         layer.K[:] = layer.K[:, :, :1, :]
+    if case.startswith("tie_group"):                   # copies of a key close to the head's first query
+        m = int(case.rsplit("_", 1)[1])
+        for b in range(B):
+            for h in range(Hkv):
+                layer.K[b, h, 1000:1000 + 3 * m:3, :] = layer.q[b, h * G, :]
     ctx = hz.make_ctx(layer)
     ctx.set_deterministic(deterministic)
     Kd, Vd, qd, Wd = (hz.dev(x, layer.kv_dtype) for x in (layer.K, layer.V, layer.q, layer.W))
