@@ -585,7 +585,7 @@ int launch_hash_keys(socket_ctx *ctx, const void *K, const void *proj, const int
     const Geometry &g = ctx->g;
     HashArgs a;
     a.K = K; a.W = proj; a.codes = codes; a.row_begin = row_begin; a.row_count = row_count;
-    a.map = RowMap{block_table, g.Hkv, g.max_n, g.page, g.max_blocks, g.num_blocks};
+    a.map = row_map(g, block_table);
     a.d = g.d; a.L = g.L; a.P = g.P; a.LP = g.L * g.P; a.Lpad = g.Lpad; a.S = g.S; a.cb = g.cb;
     a.GT = g.mode == kSplit ? g.GT : 0;
     a.rows_per_wg = 0; a.tables_per_chunk = g.L; a.n_chunks = 1;

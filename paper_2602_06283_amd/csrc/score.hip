@@ -1181,7 +1181,7 @@ int launch_project(socket_ctx *ctx, const void *q, const void *proj, float tau, 
     a.q = q; a.W = proj; a.tables = ctx->tables; a.tstats = ctx->tstats; a.tau = (double)tau;
     a.x_scale = 2.0 / (sqrt((double)g.d) * (double)tau);
     a.K = K; a.codes = codes; a.pos = pos; a.count = count; a.len_out = len_out;
-    a.map = RowMap{block_table, g.Hkv, g.max_n, g.page, g.max_blocks, g.num_blocks};
+    a.map = row_map(g, block_table);
     a.d = g.d; a.G = g.G; a.Hkv = g.Hkv; a.Hq = g.Hq; a.L = g.L; a.P = g.P; a.LP = g.L * g.P;
     a.Lpad = g.Lpad; a.S = g.S; a.cb = g.cb; a.rounds = g.rounds; a.R = g.R; a.mode = g.mode;
     a.Plo = g.Plo; a.Phi = g.Phi; a.Rlo = g.Rlo; a.Rhi = g.Rhi; a.table_rows = g.table_rows;
@@ -1231,7 +1231,7 @@ int launch_score_keys(socket_ctx *ctx, const void *codes, const float *vnorm,
     a.n_sink = ctx->n_sink; a.n_window = ctx->n_window;
     a.thr = ctx->counters + (int64_t)g.max_batch * g.Hkv * kCounterStride;
     a.codes = codes; a.tables = ctx->tables; a.vnorm = vnorm; a.seq_len = seq_len; a.scores = scores;
-    a.map = RowMap{block_table, g.Hkv, g.max_n, g.page, g.max_blocks, g.num_blocks};
+    a.map = row_map(g, block_table);
     a.Lpad = g.Lpad; a.rounds = g.rounds; a.R = g.R; a.G = g.G; a.Plo = g.Plo; a.Rlo = g.Rlo;
     a.table_rows = g.table_rows; a.table_words = g.table_words;
     if (g.mode == kSplit) {

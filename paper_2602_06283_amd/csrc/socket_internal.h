@@ -289,13 +289,29 @@ __host__ __device__ __forceinline__ int packed_pos(int tl, int t, int S) {
 struct RowMap {
     const int32_t *block_table;  // null = contiguous
     int Hkv, max_n, page, max_blocks, num_blocks;
+    int page_shift;              // log2(page) when the page size is a power of two, else -1
     // -1 when the token's block is absent (paged storage with an out-of-range table entry)
     __device__ __forceinline__ int64_t row(int b, int h, int t) const {
         if (block_table == nullptr) return ((int64_t)b * Hkv + h) * max_n + t;
-        int blk = block_table[(int64_t)b * max_blocks + t / page];
+        int slot, off;
+        if (page_shift >= 0) {   // the usual case: a shift and a mask instead of a division
+            slot = t >> page_shift;
+            off = t & (page - 1);
+        } else {
+            slot = t / page;
+            off = t - slot * page;
+        }
+        int blk = block_table[(int64_t)b * max_blocks + slot];
         if ((unsigned)blk >= (unsigned)num_blocks) return -1;
-        return ((int64_t)blk * Hkv + h) * page + (t % page);
+        return ((int64_t)blk * Hkv + h) * page + off;
     }
 };
+
+inline RowMap row_map(const Geometry &g, const int32_t *block_table) {
+    int shift = -1;
+    if (g.page > 0 && (g.page & (g.page - 1)) == 0)
+        for (shift = 0; (1 << shift) < g.page; ++shift) {}
+    return RowMap{block_table, g.Hkv, g.max_n, g.page, g.max_blocks, g.num_blocks, shift};
+}
 
 }  // namespace sk

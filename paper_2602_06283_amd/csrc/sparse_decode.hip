@@ -520,7 +520,7 @@ static DecodeArgs decode_args(socket_ctx *ctx, const void *q, const void *K, con
     DecodeArgs a;
     a.q = q; a.K = K; a.V = V; a.idx = nullptr; a.n_selected = nullptr; a.seq_len = nullptr;
     a.partials = ctx->partials; a.counters = ctx->counters; a.out = out;
-    a.map = RowMap{block_table, g.Hkv, g.max_n, g.page, g.max_blocks, g.num_blocks};
+    a.map = row_map(g, block_table);
     a.scale = scale; a.Hq = g.Hq; a.max_k = g.max_k; a.n_split = n_split; a.out_dtype = out_dtype;
     a.staged = nullptr; a.cand_key = nullptr; a.cand_idx = nullptr; a.thr = nullptr;
     return a;

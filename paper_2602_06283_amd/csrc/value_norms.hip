@@ -57,7 +57,7 @@ int launch_value_norms(socket_ctx *ctx, const void *V, const int32_t *block_tabl
     const Geometry &g = ctx->g;
     NormArgs a;
     a.V = V; a.vnorm = vnorm; a.row_begin = row_begin; a.row_count = row_count;
-    a.map = RowMap{block_table, g.Hkv, g.max_n, g.page, g.max_blocks, g.num_blocks};
+    a.map = row_map(g, block_table);
     const int rows_per_wg = (kNormThreads / (g.d / 8)) * kNormPasses;
     dim3 grid((max_rows + rows_per_wg - 1) / rows_per_wg, g.Hkv, batch);
     const bool f32 = g.kv_dtype == SOCKET_F32;
