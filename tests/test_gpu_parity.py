@@ -659,6 +659,51 @@ def test_decode_step_select_paths_agree(case, deterministic):
     ctx.close()
 
 
+@pytest.mark.parametrize("kv_dtype,d,G,n,k", [
+    (wl.BF16, 64, 8, 9008, [700, 64]),        # narrow heads, a full group of 8 queries
+    (wl.F32, 256, 2, 5008, [300, 299]),       # wide fp32 rows: the value tile takes two rounds per chunk
+    (wl.BF16, 256, 1, 7008, [1000, 1]),
+    (wl.BF16, 128, 4, 12000, [5000, 4100]),   # more than 64 rows per split: several chunks per workgroup
+    (wl.F32, 64, 1, 3008, [2999, 5]),         # nearly everything selected
+])
+def test_decode_step_shapes(kv_dtype, d, G, n, k):
+    """The fused step against the separate calls over head widths, group sizes, element types
+    and selection sizes that change how the attention workgroups cut up their work."""
+    _need_gpu()
+    B, Hkv, L, P = 2, 2, 32, 8
+    lens = np.array([n, n - n // 3], dtype=np.int32)
+    layer = small_layer(seed=97, B=B, Hq=Hkv * G, Hkv=Hkv, d=d, n=n, L=L, P=P, k=k, kv_dtype=kv_dtype, seq_len=lens)
+    Kd, Vd, qd, Wd = (hz.dev(x, layer.kv_dtype) for x in (layer.K, layer.V, layer.q, layer.W))
+    max_k = int(layer.k.max())
+    kk, zero, one = hz.i32(layer.k), hz.i32(np.zeros(B)), hz.i32(np.ones(B))
+    pos, ln = hz.i32(lens - 1), hz.i32(lens)
+    for deterministic in (False, True):
+        ctx = hz.make_ctx(layer)
+        ctx.set_deterministic(deterministic)
+
+        def fresh():
+            return dict(codes=hz.new_codes((B, Hkv), n, L, P),
+                        scores=torch.zeros((B, Hkv, n), dtype=torch.float32, device="cuda"),
+                        idx=torch.zeros((B, Hkv, max_k), dtype=torch.int32, device="cuda"),
+                        nsel=torch.zeros((B, Hkv), dtype=torch.int32, device="cuda"),
+                        out=torch.zeros((B, layer.Hq, layer.d), dtype=torch.float32, device="cuda"))
+        a, f = fresh(), fresh()
+        for t in (a, f):
+            ctx.hash_keys(Kd, Wd, zero, hz.i32(lens - 1), B, n, t["codes"])
+        ctx.hash_keys(Kd, Wd, pos, one, B, 1, a["codes"])
+        ctx.score(qd, a["codes"], Wd, 0.5, ln, B, a["scores"])
+        ctx.topk_select(a["scores"], ln, kk, B, a["idx"], a["nsel"])
+        ctx.sparse_decode(qd, Kd, Vd, a["idx"], a["nsel"], B, 1.0, a["out"])
+        for rep in range(2):
+            ctx.decode_step(qd, Kd, Vd, f["codes"], Wd, 0.5, pos, kk, B, 1.0, f["scores"], f["idx"], f["nsel"], f["out"])
+            torch.cuda.synchronize()
+            same_step_results(a, f, deterministic, (deterministic, rep))
+        if deterministic:
+            res = tuple(f[key].cpu().numpy() for key in ("codes", "scores", "idx", "nsel")) + (f["out"].cpu().numpy(),)
+            check_chain(layer, *res, atol=1e-4)
+        ctx.close()
+
+
 def test_decode_step_deterministic_route_is_bitwise_repeatable():
     """With socket_set_deterministic the fused step gives the same bits on every run; without
     it the attention output may differ in its last bits (the split a token falls in follows
