@@ -12,8 +12,8 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
-OBJ = os.environ.get("SK_OBJ_DIR", os.path.join(HERE, "_build"))
-LIB = os.environ.get("SK_LIB_OUT", os.path.join(HERE, "libsocket.so"))
+OBJ = os.path.join(HERE, "_build")
+LIB = os.path.join(HERE, "libsocket.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 SOURCES = ["socket_api.hip", "hash_keys.hip", "score.hip", "topk.hip", "sparse_decode.hip", "value_norms.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
@@ -21,12 +21,9 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
-EXTRA = os.environ.get("SK_EXTRA_FLAGS", "").split()     # experiments: e.g. -DSK_SCORE_U=8
-
-
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-    cmd = [HIPCC] + FLAGS + EXTRA + ["-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{r.stdout}")

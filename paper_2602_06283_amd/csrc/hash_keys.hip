@@ -397,10 +397,7 @@ __global__ __launch_bounds__(256) void hash_wfrag_kernel(HashArgs a, uint4 *wfra
 
 template <int V> struct IntTag { static constexpr int value = V; };
 
-#ifndef SK_HASH8_THREADS
-#define SK_HASH8_THREADS 1024
-#endif
-constexpr int kHash8Threads = SK_HASH8_THREADS;
+constexpr int kHash8Threads = 1024;
 
 template <int D>
 __global__ __launch_bounds__(kHash8Threads) void hash_mfma8_kernel(HashArgs a, const uint4 *wfrag) {

@@ -17,16 +17,6 @@
 
 namespace sk {
 
-#ifdef SK_DEBUG_CLOCKS
-__device__ long long sk_dbg2[64];
-#define SK_STAMP2(i) do { if (threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.y == 0) { sk_dbg2[i] = wall_clock64(); sk_dbg2[32 + i] = clock64(); } } while (0)
-extern "C" int socket_debug_clocks2(long long *out) {
-    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(sk_dbg2), sizeof(long long) * 64);
-}
-#else
-#define SK_STAMP2(i) ((void)0)
-#endif
-
 struct ProjectArgs {
     const void *q;          // [B, Hq, d]; null = no soft hash
     const void *W;          // [Hkv, d, L*P]
@@ -45,6 +35,7 @@ struct ProjectArgs {
     RowMap map;
     int d, G, Hkv, Hq, L, P, LP, Lpad, S, cb, rounds, R, mode, Plo, Phi, Rlo, Rhi, table_rows;
     int GT;                 // split mode: tables per group
+    int batch, nb;          // sequences in the call; sequences one workgroup serves (batched kernel)
     int cols_magic;         // ceil(2^16 / P): x / P == (x * cols_magic) >> 16 for x < 2^12
     int64_t table_words;
 };
@@ -131,7 +122,6 @@ __global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
     float *kf = wf + cols * d;                               // [d]
     uint32_t *sgn = (uint32_t *)(kf + d);                    // [16] sign bits of the key's projections
     float *s_dev = (float *)(sgn + 16);                      // [12]
-    SK_STAMP2(0);
 
     // ---- every global load of the kernel is issued here, before the first one is used
     int tok = 0;
@@ -275,7 +265,6 @@ __global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
     }
     if (tid < 16) sgn[tid] = 0;
     __syncthreads();
-    SK_STAMP2(1);
 
     // ---- appended key: 16 lanes per hyperplane, fp32 FMA over a 16th of the channels each
     if (app && live) {
@@ -298,7 +287,6 @@ __global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
         acc = row_sum<16>(acc);
         if (pl < cols && part == 0) sgn[pl] = acc >= 0.0f ? 1u : 0u;
     }
-    SK_STAMP2(8);
     // ---- queries: fp64 dot products, tpp lanes each; then u = tanh(z)/sqrt(d) and the
     //      per-plane sigmoids of +-2u/tau
     if (soft && live) {
@@ -329,9 +317,7 @@ __global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
                 z1 = fma(wv2[e].y, qv2[e].y, z1);
             }
         }
-        SK_STAMP2(9);
         const double z = group_sum_f64(z0 + z1, tpp);
-        SK_STAMP2(10);
         if (mine && part == 0) {
             // tanh|z| = (1 - t)/(1 + t) with t = exp(-2|z|); sigmoid(+-x) from e = exp(-|x|)
             const double t = exp(-2.0 * fabs(z));
@@ -346,10 +332,8 @@ __global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
             sig[(g * kPlanePad + slot) * 2 + 1] = z >= 0.0 ? big : small;
             sig[(g * kPlanePad + slot) * 2] = z >= 0.0 ? small : big;
         }
-        SK_STAMP2(11);
     }
     __syncthreads();
-    SK_STAMP2(2);
 
     // the appended key's bucket id for this table, written by one thread
     auto write_code = [&]() {
@@ -386,7 +370,6 @@ __global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
         if (code_due && tid == 0) write_code();
         return;
     }
-    SK_STAMP2(3);
 
     const int lw = a.Lpad < 64 ? a.Lpad : 64;        // distinct tables per 64-word row
     const int copies = 64 / lw;
@@ -466,7 +449,6 @@ __global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
             a.tstats[(((int64_t)b * a.Hkv + h) * a.Lpad + l) * 3 + tid] = (float)(tid == 0 ? sum * inv_r : sum);
         }
         if (code_due && tid == 64) write_code();     // off the first wavefront's path
-        SK_STAMP2(5);
     } else {
         // products over the low and the high planes: p(r) = lo[r & (Rlo-1)] * hi[r >> Plo]
         const int hrows = a.Rlo + a.Rhi;
@@ -485,6 +467,484 @@ __global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------
+// The same projections for a batch: one workgroup serves one table of one KV head for up to
+// `nb` sequences, so the table's slab of W is fetched and laid out once for all of them, and
+// every phase works on all `nb` sequences at once (the phases are latency-bound: the second
+// to the sixteenth sequence cost little more than the first).  Products of sigmoids are
+// built from quarter tables: the 16 products of the four planes of slots 4k .. 4k+3, for
+// k = 0..3, per (sequence, query head); an entry of the final table is then two or three
+// factors instead of P.
+// ---------------------------------------------------------------------------------------
+constexpr int kProjThreads = 256;
+constexpr int kProjMaxNb = 16;
+
+// bytes of dynamic LDS of project_batch_kernel
+static size_t project_batch_lds(int nb, int G, int d, int P, int elem) {
+    const int DS = d + 4, DSQ = d + 16 / elem;
+    const size_t stage = (size_t)P * DS * 4 + (size_t)nb * G * DSQ * elem + (size_t)nb * DS * 4;   // W, queries, keys
+    const size_t quarter = (size_t)nb * G * 64 * 8;
+    return (size_t)nb * G * 32 * 8 + (stage > quarter ? stage : quarter) + (size_t)nb * (8 + 4 + 48 + 64) + 64;
+}
+
+template <typename T, int G>
+__global__ __launch_bounds__(kProjThreads) void project_batch_kernel(ProjectArgs a) {
+    extern __shared__ double sm64[];
+    constexpr int EPV = 16 / (int)sizeof(T);                 // elements per 16-byte vector
+    constexpr int NT = kProjThreads;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int x = blockIdx.x;
+    const int l = (x & 7) * (a.Lpad >> 3) + (x >> 3);        // table; the 8 tables sharing lines of W on one XCD
+    const int h = blockIdx.y;
+    const int b0 = blockIdx.z * a.nb;
+    const int nb = min(a.nb, a.batch - b0);
+    const int P = a.P, d = a.d;
+    const int DS = d + 4, DSQ = d + 16 / (int)sizeof(T);     // padded row strides in LDS: fp32 rows, query rows
+    const int col0 = l * P;
+    const bool live = l < a.L;                               // tables >= L are padding: zero rows
+    const bool soft = a.q != nullptr, app = a.K != nullptr;
+
+    // LDS: sigmoids, then a region used first for the staged operands and later for the quarter
+    // tables, then small per-sequence records
+    double *sig = sm64;                                      // [nb][G][16 slots][2]
+    char *region = (char *)(sig + a.nb * G * 32);
+    float *wf = (float *)region;                             // [P][DS]
+    T *qs = (T *)(wf + P * DS);                              // [nb][G][DSQ] queries, as stored
+    float *kf = (float *)(qs + (size_t)a.nb * G * DSQ);      // [nb][DS]
+    double *qt = (double *)region;                           // [nb][G][4][16] quarter tables (after the dot products)
+    const size_t stage = (size_t)P * DS * 4 + (size_t)a.nb * G * DSQ * sizeof(T) + (size_t)a.nb * DS * 4;
+    const size_t quarter = (size_t)a.nb * G * 64 * 8;
+    char *tail = region + (((stage > quarter ? stage : quarter) + 7) & ~(size_t)7);
+    int64_t *s_krow = (int64_t *)tail;                       // [nb]
+    int *s_tok = (int *)(s_krow + a.nb);                     // [nb]
+    float *s_dev = (float *)(s_tok + a.nb);                  // [nb][4 waves][3]
+    uint32_t *sgn = (uint32_t *)(s_dev + a.nb * 12);         // [nb][16]
+
+    // ---- global loads, all issued before the first use
+    const T *Wg = (const T *)a.W + (int64_t)h * d * a.LP + col0;
+    const int row_bytes = P * (int)sizeof(T);
+    const bool wvec = (row_bytes & 15) == 0 && ((a.LP * (int)sizeof(T)) & 15) == 0;
+    const bool wdw = !wvec && sizeof(T) == 2 && (row_bytes & 3) == 0 && ((a.LP * (int)sizeof(T)) & 3) == 0 &&
+                     ((col0 * (int)sizeof(T)) & 3) == 0;
+    const int nvec = row_bytes >> 4, ndw = row_bytes >> 2;
+    auto div_small = [](int i, int n, int &rem) {            // i / n for i < 4096, n <= 16
+        const int q = (int)(((uint32_t)i * ((65536u + (uint32_t)n - 1u) / (uint32_t)n)) >> 16);
+        rem = i - q * n;
+        return q;
+    };
+    constexpr int WV = 4, WD = sizeof(T) == 2 ? 8 : 1, WE = 16;
+    uint4 wv[WV];
+    uint32_t wq[WD];
+    T we[WE];
+    if (live && wvec) {
+#pragma unroll
+        for (int j = 0; j < WV; ++j) {
+            const int i = tid + j * NT;
+            if (i < d * nvec) wv[j] = *(const uint4 *)(Wg + (int64_t)(i / nvec) * a.LP + (i % nvec) * EPV);
+        }
+    } else if (live && wdw) {
+#pragma unroll
+        for (int j = 0; j < WD; ++j) {
+            const int i = tid + j * NT;
+            int part;
+            const int c = div_small(i, ndw, part);
+            if (i < d * ndw) wq[j] = *(const uint32_t *)((const char *)(Wg + (int64_t)c * a.LP) + part * 4);
+        }
+    } else if (live) {
+#pragma unroll
+        for (int j = 0; j < WE; ++j) {
+            const int i = tid + j * NT;
+            int part;
+            const int c = div_small(i, P, part);
+            if (i < d * P) we[j] = Wg[(int64_t)c * a.LP + part];
+        }
+    }
+    // appended keys: thread -> (sequence, 16-byte piece of its row); at most KV pieces per thread
+    const int kpieces = d / EPV;
+    constexpr int KV = (kProjMaxNb * 256 * (int)sizeof(T) / 16 + NT - 1) / NT;
+    uint4 kv[KV];
+    if (app) {
+#pragma unroll
+        for (int j = 0; j < KV; ++j) {
+            const int i = tid + j * NT;
+            kv[j] = make_uint4(0, 0, 0, 0);
+            if (i < nb * kpieces && live) {
+                const int kb = i / kpieces, piece = i - kb * kpieces;
+                const int tok = a.pos[b0 + kb];
+                const bool wanted = a.count == nullptr || a.count[b0 + kb] >= 1;
+                const int64_t krow = (wanted && tok >= 0 && tok < a.map.max_n) ? a.map.row(b0 + kb, h, tok) : -1;
+                if (krow >= 0) kv[j] = *(const uint4 *)((const T *)a.K + krow * d + piece * EPV);
+            }
+        }
+        if (tid < nb) {
+            const int tok = a.pos[b0 + tid];
+            const bool wanted = a.count == nullptr || a.count[b0 + tid] >= 1;
+            s_tok[tid] = tok;
+            s_krow[tid] = (wanted && tok >= 0 && tok < a.map.max_n) ? a.map.row(b0 + tid, h, tok) : -1;
+            if (a.len_out && x == 0 && h == 0) a.len_out[b0 + tid] = tok + 1;
+        }
+    }
+    // 256 value norms spread over each sequence: their mean and spread scale the histogram bins
+    // of the weighted scores
+    const bool sampling = a.vnorm != nullptr && app && soft && live;
+    if (sampling) {
+        for (int kb = 0; kb < nb; ++kb) {
+            const int tok = a.pos[b0 + kb];
+            float nu = 0.0f;
+            if (tok >= 0 && tok < a.map.max_n) {
+                const int seq = tok + 1;
+                int t = (int)((float)(l * 256 + tid) * ((float)seq / (float)(a.L * 256)));
+                t = t < seq ? t : seq - 1;
+                nu = a.vnorm[((int64_t)(b0 + kb) * a.Hkv + h) * a.map.max_n + t];
+            }
+            const float nu1 = row_sum<64>(nu), nu2 = row_sum<64>(nu * nu);
+            if (lane == 0) {
+                s_dev[(kb * 4 + wave) * 3 + 1] = nu1;
+                s_dev[(kb * 4 + wave) * 3 + 2] = nu2;
+            }
+        }
+    } else if (tid < nb * 4) {
+        s_dev[tid * 3 + 1] = 0.0f;
+        s_dev[tid * 3 + 2] = 0.0f;
+    }
+
+    // ---- W into LDS as fp32, transposed to [plane][channel]
+    if (live && wvec) {
+#pragma unroll
+        for (int j = 0; j < WV; ++j) {
+            const int i = tid + j * NT;
+            if (i < d * nvec) {
+                float f[EPV];
+                vec_to_f32<T>(wv[j], f);
+                const int c = i / nvec, p0 = (i % nvec) * EPV;
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) wf[(p0 + e) * DS + c] = f[e];
+            }
+        }
+    } else if (live && wdw) {
+#pragma unroll
+        for (int j = 0; j < WD; ++j) {
+            const int i = tid + j * NT;
+            if (i < d * ndw) {
+                int part;
+                const int c = div_small(i, ndw, part);
+                wf[(2 * part) * DS + c] = __uint_as_float(wq[j] << 16);
+                wf[(2 * part + 1) * DS + c] = __uint_as_float(wq[j] & 0xffff0000u);
+            }
+        }
+    } else if (live) {
+#pragma unroll
+        for (int j = 0; j < WE; ++j) {
+            const int i = tid + j * NT;
+            if (i < d * P) {
+                int part;
+                const int c = div_small(i, P, part);
+                wf[part * DS + c] = elem_to_f32<T>(we[j]);
+            }
+        }
+    }
+    // ---- queries into LDS as stored (four vectors in flight per thread)
+    if (soft && live) {
+        const int qpieces = G * d / EPV;                     // 16-byte pieces per sequence
+        const int nq = nb * qpieces;
+        auto q_src = [&](int i) {
+            const int kb = i / qpieces, piece = i - kb * qpieces;
+            return (const uint4 *)((const T *)a.q + ((int64_t)(b0 + kb) * a.Hq + h * G) * d + piece * EPV);
+        };
+        auto q_dst = [&](int i) {
+            const int kb = i / qpieces, piece = i - kb * qpieces;
+            const int g = piece / (d / EPV), c = (piece - g * (d / EPV)) * EPV;
+            return (uint4 *)(qs + ((size_t)(kb * G + g)) * DSQ + c);
+        };
+        for (int i0 = tid; i0 < nq; i0 += 4 * NT) {
+            // (a piece beyond the end reads the last one again and is not stored)
+            const int i1 = i0 + NT, i2 = i0 + 2 * NT, i3 = i0 + 3 * NT;
+            const uint4 v0 = *q_src(i0);
+            const uint4 v1 = *q_src(i1 < nq ? i1 : nq - 1);
+            const uint4 v2 = *q_src(i2 < nq ? i2 : nq - 1);
+            const uint4 v3 = *q_src(i3 < nq ? i3 : nq - 1);
+            *q_dst(i0) = v0;
+            if (i1 < nq) *q_dst(i1) = v1;
+            if (i2 < nq) *q_dst(i2) = v2;
+            if (i3 < nq) *q_dst(i3) = v3;
+        }
+        for (int i = tid; i < nb * G * 32; i += NT) sig[i] = 1.0;
+    }
+    if (app) {
+#pragma unroll
+        for (int j = 0; j < KV; ++j) {
+            const int i = tid + j * NT;
+            if (i < nb * kpieces) {
+                const int kb = i / kpieces, piece = i - kb * kpieces;
+                float f[EPV];
+                vec_to_f32<T>(kv[j], f);
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) kf[kb * DS + piece * EPV + e] = f[e];
+            }
+        }
+    }
+    for (int i = tid; i < nb * 16; i += NT) sgn[i] = 0;
+    __syncthreads();
+
+    // ---- appended keys: fp32 FMA, lpd lanes per (sequence, plane)
+    if (app && live) {
+        const int ndots = nb * P;                            // <= 256
+        int lg = 0;
+        while ((2 << lg) * ndots <= NT && lg < 4 && (d >> (lg + 1)) >= 4) ++lg;
+        const int lpd = 1 << lg;
+        const int dot = tid >> lg, part = tid & (lpd - 1);
+        float acc = 0.0f;
+        const bool mine = dot < ndots;
+        const int kb = mine ? dot / P : 0, pl = mine ? dot - kb * P : 0;
+        if (mine) {
+            // lane `part` takes channel quads part, part + lpd, ...
+            const float4 *k4 = (const float4 *)(kf + kb * DS) + part;
+            const float4 *w4 = (const float4 *)(wf + pl * DS) + part;
+            const int nquad = d >> (2 + lg);
+            for (int c = 0; c < nquad; ++c) {
+                const float4 kk = k4[c << lg], ww = w4[c << lg];
+                acc = fmaf(kk.x, ww.x, acc);
+                acc = fmaf(kk.y, ww.y, acc);
+                acc = fmaf(kk.z, ww.z, acc);
+                acc = fmaf(kk.w, ww.w, acc);
+            }
+        }
+        if (lpd >= 16) {
+            acc += dpp_f32<0x128>(acc);
+            acc += dpp_f32<0x124>(acc);
+        } else if (lpd >= 8) {
+            acc += dpp_f32<0x141>(acc);
+        }
+        if (lpd >= 4) acc += dpp_f32<0x4E>(acc);
+        if (lpd >= 2) acc += dpp_f32<0xB1>(acc);
+        if (mine && part == 0) sgn[kb * 16 + pl] = acc >= 0.0f ? 1u : 0u;
+    }
+    // ---- queries: fp64 dot products, tpp lanes each; u = tanh(z)/sqrt(d), then the per-plane
+    //      sigmoids of +-2u/tau
+    if (soft && live) {
+        const int npairs = nb * G * P;
+        int lg = 0;
+        while ((2 << lg) * npairs <= NT && lg < 4 && (d >> (lg + 1)) >= 16) ++lg;   // at least 4 channel quads per lane
+        const int tpp = 1 << lg;
+        const int part = tid & (tpp - 1);
+        const int nquad = d >> (2 + lg);                     // channel quads per lane, a multiple of 4
+        for (int pair0 = 0; pair0 < npairs; pair0 += NT >> lg) {
+            const int pair = pair0 + (tid >> lg);
+            const bool mine = pair < npairs;
+            const int bg = mine ? pair / P : 0;              // (sequence, query head)
+            const int j = mine ? pair - bg * P : 0;
+            const T *qrow = qs + (size_t)bg * DSQ;
+            const float *wrow = wf + j * DS;
+            double z0 = 0.0, z1 = 0.0, z2 = 0.0, z3 = 0.0;
+            for (int c0 = 0; c0 < nquad; c0 += 4) {          // nquad is a multiple of 4; 4 quads' LDS reads at a time
+                float4 ww[4];
+                float qq[4][4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int ch = 4 * (part + ((c0 + e) << lg));
+                    ww[e] = *(const float4 *)(wrow + ch);
+                    if (sizeof(T) == 2) {
+                        const uint2 raw = *(const uint2 *)(qrow + ch);
+                        qq[e][0] = __uint_as_float(raw.x << 16); qq[e][1] = __uint_as_float(raw.x & 0xffff0000u);
+                        qq[e][2] = __uint_as_float(raw.y << 16); qq[e][3] = __uint_as_float(raw.y & 0xffff0000u);
+                    } else {
+                        const float4 raw = *(const float4 *)(qrow + ch);
+                        qq[e][0] = raw.x; qq[e][1] = raw.y; qq[e][2] = raw.z; qq[e][3] = raw.w;
+                    }
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    z0 = fma((double)ww[e].x, (double)qq[e][0], z0);
+                    z1 = fma((double)ww[e].y, (double)qq[e][1], z1);
+                    z2 = fma((double)ww[e].z, (double)qq[e][2], z2);
+                    z3 = fma((double)ww[e].w, (double)qq[e][3], z3);
+                }
+            }
+            z0 += z2;
+            z1 += z3;
+            const double z = group_sum_f64(z0 + z1, tpp);
+            if (mine && part == 0) {
+                // tanh|z| = (1 - t)/(1 + t) with t = exp(-2|z|); sigmoid(+-x) from e = exp(-|x|)
+                const double t = exp(-2.0 * fabs(z));
+                const double th = (1.0 - t) * rcp64(1.0 + t);
+                const double e = exp(-a.x_scale * th);       // x = 2 tanh|z| / (sqrt(d) tau) >= 0
+                double big = rcp64(1.0 + e), small = e * big;
+                if (a.hard) {                                // the limit tau -> 0
+                    big = 1.0;
+                    small = 0.0;
+                }
+                const int slot = (a.mode == kFactor && j >= a.Plo) ? 8 + j - a.Plo : j;
+                sig[(bg * 16 + slot) * 2 + 1] = z >= 0.0 ? big : small;
+                sig[(bg * 16 + slot) * 2] = z >= 0.0 ? small : big;
+            }
+        }
+    }
+    __syncthreads();
+
+    // the appended keys' bucket ids for this table, one thread per sequence
+    auto write_code = [&](int kb) {
+        const int64_t krow = s_krow[kb];
+        if (krow < 0) return;
+        const int tok = s_tok[kb];
+        uint32_t code = 0;
+        if (live)
+            for (int i = 0; i < P; ++i) code |= sgn[kb * 16 + i] << i;
+        if (a.mode == kSplit) {
+            // packed ids: the 10 bits sit in one or two dwords that other tables (other
+            // workgroups) write too, so they are cleared and set with atomics
+            const int grp = l / a.GT, j = packed_pos(l % a.GT, tok, a.S);
+            const int sub = j >> 4, bit = 10 * (j & 15), wi = bit >> 5, sh = bit & 31;
+            uint32_t *w0 = (uint32_t *)((char *)a.codes + packed_word(krow, grp, sub, wi, a.Lpad, a.GT));
+            atomicAnd(w0, ~(0x3ffu << sh));
+            atomicOr(w0, code << sh);
+            if (sh > 22) {
+                uint32_t *w1 = (uint32_t *)((char *)a.codes + packed_word(krow, grp, sub, wi + 1, a.Lpad, a.GT));
+                atomicAnd(w1, ~(0x3ffu >> (32 - sh)));
+                atomicOr(w1, code >> (32 - sh));
+            }
+            return;
+        }
+        const int64_t at = krow * a.Lpad + code_pos(l, tok, a.S);
+        if (a.cb == 1) ((uint8_t *)a.codes)[at] = (uint8_t)code;
+        else ((uint16_t *)a.codes)[at] = (uint16_t)code;
+    };
+    if (!soft) {
+        if (app && tid < nb) write_code(tid);
+        return;
+    }
+
+    // ---- quarter tables (over the region that held the staged operands)
+    for (int e0 = tid; e0 < nb * G * 64; e0 += 4 * NT) {     // four entries' LDS reads at a time
+        double f[4][4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int e = e0 + j * NT;
+            const int bg = e >> 6, quarter = (e >> 4) & 3, bits = e & 15;
+            const double *sp = sig + (bg * 16 + quarter * 4) * 2;
+            const bool in = e < nb * G * 64;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) f[j][i] = in ? sp[2 * i + ((bits >> i) & 1)] : 0.0;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int e = e0 + j * NT;
+            if (e < nb * G * 64) qt[e] = live ? (f[j][0] * f[j][1]) * (f[j][2] * f[j][3]) : 0.0;
+        }
+    }
+    __syncthreads();
+    if (app && tid >= 64 && tid < 64 + nb) write_code(tid - 64);   // off the first wavefront's path
+
+    const int lw = a.Lpad < 64 ? a.Lpad : 64;            // distinct tables per 64-word row
+    const int copies = 64 / lw;
+    const int c64 = l >> 6, lp = l & 63;
+    const double inv_g = 1.0 / (double)G, inv_r = 1.0 / (double)a.R;
+    if (a.mode == kDirect && a.R <= NT) {
+        // p(r) over all planes, averaged over the G queries: bucket r = tid of every sequence, four
+        // sequences' LDS reads at a time; the spreads of all sequences are reduced together
+        const int r = tid;
+        float dev2[kProjMaxNb];
+#pragma unroll
+        for (int k0 = 0; k0 < kProjMaxNb; k0 += 4) {
+            double lo[4][G], hi[4][G];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const bool in = k0 + j < nb && r < a.R;
+                const double *qb = qt + (size_t)(in ? k0 + j : 0) * G * 64;
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    lo[j][g] = qb[g * 64 + (r & 15)];
+                    hi[j][g] = qb[g * 64 + 16 + ((r >> 4) & 15)];
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int kb = k0 + j;
+                dev2[kb] = 0.0f;
+                if (kb < nb && r < a.R) {
+                    double mean = 0.0;
+#pragma unroll
+                    for (int g = 0; g < G; ++g) mean += lo[j][g] * hi[j][g];
+                    mean *= inv_g;
+                    if (live) {
+                        const double dv = mean - inv_r;      // a table's entries sum to 1: their mean is 1/R
+                        dev2[kb] = (float)(dv * dv);
+                    }
+                    float *Tg = a.tables + ((int64_t)(b0 + kb) * a.Hkv + h) * a.table_words;
+                    for (int cp = 0; cp < copies; ++cp) Tg[((int64_t)c64 * a.R + r) * 64 + lp + cp * lw] = (float)mean;
+                }
+            }
+        }
+#pragma unroll
+        for (int kb = 0; kb < kProjMaxNb; ++kb) dev2[kb] = row_sum<64>(dev2[kb]);
+#pragma unroll
+        for (int kb = 0; kb < kProjMaxNb; ++kb)
+            if (kb < nb && lane == 0) s_dev[(kb * 4 + wave) * 3] = dev2[kb];
+    } else {
+    for (int kb = 0; kb < nb; ++kb) {
+        float *Tg = a.tables + ((int64_t)(b0 + kb) * a.Hkv + h) * a.table_words;
+        const double *qb = qt + (size_t)kb * G * 64;
+        float dev2 = 0.0f;
+        if (a.mode == kDirect) {            // p(r) over all planes, averaged over the G queries
+            for (int r = tid; r < a.R; r += NT) {
+                double mean = 0.0;
+#pragma unroll
+                for (int g = 0; g < G; ++g) mean += qb[g * 64 + (r & 15)] * qb[g * 64 + 16 + (r >> 4)];
+                mean *= inv_g;
+                if (live) {
+                    const double dv = mean - inv_r;          // a table's entries sum to 1: their mean is 1/R
+                    dev2 += (float)(dv * dv);
+                }
+                for (int cp = 0; cp < copies; ++cp) Tg[((int64_t)c64 * a.R + r) * 64 + lp + cp * lw] = (float)mean;
+            }
+        } else if (a.mode == kSplit) {
+            // four consecutive buckets per thread, one 16-byte piece: a group's table is kept
+            // [bucket / 4][table][4]
+            for (int r4 = tid; r4 < (a.R >> 2); r4 += NT) {
+                float v[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int r = 4 * r4 + j;
+                    double mean = 0.0;
+#pragma unroll
+                    for (int g = 0; g < G; ++g)
+                        mean += (qb[g * 64 + (r & 15)] * qb[g * 64 + 16 + ((r >> 4) & 15)]) * qb[g * 64 + 32 + (r >> 8)];
+                    mean *= inv_g;
+                    if (live) {
+                        const double dv = mean - inv_r;
+                        dev2 += (float)(dv * dv);
+                    }
+                    v[j] = (float)mean;
+                }
+                *(float4 *)&Tg[(((int64_t)(l / a.GT) * (a.R >> 2) + r4) * a.GT + l % a.GT) * 4] =
+                    make_float4(v[0], v[1], v[2], v[3]);
+            }
+        } else {
+            // products over the low and the high planes: p(r) = lo[r & (Rlo-1)] * hi[r >> Plo]
+            const int hrows = a.Rlo + a.Rhi;
+            for (int i = tid; i < hrows * G; i += NT) {
+                const int row = i % hrows, g = i / hrows;
+                double p;
+                if (row < a.Rlo) p = (qb[g * 64 + (row & 15)] * qb[g * 64 + 16 + (row >> 4)]) * inv_g;   // the 1/G of the group mean rides on the low factor
+                else p = qb[g * 64 + 32 + ((row - a.Rlo) & 15)] * qb[g * 64 + 48 + ((row - a.Rlo) >> 4)];
+                for (int cp = 0; cp < copies; ++cp)
+                    Tg[(((int64_t)g * a.rounds + c64) * hrows + row) * 64 + lp + cp * lw] = (float)p;
+            }
+        }
+        // spread of this table's entries, from which the scoring pass sizes its histogram bins
+        dev2 = row_sum<64>(dev2);
+        if (lane == 0) s_dev[(kb * 4 + wave) * 3] = dev2;
+    }
+    }
+    if (a.mode == kFactor) return;
+    __syncthreads();
+    if (tid < nb * 3) {
+        const int kb = tid / 3, w = tid - kb * 3;
+        const float *part = s_dev + kb * 12 + w;
+        const double sum = (double)(part[0] + part[3] + part[6] + part[9]);
+        a.tstats[(((int64_t)(b0 + kb) * a.Hkv + h) * a.Lpad + l) * 3 + w] = (float)(w == 0 ? sum * inv_r : sum);
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 
 struct ScoreArgs {
     const void *codes;
@@ -499,6 +959,7 @@ struct ScoreArgs {
     int n_sink, n_window;    // the first n_sink and last n_window tokens of a sequence score +inf
     RowMap map;
     int L, Lpad, rounds, R, G, Plo, Rlo, table_rows;
+    int batch;
     int64_t table_words;
 };
 
@@ -506,7 +967,6 @@ struct ScoreArgs {
 template <int CB> struct CodeVec;
 template <> struct CodeVec<1> {
     uint4 v;
-#ifndef SK_SCORE_NO_NT
     // the id stream is read once: a non-temporal load keeps it from displacing the table and
     // the scores in L2 (measured 6 % faster)
     __device__ __forceinline__ void load(const void *p) {
@@ -514,9 +974,6 @@ template <> struct CodeVec<1> {
         u4 t = __builtin_nontemporal_load((const u4 *)p);
         v = make_uint4(t.x, t.y, t.z, t.w);
     }
-#else
-    __device__ __forceinline__ void load(const void *p) { v = *(const uint4 *)p; }
-#endif
     __device__ __forceinline__ uint32_t word(int j) const { return j == 0 ? v.x : j == 1 ? v.y : j == 2 ? v.z : v.w; }
     __device__ __forceinline__ uint32_t code(int s) const { return (word(s >> 2) >> (8 * (s & 3))) & 0xffu; }
 };
@@ -592,37 +1049,37 @@ __device__ __forceinline__ uint32_t score_order_key(float f) {
 
 template <bool V> struct BoolTag { static constexpr bool value = V; };
 
-// A workgroup owns chunks of CKEYS consecutive keys, taken round-robin; inside a chunk each
-// wavefront owns U*KPW consecutive keys and keeps U 16-byte loads per lane in flight.  Chunks
-// that lie wholly inside the sequence take a branch-free path in which the loads of the next
-// chunk are issued before the current one is processed (two register sets, ping-pong).
-template <int S, int CB, int MODE, bool ONE_ROUND, bool PAGED>
-__global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
+constexpr int kBlkTiles = 1024;                      // block ids a scoring workgroup keeps in LDS (paged caches)
+
+// The keys of all sequences of the batch are cut into units of WKEYS = U*KPW consecutive keys
+// (what one wavefront takes at a time: U 16-byte loads per lane in flight), and the units of a
+// KV head, in sequence order, are dealt out in equal contiguous runs to the workgroups of that
+// head: long and short sequences then cost their workgroups the same.  A run that crosses from
+// one sequence into the next is worked off segment by segment, the table in LDS being replaced
+// in between.  Inside a segment the wavefronts take units round-robin, and the loads of a
+// wavefront's next unit are issued before its current one is processed (two register sets,
+// ping-pong); with a paged cache the block-table entries are fetched one unit further ahead
+// still, so that no id load waits for a table entry.
+// BATCHED = false is the single-sequence case: one segment per workgroup, its units taken
+// round-robin over all workgroups of the head, and none of the bookkeeping above.
+template <int S, int CB, int MODE, bool ONE_ROUND, bool PAGED, bool BATCHED>
+// (64 tables of one-byte ids, paged: two workgroups per CU need four wavefronts per SIMD, i.e. at most 128
+// registers, which the compiler meets only when told)
+__global__ __launch_bounds__(kScoreThreads, (MODE == kDirect && S == 4 && PAGED) ? 4 : 1) void score_kernel(ScoreArgs a) {
     extern __shared__ float tbl[];
     constexpr int KPW = 64 / S;                      // keys per wavefront pass
     constexpr int NW = kScoreThreads / 64;
-    constexpr int U = kScoreU;                       // passes per wavefront per chunk
-    constexpr int WKEYS = U * KPW;                   // consecutive keys a wavefront owns in a chunk
-    constexpr int CKEYS = NW * WKEYS;                // keys per chunk
+    constexpr int U = kScoreU;                       // passes per unit
+    constexpr int WKEYS = U * KPW;                   // keys per unit
+    constexpr int EPL = U / S;                       // results a lane emits per unit
     static_assert(U % S == 0, "each lane of a key's group emits U/S results");
+    constexpr int TPU = WKEYS / 16;                  // 16-key tiles per unit (a tile never straddles a page)
+    constexpr int RPB = kBlkTiles / (NW * TPU);      // rounds of the workgroup whose block ids fit in LDS at a time
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int h = blockIdx.y, b = blockIdx.z;
-    const int64_t bh = (int64_t)b * a.map.Hkv + h;
+    const int h = blockIdx.y, slot = blockIdx.x, nslot = gridDim.x;
     const int max_n = a.map.max_n;
-    int seq = a.seq_len[b];
-    seq = seq < 0 ? 0 : (seq > max_n ? max_n : seq);
-    float *out = a.scores + bh * max_n;
-    const float *vn = a.vnorm ? a.vnorm + bh * max_n : nullptr;
     const float ninf = -__builtin_inff();
-    const int stride = gridDim.x;
-    // Every workgroup takes the same number of whole chunks (nround); what is left over - less
-    // than one chunk per workgroup, plus the tail beyond the sequence - is dealt out pass by
-    // pass over all wavefronts, so that no workgroup carries a whole extra chunk.
-    const int nround = (seq / CKEYS) / stride;
-    const int left0 = nround * stride * CKEYS;       // first key of the leftover region
-    const bool has_table = seq > 0;
     const bool adaptive = a.hist_mode == kHistAdaptive;
-    float bin_lo = 0.0f, bin_inv = 0.0f;             // adaptive histogram bins, set once the table is in
 
     const int sub = lane % S, kk = lane / S;
     const int lw = a.Lpad < 64 ? a.Lpad : 64;
@@ -634,225 +1091,285 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
     // (no static __shared__ in this kernel: the table has to sit at LDS address 0 for the
     // fast address path)
     float *s_bin = (float *)(lhist + kHistBins);     // [2], present with a histogram only
-    const char *codes_bh = (const char *)a.codes + (bh * max_n * (int64_t)a.Lpad + sub * 16) * CB;
 
-    // address of this lane's 16 ids of key `key`, round c; dead = the token's block is absent
-    auto code_ptr = [&](int key, int c, bool &dead) -> const char * {
-        if (PAGED) {
-            int64_t row = a.map.row(b, h, key);
-            dead = row < 0;
-            if (dead) row = 0;
-            return (const char *)a.codes + (row * a.Lpad + c * 64 + sub * 16) * CB;
+    // Sequence lengths: one global load each, then from LDS (the workgroup reads them twice)
+    int *s_len = (int *)(tbl + a.table_words + (a.hist ? kHistBins + 4 : 0));   // [batch]
+    int32_t *s_blk = s_len + (BATCHED ? a.batch : 0);   // [kBlkTiles] paged caches: block ids of 16-key tiles
+    const int nbatch = BATCHED ? a.batch : 1;
+    int u0 = 0, u1 = 0;
+    if (BATCHED) {
+        for (int b = tid; b < nbatch; b += kScoreThreads) {
+            const int v = a.seq_len[b];
+            s_len[b] = v < 0 ? 0 : (v > max_n ? max_n : v);
         }
-        dead = false;
-        return codes_bh + ((int64_t)key * a.Lpad + c * 64) * CB;
-    };
-    // Passes u = 0..U-1 of a wavefront cover keys base + u*KPW + kk.  Lane `sub` of a key's
-    // group writes the results of passes sub, sub+S, ...
-    // value-norm weights of the keys this lane emits for a chunk (fetched with the ids, so that
-    // their latency is hidden the same way)
-    constexpr int EPL = U / S;
-    auto load_weights = [&](float *w, int base) {
-#pragma unroll
-        for (int j = 0; j < EPL; ++j) {
-            const int key = base + (j * S + sub) * KPW + kk;
-            w[j] = (vn && key < seq) ? vn[key] : 1.0f;
-        }
-    };
-    auto emit = [&](int base, const float *sum, const bool *dead, const float *w) {
-#pragma unroll
-        for (int j = 0; j < U / S; ++j) {
-            float v = sum[j * S];
-            bool dd = dead[j * S];
-#pragma unroll
-            for (int t = 1; t < S; ++t) {
-                v = sub == t ? sum[j * S + t] : v;
-                dd = sub == t ? dead[j * S + t] : dd;
-            }
-            const int key = base + (j * S + sub) * KPW + kk;
-            if (key < max_n) {
-                if (dd) {
-                    v = ninf;
-                } else {
-                    v *= w[j];
-                    if (key < a.n_sink || key >= seq - a.n_window) v = __builtin_inff();   // sink / local window
-                }
-                out[key] = v;
-                if (a.hist && v > ninf) {
-                    const uint32_t bin = adaptive ? score_bin(v, bin_lo, bin_inv)
-                                                  : score_order_key(v) >> (32 - kHistBits);
-                    atomicAdd(&lhist[bin], 1u);
-                }
-            }
-        }
-    };
-    // (keys at or beyond the sequence, which only the leftover region has, read the last row
-    // of the buffer instead and are marked dead: every set is the same sequence of loads, so
-    // the number of loads in flight stays known)
-    auto load_set = [&](CodeVec<CB> *cv, bool *dead, float *w, int base) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int key = base + u * KPW + kk;
-            cv[u].load(code_ptr(min(key, max_n - 1), 0, dead[u]));
-            dead[u] = dead[u] || key >= seq;
-        }
-        load_weights(w, base);
-    };
-    auto chunk_base = [&](int r) { return (r * stride + (int)blockIdx.x) * CKEYS + wave * WKEYS; };
-
-    constexpr bool PREFETCH = ONE_ROUND;
-    // The leftover region is taken U passes at a time per wavefront.  With PREFETCH a
-    // wavefront's first such set rides the ping-pong below as one more round (its loads in
-    // flight during the last whole chunk's look-ups) instead of costing a memory latency of
-    // its own at the end of the kernel: a sequence length that is not a whole number of rounds,
-    // the usual case while decoding, then costs what the next whole number would.
-    const int npass = (max_n - left0 + KPW - 1) / KPW;
-    const int p_first = ((int)blockIdx.x * NW + wave) * U;
-    const int left_base = left0 + p_first * KPW;
-    const int nr = nround + (PREFETCH && p_first < npass ? 1 : 0);
-    auto round_base = [&](int r) { return r < nround ? chunk_base(r) : left_base; };
-    CodeVec<CB> setA[U], setB[U];
-    bool deadA[U], deadB[U];
-    float wgtA[EPL], wgtB[EPL];
-    if (PREFETCH && nr > 0) load_set(setA, deadA, wgtA, round_base(0));
-    // Adaptive histogram: if the keys' bucket ids were uniform, a score would have mean L/R and
-    // variance sum_l var_l; bins are laid from four deviations below that mean upwards.
-    float var_part = 0.0f, nu1_part = 0.0f, nu2_part = 0.0f;
-    if (adaptive && wave == 0)
-        for (int l = lane; l < a.Lpad; l += 64) {
-            const float *ts = a.tstats + (bh * a.Lpad + l) * 3;
-            var_part += ts[0];
-            nu1_part += ts[1];
-            nu2_part += ts[2];
-        }
-    if (has_table) {            // bucket-probability table -> LDS
-        const float4 *src = (const float4 *)(a.tables + bh * a.table_words);
-        float4 *dst = (float4 *)tbl;
-        const int n4 = (int)(a.table_words >> 2);
-        constexpr int B8 = 8;                        // independent loads in flight per thread
-        for (int i0 = tid; i0 < n4; i0 += B8 * kScoreThreads) {
-            float4 t[B8];
-#pragma unroll
-            for (int j = 0; j < B8; ++j) {
-                const int i = i0 + j * kScoreThreads;
-                t[j] = i < n4 ? src[i] : make_float4(0, 0, 0, 0);
-            }
-#pragma unroll
-            for (int j = 0; j < B8; ++j) {
-                const int i = i0 + j * kScoreThreads;
-                if (i < n4) dst[i] = t[j];
-            }
-        }
-        if (a.hist)
-            for (int i = tid; i < kHistBins; i += kScoreThreads) lhist[i] = 0;
-    }
-    if (adaptive && wave == 0) {
-        float mu = (float)a.L / (float)a.R;
-        float var = row_sum<64>(var_part);
-        const float nu1 = row_sum<64>(nu1_part), nu2 = row_sum<64>(nu2_part);
-        if (vn) {
-            // weighted scores nu * s, nu and s taken as independent: moments of the product
-            const float cnt = (float)(a.L * 256);
-            const float mnu = nu1 / cnt, vnu = fmaxf(nu2 / cnt - mnu * mnu, 0.0f);
-            var = mnu * mnu * var + mu * mu * vnu + vnu * var;
-            mu *= mnu;
-        }
-        const float sigma = fmaxf(sqrtf(var), fmaxf(mu * 1e-6f, 1e-30f));
-        const float lo = mu - 4.0f * sigma, inv = 1.0f / (4.0f * sigma);
-        if (lane == 0) {
-            s_bin[0] = lo;
-            s_bin[1] = inv;
-            if (blockIdx.x == 0) {       // the select's sweep bins with the very same pair
-                a.thr[bh * kThrStride + kThrBinLo] = __float_as_uint(lo);
-                a.thr[bh * kThrStride + kThrBinInv] = __float_as_uint(inv);
-            }
-        }
-    }
-    __syncthreads();
-    if (adaptive) {
-        bin_lo = s_bin[0];
-        bin_inv = s_bin[1];
-    }
-
-    // ---- whole chunks: branch-free, the next chunk's loads in flight during the look-ups
-    auto full_chunks = [&](auto base0) {
-        constexpr bool BASE0 = decltype(base0)::value;
-        auto process = [&](const CodeVec<CB> *cv, const bool *dead, const float *w, int base) {
-            float sum[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) sum[u] = group_sum<S>(gather16<CB, MODE, BASE0, BASE0 && ONE_ROUND>(cv[u], tbase, woff, 0, a));
-            emit(base, sum, dead, w);
-        };
-        if (PREFETCH) {
-            int r = 0;
-            while (r < nr) {
-                if (r + 1 < nr) load_set(setB, deadB, wgtB, round_base(r + 1));
-                process(setA, deadA, wgtA, round_base(r));
-                if (++r >= nr) break;
-                if (r + 1 < nr) load_set(setA, deadA, wgtA, round_base(r + 1));
-                process(setB, deadB, wgtB, round_base(r));
-                ++r;
-            }
-        } else {
-            for (int r = 0; r < nround; ++r) {
-                const int base = chunk_base(r);
-                float sum[U], w[EPL];
-                bool dead[U];
-                load_weights(w, base);
-#pragma unroll
-                for (int u = 0; u < U; ++u) sum[u] = 0.0f;
-                for (int c = 0; c < a.rounds; ++c) {
-                    CodeVec<CB> cur[U];
-#pragma unroll
-                    for (int u = 0; u < U; ++u) cur[u].load(code_ptr(base + u * KPW + kk, c, dead[u]));
-#pragma unroll
-                    for (int u = 0; u < U; ++u) sum[u] += gather16<CB, MODE, BASE0, false>(cur[u], tbase, woff, c, a);
-                }
-#pragma unroll
-                for (int u = 0; u < U; ++u) sum[u] = group_sum<S>(sum[u]);
-                emit(base, sum, dead, w);
-            }
-        }
-    };
-    if (tbase == 0) full_chunks(BoolTag<true>());
-    else full_chunks(BoolTag<false>());
-
-    // ---- (the rest of) the leftover keys and the -inf fill beyond the sequence
-    for (int p0 = p_first + (nr > nround ? stride * NW * U : 0); p0 < npass; p0 += stride * NW * U) {
-        const int base = left0 + p0 * KPW;
-        float sum[U], w[EPL];
-        bool dead[U];
-        CodeVec<CB> cv[U];
-        load_weights(w, base);
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            sum[u] = 0.0f;
-            dead[u] = base + u * KPW + kk >= seq;
-        }
-        for (int c = 0; c < a.rounds; ++c) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (dead[u]) continue;
-                bool absent;
-                cv[u].load(code_ptr(base + u * KPW + kk, c, absent));
-                if (absent) dead[u] = true;
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (!dead[u]) sum[u] += gather16<CB, MODE, false, false>(cv[u], tbase, woff, c, a);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) sum[u] = group_sum<S>(sum[u]);   // every lane of a key's group takes part
-        emit(base, sum, dead, w);
-    }
-
-    if (a.hist && has_table) {
         __syncthreads();
-        uint32_t *gh = a.hist + bh * kHistBins;
-        for (int i = tid; i < kHistBins; i += kScoreThreads)
-            if (lhist[i]) atomicAdd(&gh[i], lhist[i]);
+        // this workgroup's run of units: the first (total mod nslot) workgroups take one more
+        int total = 0;
+        for (int b = 0; b < nbatch; ++b) total += (s_len[b] + WKEYS - 1) / WKEYS;
+        const int per = total / nslot, extra = total - per * nslot;
+        u0 = slot * per + (slot < extra ? slot : extra);
+        u1 = u0 + per + (slot < extra ? 1 : 0);
     }
+
+    auto run = [&](auto base0) {
+        constexpr bool BASE0 = decltype(base0)::value;
+        int cum = 0;
+        bool first_segment = true;
+        for (int b = 0; b < nbatch; ++b) {
+            int seq;
+            if (BATCHED) {
+                seq = s_len[b];
+            } else {
+                seq = a.seq_len[0];
+                seq = seq < 0 ? 0 : (seq > max_n ? max_n : seq);
+            }
+            const int nu = (seq + WKEYS - 1) / WKEYS;
+            const int64_t bh = (int64_t)b * a.map.Hkv + h;
+            float *out = a.scores + bh * max_n;
+            // beyond the sequence's last unit: -inf, a share for every workgroup of the head
+            for (int key = nu * WKEYS + slot * kScoreThreads + tid; key < max_n; key += nslot * kScoreThreads)
+                out[key] = ninf;
+            int ub, ue, ustride;
+            if (BATCHED) {
+                const int lo = u0 > cum ? u0 : cum, hi = u1 < cum + nu ? u1 : cum + nu;
+                ub = lo - cum;                       // this workgroup's units of the sequence
+                ue = hi - cum;
+                ustride = NW;
+                cum += nu;
+            } else {
+                ub = slot * NW;                      // its wavefronts' first units; the next ones nslot * NW further on
+                ue = nu;
+                ustride = nslot * NW;
+            }
+            if (ub >= ue) continue;
+
+            const float *vn = a.vnorm ? a.vnorm + bh * max_n : nullptr;
+            const float *wsrc = vn ? vn : a.tables;  // weights, or anything loadable
+            const int nmine = ue - ub > wave ? (ue - ub - wave + ustride - 1) / ustride : 0;   // units of this wavefront
+            auto unit_base = [&](int r) { return (ub + wave + r * ustride) * WKEYS; };
+            float bin_lo = 0.0f, bin_inv = 0.0f;     // adaptive histogram bins, set once the table is in
+
+            // Paged caches: the block-table entries of the U keys base + u*KPW + kk, as loaded; what
+            // depends on them is computed when the ids are fetched, a unit later, so that nothing
+            // waits for these loads here.
+            auto locate = [&](int32_t *blks, int base) {
+                if (!PAGED) return;
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int key = base + u * KPW + kk;
+                    const int t = key < max_n ? key : max_n - 1;
+                    blks[u] = a.map.block_table[(int64_t)b * a.map.max_blocks + a.map.page_slot(t)];
+                }
+            };
+            // After the first unit the entries come from LDS: the workgroup fetches those of RPB
+            // rounds of units at a time (beside the table, for the first RPB), so that the id
+            // loads of the main loop wait for no other global load.
+            const int nround_wg = (ue - ub + ustride - 1) / ustride;   // rounds the workgroup makes over the segment
+            auto stage_blks = [&](int r0) {
+                const int rounds = nround_wg - r0 < RPB ? nround_wg - r0 : RPB;
+                for (int i = tid; i < rounds * NW * TPU; i += kScoreThreads) {
+                    const int lu = i / TPU, tile = i - lu * TPU;
+                    const int key = (ub + (r0 + lu / NW) * ustride + lu % NW) * WKEYS + tile * 16;
+                    s_blk[i] = key < max_n ? a.map.block_table[(int64_t)b * a.map.max_blocks + a.map.page_slot(key)] : -1;
+                }
+            };
+            auto staged = [&](int32_t *blks, int r, int r0) {
+                if (!PAGED) return;
+#pragma unroll
+                for (int u = 0; u < U; ++u) blks[u] = s_blk[((r - r0) * NW + wave) * TPU + u * (KPW / 16) + (kk >> 4)];
+            };
+            // The id loads of a unit.  A key at or beyond the sequence, or one whose block is absent,
+            // reads a row that exists and is marked dead: every unit is the same sequence of loads.
+            // Lane `sub` of a key's group emits the results of passes sub, sub+S, ...; the
+            // value-norm weights of those keys are fetched with the ids.
+            const char *ids = (const char *)a.codes + ((PAGED ? 0 : bh * max_n * a.Lpad) + sub * 16) * CB;
+            auto fetch = [&](CodeVec<CB> *cv, bool *dead, float *w, const int32_t *rows, int base, int c) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int key = base + u * KPW + kk;
+                    const int t = key < max_n ? key : max_n - 1;
+                    int32_t row = t;                 // row of the id tensor (fits 32 bits: socket_create checks)
+                    if (PAGED) {
+                        const int32_t blk = rows[u];
+                        row = (uint32_t)blk < (uint32_t)a.map.num_blocks ? (blk * a.map.Hkv + h) * a.map.page + a.map.page_off(t) : -1;
+                    }
+                    dead[u] = key >= seq || row < 0;
+                    row = row < 0 ? 0 : row;
+                    cv[u].load(ids + ((int64_t)row * a.Lpad + c * 64) * CB);
+                }
+                if (c == 0) {
+#pragma unroll
+                    for (int j = 0; j < EPL; ++j) {
+                        const int key = base + (j * S + sub) * KPW + kk;
+                        // (batched / paged: every lane loads a word whether there are weights or
+                        // not, so that a unit is the same number of loads either way and the
+                        // waits on the loads stay exact)
+                        if (BATCHED || PAGED) w[j] = wsrc[(vn && key < seq) ? key : 0];
+                        else w[j] = (vn && key < seq) ? vn[key] : 1.0f;
+                    }
+                }
+            };
+            auto emit = [&](int base, const float *sum, const bool *dead, const float *w) {
+#pragma unroll
+                for (int j = 0; j < EPL; ++j) {
+                    float v = sum[j * S];
+                    bool dd = dead[j * S];
+#pragma unroll
+                    for (int t = 1; t < S; ++t) {
+                        v = sub == t ? sum[j * S + t] : v;
+                        dd = sub == t ? dead[j * S + t] : dd;
+                    }
+                    const int key = base + (j * S + sub) * KPW + kk;
+                    if (key < max_n) {
+                        if (dd) {
+                            v = ninf;
+                        } else {
+                            if (vn) v *= w[j];
+                            if (key < a.n_sink || key >= seq - a.n_window) v = __builtin_inff();   // sink / local window
+                        }
+                        out[key] = v;
+                        if (a.hist && v > ninf) {
+                            const uint32_t bin = adaptive ? score_bin(v, bin_lo, bin_inv)
+                                                          : score_order_key(v) >> (32 - kHistBits);
+                            atomicAdd(&lhist[bin], 1u);
+                        }
+                    }
+                }
+            };
+
+            CodeVec<CB> setA[U], setB[U];
+            bool deadA[U], deadB[U];
+            int32_t blks[PAGED ? U : 1];
+            float wgtA[EPL], wgtB[EPL];
+            if (ONE_ROUND && nmine > 0) {            // the first unit's loads go out before the table's
+                locate(blks, unit_base(0));
+                fetch(setA, deadA, wgtA, blks, unit_base(0), 0);
+            }
+            // Adaptive histogram: if the keys' bucket ids were uniform, a score would have mean L/R
+            // and variance sum_l var_l; bins are laid from four deviations below that mean upwards.
+            float var_part = 0.0f, nu1_part = 0.0f, nu2_part = 0.0f;
+            if (adaptive && wave == 0)
+                for (int l = lane; l < a.Lpad; l += 64) {
+                    const float *ts = a.tstats + (bh * a.Lpad + l) * 3;
+                    var_part += ts[0];
+                    nu1_part += ts[1];
+                    nu2_part += ts[2];
+                }
+            if (!first_segment) __syncthreads();     // every wavefront is done with the previous table
+            first_segment = false;
+            if (PAGED && ONE_ROUND) stage_blks(0);
+            {                                        // bucket-probability table -> LDS
+                const float4 *src = (const float4 *)(a.tables + bh * a.table_words);
+                float4 *dst = (float4 *)tbl;
+                const int n4 = (int)(a.table_words >> 2);
+                constexpr int B8 = 8;                // independent loads in flight per thread
+                for (int i0 = tid; i0 < n4; i0 += B8 * kScoreThreads) {
+                    float4 t[B8];
+#pragma unroll
+                    for (int j = 0; j < B8; ++j) {
+                        const int i = i0 + j * kScoreThreads;
+                        t[j] = i < n4 ? src[i] : make_float4(0, 0, 0, 0);
+                    }
+#pragma unroll
+                    for (int j = 0; j < B8; ++j) {
+                        const int i = i0 + j * kScoreThreads;
+                        if (i < n4) dst[i] = t[j];
+                    }
+                }
+                if (a.hist)
+                    for (int i = tid; i < kHistBins; i += kScoreThreads) lhist[i] = 0;
+            }
+            if (adaptive && wave == 0) {
+                float mu = (float)a.L / (float)a.R;
+                float var = row_sum<64>(var_part);
+                const float nu1 = row_sum<64>(nu1_part), nu2 = row_sum<64>(nu2_part);
+                if (vn) {
+                    // weighted scores nu * s, nu and s taken as independent: moments of the product
+                    const float cnt = (float)(a.L * 256);
+                    const float mnu = nu1 / cnt, vnu = fmaxf(nu2 / cnt - mnu * mnu, 0.0f);
+                    var = mnu * mnu * var + mu * mu * vnu + vnu * var;
+                    mu *= mnu;
+                }
+                const float sigma = fmaxf(sqrtf(var), fmaxf(mu * 1e-6f, 1e-30f));
+                const float blo = mu - 4.0f * sigma, binv = 1.0f / (4.0f * sigma);
+                if (lane == 0) {
+                    s_bin[0] = blo;
+                    s_bin[1] = binv;
+                    if (ub == 0) {                   // the select's sweep bins with the very same pair
+                        a.thr[bh * kThrStride + kThrBinLo] = __float_as_uint(blo);
+                        a.thr[bh * kThrStride + kThrBinInv] = __float_as_uint(binv);
+                    }
+                }
+            }
+            __syncthreads();
+            if (adaptive) {
+                bin_lo = s_bin[0];
+                bin_inv = s_bin[1];
+            }
+
+            if (ONE_ROUND) {
+                auto process = [&](const CodeVec<CB> *cv, const bool *dead, const float *w, int base) {
+                    float sum[U];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) sum[u] = group_sum<S>(gather16<CB, MODE, BASE0, BASE0>(cv[u], tbase, woff, 0, a));
+                    emit(base, sum, dead, w);
+                };
+                for (int r0 = 0; r0 < (PAGED ? nround_wg : 1); r0 += RPB) {
+                    if (r0 > 0) {                    // paged: the next RPB rounds' block ids
+                        __syncthreads();
+                        stage_blks(r0);
+                        __syncthreads();
+                        if (r0 < nmine) {
+                            staged(blks, r0, r0);
+                            fetch(setA, deadA, wgtA, blks, unit_base(r0), 0);
+                        }
+                    }
+                    const int last = (PAGED && nmine > r0 + RPB ? r0 + RPB : nmine) - 1;
+                    for (int r = r0; r <= last;) {
+                        if (r < last) {
+                            staged(blks, r + 1, r0);
+                            fetch(setB, deadB, wgtB, blks, unit_base(r + 1), 0);
+                        }
+                        process(setA, deadA, wgtA, unit_base(r));
+                        if (++r > last) break;
+                        if (r < last) {
+                            staged(blks, r + 1, r0);
+                            fetch(setA, deadA, wgtA, blks, unit_base(r + 1), 0);
+                        }
+                        process(setB, deadB, wgtB, unit_base(r));
+                        ++r;
+                    }
+                }
+            } else {
+                for (int r = 0; r < nmine; ++r) {
+                    const int base = unit_base(r);
+                    float sum[U];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) sum[u] = 0.0f;
+                    locate(blks, base);
+                    for (int c = 0; c < a.rounds; ++c) {
+                        fetch(setA, deadA, wgtA, blks, base, c);
+#pragma unroll
+                        for (int u = 0; u < U; ++u) sum[u] += gather16<CB, MODE, BASE0, false>(setA[u], tbase, woff, c, a);
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) sum[u] = group_sum<S>(sum[u]);
+                    emit(base, sum, deadA, wgtA);
+                }
+            }
+
+            if (a.hist) {
+                __syncthreads();
+                uint32_t *gh = a.hist + bh * kHistBins;
+                for (int i = tid; i < kHistBins; i += kScoreThreads)
+                    if (lhist[i]) atomicAdd(&gh[i], lhist[i]);
+            }
+        }
+    };
+    if (tbase == 0) run(BoolTag<true>());
+    else run(BoolTag<false>());
 }
+
 
 // ---------------------------------------------------------------------------------------
 // Split tables (P = 9, 10; packed 10-bit ids).  The one-entry-per-bucket table of 64 tables
@@ -863,10 +1380,8 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(ScoreArgs a) {
 // 16 low bytes and one dword of high-bit pairs per key and group.  The last group applies
 // weights, forced tokens and the mask, and feeds the histogram.
 // ---------------------------------------------------------------------------------------
-#ifndef SK_SPLIT_THREADS
-#define SK_SPLIT_THREADS 1024
-#endif
-constexpr int kSplitThreads = SK_SPLIT_THREADS;
+constexpr int kSplitThreads = 1024;
+constexpr int kSplitU = 2;                           // passes a wavefront takes per turn
 
 // bins of the adaptive histogram, from the per-table spreads the projection pass left (and, for
 // weighted scores, from the value norms it sampled); called by one whole wavefront
@@ -907,10 +1422,7 @@ __global__ __launch_bounds__(kSplitThreads) void score_split_kernel(ScoreArgs a)
     constexpr int GT = 16 * S;                       // tables per group
     constexpr int KPW = 64 / S;                      // keys per wavefront pass
     constexpr int NW = kSplitThreads / 64;
-#ifndef SK_SPLIT_U
-#define SK_SPLIT_U 2
-#endif
-    constexpr int U = SK_SPLIT_U;                    // passes a wavefront takes per turn
+    constexpr int U = kSplitU;
     constexpr int EPL = U / S;                       // results a lane emits per turn
     constexpr int TP = 8192 / kSplitThreads;         // float4 of a group table each thread moves (at most 128 KB in all)
     typedef SplitSet<U, EPL> Set;
@@ -1139,27 +1651,27 @@ __global__ __launch_bounds__(kSplitThreads) void score_split_kernel(ScoreArgs a)
 
 typedef void (*score_fn_t)(ScoreArgs);
 
-template <int S, int CB, int MODE>
+template <int S, int CB, int MODE, bool BATCHED>
 static score_fn_t pick_score_variant(bool one_round, bool paged) {
-    if (one_round) return paged ? score_kernel<S, CB, MODE, true, true> : score_kernel<S, CB, MODE, true, false>;
-    return paged ? score_kernel<S, CB, MODE, false, true> : score_kernel<S, CB, MODE, false, false>;
+    if (one_round) return paged ? score_kernel<S, CB, MODE, true, true, BATCHED> : score_kernel<S, CB, MODE, true, false, BATCHED>;
+    return paged ? score_kernel<S, CB, MODE, false, true, BATCHED> : score_kernel<S, CB, MODE, false, false, BATCHED>;
 }
 
 template <int CB, int MODE>
-static score_fn_t pick_score_s(int S, bool one_round, bool paged) {
+static score_fn_t pick_score_s(int S, bool one_round, bool paged, bool batched) {
     switch (S) {
-        case 1: return pick_score_variant<1, CB, MODE>(one_round, paged);
-        case 2: return pick_score_variant<2, CB, MODE>(one_round, paged);
-        case 4: return pick_score_variant<4, CB, MODE>(one_round, paged);
+        case 1: return batched ? pick_score_variant<1, CB, MODE, true>(one_round, paged) : pick_score_variant<1, CB, MODE, false>(one_round, paged);
+        case 2: return batched ? pick_score_variant<2, CB, MODE, true>(one_round, paged) : pick_score_variant<2, CB, MODE, false>(one_round, paged);
+        case 4: return batched ? pick_score_variant<4, CB, MODE, true>(one_round, paged) : pick_score_variant<4, CB, MODE, false>(one_round, paged);
         default: return nullptr;
     }
 }
 
-static score_fn_t pick_score(const Geometry &g) {
+static score_fn_t pick_score(const Geometry &g, bool batched) {
     const bool one_round = g.rounds == 1, paged = g.page > 0;
-    if (g.mode == kDirect && g.cb == 1) return pick_score_s<1, kDirect>(g.S, one_round, paged);
-    if (g.mode == kFactor && g.cb == 1) return pick_score_s<1, kFactor>(g.S, one_round, paged);
-    if (g.mode == kFactor && g.cb == 2) return pick_score_s<2, kFactor>(g.S, one_round, paged);
+    if (g.mode == kDirect && g.cb == 1) return pick_score_s<1, kDirect>(g.S, one_round, paged, batched);
+    if (g.mode == kFactor && g.cb == 1) return pick_score_s<1, kFactor>(g.S, one_round, paged, batched);
+    if (g.mode == kFactor && g.cb == 2) return pick_score_s<2, kFactor>(g.S, one_round, paged, batched);
     return nullptr;
 }
 
@@ -1190,10 +1702,29 @@ int launch_project(socket_ctx *ctx, const void *q, const void *proj, float tau, 
     const size_t lds = (size_t)(2 * g.G * kPlanePad + g.G * g.d + g.P * g.d) * sizeof(double) +
                        (size_t)(g.P * g.d + g.d) * 4 + 64 + 48 +
                        (g.mode == kSplit ? (size_t)g.G * (256 + 4) * sizeof(double) : 0);
-    dim3 grid(g.Lpad, g.Hkv, batch);
     typedef void (*project_fn_t)(ProjectArgs);
     project_fn_t fn = nullptr;
     const bool f32 = g.kv_dtype == SOCKET_F32;
+    a.batch = batch; a.nb = 1;
+    if (batch > 1) {
+        // several sequences per workgroup: the W slab of a table is staged once for all of them
+        const int elem = f32 ? 4 : 2;
+        int nb = batch < kProjMaxNb ? batch : kProjMaxNb;
+        while (nb > 1 && project_batch_lds(nb, g.G, g.d, g.P, elem) > 64 * 1024) --nb;
+        const int groups = (batch + nb - 1) / nb;
+        a.nb = (batch + groups - 1) / groups;
+        const size_t blds = project_batch_lds(a.nb, g.G, g.d, g.P, elem);
+        switch (g.G) {
+            case 1: fn = f32 ? project_batch_kernel<float, 1> : project_batch_kernel<uint16_t, 1>; break;
+            case 2: fn = f32 ? project_batch_kernel<float, 2> : project_batch_kernel<uint16_t, 2>; break;
+            case 4: fn = f32 ? project_batch_kernel<float, 4> : project_batch_kernel<uint16_t, 4>; break;
+            case 8: fn = f32 ? project_batch_kernel<float, 8> : project_batch_kernel<uint16_t, 8>; break;
+            default: return SOCKET_EUNSUPPORTED;
+        }
+        hipLaunchKernelGGL(fn, dim3(g.Lpad, g.Hkv, groups), dim3(kProjThreads), blds, st, a);
+        return record_hip(ctx, hipGetLastError());
+    }
+    dim3 grid(g.Lpad, g.Hkv, batch);
     const bool dw = !f32 && (g.P * 2) % 16 != 0 && (g.P * 2) % 4 == 0;    // see project_kernel
     switch (g.G) {
         case 1: fn = f32 ? project_kernel<float, 1, false> : dw ? project_kernel<uint16_t, 1, true> : project_kernel<uint16_t, 1, false>; break;
@@ -1236,7 +1767,7 @@ int launch_score_keys(socket_ctx *ctx, const void *codes, const float *vnorm,
     a.table_rows = g.table_rows; a.table_words = g.table_words;
     if (g.mode == kSplit) {
         // one workgroup per CU (a group table fills most of its LDS)
-        const int keys_per_turn = (kSplitThreads / 64) * SK_SPLIT_U * (64 / g.S);
+        const int keys_per_turn = (kSplitThreads / 64) * kSplitU * (64 / g.S);
         int per_bh = 256 / (batch * g.Hkv);
         const int turns = (g.max_n + keys_per_turn - 1) / keys_per_turn;
         if (per_bh > turns) per_bh = turns;
@@ -1259,19 +1790,19 @@ int launch_score_keys(socket_ctx *ctx, const void *codes, const float *vnorm,
         hipLaunchKernelGGL(fn, dim3(per_bh, g.Hkv, batch), dim3(kSplitThreads), lds, st, a);
         return record_hip(ctx, hipGetLastError());
     }
-    // Two resident workgroups per CU over the whole launch, chunks dealt round-robin.
-    const int ckeys = (kScoreThreads / 64) * kScoreU * (64 / g.S);
-    const int nchunks = (g.max_n + ckeys - 1) / ckeys;
-#ifndef SK_SCORE_WGS
-#define SK_SCORE_WGS (256 * 1024 / SK_SCORE_THREADS)
-#endif
-    int per_bh = SK_SCORE_WGS / (batch * g.Hkv);
-    if (per_bh < 1) per_bh = 1;
-    if (per_bh > nchunks) per_bh = nchunks;
-    dim3 grid(per_bh, g.Hkv, batch);
+    // Two resident workgroups per CU over the whole launch (fewer when there is less than one
+    // unit per wavefront): each KV head's units are dealt out evenly to its workgroups.
+    const int wg_keys = (kScoreThreads / 64) * kScoreU * (64 / g.S);
+    int64_t nslot = ((int64_t)batch * g.max_n + wg_keys - 1) / wg_keys;
+    const int per_head = (256 * 1024 / kScoreThreads) / g.Hkv;
+    if (nslot > per_head) nslot = per_head;
+    if (nslot < 1) nslot = 1;
+    dim3 grid((unsigned)nslot, g.Hkv);
+    a.batch = batch;
     a.hist = want_hist ? ctx->hist : nullptr;
-    size_t lds = (size_t)g.table_words * 4 + (a.hist ? kHistBins * 4 + 16 : 0);
-    score_fn_t fn = pick_score(g);
+    size_t lds = (size_t)g.table_words * 4 + (a.hist ? kHistBins * 4 + 16 : 0) + (batch > 1 ? (size_t)batch * 4 : 0) +
+                 (g.page > 0 ? (size_t)kBlkTiles * 4 : 0);   // table, histogram + bins, lengths, block ids
+    score_fn_t fn = pick_score(g, batch > 1);
     if (!fn) return SOCKET_EUNSUPPORTED;
     // more than 64 KB of dynamic LDS has to be allowed per kernel before the launch
     if (set_lds_limit((const void *)fn, lds) != SOCKET_OK) return SOCKET_EHIP;

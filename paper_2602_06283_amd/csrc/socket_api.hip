@@ -27,8 +27,17 @@ int fill_geometry(const socket_params *p, Geometry *g) {
     if (p->page_size > 0) {
         if (p->max_blocks_per_seq < 1 || p->num_blocks < 1) return SOCKET_EINVAL;
         if ((int64_t)p->max_blocks_per_seq * p->page_size < p->max_n) return SOCKET_EINVAL;
+        // token / page is taken as a multiplication by ceil(2^32 / page): exact for every token
+        // when the page size is a power of two, else as long as max_n * page < 2^32
+        if ((p->page_size & (p->page_size - 1)) != 0 && (int64_t)p->max_n * p->page_size >= (int64_t)1 << 32)
+            return SOCKET_EUNSUPPORTED;
     }
-    if ((int64_t)p->max_batch * p->Hkv * (int64_t)p->max_n > (int64_t)1 << 40) return SOCKET_EINVAL;
+    // rows of the K / V / id tensors are numbered in 32 bits (2^31 rows of 64 bf16 elements would
+    // already be 256 GiB of keys)
+    const int64_t rows = p->page_size > 0 ? (int64_t)p->num_blocks * p->Hkv * p->page_size
+                                          : (int64_t)p->max_batch * p->Hkv * (int64_t)p->max_n;
+    if (rows >= (int64_t)1 << 31) return SOCKET_EINVAL;
+    if ((int64_t)p->max_batch * p->Hkv * (int64_t)p->max_n >= (int64_t)1 << 31) return SOCKET_EINVAL;
 
     g->d = p->d; g->Hq = p->Hq; g->Hkv = p->Hkv; g->G = G; g->L = p->L; g->P = p->P;
     g->R = 1 << p->P;

@@ -12,14 +12,8 @@ constexpr int kTile = 16;            // tokens per rotation period of the code l
 constexpr int kHistBits = 11;        // first radix digit of the top-k select (sign, exponent, 2 mantissa bits)
 constexpr int kHistBins = 1 << kHistBits;
 constexpr int kMaxLdsBytes = 160 * 1024;
-#ifndef SK_SCORE_THREADS
-#define SK_SCORE_THREADS 512
-#endif
-#ifndef SK_SCORE_U
-#define SK_SCORE_U 4
-#endif
-constexpr int kScoreThreads = SK_SCORE_THREADS;
-constexpr int kScoreU = SK_SCORE_U;          // 16-byte loads a lane keeps in flight
+constexpr int kScoreThreads = 512;
+constexpr int kScoreU = 4;           // 16-byte loads a lane keeps in flight
 constexpr int kDecodeThreads = 256;
 constexpr int kDecodeChunk = 64;     // selected rows a decode workgroup handles per pass
 constexpr int kDenseSplits = 64;     // splits per (sequence, KV head) of the dense attention baseline
@@ -289,18 +283,15 @@ __host__ __device__ __forceinline__ int packed_pos(int tl, int t, int S) {
 struct RowMap {
     const int32_t *block_table;  // null = contiguous
     int Hkv, max_n, page, max_blocks, num_blocks;
-    int page_shift;              // log2(page) when the page size is a power of two, else -1
+    uint32_t page_magic;         // ceil(2^32 / page): t / page == (t * page_magic) >> 32 for every token t < max_n
+                                 // (exact for power-of-two pages; otherwise socket_create checks max_n * page < 2^32)
+    // block-table column and offset inside the block of token t: no division, no branch
+    __device__ __forceinline__ int page_slot(int t) const { return (int)__umulhi((uint32_t)t, page_magic); }
+    __device__ __forceinline__ int page_off(int t) const { return t - page_slot(t) * page; }
     // -1 when the token's block is absent (paged storage with an out-of-range table entry)
     __device__ __forceinline__ int64_t row(int b, int h, int t) const {
         if (block_table == nullptr) return ((int64_t)b * Hkv + h) * max_n + t;
-        int slot, off;
-        if (page_shift >= 0) {   // the usual case: a shift and a mask instead of a division
-            slot = t >> page_shift;
-            off = t & (page - 1);
-        } else {
-            slot = t / page;
-            off = t - slot * page;
-        }
+        const int slot = page_slot(t), off = t - slot * page;
         int blk = block_table[(int64_t)b * max_blocks + slot];
         if ((unsigned)blk >= (unsigned)num_blocks) return -1;
         return ((int64_t)blk * Hkv + h) * page + off;
@@ -308,10 +299,8 @@ struct RowMap {
 };
 
 inline RowMap row_map(const Geometry &g, const int32_t *block_table) {
-    int shift = -1;
-    if (g.page > 0 && (g.page & (g.page - 1)) == 0)
-        for (shift = 0; (1 << shift) < g.page; ++shift) {}
-    return RowMap{block_table, g.Hkv, g.max_n, g.page, g.max_blocks, g.num_blocks, shift};
+    const uint32_t magic = g.page > 0 ? (uint32_t)((((uint64_t)1 << 32) + g.page - 1) / (uint64_t)g.page) : 0u;
+    return RowMap{block_table, g.Hkv, g.max_n, g.page, g.max_blocks, g.num_blocks, magic};
 }
 
 }  // namespace sk

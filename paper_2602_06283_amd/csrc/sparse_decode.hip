@@ -20,16 +20,6 @@
 
 namespace sk {
 
-#ifdef SK_DEBUG_CLOCKS
-__device__ long long sk_dbg3[64];
-#define SK_STAMP3(i) do { if (threadIdx.x == 0 && split == 0 && h == 0 && b == 0) sk_dbg3[i] = wall_clock64(); } while (0)
-extern "C" int socket_debug_clocks3(long long *out) {
-    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(sk_dbg3), sizeof(long long) * 64);
-}
-#else
-#define SK_STAMP3(i) ((void)0)
-#endif
-
 // where a workgroup's rows come from
 enum RowSource {
     kRowsIdx = 0,      // its slice of the ordered row idx[b, h, :n_selected]               (Eq. 2)
@@ -48,7 +38,6 @@ struct DecodeArgs {
     const int32_t *idx;
     const int32_t *n_selected;
     float *partials;
-    uint32_t *counters;
     void *out;
     RowMap map;
     float scale;
@@ -150,7 +139,6 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
     } else if (SRC == kRowsIdx) {
         count = a.n_selected[bh];
     }
-    SK_STAMP3(0);
     // too many candidates to rank here: the caller attends the head from the ordered row instead
     if (SRC == kRowsSweep && n_cand > kSweepCand) return true;
     float qf[G][8];
@@ -210,7 +198,6 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
         // ---- logits: scale * k.q for every query head of the group
 #pragma unroll
         for (int p = 0; p < NPASS; ++p) {
-            if (p == 0) SK_STAMP3(2);
             float kf[8];
             kr[p].get(kf);
 #pragma unroll
@@ -227,7 +214,6 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
             for (int p = 0; p < NPASS; ++p) vr[p].store(&s_v[p * RPP + wave * RPW + rl][sub * 8]);
         }
         __syncthreads();
-        SK_STAMP3(3);
 
         // ---- running softmax statistics, one wavefront per query head at a time
         for (int g = wave; g < G; g += NWAVE) {
@@ -245,7 +231,6 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
             }
         }
         __syncthreads();
-        SK_STAMP3(4);
 
         // ---- weighted value rows
 #pragma unroll
@@ -345,12 +330,10 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
                 s_row[tid] = row;
             }
             __syncthreads();
-            SK_STAMP3(1);
             attend_chunk();
         }
     }
 
-    SK_STAMP3(5);
     // ---- this split's partial result: (max, sum, weighted value sum) per query head
     float *part = a.partials + ((int64_t)(b * a.Hq + h * G) * a.n_split) * (D + 2);
 #pragma unroll
@@ -363,7 +346,6 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
         part[((int64_t)tid * a.n_split + split) * (D + 2) + 0] = s_m[tid];
         part[((int64_t)tid * a.n_split + split) * (D + 2) + 1] = s_l[tid];
     }
-    SK_STAMP3(6);
     return false;
 }
 
@@ -514,16 +496,19 @@ static int launch_merge(const DecodeArgs &a, const Geometry &g, int batch, hipSt
     return SOCKET_OK;
 }
 
-static DecodeArgs decode_args(socket_ctx *ctx, const void *q, const void *K, const void *V,
+static DecodeArgs decode_args(const Geometry &g, float *partials, const void *q, const void *K, const void *V,
                               const int32_t *block_table, float scale, int out_dtype, void *out, int n_split) {
-    const Geometry &g = ctx->g;
     DecodeArgs a;
     a.q = q; a.K = K; a.V = V; a.idx = nullptr; a.n_selected = nullptr; a.seq_len = nullptr;
-    a.partials = ctx->partials; a.counters = ctx->counters; a.out = out;
+    a.partials = partials; a.out = out;
     a.map = row_map(g, block_table);
     a.scale = scale; a.Hq = g.Hq; a.max_k = g.max_k; a.n_split = n_split; a.out_dtype = out_dtype;
     a.staged = nullptr; a.cand_key = nullptr; a.cand_idx = nullptr; a.thr = nullptr;
     return a;
+}
+static DecodeArgs decode_args(socket_ctx *ctx, const void *q, const void *K, const void *V,
+                              const int32_t *block_table, float scale, int out_dtype, void *out, int n_split) {
+    return decode_args(ctx->g, ctx->partials, q, K, V, block_table, scale, out_dtype, out, n_split);
 }
 
 // Eq. 1: every token below seq_len, 64 splits per (sequence, KV head)
@@ -540,16 +525,22 @@ int launch_dense_decode(socket_ctx *ctx, const void *q, const void *K, const voi
     return record_hip(ctx, hipGetLastError());
 }
 
-// Eq. 2 from the ordered index row
-int launch_sparse_decode(socket_ctx *ctx, const void *q, const void *K, const void *V,
-                         const int32_t *idx, const int32_t *n_selected, const int32_t *block_table,
-                         int batch, float scale, int out_dtype, void *out, hipStream_t st) {
-    const Geometry &g = ctx->g;
-    DecodeArgs a = decode_args(ctx, q, K, V, block_table, scale, out_dtype, out, g.n_split);
+// Eq. 2 from the ordered index row, split-K partial results in `partials`
+static int sparse_decode_launches(const Geometry &g, float *partials, const void *q, const void *K, const void *V,
+                                  const int32_t *idx, const int32_t *n_selected, const int32_t *block_table,
+                                  int batch, float scale, int out_dtype, void *out, hipStream_t st) {
+    DecodeArgs a = decode_args(g, partials, q, K, V, block_table, scale, out_dtype, out, g.n_split);
     a.idx = idx; a.n_selected = n_selected;
     int rc = launch_decode<kRowsIdx>(a, nullptr, g, dim3(g.n_split, g.Hkv, batch), st);
     if (rc != SOCKET_OK) return rc;
-    rc = launch_merge(a, g, batch, st);
+    return launch_merge(a, g, batch, st);
+}
+
+int launch_sparse_decode(socket_ctx *ctx, const void *q, const void *K, const void *V,
+                         const int32_t *idx, const int32_t *n_selected, const int32_t *block_table,
+                         int batch, float scale, int out_dtype, void *out, hipStream_t st) {
+    int rc = sparse_decode_launches(ctx->g, ctx->partials, q, K, V, idx, n_selected, block_table, batch, scale,
+                                    out_dtype, out, st);
     if (rc != SOCKET_OK) return rc;
     return record_hip(ctx, hipGetLastError());
 }
