@@ -82,6 +82,10 @@ extern "C" {
 #define SOCKET_EUNSUPPORTED (-2) /* a valid request this build has no kernel for */
 #define SOCKET_ENOMEM (-3)       /* scratch allocation failed */
 #define SOCKET_EHIP (-4)         /* a HIP call failed; see socket_last_hip_error */
+#define SOCKET_ELIMIT (-5)       /* more than socket_sparse_decode_noalloc's fixed scratch can hold */
+
+/* bytes of the fixed device array behind socket_sparse_decode_noalloc */
+#define SOCKET_NOALLOC_SCRATCH_BYTES (4 * 1024 * 1024)
 
 typedef struct socket_ctx socket_ctx;
 
@@ -242,6 +246,26 @@ int socket_sparse_decode(socket_ctx *ctx, const void *q, const void *K, const vo
                          const int32_t *idx, const int32_t *n_selected,
                          const int32_t *block_table, int32_t batch, float scale,
                          int32_t out_dtype, void *out, void *stream);
+
+/*
+ * socket_sparse_decode for callers that cannot allocate device memory and hold no context:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels and the same result as socket_sparse_decode, with the parameter block
+ * in place of the context (d, Hq, Hkv, kv_dtype, max_batch, max_n, max_k and the paging fields
+ * are used; L and P must be valid but play no part).  The split-K partial results go to a
+ * fixed array of SOCKET_NOALLOC_SCRATCH_BYTES that every GPU the library runs on holds until
+ * the process ends; the call neither allocates nor frees, on the host side of HIP or on the
+ * device.  A request that needs more, i.e.
+ *     batch * Hq * min(64, ceil(max_k / 64)) * (d + 2) * 4  >  SOCKET_NOALLOC_SCRATCH_BYTES,
+ * returns SOCKET_ELIMIT and launches nothing.  All calls on one GPU share that GPU's array:
+ * calls that overlap in time on one GPU (different streams, or this call beside another of
+ * itself) race on it; calls on one stream do not.  Nothing in the array has to be cleared
+ * between calls.  *hip_error (may be NULL) receives the HIP code when SOCKET_EHIP is returned.
+ */
+int socket_sparse_decode_noalloc(const socket_params *p, const void *q, const void *K, const void *V,
+                                 const int32_t *idx, const int32_t *n_selected,
+                                 const int32_t *block_table, int32_t batch, float scale,
+                                 int32_t out_dtype, void *out, void *stream, int32_t *hip_error);
 
 /*
  * Eq. 1 (dense softmax attention over every token t < seq_len[b]), with the same split-K

@@ -13,7 +13,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libsocket.so")
 
 BF16, F32 = 0, 1
-OK, EINVAL, EUNSUPPORTED, ENOMEM, EHIP = 0, -1, -2, -3, -4
+OK, EINVAL, EUNSUPPORTED, ENOMEM, EHIP, ELIMIT = 0, -1, -2, -3, -4, -5
+NOALLOC_SCRATCH_BYTES = 4 * 1024 * 1024
 
 
 class Params(ctypes.Structure):
@@ -60,6 +61,8 @@ def lib():
         L.socket_score_keys.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp]
         L.socket_topk_select.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp]
         L.socket_sparse_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, f32, i32, vp, vp]
+        L.socket_sparse_decode_noalloc.argtypes = [ctypes.POINTER(Params), vp, vp, vp, vp, vp, vp, i32, f32, i32, vp,
+                                                   vp, ctypes.POINTER(i32)]
         L.socket_dense_decode.argtypes = [vp, vp, vp, vp, vp, vp, i32, f32, i32, vp, vp]
         L.socket_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, i32, f32, vp, vp, vp,
                                          i32, vp, vp]
@@ -78,7 +81,7 @@ EXPORTS = ("socket_validate_params", "socket_codes_per_token", "socket_code_posi
            "socket_codes_bytes", "socket_code_location",
            "socket_create", "socket_destroy", "socket_scratch_bytes", "socket_hash_keys",
            "socket_value_norms", "socket_set_forced_tokens", "socket_set_deterministic",
-           "socket_score", "socket_soft_hash", "socket_hard_hash", "socket_score_keys", "socket_topk_select", "socket_sparse_decode", "socket_dense_decode", "socket_decode_step", "socket_strerror",
+           "socket_score", "socket_soft_hash", "socket_hard_hash", "socket_score_keys", "socket_topk_select", "socket_sparse_decode", "socket_sparse_decode_noalloc", "socket_dense_decode", "socket_decode_step", "socket_strerror",
            "socket_last_hip_error", "socket_graph_begin", "socket_graph_end",
            "socket_graph_launch", "socket_graph_destroy")
 
@@ -225,6 +228,18 @@ class Context:
                                              _ptr(k), batch, float(scale), _ptr(scores), _ptr(idx),
                                              _ptr(n_selected), out_dtype, _ptr(out), _stream(stream)),
                     "socket_decode_step")
+
+
+def sparse_decode_noalloc(params: Params, q, K, V, idx, n_selected, batch, scale, out, block_table=None,
+                          stream=None):
+    """socket_sparse_decode_noalloc: no context, no allocation (see socket.h)."""
+    out_dtype = F32 if out.dtype == torch.float32 else BF16
+    hip = ctypes.c_int32(0)
+    rc = lib().socket_sparse_decode_noalloc(ctypes.byref(params), _ptr(q), _ptr(K), _ptr(V), _ptr(idx),
+                                            _ptr(n_selected), _ptr(block_table), batch, float(scale),
+                                            out_dtype, _ptr(out), _stream(stream), ctypes.byref(hip))
+    if rc != OK:
+        raise SocketError(rc, f"socket_sparse_decode_noalloc (hip error {hip.value})")
 
 
 class Graph:

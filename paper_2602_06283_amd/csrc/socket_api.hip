@@ -348,6 +348,21 @@ int socket_sparse_decode(socket_ctx *ctx, const void *q, const void *K, const vo
                                 out, (hipStream_t)stream);
 }
 
+int socket_sparse_decode_noalloc(const socket_params *p, const void *q, const void *K, const void *V,
+                                 const int32_t *idx, const int32_t *n_selected,
+                                 const int32_t *block_table, int32_t batch, float scale,
+                                 int32_t out_dtype, void *out, void *stream, int32_t *hip_error) {
+    if (hip_error) *hip_error = 0;
+    if (!p || !q || !K || !V || !idx || !n_selected || !out) return SOCKET_EINVAL;
+    if (out_dtype != SOCKET_BF16 && out_dtype != SOCKET_F32) return SOCKET_EINVAL;
+    if (!(scale == scale) || scale > 3.0e38f || scale < -3.0e38f) return SOCKET_EINVAL;
+    int hip = 0;
+    const int rc = sparse_decode_noalloc(p, q, K, V, idx, n_selected, block_table, batch, scale, out_dtype, out,
+                                         (hipStream_t)stream, &hip);
+    if (hip_error) *hip_error = hip;
+    return rc;
+}
+
 const char *socket_strerror(int code) {
     switch (code) {
         case SOCKET_OK: return "ok";
@@ -355,6 +370,7 @@ const char *socket_strerror(int code) {
         case SOCKET_EUNSUPPORTED: return "unsupported configuration";
         case SOCKET_ENOMEM: return "scratch allocation failed";
         case SOCKET_EHIP: return "HIP runtime error";
+        case SOCKET_ELIMIT: return "request exceeds the fixed scratch of the no-allocation entry point";
         default: return "unknown error";
     }
 }

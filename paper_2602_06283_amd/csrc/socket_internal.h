@@ -123,6 +123,11 @@ int launch_value_norms(socket_ctx *ctx, const void *V, const int32_t *block_tabl
 int launch_sparse_decode(socket_ctx *ctx, const void *q, const void *K, const void *V,
                          const int32_t *idx, const int32_t *n_selected, const int32_t *block_table,
                          int batch, float scale, int out_dtype, void *out, hipStream_t st);
+// the same without a context: partial results in a file-scope device array; *hip_error gets the
+// HIP code when SOCKET_EHIP is returned
+int sparse_decode_noalloc(const socket_params *p, const void *q, const void *K, const void *V,
+                          const int32_t *idx, const int32_t *n_selected, const int32_t *block_table,
+                          int batch, float scale, int out_dtype, void *out, hipStream_t st, int *hip_error);
 
 // ---- device helpers -------------------------------------------------------------------
 

@@ -16,6 +16,8 @@
 // space, so the last bits of the output can differ from run to run.  The ordering of the
 // index row for the caller (topk_resolve_body) then runs beside the merge of the splits, as
 // extra workgroups of that launch.
+#include <mutex>
+
 #include "topk_device.h"
 
 namespace sk {
@@ -543,6 +545,69 @@ int launch_sparse_decode(socket_ctx *ctx, const void *q, const void *K, const vo
                                     out_dtype, out, st);
     if (rc != SOCKET_OK) return rc;
     return record_hip(ctx, hipGetLastError());
+}
+
+// ---------------------------------------------------------------------------------------
+// The same attention for callers that may not allocate: the split-K partial results live in
+// a file-scope device array instead of a context's scratch.  Host code never passes the
+// array's name to a kernel (there it is only a stand-in): its device address is asked for once
+// per device and kept.
+// ---------------------------------------------------------------------------------------
+constexpr size_t kStaticScratchBytes = (size_t)SOCKET_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex scratch_lock;
+static void *scratch_ptr[kMaxDevices];               // device address of `scratch` on each device, once known
+
+// the current device's copy of the array; null (and *err set) when HIP refuses
+static void *static_scratch(hipError_t *err) {
+    int dev = -1;
+    *err = hipGetDevice(&dev);
+    if (*err != hipSuccess) return nullptr;
+    if (dev < 0 || dev >= kMaxDevices) {
+        *err = hipErrorInvalidDevice;
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> hold(scratch_lock);
+    if (!scratch_ptr[dev]) {
+        void *p = nullptr;
+        *err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (*err != hipSuccess || !p) {
+            if (*err == hipSuccess) *err = hipErrorInvalidSymbol;
+            return nullptr;
+        }
+        scratch_ptr[dev] = p;
+    }
+    return scratch_ptr[dev];
+}
+
+int sparse_decode_noalloc(const socket_params *p, const void *q, const void *K, const void *V,
+                          const int32_t *idx, const int32_t *n_selected, const int32_t *block_table,
+                          int batch, float scale, int out_dtype, void *out, hipStream_t st, int *hip_error) {
+    Geometry g;
+    int rc = fill_geometry(p, &g);
+    if (rc != SOCKET_OK) return rc;
+    if (batch < 1 || batch > g.max_batch) return SOCKET_EINVAL;
+    if ((g.page > 0) != (block_table != nullptr)) return SOCKET_EINVAL;
+    const size_t need = (size_t)batch * g.Hq * g.n_split * (g.d + 2) * sizeof(float);
+    if (need > kStaticScratchBytes) return SOCKET_ELIMIT;
+    hipError_t e = hipSuccess;
+    float *partials = (float *)static_scratch(&e);
+    if (!partials) {
+        if (hip_error) *hip_error = (int)e;
+        return SOCKET_EHIP;
+    }
+    // nothing in the array has to start at zero: every split writes its whole partial result,
+    // empty splits included, before the merge reads it
+    rc = sparse_decode_launches(g, partials, q, K, V, idx, n_selected, block_table, batch, scale, out_dtype, out, st);
+    if (rc != SOCKET_OK) return rc;
+    e = hipGetLastError();
+    if (e != hipSuccess) {
+        if (hip_error) *hip_error = (int)e;
+        return SOCKET_EHIP;
+    }
+    return SOCKET_OK;
 }
 
 // The tail of the fused decode step, after the select's sweep (launch_topk_sweep): Eq. 2 from
