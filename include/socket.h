@@ -223,6 +223,46 @@ int socket_score_keys(socket_ctx *ctx, const void *codes, const float *vnorm,
                       float *scores, void *stream);
 
 /*
+ * Alg. 5 and the TopK step of Alg. 3 as the fused decode step runs them, for callers that
+ * issue the stages themselves: socket_score_keys_binned is socket_score_keys whose pass over
+ * the keys also leaves, in the context, a histogram of the scores (bins sized from the bucket
+ * probabilities the context holds, or leading digits of the score when those do not apply);
+ * socket_topk_select_binned is socket_topk_select starting from that histogram instead of
+ * making its own.  Same scores, same selection.  The two calls come in pairs on one context:
+ * a socket_topk_select_binned without the other before it returns SOCKET_EINVAL.
+ */
+int socket_score_keys_binned(socket_ctx *ctx, const void *codes, const float *vnorm,
+                             const int32_t *block_table, const int32_t *seq_len, int32_t batch,
+                             float *scores, void *stream);
+int socket_topk_select_binned(socket_ctx *ctx, const float *scores, const int32_t *seq_len,
+                              const int32_t *k, int32_t batch, int32_t *idx, int32_t *n_selected,
+                              void *stream);
+
+/*
+ * Clears the context's select scratch (histograms, counters, a pending
+ * socket_score_keys_binned), with fill kernels on `stream`: for a caller that abandoned a chain
+ * of calls half-way (an error, a socket_score_keys_binned never followed by its select).
+ */
+int socket_reset(socket_ctx *ctx, void *stream);
+
+/*
+ * Alg. 2 read-back: the bucket probabilities the context holds after socket_soft_hash,
+ * socket_hard_hash, socket_score or socket_decode_step, as the scoring pass looks them up:
+ *     probs[b, h, l, r] = (1/G) * sum_{g in group(h)} p_g^(l)(r | q)
+ * device float32 [batch, Hkv, L, R], R = 2^P, whatever layout the context keeps them in.
+ * For inspection and tests; not on the decode path.
+ */
+int socket_bucket_probs(socket_ctx *ctx, int32_t batch, float *probs, void *stream);
+
+/*
+ * Measurement aid, no part of the method: a kernel that reads `bytes` (a multiple of 16) of
+ * device memory once and does nothing else, loading the way the scoring pass loads its ids.
+ * What it reaches is the ceiling for any streaming kernel on this GPU, to be read beside the
+ * published peak.  *sink: device word the kernel may write.
+ */
+int socket_probe_stream_read(const void *buf, int64_t bytes, uint32_t *sink, void *stream);
+
+/*
  * Alg. 3, TopK step: for each (b, h) the min(k[b], #valid) tokens with the
  * largest scores, ties broken towards the smaller token position; -inf and NaN
  * scores are never selected.  The chosen positions are written in ascending

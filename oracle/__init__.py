@@ -5,5 +5,5 @@ The GPU library never imports it.
 """
 from .socket_oracle import (  # noqa: F401
     hash_keys, soft_probs, score, hard_score, topk, sparse_decode, dense_decode,
-    value_norms, force_tokens, num_threads,
+    value_norms, force_tokens, num_threads, precision, jaccard, ndcg,
 )

@@ -22,7 +22,7 @@
  *   - top-k order: larger score first, ties to the smaller index.
  *
  * Pins: every function here is pinned by tests/test_oracle_pins.py against
- * closed forms, limits, brute force and library routines; the one thing with no
+ * closed forms, limits, brute force, hand-worked cases and library routines; the one thing with no
  * pin is an end-to-end numeric value, for which the paper prints no worked
  * example ("parity unpinned" for end-to-end values only).
  */
@@ -286,5 +286,66 @@ int socket_oracle_value_norms(const float *V, long n, int d, float *vnorm) {
         for (int c = 0; c < d; ++c) s += (double)V[j * d + c] * (double)V[j * d + c];
         vnorm[j] = (float)sqrt(s);
     }
+    return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------------- *
+ * Ranking-quality metrics (appendix "Definitions of metrics", used for the
+ * ranking-quality figure).  Index sets are arrays of distinct token positions.
+ * ------------------------------------------------------------------------- */
+
+/* how many entries of a[0..na) also occur in b[0..nb) (plain double loop) */
+static long count_common(const int32_t *a, long na, const int32_t *b, long nb) {
+    long common = 0;
+    for (long i = 0; i < na; ++i)
+        for (long j = 0; j < nb; ++j)
+            if (a[i] == b[j]) {
+                ++common;
+                break;
+            }
+    return common;
+}
+
+/* Precision = |S_k intersect R| / k, S_k the k retrieved items, R the relevant ones. */
+int socket_oracle_precision(const int32_t *retrieved, long k, const int32_t *relevant, long nrel,
+                            double *out) {
+    if (!retrieved || !relevant || !out || k <= 0 || nrel < 0) return ORACLE_EINVAL;
+    *out = (double)count_common(retrieved, k, relevant, nrel) / (double)k;
+    return ORACLE_OK;
+}
+
+/* Jaccard(A, B) = |A intersect B| / |A union B|; two empty sets give 1. */
+int socket_oracle_jaccard(const int32_t *a, long na, const int32_t *b, long nb, double *out) {
+    if (!out || na < 0 || nb < 0 || (na > 0 && !a) || (nb > 0 && !b)) return ORACLE_EINVAL;
+    const long common = count_common(a, na, b, nb);
+    const long uni = na + nb - common;
+    *out = uni > 0 ? (double)common / (double)uni : 1.0;
+    return ORACLE_OK;
+}
+
+static int descending(const void *x, const void *y) {
+    const double a = *(const double *)x, b = *(const double *)y;
+    return (a < b) - (a > b);
+}
+
+/* NDCG of a ranked list of length k: DCG = sum_{i=1..k} (2^{r_i} - 1) / log2(i + 1), r_i the
+ * relevance of the item at rank i; IDCG is the DCG of the best list of length k that the n
+ * candidate items allow, i.e. their k largest relevances in decreasing order; NDCG = DCG / IDCG.
+ *   rel_ranked [k]  relevance of the retrieved items, best-ranked first
+ *   rel_all    [n]  relevance of every candidate item, n >= k                              */
+int socket_oracle_ndcg(const double *rel_ranked, long k, const double *rel_all, long n, double *out) {
+    if (!rel_ranked || !rel_all || !out || k <= 0 || n < k) return ORACLE_EINVAL;
+    double *sorted = (double *)malloc((size_t)n * sizeof(double));
+    if (!sorted) return ORACLE_ENOMEM;
+    memcpy(sorted, rel_all, (size_t)n * sizeof(double));
+    qsort(sorted, (size_t)n, sizeof(double), descending);
+    double dcg = 0.0, idcg = 0.0;
+    for (long i = 1; i <= k; ++i) {
+        const double discount = log2((double)i + 1.0);
+        dcg += (pow(2.0, rel_ranked[i - 1]) - 1.0) / discount;
+        idcg += (pow(2.0, sorted[i - 1]) - 1.0) / discount;
+    }
+    free(sorted);
+    *out = idcg != 0.0 ? dcg / idcg : 0.0;
     return ORACLE_OK;
 }

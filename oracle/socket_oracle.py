@@ -16,7 +16,8 @@ _LIB = None
 def _lib():
     global _LIB
     if _LIB is None:
-        path = _build.build(force=False)
+        # SOCKET_ORACLE_LIB: a build of the same source to load instead (the sanitizer run of the pins)
+        path = os.environ.get("SOCKET_ORACLE_LIB") or _build.build(force=False)
         lib = ctypes.CDLL(path)
         _LIB = lib
     return _LIB
@@ -177,3 +178,39 @@ def value_norms(V):
         _p(V, ctypes.c_float), ctypes.c_long(n), ctypes.c_int(d), _p(out, ctypes.c_float))
     _check(rc, "value_norms")
     return out
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def precision(retrieved, relevant):
+    """Precision = |S_k & R| / k (appendix, metric definitions).  Index arrays -> float."""
+    s, r = _i32(retrieved), _i32(relevant)
+    out = ctypes.c_double(0.0)
+    rc = _lib().socket_oracle_precision(_p(s, ctypes.c_int32), ctypes.c_long(s.shape[0]),
+                                        _p(r, ctypes.c_int32), ctypes.c_long(r.shape[0]), ctypes.byref(out))
+    _check(rc, "precision")
+    return out.value
+
+
+def jaccard(a, b):
+    """Jaccard(A, B) = |A & B| / |A | B| (appendix, metric definitions).  Index arrays -> float."""
+    a, b = _i32(a), _i32(b)
+    out = ctypes.c_double(0.0)
+    rc = _lib().socket_oracle_jaccard(_p(a, ctypes.c_int32), ctypes.c_long(a.shape[0]),
+                                      _p(b, ctypes.c_int32), ctypes.c_long(b.shape[0]), ctypes.byref(out))
+    _check(rc, "jaccard")
+    return out.value
+
+
+def ndcg(rel_ranked, rel_all):
+    """NDCG of a ranked list (appendix, metric definitions): rel_ranked [k] relevance of the
+    retrieved items best-ranked first, rel_all [n] relevance of every candidate -> float."""
+    rr = np.ascontiguousarray(rel_ranked, dtype=np.float64)
+    ra = np.ascontiguousarray(rel_all, dtype=np.float64)
+    out = ctypes.c_double(0.0)
+    rc = _lib().socket_oracle_ndcg(_p(rr, ctypes.c_double), ctypes.c_long(rr.shape[0]),
+                                   _p(ra, ctypes.c_double), ctypes.c_long(ra.shape[0]), ctypes.byref(out))
+    _check(rc, "ndcg")
+    return out.value

@@ -60,6 +60,11 @@ def lib():
         L.socket_hard_hash.argtypes = [vp, vp, vp, i32, vp]
         L.socket_score_keys.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp]
         L.socket_topk_select.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp]
+        L.socket_score_keys_binned.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp]
+        L.socket_topk_select_binned.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp]
+        L.socket_reset.argtypes = [vp, vp]
+        L.socket_bucket_probs.argtypes = [vp, i32, vp, vp]
+        L.socket_probe_stream_read.argtypes = [vp, ctypes.c_int64, vp, vp]
         L.socket_sparse_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, f32, i32, vp, vp]
         L.socket_sparse_decode_noalloc.argtypes = [ctypes.POINTER(Params), vp, vp, vp, vp, vp, vp, i32, f32, i32, vp,
                                                    vp, ctypes.POINTER(i32)]
@@ -81,7 +86,7 @@ EXPORTS = ("socket_validate_params", "socket_codes_per_token", "socket_code_posi
            "socket_codes_bytes", "socket_code_location",
            "socket_create", "socket_destroy", "socket_scratch_bytes", "socket_hash_keys",
            "socket_value_norms", "socket_set_forced_tokens", "socket_set_deterministic",
-           "socket_score", "socket_soft_hash", "socket_hard_hash", "socket_score_keys", "socket_topk_select", "socket_sparse_decode", "socket_sparse_decode_noalloc", "socket_dense_decode", "socket_decode_step", "socket_strerror",
+           "socket_score", "socket_soft_hash", "socket_hard_hash", "socket_score_keys", "socket_score_keys_binned", "socket_topk_select", "socket_topk_select_binned", "socket_reset", "socket_bucket_probs", "socket_probe_stream_read", "socket_sparse_decode", "socket_sparse_decode_noalloc", "socket_dense_decode", "socket_decode_step", "socket_strerror",
            "socket_last_hip_error", "socket_graph_begin", "socket_graph_end",
            "socket_graph_launch", "socket_graph_destroy")
 
@@ -201,6 +206,22 @@ class Context:
                                             _ptr(seq_len), batch, _ptr(scores), _stream(stream)),
                     "socket_score_keys")
 
+    def score_keys_binned(self, codes, seq_len, batch, scores, vnorm=None, block_table=None, stream=None):
+        self._check(lib().socket_score_keys_binned(self._h, _ptr(codes), _ptr(vnorm), _ptr(block_table),
+                                                   _ptr(seq_len), batch, _ptr(scores), _stream(stream)),
+                    "socket_score_keys_binned")
+
+    def topk_select_binned(self, scores, seq_len, k, batch, idx, n_selected, stream=None):
+        self._check(lib().socket_topk_select_binned(self._h, _ptr(scores), _ptr(seq_len), _ptr(k), batch,
+                                                    _ptr(idx), _ptr(n_selected), _stream(stream)),
+                    "socket_topk_select_binned")
+
+    def reset(self, stream=None):
+        self._check(lib().socket_reset(self._h, _stream(stream)), "socket_reset")
+
+    def bucket_probs(self, batch, probs, stream=None):
+        self._check(lib().socket_bucket_probs(self._h, batch, _ptr(probs), _stream(stream)), "socket_bucket_probs")
+
     def topk_select(self, scores, seq_len, k, batch, idx, n_selected, stream=None):
         self._check(lib().socket_topk_select(self._h, _ptr(scores), _ptr(seq_len), _ptr(k), batch,
                                              _ptr(idx), _ptr(n_selected), _stream(stream)),
@@ -240,6 +261,13 @@ def sparse_decode_noalloc(params: Params, q, K, V, idx, n_selected, batch, scale
                                             out_dtype, _ptr(out), _stream(stream), ctypes.byref(hip))
     if rc != OK:
         raise SocketError(rc, f"socket_sparse_decode_noalloc (hip error {hip.value})")
+
+
+def probe_stream_read(buf, sink, stream=None):
+    """socket_probe_stream_read over the whole tensor `buf` (measurement aid, see socket.h)."""
+    rc = lib().socket_probe_stream_read(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink), _stream(stream))
+    if rc != OK:
+        raise SocketError(rc, "socket_probe_stream_read")
 
 
 class Graph:

@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsocket.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-SOURCES = ["socket_api.hip", "hash_keys.hip", "score.hip", "topk.hip", "sparse_decode.hip", "value_norms.hip"]
+SOURCES = ["socket_api.hip", "hash_keys.hip", "score.hip", "topk.hip", "sparse_decode.hip", "value_norms.hip", "util.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed fp32 VALU forms have given silent wrong results on the test machines
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

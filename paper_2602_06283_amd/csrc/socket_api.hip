@@ -154,6 +154,7 @@ int socket_create(socket_ctx **out, const socket_params *p) {
     ctx->p = *p;
     ctx->g = g;
     ctx->last_hip_error = 0;
+    ctx->pending_hist = kHistNone;
     hipError_t e = hipGetDevice(&ctx->device);
     if (e != hipSuccess) {
         delete ctx;
@@ -282,6 +283,44 @@ int socket_score_keys(socket_ctx *ctx, const void *codes, const float *vnorm,
     if (!ctx || !codes || !seq_len || !scores) return SOCKET_EINVAL;
     if (!batch_ok(ctx, batch) || !paging_ok(ctx, block_table)) return SOCKET_EINVAL;
     return launch_score_keys(ctx, codes, vnorm, block_table, seq_len, batch, scores, false, nullptr, (hipStream_t)stream);
+}
+
+int socket_score_keys_binned(socket_ctx *ctx, const void *codes, const float *vnorm,
+                             const int32_t *block_table, const int32_t *seq_len, int32_t batch,
+                             float *scores, void *stream) {
+    if (!ctx || !codes || !seq_len || !scores) return SOCKET_EINVAL;
+    if (!batch_ok(ctx, batch) || !paging_ok(ctx, block_table)) return SOCKET_EINVAL;
+    int mode = sk::kHistNone;
+    const int rc = launch_score_keys(ctx, codes, vnorm, block_table, seq_len, batch, scores, true, &mode, (hipStream_t)stream);
+    if (rc == SOCKET_OK) ctx->pending_hist = mode;
+    return rc;
+}
+
+int socket_topk_select_binned(socket_ctx *ctx, const float *scores, const int32_t *seq_len,
+                              const int32_t *k, int32_t batch, int32_t *idx, int32_t *n_selected,
+                              void *stream) {
+    if (!ctx || !scores || !seq_len || !k || !idx || !n_selected) return SOCKET_EINVAL;
+    if (!batch_ok(ctx, batch)) return SOCKET_EINVAL;
+    if (ctx->pending_hist == sk::kHistNone) return SOCKET_EINVAL;    // no socket_score_keys_binned before it
+    const int mode = ctx->pending_hist;
+    ctx->pending_hist = sk::kHistNone;
+    return launch_topk(ctx, scores, seq_len, k, batch, idx, n_selected, mode, (hipStream_t)stream);
+}
+
+int socket_reset(socket_ctx *ctx, void *stream) {
+    if (!ctx) return SOCKET_EINVAL;
+    return launch_reset(ctx, (hipStream_t)stream);
+}
+
+int socket_bucket_probs(socket_ctx *ctx, int32_t batch, float *probs, void *stream) {
+    if (!ctx || !probs) return SOCKET_EINVAL;
+    if (!batch_ok(ctx, batch)) return SOCKET_EINVAL;
+    return launch_bucket_probs(ctx, batch, probs, (hipStream_t)stream);
+}
+
+int socket_probe_stream_read(const void *buf, int64_t bytes, uint32_t *sink, void *stream) {
+    if (!buf || !sink || bytes < 16 || bytes % 16) return SOCKET_EINVAL;
+    return launch_stream_read(buf, bytes, sink, (hipStream_t)stream);
 }
 
 int socket_topk_select(socket_ctx *ctx, const float *scores, const int32_t *seq_len,

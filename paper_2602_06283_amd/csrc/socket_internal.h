@@ -72,6 +72,7 @@ struct socket_ctx {
     float *tables;        // [max_batch*Hkv][table_words]
     float *tstats;        // [max_batch*Hkv][Lpad][3] spread of each table's bucket probabilities, sampled value norms
     const float *vnorm_sampled;   // the value-norm array the last projection pass sampled (or null)
+    int pending_hist;     // HistMode of what socket_score_keys_binned left for socket_topk_select_binned
     void *wfrag;          // W cut into MFMA fragments for the fast prefill hash (null when that path does not apply)
     uint32_t *hist;       // [2][max_batch*Hkv][kHistBins]
     uint32_t *counters;   // [max_batch*Hkv][kCounterStride] counters, then [max_batch*Hkv][kThrStride] records
@@ -117,6 +118,9 @@ int launch_sweep_decode(socket_ctx *ctx, const void *q, const void *K, const voi
 int launch_dense_decode(socket_ctx *ctx, const void *q, const void *K, const void *V,
                         const int32_t *block_table, const int32_t *seq_len, int batch, float scale,
                         int out_dtype, void *out, hipStream_t st);
+int launch_bucket_probs(socket_ctx *ctx, int batch, float *probs, hipStream_t st);
+int launch_reset(socket_ctx *ctx, hipStream_t st);
+int launch_stream_read(const void *buf, int64_t bytes, uint32_t *sink, hipStream_t st);
 int launch_value_norms(socket_ctx *ctx, const void *V, const int32_t *block_table,
                        const int32_t *row_begin, const int32_t *row_count, int batch, int max_rows,
                        float *vnorm, hipStream_t st);

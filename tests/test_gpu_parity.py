@@ -1016,3 +1016,97 @@ def test_sweep_hash_then_score(L, P):
             assert np.max(np.abs(got_s[b, h][live] - want_s[live]) / want_s[live]) <= 1e-5
             assert np.isneginf(got_s[b, h][~live]).all()
     ctx.close()
+
+
+# ------------------------------------------------------------------ Alg. 2 read-back, the binned pair, reset
+
+@pytest.mark.parametrize("L,P,G,kv_dtype", [(64, 8, 4, wl.BF16),      # one entry per bucket ("direct")
+                                            (24, 5, 1, wl.F32),        # fewer than 64 tables: replicated columns
+                                            (60, 10, 2, wl.BF16),      # groups of 32 tables ("split")
+                                            (40, 12, 2, wl.BF16),      # two factors per query head ("factor")
+                                            (130, 6, 8, wl.BF16)])     # more than 64 tables, a full group of 8
+def test_bucket_probs_match_oracle_entry_by_entry(L, P, G, kv_dtype):
+    """Alg. 2: every one of the L * 2^P bucket probabilities the context holds after
+    socket_soft_hash, read back with socket_bucket_probs, against the oracle's R-way softmax
+    (mean over the G queries of the group) - also the buckets no key of a test ever lands in.
+    Two sequences, so the batched projection kernel runs; one sequence again for the other."""
+    _need_gpu()
+    for B in (2, 1):
+        Hkv = 2
+        layer = small_layer(seed=131, B=B, Hq=Hkv * G, Hkv=Hkv, n=64, L=L, P=P, k=8, kv_dtype=kv_dtype)
+        ctx = hz.make_ctx(layer)
+        qd, Wd = hz.dev(layer.q, layer.kv_dtype), hz.dev(layer.W, layer.kv_dtype)
+        probs = torch.full((B, Hkv, L, 1 << P), -1.0, dtype=torch.float32, device="cuda")
+        for tau in (0.5, float(np.float32(0.05))):           # tau crosses the C ABI as a float: use a float's value
+            ctx.soft_hash(qd, Wd, tau, B)
+            ctx.bucket_probs(B, probs)
+            torch.cuda.synchronize()
+            got = probs.cpu().numpy().astype(np.float64)
+            for b in range(B):
+                for h in range(Hkv):
+                    want = hz.oracle_probs(layer, b, h, tau=tau).mean(axis=0)          # [L, R]
+                    # fp64 product of sigmoids rounded to fp32 (factor form: two fp32 factors)
+                    assert np.abs(got[b, h] - want).max() <= 3e-7 * want.max(), (B, tau, b, h)
+                    assert np.all(np.abs(got[b, h] - want) <= 3e-7 * want + 1e-37)
+                    assert np.abs(got[b, h].sum(axis=1) - 1.0).max() <= 1e-5
+        # the hard scorer's tables: 1/G at each query's own bucket
+        ctx.hard_hash(qd, Wd, B)
+        ctx.bucket_probs(B, probs)
+        torch.cuda.synchronize()
+        got = probs.cpu().numpy()
+        for b in range(B):
+            for h in range(Hkv):
+                want = np.zeros((L, 1 << P))
+                for g in range(G):
+                    qc, near = oracle.hash_keys(layer.q[b, h * G + g][None], layer.W[h], L, P)
+                    if near.any():
+                        want = None
+                        break
+                    want[np.arange(L), qc[0]] += 1.0 / G
+                if want is not None:
+                    assert np.abs(got[b, h] - want).max() <= 1e-6
+        ctx.close()
+
+
+def test_binned_score_and_select_pair_equals_the_plain_calls():
+    """socket_score_keys_binned + socket_topk_select_binned (the scoring pass also leaves the
+    histogram the select starts from) give bit for bit what socket_score_keys +
+    socket_topk_select give; with value norms the pair falls back to leading-digit bins.  A
+    select without its scoring pass is refused; socket_reset clears a pass left dangling."""
+    _need_gpu()
+    B, Hkv, G, L, P, n = 2, 2, 4, 64, 8, 9000 + 8
+    layer = small_layer(seed=133, B=B, Hq=Hkv * G, Hkv=Hkv, n=n, L=L, P=P, k=[300, 77], seq_len=[9000, 4321])
+    ctx = hz.make_ctx(layer)
+    codes = run_hash(ctx, layer, np.zeros(B), layer.seq_len, n)
+    qd, Wd = hz.dev(layer.q, layer.kv_dtype), hz.dev(layer.W, layer.kv_dtype)
+    ln, kk = hz.i32(layer.seq_len), hz.i32(layer.k)
+    rng = np.random.default_rng(134)
+    vn = torch.from_numpy(np.exp(rng.standard_normal((B, Hkv, n))).astype(np.float32)).cuda()
+
+    def buffers():
+        return (torch.zeros((B, Hkv, n), dtype=torch.float32, device="cuda"),
+                torch.zeros((B, Hkv, 300), dtype=torch.int32, device="cuda"),
+                torch.zeros((B, Hkv), dtype=torch.int32, device="cuda"))
+    for weights in (None, vn):
+        s1, i1, c1 = buffers()
+        s2, i2, c2 = buffers()
+        ctx.soft_hash(qd, Wd, 0.5, B)
+        ctx.score_keys(codes, ln, B, s1, vnorm=weights)
+        ctx.topk_select(s1, ln, kk, B, i1, c1)
+        for rep in range(2):                                   # twice: the pair leaves the scratch clean
+            ctx.score_keys_binned(codes, ln, B, s2, vnorm=weights)
+            ctx.topk_select_binned(s2, ln, kk, B, i2, c2)
+            torch.cuda.synchronize()
+            assert torch.equal(s1, s2) and torch.equal(i1, i2) and torch.equal(c1, c2)
+    with pytest.raises(sk.SocketError):
+        ctx.topk_select_binned(s2, ln, kk, B, i2, c2)          # nothing pending
+    ctx.score_keys_binned(codes, ln, B, s2)                    # left dangling ...
+    ctx.reset()                                                # ... and cleared
+    with pytest.raises(sk.SocketError):
+        ctx.topk_select_binned(s2, ln, kk, B, i2, c2)
+    s3, i3, c3 = buffers()
+    ctx.score_keys(codes, ln, B, s3, vnorm=vn)
+    ctx.topk_select(s3, ln, kk, B, i3, c3)
+    torch.cuda.synchronize()
+    assert torch.equal(i3, i1) and torch.equal(c3, c1)
+    ctx.close()

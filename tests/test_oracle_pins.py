@@ -420,3 +420,53 @@ def test_pins_catch_bit_order_mismatch():
     rev = np.array([[int(format(int(c), f"0{P}b")[::-1], 2) for c in qcode[0]]])
     assert (p.argmax(axis=1) == qcode[0]).all()
     assert not (p.argmax(axis=1) == rev[0]).all()
+
+
+# ------------------------------------------------------------------ ranking metrics (appendix)
+
+def _golden(name):
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "ranking_metrics_worked.txt")
+    for line in open(path):
+        if line.startswith(name + " "):
+            return float(line.split()[1])
+    raise KeyError(name)
+
+
+def test_ranking_metrics_hand_worked_cases():
+    """Appendix, metric definitions: values worked by hand (tests/golden/ranking_metrics_worked.txt)."""
+    ranked = [3, 2, 3, 0, 1, 2]
+    assert abs(oracle.ndcg(ranked, ranked) - _golden("ndcg_same_items")) < 5e-7
+    assert abs(oracle.ndcg(ranked, ranked + [3, 2]) - _golden("ndcg_two_missed")) < 5e-7
+    assert oracle.precision([1, 2, 3, 4], [2, 4, 6]) == _golden("precision")
+    assert abs(oracle.jaccard([1, 2, 3, 4], [2, 4, 6]) - _golden("jaccard")) < 1e-15
+
+
+def test_ranking_metrics_properties():
+    """What the definitions fix for any input: a perfectly ranked list has NDCG 1 and any
+    other order of the same items has less; NDCG does not depend on the order of the
+    candidate array; identical sets have Jaccard 1 and precision 1, disjoint sets 0; Jaccard
+    is symmetric; precision and Jaccard of two k-sets with c common items are c/k and
+    c/(2k - c); and both agree with Python's set arithmetic on random sets."""
+    rng = _rng(77)
+    rel = rng.uniform(0.0, 4.0, size=40)
+    order = np.argsort(-rel, kind="stable")
+    k = 12
+    assert abs(oracle.ndcg(rel[order[:k]], rel) - 1.0) < 1e-15
+    swapped = order[:k].copy()
+    swapped[[0, k - 1]] = swapped[[k - 1, 0]]
+    assert oracle.ndcg(rel[swapped], rel) < 1.0 - 1e-6
+    assert oracle.ndcg(rel[swapped], rel) == oracle.ndcg(rel[swapped], rel[rng.permutation(40)])
+    worse = order[5:5 + k]                               # misses the five best items
+    assert oracle.ndcg(rel[worse], rel) < oracle.ndcg(rel[swapped], rel)
+    a = rng.choice(1000, size=50, replace=False)
+    assert oracle.jaccard(a, a) == 1.0 and oracle.precision(a, a) == 1.0
+    assert oracle.jaccard(a, a + 1000) == 0.0 and oracle.precision(a, a + 1000) == 0.0
+    for _ in range(5):
+        x = rng.choice(300, size=60, replace=False)
+        y = rng.choice(300, size=60, replace=False)
+        c = len(set(x.tolist()) & set(y.tolist()))
+        assert oracle.precision(x, y) == c / 60
+        assert abs(oracle.jaccard(x, y) - c / (120 - c)) < 1e-15
+        assert oracle.jaccard(x, y) == oracle.jaccard(y, x)
+        z = rng.choice(300, size=25, replace=False)      # sets of different sizes
+        assert abs(oracle.jaccard(x, z) - len(set(x.tolist()) & set(z.tolist())) / len(set(x.tolist()) | set(z.tolist()))) < 1e-15
