@@ -232,3 +232,65 @@ def device_layer(seed: int, Hq: int, Hkv: int, d: int, n: int, n_alloc: int, L: 
         V[0, h] = torch.randn((n_alloc, d), generator=gen, device=device).to(torch.bfloat16)
     W = torch.randn((Hkv, d, L * P), generator=gen, device=device).to(torch.bfloat16)
     return K, V, q.to(torch.bfloat16), W
+
+
+def device_batch(seed: int, B: int, Hq: int, Hkv: int, d: int, n: int, n_alloc: int,
+                 channel_sigma: float = 0.5, planted_frac: float = 0.01, plant_coef: float = 0.7,
+                 device: str = "cuda"):
+    """make_layer's recipe for B sequences of n tokens in contiguous caches, drawn on the GPU:
+    K, V [B, Hkv, n_alloc, d] bf16 (rows [n, n_alloc) filled too: the rows decode steps append),
+    q [B, Hq, d] bf16.  No projection: the caller draws the hyperplanes it wants."""
+    import torch
+    G = Hq // Hkv
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    q = torch.randn((B, Hq, d), generator=gen, device=device, dtype=torch.float32)
+    scale = torch.exp(channel_sigma * torch.randn((Hkv, 1, d), generator=gen, device=device))
+    K = torch.empty((B, Hkv, n_alloc, d), device=device, dtype=torch.bfloat16)
+    V = torch.empty((B, Hkv, n_alloc, d), device=device, dtype=torch.bfloat16)
+    cnt = int(round(planted_frac * n))
+    noise_w = float(np.sqrt(max(0.0, 1.0 - plant_coef * plant_coef)))
+    for b in range(B):
+        for h in range(Hkv):
+            k = torch.randn((n_alloc, d), generator=gen, device=device) * scale[h]
+            if cnt:
+                pos = torch.randperm(n, generator=gen, device=device)[:cnt]
+                g = torch.randint(0, G, (cnt,), generator=gen, device=device)
+                k[pos] = plant_coef * q[b, h * G + g] + noise_w * torch.randn((cnt, d), generator=gen, device=device)
+            K[b, h] = k.to(torch.bfloat16)
+            V[b, h] = torch.randn((n_alloc, d), generator=gen, device=device).to(torch.bfloat16)
+    return K, V, q.to(torch.bfloat16)
+
+
+def device_paged_layer(seed: int, B: int, Hq: int, Hkv: int, d: int, lens, cap: int, page: int,
+                       block_table: np.ndarray, num_blocks: int, L: int, P: int, n_steps: int,
+                       channel_sigma: float = 0.5, planted_frac: float = 0.01, plant_coef: float = 0.7,
+                       device: str = "cuda"):
+    """make_layer's recipe for B sequences of lens[b] tokens, written into paged pools through
+    `block_table`: K, V [num_blocks, Hkv, page, d] bf16 (every sequence's rows up to `cap` are
+    filled: those beyond lens[b] are what decode steps append), queries for n_steps decode
+    steps [n_steps, B, Hq, d] bf16 (the planted keys lean on step 0's queries), W [Hkv, d, L*P]."""
+    import torch
+    G = Hq // Hkv
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    qs = torch.randn((n_steps, B, Hq, d), generator=gen, device=device, dtype=torch.float32)
+    scale = torch.exp(channel_sigma * torch.randn((Hkv, 1, d), generator=gen, device=device))
+    K = torch.zeros((num_blocks, Hkv, page, d), device=device, dtype=torch.bfloat16)
+    V = torch.zeros((num_blocks, Hkv, page, d), device=device, dtype=torch.bfloat16)
+    noise_w = float(np.sqrt(max(0.0, 1.0 - plant_coef * plant_coef)))
+    nb = cap // page
+    for b in range(B):
+        blocks = torch.from_numpy(np.ascontiguousarray(block_table[b, :nb]).astype(np.int64)).to(device)
+        n = int(lens[b])
+        cnt = int(round(planted_frac * n))
+        for h in range(Hkv):
+            k = torch.randn((cap, d), generator=gen, device=device) * scale[h]
+            if cnt:
+                pos = torch.randperm(n, generator=gen, device=device)[:cnt]
+                g = torch.randint(0, G, (cnt,), generator=gen, device=device)
+                k[pos] = plant_coef * qs[0, b, h * G + g] + noise_w * torch.randn((cnt, d), generator=gen, device=device)
+            K[blocks, h] = k.to(torch.bfloat16).view(nb, page, d)
+            V[blocks, h] = torch.randn((cap, d), generator=gen, device=device).to(torch.bfloat16).view(nb, page, d)
+    W = torch.randn((Hkv, d, L * P), generator=gen, device=device).to(torch.bfloat16)
+    return K, V, qs.to(torch.bfloat16), W
