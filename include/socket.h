@@ -177,15 +177,6 @@ int socket_value_norms(socket_ctx *ctx, const void *V, const int32_t *block_tabl
 int socket_set_forced_tokens(socket_ctx *ctx, int32_t n_sink, int32_t n_window);
 
 /*
- * Bit-repeatable fused decode step (Eq. 2 fixes the attention output as a sum; the order of
- * that sum is this library's choice).  on != 0: socket_decode_step orders the selection
- * before it attends, in six kernels, and out is bit-identical to the separate calls and the
- * same on every run.  0, the state after socket_create: see socket_decode_step.
- * Host-side state: it takes effect for calls issued (or captured) after it returns.
- */
-int socket_set_deterministic(socket_ctx *ctx, int32_t on);
-
-/*
  * Alg. 2 + Alg. 5 (SoftBucketProbs, SoftHashCollisionScores; Eq. 3, soft score).
  * Soft-hashes each query into its L x R bucket probabilities
  * (u = tanh(W q)/sqrt(d), softmax of u.c_r/tau over the R corners; evaluated in
@@ -326,12 +317,13 @@ int socket_dense_decode(socket_ctx *ctx, const void *q, const void *K, const voi
  *     socket_sparse_decode                               (Eq. 2)
  * in five kernels instead of nine: the appended key's hash shares a launch with the queries'
  * soft hash, the scoring pass also produces the histogram that the selection starts from, the
- * attention starts from the selection's unordered lists, and the index row is put in order
- * beside the merge of the attention's splits.  codes, scores, idx and n_selected are
- * bit-identical to the separate calls; out is the same sum taken over the same tokens, but
- * which split a token falls in follows the order in which the selection's workgroups
- * reserved list space, so its last bits can differ from the separate calls and from run to
- * run (see socket_set_deterministic).  With value norms the caller updates vnorm for the
+ * attention starts from the lists the selection's sweep leaves (one region per workgroup of the
+ * sweep, in position order), and the index row is put in order beside the merge of the
+ * attention's splits.  codes, scores, idx and n_selected are bit-identical to the separate calls;
+ * out is the same sum over the same tokens, cut into splits by position ranges of the sequence
+ * instead of by ranges of the index row, so it agrees with the separate calls to rounding - and
+ * with itself bit for bit: what a split sums, and in which order, depends on the scores alone
+ * (Eq. 2 fixes the sum, not its order).  With value norms the caller updates vnorm for the
  * appended row first (socket_value_norms with max_rows = 1).
  * pos, k: device int32 [batch].
  */

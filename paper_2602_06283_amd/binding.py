@@ -54,7 +54,6 @@ def lib():
         L.socket_hash_keys.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, vp, vp]
         L.socket_value_norms.argtypes = [vp, vp, vp, vp, vp, i32, i32, vp, vp]
         L.socket_set_forced_tokens.argtypes = [vp, i32, i32]
-        L.socket_set_deterministic.argtypes = [vp, i32]
         L.socket_score.argtypes = [vp, vp, vp, vp, f32, vp, vp, vp, i32, vp, vp]
         L.socket_soft_hash.argtypes = [vp, vp, vp, f32, i32, vp]
         L.socket_hard_hash.argtypes = [vp, vp, vp, i32, vp]
@@ -85,7 +84,7 @@ def lib():
 EXPORTS = ("socket_validate_params", "socket_codes_per_token", "socket_code_position",
            "socket_codes_bytes", "socket_code_location",
            "socket_create", "socket_destroy", "socket_scratch_bytes", "socket_hash_keys",
-           "socket_value_norms", "socket_set_forced_tokens", "socket_set_deterministic",
+           "socket_value_norms", "socket_set_forced_tokens",
            "socket_score", "socket_soft_hash", "socket_hard_hash", "socket_score_keys", "socket_score_keys_binned", "socket_topk_select", "socket_topk_select_binned", "socket_reset", "socket_bucket_probs", "socket_probe_stream_read", "socket_sparse_decode", "socket_sparse_decode_noalloc", "socket_dense_decode", "socket_decode_step", "socket_strerror",
            "socket_last_hip_error", "socket_graph_begin", "socket_graph_end",
            "socket_graph_launch", "socket_graph_destroy")
@@ -179,9 +178,6 @@ class Context:
         self._check(lib().socket_value_norms(self._h, _ptr(V), _ptr(block_table), _ptr(row_begin),
                                              _ptr(row_count), batch, max_rows, _ptr(vnorm),
                                              _stream(stream)), "socket_value_norms")
-
-    def set_deterministic(self, on):
-        self._check(lib().socket_set_deterministic(self._h, int(bool(on))), "socket_set_deterministic")
 
     def set_forced_tokens(self, n_sink, n_window):
         self._check(lib().socket_set_forced_tokens(self._h, int(n_sink), int(n_window)),

@@ -79,6 +79,17 @@ int fill_geometry(const socket_params *p, Geometry *g) {
     // split-K of the sparse decode: about 64 selected rows per workgroup, at most 64 splits
     int ns = (p->max_k + kDecodeChunk - 1) / kDecodeChunk;
     g->n_split = ns < 1 ? 1 : (ns > 64 ? 64 : ns);
+    // The fused step's attention is cut by regions of the select's sweep (kSlice positions each):
+    // ssr workgroups share a region when a region is expected to hold more than ~40 selected
+    // tokens, rpg regions share a workgroup when there are more regions than splits.
+    g->n_regions = (p->max_n + kSlice - 1) / kSlice;
+    if (g->n_regions > kMaxRegions) return SOCKET_EUNSUPPORTED;
+    g->ssr = 1;
+    g->rpg = (g->n_regions + kMaxSplits - 1) / kMaxSplits;
+    while (g->rpg == 1 && g->n_regions * g->ssr * 2 <= kMaxSplits && g->ssr < 16 &&
+           (int64_t)p->max_k > (int64_t)40 * g->n_regions * g->ssr)
+        g->ssr *= 2;
+    g->n_split_sweep = g->rpg > 1 ? (g->n_regions + g->rpg - 1) / g->rpg : g->n_regions * g->ssr;
     return SOCKET_OK;
 }
 
@@ -170,9 +181,10 @@ int socket_create(socket_ctx **out, const socket_params *p) {
     const int64_t sz_cnt = BH * (kCounterStride + kThrStride) * 4;
     const int64_t sz_cand = BH * g.max_n * 4;
     const int64_t sz_staged = BH * g.max_k * 4;
+    const int64_t sz_regions = BH * g.n_regions * kSlice * 4, sz_selcnt = BH * g.n_regions * 4;
     const int64_t sz_seq = (int64_t)g.max_batch * 4;
-    const int64_t sz_part = (int64_t)g.max_batch * g.Hq * (g.n_split > kDenseSplits ? g.n_split : kDenseSplits) * (g.d + 2) * 4;
-    ctx->scratch_bytes = sz_wfrag + sz_tables + sz_tstats + sz_hist + sz_cnt + 2 * sz_cand + sz_staged + sz_part + sz_seq;
+    const int64_t sz_part = (int64_t)g.max_batch * g.Hq * kMaxSplits * (g.d + 2) * 4;
+    ctx->scratch_bytes = sz_wfrag + sz_tables + sz_tstats + sz_hist + sz_cnt + 2 * sz_cand + sz_staged + sz_regions + sz_selcnt + sz_part + sz_seq;
     bool ok = hipMalloc((void **)&ctx->tables, sz_tables) == hipSuccess &&
               hipMalloc((void **)&ctx->tstats, sz_tstats) == hipSuccess &&
               (!fast_hash || hipMalloc(&ctx->wfrag, sz_wfrag) == hipSuccess) &&
@@ -181,6 +193,8 @@ int socket_create(socket_ctx **out, const socket_params *p) {
               hipMalloc((void **)&ctx->cand_key, sz_cand) == hipSuccess &&
               hipMalloc((void **)&ctx->cand_idx, sz_cand) == hipSuccess &&
               hipMalloc((void **)&ctx->staged, sz_staged) == hipSuccess &&
+              hipMalloc((void **)&ctx->sel_regions, sz_regions) == hipSuccess &&
+              hipMalloc((void **)&ctx->sel_cnt, sz_selcnt) == hipSuccess &&
               hipMalloc((void **)&ctx->partials, sz_part) == hipSuccess &&
               hipMalloc((void **)&ctx->seq_scratch, sz_seq) == hipSuccess;
     // Histograms and counters must start at zero; the kernels that use them leave them
@@ -188,6 +202,7 @@ int socket_create(socket_ctx **out, const socket_params *p) {
     ok = ok && hipMemset(ctx->hist, 0, sz_hist) == hipSuccess &&
          hipMemset(ctx->tstats, 0, sz_tstats) == hipSuccess &&
          hipMemset(ctx->counters, 0, sz_cnt) == hipSuccess &&
+         hipMemset(ctx->sel_cnt, 0, sz_selcnt) == hipSuccess &&
          hipDeviceSynchronize() == hipSuccess;
     if (!ok) {
         (void)hipGetLastError();
@@ -200,7 +215,7 @@ int socket_create(socket_ctx **out, const socket_params *p) {
 
 int socket_destroy(socket_ctx *ctx) {
     if (!ctx) return SOCKET_EINVAL;
-    void *bufs[] = {ctx->tables, ctx->tstats, ctx->wfrag, ctx->hist, ctx->counters, ctx->cand_key, ctx->cand_idx, ctx->staged, ctx->partials, ctx->seq_scratch};
+    void *bufs[] = {ctx->tables, ctx->tstats, ctx->wfrag, ctx->hist, ctx->counters, ctx->cand_key, ctx->cand_idx, ctx->staged, ctx->sel_regions, ctx->sel_cnt, ctx->partials, ctx->seq_scratch};
     for (void *b : bufs)
         if (b) (void)hipFree(b);
     delete ctx;
@@ -243,12 +258,6 @@ int socket_set_forced_tokens(socket_ctx *ctx, int32_t n_sink, int32_t n_window) 
     if (!ctx || n_sink < 0 || n_window < 0) return SOCKET_EINVAL;
     ctx->n_sink = n_sink;
     ctx->n_window = n_window;
-    return SOCKET_OK;
-}
-
-int socket_set_deterministic(socket_ctx *ctx, int32_t on) {
-    if (!ctx) return SOCKET_EINVAL;
-    ctx->deterministic = on != 0;
     return SOCKET_OK;
 }
 
@@ -362,13 +371,7 @@ int socket_decode_step(socket_ctx *ctx, const void *q, const void *K, const void
     rc = launch_score_keys(ctx, codes, vnorm, block_table, len, batch, scores, true, &hist_mode, st);
     if (rc != SOCKET_OK) return rc;
     // 3. select, 4. attend
-    if (ctx->deterministic) {
-        rc = launch_topk(ctx, scores, len, k, batch, idx, n_selected, hist_mode, st);
-        if (rc != SOCKET_OK) return rc;
-        return launch_sparse_decode(ctx, q, K, V, idx, n_selected, block_table, batch, scale, out_dtype,
-                                    out, st);
-    }
-    //    (the attention starts from the sweep's unordered lists; the index row is ordered beside the merge)
+    //    (the attention starts from the regions the sweep leaves; the index row is ordered beside the merge)
     rc = launch_topk_sweep(ctx, scores, len, k, batch, idx, n_selected, hist_mode, st);
     if (rc != SOCKET_OK) return rc;
     return launch_sweep_decode(ctx, q, K, V, scores, len, k, idx, n_selected, hist_mode, block_table,

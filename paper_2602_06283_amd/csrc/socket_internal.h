@@ -17,6 +17,11 @@ constexpr int kScoreU = 4;           // 16-byte loads a lane keeps in flight
 constexpr int kDecodeThreads = 256;
 constexpr int kDecodeChunk = 64;     // selected rows a decode workgroup handles per pass
 constexpr int kDenseSplits = 64;     // splits per (sequence, KV head) of the dense attention baseline
+constexpr int kMaxSplits = 128;      // most split-K partial results one merge takes
+constexpr int kTopkThreads = 512;
+constexpr int kPer = 8;              // scores per thread in a sweep of the select
+constexpr int kSlice = kTopkThreads * kPer;      // scores per workgroup of the sweep: one region of the selected list
+constexpr int kMaxRegions = 1024;    // regions per (sequence, KV head): max_n <= 4M tokens
 constexpr int kCounterStride = 16;   // uint32 counters per (sequence, KV head)
 constexpr int kThrStride = 16;       // uint32 words of the top-k threshold record per (sequence, KV head)
 constexpr int kThrBinLo = 8;         // words of the record that hold the adaptive binning (float bits): offset,
@@ -57,6 +62,9 @@ struct Geometry {
     int64_t table_words;  // floats per (sequence, KV head)
     int page, max_blocks, num_blocks, max_n, max_k, max_batch, kv_dtype;
     int n_split;     // split-K factor of sparse_decode
+    int n_regions;   // regions of the select's sweep per (sequence, KV head): ceil(max_n / kSlice)
+    int ssr, rpg;    // fused step: attention workgroups per region, or regions per attention workgroup
+    int n_split_sweep;   // split-K factor of the fused step's attention: n_regions * ssr / rpg
 };
 
 }  // namespace sk
@@ -68,7 +76,6 @@ struct socket_ctx {
     int last_hip_error;
     int64_t scratch_bytes;
     int n_sink, n_window; // tokens at either end of a sequence that scoring forces into the selection
-    int deterministic;    // the fused decode step orders the selection before it attends (bit-repeatable output)
     float *tables;        // [max_batch*Hkv][table_words]
     float *tstats;        // [max_batch*Hkv][Lpad][3] spread of each table's bucket probabilities, sampled value norms
     const float *vnorm_sampled;   // the value-norm array the last projection pass sampled (or null)
@@ -78,7 +85,9 @@ struct socket_ctx {
     uint32_t *counters;   // [max_batch*Hkv][kCounterStride] counters, then [max_batch*Hkv][kThrStride] records
     uint32_t *cand_key;   // [max_batch*Hkv][max_n]
     int32_t *cand_idx;    // [max_batch*Hkv][max_n]
-    int32_t *staged;      // [max_batch*Hkv][max_k] selected positions before ordering
+    int32_t *staged;      // [max_batch*Hkv][max_k] candidates picked by the long-list refinement
+    int32_t *sel_regions; // [max_batch*Hkv][n_regions][kSlice] positions selected outright, by region of the sweep
+    uint32_t *sel_cnt;    // [max_batch*Hkv][n_regions] how many each region holds
     float *partials;      // [max_batch*Hq][n_split][d+2]
     int32_t *seq_scratch; // [max_batch] lengths after the append of a fused decode step
 };

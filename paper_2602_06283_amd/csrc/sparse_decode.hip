@@ -6,16 +6,17 @@
 // Logits use no 1/sqrt(d) unless the caller passes one as `scale`; with unit-variance data
 // they reach +-100, so everything is max-subtracted.
 //
-// A split owns a fixed range of slots of the selection.  Given the ordered index row, slot r
-// is entry r of that row.  The fused decode step can also start from the unordered lists the
-// select's sweep leaves, without waiting for the ordered row: slot r below the number of
-// positions selected outright is entry r of that list, the slots after them go to the
-// candidates of the threshold bin that make the cut, best first (the workgroups that own such
-// slots rank the few candidates themselves).  The same tokens either way; which split a token
-// lands in then depends on the order in which the sweep's workgroups reserved their list
-// space, so the last bits of the output can differ from run to run.  The ordering of the
-// index row for the caller (topk_resolve_body) then runs beside the merge of the splits, as
-// extra workgroups of that launch.
+// Given the ordered index row, a split owns a fixed range of its slots.  The fused decode step
+// can also start from what the select's sweep leaves, without waiting for the ordered row: the
+// positions selected outright lie in one region per workgroup of the sweep (kSlice positions of
+// the sequence each, in position order), and a split owns a region (or an interleaved share of
+// one, or a few regions), plus those candidates of the threshold bin that make the cut and whose
+// position falls in its regions (every split ranks the few candidates itself).  Which tokens a
+// split sums, and in which order, then depends on the scores alone: the output is the same bit
+// for bit on every run.  The splits also write the ordered index row for the caller, each its
+// own entries: the regions one after the other already are the positions selected outright in
+// ascending order, so an entry's slot is the number of entries before it plus the number of kept
+// candidates below it, and a kept candidate's slot the same two counts for its position.
 #include <mutex>
 
 #include "topk_device.h"
@@ -46,7 +47,10 @@ struct DecodeArgs {
     int Hq, max_k, n_split, out_dtype;
     const int32_t *seq_len;   // dense variant only
     // kRowsSweep: the lists and the threshold record of the select's sweep
-    const int32_t *staged;
+    const int32_t *sel_regions;
+    const uint32_t *sel_cnt;
+    int n_regions, ssr, rpg;
+    int emit_idx;             // the splits write the ordered index row (a.idx) themselves
     const uint32_t *cand_key;
     const int32_t *cand_idx;
     const uint32_t *thr;
@@ -59,6 +63,10 @@ __device__ __forceinline__ float2 pair_f32(const uint16_t *p) {
 }
 __device__ __forceinline__ float2 pair_f32(const float *p) { return *(const float2 *)p; }
 
+// dynamic LDS of decode_body<kRowsSweep> while it ranks candidates: their keys (and a quad of
+// padding), then the (rank, position) pairs of its own
+constexpr size_t kSweepRankLds = (size_t)(2 * kSweepCand + 4) * 8;
+
 // dynamic LDS of decode_body: the value tile
 template <typename T, int D> constexpr size_t decode_lds_bytes() {
     constexpr int ROWB = D * (int)sizeof(T);
@@ -66,15 +74,16 @@ template <typename T, int D> constexpr size_t decode_lds_bytes() {
     return (size_t)VROWS * ROWB;
 }
 
-// One split of one (sequence, KV head), run by the first kDecodeThreads threads of a workgroup.
-// SRC says where the rows come from (RowSource).  `dyn` is decode_lds_bytes() of LDS.  Returns
+// One split of one (sequence, KV head), run by a whole workgroup of NT threads.
+// SRC says where the rows come from (RowSource).  `dyn` is decode_lds_bytes() of LDS (kRowsSweep:
+// at least kSweepRankLds).  Returns
 // true when nothing was done: kRowsSweep with more candidates than a workgroup ranks.
-template <typename T, int D, int G, int SRC>
+template <typename T, int D, int G, int SRC, int NT = kDecodeThreads>
 __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int h, int b, char *dyn) {
     constexpr bool DENSE = SRC == kRowsDense;
     constexpr int LPR = D / 8;                       // lanes per row
     constexpr int RPW = 64 / LPR;                    // rows per wavefront pass
-    constexpr int NWAVE = kDecodeThreads / 64;
+    constexpr int NWAVE = NT / 64;
     constexpr int RPP = NWAVE * RPW;                 // rows per workgroup pass
     constexpr int CH = kDecodeChunk;
     constexpr int NPASS = CH / RPP;
@@ -87,13 +96,20 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
     constexpr int VROUNDS = CH / VROWS, PPR = VROWS / RPP;      // passes per round
     static_assert(VROWS % RPP == 0 && VROWS % 4 == 0, "a round is whole passes");
     constexpr int CPAIRS = D / 2;                    // channel pairs
-    constexpr int NG = kDecodeThreads / CPAIRS;      // thread groups, each covering all channels
+    constexpr int NG = NT / CPAIRS;      // thread groups, each covering all channels
     constexpr int GPG = (G + NG - 1) / NG;           // query heads per group
 
     __shared__ __align__(16) float s_p[G][CH];       // logits, then softmax numerators
     __shared__ int64_t s_row[CH];                    // K/V row of each chunk entry (-1 = none)
     __shared__ float s_m[G], s_l[G], s_corr[G];
     __shared__ int32_t s_cpos[SRC == kRowsSweep ? kSweepCand : 1];   // candidates that make the cut, best first
+    // kRowsSweep, for the index row: every kept candidate's position (any order, padded with
+    // INT_MAX to whole quads), the head of the first region, the entry counts of the regions before it
+    constexpr int kHeadEntries = SRC == kRowsSweep ? NT : 1;
+    __shared__ __align__(16) int32_t s_kept[SRC == kRowsSweep ? kSweepCand : 4];
+    __shared__ int32_t s_head[kHeadEntries];
+    __shared__ float s_pre[NWAVE];
+    __shared__ int s_nkept;
     T (*s_v)[D] = (T (*)[D])dyn;                     // [VROWS][D]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -118,28 +134,47 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
     int32_t first = -1;                              // the list entry of slot r_begin + tid
     uint32_t pk[kCandPer];
     int32_t pp[kCandPer];
-    int count = 0, above = 0, need = 0, n_cand = 0;  // list entries that count; kRowsSweep: see below
-    if (!DENSE) {
-        list = (SRC == kRowsSweep ? a.staged : a.idx) + (int64_t)bh * a.max_k;
+    int count = 0, need = 0, n_cand = 0;             // list entries that count; kRowsSweep: see below
+    // kRowsSweep: this split's regions [reg0, reg1) of the sweep, and of a shared region the
+    // entries sub_i, sub_i + sub_n, ...
+    int reg0 = 0, reg1 = 0, sub_i = 0, sub_n = 1;
+    uint32_t cnt_before = 0;                         // entries of region `tid`, if that lies before this split's
+    int32_t head = 0;                                // entry `tid` of this split's region
+    if (SRC == kRowsIdx) {
+        list = a.idx + (int64_t)bh * a.max_k;
         if (tid < CH && r_begin + tid < r_end) first = list[r_begin + tid];
+        count = a.n_selected[bh];
     }
     if (SRC == kRowsSweep) {
+        if (a.rpg > 1) {
+            reg0 = split * a.rpg;
+            reg1 = min(a.n_regions, reg0 + a.rpg);
+        } else {
+            reg0 = split / a.ssr;
+            reg1 = reg0 + 1;
+            sub_i = split - reg0 * a.ssr;
+            sub_n = a.ssr;
+        }
+        list = a.sel_regions + (int64_t)bh * a.n_regions * kSlice;
+        if (tid < CH) first = list[(int64_t)reg0 * kSlice + sub_i + tid * sub_n];   // (inside the region's kSlice words)
+        count = (int)a.sel_cnt[(int64_t)bh * a.n_regions + reg0];
+        if (a.emit_idx) {
+            cnt_before = tid < reg0 ? a.sel_cnt[(int64_t)bh * a.n_regions + tid] : 0u;
+            if (sub_i == 0) head = list[(int64_t)reg0 * kSlice + tid];   // (inside the region's kSlice words)
+        }
 #pragma unroll
         for (int j = 0; j < kCandPer; ++j) {
-            const int i = tid + j * kDecodeThreads;
+            const int i = tid + j * NT;
             pk[j] = i < a.map.max_n ? a.cand_key[(int64_t)bh * a.map.max_n + i] : 0u;
             pp[j] = i < a.map.max_n ? a.cand_idx[(int64_t)bh * a.map.max_n + i] : 0;
         }
-        // slots [0, above): positions selected outright; [above, k_eff): the `need` best candidates
+        // the selection: every position of the regions, and the `need` best candidates of the threshold bin
         const uint32_t *thr = a.thr + (int64_t)bh * kThrStride;
         const int k_eff = min((int)thr[0], a.max_k);
-        above = k_eff ? min((int)thr[5], k_eff) : 0;
+        const int above = k_eff ? min((int)thr[5], k_eff) : 0;
         n_cand = k_eff ? (int)thr[6] : 0;
         need = k_eff - above;
-        count = above;
-        r_end = min(r_end, k_eff);
-    } else if (SRC == kRowsIdx) {
-        count = a.n_selected[bh];
+        if (k_eff == 0) count = 0;
     }
     // too many candidates to rank here: the caller attends the head from the ordered row instead
     if (SRC == kRowsSweep && n_cand > kSweepCand) return true;
@@ -155,28 +190,95 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
         s_l[tid] = 0.0f;
     }
 
-    // ---- kRowsSweep, splits that own candidate slots: the `need` best candidates on (score,
-    //      then smaller position), by all-pairs ranking
-    if (SRC == kRowsSweep && need > 0 && r_end > above) {
+    // ---- kRowsSweep: of the `need` best candidates on (score, then smaller position) those whose
+    //      position lies in this split's regions (and, of a shared region, the share of the
+    //      split that the position's parity-like residue picks), best first
+    __shared__ int s_nmine;
+    const bool emit = SRC == kRowsSweep && a.emit_idx;
+    if (SRC == kRowsSweep) {
         unsigned long long *ck = (unsigned long long *)dyn;       // the value tile is not in use yet
+        unsigned long long *mine = ck + kSweepCand + 4;           // (rank, position) of this split's candidates
+        if (tid == 0) {
+            s_nmine = 0;
+            s_nkept = 0;
+        }
+        if (emit) {
+            for (int i = tid; i < kSweepCand; i += NT) s_kept[i] = 0x7fffffff;
+            s_head[tid] = head;
+            const float wsum = row_sum<64>((float)cnt_before);   // (exact: fewer than 2^24 entries)
+            if (lane == 0) s_pre[wave] = wsum;
+        }
+        if (need > 0) {
 #pragma unroll
-        for (int j = 0; j < kCandPer; ++j) {
-            const int i = tid + j * kDecodeThreads;
-            if (i < n_cand) ck[i] = ((unsigned long long)pk[j] << 32) | (0x7fffffffu - (uint32_t)pp[j]);
+            for (int j = 0; j < kCandPer; ++j) {
+                const int i = tid + j * NT;
+                if (i < n_cand) ck[i] = ((unsigned long long)pk[j] << 32) | (0x7fffffffu - (uint32_t)pp[j]);
+            }
+            if (tid < 4) ck[n_cand + tid] = 0;                    // (whole quads for the ranking loop; beats nobody)
         }
         __syncthreads();
+        if (need > 0) {
 #pragma unroll
-        for (int j = 0; j < kCandPer; ++j) {
-            const int i = tid + j * kDecodeThreads;
-            if (i < n_cand) {
-                const unsigned long long me = ck[i];
-                int rank = 0;
-                for (int o = 0; o < n_cand; ++o) rank += ck[o] > me;
-                if (rank < need) s_cpos[rank] = pp[j];
+            for (int j = 0; j < kCandPer; ++j) {
+                const int i = tid + j * NT;
+                const int reg = pp[j] / kSlice;
+                // a shared region's candidates all go to its first split, which holds the region's head
+                const bool here = i < n_cand && reg >= reg0 && reg < reg1 && sub_i == 0;
+                if (i < n_cand && (here || emit)) {
+                    const unsigned long long me = ck[i];
+                    int rank = 0;
+                    for (int o = 0; o < n_cand; o += 4) {
+                        const ulonglong2 c0 = *(const ulonglong2 *)&ck[o], c1 = *(const ulonglong2 *)&ck[o + 2];
+                        rank += (c0.x > me) + (c0.y > me) + (c1.x > me) + (c1.y > me);
+                    }
+                    if (rank < need) {
+                        if (here) mine[atomicAdd(&s_nmine, 1)] = ((unsigned long long)rank << 32) | (uint32_t)pp[j];
+                        if (emit) s_kept[atomicAdd(&s_nkept, 1)] = pp[j];
+                    }
+                }
             }
         }
+        __syncthreads();
+        const int nm = s_nmine;                                   // put in rank order: few, so all-pairs again
+        unsigned long long e[kCandPer];
+        int slot[kCandPer];
+#pragma unroll
+        for (int j = 0; j < kCandPer; ++j) {
+            const int i = tid + j * NT;
+            slot[j] = -1;
+            if (i < nm) {
+                e[j] = mine[i];
+                slot[j] = 0;
+                for (int o = 0; o < nm; ++o) slot[j] += mine[o] < e[j];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < kCandPer; ++j)
+            if (slot[j] >= 0) s_cpos[slot[j]] = (int32_t)(uint32_t)e[j];
     }
     __syncthreads();
+    const int n_mine = SRC == kRowsSweep ? s_nmine : 0;
+    // ---- the index row: entries before this split's region, kept candidates below a position
+    int32_t *idx_row = nullptr;
+    int entries_before = 0, n_kept = 0;
+    if (emit) {
+        idx_row = (int32_t *)a.idx + (int64_t)bh * a.max_k;
+        float sum = 0.0f;
+#pragma unroll
+        for (int w = 0; w < NWAVE; ++w) sum += s_pre[w];
+        entries_before = (int)sum;
+        n_kept = s_nkept;
+    }
+    auto kept_below = [&](int32_t p) __attribute__((always_inline)) {
+        int c = 0;
+        for (int q = 0; q < n_kept; q += 4) {
+            const int4 v = *(const int4 *)&s_kept[q];
+            c += (v.x < p) + (v.y < p) + (v.z < p) + (v.w < p);
+        }
+        return c;
+    };
+    int32_t pend_t = -1;                             // the list entry this thread has yet to write to the row
+    int pend_slot = 0;
 
     // one chunk of rows (s_row filled, or kr/vr/rows loaded for the dense source): logits,
     // running softmax statistics, weighted value rows
@@ -195,6 +297,28 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
                     kr[p].zero();
                     vr[p].zero();
                 }
+            }
+            if (SRC == kRowsSweep && pend_t >= 0) {  // (while the rows are on their way)
+                if (pend_slot < 0) {
+                    // a kept candidate: the entries of its region below it (a binary search, in the
+                    // region's head in LDS or past that in memory)
+                    int lo = 0, hi = min(count, kHeadEntries);   // first entry >= the position
+                    while (lo < hi) {
+                        const int mid = (lo + hi) >> 1;
+                        if (s_head[mid] < pend_t) lo = mid + 1; else hi = mid;
+                    }
+                    if (lo == kHeadEntries) {
+                        hi = count;
+                        while (lo < hi) {
+                            const int mid = (lo + hi) >> 1;
+                            if (list[(int64_t)reg0 * kSlice + mid] < pend_t) lo = mid + 1; else hi = mid;
+                        }
+                    }
+                    pend_slot = entries_before + lo;
+                }
+                const int at = pend_slot + kept_below(pend_t);
+                if (at < a.max_k) idx_row[at] = pend_t;
+                pend_t = -1;
             }
         }
         // ---- logits: scale * k.q for every query head of the group
@@ -318,21 +442,50 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
             }
         }
     } else {
-        // ---- this split's slots of the list
-        for (int c0 = r_begin; c0 < r_end; c0 += CH) {
-            if (tid < CH) {
-                const int r = c0 + tid;
-                int64_t row = -1;
-                if (r < r_end) {
-                    int t = -1;
-                    if (r < count) t = c0 == r_begin ? first : list[r];
-                    else if (SRC == kRowsSweep) t = s_cpos[r - above];
-                    if (t >= 0 && t < a.map.max_n) row = a.map.row(b, h, t);
+        if (SRC == kRowsIdx) {
+            // ---- this split's slots of the ordered row
+            for (int c0 = r_begin; c0 < r_end; c0 += CH) {
+                if (tid < CH) {
+                    const int r = c0 + tid;
+                    int64_t row = -1;
+                    if (r < r_end && r < count) {
+                        const int t = c0 == r_begin ? first : list[r];
+                        if (t >= 0 && t < a.map.max_n) row = a.map.row(b, h, t);
+                    }
+                    s_row[tid] = row;
                 }
-                s_row[tid] = row;
+                __syncthreads();
+                attend_chunk();
             }
-            __syncthreads();
-            attend_chunk();
+        } else {
+            // ---- this split's share of its regions, then its candidates
+            for (int reg = reg0; reg < reg1; ++reg) {
+                const int cnt = reg == reg0 ? count : (int)a.sel_cnt[(int64_t)bh * a.n_regions + reg];
+                const int n_here = cnt > sub_i ? (cnt - sub_i + sub_n - 1) / sub_n : 0;     // entries of this split in the region
+                const int n_rows = n_here + (reg == reg1 - 1 ? n_mine : 0);
+                for (int c0 = 0; c0 < n_rows; c0 += CH) {
+                    if (tid < CH) {
+                        const int r = c0 + tid;
+                        int t = -1;
+                        if (r < n_here) {
+                            t = (c0 == 0 && reg == reg0) ? first : list[(int64_t)reg * kSlice + sub_i + r * sub_n];
+                            if (emit) {
+                                pend_t = t;
+                                pend_slot = entries_before + sub_i + r * sub_n;
+                            }
+                        } else if (r < n_rows) {
+                            t = s_cpos[r - n_here];
+                            if (emit) {
+                                pend_t = t;
+                                pend_slot = -1;
+                            }
+                        }
+                        s_row[tid] = (t >= 0 && t < a.map.max_n) ? a.map.row(b, h, t) : -1;
+                    }
+                    __syncthreads();
+                    attend_chunk();
+                }
+            }
         }
     }
 
@@ -358,103 +511,129 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(DecodeArg
 }
 
 // Merge of the split-K partial results of one query head: out = sum_s w_s acc_s / sum_s w_s l_s
-// with w_s = exp(m_s - max m).  One thread per output channel (threads at or beyond D only
-// keep the barriers company); every load of a thread is issued before the first use, so the
-// merge costs one memory latency.  Runs in a launch after the partial pass: no fence, no
-// signalling.  `skip`: do everything but the store.
-template <int D>
-__device__ __forceinline__ void merge_body(const DecodeArgs &a, int g, int h, int b, bool skip) {
-    __shared__ float s_w[64];
+// with w_s = exp(m_s - max m).  NT threads: thread (channel c = tid % D, group sg = tid / D)
+// takes the splits sg, sg + NT/D, ... of channel c, every load issued before the first use (at
+// most 32 per thread: the hardware tracks 63 outstanding loads per wavefront, more would stall
+// the issue), then the groups' sums are added in a fixed order through LDS.  Runs in a launch
+// after the partial pass: no fence, no signalling.
+constexpr int kMergeThreads = 512;
+
+template <int D, int NT>
+__device__ __forceinline__ void merge_body(const DecodeArgs &a, int g, int h, int b) {
+    constexpr int NG = NT / D;                       // groups of D threads
+    constexpr int PER = kMaxSplits / NG;             // splits per thread
+    static_assert(NT % D == 0 && NG >= 2 && PER <= 64, "groups of D threads, at most 64 loads in flight each");
+    __shared__ float s_w[kMaxSplits];
     __shared__ float s_den;
-    const int c = threadIdx.x;
+    __shared__ float s_red[NG][D];
+    const int tid = threadIdx.x;
+    const int c = tid % D, sg = tid / D;
     const int G = a.Hq / a.map.Hkv;
     const int64_t head = (int64_t)b * a.Hq + h * G + g;
     const float *part = a.partials + head * a.n_split * (D + 2);
     const float ninf = -__builtin_inff();
-    // the first wavefront weighs the splits: its (max, sum) loads go out first, so that the
-    // weights are ready when the value sums arrive
-    const bool live = c < 64 && c < a.n_split;
-    const float m = live ? part[(int64_t)c * (D + 2)] : ninf;
-    const float l = live ? part[(int64_t)c * (D + 2) + 1] : 0.0f;
-    float acc[64];
+    // the first wavefront weighs the splits (two per lane): its (max, sum) loads go out first, so
+    // that the weights are ready when the value sums arrive
+    float m[2], l[2];
 #pragma unroll
-    for (int s = 0; s < 64; ++s) acc[s] = s < a.n_split && c < D ? part[(int64_t)s * (D + 2) + 2 + c] : 0.0f;
-    if (c < 64) {
-        const float top = wave_max(m);
-        const float w = (m == ninf) ? 0.0f : expf(m - top);
-        const float den = row_sum<64>(w * l);
-        s_w[c] = w;
-        if (c == 0) s_den = den;
+    for (int j = 0; j < 2; ++j) {
+        const bool live = tid < 64 && tid + 64 * j < a.n_split;
+        m[j] = live ? part[(int64_t)(tid + 64 * j) * (D + 2)] : ninf;
+        l[j] = live ? part[(int64_t)(tid + 64 * j) * (D + 2) + 1] : 0.0f;
+    }
+    float acc[PER];
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+        const int s = sg + j * NG;
+        acc[j] = s < a.n_split ? part[(int64_t)s * (D + 2) + 2 + c] : 0.0f;
+    }
+    if (tid < 64) {
+        const float top = wave_max(fmaxf(m[0], m[1]));
+        const float w0 = (m[0] == ninf) ? 0.0f : expf(m[0] - top), w1 = (m[1] == ninf) ? 0.0f : expf(m[1] - top);
+        const float den = row_sum<64>(w0 * l[0] + w1 * l[1]);
+        s_w[tid] = w0;
+        s_w[tid + 64] = w1;
+        if (tid == 0) s_den = den;
     }
     __syncthreads();
     float num = 0.0f;
 #pragma unroll
-    for (int s = 0; s < 64; ++s)
-        if (s < a.n_split) num = fmaf(s_w[s], acc[s], num);
-    const float den = s_den;
-    const float y = den > 0.0f ? num / den : 0.0f;
-    if (c < D && !skip) {
+    for (int j = 0; j < PER; ++j) {
+        const int s = sg + j * NG;
+        if (s < a.n_split) num = fmaf(s_w[s], acc[j], num);
+    }
+    s_red[sg][c] = num;
+    __syncthreads();
+    if (sg == 0) {
+        float total = s_red[0][c];
+#pragma unroll
+        for (int gg = 1; gg < NG; ++gg) total += s_red[gg][c];
+        const float den = s_den;
+        const float y = den > 0.0f ? total / den : 0.0f;
         if (a.out_dtype == SOCKET_F32) ((float *)a.out)[head * D + c] = y;
         else ((uint16_t *)a.out)[head * D + c] = f32_to_bf16_rne(y);
     }
-    __syncthreads();                                 // s_w may be rewritten by a following call
+    __syncthreads();                                 // the LDS arrays may be rewritten by a following call
 }
 
 template <int D>
-__global__ __launch_bounds__(D) void decode_merge_kernel(DecodeArgs a) {
-    merge_body<D>(a, blockIdx.x, blockIdx.y, blockIdx.z, false);
+__global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(DecodeArgs a) {
+    merge_body<D, kMergeThreads>(a, blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
-// The last launch of the fused decode step: the merge of the splits (workgroups 0 .. n_merge-1,
-// one per query head, the first D threads) beside the ordering of the index row (one workgroup
-// per (sequence, KV head), all kTopkThreads threads), which nothing on the way to the output
-// waits for.  A head whose threshold bin held more candidates than the decode workgroups rank
-// was left alone by them: its ordering workgroup then attends it from the ordered row, split
-// after split, and merges it too (mass ties only; slow and exact).
+// The launch after the attention of the fused decode step: the merge of the splits for every
+// query head, and one more workgroup per (sequence, KV head) that finishes the select: the -1
+// fill behind the index row, the selected count, the shared scratch cleared for the next call.
+// Where the attention's splits did not write the index row (they do unless a split owns several
+// regions) that workgroup orders it (topk_resolve_body); where they left a head alone, its
+// threshold bin holding more candidates than they rank (mass ties only), it orders the row,
+// attends the head from it split after split, and merges it: slow and exact.
 template <typename T, int D, int G>
-__global__ __launch_bounds__(kTopkThreads) void merge_resolve_kernel(DecodeArgs a, TopkArgs t, int n_merge) {
+__global__ __launch_bounds__(kTopkThreads) void merge_finish_kernel(DecodeArgs a, TopkArgs t) {
     extern __shared__ __align__(16) char decode_lds[];
-    const int id = blockIdx.x, tid = threadIdx.x;
-    if (id < n_merge) {
-        if (tid >= D) return;
-        const int g = id % G, hb = id / G, h = hb % a.map.Hkv, b = hb / a.map.Hkv;
-        const uint32_t *thr = t.thr + (int64_t)hb * kThrStride;
-        merge_body<D>(a, g, h, b, thr[0] != 0 && thr[6] > (uint32_t)kSweepCand);
+    const int h = blockIdx.y, b = blockIdx.z, bh = b * a.map.Hkv + h, tid = threadIdx.x;
+    const uint32_t *thr = t.thr + (int64_t)bh * kThrStride;
+    const uint32_t k_eff = thr[0];
+    const bool redo = k_eff != 0 && thr[6] > (uint32_t)kSweepCand;
+    if ((int)blockIdx.x < G) {
+        if (!redo) merge_body<D, kTopkThreads>(a, blockIdx.x, h, b);
         return;
     }
-    const int bh = id - n_merge, h = bh % a.map.Hkv, b = bh / a.map.Hkv;
-    const uint32_t *thr = t.thr + (int64_t)bh * kThrStride;
-    const bool redo = thr[0] != 0 && thr[6] > (uint32_t)kSweepCand;
+    if (a.emit_idx && !redo) {
+        int32_t *out = t.idx + (int64_t)bh * t.max_k;
+        for (int i = (int)min(k_eff, (uint32_t)t.max_k) + tid; i < t.max_k; i += kTopkThreads) out[i] = -1;
+        if (tid == 0) t.n_selected[bh] = (int32_t)k_eff;
+        uint32_t *gh1 = t.hist + (int64_t)bh * kHistBins, *gh2 = t.hist2 + (int64_t)bh * kHistBins;
+        for (int i = tid; i < kHistBins; i += kTopkThreads) {
+            gh1[i] = 0;
+            gh2[i] = 0;
+        }
+        if (tid < 2) t.counters[(int64_t)bh * kCounterStride + tid] = 0;
+        return;
+    }
     topk_resolve_body(t, bh, (uint32_t *)decode_lds);
     if (!redo) return;
     __threadfence();
     __syncthreads();                                 // the ordered row and its count are written
-    if (tid >= kDecodeThreads) return;
-    for (int s = 0; s < a.n_split; ++s) decode_body<T, D, G, kRowsIdx>(a, s, h, b, decode_lds);
+    // (every thread of the workgroup takes part: the bodies below are full of barriers)
+    for (int s = 0; s < a.n_split; ++s) decode_body<T, D, G, kRowsIdx, kTopkThreads>(a, s, h, b, decode_lds);
     __threadfence();
-    __syncthreads();                                 // and so are the head's partial results
-    for (int g = 0; g < G; ++g) merge_body<D>(a, g, h, b, false);
+    __syncthreads();
+    for (int g = 0; g < G; ++g) merge_body<D, kTopkThreads>(a, g, h, b);
 }
 
 // which launch launch_decode makes: a RowSource, or
-constexpr int kMergeResolve = -1;                    // merge_resolve_kernel
+constexpr int kMergeFinish = -1;                     // merge_finish_kernel
 
 template <typename T, int D, int G, int WHAT>
 static int launch_decode_one(const DecodeArgs &a, const TopkArgs *t, dim3 grid, hipStream_t st) {
-    if constexpr (WHAT == kMergeResolve) {
+    if constexpr (WHAT == kMergeFinish) {
         constexpr size_t kLds = decode_lds_bytes<T, D>() > kResolveLds ? decode_lds_bytes<T, D>() : kResolveLds;
-        static bool lds_raised = false;   // more than 64 KB of dynamic LDS has to be allowed once per process
-        if (!lds_raised) {
-            if (hipFuncSetAttribute((const void *)merge_resolve_kernel<T, D, G>,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds) != hipSuccess)
-                return SOCKET_EHIP;
-            lds_raised = true;
-        }
-        const int BH = (int)(grid.y * grid.z), n_merge = BH * G;
-        hipLaunchKernelGGL((merge_resolve_kernel<T, D, G>), dim3(n_merge + BH), dim3(kTopkThreads), kLds, st,
-                           a, *t, n_merge);
+        static_assert(kLds <= 64 * 1024, "within the default dynamic LDS limit");
+        hipLaunchKernelGGL((merge_finish_kernel<T, D, G>), dim3(G + 1, grid.y, grid.z), dim3(kTopkThreads), kLds, st, a, *t);
     } else {
-        constexpr size_t kLds = decode_lds_bytes<T, D>();
+        constexpr size_t kTile = decode_lds_bytes<T, D>();
+        constexpr size_t kLds = WHAT == kRowsSweep && kTile < kSweepRankLds ? kSweepRankLds : kTile;
         hipLaunchKernelGGL((sparse_decode_kernel<T, D, G, WHAT>), grid, dim3(kDecodeThreads), kLds, st, a);
     }
     return SOCKET_OK;
@@ -490,9 +669,9 @@ static int launch_decode(const DecodeArgs &a, const TopkArgs *t, const Geometry 
 static int launch_merge(const DecodeArgs &a, const Geometry &g, int batch, hipStream_t st) {
     dim3 mgrid(g.G, g.Hkv, batch);
     switch (g.d) {
-        case 64: hipLaunchKernelGGL(decode_merge_kernel<64>, mgrid, dim3(64), 0, st, a); break;
-        case 128: hipLaunchKernelGGL(decode_merge_kernel<128>, mgrid, dim3(128), 0, st, a); break;
-        case 256: hipLaunchKernelGGL(decode_merge_kernel<256>, mgrid, dim3(256), 0, st, a); break;
+        case 64: hipLaunchKernelGGL(decode_merge_kernel<64>, mgrid, dim3(kMergeThreads), 0, st, a); break;
+        case 128: hipLaunchKernelGGL(decode_merge_kernel<128>, mgrid, dim3(kMergeThreads), 0, st, a); break;
+        case 256: hipLaunchKernelGGL(decode_merge_kernel<256>, mgrid, dim3(kMergeThreads), 0, st, a); break;
         default: return SOCKET_EUNSUPPORTED;
     }
     return SOCKET_OK;
@@ -505,7 +684,8 @@ static DecodeArgs decode_args(const Geometry &g, float *partials, const void *q,
     a.partials = partials; a.out = out;
     a.map = row_map(g, block_table);
     a.scale = scale; a.Hq = g.Hq; a.max_k = g.max_k; a.n_split = n_split; a.out_dtype = out_dtype;
-    a.staged = nullptr; a.cand_key = nullptr; a.cand_idx = nullptr; a.thr = nullptr;
+    a.sel_regions = nullptr; a.sel_cnt = nullptr; a.n_regions = 0; a.ssr = 1; a.rpg = 1; a.emit_idx = 0;
+    a.cand_key = nullptr; a.cand_idx = nullptr; a.thr = nullptr;
     return a;
 }
 static DecodeArgs decode_args(socket_ctx *ctx, const void *q, const void *K, const void *V,
@@ -611,20 +791,23 @@ int sparse_decode_noalloc(const socket_params *p, const void *q, const void *K, 
 }
 
 // The tail of the fused decode step, after the select's sweep (launch_topk_sweep): Eq. 2 from
-// the sweep's lists, then the merge of the splits beside the ordering of the index row.
+// the sweep's lists, the splits writing the index row as they go, then the merge of the splits
+// with the select's finishing touches beside it.
 int launch_sweep_decode(socket_ctx *ctx, const void *q, const void *K, const void *V,
                         const float *scores, const int32_t *seq_len, const int32_t *k,
                         int32_t *idx, int32_t *n_selected, int hist_mode, const int32_t *block_table,
                         int batch, float scale, int out_dtype, void *out, hipStream_t st) {
     const Geometry &g = ctx->g;
     const TopkArgs t = topk_args(ctx, scores, seq_len, k, idx, n_selected, hist_mode);
-    DecodeArgs a = decode_args(ctx, q, K, V, block_table, scale, out_dtype, out, g.n_split);
+    DecodeArgs a = decode_args(ctx, q, K, V, block_table, scale, out_dtype, out, g.n_split_sweep);
     a.idx = idx; a.n_selected = n_selected;
-    a.staged = t.staged; a.cand_key = t.cand_key; a.cand_idx = t.cand_idx; a.thr = t.thr;
-    const dim3 grid(g.n_split, g.Hkv, batch);
+    a.sel_regions = t.sel_regions; a.sel_cnt = t.sel_cnt; a.n_regions = g.n_regions; a.ssr = g.ssr; a.rpg = g.rpg;
+    a.emit_idx = g.rpg == 1 && g.n_regions <= kDecodeThreads;
+    a.cand_key = t.cand_key; a.cand_idx = t.cand_idx; a.thr = t.thr;
+    const dim3 grid(g.n_split_sweep, g.Hkv, batch);
     int rc = launch_decode<kRowsSweep>(a, nullptr, g, grid, st);
     if (rc != SOCKET_OK) return rc;
-    rc = launch_decode<kMergeResolve>(a, &t, g, grid, st);
+    rc = launch_decode<kMergeFinish>(a, &t, g, grid, st);
     if (rc != SOCKET_OK) return rc;
     return record_hip(ctx, hipGetLastError());
 }

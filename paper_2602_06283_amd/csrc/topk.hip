@@ -120,6 +120,9 @@ __global__ __launch_bounds__(kTopkThreads) void topk_filter_kernel(TopkArgs a) {
     for (int j = 0; j < PER; ++j) c2[j] = gh[tid + j * kTopkThreads];
     uint32_t *thr = a.thr + (int64_t)bh * kThrStride;
     const int key1 = min(key0 + kSlice, clamp_len(a.seq_len[b], a.max_n));
+    // this workgroup's region of the selected list: empty unless the sweep below says otherwise
+    uint32_t *selcnt = a.sel_cnt + (int64_t)bh * a.n_regions + blockIdx.x;
+    if (tid == 0) *selcnt = 0u;
     uint32_t k_eff, pair, above, n_cand;
     float bin_lo = 0.0f, bin_inv = 0.0f;
     if (ADAPT) {
@@ -168,10 +171,12 @@ __global__ __launch_bounds__(kTopkThreads) void topk_filter_kernel(TopkArgs a) {
     uint32_t *cnt = a.counters + (int64_t)bh * kCounterStride;
     uint32_t *ckey = a.cand_key + (int64_t)bh * a.max_n;
     int32_t *cidx = a.cand_idx + (int64_t)bh * a.max_n;
-    int32_t *staged = a.staged + (int64_t)bh * a.max_k;        // selected positions, unordered
+    int32_t *region = a.sel_regions + ((int64_t)bh * a.n_regions + blockIdx.x) * kSlice;
 
-    // Positions in the two lists are handed out with one atomic per workgroup and list:
-    // every thread counts its hits and a block scan turns the counts into offsets.
+    // Scores above the threshold bin go to this workgroup's own region of the selected list, in
+    // position order (no reservation across workgroups: what a region holds depends on the
+    // scores alone); candidates of the threshold bin, a handful, are appended to one list with
+    // an atomic per workgroup - they are ranked as a set, so their order does not matter.
     uint32_t keys[kPer];
     uint32_t flags = 0;                           // bit j: selected, bit 16+j: candidate
 #pragma unroll
@@ -186,15 +191,15 @@ __global__ __launch_bounds__(kTopkThreads) void topk_filter_kernel(TopkArgs a) {
     uint32_t total;
     const uint32_t before = block_excl_scan(mine, &total, tmp);   // both counts in one word
     if (tid == 0) {
-        const uint32_t nsel = total & 0xffffu, ncand = total >> 16;
-        s_base[0] = nsel ? atomicAdd(&cnt[0], nsel) : 0u;
+        const uint32_t ncand = total >> 16;
+        *selcnt = total & 0xffffu;
         s_base[1] = ncand ? atomicAdd(&cnt[1], ncand) : 0u;
     }
     __syncthreads();
-    uint32_t at_sel = s_base[0] + (before & 0xffffu), at_cand = s_base[1] + (before >> 16);
+    uint32_t at_sel = before & 0xffffu, at_cand = s_base[1] + (before >> 16);
 #pragma unroll
     for (int j = 0; j < kPer; ++j) {
-        if (flags & (1u << j)) staged[at_sel++] = i + j;
+        if (flags & (1u << j)) region[at_sel++] = i + j;
         if (flags & (1u << (16 + j))) {
             ckey[at_cand] = keys[j];
             cidx[at_cand] = i + j;
@@ -230,12 +235,7 @@ int launch_topk(socket_ctx *ctx, const float *scores, const int32_t *seq_len, co
     int rc = launch_topk_sweep(ctx, scores, seq_len, k, batch, idx, n_selected, hist_mode, st);
     if (rc != SOCKET_OK) return rc;
     const TopkArgs a = topk_args(ctx, scores, seq_len, k, idx, n_selected, hist_mode);
-    static bool lds_raised = false;   // 68 KB of dynamic LDS has to be allowed once per process
-    if (!lds_raised) {
-        if (hipFuncSetAttribute((const void *)topk_resolve_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)kResolveLds) != hipSuccess) return SOCKET_EHIP;
-        lds_raised = true;
-    }
+    static_assert(kResolveLds <= 64 * 1024, "within the default dynamic LDS limit");
     hipLaunchKernelGGL(topk_resolve_kernel, dim3(ctx->g.Hkv * batch), dim3(kTopkThreads), kResolveLds, st, a);
     return record_hip(ctx, hipGetLastError());
 }

@@ -7,15 +7,12 @@
 
 namespace sk {
 
-constexpr int kTopkThreads = 512;
 constexpr int kRefineBins = 4096;                // bins of a candidate-refinement digit
-constexpr int kBitmapWords = 8192;               // 32 KB of LDS
+constexpr int kBitmapWords = 4096;               // 16 KB of LDS
 constexpr int kBitmapTokens = kBitmapWords * 32; // tokens one LDS bitmap pass covers
 constexpr int kLowBits = 32 - kHistBits;         // score bits below the leading digit
 constexpr int kDigit2Shift = kLowBits - kHistBits;   // second digit: the next kHistBits score bits
 static_assert(kDigit2Shift >= 0 && kDigit2Shift <= 12, "the low score bits fit one refinement digit");
-constexpr int kPer = 8;                          // scores per thread in a sweep
-constexpr int kSlice = kTopkThreads * kPer;      // scores per workgroup
 constexpr int kRankMax = 2 * kTopkThreads;       // candidates the all-pairs ranking handles
 // threshold record: [0] k_eff, [1] first digit, [2] scores above it, [3] scores in it,
 //                   [4] second digit, [5] scores selected outright, [6] candidates,
@@ -33,7 +30,11 @@ struct TopkArgs {
     uint32_t *counters;
     uint32_t *cand_key;
     int32_t *cand_idx;
-    int32_t *staged;
+    int32_t *staged;      // candidates picked by the long-list refinement
+    int32_t *sel_regions; // positions selected outright, [n_regions][kSlice] per (sequence, KV head)
+    uint32_t *sel_cnt;    // [n_regions] per (sequence, KV head)
+    int n_regions;
+    int pre_shift;        // the ordering step fetches the first 2^pre_shift entries of every region up front
     int Hkv, max_n, max_k;
     int adaptive;         // candidates share an adaptive bin, not the two leading digits
 };
@@ -47,6 +48,9 @@ inline TopkArgs topk_args(socket_ctx *ctx, const float *scores, const int32_t *s
     const int64_t BHmax = (int64_t)g.max_batch * g.Hkv;
     a.hist = ctx->hist; a.hist2 = ctx->hist + BHmax * kHistBins; a.thr = ctx->counters + BHmax * kCounterStride;
     a.counters = ctx->counters; a.cand_key = ctx->cand_key; a.cand_idx = ctx->cand_idx; a.staged = ctx->staged;
+    a.sel_regions = ctx->sel_regions; a.sel_cnt = ctx->sel_cnt; a.n_regions = g.n_regions;
+    a.pre_shift = 0;                                   // 16 * 512 preloads spread over the regions
+    while (a.pre_shift < 12 && ((int64_t)g.n_regions << (a.pre_shift + 1)) <= 16 * kTopkThreads) ++a.pre_shift;
     a.Hkv = g.Hkv; a.max_n = g.max_n; a.max_k = g.max_k; a.adaptive = hist_mode == kHistAdaptive;
     return a;
 }
@@ -155,7 +159,10 @@ __device__ __forceinline__ void topk_resolve_body(const TopkArgs &a, int bh, uin
     __shared__ uint32_t res[4];
     __shared__ uint32_t chosen[kLevels];
     __shared__ uint32_t s_count;
-    constexpr int PRE = 8;                        // list entries per thread fetched up front
+    constexpr int kFastCand = 16;                 // kept candidates the merge-by-counting emit handles
+    __shared__ int32_t s_kc[kFastCand];           // their positions
+    __shared__ uint32_t s_nk;
+    constexpr int PRE = 16;                       // list entries per thread fetched up front
     const int tid = threadIdx.x;
     const int b = bh / a.Hkv;
     uint32_t *gh1 = a.hist + (int64_t)bh * kHistBins;
@@ -165,9 +172,14 @@ __device__ __forceinline__ void topk_resolve_body(const TopkArgs &a, int bh, uin
     const uint32_t *ckey = a.cand_key + (int64_t)bh * a.max_n;
     const int32_t *cidx = a.cand_idx + (int64_t)bh * a.max_n;
     int32_t *staged = a.staged + (int64_t)bh * a.max_k;
+    const int32_t *regions = a.sel_regions + (int64_t)bh * a.n_regions * kSlice;
+    const uint32_t *selcnt = a.sel_cnt + (int64_t)bh * a.n_regions;
+    __shared__ uint32_t s_regcnt[kMaxRegions];
     int32_t *out = a.idx + (int64_t)bh * a.max_k;
-    // The heads of both lists are fetched before their lengths are known (the reads stay inside
-    // the buffers), so that their latency overlaps the load of the threshold record.
+    // The heads of the lists are fetched before their lengths are known (the reads stay inside
+    // the buffers), so that their latency overlaps the load of the threshold record: two
+    // candidates per thread, and the first 2^pre_shift entries of every region.
+    const int pre_n = 1 << a.pre_shift;
     uint32_t pk[2];
     int32_t pp[2], ps[PRE];
 #pragma unroll
@@ -177,8 +189,15 @@ __device__ __forceinline__ void topk_resolve_body(const TopkArgs &a, int bh, uin
             pk[j] = i < a.max_n ? ckey[i] : 0u;
             pp[j] = i < a.max_n ? cidx[i] : 0;
         }
-        ps[j] = i < a.max_k ? staged[i] : 0;
+        const int rg = (i >> a.pre_shift) < a.n_regions ? i >> a.pre_shift : a.n_regions - 1;   // (a region that exists: the load is unconditional)
+        ps[j] = regions[(int64_t)rg * kSlice + (i & (pre_n - 1))];
     }
+    // (the loads above are wanted now, in flight beside the threshold record's: without this
+    // the compiler moves each of them down to its first use, one memory latency apiece)
+#pragma unroll
+    for (int j = 0; j < PRE; ++j) asm volatile("" : "+v"(ps[j]));
+    for (int i = tid; i < a.n_regions; i += kTopkThreads) s_regcnt[i] = selcnt[i];
+    if (tid == 0) s_nk = 0;
     const uint32_t k_eff = thr[0], above = k_eff ? thr[5] : 0u, n_cand = k_eff ? thr[6] : 0u;
     const int seq = clamp_len(a.seq_len[b], a.max_n);
     const uint32_t need0 = k_eff - above;         // candidates to keep
@@ -218,7 +237,7 @@ __device__ __forceinline__ void topk_resolve_body(const TopkArgs &a, int bh, uin
         };
         uint32_t need = need0, remaining = n_cand;
         if (tid == 0) {
-            s_count = above;                      // next free staging slot
+            s_count = 0;                          // next free slot of the picked list
             chosen[0] = thr[1];                   // the digits every two-digit candidate has
             chosen[1] = thr[4];
         }
@@ -250,7 +269,62 @@ __device__ __forceinline__ void topk_resolve_body(const TopkArgs &a, int bh, uin
         __syncthreads();
     }
 
+    // does any region hold entries beyond those in registers?
+    bool spill = false;
     if (k_eff > 0) {
+        bool mine = false;
+        for (int r = tid; r < a.n_regions; r += kTopkThreads) mine = mine || s_regcnt[r] > (uint32_t)pre_n;
+        spill = __syncthreads_or(mine);
+    }
+    const bool fast = k_eff > 0 && short_list && !spill && need0 <= (uint32_t)kFastCand && a.n_regions <= kTopkThreads;
+    if (fast) {
+        // ---- ascending emit by counting.  The regions, one after the other, already are the
+        //      positions selected outright in ascending order; the few kept candidates have to be
+        //      slipped in.  An entry's place is its index in that order plus the number of kept
+        //      candidates before it; a candidate's place is the number of entries before it (a
+        //      binary search in its own region, whose entries are all in LDS) plus the number of
+        //      kept candidates before it.
+        int32_t *s_ent = (int32_t *)h;                              // [n_regions << pre_shift]
+        uint32_t *s_regpre = h + (kTopkThreads * PRE);              // [n_regions] entries before each region
+#pragma unroll
+        for (int j = 0; j < PRE; ++j) s_ent[tid + j * kTopkThreads] = ps[j];
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            if (keep[j]) s_kc[atomicAdd(&s_nk, 1u)] = pp[j];        // (their order does not matter: they are only counted)
+        uint32_t total;
+        const uint32_t pre = block_excl_scan(tid < a.n_regions ? s_regcnt[tid] : 0u, &total, tmp);
+        s_regpre[tid] = pre;
+        __syncthreads();
+        const int nk = (int)s_nk;
+        int32_t kc[kFastCand];                                      // the kept candidates, in registers
+#pragma unroll
+        for (int q = 0; q < kFastCand; ++q) kc[q] = q < nk ? s_kc[q] : 0x7fffffff;
+        auto kept_before = [&](int32_t p) {
+            uint32_t c = 0;
+#pragma unroll
+            for (int q = 0; q < kFastCand; ++q) c += kc[q] < p;
+            return c;
+        };
+#pragma unroll
+        for (int j = 0; j < PRE; ++j) {
+            const int i = tid + j * kTopkThreads;
+            const int rg = i >> a.pre_shift, e = i & (pre_n - 1);
+            if (rg < a.n_regions && (uint32_t)e < s_regcnt[rg]) out[s_regpre[rg] + e + kept_before(ps[j])] = ps[j];
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            if (keep[j]) {
+                const int32_t p = pp[j];
+                const int rg = p / kSlice;
+                const int32_t *ent = s_ent + (rg << a.pre_shift);
+                int lo = 0, hi = (int)s_regcnt[rg];                 // first entry >= p
+                while (lo < hi) {
+                    const int mid = (lo + hi) >> 1;
+                    if (ent[mid] < p) lo = mid + 1; else hi = mid;
+                }
+                out[s_regpre[rg] + lo + kept_before(p)] = p;
+            }
+    } else if (k_eff > 0) {
         // ---- ascending emit: a bitmap of the selected positions in LDS, the running count of
         //      set bits before every bitmap word, then each selected position looks up its own
         //      rank (count before its word + set bits below it inside the word).
@@ -262,15 +336,21 @@ __device__ __forceinline__ void topk_resolve_body(const TopkArgs &a, int bh, uin
         // every selected position, wherever it is kept, goes through f once
         auto for_selected = [&](auto f) {
 #pragma unroll
-            for (int j = 0; j < PRE; ++j)         // slots filled by the sweep: already in registers
-                if (tid + j * kTopkThreads < above) f(ps[j]);
-            for (uint32_t i = tid + PRE * kTopkThreads; i < above; i += kTopkThreads) f(staged[i]);
+            for (int j = 0; j < PRE; ++j) {       // heads of the regions: already in registers
+                const int i = tid + j * kTopkThreads;
+                if ((i >> a.pre_shift) < a.n_regions && (uint32_t)(i & (pre_n - 1)) < s_regcnt[i >> a.pre_shift]) f(ps[j]);
+            }
+            if (spill)                            // regions that hold more than the entries fetched up front
+                for (int r = 0; r < a.n_regions; ++r) {
+                    const uint32_t c = s_regcnt[r];
+                    for (uint32_t e = (uint32_t)pre_n + tid; e < c; e += kTopkThreads) f(regions[(int64_t)r * kSlice + e]);
+                }
             if (short_list) {
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
                     if (keep[j]) f(pp[j]);
             } else {
-                for (uint32_t i = above + tid; i < k_eff; i += kTopkThreads) f(staged[i]);
+                for (uint32_t i = tid; i < need0; i += kTopkThreads) f(staged[i]);
             }
         };
         for (int base = 0; base < seq; base += kBitmapTokens) {

@@ -126,7 +126,12 @@ def test_null_arguments_are_rejected_without_a_gpu():
     assert lib.socket_dense_decode(None, None, None, None, None, None, 1, 1.0, 1, None, None) == sk.EINVAL
     assert lib.socket_value_norms(None, None, None, None, None, 1, 1, None, None) == sk.EINVAL
     assert lib.socket_set_forced_tokens(None, 4, 124) == sk.EINVAL
-    assert lib.socket_set_deterministic(None, 1) == sk.EINVAL
+    assert lib.socket_score_keys_binned(None, None, None, None, None, 1, None, None) == sk.EINVAL
+    assert lib.socket_topk_select_binned(None, None, None, None, 1, None, None, None) == sk.EINVAL
+    assert lib.socket_reset(None, None) == sk.EINVAL
+    assert lib.socket_bucket_probs(None, 1, None, None) == sk.EINVAL
+    assert lib.socket_probe_stream_read(None, 16, None, None) == sk.EINVAL
+    assert lib.socket_sparse_decode_noalloc(None, None, None, None, None, None, None, 1, 1.0, 1, None, None, None) == sk.EINVAL
     assert lib.socket_hard_hash(None, None, None, 1, None) == sk.EINVAL
     assert lib.socket_soft_hash(None, None, None, 0.5, 1, None) == sk.EINVAL
     assert lib.socket_score_keys(None, None, None, None, None, 1, None, None) == sk.EINVAL

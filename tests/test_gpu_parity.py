@@ -518,21 +518,21 @@ def test_runs_are_bitwise_repeatable():
 
 # ------------------------------------------------------------------ fused decode step
 
-def same_step_results(a, f, deterministic, where):
+def same_step_results(a, f, where):
     """Fused step f against the separate calls a: ids, scores, selection and count bit for bit;
-    the attention output bit for bit in deterministic mode, else to rounding (same tokens, same
-    sum, but which split a token falls in is not fixed)."""
+    the attention output to rounding (the same sum over the same tokens, cut into splits by
+    position ranges of the sequence in the fused step, by ranges of the index row in
+    socket_sparse_decode)."""
     for key in a:
-        if key == "out" and not deterministic:
+        if key == "out":
             assert torch.allclose(a[key], f[key], rtol=1e-5, atol=1e-5), (where, key)
         else:
             assert torch.equal(a[key], f[key]), (where, key)
 
 
-@pytest.mark.parametrize("deterministic", [False, True])
 @pytest.mark.parametrize("kv_dtype,L,P,G", [(wl.BF16, 64, 8, 4), (wl.F32, 32, 8, 1), (wl.BF16, 60, 10, 4),
                                             (wl.BF16, 40, 12, 2), (wl.F32, 16, 9, 1)])
-def test_decode_step_equals_separate_calls_and_oracle(kv_dtype, L, P, G, deterministic):
+def test_decode_step_equals_separate_calls_and_oracle(kv_dtype, L, P, G):
     """socket_decode_step must give what the four separate calls give (see same_step_results),
     for a few consecutive steps; the last step is also checked against the oracle."""
     _need_gpu()
@@ -542,7 +542,6 @@ def test_decode_step_equals_separate_calls_and_oracle(kv_dtype, L, P, G, determi
                         seq_len=[n0 + steps, n0 - 500 + steps])
     start = np.array([n0, n0 - 500], dtype=np.int32)
     ctx = hz.make_ctx(layer)
-    ctx.set_deterministic(deterministic)
     Kd, Vd, qd, Wd = (hz.dev(x, layer.kv_dtype) for x in (layer.K, layer.V, layer.q, layer.W))
     max_k = int(layer.k.max())
 
@@ -564,17 +563,16 @@ def test_decode_step_equals_separate_calls_and_oracle(kv_dtype, L, P, G, determi
         ctx.sparse_decode(qd, Kd, Vd, a["idx"], a["nsel"], B, 1.0, a["out"])
         ctx.decode_step(qd, Kd, Vd, f["codes"], Wd, 0.5, pos, kk, B, 1.0, f["scores"], f["idx"], f["nsel"], f["out"])
         torch.cuda.synchronize()
-        same_step_results(a, f, deterministic, s)
+        same_step_results(a, f, s)
     res = tuple(f[key].cpu().numpy() for key in ("codes", "scores", "idx", "nsel")) + (f["out"].cpu().numpy(),)
     check_chain(layer, *res, atol=1e-4)
     ctx.close()
 
 
-@pytest.mark.parametrize("deterministic", [False, True])
 @pytest.mark.parametrize("case", ["ties_cold", "ties_cold_small_k", "ties_flat", "all_equal", "take_all", "k_one",
                                   "value_norms", "value_norms_heavy", "large", "large_tiny_k", "tie_group_400",
                                   "tie_group_700"])
-def test_decode_step_select_paths_agree(case, deterministic):
+def test_decode_step_select_paths_agree(case):
     """Inside socket_decode_step the select starts from what the scoring pass leaves: a
     histogram with bins sized from the bucket-probability tables when the scores are
     unweighted, and, when k is a small part of the sequence, lists of the scores above a guessed
@@ -582,10 +580,10 @@ def test_decode_step_select_paths_agree(case, deterministic):
     All are exact, so they must pick the same tokens - also when nearly all scores tie (tau -> 0
     makes them collision counts, tau -> inf makes them all L/R, identical keys make them one
     value), when k covers the whole sequence, and with value norms (bins then also scaled by a
-    sample of the norms), well behaved or spread over five decades.  Without the deterministic
-    switch the attention of the step starts from the select's unordered lists; threshold bins
-    with more candidates than a decode workgroup ranks (the tie cases) take the route through
-    the ordered row inside the last launch."""
+    sample of the norms), well behaved or spread over five decades.  The attention of the step
+    starts from the lists the select's sweep leaves; threshold bins with more candidates than
+    a decode workgroup ranks (the tie cases) take the route through the ordered row inside the
+    last launch."""
     _need_gpu()
     cfg = {
         "ties_cold": dict(n=6000, k=[300, 777], tau=1e-4, lens=[6000, 4100]),
@@ -615,7 +613,6 @@ def test_decode_step_select_paths_agree(case, deterministic):
             for h in range(Hkv):
                 layer.K[b, h, 1000:1000 + 3 * m:3, :] = layer.q[b, h * G, :]
     ctx = hz.make_ctx(layer)
-    ctx.set_deterministic(deterministic)
     Kd, Vd, qd, Wd = (hz.dev(x, layer.kv_dtype) for x in (layer.K, layer.V, layer.q, layer.W))
     max_k = int(layer.k.max())
     vn = None
@@ -648,7 +645,7 @@ def test_decode_step_select_paths_agree(case, deterministic):
         ctx.decode_step(qd, Kd, Vd, f["codes"], Wd, layer.tau, pos, kk, B, 1.0, f["scores"], f["idx"], f["nsel"],
                         f["out"], vnorm=vn)
         torch.cuda.synchronize()
-        same_step_results(a, f, deterministic, rep)
+        same_step_results(a, f, rep)
     # and the selection is the oracle's on the GPU's own scores (exact, ties to the smaller position)
     sc, idx, nsel = (f[key].cpu().numpy() for key in ("scores", "idx", "nsel"))
     for b in range(B):
@@ -677,51 +674,53 @@ def test_decode_step_shapes(kv_dtype, d, G, n, k):
     max_k = int(layer.k.max())
     kk, zero, one = hz.i32(layer.k), hz.i32(np.zeros(B)), hz.i32(np.ones(B))
     pos, ln = hz.i32(lens - 1), hz.i32(lens)
-    for deterministic in (False, True):
-        ctx = hz.make_ctx(layer)
-        ctx.set_deterministic(deterministic)
+    ctx = hz.make_ctx(layer)
 
-        def fresh():
-            return dict(codes=hz.new_codes((B, Hkv), n, L, P),
-                        scores=torch.zeros((B, Hkv, n), dtype=torch.float32, device="cuda"),
-                        idx=torch.zeros((B, Hkv, max_k), dtype=torch.int32, device="cuda"),
-                        nsel=torch.zeros((B, Hkv), dtype=torch.int32, device="cuda"),
-                        out=torch.zeros((B, layer.Hq, layer.d), dtype=torch.float32, device="cuda"))
-        a, f = fresh(), fresh()
-        for t in (a, f):
-            ctx.hash_keys(Kd, Wd, zero, hz.i32(lens - 1), B, n, t["codes"])
-        ctx.hash_keys(Kd, Wd, pos, one, B, 1, a["codes"])
-        ctx.score(qd, a["codes"], Wd, 0.5, ln, B, a["scores"])
-        ctx.topk_select(a["scores"], ln, kk, B, a["idx"], a["nsel"])
-        ctx.sparse_decode(qd, Kd, Vd, a["idx"], a["nsel"], B, 1.0, a["out"])
-        for rep in range(2):
-            ctx.decode_step(qd, Kd, Vd, f["codes"], Wd, 0.5, pos, kk, B, 1.0, f["scores"], f["idx"], f["nsel"], f["out"])
-            torch.cuda.synchronize()
-            same_step_results(a, f, deterministic, (deterministic, rep))
-        if deterministic:
-            res = tuple(f[key].cpu().numpy() for key in ("codes", "scores", "idx", "nsel")) + (f["out"].cpu().numpy(),)
-            check_chain(layer, *res, atol=1e-4)
-        ctx.close()
+    def fresh():
+        return dict(codes=hz.new_codes((B, Hkv), n, L, P),
+                    scores=torch.zeros((B, Hkv, n), dtype=torch.float32, device="cuda"),
+                    idx=torch.zeros((B, Hkv, max_k), dtype=torch.int32, device="cuda"),
+                    nsel=torch.zeros((B, Hkv), dtype=torch.int32, device="cuda"),
+                    out=torch.zeros((B, layer.Hq, layer.d), dtype=torch.float32, device="cuda"))
+    a, f = fresh(), fresh()
+    for t in (a, f):
+        ctx.hash_keys(Kd, Wd, zero, hz.i32(lens - 1), B, n, t["codes"])
+    ctx.hash_keys(Kd, Wd, pos, one, B, 1, a["codes"])
+    ctx.score(qd, a["codes"], Wd, 0.5, ln, B, a["scores"])
+    ctx.topk_select(a["scores"], ln, kk, B, a["idx"], a["nsel"])
+    ctx.sparse_decode(qd, Kd, Vd, a["idx"], a["nsel"], B, 1.0, a["out"])
+    for rep in range(2):
+        ctx.decode_step(qd, Kd, Vd, f["codes"], Wd, 0.5, pos, kk, B, 1.0, f["scores"], f["idx"], f["nsel"], f["out"])
+        torch.cuda.synchronize()
+        same_step_results(a, f, rep)
+    res = tuple(f[key].cpu().numpy() for key in ("codes", "scores", "idx", "nsel")) + (f["out"].cpu().numpy(),)
+    check_chain(layer, *res, atol=1e-4)
+    ctx.close()
 
 
-def test_decode_step_deterministic_route_is_bitwise_repeatable():
-    """With socket_set_deterministic the fused step gives the same bits on every run; without
-    it the attention output may differ in its last bits (the split a token falls in follows
-    the order in which the select's workgroups reserved list space) and nothing else may."""
+@pytest.mark.parametrize("n,lens,k", [(20000, [20000, 12345], [512, 300]),      # several regions, a few dozen rows each
+                                      (9000, [9000, 4100], [3000, 64]),           # a third of the tokens: shared regions
+                                      (4000, [3999, 17], [100, 17])])             # a single region; take-all
+def test_decode_step_is_bitwise_repeatable(n, lens, k):
+    """The fused step gives the same bits on every run, the attention output included: its
+    splits are cut by position ranges of the sequence, so which tokens a split sums, and in
+    which order, depends on the scores alone - not on the order in which workgroups of the
+    select happen to run.  (Run-to-run bit equality doubles as the race test of the chain.)"""
     _need_gpu()
-    B, Hkv, G, L, P, n = 2, 2, 4, 64, 8, 20000
-    lens = np.array([20000, 12345], dtype=np.int32)
-    layer = small_layer(seed=91, B=B, Hq=Hkv * G, Hkv=Hkv, n=n, L=L, P=P, k=[512, 300], seq_len=lens)
+    B, Hkv, G, L, P = 2, 2, 4, 64, 8
+    cap = (n + 31) // 16 * 16
+    lens = np.array(lens, dtype=np.int32)
+    layer = small_layer(seed=91, B=B, Hq=Hkv * G, Hkv=Hkv, n=cap, L=L, P=P, k=k, seq_len=lens)
     ctx = hz.make_ctx(layer)
     Kd, Vd, qd, Wd = (hz.dev(x, layer.kv_dtype) for x in (layer.K, layer.V, layer.q, layer.W))
     max_k = int(layer.k.max())
-    codes = hz.new_codes((B, Hkv), n, L, P)
+    codes = hz.new_codes((B, Hkv), cap, L, P)
     kk, zero = hz.i32(layer.k), hz.i32(np.zeros(B))
-    ctx.hash_keys(Kd, Wd, zero, hz.i32(lens - 1), B, n, codes)
+    ctx.hash_keys(Kd, Wd, zero, hz.i32(lens - 1), B, cap, codes)
     pos = hz.i32(lens - 1)
 
     def run():
-        r = dict(scores=torch.zeros((B, Hkv, n), dtype=torch.float32, device="cuda"),
+        r = dict(scores=torch.zeros((B, Hkv, cap), dtype=torch.float32, device="cuda"),
                  idx=torch.zeros((B, Hkv, max_k), dtype=torch.int32, device="cuda"),
                  nsel=torch.zeros((B, Hkv), dtype=torch.int32, device="cuda"),
                  out=torch.zeros((B, layer.Hq, layer.d), dtype=torch.float32, device="cuda"))
@@ -729,13 +728,11 @@ def test_decode_step_deterministic_route_is_bitwise_repeatable():
         torch.cuda.synchronize()
         return r
 
-    ctx.set_deterministic(True)
     ref = run()
-    for _ in range(3):
-        same_step_results(ref, run(), True, "deterministic")
-    ctx.set_deterministic(False)
-    for _ in range(3):
-        same_step_results(ref, run(), False, "fast")
+    for _ in range(5):
+        again = run()
+        for key in ref:
+            assert torch.equal(ref[key], again[key]), key
     ctx.close()
 
 
@@ -865,7 +862,7 @@ def test_forced_sink_and_window_tokens_through_the_chain():
     ctx.sparse_decode(qd, Kd, Vd, a["idx"], a["nsel"], B, 1.0, a["out"])
     ctx.decode_step(qd, Kd, Vd, f["codes"], Wd, 0.5, pos, kk, B, 1.0, f["scores"], f["idx"], f["nsel"], f["out"])
     torch.cuda.synchronize()
-    same_step_results(a, f, False, "forced")
+    same_step_results(a, f, "forced")
     sc, idx, nsel = (f[key].cpu().numpy() for key in ("scores", "idx", "nsel"))
     for b in range(B):
         for h in range(Hkv):
