@@ -571,7 +571,7 @@ def test_decode_step_equals_separate_calls_and_oracle(kv_dtype, L, P, G):
 
 @pytest.mark.parametrize("case", ["ties_cold", "ties_cold_small_k", "ties_flat", "all_equal", "take_all", "k_one",
                                   "value_norms", "value_norms_heavy", "large", "large_tiny_k", "tie_group_400",
-                                  "tie_group_700"])
+                                  "tie_group_700", "half_selected", "several_regions_per_split"])
 def test_decode_step_select_paths_agree(case):
     """Inside socket_decode_step the select starts from what the scoring pass leaves: a
     histogram with bins sized from the bucket-probability tables when the scores are
@@ -600,6 +600,11 @@ def test_decode_step_select_paths_agree(case):
         # the threshold bin (400: ranked by the attention workgroups; 700: the ordered route)
         "tie_group_400": dict(n=6000, k=[300, 250], tau=0.5, lens=[6000, 5000]),
         "tie_group_700": dict(n=6000, k=[300, 250], tau=0.5, lens=[6000, 5000]),
+        # thousands of selected positions per region of the sweep, candidates among them
+        "half_selected": dict(n=6000, k=[3000, 1500], tau=0.5, lens=[6000, 5000]),
+        # more regions than attention splits: a split owns several, the index row is ordered
+        # beside the merge
+        "several_regions_per_split": dict(n=530000, k=[1024, 200], tau=0.5, lens=[530000, 300000]),
     }[case]
     B, Hkv, G, L, P = 2, 2, 4, 64, 8
     n = (cfg["n"] + 31) // 16 * 16
