@@ -945,6 +945,278 @@ __global__ __launch_bounds__(kProjThreads) void project_batch_kernel(ProjectArgs
 }
 
 // ---------------------------------------------------------------------------------------
+// The batched projections in their common case (one-entry-per-bucket tables of P = 4 or 8
+// planes, the soft hash wanted): one workgroup serves one sequence, one KV head and a GROUP of
+// TG = 128 / P tables, i.e. 128 adjacent columns of W.
+//   - The slab of W stays in LDS as stored ([channel][128 columns]); a thread owns two adjacent
+//     columns and one or two query heads and a range of channels: one conversion to fp64 per
+//     element of W serves two multiply-adds, against two conversions per multiply-add when a
+//     thread owns a single (query, plane) pair.
+//   - Products of sigmoids come from quarter tables as in the kernels above, laid out
+//     table-minor so that lanes over the tables of the group read adjacent words.
+//   - A thread's entries of the final tables belong to one table, and 16 (or 32) lanes over the
+//     group's tables write adjacent words of a row of the table block: 64-byte (128-byte)
+//     runs instead of single words a row apart.
+// ---------------------------------------------------------------------------------------
+constexpr int kGroupCols = 128;
+constexpr int kGroupThreads = 512;
+
+static size_t project_group_lds(int G, int d, int P, int elem) {
+    const int TG = kGroupCols / P, NQ = (P + 3) / 4;
+    const int QPT = G >= 2 ? 2 : 1, NQG = G / QPT, CS = kGroupThreads / (64 * NQG);
+    const size_t slab = (size_t)d * kGroupCols * elem, quarter = (size_t)G * NQ * 16 * TG * 8;
+    return (slab > quarter ? slab : quarter) + (size_t)d * G * 8 + (size_t)CS * G * kGroupCols * 8 +
+           (size_t)G * P * 2 * TG * 8 + (size_t)d * 4 + (kGroupThreads / 64) * kGroupCols * 4 + 3 * kGroupThreads * 4 + kGroupCols * 4;
+}
+
+template <typename T, int G, int P>
+__global__ __launch_bounds__(kGroupThreads) void project_group_kernel(ProjectArgs a) {
+    extern __shared__ double sm64[];
+    constexpr int NT = kGroupThreads, NW = NT / 64, COLS = kGroupCols, TG = COLS / P, R = 1 << P, NQ = (P + 3) / 4;
+    constexpr int EPV = 16 / (int)sizeof(T);
+    constexpr int QPT = G >= 2 ? 2 : 1;              // query heads per thread
+    constexpr int NQG = G / QPT;                     // thread groups over the query heads
+    constexpr int CS = NT / (64 * NQG);              // channel ranges
+    static_assert(P == 4 || P == 8, "whole quarters");
+    static_assert(CS >= 1 && CS * NQG * 64 == NT, "every thread has a share of the dot products");
+    const int tid = threadIdx.x;
+    const int tg = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int d = a.d;
+    const int l0 = tg * TG;                          // first table of the group
+    const bool app = a.K != nullptr;
+
+    // LDS: the slab of W (later the quarter tables), queries, partial dot products, sigmoids, the key
+    const size_t slab = (size_t)d * COLS * sizeof(T), quarter = (size_t)G * NQ * 16 * TG * 8;
+    T *ws = (T *)sm64;                               // [d][COLS]
+    double *qt = sm64;                               // [G][NQ][16][TG]
+    double *qd = (double *)((char *)sm64 + (slab > quarter ? slab : quarter));   // [d][G]
+    double *zb = qd + (size_t)d * G;                 // [CS][G][COLS]
+    double *sig = zb + CS * G * COLS;                // [G][P][2][TG]
+    float *kf = (float *)(sig + G * P * 2 * TG);     // [d]
+    float *kz = kf + d;                              // [NW][COLS]
+    float *s_part = kz + NW * COLS;                   // [3][NT]
+    uint32_t *sgn = (uint32_t *)(s_part + 3 * NT);   // [COLS]
+
+    // ---- global loads, all issued before the first use
+    int tok = 0;
+    int64_t krow = -1;
+    if (app) {
+        tok = a.pos[b];
+        const bool wanted = a.count == nullptr || a.count[b] >= 1;
+        if (wanted && tok >= 0 && tok < a.map.max_n) krow = a.map.row(b, h, tok);
+        if (a.len_out && tg == 0 && h == 0 && tid == 0) a.len_out[b] = tok + 1;
+    }
+    // W: rows of COLS elements (columns at or beyond L * P do not exist: zero)
+    constexpr int VPR = COLS / EPV;                  // 16-byte vectors per row
+    constexpr int WV = 2048 / NT;                    // vectors per thread: d * VPR <= 2048
+    const T *Wg = (const T *)a.W + (int64_t)h * d * a.LP + (int64_t)l0 * P;
+    uint4 wv[WV];
+#pragma unroll
+    for (int j = 0; j < WV; ++j) {
+        const int i = tid + j * NT;
+        const int c = i / VPR, v = i % VPR;
+        wv[j] = make_uint4(0, 0, 0, 0);
+        if (c < d && l0 * P + (v + 1) * EPV <= a.LP) wv[j] = *(const uint4 *)(Wg + (int64_t)c * a.LP + v * EPV);
+    }
+    // queries: 16-byte pieces of the G rows; the appended key's row
+    const int qpieces = G * d / EPV, kpieces = d / EPV;
+    uint4 qv = make_uint4(0, 0, 0, 0), kv = make_uint4(0, 0, 0, 0);
+    if (tid < qpieces) qv = *(const uint4 *)((const T *)a.q + ((int64_t)b * a.Hq + h * G) * d + tid * EPV);
+    if (app && krow >= 0 && tid >= NT - kpieces) kv = *(const uint4 *)((const T *)a.K + krow * d + (tid - (NT - kpieces)) * EPV);
+    // 256 value norms spread over the sequence per table: thread -> table tid % TG, samples tid / TG + (NT / TG) m
+    constexpr int SPT = 256 * TG / NT;               // samples per thread
+    const int li_own = tid % TG;                     // the table of this thread's samples and table entries
+    float nu1 = 0.0f, nu2 = 0.0f;
+    if (a.vnorm != nullptr && app && l0 + li_own < a.L && tok >= 0 && tok < a.map.max_n) {
+        const int seq = tok + 1;
+        const float step = (float)seq / (float)(a.L * 256);
+        float nu[SPT];
+#pragma unroll
+        for (int m = 0; m < SPT; ++m) {
+            const int j = tid / TG + (NT / TG) * m;
+            int t = (int)((float)((l0 + li_own) * 256 + j) * step);
+            t = t < seq ? t : seq - 1;
+            nu[m] = a.vnorm[((int64_t)b * a.Hkv + h) * a.map.max_n + t];
+        }
+#pragma unroll
+        for (int m = 0; m < SPT; ++m) {
+            nu1 += nu[m];
+            nu2 = fmaf(nu[m], nu[m], nu2);
+        }
+    }
+
+    // ---- into LDS
+#pragma unroll
+    for (int j = 0; j < WV; ++j) {
+        const int i = tid + j * NT;
+        if (i < d * VPR) *(uint4 *)(ws + (size_t)i * EPV) = wv[j];
+    }
+    if (tid < qpieces) {
+        float f[EPV];
+        vec_to_f32<T>(qv, f);
+        const int g = tid / kpieces, c0 = (tid - g * kpieces) * EPV;
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) qd[(size_t)(c0 + e) * G + g] = (double)f[e];
+    }
+    if (app && tid >= NT - kpieces) {
+        float f[EPV];
+        vec_to_f32<T>(kv, f);
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) kf[(tid - (NT - kpieces)) * EPV + e] = f[e];
+    }
+    __syncthreads();
+
+    // ---- dot products: columns 2 cpi, 2 cpi + 1; query heads qg QPT ..; channels of range cs
+    const int cpi = tid & 63;
+    auto w_pair = [&](int c, float &wa, float &wb) __attribute__((always_inline)) {
+        if (sizeof(T) == 2) {
+            const uint32_t w2 = ((const uint32_t *)ws)[c * (COLS / 2) + cpi];
+            wa = __uint_as_float(w2 << 16);
+            wb = __uint_as_float(w2 & 0xffff0000u);
+        } else {
+            const float2 w2 = ((const float2 *)ws)[c * (COLS / 2) + cpi];
+            wa = w2.x;
+            wb = w2.y;
+        }
+    };
+    {
+        const int qg = (tid >> 6) % NQG, cs = tid / (64 * NQG);
+        const int cn = d / CS;
+        double z[QPT][2];
+#pragma unroll
+        for (int qq = 0; qq < QPT; ++qq) z[qq][0] = z[qq][1] = 0.0;
+#pragma unroll 8
+        for (int c = cs * cn; c < (cs + 1) * cn; ++c) {
+            float wa, wb;
+            w_pair(c, wa, wb);
+            const double da = (double)wa, db = (double)wb;
+#pragma unroll
+            for (int qq = 0; qq < QPT; ++qq) {
+                const double qvv = qd[(size_t)c * G + qg * QPT + qq];
+                z[qq][0] = fma(da, qvv, z[qq][0]);
+                z[qq][1] = fma(db, qvv, z[qq][1]);
+            }
+        }
+#pragma unroll
+        for (int qq = 0; qq < QPT; ++qq)
+            *(double2 *)&zb[((size_t)cs * G + qg * QPT + qq) * COLS + 2 * cpi] = make_double2(z[qq][0], z[qq][1]);
+    }
+    if (app) {                                       // the key, in fp32: a range of the channels per wavefront
+        const int cs4 = tid >> 6, cn = d / NW;
+        float k0 = 0.0f, k1 = 0.0f;
+#pragma unroll 8
+        for (int c = cs4 * cn; c < (cs4 + 1) * cn; ++c) {
+            float wa, wb;
+            w_pair(c, wa, wb);
+            const float kk = kf[c];
+            k0 = fmaf(wa, kk, k0);
+            k1 = fmaf(wb, kk, k1);
+        }
+        *(float2 *)&kz[cs4 * COLS + 2 * cpi] = make_float2(k0, k1);
+    }
+    __syncthreads();
+
+    // ---- per (query head, column): u = tanh(z)/sqrt(d), then the sigmoids of +-2u/tau
+    for (int v = tid; v < G * COLS; v += NT) {
+        const int g = v / COLS, col = v % COLS;
+        double z = zb[(size_t)g * COLS + col];
+#pragma unroll
+        for (int cs = 1; cs < CS; ++cs) z += zb[((size_t)cs * G + g) * COLS + col];
+        // tanh|z| = (1 - t)/(1 + t) with t = exp(-2|z|); sigmoid(+-x) from e = exp(-|x|)
+        const double t = exp(-2.0 * fabs(z));
+        const double th = (1.0 - t) * rcp64(1.0 + t);
+        const double e = exp(-a.x_scale * th);       // x = 2 tanh|z| / (sqrt(d) tau) >= 0
+        double big = rcp64(1.0 + e), small = e * big;
+        if (a.hard) {                                // the limit tau -> 0
+            big = 1.0;
+            small = 0.0;
+        }
+        const int li = col / P, pl = col % P;
+        sig[((g * P + pl) * 2 + 1) * TG + li] = z >= 0.0 ? big : small;
+        sig[((g * P + pl) * 2) * TG + li] = z >= 0.0 ? small : big;
+    }
+    if (app && tid < COLS) {
+        float ks = 0.0f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) ks += kz[w * COLS + tid];
+        sgn[tid] = ks >= 0.0f ? 1u : 0u;
+    }
+    __syncthreads();
+
+    // ---- quarter tables (over the slab of W): products over planes 4 qr .. 4 qr + 3
+    for (int e = tid; e < G * NQ * 16 * TG; e += NT) {
+        const int li = e % TG, bits = (e / TG) & 15, gq = e / (TG * 16);     // gq = g * NQ + qr
+        const int g = gq / NQ, qr = gq % NQ;
+        const double *sp = sig + ((g * P + qr * 4) * 2) * TG + li;
+        const double f0 = sp[(0 + ((bits >> 0) & 1)) * TG], f1 = sp[(2 + ((bits >> 1) & 1)) * TG];
+        const double f2 = sp[(4 + ((bits >> 2) & 1)) * TG], f3 = sp[(6 + ((bits >> 3) & 1)) * TG];
+        qt[e] = (f0 * f1) * (f2 * f3);
+    }
+    // the appended key's bucket ids, one thread per table of the group (tables >= L: id 0)
+    if (app && krow >= 0 && tid >= 64 && tid < 64 + TG && l0 + tid - 64 < a.Lpad) {
+        const int li = tid - 64, l = l0 + li;
+        uint32_t code = 0;
+        if (l < a.L)
+#pragma unroll
+            for (int i = 0; i < P; ++i) code |= sgn[li * P + i] << i;
+        ((uint8_t *)a.codes)[krow * a.Lpad + code_pos(l, tok, a.S)] = (uint8_t)code;
+    }
+    __syncthreads();
+
+    // ---- the tables: p(r) over all planes, averaged over the G queries.  Thread -> table li_own,
+    //      buckets tid / TG + (NT / TG) k.
+    {
+        constexpr int RSTEP = NT / TG, NK = R / RSTEP;
+        const int l = l0 + li_own;
+        const bool live = l < a.L;
+        const int lw = a.Lpad < 64 ? a.Lpad : 64, copies = 64 / lw;
+        const int c64 = l >> 6, lp = l & 63;
+        const double inv_g = 1.0 / (double)G, inv_r = 1.0 / (double)R;
+        float *Tg = a.tables + ((int64_t)b * a.Hkv + h) * a.table_words;
+        const int r0 = tid / TG;
+        double lo[G];
+        static_assert(RSTEP % 16 == 0 || P <= 4, "the low four bits of a thread's buckets are the same for every k");
+        if (P > 4) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) lo[g] = qt[((g * NQ) * 16 + (r0 & 15)) * TG + li_own];
+        }
+        float dev2 = 0.0f;
+#pragma unroll
+        for (int k = 0; k < NK; ++k) {
+            const int r = r0 + RSTEP * k;
+            double mean = 0.0;
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                if (P > 4) mean = fma(lo[g], qt[((g * NQ + 1) * 16 + (r >> 4)) * TG + li_own], mean);
+                else mean += qt[((g * NQ) * 16 + r) * TG + li_own];
+            }
+            mean *= inv_g;
+            if (!live) mean = 0.0;
+            else {
+                const double dv = mean - inv_r;      // a table's entries sum to 1: their mean is 1/R
+                dev2 += (float)(dv * dv);
+            }
+            if (l < a.Lpad)
+                for (int cp = 0; cp < copies; ++cp) Tg[((int64_t)c64 * R + r) * 64 + lp + cp * lw] = (float)mean;
+        }
+        s_part[tid] = dev2;
+        s_part[NT + tid] = nu1;
+        s_part[2 * NT + tid] = nu2;
+    }
+    __syncthreads();
+    // spread of each table's entries and its sampled value norms, from which the scoring pass
+    // sizes its histogram bins
+    if (tid < 3 * TG) {
+        const int w = tid / TG, li = tid % TG;
+        float sum = 0.0f;
+#pragma unroll
+        for (int j = 0; j < NT / TG; ++j) sum += s_part[w * NT + li + j * TG];
+        if (l0 + li < a.Lpad)
+            a.tstats[(((int64_t)b * a.Hkv + h) * a.Lpad + l0 + li) * 3 + w] = w == 0 ? (float)((double)sum / (double)R) : sum;
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 
 struct ScoreArgs {
     const void *codes;
@@ -1709,6 +1981,27 @@ int launch_project(socket_ctx *ctx, const void *q, const void *proj, float tau, 
     if (batch > 1) {
         // several sequences per workgroup: the W slab of a table is staged once for all of them
         const int elem = f32 ? 4 : 2;
+        // the common case: a workgroup per (sequence, KV head, group of 128 columns of W)
+        if (q && g.mode == kDirect && g.cb == 1 && (g.P == 4 || g.P == 8) && g.R == (1 << g.P) &&
+            (size_t)g.d * kGroupCols * elem <= 32 * 1024 && (a.LP * elem) % 16 == 0 && g.G * g.d / (16 / elem) <= kGroupThreads - g.d / (16 / elem)) {
+            const size_t glds = project_group_lds(g.G, g.d, g.P, elem);
+            const bool p8 = g.P == 8;
+            switch (g.G) {
+                case 1: fn = f32 ? (p8 ? project_group_kernel<float, 1, 8> : project_group_kernel<float, 1, 4>)
+                                 : (p8 ? project_group_kernel<uint16_t, 1, 8> : project_group_kernel<uint16_t, 1, 4>); break;
+                case 2: fn = f32 ? (p8 ? project_group_kernel<float, 2, 8> : project_group_kernel<float, 2, 4>)
+                                 : (p8 ? project_group_kernel<uint16_t, 2, 8> : project_group_kernel<uint16_t, 2, 4>); break;
+                case 4: fn = f32 ? (p8 ? project_group_kernel<float, 4, 8> : project_group_kernel<float, 4, 4>)
+                                 : (p8 ? project_group_kernel<uint16_t, 4, 8> : project_group_kernel<uint16_t, 4, 4>); break;
+                case 8: fn = f32 ? (p8 ? project_group_kernel<float, 8, 8> : project_group_kernel<float, 8, 4>)
+                                 : (p8 ? project_group_kernel<uint16_t, 8, 8> : project_group_kernel<uint16_t, 8, 4>); break;
+                default: return SOCKET_EUNSUPPORTED;
+            }
+            if (set_lds_limit((const void *)fn, glds) != SOCKET_OK) return SOCKET_EHIP;
+            const int TG = kGroupCols / g.P;
+            hipLaunchKernelGGL(fn, dim3((g.Lpad + TG - 1) / TG, g.Hkv, batch), dim3(kGroupThreads), glds, st, a);
+            return record_hip(ctx, hipGetLastError());
+        }
         int nb = batch < kProjMaxNb ? batch : kProjMaxNb;
         while (nb > 1 && project_batch_lds(nb, g.G, g.d, g.P, elem) > 64 * 1024) --nb;
         const int groups = (batch + nb - 1) / nb;
