@@ -81,13 +81,16 @@ int fill_geometry(const socket_params *p, Geometry *g) {
     g->n_split = ns < 1 ? 1 : (ns > 64 ? 64 : ns);
     // The fused step's attention is cut by regions of the select's sweep (kSlice positions each):
     // ssr workgroups share a region when a region is expected to hold more than ~40 selected
-    // tokens, rpg regions share a workgroup when there are more regions than splits.
+    // tokens (as long as the whole batch's workgroups stay resident together: about five of
+    // them per compute unit), rpg regions share a workgroup when there are more regions than
+    // splits.
     g->n_regions = (p->max_n + kSlice - 1) / kSlice;
     if (g->n_regions > kMaxRegions) return SOCKET_EUNSUPPORTED;
     g->ssr = 1;
     g->rpg = (g->n_regions + kMaxSplits - 1) / kMaxSplits;
     while (g->rpg == 1 && g->n_regions * g->ssr * 2 <= kMaxSplits && g->ssr < 16 &&
-           (int64_t)p->max_k > (int64_t)40 * g->n_regions * g->ssr)
+           (int64_t)p->max_k > (int64_t)40 * g->n_regions * g->ssr &&
+           (int64_t)g->n_regions * g->ssr * 2 * p->Hkv * p->max_batch <= 1280)
         g->ssr *= 2;
     g->n_split_sweep = g->rpg > 1 ? (g->n_regions + g->rpg - 1) / g->rpg : g->n_regions * g->ssr;
     return SOCKET_OK;

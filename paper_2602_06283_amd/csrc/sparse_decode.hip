@@ -45,7 +45,7 @@ struct DecodeArgs {
     RowMap map;
     float scale;
     int Hq, max_k, n_split, out_dtype;
-    const int32_t *seq_len;   // dense variant only
+    const int32_t *seq_len;   // dense variant, and kRowsSweep: tokens of each sequence
     // kRowsSweep: the lists and the threshold record of the select's sweep
     const int32_t *sel_regions;
     const uint32_t *sel_cnt;
@@ -100,8 +100,9 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
     constexpr int GPG = (G + NG - 1) / NG;           // query heads per group
 
     __shared__ __align__(16) float s_p[G][CH];       // logits, then softmax numerators
-    __shared__ int64_t s_row[CH];                    // K/V row of each chunk entry (-1 = none)
+    __shared__ int64_t s_row[2][CH];                 // K/V row of each chunk entry (-1 = none), two chunks
     __shared__ float s_m[G], s_l[G], s_corr[G];
+    __shared__ __align__(16) float s_q[G][D];        // the queries as floats
     __shared__ int32_t s_cpos[SRC == kRowsSweep ? kSweepCand : 1];   // candidates that make the cut, best first
     // kRowsSweep, for the index row: every kept candidate's position (any order, padded with
     // INT_MAX to whole quads), the head of the first region, the entry counts of the regions before it
@@ -110,6 +111,7 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
     __shared__ int32_t s_head[kHeadEntries];
     __shared__ float s_pre[NWAVE];
     __shared__ int s_nkept;
+    __shared__ int64_t s_own[kHeadEntries];          // kRowsSweep: the K/V rows of the first NT entries
     T (*s_v)[D] = (T (*)[D])dyn;                     // [VROWS][D]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -127,11 +129,13 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
     // ---- every load that needs nothing else first, issued before anything waits: the queries,
     //      the first chunk's list entries, the counts and (kRowsSweep) one candidate per thread
     //      (the reads stay inside the buffers)
-    Row8<T> qr[G];
+    Row8<T> qr[G];                                   // (the first LPR threads: 8 channels of every query head each)
+    if (tid < LPR) {
 #pragma unroll
-    for (int g = 0; g < G; ++g) qr[g].load((const T *)a.q + ((int64_t)b * a.Hq + h * G + g) * D + sub * 8);
+        for (int g = 0; g < G; ++g) qr[g].load((const T *)a.q + ((int64_t)b * a.Hq + h * G + g) * D + tid * 8);
+    }
     const int32_t *list = nullptr;
-    int32_t first = -1;                              // the list entry of slot r_begin + tid
+    int32_t first = -1;                              // the list entry of slot r_begin + tid (kRowsSweep: entry tid of the split's share of its first region)
     uint32_t pk[kCandPer];
     int32_t pp[kCandPer];
     int count = 0, need = 0, n_cand = 0;             // list entries that count; kRowsSweep: see below
@@ -155,8 +159,19 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
             sub_i = split - reg0 * a.ssr;
             sub_n = a.ssr;
         }
+        // regions past the end of the sequence hold nothing: an empty partial result, at once
+        // (in a batch of mixed lengths that is a good part of the workgroups)
+        if ((int64_t)reg0 * kSlice >= a.seq_len[b]) {
+            float *part = a.partials + ((int64_t)(b * a.Hq + h * G) * a.n_split) * (D + 2);
+            if (tid < G) {
+                part[((int64_t)tid * a.n_split + split) * (D + 2) + 0] = ninf;
+                part[((int64_t)tid * a.n_split + split) * (D + 2) + 1] = 0.0f;
+            }
+            for (int i = tid; i < G * D; i += NT) part[((int64_t)(i / D) * a.n_split + split) * (D + 2) + 2 + i % D] = 0.0f;
+            return false;
+        }
         list = a.sel_regions + (int64_t)bh * a.n_regions * kSlice;
-        if (tid < CH) first = list[(int64_t)reg0 * kSlice + sub_i + tid * sub_n];   // (inside the region's kSlice words)
+        first = list[(int64_t)reg0 * kSlice + sub_i + tid * sub_n];   // (inside the region's kSlice words: sub_n <= 16)
         count = (int)a.sel_cnt[(int64_t)bh * a.n_regions + reg0];
         if (a.emit_idx) {
             cnt_before = tid < reg0 ? a.sel_cnt[(int64_t)bh * a.n_regions + tid] : 0u;
@@ -178,9 +193,21 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
     }
     // too many candidates to rank here: the caller attends the head from the ordered row instead
     if (SRC == kRowsSweep && n_cand > kSweepCand) return true;
-    float qf[G][8];
+    // the queries wait in LDS (in registers they would cost a workgroup per compute unit)
+    if (tid < LPR) {
 #pragma unroll
-    for (int g = 0; g < G; ++g) qr[g].get(qf[g]);
+        for (int g = 0; g < G; ++g) {
+            float qf[8];
+            qr[g].get(qf);
+            *(float4 *)&s_q[g][tid * 8] = make_float4(qf[0], qf[1], qf[2], qf[3]);
+            *(float4 *)&s_q[g][tid * 8 + 4] = make_float4(qf[4], qf[5], qf[6], qf[7]);
+        }
+    }
+    // kRowsSweep: the K/V row of this thread's entry (paged: a block-table lookup, in flight while
+    // the candidates are ranked)
+    const int n_first = count > sub_i ? (count - sub_i + sub_n - 1) / sub_n : 0;   // entries of this split in its first region
+    int64_t own_row = -1;
+    if (SRC == kRowsSweep && tid < n_first && first >= 0 && first < a.map.max_n) own_row = a.map.row(b, h, first);
 
     float acc[GPG][2];
 #pragma unroll
@@ -255,6 +282,7 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
 #pragma unroll
         for (int j = 0; j < kCandPer; ++j)
             if (slot[j] >= 0) s_cpos[slot[j]] = (int32_t)(uint32_t)e[j];
+        s_own[tid] = own_row;
     }
     __syncthreads();
     const int n_mine = SRC == kRowsSweep ? s_nmine : 0;
@@ -279,71 +307,90 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
     };
     int32_t pend_t = -1;                             // the list entry this thread has yet to write to the row
     int pend_slot = 0;
+    if (SRC == kRowsSweep && emit && tid < n_first) {
+        pend_t = first;
+        pend_slot = entries_before + sub_i + tid * sub_n;
+    }
 
     // one chunk of rows (s_row filled, or kr/vr/rows loaded for the dense source): logits,
-    // running softmax statistics, weighted value rows
+    // running softmax statistics, weighted value rows.  Only the first n_live slots of the chunk
+    // hold rows: passes over the slots behind them are skipped.
     Row8<T> kr[NPASS], vr[NPASS], kn[NPASS], vn[NPASS];
     int64_t rows[NPASS], rown[NPASS];
-    auto attend_chunk = [&]() __attribute__((always_inline)) {
-        if (!DENSE) {
-            // ---- gather this chunk's K and V rows together (one memory latency, not two)
-#pragma unroll
-            for (int p = 0; p < NPASS; ++p) {
-                rows[p] = s_row[p * RPP + wave * RPW + rl];
-                if (rows[p] >= 0) {
-                    kr[p].load((const T *)a.K + rows[p] * D + sub * 8);
-                    vr[p].load((const T *)a.V + rows[p] * D + sub * 8);
-                } else {
-                    kr[p].zero();
-                    vr[p].zero();
-                }
-            }
-            if (SRC == kRowsSweep && pend_t >= 0) {  // (while the rows are on their way)
-                if (pend_slot < 0) {
-                    // a kept candidate: the entries of its region below it (a binary search, in the
-                    // region's head in LDS or past that in memory)
-                    int lo = 0, hi = min(count, kHeadEntries);   // first entry >= the position
-                    while (lo < hi) {
-                        const int mid = (lo + hi) >> 1;
-                        if (s_head[mid] < pend_t) lo = mid + 1; else hi = mid;
-                    }
-                    if (lo == kHeadEntries) {
-                        hi = count;
-                        while (lo < hi) {
-                            const int mid = (lo + hi) >> 1;
-                            if (list[(int64_t)reg0 * kSlice + mid] < pend_t) lo = mid + 1; else hi = mid;
-                        }
-                    }
-                    pend_slot = entries_before + lo;
-                }
-                const int at = pend_slot + kept_below(pend_t);
-                if (at < a.max_k) idx_row[at] = pend_t;
-                pend_t = -1;
-            }
-        }
-        // ---- logits: scale * k.q for every query head of the group
+    // the K and V rows of the first n_live slots of a chunk, from the row numbers in srow: both
+    // fetched together (one memory latency, not two)
+    auto gather = [&](const int64_t *srow, int n_live, Row8<T> *kd, Row8<T> *vd, int64_t *rd) __attribute__((always_inline)) {
+        constexpr int STEP = RPP > 16 ? RPP : 16;
+        const int np = (n_live + STEP - 1) / STEP * STEP / RPP;
 #pragma unroll
         for (int p = 0; p < NPASS; ++p) {
-            float kf[8];
-            kr[p].get(kf);
+            rd[p] = p < np ? srow[p * RPP + wave * RPW + rl] : -1;
+            if (rd[p] >= 0) {
+                kd[p].load((const T *)a.K + rd[p] * D + sub * 8);
+                vd[p].load((const T *)a.V + rd[p] * D + sub * 8);
+            } else {
+                kd[p].zero();
+                vd[p].zero();
+            }
+        }
+    };
+    // kRowsSweep: this thread's pending entry of the index row, written while rows are on their way
+    auto emit_pending = [&]() __attribute__((always_inline)) {
+        if (SRC == kRowsSweep && pend_t >= 0) {
+            if (pend_slot < 0) {
+                // a kept candidate: the entries of its region below it (a binary search, in the
+                // region's head in LDS or past that in memory)
+                int lo = 0, hi = min(count, kHeadEntries);   // first entry >= the position
+                while (lo < hi) {
+                    const int mid = (lo + hi) >> 1;
+                    if (s_head[mid] < pend_t) lo = mid + 1; else hi = mid;
+                }
+                if (lo == kHeadEntries) {
+                    hi = count;
+                    while (lo < hi) {
+                        const int mid = (lo + hi) >> 1;
+                        if (list[(int64_t)reg0 * kSlice + mid] < pend_t) lo = mid + 1; else hi = mid;
+                    }
+                }
+                pend_slot = entries_before + lo;
+            }
+            const int at = pend_slot + kept_below(pend_t);
+            if (at < a.max_k) idx_row[at] = pend_t;
+            pend_t = -1;
+        }
+    };
+    // (kr, vr, rows hold the chunk's rows)
+    auto attend_chunk = [&](int n_live) __attribute__((always_inline)) {
+        constexpr int STEP = RPP > 16 ? RPP : 16;    // whole passes and whole batches of the value product
+        const int live = (n_live + STEP - 1) / STEP * STEP;   // slots worked on
+        const int np = live / RPP;
+        // ---- logits: scale * k.q for every query head of the group
 #pragma unroll
-            for (int g = 0; g < G; ++g) {
+        for (int g = 0; g < G; ++g) {
+            const float4 q0 = *(const float4 *)&s_q[g][sub * 8], q1 = *(const float4 *)&s_q[g][sub * 8 + 4];
+            const float qf[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
+#pragma unroll
+            for (int p = 0; p < NPASS; ++p) {
+                if (p >= np) break;
+                float kf[8];
+                kr[p].get(kf);
                 float dot = 0.0f;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) dot = fmaf(kf[e], qf[g][e], dot);
+                for (int e = 0; e < 8; ++e) dot = fmaf(kf[e], qf[e], dot);
                 dot = row_sum<LPR>(dot);
                 if (sub == 0) s_p[g][p * RPP + wave * RPW + rl] = rows[p] >= 0 ? dot * a.scale : ninf;
             }
         }
         if (VROUNDS == 1) {                          // the value rows ride along with the logits
 #pragma unroll
-            for (int p = 0; p < NPASS; ++p) vr[p].store(&s_v[p * RPP + wave * RPW + rl][sub * 8]);
+            for (int p = 0; p < NPASS; ++p)
+                if (p < np) vr[p].store(&s_v[p * RPP + wave * RPW + rl][sub * 8]);
         }
         __syncthreads();
 
         // ---- running softmax statistics, one wavefront per query head at a time
         for (int g = wave; g < G; g += NWAVE) {
-            const float v = s_p[g][lane];            // CH == 64 == wavefront size
+            const float v = lane < live ? s_p[g][lane] : ninf;   // CH == 64 == wavefront size
             const float m_old = s_m[g];
             const float m_new = fmaxf(m_old, wave_max(v));
             const float p = (v == ninf) ? 0.0f : expf(v - m_new);
@@ -369,6 +416,7 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
         }
 #pragma unroll
         for (int round = 0; round < VROUNDS; ++round) {
+            if (round * VROWS >= live) break;
             if (VROUNDS > 1) {
                 if (round > 0) __syncthreads();      // the previous round's rows have been consumed
 #pragma unroll
@@ -379,7 +427,7 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
             if (g0 < G) {
                 constexpr int RB = 16;               // rows whose LDS reads are issued together
                 static_assert(VROWS % RB == 0, "whole row batches");
-                for (int r = 0; r < VROWS; r += RB) {
+                for (int r = 0; r < VROWS && round * VROWS + r < live; r += RB) {
                     float2 v2[RB];
 #pragma unroll
                     for (int j = 0; j < RB; ++j) v2[j] = pair_f32(&s_v[r + j][2 * cp]);
@@ -433,7 +481,7 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
         if (d_begin < d_end) load_dense(d_begin, kr, vr, rows);
         for (int c0 = d_begin; c0 < d_end; c0 += CH) {
             if (c0 + CH < d_end) load_dense(c0 + CH, kn, vn, rown);
-            attend_chunk();
+            attend_chunk(min(CH, d_end - c0));
 #pragma unroll
             for (int p = 0; p < NPASS; ++p) {
                 kr[p] = kn[p];
@@ -452,10 +500,12 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
                         const int t = c0 == r_begin ? first : list[r];
                         if (t >= 0 && t < a.map.max_n) row = a.map.row(b, h, t);
                     }
-                    s_row[tid] = row;
+                    s_row[0][tid] = row;
                 }
                 __syncthreads();
-                attend_chunk();
+                const int n_live = max(0, min(CH, min(r_end, count) - c0));
+                gather(s_row[0], n_live, kr, vr, rows);
+                attend_chunk(n_live);
             }
         } else {
             // ---- this split's share of its regions, then its candidates
@@ -463,12 +513,15 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
                 const int cnt = reg == reg0 ? count : (int)a.sel_cnt[(int64_t)bh * a.n_regions + reg];
                 const int n_here = cnt > sub_i ? (cnt - sub_i + sub_n - 1) / sub_n : 0;     // entries of this split in the region
                 const int n_rows = n_here + (reg == reg1 - 1 ? n_mine : 0);
-                for (int c0 = 0; c0 < n_rows; c0 += CH) {
+                // the rows of chunk c0 into s_row[buf]
+                auto fill = [&](int c0, int buf) __attribute__((always_inline)) {
                     if (tid < CH) {
                         const int r = c0 + tid;
                         int t = -1;
-                        if (r < n_here) {
-                            t = (c0 == 0 && reg == reg0) ? first : list[(int64_t)reg * kSlice + sub_i + r * sub_n];
+                        const bool ahead = reg == reg0 && r < n_here && r < NT;   // looked up by thread r at the start
+                        if (ahead) {
+                        } else if (r < n_here) {
+                            t = list[(int64_t)reg * kSlice + sub_i + r * sub_n];
                             if (emit) {
                                 pend_t = t;
                                 pend_slot = entries_before + sub_i + r * sub_n;
@@ -480,10 +533,35 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
                                 pend_slot = -1;
                             }
                         }
-                        s_row[tid] = (t >= 0 && t < a.map.max_n) ? a.map.row(b, h, t) : -1;
+                        s_row[buf][tid] = ahead ? s_own[r] : (t >= 0 && t < a.map.max_n) ? a.map.row(b, h, t) : -1;
                     }
+                };
+                // the next chunk's rows are fetched before the current chunk is worked on
+                if (n_rows > 0) {
+                    fill(0, 0);
                     __syncthreads();
-                    attend_chunk();
+                    gather(s_row[0], min(CH, n_rows), kr, vr, rows);
+                    emit_pending();
+                }
+                int buf = 0;
+                for (int c0 = 0; c0 < n_rows; c0 += CH) {
+                    const bool more = c0 + CH < n_rows;
+                    if (more) {
+                        fill(c0 + CH, buf ^ 1);
+                        __syncthreads();
+                        gather(s_row[buf ^ 1], min(CH, n_rows - c0 - CH), kn, vn, rown);
+                        emit_pending();
+                    }
+                    attend_chunk(min(CH, n_rows - c0));
+                    if (more) {
+#pragma unroll
+                        for (int p = 0; p < NPASS; ++p) {
+                            kr[p] = kn[p];
+                            vr[p] = vn[p];
+                            rows[p] = rown[p];
+                        }
+                    }
+                    buf ^= 1;
                 }
             }
         }
@@ -803,6 +881,7 @@ int launch_sweep_decode(socket_ctx *ctx, const void *q, const void *K, const voi
     a.idx = idx; a.n_selected = n_selected;
     a.sel_regions = t.sel_regions; a.sel_cnt = t.sel_cnt; a.n_regions = g.n_regions; a.ssr = g.ssr; a.rpg = g.rpg;
     a.emit_idx = g.rpg == 1 && g.n_regions <= kDecodeThreads;
+    a.seq_len = seq_len;
     a.cand_key = t.cand_key; a.cand_idx = t.cand_idx; a.thr = t.thr;
     const dim3 grid(g.n_split_sweep, g.Hkv, batch);
     int rc = launch_decode<kRowsSweep>(a, nullptr, g, grid, st);
