@@ -526,6 +526,20 @@ static int launch_rows(const HashArgs &a, int Hkv, int batch, int max_rows, hipS
     return SOCKET_OK;
 }
 
+// dynamic LDS of hash_mfma8_kernel: the W slab as fragments, one id-word row per key of every wavefront's block
+template <int D> constexpr size_t hash8_lds() {
+    return (size_t)16 * (D / 16) * 64 * 16 + (size_t)(kHash8Threads / 64) * 64 * 16;
+}
+
+// once per context that uses the fast 8-plane hash: more than 64 KB of dynamic LDS has to be
+// allowed before the first launch
+int hash_prepare(int d) {
+    hipError_t e = hipSuccess;
+    if (d == 64) e = hipFuncSetAttribute((const void *)hash_mfma8_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)hash8_lds<64>());
+    if (d == 128) e = hipFuncSetAttribute((const void *)hash_mfma8_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)hash8_lds<128>());
+    return e == hipSuccess ? SOCKET_OK : SOCKET_EHIP;
+}
+
 template <int D>
 static int launch_mfma8(HashArgs a, uint4 *wfrag, int Hkv, int batch, int max_rows, hipStream_t st) {
     constexpr int NW = kHash8Threads / 64;
@@ -538,15 +552,8 @@ static int launch_mfma8(HashArgs a, uint4 *wfrag, int Hkv, int batch, int max_ro
     const int nblocks = (max_rows + 63) / 64;
     if (per > (nblocks + NW - 1) / NW) per = (nblocks + NW - 1) / NW;
     if (per < 1) per = 1;
-    const size_t lds = (size_t)16 * (D / 16) * 64 * 16 + (size_t)NW * 64 * 16;
-    static bool raised = false;     // more than 64 KB of dynamic LDS has to be allowed once per process
-    if (!raised) {
-        if (hipFuncSetAttribute((const void *)hash_mfma8_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)lds) != hipSuccess) return SOCKET_EHIP;
-        raised = true;
-    }
     dim3 grid(per, Hkv * a.n_chunks, batch);
-    hipLaunchKernelGGL((hash_mfma8_kernel<D>), grid, dim3(kHash8Threads), lds, st, a, (const uint4 *)wfrag);
+    hipLaunchKernelGGL((hash_mfma8_kernel<D>), grid, dim3(kHash8Threads), hash8_lds<D>(), st, a, (const uint4 *)wfrag);
     return SOCKET_OK;
 }
 

@@ -2040,6 +2040,18 @@ int launch_soft_hash(socket_ctx *ctx, const void *q, const void *proj, float tau
     return launch_project(ctx, q, proj, tau, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, batch, st);
 }
 
+// once per context: the packed-id scoring kernel forms its table addresses from LDS address 0,
+// so it must own no static LDS
+int score_prepare(const Geometry &g) {
+    if (g.mode != kSplit) return SOCKET_OK;
+    const bool paged = g.page > 0;
+    score_fn_t fn = g.S == 1 ? (paged ? score_split_kernel<1, true> : score_split_kernel<1, false>)
+                             : (paged ? score_split_kernel<2, true> : score_split_kernel<2, false>);
+    hipFuncAttributes attr;
+    if (hipFuncGetAttributes(&attr, (const void *)fn) != hipSuccess) return SOCKET_EHIP;
+    return attr.sharedSizeBytes == 0 ? SOCKET_OK : SOCKET_EUNSUPPORTED;
+}
+
 int launch_score_keys(socket_ctx *ctx, const void *codes, const float *vnorm,
                       const int32_t *block_table, const int32_t *seq_len, int batch, float *scores,
                       bool want_hist, int *hist_mode, hipStream_t st) {
@@ -2071,15 +2083,7 @@ int launch_score_keys(socket_ctx *ctx, const void *codes, const float *vnorm,
         score_fn_t fn = g.S == 1 ? (paged ? score_split_kernel<1, true> : score_split_kernel<1, false>)
                                  : (paged ? score_split_kernel<2, true> : score_split_kernel<2, false>);
         if (set_lds_limit((const void *)fn, lds) != SOCKET_OK) return SOCKET_EHIP;
-        // the kernel forms its table addresses from LDS address 0: it must own no static LDS
-        static int static_lds[4] = {-1, -1, -1, -1};          // per kernel variant, asked once
-        int &mine = static_lds[(g.S == 1 ? 0 : 2) + (paged ? 1 : 0)];
-        if (mine < 0) {
-            hipFuncAttributes attr;
-            if (hipFuncGetAttributes(&attr, (const void *)fn) != hipSuccess) return SOCKET_EHIP;
-            mine = (int)attr.sharedSizeBytes;
-        }
-        if (mine != 0) return SOCKET_EUNSUPPORTED;
+        // (the kernel forms its table addresses from LDS address 0: score_prepare has checked that it owns no static LDS)
         hipLaunchKernelGGL(fn, dim3(per_bh, g.Hkv, batch), dim3(kSplitThreads), lds, st, a);
         return record_hip(ctx, hipGetLastError());
     }

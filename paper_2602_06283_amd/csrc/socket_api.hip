@@ -188,9 +188,10 @@ int socket_create(socket_ctx **out, const socket_params *p) {
     const int64_t sz_seq = (int64_t)g.max_batch * 4;
     const int64_t sz_part = (int64_t)g.max_batch * g.Hq * kMaxSplits * (g.d + 2) * 4;
     ctx->scratch_bytes = sz_wfrag + sz_tables + sz_tstats + sz_hist + sz_cnt + 2 * sz_cand + sz_staged + sz_regions + sz_selcnt + sz_part + sz_seq;
-    bool ok = hipMalloc((void **)&ctx->tables, sz_tables) == hipSuccess &&
+    bool ok = score_prepare(g) == SOCKET_OK &&
+              hipMalloc((void **)&ctx->tables, sz_tables) == hipSuccess &&
               hipMalloc((void **)&ctx->tstats, sz_tstats) == hipSuccess &&
-              (!fast_hash || hipMalloc(&ctx->wfrag, sz_wfrag) == hipSuccess) &&
+              (!fast_hash || (hipMalloc(&ctx->wfrag, sz_wfrag) == hipSuccess && hash_prepare(g.d) == SOCKET_OK)) &&
               hipMalloc((void **)&ctx->hist, sz_hist) == hipSuccess &&
               hipMalloc((void **)&ctx->counters, sz_cnt) == hipSuccess &&
               hipMalloc((void **)&ctx->cand_key, sz_cand) == hipSuccess &&

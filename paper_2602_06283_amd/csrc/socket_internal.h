@@ -98,6 +98,8 @@ int fill_geometry(const socket_params *p, Geometry *g);  // host-only validation
 int record_hip(socket_ctx *ctx, hipError_t e);
 
 // launchers (each returns a SOCKET_* code)
+int score_prepare(const Geometry &g);   // once per context: checks the packed-id scoring kernel
+int hash_prepare(int d);   // once per context that owns MFMA fragments of W (the fast 8-plane hash)
 int launch_hash_keys(socket_ctx *ctx, const void *K, const void *proj, const int32_t *block_table,
                      const int32_t *row_begin, const int32_t *row_count, int batch, int max_rows,
                      void *codes, hipStream_t st);
