@@ -471,6 +471,7 @@ __global__ __launch_bounds__(kHash8Threads) void hash_mfma8_kernel(HashArgs a, c
         const int r0 = blk * 64;
         const int64_t prow = key_row(r0 + lane);        // the key this lane packs
         const int rot = (begin + r0 + lane) & 15;
+        uint4 done[3];                                  // the key's position groups 0..2, kept until the row is whole
 #pragma unroll 1
         for (int p = 0; p < NCB; ++p) {
             const int sub = p >> 2, q = p & 3;
@@ -502,7 +503,18 @@ __global__ __launch_bounds__(kHash8Threads) void hash_mfma8_kernel(HashArgs a, c
                 o.y = __builtin_amdgcn_alignbyte(x2, x1, sh);
                 o.z = __builtin_amdgcn_alignbyte(x3, x2, sh);
                 o.w = __builtin_amdgcn_alignbyte(x0, x3, sh);
-                if (prow >= 0) *(uint4 *)(Cb + prow * (int64_t)a.Lpad + first_table + sub * 16) = o;
+                // the four groups of a key go out together: 64 adjacent bytes, written back as one
+                // whole line instead of four partial ones a quarter of the block apart
+                if (sub == 0) done[0] = o;
+                else if (sub == 1) done[1] = o;
+                else if (sub == 2) done[2] = o;
+                else if (prow >= 0) {
+                    uint4 *dst = (uint4 *)(Cb + prow * (int64_t)a.Lpad + first_table);
+                    dst[0] = done[0];
+                    dst[1] = done[1];
+                    dst[2] = done[2];
+                    dst[3] = o;
+                }
             }
         }
         if (blk + stride < nblocks) load_keys((blk + stride) * 64);
