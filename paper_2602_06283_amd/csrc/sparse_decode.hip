@@ -100,7 +100,7 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
     constexpr int GPG = (G + NG - 1) / NG;           // query heads per group
 
     __shared__ __align__(16) float s_p[G][CH];       // logits, then softmax numerators
-    __shared__ int64_t s_row[2][CH];                 // K/V row of each chunk entry (-1 = none), two chunks
+    __shared__ int64_t s_row[1][CH];                 // K/V row of each chunk entry (-1 = none)
     __shared__ float s_m[G], s_l[G], s_corr[G];
     __shared__ __align__(16) float s_q[G][D];        // the queries as floats
     __shared__ int32_t s_cpos[SRC == kRowsSweep ? kSweepCand : 1];   // candidates that make the cut, best first
@@ -536,32 +536,12 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
                         s_row[buf][tid] = ahead ? s_own[r] : (t >= 0 && t < a.map.max_n) ? a.map.row(b, h, t) : -1;
                     }
                 };
-                // the next chunk's rows are fetched before the current chunk is worked on
-                if (n_rows > 0) {
-                    fill(0, 0);
-                    __syncthreads();
-                    gather(s_row[0], min(CH, n_rows), kr, vr, rows);
-                    emit_pending();
-                }
-                int buf = 0;
                 for (int c0 = 0; c0 < n_rows; c0 += CH) {
-                    const bool more = c0 + CH < n_rows;
-                    if (more) {
-                        fill(c0 + CH, buf ^ 1);
-                        __syncthreads();
-                        gather(s_row[buf ^ 1], min(CH, n_rows - c0 - CH), kn, vn, rown);
-                        emit_pending();
-                    }
+                    fill(c0, 0);
+                    __syncthreads();
+                    gather(s_row[0], min(CH, n_rows - c0), kr, vr, rows);
+                    emit_pending();
                     attend_chunk(min(CH, n_rows - c0));
-                    if (more) {
-#pragma unroll
-                        for (int p = 0; p < NPASS; ++p) {
-                            kr[p] = kn[p];
-                            vr[p] = vn[p];
-                            rows[p] = rown[p];
-                        }
-                    }
-                    buf ^= 1;
                 }
             }
         }
