@@ -647,7 +647,7 @@ __global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(DecodeArgs 
 // threshold bin holding more candidates than they rank (mass ties only), it orders the row,
 // attends the head from it split after split, and merges it: slow and exact.
 template <typename T, int D, int G>
-__global__ __launch_bounds__(kTopkThreads) void merge_finish_kernel(DecodeArgs a, TopkArgs t) {
+__global__ __launch_bounds__(kTopkThreads, 6) void merge_finish_kernel(DecodeArgs a, TopkArgs t) {
     extern __shared__ __align__(16) char decode_lds[];
     const int h = blockIdx.y, b = blockIdx.z, bh = b * a.map.Hkv + h, tid = threadIdx.x;
     const uint32_t *thr = t.thr + (int64_t)bh * kThrStride;
