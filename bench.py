@@ -31,7 +31,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 
 # HBM bytes per launch of the scoring kernel with the select's histogram, 128K workload, from
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a plain copy (profiles/score_kernel_128k.md)
-PROFILED_SCORE_TRAFFIC = {("128k", 32, 64, 8): (75.7e6, "profiles/score_kernel_128k.md")}
+PROFILED_SCORE_TRAFFIC = {("128k", 32, 64, 8): (77.0e6, "profiles/score_kernel_128k.md")}
 
 WORKLOADS = {
     # name: (n, k, seed)   -- the 128K roofline workload and the 32K one

@@ -63,9 +63,8 @@ __device__ __forceinline__ float2 pair_f32(const uint16_t *p) {
 }
 __device__ __forceinline__ float2 pair_f32(const float *p) { return *(const float2 *)p; }
 
-// dynamic LDS of decode_body<kRowsSweep> while it ranks candidates: their keys (and a quad of
-// padding), then the (rank, position) pairs of its own
-constexpr size_t kSweepRankLds = (size_t)(2 * kSweepCand + 4) * 8;
+// dynamic LDS of decode_body<kRowsSweep> while it ranks candidates: their keys and a quad of padding
+constexpr size_t kSweepRankLds = (size_t)(kSweepCand + 4) * 8;
 
 // dynamic LDS of decode_body: the value tile
 template <typename T, int D> constexpr size_t decode_lds_bytes() {
@@ -224,7 +223,6 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
     const bool emit = SRC == kRowsSweep && a.emit_idx;
     if (SRC == kRowsSweep) {
         unsigned long long *ck = (unsigned long long *)dyn;       // the value tile is not in use yet
-        unsigned long long *mine = ck + kSweepCand + 4;           // (rank, position) of this split's candidates
         if (tid == 0) {
             s_nmine = 0;
             s_nkept = 0;
@@ -252,36 +250,29 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
                 // a shared region's candidates all go to its first split, which holds the region's head
                 const bool here = i < n_cand && reg >= reg0 && reg < reg1 && sub_i == 0;
                 if (i < n_cand && (here || emit)) {
+                    // rank among all candidates, and among those of this split's regions: whoever
+                    // beats a kept candidate is kept as well, so the second count is the
+                    // candidate's place in this split's list
                     const unsigned long long me = ck[i];
-                    int rank = 0;
+                    const uint32_t plo = 0x7fffffffu - (uint32_t)reg1 * kSlice, phi = 0x7fffffffu - (uint32_t)reg0 * kSlice;
+                    auto inside = [&](unsigned long long c) { return (uint32_t)c > plo && (uint32_t)c <= phi; };   // position in [reg0, reg1) * kSlice
+                    int rank = 0, place = 0;
                     for (int o = 0; o < n_cand; o += 4) {
                         const ulonglong2 c0 = *(const ulonglong2 *)&ck[o], c1 = *(const ulonglong2 *)&ck[o + 2];
-                        rank += (c0.x > me) + (c0.y > me) + (c1.x > me) + (c1.y > me);
+                        const bool b0 = c0.x > me, b1 = c0.y > me, b2 = c1.x > me, b3 = c1.y > me;
+                        rank += b0 + b1 + b2 + b3;
+                        place += (b0 && inside(c0.x)) + (b1 && inside(c0.y)) + (b2 && inside(c1.x)) + (b3 && inside(c1.y));
                     }
                     if (rank < need) {
-                        if (here) mine[atomicAdd(&s_nmine, 1)] = ((unsigned long long)rank << 32) | (uint32_t)pp[j];
+                        if (here) {
+                            s_cpos[place] = pp[j];
+                            atomicAdd(&s_nmine, 1);
+                        }
                         if (emit) s_kept[atomicAdd(&s_nkept, 1)] = pp[j];
                     }
                 }
             }
         }
-        __syncthreads();
-        const int nm = s_nmine;                                   // put in rank order: few, so all-pairs again
-        unsigned long long e[kCandPer];
-        int slot[kCandPer];
-#pragma unroll
-        for (int j = 0; j < kCandPer; ++j) {
-            const int i = tid + j * NT;
-            slot[j] = -1;
-            if (i < nm) {
-                e[j] = mine[i];
-                slot[j] = 0;
-                for (int o = 0; o < nm; ++o) slot[j] += mine[o] < e[j];
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < kCandPer; ++j)
-            if (slot[j] >= 0) s_cpos[slot[j]] = (int32_t)(uint32_t)e[j];
         s_own[tid] = own_row;
     }
     __syncthreads();
