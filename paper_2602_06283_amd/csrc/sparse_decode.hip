@@ -23,6 +23,8 @@
 
 namespace sk {
 
+template <bool V> struct IntTag { static constexpr bool value = V; };
+
 // where a workgroup's rows come from
 enum RowSource {
     kRowsIdx = 0,      // its slice of the ordered row idx[b, h, :n_selected]               (Eq. 2)
@@ -277,6 +279,15 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
     }
     __syncthreads();
     const int n_mine = SRC == kRowsSweep ? s_nmine : 0;
+    float qf[SRC == kRowsSweep ? 1 : G][8];
+    if (SRC != kRowsSweep) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const float4 q0 = *(const float4 *)&s_q[g][sub * 8], q1 = *(const float4 *)&s_q[g][sub * 8 + 4];
+            qf[g][0] = q0.x; qf[g][1] = q0.y; qf[g][2] = q0.z; qf[g][3] = q0.w;
+            qf[g][4] = q1.x; qf[g][5] = q1.y; qf[g][6] = q1.z; qf[g][7] = q1.w;
+        }
+    }
     // ---- the index row: entries before this split's region, kept candidates below a position
     int32_t *idx_row = nullptr;
     int entries_before = 0, n_kept = 0;
@@ -351,25 +362,43 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
         }
     };
     // (kr, vr, rows hold the chunk's rows)
-    auto attend_chunk = [&](int n_live) __attribute__((always_inline)) {
+    auto attend_chunk = [&](int n_live, auto whole) __attribute__((always_inline)) {
         constexpr int STEP = RPP > 16 ? RPP : 16;    // whole passes and whole batches of the value product
-        const int live = (n_live + STEP - 1) / STEP * STEP;   // slots worked on
-        const int np = live / RPP;
+        constexpr bool WHOLE = decltype(whole)::value;        // every slot holds a row: nothing to skip
+        const int live = WHOLE ? CH : (n_live + STEP - 1) / STEP * STEP;   // slots worked on
+        const int np = WHOLE ? NPASS : live / RPP;
         // ---- logits: scale * k.q for every query head of the group
+        if (SRC == kRowsSweep) {                     // (queries from LDS: registers decide how many workgroups fit)
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-            const float4 q0 = *(const float4 *)&s_q[g][sub * 8], q1 = *(const float4 *)&s_q[g][sub * 8 + 4];
-            const float qf[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
+            for (int g = 0; g < G; ++g) {
+                const float4 q0 = *(const float4 *)&s_q[g][sub * 8], q1 = *(const float4 *)&s_q[g][sub * 8 + 4];
+                const float qg[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
+#pragma unroll
+                for (int p = 0; p < NPASS; ++p) {
+                    if (p >= np) break;
+                    float kf[8];
+                    kr[p].get(kf);
+                    float dot = 0.0f;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) dot = fmaf(kf[e], qg[e], dot);
+                    dot = row_sum<LPR>(dot);
+                    if (sub == 0) s_p[g][p * RPP + wave * RPW + rl] = rows[p] >= 0 ? dot * a.scale : ninf;
+                }
+            }
+        } else {                                     // (long runs of chunks: queries in registers, a row unpacked once)
 #pragma unroll
             for (int p = 0; p < NPASS; ++p) {
                 if (p >= np) break;
                 float kf[8];
                 kr[p].get(kf);
-                float dot = 0.0f;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) dot = fmaf(kf[e], qf[e], dot);
-                dot = row_sum<LPR>(dot);
-                if (sub == 0) s_p[g][p * RPP + wave * RPW + rl] = rows[p] >= 0 ? dot * a.scale : ninf;
+                for (int g = 0; g < G; ++g) {
+                    float dot = 0.0f;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) dot = fmaf(kf[e], qf[g][e], dot);
+                    dot = row_sum<LPR>(dot);
+                    if (sub == 0) s_p[g][p * RPP + wave * RPW + rl] = rows[p] >= 0 ? dot * a.scale : ninf;
+                }
             }
         }
         if (VROUNDS == 1) {                          // the value rows ride along with the logits
@@ -472,7 +501,8 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
         if (d_begin < d_end) load_dense(d_begin, kr, vr, rows);
         for (int c0 = d_begin; c0 < d_end; c0 += CH) {
             if (c0 + CH < d_end) load_dense(c0 + CH, kn, vn, rown);
-            attend_chunk(min(CH, d_end - c0));
+            if (c0 + CH <= d_end) attend_chunk(CH, IntTag<true>());
+            else attend_chunk(d_end - c0, IntTag<false>());
 #pragma unroll
             for (int p = 0; p < NPASS; ++p) {
                 kr[p] = kn[p];
@@ -496,7 +526,7 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
                 __syncthreads();
                 const int n_live = max(0, min(CH, min(r_end, count) - c0));
                 gather(s_row[0], n_live, kr, vr, rows);
-                attend_chunk(n_live);
+                attend_chunk(n_live, IntTag<false>());
             }
         } else {
             // ---- this split's share of its regions, then its candidates
@@ -532,7 +562,7 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
                     __syncthreads();
                     gather(s_row[0], min(CH, n_rows - c0), kr, vr, rows);
                     emit_pending();
-                    attend_chunk(min(CH, n_rows - c0));
+                    attend_chunk(min(CH, n_rows - c0), IntTag<false>());
                 }
             }
         }
