@@ -69,7 +69,7 @@ def check_codes(layer, codes_t, rows_of):
     (wl.BF16, 2048, 16, 4),
     (wl.BF16, 2048, 128, 8),    # two column chunks of 64 tables
     (wl.BF16, 1024, 100, 8),    # second chunk with 36 live tables: the rest of the row holds 0
-    (wl.BF16, 1024, 64, 10),    # uint16 ids, chunks that split a 64-table group
+    (wl.BF16, 1024, 64, 10),    # packed 10-bit ids, two groups of 32 tables
     (wl.BF16, 1024, 60, 10),    # the paper's main (P, L)
     (wl.BF16, 1024, 24, 5),
     (wl.F32, 512, 40, 12),
