@@ -68,16 +68,18 @@ __device__ __forceinline__ float2 pair_f32(const float *p) { return *(const floa
 // dynamic LDS of decode_body<kRowsSweep> while it ranks candidates: their keys and a quad of padding
 constexpr size_t kSweepRankLds = (size_t)(kSweepCand + 4) * 8;
 
-// dynamic LDS of decode_body: the value tile
-template <typename T, int D> constexpr size_t decode_lds_bytes() {
+// dynamic LDS of decode_body<.., G, .., NT>: the value tile, over which the thread groups' shares
+// of the value sum are added at the end
+template <typename T, int D, int G, int NT = kDecodeThreads> constexpr size_t decode_lds_bytes() {
     constexpr int ROWB = D * (int)sizeof(T);
     constexpr int VROWS = kDecodeChunk * ROWB <= 32768 ? kDecodeChunk : 32768 / ROWB;
-    return (size_t)VROWS * ROWB;
+    constexpr size_t tile = (size_t)VROWS * ROWB, sums = (size_t)(NT / (D / 2)) * G * D * 4;
+    return tile > sums ? tile : sums;
 }
 
 // One split of one (sequence, KV head), run by a whole workgroup of NT threads.
-// SRC says where the rows come from (RowSource).  `dyn` is decode_lds_bytes() of LDS (kRowsSweep:
-// at least kSweepRankLds).  Returns
+// SRC says where the rows come from (RowSource).  `dyn` is decode_lds_bytes<T, D, G, NT>() of LDS
+// (kRowsSweep: at least kSweepRankLds).  Returns
 // true when nothing was done: kRowsSweep with more candidates than a workgroup ranks.
 template <typename T, int D, int G, int SRC, int NT = kDecodeThreads>
 __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int h, int b, char *dyn) {
@@ -90,15 +92,18 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
     constexpr int NPASS = CH / RPP;
     static_assert(CH % RPP == 0, "chunk must be whole passes");
     // The value rows of a chunk go through LDS (at most 32 KB at a time), where every thread
-    // owns two adjacent output channels of GPG query heads and walks the rows itself: no
+    // owns two adjacent output channels of every query head for a share of the rows: no
     // cross-lane sums in the value product.
     constexpr int ROWB = D * (int)sizeof(T);
     constexpr int VROWS = CH * ROWB <= 32768 ? CH : 32768 / ROWB;
     constexpr int VROUNDS = CH / VROWS, PPR = VROWS / RPP;      // passes per round
     static_assert(VROWS % RPP == 0 && VROWS % 4 == 0, "a round is whole passes");
     constexpr int CPAIRS = D / 2;                    // channel pairs
-    constexpr int NG = NT / CPAIRS;      // thread groups, each covering all channels
-    constexpr int GPG = (G + NG - 1) / NG;           // query heads per group
+    constexpr int NG = NT / CPAIRS;      // thread groups, each covering all channels: a group walks its own rows of the tile
+    constexpr int RPR = VROWS / NG;                  // rows of the tile per group
+    static_assert(VROWS % NG == 0 && RPR >= 1, "every group has whole rows of the tile");
+    constexpr int RB = RPR < 16 ? RPR : 16;          // rows whose LDS reads are issued together
+    static_assert(RPR % RB == 0, "whole batches of rows");
 
     __shared__ __align__(16) float s_p[G][CH];       // logits, then softmax numerators
     __shared__ int64_t s_row[1][CH];                 // K/V row of each chunk entry (-1 = none)
@@ -118,7 +123,7 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int bh = b * a.map.Hkv + h;
     const int sub = lane % LPR, rl = lane / LPR;     // this lane's 8-element slice and row slot
-    const int cp = tid % CPAIRS, g0 = (tid / CPAIRS) * GPG;   // this thread's channel pair and first query head
+    const int cp = tid % CPAIRS, grp = tid / CPAIRS;  // this thread's channel pair and row group of the value tile
     const float ninf = -__builtin_inff();
 
     // Splits own fixed ranges of the max_k slots, so no load has to wait for the selected
@@ -210,9 +215,9 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
     int64_t own_row = -1;
     if (SRC == kRowsSweep && tid < n_first && first >= 0 && first < a.map.max_n) own_row = a.map.row(b, h, first);
 
-    float acc[GPG][2];
+    float acc[G][2];
 #pragma unroll
-    for (int gg = 0; gg < GPG; ++gg) acc[gg][0] = acc[gg][1] = 0.0f;
+    for (int g = 0; g < G; ++g) acc[g][0] = acc[g][1] = 0.0f;
     if (tid < G) {
         s_m[tid] = ninf;
         s_l[tid] = 0.0f;
@@ -425,14 +430,12 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
         }
         __syncthreads();
 
-        // ---- weighted value rows
+        // ---- weighted value rows: one read of a row's channel pair serves all G query heads
 #pragma unroll
-        for (int gg = 0; gg < GPG; ++gg) {
-            if (g0 + gg < G) {
-                const float corr = s_corr[g0 + gg];
-                acc[gg][0] *= corr;
-                acc[gg][1] *= corr;
-            }
+        for (int g = 0; g < G; ++g) {
+            const float corr = s_corr[g];
+            acc[g][0] *= corr;
+            acc[g][1] *= corr;
         }
 #pragma unroll
         for (int round = 0; round < VROUNDS; ++round) {
@@ -444,31 +447,31 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
                     vr[round * PPR + p].store(&s_v[p * RPP + wave * RPW + rl][sub * 8]);
                 __syncthreads();
             }
-            if (g0 < G) {
-                constexpr int RB = 16;               // rows whose LDS reads are issued together
-                static_assert(VROWS % RB == 0, "whole row batches");
-                for (int r = 0; r < VROWS && round * VROWS + r < live; r += RB) {
-                    float2 v2[RB];
+            // this group's rows of the tile, RB at a time
 #pragma unroll
-                    for (int j = 0; j < RB; ++j) v2[j] = pair_f32(&s_v[r + j][2 * cp]);
+            for (int rb = 0; rb < RPR; rb += RB) {
+                const int r0 = grp * RPR + rb;
+                if (round * VROWS + r0 >= live) break;
+                float2 v2[RB];
 #pragma unroll
-                    for (int gg = 0; gg < GPG; ++gg) {
-                        if (g0 + gg < G) {
-                            float4 w[RB / 4];
+                for (int j = 0; j < RB; ++j) v2[j] = pair_f32(&s_v[r0 + j][2 * cp]);
 #pragma unroll
-                            for (int j = 0; j < RB / 4; ++j) w[j] = *(const float4 *)&s_p[g0 + gg][round * VROWS + r + 4 * j];
+                for (int g = 0; g < G; ++g) {
+                    float w[RB];
+                    if (RB % 4 == 0) {
 #pragma unroll
-                            for (int j = 0; j < RB / 4; ++j) {
-                                acc[gg][0] = fmaf(w[j].x, v2[4 * j].x, acc[gg][0]);
-                                acc[gg][1] = fmaf(w[j].x, v2[4 * j].y, acc[gg][1]);
-                                acc[gg][0] = fmaf(w[j].y, v2[4 * j + 1].x, acc[gg][0]);
-                                acc[gg][1] = fmaf(w[j].y, v2[4 * j + 1].y, acc[gg][1]);
-                                acc[gg][0] = fmaf(w[j].z, v2[4 * j + 2].x, acc[gg][0]);
-                                acc[gg][1] = fmaf(w[j].z, v2[4 * j + 2].y, acc[gg][1]);
-                                acc[gg][0] = fmaf(w[j].w, v2[4 * j + 3].x, acc[gg][0]);
-                                acc[gg][1] = fmaf(w[j].w, v2[4 * j + 3].y, acc[gg][1]);
-                            }
+                        for (int j = 0; j < RB / 4; ++j) {
+                            const float4 w4 = *(const float4 *)&s_p[g][round * VROWS + r0 + 4 * j];
+                            w[4 * j] = w4.x; w[4 * j + 1] = w4.y; w[4 * j + 2] = w4.z; w[4 * j + 3] = w4.w;
                         }
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < RB; ++j) w[j] = s_p[g][round * VROWS + r0 + j];
+                    }
+#pragma unroll
+                    for (int j = 0; j < RB; ++j) {
+                        acc[g][0] = fmaf(w[j], v2[j].x, acc[g][0]);
+                        acc[g][1] = fmaf(w[j], v2[j].y, acc[g][1]);
                     }
                 }
             }
@@ -568,13 +571,26 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
         }
     }
 
-    // ---- this split's partial result: (max, sum, weighted value sum) per query head
+    // ---- this split's partial result: (max, sum, weighted value sum) per query head.  The
+    //      groups' shares of the value sum are added in a fixed order through LDS (over the tile).
     float *part = a.partials + ((int64_t)(b * a.Hq + h * G) * a.n_split) * (D + 2);
+    {
+        float *s_red = (float *)dyn;                 // [NG][G][D]
 #pragma unroll
-    for (int gg = 0; gg < GPG; ++gg) {
-        const int g = g0 + gg;
-        if (g < G)
-            *(float2 *)&part[((int64_t)g * a.n_split + split) * (D + 2) + 2 + 2 * cp] = make_float2(acc[gg][0], acc[gg][1]);
+        for (int g = 0; g < G; ++g)
+            *(float2 *)&s_red[((size_t)grp * G + g) * D + 2 * cp] = make_float2(acc[g][0], acc[g][1]);
+        __syncthreads();
+        for (int o = tid; o < G * D / 2; o += NT) {  // a channel pair of one query head
+            const int g = o / CPAIRS, c2 = o % CPAIRS;
+            float2 sum = *(const float2 *)&s_red[(size_t)g * D + 2 * c2];
+#pragma unroll
+            for (int k = 1; k < NG; ++k) {
+                const float2 t = *(const float2 *)&s_red[((size_t)k * G + g) * D + 2 * c2];
+                sum.x += t.x;
+                sum.y += t.y;
+            }
+            *(float2 *)&part[((int64_t)g * a.n_split + split) * (D + 2) + 2 + 2 * c2] = sum;
+        }
     }
     if (tid < G) {
         part[((int64_t)tid * a.n_split + split) * (D + 2) + 0] = s_m[tid];
@@ -707,11 +723,11 @@ constexpr int kMergeFinish = -1;                     // merge_finish_kernel
 template <typename T, int D, int G, int WHAT>
 static int launch_decode_one(const DecodeArgs &a, const TopkArgs *t, dim3 grid, hipStream_t st) {
     if constexpr (WHAT == kMergeFinish) {
-        constexpr size_t kLds = decode_lds_bytes<T, D>() > kResolveLds ? decode_lds_bytes<T, D>() : kResolveLds;
+        constexpr size_t kLds = decode_lds_bytes<T, D, G, kTopkThreads>() > kResolveLds ? decode_lds_bytes<T, D, G, kTopkThreads>() : kResolveLds;
         static_assert(kLds <= 64 * 1024, "within the default dynamic LDS limit");
         hipLaunchKernelGGL((merge_finish_kernel<T, D, G>), dim3(G + 1, grid.y, grid.z), dim3(kTopkThreads), kLds, st, a, *t);
     } else {
-        constexpr size_t kTile = decode_lds_bytes<T, D>();
+        constexpr size_t kTile = decode_lds_bytes<T, D, G>();
         constexpr size_t kLds = WHAT == kRowsSweep && kTile < kSweepRankLds ? kSweepRankLds : kTile;
         hipLaunchKernelGGL((sparse_decode_kernel<T, D, G, WHAT>), grid, dim3(kDecodeThreads), kLds, st, a);
     }
