@@ -25,6 +25,9 @@ namespace sk {
 
 template <bool V> struct IntTag { static constexpr bool value = V; };
 
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4_t;
+
 // where a workgroup's rows come from
 enum RowSource {
     kRowsIdx = 0,      // its slice of the ordered row idx[b, h, :n_selected]               (Eq. 2)
@@ -108,7 +111,16 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
     __shared__ __align__(16) float s_p[G][CH];       // logits, then softmax numerators
     __shared__ int64_t s_row[1][CH];                 // K/V row of each chunk entry (-1 = none)
     __shared__ float s_m[G], s_l[G], s_corr[G];
-    __shared__ __align__(16) float s_q[G][D];        // the queries as floats
+    // bf16 caches: the logits of a chunk are one 16-row MFMA tile per wavefront (rows = keys,
+    // columns = query heads, padded to 16), K fetched straight into A-operand registers: lane
+    // (row = lane % 16, group kg = lane / 16) holds channels 32 s + 8 kg .. + 7 of its row for
+    // k-step s.  fp32 caches keep the FMA + DPP row sums.
+    constexpr bool MF = sizeof(T) == 2;
+    constexpr int KST = D / 32;                      // MFMA k-steps
+    constexpr int NLW = CH / 16;                     // wavefronts that hold a tile of the chunk
+    static_assert(NLW <= NWAVE, "a chunk's tiles fit the workgroup's wavefronts");
+    __shared__ __align__(16) float s_q[MF ? 1 : G][MF ? 8 : D];          // the queries as floats
+    __shared__ __align__(16) uint16_t s_qb[MF ? G : 1][MF ? D : 8];      // the queries as stored (bf16)
     __shared__ int32_t s_cpos[SRC == kRowsSweep ? kSweepCand : 1];   // candidates that make the cut, best first
     // kRowsSweep, for the index row: every kept candidate's position (any order, padded with
     // INT_MAX to whole quads), the head of the first region, the entry counts of the regions before it
@@ -203,10 +215,14 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
     if (tid < LPR) {
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            float qf[8];
-            qr[g].get(qf);
-            *(float4 *)&s_q[g][tid * 8] = make_float4(qf[0], qf[1], qf[2], qf[3]);
-            *(float4 *)&s_q[g][tid * 8 + 4] = make_float4(qf[4], qf[5], qf[6], qf[7]);
+            if (MF) {
+                qr[g].store(&s_qb[g][tid * 8]);
+            } else {
+                float qf[8];
+                qr[g].get(qf);
+                *(float4 *)&s_q[g][tid * 8] = make_float4(qf[0], qf[1], qf[2], qf[3]);
+                *(float4 *)&s_q[g][tid * 8 + 4] = make_float4(qf[4], qf[5], qf[6], qf[7]);
+            }
         }
     }
     // kRowsSweep: the K/V row of this thread's entry (paged: a block-table lookup, in flight while
@@ -284,8 +300,8 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
     }
     __syncthreads();
     const int n_mine = SRC == kRowsSweep ? s_nmine : 0;
-    float qf[SRC == kRowsSweep ? 1 : G][8];
-    if (SRC != kRowsSweep) {
+    float qf[(SRC == kRowsSweep || MF) ? 1 : G][8];
+    if (SRC != kRowsSweep && !MF) {
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             const float4 q0 = *(const float4 *)&s_q[g][sub * 8], q1 = *(const float4 *)&s_q[g][sub * 8 + 4];
@@ -322,21 +338,34 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
     // one chunk of rows (s_row filled, or kr/vr/rows loaded for the dense source): logits,
     // running softmax statistics, weighted value rows.  Only the first n_live slots of the chunk
     // hold rows: passes over the slots behind them are skipped.
-    Row8<T> kr[NPASS], vr[NPASS], kn[NPASS], vn[NPASS];
+    Row8<T> kr[MF ? 1 : NPASS], vr[NPASS], kn[MF ? 1 : NPASS], vn[NPASS];
+    uint4 ka[MF ? KST : 1], kan[MF ? KST : 1];       // K in A-operand layout (bf16 caches)
+    bool kvalid = false, kvalidn = false;            // this lane's tile row holds a key
     int64_t rows[NPASS], rown[NPASS];
     // the K and V rows of the first n_live slots of a chunk, from the row numbers in srow: both
     // fetched together (one memory latency, not two)
-    auto gather = [&](const int64_t *srow, int n_live, Row8<T> *kd, Row8<T> *vd, int64_t *rd) __attribute__((always_inline)) {
+    auto gather = [&](const int64_t *srow, int n_live, Row8<T> *kd, uint4 *kad, bool &kval, Row8<T> *vd, int64_t *rd) __attribute__((always_inline)) {
         constexpr int STEP = RPP > 16 ? RPP : 16;
-        const int np = (n_live + STEP - 1) / STEP * STEP / RPP;
+        const int live = (n_live + STEP - 1) / STEP * STEP;
+        const int np = live / RPP;
+        if (MF) {
+            kval = false;
+            if (wave < NLW && wave * 16 < live) {
+                const int64_t row = srow[wave * 16 + (lane & 15)];
+                kval = row >= 0;
+                const T *src = (const T *)a.K + (kval ? row : 0) * D + 8 * (lane >> 4);   // (a slot without a key reads row 0: never used)
+#pragma unroll
+                for (int st = 0; st < KST; ++st) kad[st] = *(const uint4 *)(src + 32 * st);
+            }
+        }
 #pragma unroll
         for (int p = 0; p < NPASS; ++p) {
             rd[p] = p < np ? srow[p * RPP + wave * RPW + rl] : -1;
             if (rd[p] >= 0) {
-                kd[p].load((const T *)a.K + rd[p] * D + sub * 8);
+                if (!MF) kd[p].load((const T *)a.K + rd[p] * D + sub * 8);
                 vd[p].load((const T *)a.V + rd[p] * D + sub * 8);
             } else {
-                kd[p].zero();
+                if (!MF) kd[p].zero();
                 vd[p].zero();
             }
         }
@@ -373,7 +402,28 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
         const int live = WHOLE ? CH : (n_live + STEP - 1) / STEP * STEP;   // slots worked on
         const int np = WHOLE ? NPASS : live / RPP;
         // ---- logits: scale * k.q for every query head of the group
-        if (SRC == kRowsSweep) {                     // (queries from LDS: registers decide how many workgroups fit)
+        if (MF) {
+            if (wave < NLW && wave * 16 < live) {
+                const int g = lane & 15, kg = lane >> 4;
+                floatx4_t c = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                for (int st = 0; st < KST; ++st) {
+                    union { uint4 u; bf16x8_t v; } ua, ub;
+                    ua.u = ka[st];
+                    ub.u = g < G ? *(const uint4 *)&s_qb[g < G ? g : 0][32 * st + 8 * kg] : make_uint4(0, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ua.v, ub.v, c, 0, 0, 0);
+                }
+                // c[e] = logit of tile row 4 kg + e for query head g; whether that row holds a key
+                // is known to the lane that fetched it
+                const unsigned long long have = __ballot(kvalid);
+                if (g < G) {
+                    float o[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = ((have >> (4 * kg + e)) & 1ull) ? c[e] * a.scale : ninf;
+                    *(float4 *)&s_p[g][wave * 16 + 4 * kg] = make_float4(o[0], o[1], o[2], o[3]);
+                }
+            }
+        } else if (SRC == kRowsSweep) {              // (queries from LDS: registers decide how many workgroups fit)
 #pragma unroll
             for (int g = 0; g < G; ++g) {
                 const float4 q0 = *(const float4 *)&s_q[g][sub * 8], q1 = *(const float4 *)&s_q[g][sub * 8 + 4];
@@ -487,30 +537,45 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
         const int d_per = (((total + CH - 1) / CH + a.n_split - 1) / a.n_split) * CH;
         const int d_begin = split * d_per;
         const int d_end = min(total, d_begin + d_per);
-        auto load_dense = [&](int c0, Row8<T> *kd, Row8<T> *vd, int64_t *rd) __attribute__((always_inline)) {
+        auto load_dense = [&](int c0, Row8<T> *kd, uint4 *kad, bool &kval, Row8<T> *vd, int64_t *rd) __attribute__((always_inline)) {
+            if (MF) {
+                kval = false;
+                if (wave < NLW) {
+                    const int t = c0 + wave * 16 + (lane & 15);
+                    kval = t < d_end;
+                    const T *src = (const T *)a.K + (kval ? a.map.row(b, h, t) : 0) * D + 8 * (lane >> 4);
+#pragma unroll
+                    for (int st = 0; st < KST; ++st) kad[st] = *(const uint4 *)(src + 32 * st);
+                }
+            }
 #pragma unroll
             for (int p = 0; p < NPASS; ++p) {
                 const int t = c0 + p * RPP + wave * RPW + rl;
                 rd[p] = t < d_end ? a.map.row(b, h, t) : -1;
                 if (rd[p] >= 0) {
-                    kd[p].load((const T *)a.K + rd[p] * D + sub * 8);
+                    if (!MF) kd[p].load((const T *)a.K + rd[p] * D + sub * 8);
                     vd[p].load((const T *)a.V + rd[p] * D + sub * 8);
                 } else {
-                    kd[p].zero();
+                    if (!MF) kd[p].zero();
                     vd[p].zero();
                 }
             }
         };
-        if (d_begin < d_end) load_dense(d_begin, kr, vr, rows);
+        if (d_begin < d_end) load_dense(d_begin, kr, ka, kvalid, vr, rows);
         for (int c0 = d_begin; c0 < d_end; c0 += CH) {
-            if (c0 + CH < d_end) load_dense(c0 + CH, kn, vn, rown);
+            if (c0 + CH < d_end) load_dense(c0 + CH, kn, kan, kvalidn, vn, rown);
             if (c0 + CH <= d_end) attend_chunk(CH, IntTag<true>());
             else attend_chunk(d_end - c0, IntTag<false>());
 #pragma unroll
             for (int p = 0; p < NPASS; ++p) {
-                kr[p] = kn[p];
+                if (!MF) kr[p] = kn[p];
                 vr[p] = vn[p];
                 rows[p] = rown[p];
+            }
+            if (MF) {
+#pragma unroll
+                for (int st = 0; st < KST; ++st) ka[st] = kan[st];
+                kvalid = kvalidn;
             }
         }
     } else {
@@ -528,7 +593,7 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
                 }
                 __syncthreads();
                 const int n_live = max(0, min(CH, min(r_end, count) - c0));
-                gather(s_row[0], n_live, kr, vr, rows);
+                gather(s_row[0], n_live, kr, ka, kvalid, vr, rows);
                 attend_chunk(n_live, IntTag<false>());
             }
         } else {
@@ -563,7 +628,7 @@ __device__ __forceinline__ bool decode_body(const DecodeArgs &a, int split, int 
                 for (int c0 = 0; c0 < n_rows; c0 += CH) {
                     fill(c0, 0);
                     __syncthreads();
-                    gather(s_row[0], min(CH, n_rows - c0), kr, vr, rows);
+                    gather(s_row[0], min(CH, n_rows - c0), kr, ka, kvalid, vr, rows);
                     emit_pending();
                     attend_chunk(min(CH, n_rows - c0), IntTag<false>());
                 }
