@@ -1026,7 +1026,10 @@ def test_sweep_hash_then_score(L, P):
                                             (24, 5, 1, wl.F32),        # fewer than 64 tables: replicated columns
                                             (60, 10, 2, wl.BF16),      # groups of 32 tables ("split")
                                             (40, 12, 2, wl.BF16),      # two factors per query head ("factor")
-                                            (130, 6, 8, wl.BF16)])     # more than 64 tables, a full group of 8
+                                            (130, 6, 8, wl.BF16),      # more than 64 tables, a full group of 8
+                                            # the batched pass by groups of 128 columns of W, its other shapes:
+                                            (64, 8, 8, wl.BF16), (48, 4, 8, wl.BF16), (72, 8, 1, wl.BF16),
+                                            (32, 4, 2, wl.BF16)])
 def test_bucket_probs_match_oracle_entry_by_entry(L, P, G, kv_dtype):
     """Alg. 2: every one of the L * 2^P bucket probabilities the context holds after
     socket_soft_hash, read back with socket_bucket_probs, against the oracle's R-way softmax
@@ -1068,6 +1071,28 @@ def test_bucket_probs_match_oracle_entry_by_entry(L, P, G, kv_dtype):
                 if want is not None:
                     assert np.abs(got[b, h] - want).max() <= 1e-6
         ctx.close()
+
+
+@pytest.mark.parametrize("d,kv_dtype,G,P", [(64, wl.BF16, 4, 8), (64, wl.F32, 2, 8), (64, wl.F32, 8, 4), (256, wl.BF16, 2, 8)])
+def test_bucket_probs_other_head_widths(d, kv_dtype, G, P):
+    """Alg. 2 for a batch of three sequences at head widths 64 and 256 (the batched projection
+    pass takes different routes by width and element type): every bucket probability against
+    the oracle."""
+    _need_gpu()
+    B, Hkv, L = 3, 2, 64
+    layer = small_layer(seed=137, B=B, Hq=Hkv * G, Hkv=Hkv, d=d, n=64, L=L, P=P, k=8, kv_dtype=kv_dtype)
+    ctx = hz.make_ctx(layer)
+    qd, Wd = hz.dev(layer.q, layer.kv_dtype), hz.dev(layer.W, layer.kv_dtype)
+    probs = torch.full((B, Hkv, L, 1 << P), -1.0, dtype=torch.float32, device="cuda")
+    ctx.soft_hash(qd, Wd, 0.5, B)
+    ctx.bucket_probs(B, probs)
+    torch.cuda.synchronize()
+    got = probs.cpu().numpy().astype(np.float64)
+    for b in range(B):
+        for h in range(Hkv):
+            want = hz.oracle_probs(layer, b, h, tau=0.5).mean(axis=0)
+            assert np.all(np.abs(got[b, h] - want) <= 3e-7 * want + 1e-37), (b, h)
+    ctx.close()
 
 
 def test_binned_score_and_select_pair_equals_the_plain_calls():
