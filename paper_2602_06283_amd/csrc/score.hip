@@ -1688,7 +1688,12 @@ template <int U, int EPL> struct SplitSet {
     float carry[EPL], w[EPL];
 };
 
-template <int S, bool PAGED>
+// KEEP: no wavefront has more than kKeepTurns turns, and the partial sums of its keys stay in
+// LDS (behind the table and the histogram) from one group of tables to the next; otherwise they
+// travel through `scores`.
+constexpr int kKeepTurns = 5;
+
+template <int S, bool PAGED, bool KEEP>
 __global__ __launch_bounds__(kSplitThreads) void score_split_kernel(ScoreArgs a) {
     extern __shared__ float tbl[];
     constexpr int GT = 16 * S;                       // tables per group
@@ -1717,6 +1722,7 @@ __global__ __launch_bounds__(kSplitThreads) void score_split_kernel(ScoreArgs a)
     const int n4 = group_words >> 2;                 // <= TP * kSplitThreads
     uint32_t *lhist = (uint32_t *)(tbl + group_words);
     float *s_bin = (float *)(lhist + kHistBins);     // [2], present with a histogram only
+    float *s_keep = a.hist ? s_bin + 4 : (float *)lhist;   // [NW][kKeepTurns][EPL][64] partial sums (KEEP)
     const char *cb = (const char *)a.codes;
     float bin_lo = 0.0f, bin_inv = 0.0f;
 
@@ -1730,6 +1736,7 @@ __global__ __launch_bounds__(kSplitThreads) void score_split_kernel(ScoreArgs a)
     const int first_p0 = ((int)blockIdx.x * NW + wave) * U;
     const int nturn = first_p0 < npass ? (npass - first_p0 + stride - 1) / stride : 0;
     const float *wsrc = vn ? vn : out;               // weights, or anything loadable
+    constexpr bool in_regs = KEEP;
 
     // this lane's part of a string address that does not change from turn to turn: its token's
     // tile among the tiles of a pass, its row in the tile, its string in the row
@@ -1766,11 +1773,13 @@ __global__ __launch_bounds__(kSplitThreads) void score_split_kernel(ScoreArgs a)
             key = key < seq ? key : 0;
             // (with a single turn per group the partial sums are written by the turn that is
             // still ahead when this runs: process() fetches them itself then)
-            st.carry[j] = out[key];
+            if (!in_regs) st.carry[j] = out[key];
             st.w[j] = wsrc[key];
         }
     };
     auto process = [&](const Set &st, int grp, int tix) __attribute__((always_inline)) {
+        constexpr bool KEPT = KEEP;
+        float *kept = s_keep + ((wave * kKeepTurns + tix) * EPL) * 64 + lane;   // [j] at stride 64
         const int base = (first_p0 + tix * stride) * KPW;
         const bool first = grp == 0, last = grp == a.rounds - 1;
         float sum[U];
@@ -1810,10 +1819,18 @@ __global__ __launch_bounds__(kSplitThreads) void score_split_kernel(ScoreArgs a)
             }
             const int key = base + (j * S + sub) * KPW + kk;
             if (key >= seq) continue;
-            if (!first) v += nturn == 1 ? out[key] : st.carry[j];
-            if (!last) {
-                if (!dd) out[key] = v;
-                continue;
+            if (KEPT) {
+                if (!first) v += kept[j * 64];
+                if (!last) {
+                    kept[j * 64] = v;
+                    continue;
+                }
+            } else {
+                if (!first) v += nturn == 1 ? out[key] : st.carry[j];
+                if (!last) {
+                    if (!dd) out[key] = v;
+                    continue;
+                }
             }
             if (dd) {
                 v = ninf;
@@ -2040,18 +2057,26 @@ int launch_soft_hash(socket_ctx *ctx, const void *q, const void *proj, float tau
     return launch_project(ctx, q, proj, tau, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, batch, st);
 }
 
+static score_fn_t pick_split(int S, bool paged, bool keep) {
+    if (S == 1) return paged ? (keep ? score_split_kernel<1, true, true> : score_split_kernel<1, true, false>)
+                             : (keep ? score_split_kernel<1, false, true> : score_split_kernel<1, false, false>);
+    return paged ? (keep ? score_split_kernel<2, true, true> : score_split_kernel<2, true, false>)
+                 : (keep ? score_split_kernel<2, false, true> : score_split_kernel<2, false, false>);
+}
+
 // once per context: the packed-id scoring kernel forms its table addresses from LDS address 0,
 // so it must own no static LDS
 int score_prepare(const Geometry &g) {
     if (g.mode != kSplit) return SOCKET_OK;
     const bool paged = g.page > 0;
-    score_fn_t fn = g.S == 1 ? (paged ? score_split_kernel<1, true> : score_split_kernel<1, false>)
-                             : (paged ? score_split_kernel<2, true> : score_split_kernel<2, false>);
     hipFuncAttributes attr;
-    if (hipFuncGetAttributes(&attr, (const void *)fn) != hipSuccess) return SOCKET_EHIP;
-    return attr.sharedSizeBytes == 0 ? SOCKET_OK : SOCKET_EUNSUPPORTED;
+    for (int keep = 0; keep < 2; ++keep) {
+        score_fn_t fn = pick_split(g.S, paged, keep != 0);
+        if (hipFuncGetAttributes(&attr, (const void *)fn) != hipSuccess) return SOCKET_EHIP;
+        if (attr.sharedSizeBytes != 0) return SOCKET_EUNSUPPORTED;
+    }
+    return SOCKET_OK;
 }
-
 int launch_score_keys(socket_ctx *ctx, const void *codes, const float *vnorm,
                       const int32_t *block_table, const int32_t *seq_len, int batch, float *scores,
                       bool want_hist, int *hist_mode, hipStream_t st) {
@@ -2078,10 +2103,14 @@ int launch_score_keys(socket_ctx *ctx, const void *codes, const float *vnorm,
         if (per_bh > turns) per_bh = turns;
         if (per_bh < 1) per_bh = 1;
         a.hist = want_hist ? ctx->hist : nullptr;
-        const size_t lds = (size_t)g.R * g.GT * 4 + (a.hist ? kHistBins * 4 + 16 : 0);
+        size_t lds = (size_t)g.R * g.GT * 4 + (a.hist ? kHistBins * 4 + 16 : 0);
         const bool paged = g.page > 0;
-        score_fn_t fn = g.S == 1 ? (paged ? score_split_kernel<1, true> : score_split_kernel<1, false>)
-                                 : (paged ? score_split_kernel<2, true> : score_split_kernel<2, false>);
+        // partial sums in LDS when no wavefront has more than kKeepTurns turns and they fit
+        const int turns_per_wave = (turns + per_bh - 1) / per_bh;
+        const size_t keep_bytes = (size_t)(kSplitThreads / 64) * kKeepTurns * (kSplitU / g.S) * 64 * 4;
+        const bool keep = g.rounds > 1 && turns_per_wave <= kKeepTurns && lds + keep_bytes <= 160 * 1024;
+        if (keep) lds += keep_bytes;
+        score_fn_t fn = pick_split(g.S, paged, keep);
         if (set_lds_limit((const void *)fn, lds) != SOCKET_OK) return SOCKET_EHIP;
         // (the kernel forms its table addresses from LDS address 0: score_prepare has checked that it owns no static LDS)
         hipLaunchKernelGGL(fn, dim3(per_bh, g.Hkv, batch), dim3(kSplitThreads), lds, st, a);
