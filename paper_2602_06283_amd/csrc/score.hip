@@ -1347,6 +1347,7 @@ __global__ __launch_bounds__(kScoreThreads, (MODE == kDirect && S == 4 && PAGED)
     static_assert(U % S == 0, "each lane of a key's group emits U/S results");
     constexpr int TPU = WKEYS / 16;                  // 16-key tiles per unit (a tile never straddles a page)
     constexpr int RPB = kBlkTiles / (NW * TPU);      // rounds of the workgroup whose block ids fit in LDS at a time
+    constexpr int kTableCost = 2 * NW;                   // a table load, in units (one per wavefront): measured 2-3 us
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int h = blockIdx.y, slot = blockIdx.x, nslot = gridDim.x;
     const int max_n = a.map.max_n;
@@ -1375,12 +1376,19 @@ __global__ __launch_bounds__(kScoreThreads, (MODE == kDirect && S == 4 && PAGED)
             s_len[b] = v < 0 ? 0 : (v > max_n ? max_n : v);
         }
         __syncthreads();
-        // this workgroup's run of units: the first (total mod nslot) workgroups take one more
+        // this workgroup's run of units: the first (total mod nslot) workgroups take one more.
+        // Runs are cut in cost, not in units: entering a sequence costs a load of its table,
+        // about what kTableCost units take, so a workgroup whose run crosses into the next
+        // sequence is given that many units less.
         int total = 0;
-        for (int b = 0; b < nbatch; ++b) total += (s_len[b] + WKEYS - 1) / WKEYS;
+        for (int b = 0; b < nbatch; ++b) total += (s_len[b] + WKEYS - 1) / WKEYS + kTableCost;
         const int per = total / nslot, extra = total - per * nslot;
-        u0 = slot * per + (slot < extra ? slot : extra);
-        u1 = u0 + per + (slot < extra ? 1 : 0);
+        // Workgroups go to the 8 XCDs round-robin: neighbouring runs (mostly the same sequence,
+        // so the same probability table) are given to workgroups of one XCD, whose L2 then
+        // serves the table to all but the first of them.
+        const int run_id = (nslot & 7) == 0 ? (slot & 7) * (nslot >> 3) + (slot >> 3) : slot;
+        u0 = run_id * per + (run_id < extra ? run_id : extra);
+        u1 = u0 + per + (run_id < extra ? 1 : 0);
     }
 
     auto run = [&](auto base0) {
@@ -1403,11 +1411,12 @@ __global__ __launch_bounds__(kScoreThreads, (MODE == kDirect && S == 4 && PAGED)
                 out[key] = ninf;
             int ub, ue, ustride;
             if (BATCHED) {
-                const int lo = u0 > cum ? u0 : cum, hi = u1 < cum + nu ? u1 : cum + nu;
-                ub = lo - cum;                       // this workgroup's units of the sequence
-                ue = hi - cum;
+                const int first = cum + kTableCost;  // cost position of the sequence's first unit
+                const int lo = u0 > first ? u0 : first, hi = u1 < first + nu ? u1 : first + nu;
+                ub = lo - first;                     // this workgroup's units of the sequence
+                ue = hi - first;
                 ustride = NW;
-                cum += nu;
+                cum += nu + kTableCost;
             } else {
                 ub = slot * NW;                      // its wavefronts' first units; the next ones nslot * NW further on
                 ue = nu;
