@@ -1197,7 +1197,8 @@ __global__ __launch_bounds__(kGroupThreads) void project_group_kernel(ProjectArg
                 dev2 += (float)(dv * dv);
             }
             if (l < a.Lpad)
-                for (int cp = 0; cp < copies; ++cp) Tg[((int64_t)c64 * R + r) * 64 + lp + cp * lw] = (float)mean;
+                // (streaming stores: the tables are read next by workgroups of every XCD, through memory)
+                for (int cp = 0; cp < copies; ++cp) __builtin_nontemporal_store((float)mean, &Tg[((int64_t)c64 * R + r) * 64 + lp + cp * lw]);
         }
         s_part[tid] = dev2;
         s_part[NT + tid] = nu1;
