@@ -543,8 +543,10 @@ def sweep(tools, wl, steps=256, B=4, n=65536, seed=1004):
 def hard_vs_soft(tools, wl, n=32768, seed=1001):
     """Scoring cost of the hard LSH scorer (Eq. 3, hard form) at (P, L) = (2, 300/400/500) beside
     the soft scorer at the paper's main setting (10, 60), one sequence of 32768 keys, 8 KV heads:
-    the shape of the paper's cost table (time grows with L; many 2-plane tables cost more
-    than 60 ten-plane ones).  Each point: 8 caches of distinct ids so that HBM is what is read."""
+    the paper's cost table has many 2-plane tables cost 2.7-4.2x what 60 ten-plane ones cost.
+    Here four 2-bit ids share a byte and a byte's look-up returns the sum of its four tables'
+    terms, so (2, 300..500) reads 128 bytes per key (two chunks of 64 bytes) against 80 at
+    (10, 60).  Each point: caches of distinct ids so that HBM is what is read."""
     torch, sk, stream = tools.torch, tools.sk, tools.stream
     Hq, Hkv, d = 32, 8, 128
     cap = n + 16
@@ -614,7 +616,7 @@ def cpu_baseline(layer0, k, n, Hq, Hkv, d, L, P, tau, NL, budget_s):
     Vh = V[0, :, :n + 1].float().cpu().numpy()
     qh = q[0].float().cpu().numpy()
     Wh = W.float().cpu().numpy()
-    rows = hz.rows_from_device(codes.view(1, Hkv, -1, hz.lpad_of(L) * (1 if P <= 8 else 2)) if not hz.packed(P)
+    rows = hz.rows_from_device(codes.view(1, Hkv, -1, hz.lpad_of(L, P) * (1 if P <= 8 else 2)) if not hz.packed(P)
                                else codes.view(1, Hkv, -1, 20 * hz.lpad_of(L)), L, P)
     nat = hz.codes_to_natural(rows[0, :, :n + 1], L, P=P).astype(np.uint16)
     G = Hq // Hkv

@@ -56,7 +56,13 @@
  *            A block keeps bytes 0..15 of the strings in 16 rows (token t mod 16) of GT
  *            bytes, string `sub` at byte 16*sub, followed by 16 rows of GT/4 bytes with
  *            bytes 16..19 of the strings, string `sub` at byte 4*sub.
- *            socket_codes_bytes() and socket_code_location() describe all three forms.
+ *            P = 1, 2 and 4 keep f = 8/P ids to a byte when L is a multiple of f and L/f is
+ *            32..128 (else a byte per id, as above): the byte for tables f*m .. f*m+f-1, table
+ *            f*m+j in bits [P*j, P*j+P), is the 8-plane id of columns 8m .. 8m+7 of proj, and
+ *            the code row is that of L/f eight-plane tables (Lpad and positions above with
+ *            L/f for L and m for l).  The look-up table of such a byte holds the sum of its f
+ *            tables' probabilities, so Eq. 3 stays one look-up per byte.
+ *            socket_codes_bytes() and socket_code_location() describe all four forms.
  *   bucket id: bit i is 1 when hyperplane i gives a projection >= 0.
  *   scores   [B, Hkv, max_n] float32, logical token order; -inf for t >= seq_len
  *   idx      [B, Hkv, max_k] int32 logical token positions in ascending order,
@@ -110,7 +116,8 @@ typedef struct socket_params {
  * the 160 KB of LDS). */
 int socket_validate_params(const socket_params *p);
 
-/* Padded codes-per-token (Lpad above) for L tables; -1 when L is out of range. */
+/* Padded codes-per-token (Lpad above) for L tables; -1 when L is out of range.  (Ids that
+ * share bytes: call it with the number of bytes, L*P/8.) */
 int32_t socket_codes_per_token(int32_t L);
 
 /* Position of table l's bucket id inside token t's Lpad-long code row. */
@@ -122,7 +129,8 @@ int64_t socket_codes_bytes(int32_t L, int32_t P, int64_t tokens);
 
 /* Where the bucket id of table l (< Lpad) of token t is kept, as byte offsets from the start
  * of the (sequence or block, KV head) slab: with B0 the byte at *lo_byte and B1 the byte at
- * *hi_byte (taken as 0 when *hi_byte = -1, which is the case for P <= 8),
+ * *hi_byte (taken as 0 when *hi_byte = -1, which is the case for P <= 8; l < L where ids
+ * share bytes),
  *     id = ((B0 | B1 << 8) >> *hi_shift) & (2^P - 1).
  * Host-only; 0 or SOCKET_EINVAL. */
 int socket_code_location(int32_t L, int32_t P, int32_t l, int32_t t, int64_t *lo_byte,
@@ -240,7 +248,8 @@ int socket_reset(socket_ctx *ctx, void *stream);
  * Alg. 2 read-back: the bucket probabilities the context holds after socket_soft_hash,
  * socket_hard_hash, socket_score or socket_decode_step, as the scoring pass looks them up:
  *     probs[b, h, l, r] = (1/G) * sum_{g in group(h)} p_g^(l)(r | q)
- * device float32 [batch, Hkv, L, R], R = 2^P, whatever layout the context keeps them in.
+ * device float32 [batch, Hkv, L, R], R = 2^P, whatever layout the context keeps them in
+ * (ids that share bytes: a per-table copy the projection pass writes beside the summed tables).
  * For inspection and tests; not on the decode path.
  */
 int socket_bucket_probs(socket_ctx *ctx, int32_t batch, float *probs, void *stream);

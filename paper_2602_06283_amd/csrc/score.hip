@@ -35,6 +35,9 @@ struct ProjectArgs {
     RowMap map;
     int d, G, Hkv, Hq, L, P, LP, Lpad, S, cb, rounds, R, mode, Plo, Phi, Rlo, Rhi, table_rows;
     int GT;                 // split mode: tables per group
+    int pf, Pu;             // ids per byte and the caller's P when ids share bytes (else 1, P)
+    double tmean;           // mean of a table's entries: pf / 2^Pu
+    float *subprobs;        // ids that share bytes: [B*Hkv][L*pf][2^Pu] probabilities of the caller's tables
     int batch, nb;          // sequences in the call; sequences one workgroup serves (batched kernel)
     int cols_magic;         // ceil(2^16 / P): x / P == (x * cols_magic) >> 16 for x < 2^12
     int64_t table_words;
@@ -383,6 +386,28 @@ __global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
         for (int i = 0; i < 8; ++i) f[i] = sig[(g * kPlanePad + s0 + i) * 2 + ((bits >> i) & 1)];
         return ((f[0] * f[1]) * (f[2] * f[3])) * ((f[4] * f[5]) * (f[6] * f[7]));
     };
+    // ids that share a byte (pf tables of Pu planes each): a look-up with the byte gives the sum
+    // of the pf tables' probabilities, each a product over its own Pu planes
+    auto shared_sum = [&](int g, int bits) -> double {
+        double f[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) f[i] = sig[(g * kPlanePad + i) * 2 + ((bits >> i) & 1)];
+        if (a.pf == 2) return (f[0] * f[1]) * (f[2] * f[3]) + (f[4] * f[5]) * (f[6] * f[7]);
+        if (a.pf == 4) return (f[0] * f[1] + f[2] * f[3]) + (f[4] * f[5] + f[6] * f[7]);
+        return ((f[0] + f[1]) + (f[2] + f[3])) + ((f[4] + f[5]) + (f[6] + f[7]));
+    };
+    if (a.pf > 1 && live && tid < a.pf << a.Pu) {
+        // the caller's tables one by one, for the read-back
+        const int j = tid >> a.Pu, x = tid & ((1 << a.Pu) - 1);
+        double mean = 0.0;
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            double pr = 1.0;
+            for (int i = 0; i < a.Pu; ++i) pr *= sig[(g * kPlanePad + j * a.Pu + i) * 2 + ((x >> i) & 1)];
+            mean += pr;
+        }
+        a.subprobs[((((int64_t)b * a.Hkv + h) * a.L + l) * a.pf + j) * (1 << a.Pu) + x] = (float)(mean / (double)G);
+    }
     if (a.mode == kDirect || a.mode == kSplit) {
         // p(r) over all planes, averaged over the G queries: one entry per thread and pass
         // (planes 8 and 9 of the split form sit in slots 8 and 9)
@@ -427,10 +452,10 @@ __global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
             double mean = 0.0;
             if (live) {
 #pragma unroll
-                for (int g = 0; g < G; ++g) mean += plane_product(g, 0, r);
+                for (int g = 0; g < G; ++g) mean += a.pf == 1 ? plane_product(g, 0, r) : shared_sum(g, r);
                 mean *= inv_g;
-                const double dv = mean - inv_r;      // a table's entries sum to 1: their mean is 1/R
-                dev2 += (float)(dv * dv);
+                const double dv = mean - a.tmean;    // a table's entries sum to 1: their mean is 1/R
+                dev2 += (float)(dv * dv);            // (pf tables' entries summed: pf / 2^Pu)
             }
             for (int cp = 0; cp < copies; ++cp) Tg[((int64_t)c64 * a.R + r) * 64 + lp + cp * lw] = (float)mean;
         }
@@ -1150,7 +1175,24 @@ __global__ __launch_bounds__(kGroupThreads) void project_group_kernel(ProjectArg
         const double *sp = sig + ((g * P + qr * 4) * 2) * TG + li;
         const double f0 = sp[(0 + ((bits >> 0) & 1)) * TG], f1 = sp[(2 + ((bits >> 1) & 1)) * TG];
         const double f2 = sp[(4 + ((bits >> 2) & 1)) * TG], f3 = sp[(6 + ((bits >> 3) & 1)) * TG];
-        qt[e] = (f0 * f1) * (f2 * f3);
+        // (ids that share a byte: the byte's entry is a sum over its pf small tables, so a
+        // quarter holds one 4-plane table, two 2-plane tables or four 1-plane tables)
+        qt[e] = a.pf <= 2 ? (f0 * f1) * (f2 * f3) : a.pf == 4 ? f0 * f1 + f2 * f3 : (f0 + f1) + (f2 + f3);
+    }
+    if (a.pf > 1) {
+        // the caller's tables one by one, for the read-back
+        const int Ru = 1 << a.Pu;
+        for (int e = tid; e < TG * a.pf * Ru; e += NT) {
+            const int x = e % Ru, j = (e / Ru) % a.pf, li = e / (Ru * a.pf);
+            if (l0 + li >= a.L) continue;
+            double mean = 0.0;
+            for (int g = 0; g < G; ++g) {
+                double pr = 1.0;
+                for (int i = 0; i < a.Pu; ++i) pr *= sig[((g * P + j * a.Pu + i) * 2 + ((x >> i) & 1)) * TG + li];
+                mean += pr;
+            }
+            a.subprobs[((((int64_t)b * a.Hkv + h) * a.L + l0 + li) * a.pf + j) * Ru + x] = (float)(mean / (double)G);
+        }
     }
     // the appended key's bucket ids, one thread per table of the group (tables >= L: id 0)
     if (app && krow >= 0 && tid >= 64 && tid < 64 + TG && l0 + tid - 64 < a.Lpad) {
@@ -1171,7 +1213,7 @@ __global__ __launch_bounds__(kGroupThreads) void project_group_kernel(ProjectArg
         const bool live = l < a.L;
         const int lw = a.Lpad < 64 ? a.Lpad : 64, copies = 64 / lw;
         const int c64 = l >> 6, lp = l & 63;
-        const double inv_g = 1.0 / (double)G, inv_r = 1.0 / (double)R;
+        const double inv_g = 1.0 / (double)G;
         float *Tg = a.tables + ((int64_t)b * a.Hkv + h) * a.table_words;
         const int r0 = tid / TG;
         double lo[G];
@@ -1187,13 +1229,15 @@ __global__ __launch_bounds__(kGroupThreads) void project_group_kernel(ProjectArg
             double mean = 0.0;
 #pragma unroll
             for (int g = 0; g < G; ++g) {
-                if (P > 4) mean = fma(lo[g], qt[((g * NQ + 1) * 16 + (r >> 4)) * TG + li_own], mean);
-                else mean += qt[((g * NQ) * 16 + r) * TG + li_own];
+                if (P > 4) {
+                    const double hi = qt[((g * NQ + 1) * 16 + (r >> 4)) * TG + li_own];
+                    mean = a.pf > 1 ? mean + (lo[g] + hi) : fma(lo[g], hi, mean);
+                } else mean += qt[((g * NQ) * 16 + r) * TG + li_own];
             }
             mean *= inv_g;
             if (!live) mean = 0.0;
             else {
-                const double dv = mean - inv_r;      // a table's entries sum to 1: their mean is 1/R
+                const double dv = mean - a.tmean;    // a table's entries sum to 1: their mean is 1/R (pf / 2^Pu when ids share bytes)
                 dev2 += (float)(dv * dv);
             }
             if (l < a.Lpad)
@@ -1232,6 +1276,7 @@ struct ScoreArgs {
     int n_sink, n_window;    // the first n_sink and last n_window tokens of a sequence score +inf
     RowMap map;
     int L, Lpad, rounds, R, G, Plo, Rlo, table_rows;
+    float mu;               // mean score of a uniformly drawn key (the caller's L / 2^P)
     int batch;
     int64_t table_words;
 };
@@ -1562,7 +1607,7 @@ __global__ __launch_bounds__(kScoreThreads, (MODE == kDirect && S == 4 && PAGED)
                     for (int i = tid; i < kHistBins; i += kScoreThreads) lhist[i] = 0;
             }
             if (adaptive && wave == 0) {
-                float mu = (float)a.L / (float)a.R;
+                float mu = a.mu;
                 float var = row_sum<64>(var_part);
                 const float nu1 = row_sum<64>(nu1_part), nu2 = row_sum<64>(nu2_part);
                 if (vn) {
@@ -1676,7 +1721,7 @@ __device__ __forceinline__ void adaptive_bin_params(const ScoreArgs &a, int64_t 
         nu1_part += ts[1];
         nu2_part += ts[2];
     }
-    float mu = (float)a.L / (float)a.R;
+    float mu = a.mu;
     float var = row_sum<64>(var_part);
     const float nu1 = row_sum<64>(nu1_part), nu2 = row_sum<64>(nu2_part);
     if (weighted) {          // weighted scores nu * s, nu and s taken as independent: moments of the product
@@ -1997,6 +2042,7 @@ int launch_project(socket_ctx *ctx, const void *q, const void *proj, float tau, 
     a.Lpad = g.Lpad; a.S = g.S; a.cb = g.cb; a.rounds = g.rounds; a.R = g.R; a.mode = g.mode;
     a.Plo = g.Plo; a.Phi = g.Phi; a.Rlo = g.Rlo; a.Rhi = g.Rhi; a.table_rows = g.table_rows;
     a.table_words = g.table_words; a.GT = g.GT;
+    a.pf = g.pf; a.Pu = g.Pu; a.tmean = (double)g.pf / (double)(1 << g.Pu); a.subprobs = ctx->subprobs;
     a.cols_magic = (65536 + g.P - 1) / g.P;
     const size_t lds = (size_t)(2 * g.G * kPlanePad + g.G * g.d + g.P * g.d) * sizeof(double) +
                        (size_t)(g.P * g.d + g.d) * 4 + 64 + 48 +
@@ -2005,12 +2051,14 @@ int launch_project(socket_ctx *ctx, const void *q, const void *proj, float tau, 
     project_fn_t fn = nullptr;
     const bool f32 = g.kv_dtype == SOCKET_F32;
     a.batch = batch; a.nb = 1;
-    if (batch > 1) {
+    const int elem = f32 ? 4 : 2;
+    // batches, the common case: a workgroup per (sequence, KV head, group of 128 columns of W)
+    const bool by_group = q && g.mode == kDirect && g.cb == 1 && (g.P == 4 || g.P == 8) && g.R == (1 << g.P) &&
+                          (size_t)g.d * kGroupCols * elem <= 32 * 1024 && (a.LP * elem) % 16 == 0 &&
+                          g.G * g.d / (16 / elem) <= kGroupThreads - g.d / (16 / elem);
+    if (batch > 1 && (g.pf == 1 || by_group)) {   // (ids that share bytes: that kernel or the one-sequence kernel)
         // several sequences per workgroup: the W slab of a table is staged once for all of them
-        const int elem = f32 ? 4 : 2;
-        // the common case: a workgroup per (sequence, KV head, group of 128 columns of W)
-        if (q && g.mode == kDirect && g.cb == 1 && (g.P == 4 || g.P == 8) && g.R == (1 << g.P) &&
-            (size_t)g.d * kGroupCols * elem <= 32 * 1024 && (a.LP * elem) % 16 == 0 && g.G * g.d / (16 / elem) <= kGroupThreads - g.d / (16 / elem)) {
+        if (by_group) {
             const size_t glds = project_group_lds(g.G, g.d, g.P, elem);
             const bool p8 = g.P == 8;
             switch (g.G) {
@@ -2098,7 +2146,7 @@ int launch_score_keys(socket_ctx *ctx, const void *codes, const float *vnorm,
                      : (g.mode != kFactor && (vnorm == nullptr || vnorm == ctx->vnorm_sampled)) ? kHistAdaptive
                                                                                               : kHistDigit;
     if (hist_mode) *hist_mode = mode;
-    a.hist_mode = mode; a.tstats = ctx->tstats; a.L = g.L;
+    a.hist_mode = mode; a.tstats = ctx->tstats; a.L = g.L; a.mu = g.mu;
     a.n_sink = ctx->n_sink; a.n_window = ctx->n_window;
     a.thr = ctx->counters + (int64_t)g.max_batch * g.Hkv * kCounterStride;
     a.codes = codes; a.tables = ctx->tables; a.vnorm = vnorm; a.seq_len = seq_len; a.scores = scores;

@@ -39,12 +39,16 @@ int fill_geometry(const socket_params *p, Geometry *g) {
     if (rows >= (int64_t)1 << 31) return SOCKET_EINVAL;
     if ((int64_t)p->max_batch * p->Hkv * (int64_t)p->max_n >= (int64_t)1 << 31) return SOCKET_EINVAL;
 
-    g->d = p->d; g->Hq = p->Hq; g->Hkv = p->Hkv; g->G = G; g->L = p->L; g->P = p->P;
-    g->R = 1 << p->P;
-    g->Lpad = pad_codes(p->L);
+    g->pf = pack_factor(p->L, p->P);
+    g->Lu = p->L; g->Pu = p->P;
+    g->mu = (float)((double)p->L / (double)(1 << p->P));
+    const int L = p->L / g->pf, P = g->pf > 1 ? 8 : p->P;
+    g->d = p->d; g->Hq = p->Hq; g->Hkv = p->Hkv; g->G = G; g->L = L; g->P = P;
+    g->R = 1 << P;
+    g->Lpad = pad_codes(L);
     g->S = g->Lpad >= 64 ? 4 : g->Lpad / 16;
     g->rounds = g->Lpad >= 64 ? g->Lpad / 64 : 1;
-    g->cb = p->P <= 8 ? 1 : 2;
+    g->cb = P <= 8 ? 1 : 2;
     g->page = p->page_size; g->max_blocks = p->max_blocks_per_seq; g->num_blocks = p->num_blocks;
     g->max_n = p->max_n; g->max_k = p->max_k; g->max_batch = p->max_batch;
     g->kv_dtype = p->kv_dtype;
@@ -52,15 +56,15 @@ int fill_geometry(const socket_params *p, Geometry *g) {
     // Pick the bucket-probability layout that fits in LDS (a row is 64 floats = 256 B).
     const int64_t budget = 144 * 1024;
     int64_t direct = (int64_t)g->rounds * g->R * 256;
-    g->Plo = (p->P + 1) / 2; g->Phi = p->P - g->Plo;
+    g->Plo = (P + 1) / 2; g->Phi = P - g->Plo;
     g->Rlo = 1 << g->Plo; g->Rhi = 1 << g->Phi;
     g->GT = 0;
     int64_t factor = (int64_t)G * g->rounds * (g->Rlo + g->Rhi) * 256;
-    if (p->P <= 8 && direct <= 128 * 1024) {
+    if (P <= 8 && direct <= 128 * 1024) {
         g->mode = kDirect;
         g->table_rows = g->R;
         g->table_words = (int64_t)g->rounds * g->R * 64;
-    } else if (p->P == 9 || p->P == 10) {
+    } else if (P == 9 || P == 10) {
         // packed ids, one table per (table, bucket), scored group by group
         g->mode = kSplit;
         g->cb = 0;
@@ -69,7 +73,7 @@ int fill_geometry(const socket_params *p, Geometry *g) {
         g->rounds = g->Lpad / g->GT;
         g->table_rows = g->R;
         g->table_words = (int64_t)g->rounds * g->R * g->GT;
-    } else if (p->P >= 2 && factor <= budget) {
+    } else if (g->pf == 1 && P >= 2 && factor <= budget) {
         g->mode = kFactor;
         g->table_rows = g->Rlo + g->Rhi;
         g->table_words = (int64_t)G * g->rounds * g->table_rows * 64;
@@ -129,17 +133,27 @@ int32_t socket_code_position(int32_t L, int32_t l, int32_t t) {
 static bool packed_ids(int P) { return P == 9 || P == 10; }
 
 int64_t socket_codes_bytes(int32_t L, int32_t P, int64_t tokens) {
-    const int Lpad = pad_codes(L);
-    if (Lpad < 0 || P < 1 || P > 16 || tokens < 0 || tokens % 16) return -1;
+    if (L < 1 || P < 1 || P > 16 || tokens < 0 || tokens % 16) return -1;
+    const int Lpad = pad_codes(L / pack_factor(L, P));
+    if (Lpad < 0) return -1;
     if (packed_ids(P)) return tokens / 16 * packed_tile_bytes(Lpad);
     return tokens * Lpad * (P <= 8 ? 1 : 2);
 }
 
 int socket_code_location(int32_t L, int32_t P, int32_t l, int32_t t, int64_t *lo_byte,
                          int64_t *hi_byte, int32_t *hi_shift) {
-    const int Lpad = pad_codes(L);
-    if (Lpad < 0 || P < 1 || P > 16 || l < 0 || l >= Lpad || t < 0 || !lo_byte || !hi_byte || !hi_shift)
+    if (L < 1 || P < 1 || P > 16) return SOCKET_EINVAL;
+    const int pf = pack_factor(L, P);
+    const int Lpad = pad_codes(L / pf);
+    if (Lpad < 0 || l < 0 || l >= Lpad * pf || t < 0 || !lo_byte || !hi_byte || !hi_shift)
         return SOCKET_EINVAL;
+    if (pf > 1) {
+        // 8/P ids to a byte: the byte is the id of 8-plane table l / pf
+        *lo_byte = (int64_t)t * Lpad + socket_code_position(L / pf, l / pf, t);
+        *hi_byte = -1;
+        *hi_shift = P * (l % pf);
+        return SOCKET_OK;
+    }
     if (packed_ids(P)) {
         const int GT = Lpad < 32 ? Lpad : 32, S = GT / 16;
         const int grp = l / GT, j = packed_pos(l % GT, t, S);
@@ -177,6 +191,7 @@ int socket_create(socket_ctx **out, const socket_params *p) {
     const int64_t BH = (int64_t)g.max_batch * g.Hkv;
     const int64_t sz_tables = BH * g.table_words * 4;
     const int64_t sz_tstats = BH * g.Lpad * 3 * 4;
+    const int64_t sz_sub = g.pf > 1 ? BH * g.Lu * (1 << g.Pu) * 4 : 0;   // shared-byte ids: the small tables, for the read-back
     // fast prefill hash: bf16 keys, 8-plane tables, whole 64-table chunks, W slab of a chunk fits LDS
     const bool fast_hash = g.kv_dtype == SOCKET_BF16 && g.P == 8 && g.L >= 64 && g.d <= 128;
     const int64_t sz_wfrag = fast_hash ? (int64_t)g.Hkv * ((g.L + 63) / 64) * g.d * 1024 : 0;
@@ -187,10 +202,11 @@ int socket_create(socket_ctx **out, const socket_params *p) {
     const int64_t sz_regions = BH * g.n_regions * kSlice * 4, sz_selcnt = BH * g.n_regions * 4;
     const int64_t sz_seq = (int64_t)g.max_batch * 4;
     const int64_t sz_part = (int64_t)g.max_batch * g.Hq * kMaxSplits * (g.d + 2) * 4;
-    ctx->scratch_bytes = sz_wfrag + sz_tables + sz_tstats + sz_hist + sz_cnt + 2 * sz_cand + sz_staged + sz_regions + sz_selcnt + sz_part + sz_seq;
+    ctx->scratch_bytes = sz_wfrag + sz_tables + sz_tstats + sz_sub + sz_hist + sz_cnt + 2 * sz_cand + sz_staged + sz_regions + sz_selcnt + sz_part + sz_seq;
     bool ok = score_prepare(g) == SOCKET_OK &&
               hipMalloc((void **)&ctx->tables, sz_tables) == hipSuccess &&
               hipMalloc((void **)&ctx->tstats, sz_tstats) == hipSuccess &&
+              (sz_sub == 0 || hipMalloc((void **)&ctx->subprobs, sz_sub) == hipSuccess) &&
               (!fast_hash || (hipMalloc(&ctx->wfrag, sz_wfrag) == hipSuccess && hash_prepare(g.d) == SOCKET_OK)) &&
               hipMalloc((void **)&ctx->hist, sz_hist) == hipSuccess &&
               hipMalloc((void **)&ctx->counters, sz_cnt) == hipSuccess &&
@@ -219,7 +235,7 @@ int socket_create(socket_ctx **out, const socket_params *p) {
 
 int socket_destroy(socket_ctx *ctx) {
     if (!ctx) return SOCKET_EINVAL;
-    void *bufs[] = {ctx->tables, ctx->tstats, ctx->wfrag, ctx->hist, ctx->counters, ctx->cand_key, ctx->cand_idx, ctx->staged, ctx->sel_regions, ctx->sel_cnt, ctx->partials, ctx->seq_scratch};
+    void *bufs[] = {ctx->tables, ctx->tstats, ctx->subprobs, ctx->wfrag, ctx->hist, ctx->counters, ctx->cand_key, ctx->cand_idx, ctx->staged, ctx->sel_regions, ctx->sel_cnt, ctx->partials, ctx->seq_scratch};
     for (void *b : bufs)
         if (b) (void)hipFree(b);
     delete ctx;

@@ -49,6 +49,13 @@ enum TableMode { kDirect = 0, kFactor = 1, kSplit = 2 };
 enum HistMode { kHistNone = 0, kHistDigit = 1, kHistAdaptive = 2 };
 
 struct Geometry {
+    // Ids of 1, 2 or 4 bits are kept 8 / P to a byte when L is a multiple of that: the byte of
+    // tables 8/P * l' .. is exactly the id of one 8-plane table l' over the same columns of W,
+    // so everything below runs as (P, L) = (8, L * P / 8); only the bucket-probability tables
+    // differ (an entry is the sum of the 8/P small tables' entries, not one product).
+    int pf;          // ids per byte (1 = not shared)
+    int Lu, Pu;      // the caller's L and P
+    float mu;        // mean score of a uniformly drawn key: Lu / 2^Pu
     int d, Hq, Hkv, G, L, P, R;
     int Lpad;        // codes per token
     int S;           // lanes that share one token's 64 codes of a chunk (Lpad<64: Lpad/16, else 4);
@@ -78,6 +85,7 @@ struct socket_ctx {
     int n_sink, n_window; // tokens at either end of a sequence that scoring forces into the selection
     float *tables;        // [max_batch*Hkv][table_words]
     float *tstats;        // [max_batch*Hkv][Lpad][3] spread of each table's bucket probabilities, sampled value norms
+    float *subprobs;      // ids that share bytes only: [max_batch*Hkv][Lu][2^Pu] group-mean probabilities of the caller's tables
     const float *vnorm_sampled;   // the value-norm array the last projection pass sampled (or null)
     int pending_hist;     // HistMode of what socket_score_keys_binned left for socket_topk_select_binned
     void *wfrag;          // W cut into MFMA fragments for the fast prefill hash (null when that path does not apply)
@@ -95,6 +103,13 @@ struct socket_ctx {
 namespace sk {
 
 int fill_geometry(const socket_params *p, Geometry *g);  // host-only validation
+inline int pack_factor(int L, int P) {
+    // (at most 128 bytes of shared ids per token: two 64-table chunks of 256-entry tables are
+    // what the scoring kernel's LDS holds; at least 32: shorter rows score no faster than a byte
+    // per id with its small tables, measured)
+    const int f = (P == 1 || P == 2 || P == 4) ? 8 / P : 1;
+    return (L % f == 0 && L / f >= 32 && L / f <= 128) ? f : 1;
+}
 int record_hip(socket_ctx *ctx, hipError_t e);
 
 // launchers (each returns a SOCKET_* code)

@@ -40,6 +40,9 @@ __global__ __launch_bounds__(256) void bucket_probs_kernel(ProbsArgs a) {
 
 int launch_bucket_probs(socket_ctx *ctx, int batch, float *probs, hipStream_t st) {
     const Geometry &g = ctx->g;
+    if (g.pf > 1)   // ids that share bytes: the projection pass keeps the caller's tables beside the summed ones
+        return record_hip(ctx, hipMemcpyAsync(probs, ctx->subprobs, (size_t)batch * g.Hkv * g.Lu * (1 << g.Pu) * 4,
+                                              hipMemcpyDeviceToDevice, st));
     ProbsArgs a;
     a.tables = ctx->tables; a.out = probs;
     a.L = g.L; a.R = g.R; a.G = g.G; a.Lpad = g.Lpad; a.rounds = g.rounds; a.GT = g.GT; a.mode = g.mode;

@@ -21,7 +21,16 @@ def i32(x) -> torch.Tensor:
     return torch.tensor(np.asarray(x, dtype=np.int32), dtype=torch.int32, device="cuda")
 
 
-def lpad_of(L: int) -> int:
+def pack_factor(L: int, P: int) -> int:
+    """Ids of 1, 2 or 4 bits share bytes, 8/P of them, when L is a multiple of that and the bytes
+    per token come to 32..128 (see socket.h)."""
+    f = 8 // P if P in (1, 2, 4) else 1
+    return f if L % f == 0 and 32 <= L // f <= 128 else 1
+
+
+def lpad_of(L: int, P: int = 8) -> int:
+    """Elements of a token's code row."""
+    L //= pack_factor(L, P)
     if L <= 16:
         return 16
     if L <= 32:
@@ -37,7 +46,11 @@ def packed(P: int) -> bool:
 
 
 def positions(L: int, n: int, P: int = 8) -> np.ndarray:
-    """pos[t, l] = where table l's id sits in token t's Lpad-long code row (see socket.h)."""
+    """pos[t, l] = where table l's id sits in token t's Lpad-long code row (see socket.h); ids
+    that share bytes: the position of the byte that holds it."""
+    pf = pack_factor(L, P)
+    if pf > 1:
+        return np.repeat(positions(L // pf, n, 8), pf, axis=1)
     Lpad = lpad_of(L)
     l = np.arange(L)[None, :]
     t = np.arange(n)[:, None]
@@ -56,11 +69,20 @@ def codes_to_natural(codes: np.ndarray, L: int, t0: int = 0, P: int = 8) -> np.n
     """[..., n, Lpad] code rows in the library's order -> [..., n, L]; row i is token t0 + i."""
     n = codes.shape[-2]
     pos = positions(L, t0 + n, P)[t0:]
-    return np.take_along_axis(codes, np.broadcast_to(pos, codes.shape[:-1] + (L,)), axis=-1)
+    nat = np.take_along_axis(codes, np.broadcast_to(pos, codes.shape[:-1] + (L,)), axis=-1)
+    pf = pack_factor(L, P)
+    if pf > 1:                          # field l % pf of the shared byte
+        nat = (nat >> (P * (np.arange(L) % pf)).astype(nat.dtype)) & nat.dtype.type((1 << P) - 1)
+    return nat
 
 
 def codes_from_natural(nat: np.ndarray, L: int, dtype, P: int = 8) -> np.ndarray:
     """[..., n, L] -> [..., n, Lpad] code rows in the library's order (padding positions 0)."""
+    pf = pack_factor(L, P)
+    if pf > 1:                          # pf ids to a byte, then the byte as an 8-bit id of table l // pf
+        fields = nat.reshape(nat.shape[:-1] + (L // pf, pf)).astype(np.uint32)
+        byte = (fields << (P * np.arange(pf)).astype(np.uint32)).sum(axis=-1)
+        return codes_from_natural(byte, L // pf, dtype, 8)
     n = nat.shape[-2]
     out = np.zeros(nat.shape[:-1] + (lpad_of(L),), dtype=dtype)
     pos = positions(L, n, P)
@@ -84,7 +106,7 @@ def fill_id(P: int) -> int:
 def new_codes(lead, n: int, L: int, P: int, fill: int = 0) -> torch.Tensor:
     """Device bucket-id buffer for `lead` (sequences or blocks, KV heads) x n tokens, every
     byte = fill.  Unpacked: [*lead, n, Lpad] uint8 / int16; packed: [*lead, n/16, 20*Lpad] bytes."""
-    Lpad = lpad_of(L)
+    Lpad = lpad_of(L, P)
     if packed(P):
         assert n % 16 == 0
         return torch.full(tuple(lead) + (n // 16, 20 * Lpad), fill, dtype=torch.uint8, device="cuda")

@@ -79,10 +79,11 @@ def test_code_layout_matches_documented_formula():
 
 def test_layout_round_trip():
     rng = np.random.default_rng(5)
-    for L, P in ((24, 8), (64, 8), (128, 4), (60, 10), (16, 9), (100, 10), (40, 12)):
+    for L, P in ((24, 8), (64, 8), (128, 4), (60, 10), (16, 9), (100, 10), (40, 12), (300, 2), (16, 4), (66, 4),
+                 (7, 4), (256, 1), (600, 2)):
         nat = rng.integers(0, 1 << P, size=(2, 48, L)).astype(harness.code_dtype(P))
         lay = harness.codes_from_natural(nat, L, harness.code_dtype(P), P=P)
-        assert lay.shape[-1] == harness.lpad_of(L)
+        assert lay.shape[-1] == harness.lpad_of(L, P)
         assert (harness.codes_to_natural(lay, L, P=P) == nat).all()
         store = harness.rows_to_storage(lay, L, P)
         assert store.nbytes == 2 * sk.codes_bytes(L, P, 48)
@@ -91,9 +92,11 @@ def test_layout_round_trip():
 
 def test_code_location_describes_every_storage_form():
     """socket_code_location against the harness's own packing of random ids: one-byte ids,
-    two-byte ids and the packed 10-bit form (whose tiles and groups it has to walk)."""
+    two-byte ids, the packed 10-bit form (whose tiles and groups it has to walk) and ids of 1, 2
+    or 4 bits that share bytes (not when L is no multiple of 8/P or the row would not come to 32..128 bytes)."""
     rng = np.random.default_rng(6)
-    for L, P in ((64, 8), (24, 5), (60, 10), (64, 9), (16, 10), (128, 10), (40, 12)):
+    for L, P in ((64, 8), (24, 5), (60, 10), (64, 9), (16, 10), (128, 10), (40, 12), (300, 2), (128, 4), (16, 4),
+                 (66, 4), (7, 4), (256, 1), (600, 2), (2, 2), (64, 4)):
         n = 48
         nat = rng.integers(0, 1 << P, size=(n, L)).astype(harness.code_dtype(P))
         lay = harness.codes_from_natural(nat, L, harness.code_dtype(P), P=P)
@@ -107,12 +110,15 @@ def test_code_location_describes_every_storage_form():
                 if P > 8:
                     got = ((got | int(flat[hi]) << 8) >> sh) & ((1 << P) - 1)
                 else:
-                    assert hi == -1 and sh == 0
+                    assert hi == -1 and sh == P * (l % harness.pack_factor(L, P))
+                    got = (got >> sh) & ((1 << P) - 1)
                 assert got == int(nat[t, l]), (L, P, l, t)
                 seen.add((lo, hi, sh))
         assert len(seen) == 7 * L                      # no two ids share their bits
     assert sk.codes_bytes(64, 10, 15) == -1 and sk.codes_bytes(64, 10, 32) == 2 * 20 * 64
     assert sk.codes_bytes(64, 8, 32) == 32 * 64 and sk.codes_bytes(64, 12, 32) == 32 * 64 * 2
+    assert sk.codes_bytes(300, 2, 32) == 32 * 128 and sk.codes_bytes(128, 4, 32) == 32 * 64
+    assert sk.codes_bytes(600, 2, 32) == 32 * 640 and sk.codes_bytes(7, 4, 16) == 16 * 16
 
 
 def test_null_arguments_are_rejected_without_a_gpu():

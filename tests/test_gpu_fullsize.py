@@ -25,7 +25,7 @@ def run_step(layer, n):
     ctx = hz.make_ctx(layer)
     Kd, Vd, qd, Wd = (hz.dev(x, layer.kv_dtype) for x in (layer.K, layer.V, layer.q, layer.W))
     k = int(layer.k.max())
-    codes = torch.zeros((B, Hkv, cap, hz.lpad_of(layer.L)), dtype=torch.uint8, device="cuda")
+    codes = torch.zeros((B, Hkv, cap, hz.lpad_of(layer.L, layer.P)), dtype=torch.uint8, device="cuda")
     scores = torch.zeros((B, Hkv, cap), dtype=torch.float32, device="cuda")
     idx = torch.zeros((B, Hkv, k), dtype=torch.int32, device="cuda")
     nsel = torch.zeros((B, Hkv), dtype=torch.int32, device="cuda")

@@ -73,6 +73,11 @@ def check_codes(layer, codes_t, rows_of):
     (wl.BF16, 1024, 60, 10),    # the paper's main (P, L)
     (wl.BF16, 1024, 24, 5),
     (wl.F32, 512, 40, 12),
+    (wl.BF16, 1024, 300, 2),    # four 2-bit ids to a byte: 75 bytes per token, two chunks
+    (wl.BF16, 1024, 128, 4),    # two 4-bit ids to a byte
+    (wl.F32, 512, 256, 1),      # eight 1-bit ids to a byte
+    (wl.BF16, 512, 66, 4),      # 33 bytes
+    (wl.BF16, 512, 7, 4),       # an odd table count: a byte per id
 ])
 def test_hash_keys_prefill(kv_dtype, n, L, P):
     _need_gpu()
@@ -172,7 +177,7 @@ def check_scores(layer, got, codes_nat, tau, vnorm=None, seq_len=None, q=None, r
 
 
 @pytest.mark.parametrize("L,P,G", [(64, 8, 4), (32, 8, 1), (16, 4, 2), (128, 8, 4), (60, 10, 4),
-                                   (64, 10, 1), (24, 5, 8), (128, 4, 4), (200, 2, 1),
+                                   (64, 10, 1), (24, 5, 8), (128, 4, 4), (200, 2, 1), (300, 2, 4), (256, 1, 2), (66, 4, 8), (7, 4, 1),     # ids that share bytes (not the last)
                                    (16, 10, 2), (100, 9, 8),      # packed ids: one 16-table group; four groups
                                    (40, 12, 2), (64, 11, 4)])     # two-byte ids, factored tables
 def test_score_matches_oracle(L, P, G):
@@ -531,7 +536,8 @@ def same_step_results(a, f, where):
 
 
 @pytest.mark.parametrize("kv_dtype,L,P,G", [(wl.BF16, 64, 8, 4), (wl.F32, 32, 8, 1), (wl.BF16, 60, 10, 4),
-                                            (wl.BF16, 40, 12, 2), (wl.F32, 16, 9, 1)])
+                                            (wl.BF16, 40, 12, 2), (wl.F32, 16, 9, 1),
+                                            (wl.BF16, 128, 4, 4), (wl.BF16, 300, 2, 2)])   # ids that share bytes
 def test_decode_step_equals_separate_calls_and_oracle(kv_dtype, L, P, G):
     """socket_decode_step must give what the four separate calls give (see same_step_results),
     for a few consecutive steps; the last step is also checked against the oracle."""
@@ -845,7 +851,7 @@ def test_forced_sink_and_window_tokens_through_the_chain():
     max_k = int(layer.k.max())
 
     def fresh():
-        return dict(codes=torch.zeros((B, Hkv, n, hz.lpad_of(L)), dtype=torch.uint8, device="cuda"),
+        return dict(codes=torch.zeros((B, Hkv, n, hz.lpad_of(L, P)), dtype=torch.uint8, device="cuda"),
                     scores=torch.zeros((B, Hkv, n), dtype=torch.float32, device="cuda"),
                     idx=torch.zeros((B, Hkv, max_k), dtype=torch.int32, device="cuda"),
                     nsel=torch.zeros((B, Hkv), dtype=torch.int32, device="cuda"),
@@ -914,7 +920,7 @@ def paged_codes_to_logical(codes_p, table, n_cap, page):
     return out
 
 
-@pytest.mark.parametrize("L,P,page", [(64, 8, 16), (60, 10, 16), (64, 10, 32)])
+@pytest.mark.parametrize("L,P,page", [(64, 8, 16), (60, 10, 16), (64, 10, 32), (128, 4, 16)])
 def test_paged_chain_with_appends_across_page_boundaries(L, P, page):
     """Batched paged decode: prefill-hash ragged lengths, then several fused decode steps that
     append one key per sequence (crossing page edges), all checked against the oracle on
@@ -968,7 +974,7 @@ def test_paged_absent_block_is_masked_not_faulted():
     Kd, Vd = hz.dev(Kp, layer.kv_dtype), hz.dev(Vp, layer.kv_dtype)
     qd, Wd = hz.dev(layer.q, layer.kv_dtype), hz.dev(layer.W, layer.kv_dtype)
     bt = hz.i32(table)
-    codes = torch.zeros((nblocks, Hkv, page, hz.lpad_of(L)), dtype=torch.uint8, device="cuda")
+    codes = torch.zeros((nblocks, Hkv, page, hz.lpad_of(L, P)), dtype=torch.uint8, device="cuda")
     scores = torch.zeros((B, Hkv, n_cap), dtype=torch.float32, device="cuda")
     idx = torch.zeros((B, Hkv, 32), dtype=torch.int32, device="cuda")
     nsel = torch.zeros((B, Hkv), dtype=torch.int32, device="cuda")
@@ -1029,7 +1035,8 @@ def test_sweep_hash_then_score(L, P):
                                             (130, 6, 8, wl.BF16),      # more than 64 tables, a full group of 8
                                             # the batched pass by groups of 128 columns of W, its other shapes:
                                             (64, 8, 8, wl.BF16), (48, 4, 8, wl.BF16), (72, 8, 1, wl.BF16),
-                                            (32, 4, 2, wl.BF16)])
+                                            (32, 4, 2, wl.BF16),
+                                            (300, 2, 4, wl.BF16), (256, 1, 2, wl.F32), (64, 4, 8, wl.BF16)])   # ids that share bytes
 def test_bucket_probs_match_oracle_entry_by_entry(L, P, G, kv_dtype):
     """Alg. 2: every one of the L * 2^P bucket probabilities the context holds after
     socket_soft_hash, read back with socket_bucket_probs, against the oracle's R-way softmax
