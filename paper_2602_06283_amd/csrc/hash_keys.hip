@@ -521,6 +521,156 @@ __global__ __launch_bounds__(kHash8Threads) void hash_mfma8_kernel(HashArgs a, c
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// The same structure for 10-plane tables with packed ids (groups of 32 tables, d <= 128): a
+// workgroup keeps the W slab of one group (320 columns = ten 32-column blocks) in LDS as MFMA
+// fragments; every wavefront works on 64-key blocks of its own.
+//
+// Column order.  String `sub` (0, 1) of a token's group holds, before its rotation by the token
+// position, the ids of tables sub, sub + 2, .., sub + 30 in bits [10 j, 10 j + 10): 160 bits =
+// five sign words.  Block p = 5 sub + q produces word q: bit u = 32 q + (bit of the word) of the
+// string is plane u % 10 of table sub + 2 (u / 10).  The stored string is that one rotated right
+// by 10 (t mod 16) bits: a rotation of the five words and one funnel shift.
+// ---------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void hash_wfrag10_kernel(HashArgs a, uint4 *wfrag) {
+    constexpr int KS = D / 16;
+    const int p = blockIdx.x, grp = blockIdx.y % a.n_chunks, h = blockIdx.y / a.n_chunks;
+    const int first_table = grp * 32;
+    const int ntab = min(32, a.L - first_table);
+    const int sub = p / 5, q = p % 5;
+    const uint16_t *W = (const uint16_t *)a.W + (int64_t)h * D * a.LP;
+    uint4 *dst = wfrag + ((int64_t)blockIdx.y * 10 + p) * KS * 64;
+    for (int f = threadIdx.x; f < KS * 64; f += 256) {
+        const int ks = f >> 6, lane = f & 63;
+        const int g = lane >> 5, m = lane & 31;
+        const int bit = 16 * ((m >> 2) & 1) + 4 * (m >> 3) + (m & 3);   // bit of the sign word that MFMA row m becomes
+        const int u = 32 * q + bit;
+        const int tt = sub + 2 * (u / 10);                     // group-local table
+        const int col = (first_table + tt) * 10 + u % 10;
+        uint32_t w[4] = {0u, 0u, 0u, 0u};
+        if (tt < ntab) {
+            uint16_t e[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) e[i] = W[(int64_t)(ks * 16 + g * 8 + i) * a.LP + col];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) w[i >> 1] |= (uint32_t)e[i] << (16 * (i & 1));
+        }
+        dst[f] = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(kHash8Threads) void hash_mfma10_kernel(HashArgs a, const uint4 *wfrag) {
+    constexpr int KS = D / 16;                 // MFMA k-steps
+    constexpr int NCB = 10;                    // 32-column blocks of a group
+    constexpr int NW = kHash8Threads / 64;
+    extern __shared__ uint32_t smem[];
+    uint4 *wl = (uint4 *)smem;                         // [NCB][KS][64 lanes] A fragments
+    uint32_t *bits = smem + NCB * KS * 64 * 4;         // [NW waves][64 keys][5 words]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int grp = blockIdx.y % a.n_chunks, h = blockIdx.y / a.n_chunks, b = blockIdx.z;
+    const int count = a.row_count[b];
+    const int begin = a.row_begin[b];
+    const int ntab = max(0, min(32, a.L - grp * 32));
+
+    {
+        const uint4 *src = wfrag + (int64_t)blockIdx.y * NCB * KS * 64;
+        for (int i = tid; i < NCB * KS * 64; i += kHash8Threads) wl[i] = src[i];
+    }
+    __syncthreads();
+
+    uint32_t *mybits = bits + wave * 320;
+    const int n = lane & 31, g = lane >> 5;
+    const char *Kb = (const char *)a.K;
+    char *Cb = (char *)a.codes;
+
+    auto key_row = [&](int r) -> int64_t {
+        const int t = begin + r;
+        return (r < count && t >= 0 && t < a.map.max_n) ? a.map.row(b, h, t) : -1;
+    };
+    // (a key that does not exist reads row 0 of the cache instead; its ids are never stored)
+    bf16x8_t kf[2][KS];
+    auto load_keys = [&](int r0) {
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) {
+            const int64_t row = key_row(r0 + nb * 32 + n);
+            const char *src = Kb + (row >= 0 ? row : 0) * (int64_t)(D * 2) + g * 16;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) kf[nb][ks] = *(const bf16x8_t *)(src + ks * 32);
+        }
+    };
+    auto sign_word = [&](const floatx16_t &acc) -> uint32_t {
+        uint32_t neg = __float_as_uint(acc[15]) >> 31;
+#pragma unroll
+        for (int i = 14; i >= 0; --i) neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(acc[i]), 31);
+        auto both = __builtin_amdgcn_permlane32_swap(neg, neg, false, false);
+        return ~(both[0] | (both[1] << 16));
+    };
+
+    const int nblocks = (count + 63) >> 6;
+    const int stride = gridDim.x * NW;
+    int blk = blockIdx.x * NW + wave;
+    if (blk < nblocks) load_keys(blk * 64);
+    for (; blk < nblocks; blk += stride) {
+        const int r0 = blk * 64;
+        const int64_t prow = key_row(r0 + lane);        // the key this lane packs
+        const uint32_t turn = 10u * (uint32_t)((begin + r0 + lane) & 15);   // bits the string is rotated by
+        uint4 head0 = make_uint4(0, 0, 0, 0);           // string 0, kept until string 1 is there too
+        uint32_t tail0 = 0;
+#pragma unroll 1
+        for (int p = 0; p < NCB; ++p) {
+            const int sub = p >= 5 ? 1 : 0, q = p - 5 * sub;
+            const uint4 *af = wl + (p * KS) * 64 + lane;
+            floatx16_t acc0, acc1;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc0[i] = acc1[i] = 0.0f;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                union { uint4 u; bf16x8_t v; } fa;
+                fa.u = af[ks * 64];
+                acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa.v, kf[0][ks], acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa.v, kf[1][ks], acc1, 0, 0, 0);
+            }
+            // ids of tables beyond the live ones stay zero: the string's first 10 nj bits are live
+            const int nj = max(0, (ntab - sub + 1) >> 1);
+            const int nlive = 10 * nj - 32 * q;
+            const uint32_t live_mask = nlive >= 32 ? 0xffffffffu : nlive <= 0 ? 0u : (1u << nlive) - 1u;
+            const uint32_t w0 = sign_word(acc0), w1 = sign_word(acc1);
+            mybits[lane * 5 + q] = (lane < 32 ? w0 : w1) & live_mask;   // lane = key n or 32 + n
+            if (q == 4) {
+                uint32_t x0 = mybits[lane * 5], x1 = mybits[lane * 5 + 1], x2 = mybits[lane * 5 + 2];
+                uint32_t x3 = mybits[lane * 5 + 3], x4 = mybits[lane * 5 + 4];
+                // stored word k = bits [32 k + turn, +32) of the string, cyclically: words turned
+                // by turn / 32, then a funnel shift by turn % 32
+                const uint32_t wo = turn >> 5, sh = turn & 31;
+                if (wo & 1) { const uint32_t t0 = x0; x0 = x1; x1 = x2; x2 = x3; x3 = x4; x4 = t0; }
+                if (wo & 2) { const uint32_t t0 = x0, t1 = x1; x0 = x2; x1 = x3; x2 = x4; x3 = t0; x4 = t1; }
+                if (wo & 4) { const uint32_t t4 = x4; x4 = x3; x3 = x2; x2 = x1; x1 = x0; x0 = t4; }
+                uint4 o;
+                o.x = __builtin_amdgcn_alignbit(x1, x0, sh);
+                o.y = __builtin_amdgcn_alignbit(x2, x1, sh);
+                o.z = __builtin_amdgcn_alignbit(x3, x2, sh);
+                o.w = __builtin_amdgcn_alignbit(x4, x3, sh);
+                const uint32_t ot = __builtin_amdgcn_alignbit(x0, x4, sh);
+                if (sub == 0) {
+                    head0 = o;
+                    tail0 = ot;
+                } else if (prow >= 0) {
+                    // both strings of the key's group together: 32 adjacent bytes of the tile's
+                    // main rows and 8 of its tail rows
+                    uint4 *dst = (uint4 *)(Cb + packed_main_row(prow, grp, a.Lpad, 32));
+                    dst[0] = head0;
+                    dst[1] = o;
+                    *(uint2 *)(Cb + packed_tail_row(prow, grp, a.Lpad, 32)) = make_uint2(tail0, ot);
+                }
+            }
+        }
+        if (blk + stride < nblocks) load_keys((blk + stride) * 64);
+    }
+}
+
 template <typename T>
 static int launch_rows(const HashArgs &a, int Hkv, int batch, int max_rows, hipStream_t st) {
     const int bw = 2 * ((a.LP + 63) / 64);
@@ -543,10 +693,17 @@ template <int D> constexpr size_t hash8_lds() {
     return (size_t)16 * (D / 16) * 64 * 16 + (size_t)(kHash8Threads / 64) * 64 * 16;
 }
 
-// once per context that uses the fast 8-plane hash: more than 64 KB of dynamic LDS has to be
-// allowed before the first launch
+template <int D> constexpr size_t hash10_lds() {
+    return (size_t)10 * (D / 16) * 64 * 16 + (size_t)(kHash8Threads / 64) * 64 * 20;
+}
+
+// once per context that uses a fast hash: more than 64 KB of dynamic LDS has to be allowed
+// before the first launch
 int hash_prepare(int d) {
     hipError_t e = hipSuccess;
+    if (d == 64) e = hipFuncSetAttribute((const void *)hash_mfma10_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)hash10_lds<64>());
+    if (d == 128) e = hipFuncSetAttribute((const void *)hash_mfma10_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)hash10_lds<128>());
+    if (e != hipSuccess) return SOCKET_EHIP;
     if (d == 64) e = hipFuncSetAttribute((const void *)hash_mfma8_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)hash8_lds<64>());
     if (d == 128) e = hipFuncSetAttribute((const void *)hash_mfma8_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)hash8_lds<128>());
     return e == hipSuccess ? SOCKET_OK : SOCKET_EHIP;
@@ -566,6 +723,21 @@ static int launch_mfma8(HashArgs a, uint4 *wfrag, int Hkv, int batch, int max_ro
     if (per < 1) per = 1;
     dim3 grid(per, Hkv * a.n_chunks, batch);
     hipLaunchKernelGGL((hash_mfma8_kernel<D>), grid, dim3(kHash8Threads), hash8_lds<D>(), st, a, (const uint4 *)wfrag);
+    return SOCKET_OK;
+}
+
+template <int D>
+static int launch_mfma10(HashArgs a, uint4 *wfrag, int Hkv, int batch, int max_rows, hipStream_t st) {
+    constexpr int NW = kHash8Threads / 64;
+    a.tables_per_chunk = 32;
+    a.n_chunks = a.Lpad / 32;                  // groups, padding groups included (their ids are zero)
+    hipLaunchKernelGGL((hash_wfrag10_kernel<D>), dim3(10, Hkv * a.n_chunks), dim3(256), 0, st, a, wfrag);
+    int per = 256 / (Hkv * a.n_chunks * batch);
+    const int nblocks = (max_rows + 63) / 64;
+    if (per > (nblocks + NW - 1) / NW) per = (nblocks + NW - 1) / NW;
+    if (per < 1) per = 1;
+    dim3 grid(per, Hkv * a.n_chunks, batch);
+    hipLaunchKernelGGL((hash_mfma10_kernel<D>), grid, dim3(kHash8Threads), hash10_lds<D>(), st, a, (const uint4 *)wfrag);
     return SOCKET_OK;
 }
 
@@ -615,12 +787,15 @@ int launch_hash_keys(socket_ctx *ctx, const void *K, const void *proj, const int
     } else if (max_rows < 64) {
         rc = launch_rows<uint16_t>(a, g.Hkv, batch, max_rows, st);
     } else {
-        const bool fast8 = ctx->wfrag != nullptr;      // one-byte ids, whole 64-table chunks, d <= 128
+        const bool fast8 = ctx->wfrag != nullptr && g.P == 8;      // one-byte ids, whole 64-table chunks, d <= 128
+        const bool fast10 = ctx->wfrag != nullptr && g.P == 10;    // packed ids in groups of 32 tables, d <= 128
         switch (g.d) {
             case 64: rc = fast8 ? launch_mfma8<64>(a, (uint4 *)ctx->wfrag, g.Hkv, batch, max_rows, st)
-                                : launch_mfma<64>(a, g.Hkv, batch, max_rows, st); break;
+                          : fast10 ? launch_mfma10<64>(a, (uint4 *)ctx->wfrag, g.Hkv, batch, max_rows, st)
+                                   : launch_mfma<64>(a, g.Hkv, batch, max_rows, st); break;
             case 128: rc = fast8 ? launch_mfma8<128>(a, (uint4 *)ctx->wfrag, g.Hkv, batch, max_rows, st)
-                                 : launch_mfma<128>(a, g.Hkv, batch, max_rows, st); break;
+                           : fast10 ? launch_mfma10<128>(a, (uint4 *)ctx->wfrag, g.Hkv, batch, max_rows, st)
+                                    : launch_mfma<128>(a, g.Hkv, batch, max_rows, st); break;
             case 256: rc = launch_mfma<256>(a, g.Hkv, batch, max_rows, st); break;
             default: return SOCKET_EUNSUPPORTED;
         }
