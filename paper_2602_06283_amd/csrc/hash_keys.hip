@@ -351,13 +351,15 @@ __global__ __launch_bounds__(512, D <= 128 ? 4 : 2) void hash_mfma_kernel(HashAr
 }
 
 // ---------------------------------------------------------------------------------------
-// bf16 MFMA kernel for 8-plane tables (one-byte ids), d <= 128, L >= 64: the fast path.
+// bf16 MFMA kernel for 8-plane tables (one-byte ids), d <= 128: the fast path.
 // A workgroup keeps the W slab of one 64-table chunk (512 columns) in LDS, already cut into
 // MFMA A-operand fragments, and each of its 16 wavefronts works on 64-key blocks of its own:
 // the keys go from memory straight into B-operand registers, so there is no staging, no
 // barrier in the main loop, and the wavefronts drift apart - some multiply while others pack.
 //
-// Column order.  Position 16 sub + s of token t holds table sub + 4 ((t + s) mod 16).  The
+// Column order (S = 4 position groups of 16 ids per 64-table chunk; rows of 16 or 32 ids have
+// S = 1 or 2 and read 4 as S below).  Position 16 sub + s of token t holds table
+// sub + 4 ((t + s) mod 16).  The
 // 32-column block p = 4 sub + q therefore holds tables sub + 4 (4q + e), e = 0..3: after four
 // blocks the wavefront has, for each key, the 16 ids of position group `sub` in table order
 // j = 4q + e as the 16 bytes of four sign words, and the stored group is those bytes rotated
@@ -368,7 +370,7 @@ __global__ __launch_bounds__(512, D <= 128 ? 4 : 2) void hash_mfma_kernel(HashAr
 // lane collects from its accumulators are, in order, one half of the key's 32-bit sign word.
 // hash_wfrag_kernel lays W out that way once per call; the main kernel copies it into LDS.
 // ---------------------------------------------------------------------------------------
-template <int D>
+template <int D, int S>
 __global__ __launch_bounds__(256) void hash_wfrag_kernel(HashArgs a, uint4 *wfrag) {
     constexpr int KS = D / 16;
     const int p = blockIdx.x, chunk = blockIdx.y % a.n_chunks, h = blockIdx.y / a.n_chunks;
@@ -376,12 +378,12 @@ __global__ __launch_bounds__(256) void hash_wfrag_kernel(HashArgs a, uint4 *wfra
     const int ntab = min(64, a.L - first_table);
     const int sub = p >> 2, q = p & 3;
     const uint16_t *W = (const uint16_t *)a.W + (int64_t)h * D * a.LP;
-    uint4 *dst = wfrag + ((int64_t)blockIdx.y * 16 + p) * KS * 64;
+    uint4 *dst = wfrag + ((int64_t)blockIdx.y * (4 * S) + p) * KS * 64;
     for (int f = threadIdx.x; f < KS * 64; f += 256) {
         const int ks = f >> 6, lane = f & 63;
         const int g = lane >> 5, m = lane & 31;
         const int bit = 16 * ((m >> 2) & 1) + 4 * (m >> 3) + (m & 3);
-        const int tt = sub + 4 * (4 * q + (bit >> 3));         // chunk-local table
+        const int tt = sub + S * (4 * q + (bit >> 3));         // chunk-local table
         const int col = (first_table + tt) * 8 + (bit & 7);
         uint32_t w[4] = {0u, 0u, 0u, 0u};
         if (tt < ntab) {
@@ -399,10 +401,10 @@ template <int V> struct IntTag { static constexpr int value = V; };
 
 constexpr int kHash8Threads = 1024;
 
-template <int D>
+template <int D, int S>
 __global__ __launch_bounds__(kHash8Threads) void hash_mfma8_kernel(HashArgs a, const uint4 *wfrag) {
     constexpr int KS = D / 16;                 // MFMA k-steps
-    constexpr int NCB = 16;                    // 32-column blocks of a chunk
+    constexpr int NCB = 4 * S;                 // 32-column blocks of a chunk (S position groups of 16 ids)
     constexpr int NW = kHash8Threads / 64;
     extern __shared__ uint32_t smem[];
     uint4 *wl = (uint4 *)smem;                         // [NCB][KS][64 lanes] A fragments
@@ -471,7 +473,7 @@ __global__ __launch_bounds__(kHash8Threads) void hash_mfma8_kernel(HashArgs a, c
         const int r0 = blk * 64;
         const int64_t prow = key_row(r0 + lane);        // the key this lane packs
         const int rot = (begin + r0 + lane) & 15;
-        uint4 done[3];                                  // the key's position groups 0..2, kept until the row is whole
+        uint4 done[S > 1 ? S - 1 : 1];                  // the key's position groups before the last, kept until the row is whole
 #pragma unroll 1
         for (int p = 0; p < NCB; ++p) {
             const int sub = p >> 2, q = p & 3;
@@ -486,8 +488,8 @@ __global__ __launch_bounds__(kHash8Threads) void hash_mfma8_kernel(HashArgs a, c
                 acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa.v, kf[0][ks], acc0, 0, 0, 0);
                 acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa.v, kf[1][ks], acc1, 0, 0, 0);
             }
-            // bytes whose table (sub + 4 (4q + e)) lies beyond the chunk's live tables stay zero
-            const int nlive = (ntab - sub - 16 * q + 3) >> 2;            // live tables among e = 0..3
+            // bytes whose table (sub + S (4q + e)) lies beyond the chunk's live tables stay zero
+            const int nlive = (ntab - sub - 4 * S * q + S - 1) >> (S == 4 ? 2 : S == 2 ? 1 : 0);   // live tables among e = 0..3 (<= 0: none)
             const uint32_t live_mask = nlive >= 4 ? 0xffffffffu : nlive <= 0 ? 0u : (1u << (8 * nlive)) - 1u;
             const uint32_t w0 = sign_word(acc0), w1 = sign_word(acc1);
             mybits[lane * 4 + q] = (lane < 32 ? w0 : w1) & live_mask;   // lane = key n or 32 + n
@@ -505,15 +507,14 @@ __global__ __launch_bounds__(kHash8Threads) void hash_mfma8_kernel(HashArgs a, c
                 o.w = __builtin_amdgcn_alignbyte(x0, x3, sh);
                 // the four groups of a key go out together: 64 adjacent bytes, written back as one
                 // whole line instead of four partial ones a quarter of the block apart
-                if (sub == 0) done[0] = o;
-                else if (sub == 1) done[1] = o;
-                else if (sub == 2) done[2] = o;
+                if (S > 1 && sub == 0) done[0] = o;
+                else if (S > 2 && sub == 1) done[1] = o;
+                else if (S > 2 && sub == 2) done[2] = o;
                 else if (prow >= 0) {
                     uint4 *dst = (uint4 *)(Cb + prow * (int64_t)a.Lpad + first_table);
-                    dst[0] = done[0];
-                    dst[1] = done[1];
-                    dst[2] = done[2];
-                    dst[3] = o;
+#pragma unroll
+                    for (int i = 0; i + 1 < S; ++i) dst[i] = done[i];
+                    dst[S - 1] = o;
                 }
             }
         }
@@ -689,8 +690,8 @@ static int launch_rows(const HashArgs &a, int Hkv, int batch, int max_rows, hipS
 }
 
 // dynamic LDS of hash_mfma8_kernel: the W slab as fragments, one id-word row per key of every wavefront's block
-template <int D> constexpr size_t hash8_lds() {
-    return (size_t)16 * (D / 16) * 64 * 16 + (size_t)(kHash8Threads / 64) * 64 * 16;
+template <int D, int S> constexpr size_t hash8_lds() {
+    return (size_t)(4 * S) * (D / 16) * 64 * 16 + (size_t)(kHash8Threads / 64) * 64 * 16;
 }
 
 template <int D> constexpr size_t hash10_lds() {
@@ -704,26 +705,34 @@ int hash_prepare(int d) {
     if (d == 64) e = hipFuncSetAttribute((const void *)hash_mfma10_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)hash10_lds<64>());
     if (d == 128) e = hipFuncSetAttribute((const void *)hash_mfma10_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)hash10_lds<128>());
     if (e != hipSuccess) return SOCKET_EHIP;
-    if (d == 64) e = hipFuncSetAttribute((const void *)hash_mfma8_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)hash8_lds<64>());
-    if (d == 128) e = hipFuncSetAttribute((const void *)hash_mfma8_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)hash8_lds<128>());
+    if (d == 64) e = hipFuncSetAttribute((const void *)hash_mfma8_kernel<64, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)hash8_lds<64, 4>());
+    if (d == 128) e = hipFuncSetAttribute((const void *)hash_mfma8_kernel<128, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)hash8_lds<128, 4>());
+    if (e == hipSuccess && d == 128) e = hipFuncSetAttribute((const void *)hash_mfma8_kernel<128, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)hash8_lds<128, 2>());
     return e == hipSuccess ? SOCKET_OK : SOCKET_EHIP;
 }
 
-template <int D>
+template <int D, int S>
 static int launch_mfma8(HashArgs a, uint4 *wfrag, int Hkv, int batch, int max_rows, hipStream_t st) {
     constexpr int NW = kHash8Threads / 64;
-    a.tables_per_chunk = 64;
-    a.n_chunks = (a.L + 63) / 64;
+    a.tables_per_chunk = 16 * S;
+    a.n_chunks = S == 4 ? (a.L + 63) / 64 : 1;
     // W as MFMA fragments, once per call
-    hipLaunchKernelGGL((hash_wfrag_kernel<D>), dim3(16, Hkv * a.n_chunks), dim3(256), 0, st, a, wfrag);
+    hipLaunchKernelGGL((hash_wfrag_kernel<D, S>), dim3(4 * S, Hkv * a.n_chunks), dim3(256), 0, st, a, wfrag);
     // one workgroup per CU (the W slab fills most of its LDS); each wavefront takes 64-key blocks
     int per = 256 / (Hkv * a.n_chunks * batch);
     const int nblocks = (max_rows + 63) / 64;
     if (per > (nblocks + NW - 1) / NW) per = (nblocks + NW - 1) / NW;
     if (per < 1) per = 1;
     dim3 grid(per, Hkv * a.n_chunks, batch);
-    hipLaunchKernelGGL((hash_mfma8_kernel<D>), grid, dim3(kHash8Threads), hash8_lds<D>(), st, a, (const uint4 *)wfrag);
+    constexpr size_t lds = hash8_lds<D, S>();
+    hipLaunchKernelGGL((hash_mfma8_kernel<D, S>), grid, dim3(kHash8Threads), lds, st, a, (const uint4 *)wfrag);
     return SOCKET_OK;
+}
+template <int D>
+static int launch_mfma8(HashArgs a, uint4 *wfrag, int Hkv, int batch, int max_rows, hipStream_t st) {
+    return a.S == 4 ? launch_mfma8<D, 4>(a, wfrag, Hkv, batch, max_rows, st)
+         : a.S == 2 ? launch_mfma8<D, 2>(a, wfrag, Hkv, batch, max_rows, st)
+                    : launch_mfma8<D, 1>(a, wfrag, Hkv, batch, max_rows, st);
 }
 
 template <int D>

@@ -73,6 +73,10 @@ def check_codes(layer, codes_t, rows_of):
     (wl.BF16, 1024, 60, 10),    # the paper's main (P, L)
     (wl.BF16, 1024, 24, 5),
     (wl.F32, 512, 40, 12),
+    (wl.BF16, 1024, 32, 8),     # MFMA kernel with rows of 32 ids
+    (wl.BF16, 1024, 24, 8),     # ... 24 of them live
+    (wl.BF16, 1024, 16, 8),     # rows of 16 ids
+    (wl.BF16, 1024, 9, 8),
     (wl.BF16, 1024, 300, 2),    # four 2-bit ids to a byte: 75 bytes per token, two chunks
     (wl.BF16, 1024, 128, 4),    # two 4-bit ids to a byte
     (wl.F32, 512, 256, 1),      # eight 1-bit ids to a byte
