@@ -924,7 +924,7 @@ def paged_codes_to_logical(codes_p, table, n_cap, page):
     return out
 
 
-@pytest.mark.parametrize("L,P,page", [(64, 8, 16), (60, 10, 16), (64, 10, 32), (128, 4, 16)])
+@pytest.mark.parametrize("L,P,page", [(64, 8, 16), (60, 10, 16), (64, 10, 32), (128, 4, 16), (128, 8, 16), (300, 2, 32)])
 def test_paged_chain_with_appends_across_page_boundaries(L, P, page):
     """Batched paged decode: prefill-hash ragged lengths, then several fused decode steps that
     append one key per sequence (crossing page edges), all checked against the oracle on
