@@ -37,6 +37,8 @@ def test_validate_params_accepts_the_benchmark_shapes():
     for L in (16, 32, 64, 128):
         for P in (4, 8, 10):
             assert sk.validate_params(sk.make_params(128, 32, 8, L, P, sk.BF16, 4, 65536, 1024)) == sk.OK
+    for L, P in ((300, 2), (400, 2), (500, 2), (600, 2), (1024, 2), (1024, 1), (256, 4), (258, 4), (7, 4), (1, 1)):
+        assert sk.validate_params(sk.make_params(128, 32, 8, L, P, sk.BF16, 1, 32784, 1024)) == sk.OK, (L, P)
     paged = dict(good(), max_batch=16, max_n=32832, max_k=700, page_size=16, max_blocks_per_seq=2052,
                  num_blocks=40000)
     assert sk.validate_params(sk.make_params(**paged)) == sk.OK

@@ -182,6 +182,7 @@ def check_scores(layer, got, codes_nat, tau, vnorm=None, seq_len=None, q=None, r
 
 @pytest.mark.parametrize("L,P,G", [(64, 8, 4), (32, 8, 1), (16, 4, 2), (128, 8, 4), (60, 10, 4),
                                    (64, 10, 1), (24, 5, 8), (128, 4, 4), (200, 2, 1), (300, 2, 4), (256, 1, 2), (66, 4, 8), (7, 4, 1),     # ids that share bytes (not the last)
+                                   (130, 6, 2), (600, 2, 1), (258, 4, 4),   # three, ten and five chunks of 64 tables
                                    (16, 10, 2), (100, 9, 8),      # packed ids: one 16-table group; four groups
                                    (40, 12, 2), (64, 11, 4)])     # two-byte ids, factored tables
 def test_score_matches_oracle(L, P, G):
