@@ -1,14 +1,18 @@
 // Alg. 1 (PrecomputeKeyHashes): sign random projections of cached keys, packed into bucket ids.
 //
-// Two kernels:
-//   hash_mfma_kernel   bf16 keys, many rows: K[rows x d] * W[d x L*P] on bf16 MFMA
+// Kernels:
+//   hash_mfma8_kernel  bf16 keys, 8-plane tables (one-byte ids), d <= 128: the W slab of a chunk
+//                      of up to 64 tables sits in LDS as MFMA fragments, keys go from memory
+//                      straight into registers, the ids are assembled in registers.
+//   hash_mfma10_kernel the same structure for 10-plane tables with packed 10-bit ids.
+//   hash_mfma_kernel   bf16 keys, any other shape: K[rows x d] * W[d x L*P] on bf16 MFMA
 //                      (v_mfma_f32_32x32x16_bf16, fp32 accumulate), W held in registers,
 //                      key tiles staged through LDS, sign bits taken from the accumulators'
 //                      sign bit and packed into a per-key bit matrix in LDS.
 //   hash_rows_kernel   fp32 keys, or a handful of appended rows: fp32 FMA, one thread per
 //                      projection column, sign bits gathered with a wavefront ballot.
-// Both end in pack_codes(), which cuts the bit matrix into P-bit bucket ids and writes them
-// in the rotated order the scoring kernel reads.
+// The last two end in pack_codes(), which cuts the bit matrix into P-bit bucket ids and writes
+// them in the rotated order the scoring kernel reads.
 #include "socket_internal.h"
 
 namespace sk {
