@@ -413,14 +413,18 @@ __global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
         // (planes 8 and 9 of the split form sit in slots 8 and 9)
         const double inv_g = 1.0 / (double)G, inv_r = 1.0 / (double)a.R;
         const bool split = a.mode == kSplit;
-        // split form: the products over planes 0..7 for each low byte of the id and over planes
-        // 8, 9 for its two high bits, once per query head; an entry is then one product of two
-        constexpr int kAb = 256 + 4;
+        // split form: the products over planes 0..3, 4..7 and 8, 9 for every value of those bits,
+        // once per query head; an entry is then a product of three of them
+        constexpr int kAb = 16 + 16 + 4;
         double *ab = (double *)(s_dev + 12);         // [G][kAb]
         if (split) {
             for (int i = tid; i < G * kAb; i += 256) {
-                const int g = i / kAb, r = i - g * kAb;
-                ab[i] = !live ? 0.0 : r < 256 ? plane_product(g, 0, r) : plane_product(g, 8, r - 256);
+                const int g = i / kAb, e = i - g * kAb;
+                const int s0 = e < 16 ? 0 : e < 32 ? 4 : 8, bits = e < 32 ? (e & 15) : e - 32;
+                const double *sp = sig + (g * kPlanePad + s0) * 2;
+                double v = sp[bits & 1] * sp[2 + ((bits >> 1) & 1)];
+                if (e < 32) v *= sp[4 + ((bits >> 2) & 1)] * sp[6 + ((bits >> 3) & 1)];
+                ab[i] = live ? v : 0.0;
             }
             __syncthreads();
         }
@@ -430,19 +434,25 @@ __global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
             // is kept as [bucket / 4][table][4] (the other tables of the group come from other
             // workgroups, so longer contiguous runs per table mean fewer partial writes)
             for (int r4 = tid; r4 < (a.R >> 2); r4 += 256) {
+                double mean[4] = {0.0, 0.0, 0.0, 0.0};
+                if (live) {
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        const double *t = ab + g * kAb;
+                        const double up = t[16 + ((r4 >> 2) & 15)] * t[32 + (r4 >> 6)];   // bits 4..7 and 8, 9 of the id
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) mean[j] = fma(t[(r4 & 3) * 4 + j], up, mean[j]);
+                    }
+                }
                 float v[4];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const int r = 4 * r4 + j;
-                    double mean = 0.0;
+                    mean[j] *= inv_g;
                     if (live) {
-#pragma unroll
-                        for (int g = 0; g < G; ++g) mean += ab[g * kAb + (r & 255)] * ab[g * kAb + 256 + (r >> 8)];
-                        mean *= inv_g;
-                        const double dv = mean - inv_r;
+                        const double dv = mean[j] - inv_r;
                         dev2 += (float)(dv * dv);
                     }
-                    v[j] = (float)mean;
+                    v[j] = (float)mean[j];
                 }
                 *(float4 *)&Tg[(((int64_t)(l / a.GT) * (a.R >> 2) + r4) * a.GT + l % a.GT) * 4] =
                     make_float4(v[0], v[1], v[2], v[3]);
@@ -2059,7 +2069,7 @@ int launch_project(socket_ctx *ctx, const void *q, const void *proj, float tau, 
     a.cols_magic = (65536 + g.P - 1) / g.P;
     const size_t lds = (size_t)(2 * g.G * kPlanePad + g.G * g.d + g.P * g.d) * sizeof(double) +
                        (size_t)(g.P * g.d + g.d) * 4 + 64 + 48 +
-                       (g.mode == kSplit ? (size_t)g.G * (256 + 4) * sizeof(double) : 0);
+                       (g.mode == kSplit ? (size_t)g.G * 36 * sizeof(double) : 0);
     typedef void (*project_fn_t)(ProjectArgs);
     project_fn_t fn = nullptr;
     const bool f32 = g.kv_dtype == SOCKET_F32;
