@@ -461,8 +461,13 @@ __global__ __launch_bounds__(256) void project_kernel(ProjectArgs a) {
         for (int r = tid; r < a.R && !split; r += 256) {
             double mean = 0.0;
             if (live) {
+                if (a.pf == 1) {
 #pragma unroll
-                for (int g = 0; g < G; ++g) mean += a.pf == 1 ? plane_product(g, 0, r) : shared_sum(g, r);
+                    for (int g = 0; g < G; ++g) mean += plane_product(g, 0, r);
+                } else {
+#pragma unroll
+                    for (int g = 0; g < G; ++g) mean += shared_sum(g, r);
+                }
                 mean *= inv_g;
                 const double dv = mean - a.tmean;    // a table's entries sum to 1: their mean is 1/R
                 dev2 += (float)(dv * dv);            // (pf tables' entries summed: pf / 2^Pu)
@@ -993,6 +998,7 @@ __global__ __launch_bounds__(kProjThreads) void project_batch_kernel(ProjectArgs
 //     group's tables write adjacent words of a row of the table block: 64-byte (128-byte)
 //     runs instead of single words a row apart.
 // ---------------------------------------------------------------------------------------
+template <bool V> struct GroupTag { static constexpr bool value = V; };
 constexpr int kGroupCols = 128;
 constexpr int kGroupThreads = 512;
 
@@ -1187,7 +1193,9 @@ __global__ __launch_bounds__(kGroupThreads) void project_group_kernel(ProjectArg
         const double f2 = sp[(4 + ((bits >> 2) & 1)) * TG], f3 = sp[(6 + ((bits >> 3) & 1)) * TG];
         // (ids that share a byte: the byte's entry is a sum over its pf small tables, so a
         // quarter holds one 4-plane table, two 2-plane tables or four 1-plane tables)
-        qt[e] = a.pf <= 2 ? (f0 * f1) * (f2 * f3) : a.pf == 4 ? f0 * f1 + f2 * f3 : (f0 + f1) + (f2 + f3);
+        double v = (f0 * f1) * (f2 * f3);
+        if (a.pf > 2) v = a.pf == 4 ? f0 * f1 + f2 * f3 : (f0 + f1) + (f2 + f3);
+        qt[e] = v;
     }
     if (a.pf > 1) {
         // the caller's tables one by one, for the read-back
@@ -1233,27 +1241,35 @@ __global__ __launch_bounds__(kGroupThreads) void project_group_kernel(ProjectArg
             for (int g = 0; g < G; ++g) lo[g] = qt[((g * NQ) * 16 + (r0 & 15)) * TG + li_own];
         }
         float dev2 = 0.0f;
+        // (ids that share a byte: the byte's entry is the sum of the two quarters, else their
+        // product; two copies of the loop, so that neither pays for the other)
+        auto fill = [&](auto shared_tag) __attribute__((always_inline)) {
+            constexpr bool SHARED = decltype(shared_tag)::value;
 #pragma unroll
-        for (int k = 0; k < NK; ++k) {
-            const int r = r0 + RSTEP * k;
-            double mean = 0.0;
+            for (int k = 0; k < NK; ++k) {
+                const int r = r0 + RSTEP * k;
+                double mean = 0.0;
 #pragma unroll
-            for (int g = 0; g < G; ++g) {
-                if (P > 4) {
-                    const double hi = qt[((g * NQ + 1) * 16 + (r >> 4)) * TG + li_own];
-                    mean = a.pf > 1 ? mean + (lo[g] + hi) : fma(lo[g], hi, mean);
-                } else mean += qt[((g * NQ) * 16 + r) * TG + li_own];
+                for (int g = 0; g < G; ++g) {
+                    if (P > 4) {
+                        const double hi = qt[((g * NQ + 1) * 16 + (r >> 4)) * TG + li_own];
+                        if (SHARED) mean += lo[g] + hi;
+                        else mean = fma(lo[g], hi, mean);
+                    } else mean += qt[((g * NQ) * 16 + r) * TG + li_own];
+                }
+                mean *= inv_g;
+                if (!live) mean = 0.0;
+                else {
+                    const double dv = mean - (SHARED ? a.tmean : 1.0 / (double)R);   // a table's entries sum to 1: their mean is 1/R (pf / 2^Pu when ids share bytes)
+                    dev2 += (float)(dv * dv);
+                }
+                if (l < a.Lpad)
+                    // (streaming stores: the tables are read next by workgroups of every XCD, through memory)
+                    for (int cp = 0; cp < copies; ++cp) __builtin_nontemporal_store((float)mean, &Tg[((int64_t)c64 * R + r) * 64 + lp + cp * lw]);
             }
-            mean *= inv_g;
-            if (!live) mean = 0.0;
-            else {
-                const double dv = mean - a.tmean;    // a table's entries sum to 1: their mean is 1/R (pf / 2^Pu when ids share bytes)
-                dev2 += (float)(dv * dv);
-            }
-            if (l < a.Lpad)
-                // (streaming stores: the tables are read next by workgroups of every XCD, through memory)
-                for (int cp = 0; cp < copies; ++cp) __builtin_nontemporal_store((float)mean, &Tg[((int64_t)c64 * R + r) * 64 + lp + cp * lw]);
-        }
+        };
+        if (a.pf > 1) fill(GroupTag<true>());
+        else fill(GroupTag<false>());
         s_part[tid] = dev2;
         s_part[NT + tid] = nu1;
         s_part[2 * NT + tid] = nu2;
