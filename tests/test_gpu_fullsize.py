@@ -5,7 +5,8 @@ checks the bucket ids on a sample of rows (the oracle's fp64 hashing of a millio
 long for a test) and everything downstream on all keys; configs[3] (16 paged sequences, 64
 appending steps) and the largest point of configs[4] (L = 128, P = 10, 4 x 65536 keys) check the
 ids on a sample of rows plus every appended row, and scores, selection and attention of the last
-step on every key of every (sequence, head) resp. of a stated sample of them."""
+step on every key of every (sequence, head) resp. of a stated sample of them.  The hard scorer
+is checked at the largest setting of the cost comparison, (P, L) = (2, 500) on 32768 keys."""
 import numpy as np
 import pytest
 import torch
@@ -226,4 +227,58 @@ def test_sweep_largest_point_l128_p10():
             want_y = hz.oracle_attention(layer, b, h, ix[b, h])
             assert np.abs(y[b, h * G:(h + 1) * G] - want_y).max() <= 1e-4
     assert exempt <= 2e-3 * checked
+    ctx.close()
+
+
+def test_hard_scorer_at_the_cost_comparison_shape():
+    """The hard LSH scorer at the largest setting of the cost comparison bench.py prints,
+    (P, L) = (2, 500), one sequence of 32768 keys, 8 KV heads of 4 queries: the 2-bit ids go four
+    to a byte and a byte's look-up returns the sum of its four tables' terms.  Ids: 256 sampled
+    rows of every head against the oracle; collision counts (Eq. 3, hard form) on every key of
+    every head whose queries have no projection within 1e-4 of zero, exactly; then the selection
+    of k = 1024 keys among the (heavily tied) counts and the attention over it."""
+    assert torch.cuda.is_available()
+    B, Hq, Hkv, d, L, P, n, k = 1, 32, 8, 128, 500, 2, 32768, 1024
+    layer = wl.make_layer(1001, B=B, Hq=Hq, Hkv=Hkv, d=d, n=n, L=L, P=P, k=k, kv_dtype=wl.BF16)
+    ctx = hz.make_ctx(layer)
+    Kd, Vd, qd, Wd = (hz.dev(x, wl.BF16) for x in (layer.K, layer.V, layer.q, layer.W))
+    codes = hz.new_codes((B, Hkv), n, L, P, fill=0x55)
+    assert codes.numel() == B * Hkv * n * 128        # 125 bytes of ids per key, padded to two 64-byte chunks
+    scores = torch.zeros((B, Hkv, n), dtype=torch.float32, device="cuda")
+    idx = torch.zeros((B, Hkv, k), dtype=torch.int32, device="cuda")
+    nsel = torch.zeros((B, Hkv), dtype=torch.int32, device="cuda")
+    out = torch.zeros((B, Hq, d), dtype=torch.float32, device="cuda")
+    ctx.hash_keys(Kd, Wd, hz.i32([0]), hz.i32([n]), B, n, codes)
+    ctx.hard_hash(qd, Wd, B)
+    ctx.score_keys(codes, hz.i32([n]), B, scores)
+    ctx.topk_select(scores, hz.i32([n]), hz.i32([k]), B, idx, nsel)
+    ctx.sparse_decode(qd, Kd, Vd, idx, nsel, B, 1.0, out)
+    torch.cuda.synchronize()
+    raw = hz.rows_from_device(codes, L, P)
+    sc, ix, cnt, y = scores.cpu().numpy(), idx.cpu().numpy(), nsel.cpu().numpy(), out.cpu().numpy()[0]
+    G = Hq // Hkv
+    rows = np.sort(np.random.default_rng(9).choice(n, size=256, replace=False))
+    exempt = checked = scored = 0
+    for h in range(Hkv):
+        got = hz.codes_to_natural(raw[0, h], L, P=P)
+        want, near = oracle.hash_keys(layer.K[0, h][rows], layer.W[h], L, P)
+        assert not ((got[rows] != want) & ~near).any(), h
+        exempt += int(near.sum()); checked += want.size
+        want_s = np.zeros(n)
+        clean = True
+        for g in range(G):
+            qc, qnear = oracle.hash_keys(layer.q[0, h * G + g][None], layer.W[h], L, P)
+            clean = clean and not qnear.any()
+            want_s += oracle.hard_score(got.astype(np.uint16), qc[0])
+        if not clean:
+            continue
+        scored += 1
+        want_s = (want_s / G).astype(np.float32)
+        assert (sc[0, h] == want_s).all(), h
+        want_idx, c = oracle.topk(want_s.astype(np.float64), k)
+        assert cnt[0, h] == c == k
+        assert (ix[0, h] == np.sort(want_idx)).all(), h      # ties go to the smaller position on both sides
+        want_y = hz.oracle_attention(layer, 0, h, ix[0, h])
+        assert np.abs(y[h * G:(h + 1) * G] - want_y).max() <= 1e-4
+    assert exempt <= 2e-3 * checked and scored >= 1
     ctx.close()
