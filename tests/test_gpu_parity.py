@@ -585,7 +585,8 @@ def test_decode_step_equals_separate_calls_and_oracle(kv_dtype, L, P, G):
 
 @pytest.mark.parametrize("case", ["ties_cold", "ties_cold_small_k", "ties_flat", "all_equal", "take_all", "k_one",
                                   "value_norms", "value_norms_heavy", "large", "large_tiny_k", "tie_group_400",
-                                  "tie_group_700", "half_selected", "several_regions_per_split"])
+                                  "tie_group_700", "half_selected", "several_regions_per_split",
+                                  "value_norms_shared_bytes", "ties_cold_shared_bytes"])
 def test_decode_step_select_paths_agree(case):
     """Inside socket_decode_step the select starts from what the scoring pass leaves: a
     histogram with bins sized from the bucket-probability tables when the scores are
@@ -619,8 +620,12 @@ def test_decode_step_select_paths_agree(case):
         # more regions than attention splits: a split owns several, the index row is ordered
         # beside the merge
         "several_regions_per_split": dict(n=530000, k=[1024, 200], tau=0.5, lens=[530000, 300000]),
+        # ids of 4 and 2 bits that share bytes: the bins are sized from tables of summed entries
+        "value_norms_shared_bytes": dict(n=6000, k=[256, 100], tau=0.5, lens=[6000, 3333], LP=(128, 4)),
+        "ties_cold_shared_bytes": dict(n=6000, k=[300, 777], tau=1e-4, lens=[6000, 4100], LP=(300, 2)),
     }[case]
-    B, Hkv, G, L, P = 2, 2, 4, 64, 8
+    B, Hkv, G = 2, 2, 4
+    L, P = cfg.get("LP", (64, 8))
     n = (cfg["n"] + 31) // 16 * 16
     lens = np.array(cfg["lens"], dtype=np.int32)
     layer = small_layer(seed=71, B=B, Hq=Hkv * G, Hkv=Hkv, n=n, L=L, P=P, k=cfg["k"], seq_len=lens, tau=cfg["tau"])
@@ -635,7 +640,7 @@ def test_decode_step_select_paths_agree(case):
     Kd, Vd, qd, Wd = (hz.dev(x, layer.kv_dtype) for x in (layer.K, layer.V, layer.q, layer.W))
     max_k = int(layer.k.max())
     vn = None
-    if case == "value_norms":
+    if case in ("value_norms", "value_norms_shared_bytes"):
         vn = torch.from_numpy(np.stack([np.stack([oracle.value_norms(layer.V[b, h]) for h in range(Hkv)])
                                         for b in range(B)]).astype(np.float32)).cuda()
     if case == "value_norms_heavy":                    # weights over five decades, some exactly 0
