@@ -527,31 +527,31 @@ __global__ __launch_bounds__(kHash8Threads) void hash_mfma8_kernel(HashArgs a, c
 }
 
 // ---------------------------------------------------------------------------------------
-// The same structure for 10-plane tables with packed ids (groups of 32 tables, d <= 128): a
-// workgroup keeps the W slab of one group (320 columns = ten 32-column blocks) in LDS as MFMA
-// fragments; every wavefront works on 64-key blocks of its own.
+// The same structure for 10-plane tables with packed ids (groups of 16 S tables, S = 1 or 2,
+// d <= 128): a workgroup keeps the W slab of one group (S x 160 columns = 5 S 32-column blocks)
+// in LDS as MFMA fragments; every wavefront works on 64-key blocks of its own.
 //
-// Column order.  String `sub` (0, 1) of a token's group holds, before its rotation by the token
-// position, the ids of tables sub, sub + 2, .., sub + 30 in bits [10 j, 10 j + 10): 160 bits =
+// Column order.  String `sub` (< S) of a token's group holds, before its rotation by the token
+// position, the ids of tables sub, sub + S, .., sub + 15 S in bits [10 j, 10 j + 10): 160 bits =
 // five sign words.  Block p = 5 sub + q produces word q: bit u = 32 q + (bit of the word) of the
-// string is plane u % 10 of table sub + 2 (u / 10).  The stored string is that one rotated right
+// string is plane u % 10 of table sub + S (u / 10).  The stored string is that one rotated right
 // by 10 (t mod 16) bits: a rotation of the five words and one funnel shift.
 // ---------------------------------------------------------------------------------------
-template <int D>
+template <int D, int S>
 __global__ __launch_bounds__(256) void hash_wfrag10_kernel(HashArgs a, uint4 *wfrag) {
     constexpr int KS = D / 16;
     const int p = blockIdx.x, grp = blockIdx.y % a.n_chunks, h = blockIdx.y / a.n_chunks;
-    const int first_table = grp * 32;
-    const int ntab = min(32, a.L - first_table);
+    const int first_table = grp * 16 * S;
+    const int ntab = min(16 * S, a.L - first_table);
     const int sub = p / 5, q = p % 5;
     const uint16_t *W = (const uint16_t *)a.W + (int64_t)h * D * a.LP;
-    uint4 *dst = wfrag + ((int64_t)blockIdx.y * 10 + p) * KS * 64;
+    uint4 *dst = wfrag + ((int64_t)blockIdx.y * (5 * S) + p) * KS * 64;
     for (int f = threadIdx.x; f < KS * 64; f += 256) {
         const int ks = f >> 6, lane = f & 63;
         const int g = lane >> 5, m = lane & 31;
         const int bit = 16 * ((m >> 2) & 1) + 4 * (m >> 3) + (m & 3);   // bit of the sign word that MFMA row m becomes
         const int u = 32 * q + bit;
-        const int tt = sub + 2 * (u / 10);                     // group-local table
+        const int tt = sub + S * (u / 10);                     // group-local table
         const int col = (first_table + tt) * 10 + u % 10;
         uint32_t w[4] = {0u, 0u, 0u, 0u};
         if (tt < ntab) {
@@ -565,10 +565,11 @@ __global__ __launch_bounds__(256) void hash_wfrag10_kernel(HashArgs a, uint4 *wf
     }
 }
 
-template <int D>
+template <int D, int S>
 __global__ __launch_bounds__(kHash8Threads) void hash_mfma10_kernel(HashArgs a, const uint4 *wfrag) {
     constexpr int KS = D / 16;                 // MFMA k-steps
-    constexpr int NCB = 10;                    // 32-column blocks of a group
+    constexpr int NCB = 5 * S;                 // 32-column blocks of a group
+    constexpr int GT = 16 * S;                 // tables of a group
     constexpr int NW = kHash8Threads / 64;
     extern __shared__ uint32_t smem[];
     uint4 *wl = (uint4 *)smem;                         // [NCB][KS][64 lanes] A fragments
@@ -578,7 +579,7 @@ __global__ __launch_bounds__(kHash8Threads) void hash_mfma10_kernel(HashArgs a, 
     const int grp = blockIdx.y % a.n_chunks, h = blockIdx.y / a.n_chunks, b = blockIdx.z;
     const int count = a.row_count[b];
     const int begin = a.row_begin[b];
-    const int ntab = max(0, min(32, a.L - grp * 32));
+    const int ntab = max(0, min(GT, a.L - grp * GT));
 
     {
         const uint4 *src = wfrag + (int64_t)blockIdx.y * NCB * KS * 64;
@@ -639,7 +640,7 @@ __global__ __launch_bounds__(kHash8Threads) void hash_mfma10_kernel(HashArgs a, 
                 acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa.v, kf[1][ks], acc1, 0, 0, 0);
             }
             // ids of tables beyond the live ones stay zero: the string's first 10 nj bits are live
-            const int nj = max(0, (ntab - sub + 1) >> 1);
+            const int nj = max(0, (ntab - sub + S - 1) / S);
             const int nlive = 10 * nj - 32 * q;
             const uint32_t live_mask = nlive >= 32 ? 0xffffffffu : nlive <= 0 ? 0u : (1u << nlive) - 1u;
             const uint32_t w0 = sign_word(acc0), w1 = sign_word(acc1);
@@ -659,16 +660,21 @@ __global__ __launch_bounds__(kHash8Threads) void hash_mfma10_kernel(HashArgs a, 
                 o.z = __builtin_amdgcn_alignbit(x3, x2, sh);
                 o.w = __builtin_amdgcn_alignbit(x4, x3, sh);
                 const uint32_t ot = __builtin_amdgcn_alignbit(x0, x4, sh);
-                if (sub == 0) {
+                if (S == 2 && sub == 0) {
                     head0 = o;
                     tail0 = ot;
                 } else if (prow >= 0) {
-                    // both strings of the key's group together: 32 adjacent bytes of the tile's
-                    // main rows and 8 of its tail rows
-                    uint4 *dst = (uint4 *)(Cb + packed_main_row(prow, grp, a.Lpad, 32));
-                    dst[0] = head0;
-                    dst[1] = o;
-                    *(uint2 *)(Cb + packed_tail_row(prow, grp, a.Lpad, 32)) = make_uint2(tail0, ot);
+                    // the strings of the key's group together: 16 S adjacent bytes of the tile's
+                    // main rows and 4 S of its tail rows
+                    uint4 *dst = (uint4 *)(Cb + packed_main_row(prow, grp, a.Lpad, GT));
+                    if (S == 2) {
+                        dst[0] = head0;
+                        dst[1] = o;
+                        *(uint2 *)(Cb + packed_tail_row(prow, grp, a.Lpad, GT)) = make_uint2(tail0, ot);
+                    } else {
+                        dst[0] = o;
+                        *(uint32_t *)(Cb + packed_tail_row(prow, grp, a.Lpad, GT)) = ot;
+                    }
                 }
             }
         }
@@ -698,16 +704,15 @@ template <int D, int S> constexpr size_t hash8_lds() {
     return (size_t)(4 * S) * (D / 16) * 64 * 16 + (size_t)(kHash8Threads / 64) * 64 * 16;
 }
 
-template <int D> constexpr size_t hash10_lds() {
-    return (size_t)10 * (D / 16) * 64 * 16 + (size_t)(kHash8Threads / 64) * 64 * 20;
+template <int D, int S> constexpr size_t hash10_lds() {
+    return (size_t)(5 * S) * (D / 16) * 64 * 16 + (size_t)(kHash8Threads / 64) * 64 * 20;
 }
 
 // once per context that uses a fast hash: more than 64 KB of dynamic LDS has to be allowed
 // before the first launch
 int hash_prepare(int d) {
     hipError_t e = hipSuccess;
-    if (d == 64) e = hipFuncSetAttribute((const void *)hash_mfma10_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)hash10_lds<64>());
-    if (d == 128) e = hipFuncSetAttribute((const void *)hash_mfma10_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)hash10_lds<128>());
+    if (d == 128) e = hipFuncSetAttribute((const void *)hash_mfma10_kernel<128, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)hash10_lds<128, 2>());
     if (e != hipSuccess) return SOCKET_EHIP;
     if (d == 64) e = hipFuncSetAttribute((const void *)hash_mfma8_kernel<64, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)hash8_lds<64, 4>());
     if (d == 128) e = hipFuncSetAttribute((const void *)hash_mfma8_kernel<128, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)hash8_lds<128, 4>());
@@ -739,19 +744,25 @@ static int launch_mfma8(HashArgs a, uint4 *wfrag, int Hkv, int batch, int max_ro
                     : launch_mfma8<D, 1>(a, wfrag, Hkv, batch, max_rows, st);
 }
 
-template <int D>
+template <int D, int S>
 static int launch_mfma10(HashArgs a, uint4 *wfrag, int Hkv, int batch, int max_rows, hipStream_t st) {
     constexpr int NW = kHash8Threads / 64;
-    a.tables_per_chunk = 32;
-    a.n_chunks = a.Lpad / 32;                  // groups, padding groups included (their ids are zero)
-    hipLaunchKernelGGL((hash_wfrag10_kernel<D>), dim3(10, Hkv * a.n_chunks), dim3(256), 0, st, a, wfrag);
+    a.tables_per_chunk = 16 * S;
+    a.n_chunks = a.Lpad / (16 * S);            // groups, padding groups included (their ids are zero)
+    hipLaunchKernelGGL((hash_wfrag10_kernel<D, S>), dim3(5 * S, Hkv * a.n_chunks), dim3(256), 0, st, a, wfrag);
     int per = 256 / (Hkv * a.n_chunks * batch);
     const int nblocks = (max_rows + 63) / 64;
     if (per > (nblocks + NW - 1) / NW) per = (nblocks + NW - 1) / NW;
     if (per < 1) per = 1;
     dim3 grid(per, Hkv * a.n_chunks, batch);
-    hipLaunchKernelGGL((hash_mfma10_kernel<D>), grid, dim3(kHash8Threads), hash10_lds<D>(), st, a, (const uint4 *)wfrag);
+    constexpr size_t lds = hash10_lds<D, S>();
+    hipLaunchKernelGGL((hash_mfma10_kernel<D, S>), grid, dim3(kHash8Threads), lds, st, a, (const uint4 *)wfrag);
     return SOCKET_OK;
+}
+template <int D>
+static int launch_mfma10(HashArgs a, uint4 *wfrag, int Hkv, int batch, int max_rows, hipStream_t st) {
+    return a.GT == 32 ? launch_mfma10<D, 2>(a, wfrag, Hkv, batch, max_rows, st)
+                      : launch_mfma10<D, 1>(a, wfrag, Hkv, batch, max_rows, st);
 }
 
 template <int D>

@@ -194,11 +194,11 @@ int socket_create(socket_ctx **out, const socket_params *p) {
     const int64_t sz_sub = g.pf > 1 ? BH * g.Lu * (1 << g.Pu) * 4 : 0;   // shared-byte ids: the small tables, for the read-back
     // fast prefill hash: bf16 keys, 8-plane tables, W slab of a chunk of up to 64 tables fits LDS
     const bool fast8 = g.kv_dtype == SOCKET_BF16 && g.P == 8 && g.cb == 1 && g.d <= 128;
-    // the same for 10-plane tables with packed ids in groups of 32 tables
-    const bool fast10 = g.kv_dtype == SOCKET_BF16 && g.P == 10 && g.mode == kSplit && g.GT == 32 && g.d <= 128;
+    // the same for 10-plane tables with packed ids (groups of 32 tables, or one group of 16)
+    const bool fast10 = g.kv_dtype == SOCKET_BF16 && g.P == 10 && g.mode == kSplit && (g.GT == 32 || g.GT == 16) && g.d <= 128;
     const bool fast_hash = fast8 || fast10;
     const int64_t sz_wfrag = fast8 ? (int64_t)g.Hkv * ((g.L + 63) / 64) * g.d * 1024
-                             : fast10 ? (int64_t)g.Hkv * (g.Lpad / 32) * 10 * (g.d / 16) * 1024 : 0;
+                             : fast10 ? (int64_t)g.Hkv * (g.Lpad / g.GT) * (5 * g.GT / 16) * (g.d / 16) * 1024 : 0;
     const int64_t sz_hist = 2 * BH * kHistBins * 4;   // first- and second-digit histograms
     const int64_t sz_cnt = BH * (kCounterStride + kThrStride) * 4;
     const int64_t sz_cand = BH * g.max_n * 4;

@@ -73,7 +73,8 @@ def check_codes(layer, codes_t, rows_of):
     (wl.BF16, 1024, 60, 10),    # the paper's main (P, L)
     (wl.BF16, 1024, 20, 10),    # one group of 32 table slots, 20 live
     (wl.BF16, 1024, 100, 10),   # four groups, the last with 4 live tables
-    (wl.BF16, 1024, 16, 10),    # one group of 16 tables (the generic MFMA kernel)
+    (wl.BF16, 1024, 16, 10),    # one group of 16 tables: one id string per key
+    (wl.BF16, 1024, 11, 10),    # ... 11 of them live
     (wl.BF16, 1024, 24, 5),
     (wl.F32, 512, 40, 12),
     (wl.BF16, 1024, 32, 8),     # MFMA kernel with rows of 32 ids
