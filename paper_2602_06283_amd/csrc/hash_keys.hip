@@ -1,9 +1,9 @@
 // Alg. 1 (PrecomputeKeyHashes): sign random projections of cached keys, packed into bucket ids.
 //
 // Kernels:
-//   hash_mfma8_kernel  bf16 keys, 8-plane tables (one-byte ids), d <= 128: the W slab of a chunk
-//                      of up to 64 tables sits in LDS as MFMA fragments, keys go from memory
-//                      straight into registers, the ids are assembled in registers.
+//   hash_mfma8_kernel  bf16 keys, 8- or 4-plane tables (one-byte ids), d <= 128: the W slab of a
+//                      chunk of up to 64 tables sits in LDS as MFMA fragments, keys go from
+//                      memory straight into registers, the ids are assembled in registers.
 //   hash_mfma10_kernel the same structure for 10-plane tables with packed 10-bit ids.
 //   hash_mfma_kernel   bf16 keys, any other shape: K[rows x d] * W[d x L*P] on bf16 MFMA
 //                      (v_mfma_f32_32x32x16_bf16, fp32 accumulate), W held in registers,
@@ -374,21 +374,23 @@ __global__ __launch_bounds__(512, D <= 128 ? 4 : 2) void hash_mfma_kernel(HashAr
 // lane collects from its accumulators are, in order, one half of the key's 32-bit sign word.
 // hash_wfrag_kernel lays W out that way once per call; the main kernel copies it into LDS.
 // ---------------------------------------------------------------------------------------
-template <int D, int S>
+template <int D, int S, int P>
 __global__ __launch_bounds__(256) void hash_wfrag_kernel(HashArgs a, uint4 *wfrag) {
+    constexpr int BPG = P / 2;                 // 32-column blocks per position group of 16 ids (P = 8: 4, P = 4: 2)
     constexpr int KS = D / 16;
     const int p = blockIdx.x, chunk = blockIdx.y % a.n_chunks, h = blockIdx.y / a.n_chunks;
     const int first_table = chunk * 64;
     const int ntab = min(64, a.L - first_table);
-    const int sub = p >> 2, q = p & 3;
+    const int sub = p / BPG, q = p % BPG;
     const uint16_t *W = (const uint16_t *)a.W + (int64_t)h * D * a.LP;
-    uint4 *dst = wfrag + ((int64_t)blockIdx.y * (4 * S) + p) * KS * 64;
+    uint4 *dst = wfrag + ((int64_t)blockIdx.y * (BPG * S) + p) * KS * 64;
     for (int f = threadIdx.x; f < KS * 64; f += 256) {
         const int ks = f >> 6, lane = f & 63;
         const int g = lane >> 5, m = lane & 31;
         const int bit = 16 * ((m >> 2) & 1) + 4 * (m >> 3) + (m & 3);
-        const int tt = sub + S * (4 * q + (bit >> 3));         // chunk-local table
-        const int col = (first_table + tt) * 8 + (bit & 7);
+        // (a block holds 32 / P tables: table e of the block in bits [P e, P e + P) of the sign word)
+        const int tt = sub + S * ((32 / P) * q + bit / P);     // chunk-local table
+        const int col = (first_table + tt) * P + bit % P;
         uint32_t w[4] = {0u, 0u, 0u, 0u};
         if (tt < ntab) {
             uint16_t e[8];
@@ -405,10 +407,12 @@ template <int V> struct IntTag { static constexpr int value = V; };
 
 constexpr int kHash8Threads = 1024;
 
-template <int D, int S>
+template <int D, int S, int P>
 __global__ __launch_bounds__(kHash8Threads) void hash_mfma8_kernel(HashArgs a, const uint4 *wfrag) {
+    static_assert(P == 8 || P == 4, "one-byte ids of 8 planes, or of 4 (a block's eight nibbles are spread over two words)");
     constexpr int KS = D / 16;                 // MFMA k-steps
-    constexpr int NCB = 4 * S;                 // 32-column blocks of a chunk (S position groups of 16 ids)
+    constexpr int BPG = P / 2;                 // 32-column blocks per position group of 16 ids
+    constexpr int NCB = BPG * S;               // 32-column blocks of a chunk (S position groups)
     constexpr int NW = kHash8Threads / 64;
     extern __shared__ uint32_t smem[];
     uint4 *wl = (uint4 *)smem;                         // [NCB][KS][64 lanes] A fragments
@@ -424,15 +428,20 @@ __global__ __launch_bounds__(kHash8Threads) void hash_mfma8_kernel(HashArgs a, c
     // ---- W slab -> LDS
     {
         const uint4 *src = wfrag + (int64_t)blockIdx.y * NCB * KS * 64;
-        constexpr int N = NCB * KS * 64, PER = N / kHash8Threads, NB = PER < 8 ? PER : 8;
-        static_assert(N % kHash8Threads == 0 && PER % NB == 0, "whole batches of copies per thread");
+        constexpr int N = NCB * KS * 64;
+        if constexpr (N % kHash8Threads == 0) {
+            constexpr int PER = N / kHash8Threads, NB = PER < 8 ? PER : 8;
+            static_assert(PER % NB == 0, "whole batches of copies per thread");
 #pragma unroll 1
-        for (int u0 = 0; u0 < PER; u0 += NB) {
-            uint4 v[NB];
+            for (int u0 = 0; u0 < PER; u0 += NB) {
+                uint4 v[NB];
 #pragma unroll
-            for (int u = 0; u < NB; ++u) v[u] = src[tid + (u0 + u) * kHash8Threads];
+                for (int u = 0; u < NB; ++u) v[u] = src[tid + (u0 + u) * kHash8Threads];
 #pragma unroll
-            for (int u = 0; u < NB; ++u) wl[tid + (u0 + u) * kHash8Threads] = v[u];
+                for (int u = 0; u < NB; ++u) wl[tid + (u0 + u) * kHash8Threads] = v[u];
+            }
+        } else {
+            for (int i = tid; i < N; i += kHash8Threads) wl[i] = src[i];
         }
     }
     __syncthreads();
@@ -480,7 +489,7 @@ __global__ __launch_bounds__(kHash8Threads) void hash_mfma8_kernel(HashArgs a, c
         uint4 done[S > 1 ? S - 1 : 1];                  // the key's position groups before the last, kept until the row is whole
 #pragma unroll 1
         for (int p = 0; p < NCB; ++p) {
-            const int sub = p >> 2, q = p & 3;
+            const int sub = p / BPG, q = p % BPG;
             const uint4 *af = wl + (p * KS) * 64 + lane;
             floatx16_t acc0, acc1;
 #pragma unroll
@@ -492,12 +501,27 @@ __global__ __launch_bounds__(kHash8Threads) void hash_mfma8_kernel(HashArgs a, c
                 acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa.v, kf[0][ks], acc0, 0, 0, 0);
                 acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa.v, kf[1][ks], acc1, 0, 0, 0);
             }
-            // bytes whose table (sub + S (4q + e)) lies beyond the chunk's live tables stay zero
-            const int nlive = (ntab - sub - 4 * S * q + S - 1) >> (S == 4 ? 2 : S == 2 ? 1 : 0);   // live tables among e = 0..3 (<= 0: none)
-            const uint32_t live_mask = nlive >= 4 ? 0xffffffffu : nlive <= 0 ? 0u : (1u << (8 * nlive)) - 1u;
             const uint32_t w0 = sign_word(acc0), w1 = sign_word(acc1);
-            mybits[lane * 4 + q] = (lane < 32 ? w0 : w1) & live_mask;   // lane = key n or 32 + n
-            if (q == 3) {
+            const uint32_t w = lane < 32 ? w0 : w1;                     // lane = key n or 32 + n
+            if (P == 8) {
+                // bytes whose table (sub + S (4q + e)) lies beyond the chunk's live tables stay zero
+                const int nlive = (ntab - sub - 4 * S * q + S - 1) >> (S == 4 ? 2 : S == 2 ? 1 : 0);   // live tables among e = 0..3 (<= 0: none)
+                const uint32_t live_mask = nlive >= 4 ? 0xffffffffu : nlive <= 0 ? 0u : (1u << (8 * nlive)) - 1u;
+                mybits[lane * 4 + q] = w & live_mask;
+            } else {
+                // eight 4-bit ids: each nibble becomes the byte of its table (sub + S (8q + e))
+                auto spread = [](uint32_t x) {          // nibbles 0..3 of x -> bytes 0..3
+                    const uint32_t t = (x | (x << 8)) & 0x00ff00ffu;
+                    return (t | (t << 4)) & 0x0f0f0f0fu;
+                };
+                const int nlive = (ntab - sub - 8 * S * q + S - 1) >> (S == 4 ? 2 : S == 2 ? 1 : 0);   // live tables among e = 0..7
+                const int n0 = nlive < 4 ? nlive : 4, n1 = nlive - 4 < 4 ? nlive - 4 : 4;
+                const uint32_t m0 = n0 >= 4 ? 0xffffffffu : n0 <= 0 ? 0u : (1u << (8 * n0)) - 1u;
+                const uint32_t m1 = n1 >= 4 ? 0xffffffffu : n1 <= 0 ? 0u : (1u << (8 * n1)) - 1u;
+                mybits[lane * 4 + 2 * q] = spread(w & 0xffffu) & m0;
+                mybits[lane * 4 + 2 * q + 1] = spread(w >> 16) & m1;
+            }
+            if (q == BPG - 1) {
                 // ---- the 16 ids of position group `sub`, rotated by the token position
                 const uint4 wv = *(const uint4 *)(mybits + lane * 4);
                 const bool r1 = rot & 4, r2 = rot & 8;
@@ -512,8 +536,8 @@ __global__ __launch_bounds__(kHash8Threads) void hash_mfma8_kernel(HashArgs a, c
                 // the four groups of a key go out together: 64 adjacent bytes, written back as one
                 // whole line instead of four partial ones a quarter of the block apart
                 if (S > 1 && sub == 0) done[0] = o;
-                else if (S > 2 && sub == 1) done[1] = o;
-                else if (S > 2 && sub == 2) done[2] = o;
+                else if (S > 2 && sub == 1) done[S > 2 ? 1 : 0] = o;
+                else if (S > 2 && sub == 2) done[S > 2 ? 2 : 0] = o;
                 else if (prow >= 0) {
                     uint4 *dst = (uint4 *)(Cb + prow * (int64_t)a.Lpad + first_table);
 #pragma unroll
@@ -700,8 +724,8 @@ static int launch_rows(const HashArgs &a, int Hkv, int batch, int max_rows, hipS
 }
 
 // dynamic LDS of hash_mfma8_kernel: the W slab as fragments, one id-word row per key of every wavefront's block
-template <int D, int S> constexpr size_t hash8_lds() {
-    return (size_t)(4 * S) * (D / 16) * 64 * 16 + (size_t)(kHash8Threads / 64) * 64 * 16;
+template <int D, int S, int P> constexpr size_t hash8_lds() {
+    return (size_t)(P / 2 * S) * (D / 16) * 64 * 16 + (size_t)(kHash8Threads / 64) * 64 * 16;
 }
 
 template <int D, int S> constexpr size_t hash10_lds() {
@@ -714,34 +738,40 @@ int hash_prepare(int d) {
     hipError_t e = hipSuccess;
     if (d == 128) e = hipFuncSetAttribute((const void *)hash_mfma10_kernel<128, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)hash10_lds<128, 2>());
     if (e != hipSuccess) return SOCKET_EHIP;
-    if (d == 64) e = hipFuncSetAttribute((const void *)hash_mfma8_kernel<64, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)hash8_lds<64, 4>());
-    if (d == 128) e = hipFuncSetAttribute((const void *)hash_mfma8_kernel<128, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)hash8_lds<128, 4>());
-    if (e == hipSuccess && d == 128) e = hipFuncSetAttribute((const void *)hash_mfma8_kernel<128, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)hash8_lds<128, 2>());
+    if (d == 64) e = hipFuncSetAttribute((const void *)hash_mfma8_kernel<64, 4, 8>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)hash8_lds<64, 4, 8>());
+    if (d == 128) e = hipFuncSetAttribute((const void *)hash_mfma8_kernel<128, 4, 8>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)hash8_lds<128, 4, 8>());
+    if (e == hipSuccess && d == 128) e = hipFuncSetAttribute((const void *)hash_mfma8_kernel<128, 2, 8>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)hash8_lds<128, 2, 8>());
+    if (e == hipSuccess && d == 128) e = hipFuncSetAttribute((const void *)hash_mfma8_kernel<128, 4, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)hash8_lds<128, 4, 4>());
     return e == hipSuccess ? SOCKET_OK : SOCKET_EHIP;
 }
 
-template <int D, int S>
+template <int D, int S, int P>
 static int launch_mfma8(HashArgs a, uint4 *wfrag, int Hkv, int batch, int max_rows, hipStream_t st) {
     constexpr int NW = kHash8Threads / 64;
     a.tables_per_chunk = 16 * S;
     a.n_chunks = S == 4 ? (a.L + 63) / 64 : 1;
     // W as MFMA fragments, once per call
-    hipLaunchKernelGGL((hash_wfrag_kernel<D, S>), dim3(4 * S, Hkv * a.n_chunks), dim3(256), 0, st, a, wfrag);
+    hipLaunchKernelGGL((hash_wfrag_kernel<D, S, P>), dim3(P / 2 * S, Hkv * a.n_chunks), dim3(256), 0, st, a, wfrag);
     // one workgroup per CU (the W slab fills most of its LDS); each wavefront takes 64-key blocks
     int per = 256 / (Hkv * a.n_chunks * batch);
     const int nblocks = (max_rows + 63) / 64;
     if (per > (nblocks + NW - 1) / NW) per = (nblocks + NW - 1) / NW;
     if (per < 1) per = 1;
     dim3 grid(per, Hkv * a.n_chunks, batch);
-    constexpr size_t lds = hash8_lds<D, S>();
-    hipLaunchKernelGGL((hash_mfma8_kernel<D, S>), grid, dim3(kHash8Threads), lds, st, a, (const uint4 *)wfrag);
+    constexpr size_t lds = hash8_lds<D, S, P>();
+    hipLaunchKernelGGL((hash_mfma8_kernel<D, S, P>), grid, dim3(kHash8Threads), lds, st, a, (const uint4 *)wfrag);
     return SOCKET_OK;
+}
+template <int D, int P>
+static int launch_mfma8(HashArgs a, uint4 *wfrag, int Hkv, int batch, int max_rows, hipStream_t st) {
+    return a.S == 4 ? launch_mfma8<D, 4, P>(a, wfrag, Hkv, batch, max_rows, st)
+         : a.S == 2 ? launch_mfma8<D, 2, P>(a, wfrag, Hkv, batch, max_rows, st)
+                    : launch_mfma8<D, 1, P>(a, wfrag, Hkv, batch, max_rows, st);
 }
 template <int D>
 static int launch_mfma8(HashArgs a, uint4 *wfrag, int Hkv, int batch, int max_rows, hipStream_t st) {
-    return a.S == 4 ? launch_mfma8<D, 4>(a, wfrag, Hkv, batch, max_rows, st)
-         : a.S == 2 ? launch_mfma8<D, 2>(a, wfrag, Hkv, batch, max_rows, st)
-                    : launch_mfma8<D, 1>(a, wfrag, Hkv, batch, max_rows, st);
+    return a.P == 8 ? launch_mfma8<D, 8>(a, wfrag, Hkv, batch, max_rows, st)
+                    : launch_mfma8<D, 4>(a, wfrag, Hkv, batch, max_rows, st);
 }
 
 template <int D, int S>
@@ -811,7 +841,7 @@ int launch_hash_keys(socket_ctx *ctx, const void *K, const void *proj, const int
     } else if (max_rows < 64) {
         rc = launch_rows<uint16_t>(a, g.Hkv, batch, max_rows, st);
     } else {
-        const bool fast8 = ctx->wfrag != nullptr && g.P == 8;      // one-byte ids, whole 64-table chunks, d <= 128
+        const bool fast8 = ctx->wfrag != nullptr && (g.P == 8 || g.P == 4);   // one-byte ids of 8 or 4 planes, d <= 128
         const bool fast10 = ctx->wfrag != nullptr && g.P == 10;    // packed ids in groups of 32 tables, d <= 128
         switch (g.d) {
             case 64: rc = fast8 ? launch_mfma8<64>(a, (uint4 *)ctx->wfrag, g.Hkv, batch, max_rows, st)

@@ -192,8 +192,8 @@ int socket_create(socket_ctx **out, const socket_params *p) {
     const int64_t sz_tables = BH * g.table_words * 4;
     const int64_t sz_tstats = BH * g.Lpad * 3 * 4;
     const int64_t sz_sub = g.pf > 1 ? BH * g.Lu * (1 << g.Pu) * 4 : 0;   // shared-byte ids: the small tables, for the read-back
-    // fast prefill hash: bf16 keys, 8-plane tables, W slab of a chunk of up to 64 tables fits LDS
-    const bool fast8 = g.kv_dtype == SOCKET_BF16 && g.P == 8 && g.cb == 1 && g.d <= 128;
+    // fast prefill hash: bf16 keys, one-byte ids of 8 or 4 planes, W slab of a chunk of up to 64 tables fits LDS
+    const bool fast8 = g.kv_dtype == SOCKET_BF16 && (g.P == 8 || g.P == 4) && g.cb == 1 && g.mode == kDirect && g.d <= 128;
     // the same for 10-plane tables with packed ids (groups of 32 tables, or one group of 16)
     const bool fast10 = g.kv_dtype == SOCKET_BF16 && g.P == 10 && g.mode == kSplit && (g.GT == 32 || g.GT == 16) && g.d <= 128;
     const bool fast_hash = fast8 || fast10;

@@ -86,6 +86,9 @@ def check_codes(layer, codes_t, rows_of):
     (wl.F32, 512, 256, 1),      # eight 1-bit ids to a byte
     (wl.BF16, 512, 66, 4),      # 33 bytes
     (wl.BF16, 512, 7, 4),       # an odd table count: a byte per id
+    (wl.BF16, 1024, 65, 4),     # ... two chunks, the second with one table
+    (wl.BF16, 512, 31, 4),      # ... rows of 32 ids
+    (wl.BF16, 512, 257, 4),     # ... five chunks
 ])
 def test_hash_keys_prefill(kv_dtype, n, L, P):
     _need_gpu()
